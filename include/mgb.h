@@ -1,0 +1,264 @@
+/*
+ * mgb.h -- C ABI of the one-GPU task co-execution library.
+ *
+ * The library implements, for a single AMD CDNA4 device, the resource-aware
+ * sharing scheme of "Effective GPU Sharing Under Compiler Guidance"
+ * (arXiv 2107.08538): every GPU task announces its memory footprint and launch
+ * geometry through a probe before it touches the device (Sec. III-A, Fig. 3:
+ * the instrumented task_begin(mem, threads, blocks)); a user-level scheduler
+ * answers with a placement or makes the task wait (Sec. III-B, Algorithms 2
+ * and 3); resources are handed back when the task completes and waiting tasks
+ * are retried (Sec. IV).  Where the paper picks one of several GPUs and relies
+ * on a process-sharing service to co-run kernels, this library partitions the
+ * compute units of one device: a placement is a set of compute "granules"
+ * (groups of CUs) realised as a CU-masked HIP stream.
+ *
+ * Conventions
+ *   - plain C types only; all handles are opaque; no exceptions cross the ABI.
+ *   - return value: 0 = MGB_OK, > 0 = non-error status, < 0 = error.
+ *   - "device pointer" = address in GPU memory owned by the caller; the
+ *     library never allocates or frees task buffers.  "host pointer" = CPU
+ *     memory.  Out-parameters are host pointers written before return.
+ *   - every function is thread-safe unless stated otherwise.
+ *   - the memory ledger is pure accounting (as in the paper, where the
+ *     scheduler tracks FreeMem but allocates nothing).
+ */
+#ifndef MGB_H
+#define MGB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ------------------------------------------------------ */
+#define MGB_OK 0
+#define MGB_WAIT 1               /* probe accepted, task queued             */
+#define MGB_TIMEOUT 2            /* mgb_task_wait gave up, task still queued */
+#define MGB_E_INVAL (-1)         /* null pointer, zero / oversized geometry */
+#define MGB_E_TOO_BIG (-2)       /* footprint larger than the whole cap     */
+#define MGB_E_UNKNOWN_TICKET (-3)
+#define MGB_E_BAD_STATE (-4)     /* e.g. complete of a waiting task         */
+#define MGB_E_BUSY (-5)          /* destroy with tasks in flight            */
+#define MGB_E_BACKEND (-6)       /* HIP call failed; see mgb_last_error     */
+#define MGB_E_UNSUPPORTED (-7)   /* shape outside what a kernel accepts     */
+
+/* ---- policies (Sec. III-B and Sec. IV) --------------------------------- */
+#define MGB_POLICY_HARD 0    /* Algorithm 2: memory and compute both hard   */
+#define MGB_POLICY_SOFT 1    /* Algorithm 3: memory hard, compute by load   */
+#define MGB_POLICY_SERIAL 2  /* single-assignment baseline: one task owns the device */
+#define MGB_QUEUE_BACKFILL 0 /* on release retry every waiter in arrival order */
+#define MGB_QUEUE_FIFO 1     /* stop at the first waiter that does not fit  */
+#define MGB_BACKEND_NULL 0   /* bookkeeping only, no HIP call (host tests)  */
+#define MGB_BACKEND_HIP 1    /* placements carry a CU-masked hipStream_t    */
+
+typedef struct mgb_sched mgb_sched;
+
+typedef struct { uint32_t x, y, z; } mgb_dim3;
+
+/* Device description; copied by mgb_sched_create.  The per-CU limits are the
+ * analogue of the "max thread blocks and warps per SM" that Algorithm 2
+ * tracks.  n_cu must be a multiple of granule_cus and n_cu / granule_cus must
+ * be <= 32.  With the HIP backend granule_cus must be a multiple of 8: CU-mask
+ * bit i selects a CU of XCD (i mod 8), so 8 consecutive aligned bits are one CU
+ * in every XCD, and a mask that leaves an XCD without CUs is never built.    */
+typedef struct {
+  uint64_t mem_cap_bytes;      /* ledger capacity                           */
+  uint32_t n_cu;               /* 256                                       */
+  uint32_t granule_cus;        /* 8                                         */
+  uint32_t wave_size;          /* 64                                        */
+  uint32_t max_waves_per_cu;   /* 32                                        */
+  uint32_t max_wg_per_cu;      /* 32                                        */
+  uint32_t policy;             /* MGB_POLICY_*                              */
+  uint32_t queue_mode;         /* MGB_QUEUE_*                               */
+  uint32_t backend;            /* MGB_BACKEND_*                             */
+  int32_t  device;             /* HIP device ordinal (HIP backend)          */
+  uint32_t reserved;
+} mgb_device_desc;
+
+/* Answer to a probe.  `stream` is a hipStream_t owned by the library (NULL
+ * with the null backend); it is valid until mgb_task_complete(ticket).
+ * Granule k owns CU-mask bits [k*granule_cus, (k+1)*granule_cus).            */
+typedef struct {
+  uint64_t ticket;             /* handle of this task inside the scheduler  */
+  uint32_t granule_mask;       /* bit k set = granule k granted             */
+  uint32_t n_granules;         /* granules demanded (= granted)             */
+  uint32_t cu_mask[8];         /* 256-bit CU mask derived from granule_mask */
+  void*    stream;
+} mgb_placement;
+
+typedef struct {
+  uint64_t free_bytes;
+  uint32_t free_granules;      /* bitmap (HARD / SERIAL)                    */
+  uint32_t n_running;
+  uint32_t n_waiting;
+  uint32_t n_streams;          /* masked streams created so far             */
+  uint64_t n_events;           /* trace records so far                      */
+} mgb_stats;
+
+/* ---- event trace -------------------------------------------------------- */
+#define MGB_EV_PROBE 0       /* input: a probe arrived (mem, grid, block)   */
+#define MGB_EV_COMPLETE 1    /* input: mgb_task_complete(ticket)            */
+#define MGB_EV_CANCEL 2      /* input: mgb_task_cancel(ticket)              */
+#define MGB_EV_ADMIT 16      /* decision: placed (granule_mask, cu_mask)    */
+#define MGB_EV_QUEUED 17     /* decision: must wait                         */
+#define MGB_EV_REJECT 18     /* decision: refused, `code` says why          */
+#define MGB_EV_RELEASE 19    /* decision: resources credited back           */
+#define MGB_EV_CANCELLED 20  /* decision: waiter removed                    */
+
+/* One record per event, in the total order in which the scheduler lock was
+ * taken.  Input records carry what the caller passed; decision records carry
+ * the state after the decision.  Replaying the input records through an
+ * independent implementation of the policy must regenerate the decisions.   */
+typedef struct {
+  uint64_t seq;
+  uint64_t t_ns;               /* monotonic clock                           */
+  uint64_t task_id;
+  uint64_t ticket;
+  uint64_t mem_bytes;
+  uint64_t free_bytes;         /* after the event                           */
+  uint32_t kind;               /* MGB_EV_*                                  */
+  int32_t  code;               /* reject reason or 0                        */
+  uint32_t granule_mask;
+  uint32_t free_granules;      /* after the event                           */
+  uint32_t demand;             /* granules demanded                         */
+  uint32_t cause_seq;          /* seq of the input record that caused a decision */
+  mgb_dim3 grid, block;
+  uint32_t cu_mask[8];
+} mgb_trace_rec;
+
+/* ---- scheduler ----------------------------------------------------------
+ * Fill `out` with the defaults for one MI355X: 256 CUs in granules of 8,
+ * 64-lane waves, 32 waves and 32 workgroups per CU, cap 288e9 bytes, HARD,
+ * BACKFILL, HIP backend, device 0.                                          */
+void mgb_device_desc_default(mgb_device_desc* out);
+
+/* Create a scheduler for one device.  Errors: MGB_E_INVAL (bad descriptor),
+ * MGB_E_BACKEND (HIP device unusable).                                      */
+int mgb_sched_create(const mgb_device_desc* desc, mgb_sched** out);
+
+/* Destroy; MGB_E_BUSY if any task is running or waiting (nothing is freed). */
+int mgb_sched_destroy(mgb_sched* s);
+
+/* The probe (the paper's task_begin, Fig. 3 and Sec. IV): announce footprint
+ * and launch geometry of a task before it runs.  A task that launches several
+ * kernels on the same buffers is ONE task (Algorithm 1 merges launches that
+ * share memory objects): pass the largest geometry of its launches.
+ *   MGB_OK    placed: *out holds granules, CU mask, stream.
+ *   MGB_WAIT  queued: out->ticket valid, call mgb_task_wait.
+ *   MGB_E_INVAL  grid or block has a zero dimension or block > 1024 threads.
+ *   MGB_E_TOO_BIG  mem_bytes exceeds the cap; the task is never queued.
+ * Compute demand (Algorithm 2's per-SM residency limits, per CU here):
+ *   waves/wg = ceil(threads / wave_size);
+ *   wg/CU    = max(1, min(max_wg_per_cu, max_waves_per_cu / waves/wg));
+ *   CUs      = min(n_cu, ceil(workgroups / wg/CU)); granules = ceil(CUs / granule_cus). */
+int mgb_task_probe(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 grid,
+                   mgb_dim3 block, mgb_placement* out);
+
+/* Block until the queued task is admitted (MGB_OK, *out filled) or
+ * timeout_ns elapsed (MGB_TIMEOUT, task stays queued; < 0 waits forever).    */
+int mgb_task_wait(mgb_sched* s, uint64_t ticket, int64_t timeout_ns, mgb_placement* out);
+
+/* Remove a queued (not yet admitted) task.  MGB_E_BAD_STATE if it runs.      */
+int mgb_task_cancel(mgb_sched* s, uint64_t ticket);
+
+/* Run enqueue(stream, user) on the task's stream, bracketed by timing events
+ * (HIP backend).  enqueue must only enqueue work on `stream` (it may
+ * synchronise that stream).  Its return value != 0 is passed back.          */
+int mgb_task_launch(mgb_sched* s, uint64_t ticket, int (*enqueue)(void* stream, void* user),
+                    void* user);
+
+/* Wait until everything launched for the task has finished; *gpu_ms (may be
+ * NULL) receives the time between the bracketing events.                    */
+int mgb_task_sync(mgb_sched* s, uint64_t ticket, double* gpu_ms);
+
+/* Task finished: credit memory and granules back and retry the waiters
+ * (Sec. IV).  The caller must have synchronised the task's work first.      */
+int mgb_task_complete(mgb_sched* s, uint64_t ticket);
+
+int mgb_sched_stats(mgb_sched* s, mgb_stats* out);
+/* Copy up to `cap` trace records starting at sequence number `first` into
+ * `out` (host); returns the number copied or < 0.                           */
+int64_t mgb_trace_read(mgb_sched* s, uint64_t first, mgb_trace_rec* out, uint64_t cap);
+/* Write the whole trace as JSON lines to `path`.                             */
+int mgb_trace_dump(mgb_sched* s, const char* path);
+/* Text of the last backend error seen by this thread ("" if none).          */
+const char* mgb_last_error(void);
+
+/* ---- task kernels ---------------------------------------------------------
+ * Each task kind has a *probe* -- the requirement derivation a compiler pass
+ * would have inserted (Sec. III-A: footprint = sum of the task's allocations,
+ * compute = grid and block of its launches) -- and an *enqueue* that puts the
+ * task's kernels on a stream.  Probes are pure host arithmetic.  Enqueues
+ * return MGB_E_UNSUPPORTED / MGB_E_INVAL before launching anything if the
+ * arguments do not fit what the kernels assume.  All device buffers are
+ * caller-owned and must stay valid until the stream has drained.            */
+
+/* fp32 5-point Jacobi relaxation on an n x n row-major grid whose outermost
+ * ring is a fixed boundary: v = 0.25f * ((N + S) + (W + E)) on the interior,
+ * `iters` sweeps ping-ponging between u0 (initial state) and u1; the result is
+ * in u0 if iters is even, else u1.  Both buffers must hold the same ring.
+ * Footprint 2*n*n*4 bytes.  n >= 3.                                         */
+int mgb_jacobi_probe(uint32_t n, uint32_t iters, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block);
+int mgb_jacobi_enqueue(void* stream, float* u0, float* u1, uint32_t n, uint32_t iters);
+
+/* fp32 GEMM C = A * B, row-major A (m x k), B (k x n), C (m x n), fp32 MFMA
+ * accumulation.  Footprint (m*k + k*n + m*n)*4.                              */
+int mgb_gemm_f32_probe(uint32_t m, uint32_t n, uint32_t k, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block);
+int mgb_gemm_f32_enqueue(void* stream, const float* A, const float* B, float* C, uint32_t m, uint32_t n, uint32_t k);
+
+/* bf16 GEMM: A, B hold bfloat16 bit patterns (uint16), C is fp32; products are
+ * accumulated in fp32 by the bf16 MFMA.  Footprint (m*k + k*n)*2 + m*n*4.    */
+int mgb_gemm_bf16_probe(uint32_t m, uint32_t n, uint32_t k, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block);
+int mgb_gemm_bf16_enqueue(void* stream, const uint16_t* A, const uint16_t* B, float* C, uint32_t m, uint32_t n, uint32_t k);
+
+/* One 3x3 convolution + ReLU, padding 1, stride 1 or 2, as an implicit GEMM.
+ * x: N,H,W,C bf16; w: K,3,3,C bf16; y: N,Ho,Wo,K with Ho = (H-1)/stride + 1,
+ * stored as bf16 (round to nearest even) if out_f32 == 0 else as fp32.
+ * fp32 accumulation.                                                         */
+typedef struct {
+  uint32_t c_in, c_out, stride;
+} mgb_conv_layer;
+int mgb_conv3x3_probe(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_out,
+                      uint32_t stride, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block);
+int mgb_conv3x3_enqueue(void* stream, const uint16_t* x, const uint16_t* w, void* y, uint32_t batch,
+                        uint32_t h, uint32_t wd, uint32_t c_in, uint32_t c_out, uint32_t stride,
+                        uint32_t out_f32);
+
+/* A chain of n_layers conv+ReLU layers run as one task.  Activations ping-pong
+ * between act0 and act1 (bf16, each large enough for the largest intermediate
+ * activation); the last layer writes fp32 to `out`.  weights[i] is the device
+ * pointer of layer i's K,3,3,C tensor (host array of device pointers).
+ * Footprint = input + all weights + 2 * largest intermediate + fp32 output;
+ * geometry = the largest over the layers.                                    */
+int mgb_cnn_probe(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, uint32_t h,
+                  uint32_t w, uint64_t* mem_bytes, uint64_t* act_bytes, uint64_t* out_bytes,
+                  mgb_dim3* grid, mgb_dim3* block);
+int mgb_cnn_enqueue(void* stream, const mgb_conv_layer* layers, uint32_t n_layers,
+                    const uint16_t* x, const uint16_t* const* weights, uint16_t* act0,
+                    uint16_t* act1, float* out, uint32_t batch, uint32_t h, uint32_t w);
+
+/* Level-synchronous BFS on a CSR graph (row_ptr int32[n+1], col_idx int32[m]).
+ * level[v] = hop distance from `source`, -1 if unreachable.  `work` is scratch
+ * of mgb_bfs_work_bytes(n) bytes (two frontier queues and per-level counters).
+ * The call enqueues batches of level kernels and synchronises the stream
+ * between batches to learn whether the frontier is empty; on return `level` is
+ * complete.  *depth (host, may be NULL) receives the number of levels.
+ * Footprint (n+1+m)*4 + n*4 + work.                                          */
+uint64_t mgb_bfs_work_bytes(uint32_t n);
+int mgb_bfs_probe(uint32_t n, uint64_t m, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block);
+int mgb_bfs_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
+                    uint32_t source, int32_t* level, void* work, uint32_t* depth);
+
+/* Diagnostic: launch n_blocks one-wave workgroups on `stream`; workgroup i
+ * stores where it ran in out[i] (device, uint32): (xcd << 8) | (shader engine
+ * << 4) | CU index within the engine.  Shows which physical CUs a placement's
+ * stream reaches.  n_blocks in [1, 2^20].                                    */
+int mgb_cu_trace_enqueue(void* stream, uint32_t* out, uint32_t n_blocks);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MGB_H */

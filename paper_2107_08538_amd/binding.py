@@ -1,0 +1,224 @@
+"""ctypes declarations mirroring include/mgb.h, plus small marshalling helpers."""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmgb.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libmgb.so is not built: run `python -m paper_2107_08538_amd.build` "
+        "(or __graft_entry__.build()) first; there is no fallback path")
+
+# PyTorch provides device memory and streams, and it bundles its own copy of the
+# HIP runtime (same soname as the one libmgb.so was linked against).  A process
+# must hold exactly one HIP runtime, so torch is loaded first and libmgb.so then
+# binds to that copy; loading them the other way round gives two runtimes of
+# which the second finds no device.
+import torch  # noqa: E402,F401
+
+lib = C.CDLL(LIB_PATH)
+
+MGB_OK, MGB_WAIT, MGB_TIMEOUT = 0, 1, 2
+MGB_E_INVAL, MGB_E_TOO_BIG, MGB_E_UNKNOWN_TICKET, MGB_E_BAD_STATE = -1, -2, -3, -4
+MGB_E_BUSY, MGB_E_BACKEND, MGB_E_UNSUPPORTED = -5, -6, -7
+MGB_POLICY_HARD, MGB_POLICY_SOFT, MGB_POLICY_SERIAL = 0, 1, 2
+MGB_QUEUE_BACKFILL, MGB_QUEUE_FIFO = 0, 1
+MGB_BACKEND_NULL, MGB_BACKEND_HIP = 0, 1
+MGB_EV_PROBE, MGB_EV_COMPLETE, MGB_EV_CANCEL = 0, 1, 2
+MGB_EV_ADMIT, MGB_EV_QUEUED, MGB_EV_REJECT, MGB_EV_RELEASE, MGB_EV_CANCELLED = 16, 17, 18, 19, 20
+
+
+class mgb_dim3(C.Structure):
+    _fields_ = [("x", C.c_uint32), ("y", C.c_uint32), ("z", C.c_uint32)]
+
+    def tuple(self):
+        return (self.x, self.y, self.z)
+
+
+class mgb_device_desc(C.Structure):
+    _fields_ = [("mem_cap_bytes", C.c_uint64), ("n_cu", C.c_uint32), ("granule_cus", C.c_uint32),
+                ("wave_size", C.c_uint32), ("max_waves_per_cu", C.c_uint32),
+                ("max_wg_per_cu", C.c_uint32), ("policy", C.c_uint32), ("queue_mode", C.c_uint32),
+                ("backend", C.c_uint32), ("device", C.c_int32), ("reserved", C.c_uint32)]
+
+
+class mgb_placement(C.Structure):
+    _fields_ = [("ticket", C.c_uint64), ("granule_mask", C.c_uint32), ("n_granules", C.c_uint32),
+                ("cu_mask", C.c_uint32 * 8), ("stream", C.c_void_p)]
+
+
+class mgb_stats(C.Structure):
+    _fields_ = [("free_bytes", C.c_uint64), ("free_granules", C.c_uint32),
+                ("n_running", C.c_uint32), ("n_waiting", C.c_uint32), ("n_streams", C.c_uint32),
+                ("n_events", C.c_uint64)]
+
+
+class mgb_conv_layer(C.Structure):
+    _fields_ = [("c_in", C.c_uint32), ("c_out", C.c_uint32), ("stride", C.c_uint32)]
+
+
+TRACE_DT = np.dtype([("seq", "<u8"), ("t_ns", "<u8"), ("task_id", "<u8"), ("ticket", "<u8"),
+                     ("mem_bytes", "<u8"), ("free_bytes", "<u8"), ("kind", "<u4"), ("code", "<i4"),
+                     ("granule_mask", "<u4"), ("free_granules", "<u4"), ("demand", "<u4"),
+                     ("cause_seq", "<u4"), ("grid", "<u4", (3,)), ("block", "<u4", (3,)),
+                     ("cu_mask", "<u4", (8,))])
+assert TRACE_DT.itemsize == 128
+
+ENQUEUE_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_void_p)
+
+_u32, _u64, _vp, _i64 = C.c_uint32, C.c_uint64, C.c_void_p, C.c_int64
+_P = C.POINTER
+
+
+def _sig(name, restype, *argtypes):
+    fn = getattr(lib, name)       # AttributeError here = header / library mismatch
+    fn.restype = restype
+    fn.argtypes = list(argtypes)
+    return fn
+
+
+mgb_device_desc_default = _sig("mgb_device_desc_default", None, _P(mgb_device_desc))
+mgb_sched_create = _sig("mgb_sched_create", C.c_int, _P(mgb_device_desc), _P(_vp))
+mgb_sched_destroy = _sig("mgb_sched_destroy", C.c_int, _vp)
+mgb_task_probe = _sig("mgb_task_probe", C.c_int, _vp, _u64, _u64, mgb_dim3, mgb_dim3, _P(mgb_placement))
+mgb_task_wait = _sig("mgb_task_wait", C.c_int, _vp, _u64, _i64, _P(mgb_placement))
+mgb_task_cancel = _sig("mgb_task_cancel", C.c_int, _vp, _u64)
+mgb_task_launch = _sig("mgb_task_launch", C.c_int, _vp, _u64, ENQUEUE_FN, _vp)
+mgb_task_sync = _sig("mgb_task_sync", C.c_int, _vp, _u64, _P(C.c_double))
+mgb_task_complete = _sig("mgb_task_complete", C.c_int, _vp, _u64)
+mgb_sched_stats = _sig("mgb_sched_stats", C.c_int, _vp, _P(mgb_stats))
+mgb_trace_read = _sig("mgb_trace_read", _i64, _vp, _u64, _vp, _u64)
+mgb_trace_dump = _sig("mgb_trace_dump", C.c_int, _vp, C.c_char_p)
+mgb_last_error = _sig("mgb_last_error", C.c_char_p)
+
+_probe_tail = (_P(_u64), _P(mgb_dim3), _P(mgb_dim3))
+mgb_jacobi_probe = _sig("mgb_jacobi_probe", C.c_int, _u32, _u32, *_probe_tail)
+mgb_jacobi_enqueue = _sig("mgb_jacobi_enqueue", C.c_int, _vp, _vp, _vp, _u32, _u32)
+mgb_gemm_f32_probe = _sig("mgb_gemm_f32_probe", C.c_int, _u32, _u32, _u32, *_probe_tail)
+mgb_gemm_f32_enqueue = _sig("mgb_gemm_f32_enqueue", C.c_int, _vp, _vp, _vp, _vp, _u32, _u32, _u32)
+mgb_gemm_bf16_probe = _sig("mgb_gemm_bf16_probe", C.c_int, _u32, _u32, _u32, *_probe_tail)
+mgb_gemm_bf16_enqueue = _sig("mgb_gemm_bf16_enqueue", C.c_int, _vp, _vp, _vp, _vp, _u32, _u32, _u32)
+mgb_conv3x3_probe = _sig("mgb_conv3x3_probe", C.c_int, _u32, _u32, _u32, _u32, _u32, _u32, *_probe_tail)
+mgb_conv3x3_enqueue = _sig("mgb_conv3x3_enqueue", C.c_int, _vp, _vp, _vp, _vp, _u32, _u32, _u32,
+                           _u32, _u32, _u32, _u32)
+mgb_cnn_probe = _sig("mgb_cnn_probe", C.c_int, _P(mgb_conv_layer), _u32, _u32, _u32, _u32,
+                     _P(_u64), _P(_u64), _P(_u64), _P(mgb_dim3), _P(mgb_dim3))
+mgb_cnn_enqueue = _sig("mgb_cnn_enqueue", C.c_int, _vp, _P(mgb_conv_layer), _u32, _vp, _P(_vp),
+                       _vp, _vp, _vp, _u32, _u32, _u32)
+mgb_bfs_work_bytes = _sig("mgb_bfs_work_bytes", _u64, _u32)
+mgb_bfs_probe = _sig("mgb_bfs_probe", C.c_int, _u32, _u64, *_probe_tail)
+mgb_bfs_enqueue = _sig("mgb_bfs_enqueue", C.c_int, _vp, _vp, _vp, _u32, _u32, _vp, _vp, _P(_u32))
+mgb_cu_trace_enqueue = _sig("mgb_cu_trace_enqueue", C.c_int, _vp, _vp, _u32)
+
+EXPORTS = [
+    "mgb_device_desc_default", "mgb_sched_create", "mgb_sched_destroy", "mgb_task_probe",
+    "mgb_task_wait", "mgb_task_cancel", "mgb_task_launch", "mgb_task_sync", "mgb_task_complete",
+    "mgb_sched_stats", "mgb_trace_read", "mgb_trace_dump", "mgb_last_error",
+    "mgb_jacobi_probe", "mgb_jacobi_enqueue", "mgb_gemm_f32_probe", "mgb_gemm_f32_enqueue",
+    "mgb_gemm_bf16_probe", "mgb_gemm_bf16_enqueue", "mgb_conv3x3_probe", "mgb_conv3x3_enqueue",
+    "mgb_cnn_probe", "mgb_cnn_enqueue", "mgb_bfs_work_bytes", "mgb_bfs_probe", "mgb_bfs_enqueue",
+    "mgb_cu_trace_enqueue",
+]
+
+
+# ------------------------------------------------------------------ helpers
+class MgbError(RuntimeError):
+    def __init__(self, code, where):
+        msg = mgb_last_error().decode() if code == MGB_E_BACKEND else ""
+        super().__init__("%s failed with status %d %s" % (where, code, msg))
+        self.code = code
+
+
+def check(code, where):
+    if code < 0:
+        raise MgbError(code, where)
+    return code
+
+
+def default_desc(**overrides):
+    d = mgb_device_desc()
+    mgb_device_desc_default(C.byref(d))
+    for k, v in overrides.items():
+        setattr(d, k, v)
+    return d
+
+
+def dev_ptr(t):
+    """Device address of a torch tensor (or None)."""
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def probe_of(fn, *shape):
+    """Call one of the mgb_*_probe functions; returns (mem_bytes, grid, block)."""
+    mem, grid, block = _u64(0), mgb_dim3(), mgb_dim3()
+    check(fn(*shape, C.byref(mem), C.byref(grid), C.byref(block)), fn.__name__)
+    return int(mem.value), grid, block
+
+
+class Sched:
+    """Owns one mgb_sched handle; methods are 1:1 with the C entry points."""
+
+    def __init__(self, desc=None, **overrides):
+        self.desc = desc if desc is not None else default_desc(**overrides)
+        h = _vp()
+        check(mgb_sched_create(C.byref(self.desc), C.byref(h)), "mgb_sched_create")
+        self.h = h
+
+    def probe(self, task_id, mem_bytes, grid, block):
+        grid = grid if isinstance(grid, mgb_dim3) else mgb_dim3(*grid)
+        block = block if isinstance(block, mgb_dim3) else mgb_dim3(*block)
+        pl = mgb_placement()
+        rc = mgb_task_probe(self.h, task_id, mem_bytes, grid, block, C.byref(pl))
+        return rc, pl
+
+    def wait(self, ticket, timeout_ns=-1):
+        pl = mgb_placement()
+        rc = mgb_task_wait(self.h, ticket, timeout_ns, C.byref(pl))
+        return rc, pl
+
+    def cancel(self, ticket):
+        return mgb_task_cancel(self.h, ticket)
+
+    def launch(self, ticket, fn):
+        """fn(stream_void_p) -> int enqueues the task's kernels."""
+        cb = ENQUEUE_FN(lambda stream, user: int(fn(stream) or 0))
+        return mgb_task_launch(self.h, ticket, cb, None)
+
+    def sync(self, ticket):
+        ms = C.c_double(0.0)
+        rc = mgb_task_sync(self.h, ticket, C.byref(ms))
+        return rc, ms.value
+
+    def complete(self, ticket):
+        return mgb_task_complete(self.h, ticket)
+
+    def stats(self):
+        st = mgb_stats()
+        check(mgb_sched_stats(self.h, C.byref(st)), "mgb_sched_stats")
+        return st
+
+    def trace(self):
+        n = int(self.stats().n_events)
+        out = np.zeros(n, dtype=TRACE_DT)
+        got = mgb_trace_read(self.h, 0, out.ctypes.data_as(_vp), n)
+        check(int(got), "mgb_trace_read")
+        return out[:got]
+
+    def dump(self, path):
+        return mgb_trace_dump(self.h, path.encode())
+
+    def destroy(self):
+        if self.h is not None:
+            rc = mgb_sched_destroy(self.h)
+            if rc == MGB_OK:
+                self.h = None
+            return rc
+        return MGB_OK
+
+
+__all__ = [n for n in dir() if n.startswith(("mgb_", "MGB_"))] + [
+    "lib", "LIB_PATH", "TRACE_DT", "ENQUEUE_FN", "EXPORTS", "MgbError", "check", "default_desc",
+    "dev_ptr", "probe_of", "Sched"]

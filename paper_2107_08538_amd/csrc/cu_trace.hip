@@ -1,0 +1,31 @@
+// Diagnostic kernel: record on which physical compute unit each workgroup ran.
+// Used to show that a placement's CU-masked stream confines work to its
+// granules and that disjoint granule sets are disjoint sets of physical CUs.
+#include "../../include/mgb.h"
+#include "launch_util.h"
+
+#include <hip/hip_runtime.h>
+
+namespace {
+
+__global__ __launch_bounds__(64) void cu_trace_kernel(uint32_t* __restrict__ out, uint32_t spin_clocks) {
+  uint32_t hw_id, xcc_id;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw_id));
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc_id));
+  // stay resident for a bounded while so that later workgroups land on other CUs
+  const unsigned long long t0 = clock64();
+  while (clock64() - t0 < (unsigned long long)spin_clocks) {
+  }
+  if (threadIdx.x == 0) {
+    const uint32_t cu = (hw_id >> 8) & 0xfu, se = (hw_id >> 13) & 0x7u, xcc = xcc_id & 0xfu;
+    out[blockIdx.x] = (xcc << 8) | (se << 4) | cu;
+  }
+}
+
+}  // namespace
+
+extern "C" int mgb_cu_trace_enqueue(void* stream, uint32_t* out, uint32_t n_blocks) {
+  if (!out || n_blocks == 0u || n_blocks > (1u << 20)) return MGB_E_INVAL;
+  hipLaunchKernelGGL(cu_trace_kernel, dim3(n_blocks), dim3(64), 0, (hipStream_t)stream, out, 20000u);
+  return mgb_check_launch("cu_trace_kernel");
+}

@@ -1,0 +1,524 @@
+// Scheduler core: memory ledger, CU-granule partitioner, wait queue, event
+// trace, and the stream backend behind placements.
+//
+// One device, one mutex.  The policy follows Sec. III-B of the paper
+// (Algorithm 2: memory and compute both hard; Algorithm 3: memory hard,
+// compute placed by load) with the device's SMs replaced by granules of CUs
+// that are handed out exclusively (HARD) and realised as CU-masked streams.
+#include "../../include/mgb.h"
+#include "launch_util.h"
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+
+#include <algorithm>
+#include <chrono>
+#include <condition_variable>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <map>
+#include <mutex>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+namespace {
+
+thread_local std::string g_last_error;
+
+void set_error(const char* what, hipError_t e) {
+  g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+}
+
+uint64_t now_ns() {
+  return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+             std::chrono::steady_clock::now().time_since_epoch())
+      .count();
+}
+
+enum class State { Waiting, Running };
+
+struct Task {
+  uint64_t ticket = 0, task_id = 0, mem = 0, waves = 0, share = 0;
+  uint32_t demand = 0, granted = 0;
+  mgb_dim3 grid{}, block{};
+  State state = State::Waiting;
+  hipStream_t stream = nullptr;
+  hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+  bool launched = false;
+};
+
+}  // namespace
+
+void mgb_internal_set_error(const char* what, hipError_t e) { set_error(what, e); }
+void mgb_internal_set_error_text(const char* text) { g_last_error = text; }
+
+struct mgb_sched {
+  mgb_device_desc d{};
+  uint32_t G = 0;            // number of granules
+  uint32_t all_mask = 0;
+  std::mutex mu;
+  std::condition_variable cv;
+  uint64_t free_bytes = 0;
+  uint32_t free_map = 0;
+  std::vector<uint64_t> load;                 // SOFT: in-use waves per granule
+  std::unordered_map<uint64_t, Task> tasks;   // live tasks by ticket
+  std::deque<uint64_t> waitq;                 // tickets in arrival order
+  uint64_t next_ticket = 0;
+  std::vector<mgb_trace_rec> trace;
+  // backend: idle masked streams by granule mask, idle timing events
+  std::multimap<uint32_t, hipStream_t> idle_streams;
+  std::vector<hipEvent_t> idle_events;
+  uint32_t n_streams = 0;
+
+  void cu_mask_of(uint32_t gmask, uint32_t out[8]) const {
+    std::memset(out, 0, 8 * sizeof(uint32_t));
+    for (uint32_t g = 0; g < G; ++g) {
+      if (!(gmask >> g & 1u)) continue;
+      for (uint32_t c = 0; c < d.granule_cus; ++c) {
+        uint32_t bit = g * d.granule_cus + c;
+        out[bit >> 5] |= 1u << (bit & 31);
+      }
+    }
+  }
+
+  uint64_t log(uint32_t kind, const Task* t, uint64_t task_id, uint64_t ticket, uint64_t mem,
+               mgb_dim3 grid, mgb_dim3 block, uint32_t gmask, int32_t code, uint64_t cause) {
+    mgb_trace_rec r;
+    std::memset(&r, 0, sizeof r);
+    r.seq = trace.size();
+    r.t_ns = now_ns();
+    r.task_id = t ? t->task_id : task_id;
+    r.ticket = t ? t->ticket : ticket;
+    r.mem_bytes = t ? t->mem : mem;
+    r.free_bytes = free_bytes;
+    r.kind = kind;
+    r.code = code;
+    r.granule_mask = gmask;
+    r.free_granules = free_map;
+    r.demand = t ? t->demand : 0;
+    r.cause_seq = (uint32_t)cause;
+    r.grid = t ? t->grid : grid;
+    r.block = t ? t->block : block;
+    cu_mask_of(gmask, r.cu_mask);
+    trace.push_back(r);
+    return r.seq;
+  }
+
+  // Memory first (hard in every policy), then compute.
+  bool try_admit(Task& t) {
+    if (t.mem > free_bytes) return false;
+    uint32_t pick = 0;
+    if (d.policy == MGB_POLICY_SOFT) {
+      // never blocks on compute: the `demand` granules carrying the fewest
+      // in-use waves, lower index winning ties
+      uint32_t taken = 0;
+      for (uint32_t n = 0; n < t.demand; ++n) {
+        uint32_t best = G;
+        for (uint32_t g = 0; g < G; ++g) {
+          if (taken >> g & 1u) continue;
+          if (best == G || load[g] < load[best]) best = g;
+        }
+        taken |= 1u << best;
+      }
+      pick = taken;
+      t.share = (t.waves + t.demand - 1) / t.demand;
+      for (uint32_t g = 0; g < G; ++g)
+        if (pick >> g & 1u) load[g] += t.share;
+    } else {
+      if ((uint32_t)__builtin_popcount(free_map) < t.demand) return false;
+      uint32_t m = free_map;
+      for (uint32_t n = 0; n < t.demand; ++n) {
+        uint32_t low = m & (~m + 1u);  // lowest free granule
+        pick |= low;
+        m &= ~low;
+      }
+      free_map &= ~pick;
+    }
+    free_bytes -= t.mem;
+    t.granted = pick;
+    t.state = State::Running;
+    return true;
+  }
+
+  void release(Task& t) {
+    free_bytes += t.mem;
+    if (d.policy == MGB_POLICY_SOFT) {
+      for (uint32_t g = 0; g < G; ++g)
+        if (t.granted >> g & 1u) load[g] -= t.share;
+    } else {
+      free_map |= t.granted;
+    }
+  }
+
+  // Offer what is free to the waiters, oldest first.
+  bool rescan(uint64_t cause) {
+    bool any = false;
+    for (size_t i = 0; i < waitq.size();) {
+      Task& t = tasks[waitq[i]];
+      if (try_admit(t)) {
+        waitq.erase(waitq.begin() + (long)i);
+        log(MGB_EV_ADMIT, &t, 0, 0, 0, {}, {}, t.granted, 0, cause);
+        any = true;
+      } else if (d.queue_mode == MGB_QUEUE_FIFO) {
+        break;
+      } else {
+        ++i;
+      }
+    }
+    return any;
+  }
+
+  // ---- backend -----------------------------------------------------------
+  int bind_stream(Task& t) {
+    if (d.backend != MGB_BACKEND_HIP) return MGB_OK;
+    if (t.stream) return MGB_OK;
+    auto it = idle_streams.find(t.granted);
+    if (it != idle_streams.end()) {
+      t.stream = it->second;
+      idle_streams.erase(it);
+    } else {
+      uint32_t cu[8];
+      cu_mask_of(t.granted, cu);
+      hipError_t e = hipSetDevice(d.device);
+      if (e == hipSuccess) e = hipExtStreamCreateWithCUMask(&t.stream, 8, cu);
+      if (e != hipSuccess) {
+        set_error("hipExtStreamCreateWithCUMask", e);
+        t.stream = nullptr;
+        return MGB_E_BACKEND;
+      }
+      ++n_streams;
+    }
+    for (hipEvent_t* ev : {&t.ev_start, &t.ev_stop}) {
+      if (!idle_events.empty()) {
+        *ev = idle_events.back();
+        idle_events.pop_back();
+      } else {
+        hipError_t e = hipEventCreate(ev);
+        if (e != hipSuccess) {
+          set_error("hipEventCreate", e);
+          return MGB_E_BACKEND;
+        }
+      }
+    }
+    return MGB_OK;
+  }
+
+  void unbind_stream(Task& t) {
+    if (t.stream) idle_streams.emplace(t.granted, t.stream);
+    if (t.ev_start) idle_events.push_back(t.ev_start);
+    if (t.ev_stop) idle_events.push_back(t.ev_stop);
+    t.stream = nullptr;
+    t.ev_start = t.ev_stop = nullptr;
+  }
+
+  int fill(Task& t, mgb_placement* out) {
+    int rc = bind_stream(t);
+    out->ticket = t.ticket;
+    out->granule_mask = t.granted;
+    out->n_granules = t.demand;
+    cu_mask_of(t.granted, out->cu_mask);
+    out->stream = (void*)t.stream;
+    return rc;
+  }
+};
+
+extern "C" {
+
+const char* mgb_last_error(void) { return g_last_error.c_str(); }
+
+void mgb_device_desc_default(mgb_device_desc* out) {
+  if (!out) return;
+  std::memset(out, 0, sizeof *out);
+  out->mem_cap_bytes = 288ull * 1000 * 1000 * 1000;
+  out->n_cu = 256;
+  out->granule_cus = 8;
+  out->wave_size = 64;
+  out->max_waves_per_cu = 32;
+  out->max_wg_per_cu = 32;
+  out->policy = MGB_POLICY_HARD;
+  out->queue_mode = MGB_QUEUE_BACKFILL;
+  out->backend = MGB_BACKEND_HIP;
+  out->device = 0;
+}
+
+int mgb_sched_create(const mgb_device_desc* desc, mgb_sched** out) {
+  if (!desc || !out) return MGB_E_INVAL;
+  *out = nullptr;
+  const mgb_device_desc& d = *desc;
+  if (d.n_cu == 0 || d.granule_cus == 0 || d.n_cu % d.granule_cus != 0) return MGB_E_INVAL;
+  if (d.n_cu > 256 || d.n_cu / d.granule_cus > 32) return MGB_E_INVAL;
+  if (d.wave_size == 0 || d.max_waves_per_cu == 0 || d.max_wg_per_cu == 0) return MGB_E_INVAL;
+  if (d.policy > MGB_POLICY_SERIAL || d.queue_mode > MGB_QUEUE_FIFO) return MGB_E_INVAL;
+  if (d.backend > MGB_BACKEND_HIP) return MGB_E_INVAL;
+  if (d.backend == MGB_BACKEND_HIP) {
+    // a mask must keep at least one CU in each of the 8 XCDs
+    if (d.granule_cus % 8 != 0) return MGB_E_INVAL;
+    int count = 0;
+    hipError_t e = hipGetDeviceCount(&count);
+    if (e != hipSuccess || d.device < 0 || d.device >= count) {
+      set_error("hipGetDeviceCount", e == hipSuccess ? hipErrorInvalidDevice : e);
+      return MGB_E_BACKEND;
+    }
+    hipDeviceProp_t p;
+    e = hipGetDeviceProperties(&p, d.device);
+    if (e != hipSuccess) {
+      set_error("hipGetDeviceProperties", e);
+      return MGB_E_BACKEND;
+    }
+    if ((uint32_t)p.multiProcessorCount != d.n_cu) {
+      g_last_error = "device CU count does not match descriptor n_cu";
+      return MGB_E_BACKEND;
+    }
+  }
+  mgb_sched* s = new (std::nothrow) mgb_sched;
+  if (!s) return MGB_E_BACKEND;
+  s->d = d;
+  s->G = d.n_cu / d.granule_cus;
+  s->all_mask = s->G >= 32 ? 0xffffffffu : ((1u << s->G) - 1u);
+  s->free_bytes = d.mem_cap_bytes;
+  s->free_map = s->all_mask;
+  s->load.assign(s->G, 0);
+  *out = s;
+  return MGB_OK;
+}
+
+int mgb_sched_destroy(mgb_sched* s) {
+  if (!s) return MGB_E_INVAL;
+  {
+    std::lock_guard<std::mutex> lk(s->mu);
+    if (!s->tasks.empty()) return MGB_E_BUSY;
+    for (auto& kv : s->idle_streams) (void)hipStreamDestroy(kv.second);
+    for (hipEvent_t e : s->idle_events) (void)hipEventDestroy(e);
+    s->idle_streams.clear();
+    s->idle_events.clear();
+  }
+  delete s;
+  return MGB_OK;
+}
+
+int mgb_task_probe(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 grid,
+                   mgb_dim3 block, mgb_placement* out) {
+  if (!s || !out) return MGB_E_INVAL;
+  std::memset(out, 0, sizeof *out);
+  std::lock_guard<std::mutex> lk(s->mu);
+  uint64_t cause = s->log(MGB_EV_PROBE, nullptr, task_id, 0, mem_bytes, grid, block, 0, 0, 0);
+  s->trace.back().cause_seq = (uint32_t)cause;
+  const uint64_t W = (uint64_t)grid.x * grid.y * grid.z;
+  const uint64_t T = (uint64_t)block.x * block.y * block.z;
+  if (W == 0 || T == 0 || T > 1024) {
+    s->log(MGB_EV_REJECT, nullptr, task_id, 0, mem_bytes, grid, block, 0, MGB_E_INVAL, cause);
+    return MGB_E_INVAL;
+  }
+  if (mem_bytes > s->d.mem_cap_bytes) {
+    s->log(MGB_EV_REJECT, nullptr, task_id, 0, mem_bytes, grid, block, 0, MGB_E_TOO_BIG, cause);
+    return MGB_E_TOO_BIG;
+  }
+  // residency-based compute demand (per-CU wave and workgroup limits)
+  const uint64_t waves_per_wg = (T + s->d.wave_size - 1) / s->d.wave_size;
+  uint64_t wg_per_cu = s->d.max_waves_per_cu / waves_per_wg;
+  wg_per_cu = std::max<uint64_t>(1, std::min<uint64_t>(wg_per_cu, s->d.max_wg_per_cu));
+  const uint64_t cus = std::min<uint64_t>(s->d.n_cu, (W + wg_per_cu - 1) / wg_per_cu);
+  Task t;
+  t.ticket = ++s->next_ticket;
+  t.task_id = task_id;
+  t.mem = mem_bytes;
+  t.waves = W * waves_per_wg;
+  t.demand = (uint32_t)((cus + s->d.granule_cus - 1) / s->d.granule_cus);
+  if (s->d.policy == MGB_POLICY_SERIAL) t.demand = s->G;
+  t.grid = grid;
+  t.block = block;
+  Task& ref = s->tasks.emplace(t.ticket, t).first->second;
+  const bool behind_queue = s->d.queue_mode == MGB_QUEUE_FIFO && !s->waitq.empty();
+  if (!behind_queue && s->try_admit(ref)) {
+    s->log(MGB_EV_ADMIT, &ref, 0, 0, 0, {}, {}, ref.granted, 0, cause);
+    return s->fill(ref, out);
+  }
+  s->waitq.push_back(ref.ticket);
+  s->log(MGB_EV_QUEUED, &ref, 0, 0, 0, {}, {}, 0, 0, cause);
+  out->ticket = ref.ticket;
+  out->n_granules = ref.demand;
+  return MGB_WAIT;
+}
+
+int mgb_task_wait(mgb_sched* s, uint64_t ticket, int64_t timeout_ns, mgb_placement* out) {
+  if (!s || !out) return MGB_E_INVAL;
+  std::unique_lock<std::mutex> lk(s->mu);
+  auto admitted = [&]() {
+    auto it = s->tasks.find(ticket);
+    return it == s->tasks.end() || it->second.state == State::Running;
+  };
+  if (s->tasks.find(ticket) == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;
+  if (timeout_ns < 0) {
+    s->cv.wait(lk, admitted);
+  } else if (!s->cv.wait_for(lk, std::chrono::nanoseconds(timeout_ns), admitted)) {
+    return MGB_TIMEOUT;
+  }
+  auto it = s->tasks.find(ticket);
+  if (it == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;  // cancelled meanwhile
+  return s->fill(it->second, out);
+}
+
+int mgb_task_cancel(mgb_sched* s, uint64_t ticket) {
+  if (!s) return MGB_E_INVAL;
+  std::lock_guard<std::mutex> lk(s->mu);
+  uint64_t cause = s->log(MGB_EV_CANCEL, nullptr, 0, ticket, 0, {}, {}, 0, 0, 0);
+  s->trace.back().cause_seq = (uint32_t)cause;
+  auto it = s->tasks.find(ticket);
+  if (it == s->tasks.end()) {
+    s->log(MGB_EV_REJECT, nullptr, 0, ticket, 0, {}, {}, 0, MGB_E_UNKNOWN_TICKET, cause);
+    return MGB_E_UNKNOWN_TICKET;
+  }
+  if (it->second.state != State::Waiting) {
+    s->log(MGB_EV_REJECT, &it->second, 0, 0, 0, {}, {}, 0, MGB_E_BAD_STATE, cause);
+    return MGB_E_BAD_STATE;
+  }
+  s->log(MGB_EV_CANCELLED, &it->second, 0, 0, 0, {}, {}, 0, 0, cause);
+  s->waitq.erase(std::find(s->waitq.begin(), s->waitq.end(), ticket));
+  s->tasks.erase(it);
+  s->rescan(cause);
+  s->cv.notify_all();
+  return MGB_OK;
+}
+
+int mgb_task_launch(mgb_sched* s, uint64_t ticket, int (*enqueue)(void* stream, void* user),
+                    void* user) {
+  if (!s || !enqueue) return MGB_E_INVAL;
+  hipStream_t stream = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  bool hip = false;
+  {
+    std::lock_guard<std::mutex> lk(s->mu);
+    auto it = s->tasks.find(ticket);
+    if (it == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;
+    if (it->second.state != State::Running) return MGB_E_BAD_STATE;
+    hip = s->d.backend == MGB_BACKEND_HIP;
+    if (hip) {
+      int rc = s->bind_stream(it->second);
+      if (rc != MGB_OK) return rc;
+    }
+    stream = it->second.stream;
+    e0 = it->second.ev_start;
+    e1 = it->second.ev_stop;
+    it->second.launched = true;
+  }
+  if (hip) {
+    hipError_t e = hipSetDevice(s->d.device);
+    if (e == hipSuccess) e = hipEventRecord(e0, stream);
+    if (e != hipSuccess) {
+      set_error("hipEventRecord", e);
+      return MGB_E_BACKEND;
+    }
+  }
+  int rc = enqueue((void*)stream, user);
+  if (hip) {
+    hipError_t e = hipEventRecord(e1, stream);
+    if (e != hipSuccess) {
+      set_error("hipEventRecord", e);
+      return MGB_E_BACKEND;
+    }
+  }
+  return rc;
+}
+
+int mgb_task_sync(mgb_sched* s, uint64_t ticket, double* gpu_ms) {
+  if (!s) return MGB_E_INVAL;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  bool launched = false;
+  {
+    std::lock_guard<std::mutex> lk(s->mu);
+    auto it = s->tasks.find(ticket);
+    if (it == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;
+    if (it->second.state != State::Running) return MGB_E_BAD_STATE;
+    e0 = it->second.ev_start;
+    e1 = it->second.ev_stop;
+    launched = it->second.launched;
+  }
+  if (gpu_ms) *gpu_ms = 0.0;
+  if (s->d.backend != MGB_BACKEND_HIP || !launched) return MGB_OK;
+  hipError_t e = hipEventSynchronize(e1);
+  if (e != hipSuccess) {
+    set_error("hipEventSynchronize", e);
+    return MGB_E_BACKEND;
+  }
+  if (gpu_ms) {
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, e0, e1);
+    if (e != hipSuccess) {
+      set_error("hipEventElapsedTime", e);
+      return MGB_E_BACKEND;
+    }
+    *gpu_ms = ms;
+  }
+  return MGB_OK;
+}
+
+int mgb_task_complete(mgb_sched* s, uint64_t ticket) {
+  if (!s) return MGB_E_INVAL;
+  std::lock_guard<std::mutex> lk(s->mu);
+  uint64_t cause = s->log(MGB_EV_COMPLETE, nullptr, 0, ticket, 0, {}, {}, 0, 0, 0);
+  s->trace.back().cause_seq = (uint32_t)cause;
+  auto it = s->tasks.find(ticket);
+  if (it == s->tasks.end()) {
+    s->log(MGB_EV_REJECT, nullptr, 0, ticket, 0, {}, {}, 0, MGB_E_UNKNOWN_TICKET, cause);
+    return MGB_E_UNKNOWN_TICKET;
+  }
+  Task& t = it->second;
+  if (t.state != State::Running) {
+    s->log(MGB_EV_REJECT, &t, 0, 0, 0, {}, {}, 0, MGB_E_BAD_STATE, cause);
+    return MGB_E_BAD_STATE;
+  }
+  s->release(t);
+  s->log(MGB_EV_RELEASE, &t, 0, 0, 0, {}, {}, t.granted, 0, cause);
+  s->unbind_stream(t);
+  s->tasks.erase(it);
+  if (s->rescan(cause)) s->cv.notify_all();
+  return MGB_OK;
+}
+
+int mgb_sched_stats(mgb_sched* s, mgb_stats* out) {
+  if (!s || !out) return MGB_E_INVAL;
+  std::lock_guard<std::mutex> lk(s->mu);
+  out->free_bytes = s->free_bytes;
+  out->free_granules = s->free_map;
+  out->n_waiting = (uint32_t)s->waitq.size();
+  out->n_running = (uint32_t)(s->tasks.size() - s->waitq.size());
+  out->n_streams = s->n_streams;
+  out->n_events = s->trace.size();
+  return MGB_OK;
+}
+
+int64_t mgb_trace_read(mgb_sched* s, uint64_t first, mgb_trace_rec* out, uint64_t cap) {
+  if (!s || (!out && cap)) return MGB_E_INVAL;
+  std::lock_guard<std::mutex> lk(s->mu);
+  if (first >= s->trace.size()) return 0;
+  uint64_t n = std::min<uint64_t>(cap, s->trace.size() - first);
+  std::memcpy(out, s->trace.data() + first, n * sizeof(mgb_trace_rec));
+  return (int64_t)n;
+}
+
+int mgb_trace_dump(mgb_sched* s, const char* path) {
+  if (!s || !path) return MGB_E_INVAL;
+  std::lock_guard<std::mutex> lk(s->mu);
+  FILE* f = std::fopen(path, "w");
+  if (!f) return MGB_E_INVAL;
+  for (const mgb_trace_rec& r : s->trace) {
+    std::fprintf(f,
+                 "{\"seq\":%llu,\"t_ns\":%llu,\"kind\":%u,\"task_id\":%llu,\"ticket\":%llu,"
+                 "\"mem_bytes\":%llu,\"free_bytes\":%llu,\"code\":%d,\"granule_mask\":%u,"
+                 "\"free_granules\":%u,\"demand\":%u,\"cause_seq\":%u,\"grid\":[%u,%u,%u],"
+                 "\"block\":[%u,%u,%u],\"cu_mask\":[%u,%u,%u,%u,%u,%u,%u,%u]}\n",
+                 (unsigned long long)r.seq, (unsigned long long)r.t_ns, r.kind,
+                 (unsigned long long)r.task_id, (unsigned long long)r.ticket,
+                 (unsigned long long)r.mem_bytes, (unsigned long long)r.free_bytes, r.code,
+                 r.granule_mask, r.free_granules, r.demand, r.cause_seq, r.grid.x, r.grid.y,
+                 r.grid.z, r.block.x, r.block.y, r.block.z, r.cu_mask[0], r.cu_mask[1],
+                 r.cu_mask[2], r.cu_mask[3], r.cu_mask[4], r.cu_mask[5], r.cu_mask[6],
+                 r.cu_mask[7]);
+  }
+  std::fclose(f);
+  return MGB_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,202 @@
+"""Host-side checks that run without a GPU: the library loads and exports what the header
+declares, and the scheduler core (null backend) agrees with the independent replay."""
+import ctypes as C
+import os
+import re
+import threading
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2107_08538_amd as mgb
+from helpers import assert_trace_matches_replay
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "mgb.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(mgb_[a-z0-9_]+)\s*\(", hdr))
+    assert len(declared) >= 27
+    for name in declared:
+        assert hasattr(mgb.lib, name), name
+    assert declared == set(mgb.EXPORTS)
+
+
+def test_struct_layouts_match_header():
+    assert C.sizeof(mgb.mgb_device_desc) == 48
+    assert C.sizeof(mgb.mgb_placement) == 56
+    assert mgb.TRACE_DT.itemsize == 128
+    d = mgb.default_desc()
+    assert (d.mem_cap_bytes, d.n_cu, d.granule_cus, d.wave_size) == (288 * 10 ** 9, 256, 8, 64)
+    assert (d.max_waves_per_cu, d.max_wg_per_cu, d.policy, d.queue_mode) == (32, 32, 0, 0)
+
+
+def _null(**kw):
+    return mgb.Sched(backend=mgb.MGB_BACKEND_NULL, **kw)
+
+
+def test_create_rejects_bad_descriptors():
+    h = C.c_void_p()
+    for kw in (dict(n_cu=0), dict(granule_cus=0), dict(n_cu=250), dict(granule_cus=4),
+               dict(policy=9), dict(queue_mode=5), dict(wave_size=0), dict(backend=7)):
+        d = mgb.default_desc(backend=mgb.MGB_BACKEND_NULL)
+        for k, v in kw.items():
+            setattr(d, k, v)
+        assert mgb.mgb_sched_create(C.byref(d), C.byref(h)) == mgb.MGB_E_INVAL, kw
+    assert mgb.mgb_sched_create(None, C.byref(h)) == mgb.MGB_E_INVAL
+    # the HIP backend refuses granules that could leave an XCD without CUs
+    d = mgb.default_desc(granule_cus=4)
+    assert mgb.mgb_sched_create(C.byref(d), C.byref(h)) == mgb.MGB_E_INVAL
+
+
+def test_error_paths_leave_the_ledger_unchanged():
+    s = _null(mem_cap_bytes=1000)
+    rc, pl = s.probe(1, 1001, (1, 1, 1), (64, 1, 1))
+    assert rc == mgb.MGB_E_TOO_BIG and s.stats().n_waiting == 0      # never queued
+    assert s.probe(1, 10, (0, 1, 1), (64, 1, 1))[0] == mgb.MGB_E_INVAL
+    assert s.probe(1, 10, (1, 1, 1), (1025, 1, 1))[0] == mgb.MGB_E_INVAL
+    assert s.probe(1, 10, (1, 1, 1), (32, 33, 1))[0] == mgb.MGB_E_INVAL
+    assert s.complete(77) == mgb.MGB_E_UNKNOWN_TICKET
+    rc, pl = s.probe(2, 600, (1, 1, 1), (64, 1, 1))
+    assert rc == mgb.MGB_OK and pl.granule_mask == 1 and pl.stream is None
+    rc, pl2 = s.probe(3, 600, (1, 1, 1), (64, 1, 1))
+    assert rc == mgb.MGB_WAIT
+    assert s.complete(pl2.ticket) == mgb.MGB_E_BAD_STATE              # still waiting
+    assert s.cancel(pl.ticket) == mgb.MGB_E_BAD_STATE                 # already running
+    assert s.wait(pl2.ticket, 1_000_000)[0] == mgb.MGB_TIMEOUT
+    assert s.destroy() == mgb.MGB_E_BUSY
+    st = s.stats()
+    assert (st.free_bytes, st.n_running, st.n_waiting) == (400, 1, 1)
+    assert s.complete(pl.ticket) == mgb.MGB_OK
+    assert s.complete(pl.ticket) == mgb.MGB_E_UNKNOWN_TICKET          # double complete
+    rc, pl3 = s.wait(pl2.ticket, 0)
+    assert rc == mgb.MGB_OK and pl3.ticket == pl2.ticket and pl3.granule_mask == 1
+    assert s.complete(pl2.ticket) == mgb.MGB_OK
+    assert s.stats().free_bytes == 1000 and s.stats().free_granules == 0xFFFFFFFF
+    assert_trace_matches_replay(s.desc, s.trace())
+    assert s.destroy() == mgb.MGB_OK
+
+
+def test_stuck_task_does_not_block_tasks_that_fit():
+    s = _null(mem_cap_bytes=1000)
+    rc, big = s.probe(1, 900, (100000, 1, 1), (256, 1, 1))            # whole device, never completes
+    assert rc == mgb.MGB_OK and big.granule_mask == 0xFFFFFFFF
+    rc, w = s.probe(2, 50, (1, 1, 1), (64, 1, 1))
+    assert rc == mgb.MGB_WAIT                                         # compute is hard: must wait
+    s2 = _null(mem_cap_bytes=1000)
+    rc, half = s2.probe(1, 900, (1024, 1, 1), (256, 1, 1))            # half the device, never completes
+    assert rc == mgb.MGB_OK and half.granule_mask == 0x0000FFFF
+    for i in range(16):
+        rc, pl = s2.probe(10 + i, 5, (8, 1, 1), (256, 1, 1))
+        assert rc == mgb.MGB_OK and pl.granule_mask == 1 << (16 + i)
+        assert list(pl.cu_mask) == [0] * (4 + i // 4) + [0xFF << (8 * (i % 4))] + [0] * (3 - i // 4)
+
+
+def _random_storm(s, rng, n_ops):
+    live = []
+    for i in range(n_ops):
+        if not live or rng.random() < 0.5:
+            mem = int(rng.integers(1, 6000))
+            grid = (int(rng.integers(0 if rng.random() < 0.02 else 1, 4000)), int(rng.integers(1, 3)), 1)
+            block = (int(rng.choice([64, 192, 256, 1024])), 1, 1)
+            rc, pl = s.probe(i, mem, grid, block)
+            if rc >= 0:
+                live.append(pl.ticket)
+        else:
+            t = live.pop(int(rng.integers(0, len(live))))
+            rc = s.complete(t) if rng.random() < 0.85 else s.cancel(t)
+            if rc < 0:
+                live.append(t)
+    for _ in range(len(live) + 1):
+        for t in list(live):
+            if s.complete(t) == mgb.MGB_OK:
+                live.remove(t)
+    return live
+
+
+@pytest.mark.parametrize("policy", [mgb.MGB_POLICY_HARD, mgb.MGB_POLICY_SOFT, mgb.MGB_POLICY_SERIAL])
+@pytest.mark.parametrize("mode", [mgb.MGB_QUEUE_BACKFILL, mgb.MGB_QUEUE_FIFO])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_library_decisions_equal_replay_on_random_streams(policy, mode, seed):
+    s = _null(mem_cap_bytes=10_000, policy=policy, queue_mode=mode)
+    left = _random_storm(s, np.random.default_rng(seed), 400)
+    assert not left
+    dec = assert_trace_matches_replay(s.desc, s.trace())
+    assert (dec["kind"] == oracle.D_ADMIT).sum() > 20
+    assert s.stats().free_bytes == 10_000
+    assert s.destroy() == mgb.MGB_OK
+
+
+def test_small_device_and_other_granule_shapes_equal_replay():
+    for n_cu, g in ((32, 8), (64, 2), (24, 1), (256, 64)):
+        s = _null(mem_cap_bytes=5000, n_cu=n_cu, granule_cus=g, max_wg_per_cu=8, max_waves_per_cu=40)
+        _random_storm(s, np.random.default_rng(n_cu), 300)
+        assert_trace_matches_replay(s.desc, s.trace())
+
+
+def test_concurrent_probe_complete_storm_is_consistent():
+    s = _null(mem_cap_bytes=50_000)
+    errors = []
+
+    def worker(k):
+        rng = np.random.default_rng(100 + k)
+        try:
+            for i in range(150):
+                mem = int(rng.integers(1, 20_000))
+                grid = (int(rng.integers(1, 3000)), 1, 1)
+                rc, pl = s.probe(k * 1000 + i, mem, grid, (256, 1, 1))
+                if rc == mgb.MGB_WAIT:
+                    rc, pl = s.wait(pl.ticket, -1)
+                assert rc == mgb.MGB_OK and pl.granule_mask != 0
+                assert s.complete(pl.ticket) == mgb.MGB_OK
+        except Exception as e:          # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=120)
+    assert not errors and not any(t.is_alive() for t in threads)
+    st = s.stats()
+    assert (st.free_bytes, st.n_running, st.n_waiting) == (50_000, 0, 0)
+    assert_trace_matches_replay(s.desc, s.trace())       # whatever the interleaving was, it replays
+    assert s.destroy() == mgb.MGB_OK
+
+
+def test_launch_and_sync_with_null_backend_and_trace_dump(tmp_path):
+    s = _null()
+    rc, pl = s.probe(5, 100, (10, 1, 1), (256, 1, 1))
+    seen = []
+    assert s.launch(pl.ticket, lambda stream: seen.append(stream) or 0) == 0
+    assert seen == [None]
+    assert s.launch(pl.ticket, lambda stream: 7) == 7                 # enqueue status is passed back
+    assert s.launch(999, lambda stream: 0) == mgb.MGB_E_UNKNOWN_TICKET
+    assert s.sync(pl.ticket) == (0, 0.0)
+    assert s.complete(pl.ticket) == 0
+    p = str(tmp_path / "trace.jsonl")
+    assert s.dump(p) == 0
+    import json
+    lines = [json.loads(l) for l in open(p)]
+    assert [l["kind"] for l in lines] == [0, 16, 1, 19] and lines[1]["cu_mask"][0] == 0xFF
+
+
+def test_probe_functions_agree_with_checker_formulas():
+    out = (C.c_uint64 * 7)()
+    for n in (3, 4, 5, 64, 77, 512, 1023, 1024, 1025, 4096, 16384):
+        mem, grid, block = mgb.probe_of(mgb.mgb_jacobi_probe, n, 10)
+        oracle.lib().orc_jacobi_probe(C.c_uint64(n), out)
+        assert [mem, *grid.tuple(), *block.tuple()] == list(out), n
+    for m, n, k in ((1, 1, 1), (128, 128, 16), (129, 257, 17), (256, 256, 256), (4096, 4096, 4096),
+                    (32768, 32768, 32768), (1000, 3000, 50)):
+        mem, grid, block = mgb.probe_of(mgb.mgb_gemm_f32_probe, m, n, k)
+        oracle.lib().orc_gemm_f32_probe(C.c_uint64(m), C.c_uint64(n), C.c_uint64(k), out)
+        assert [mem, *grid.tuple(), *block.tuple()] == list(out), (m, n, k)
+    mem, grid, block = mgb.mgb_dim3(), None, None
+    assert mgb.mgb_jacobi_probe(2, 1, C.byref(C.c_uint64()), C.byref(mgb.mgb_dim3()),
+                                C.byref(mgb.mgb_dim3())) == mgb.MGB_E_UNSUPPORTED
+    assert mgb.mgb_gemm_f32_probe(0, 1, 1, C.byref(C.c_uint64()), C.byref(mgb.mgb_dim3()),
+                                  C.byref(mgb.mgb_dim3())) == mgb.MGB_E_UNSUPPORTED

@@ -1,0 +1,193 @@
+"""The scheduler with the HIP backend: CU-masked placements, end-to-end Mix-4, trace replay."""
+import ctypes as C
+import threading
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+from helpers import assert_trace_matches_replay
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+import paper_2107_08538_amd as mgb  # noqa: E402
+
+DEV = "cuda:0"
+
+
+def P(t):
+    return C.c_void_p(t.data_ptr())
+
+
+def _where(stream, n_blocks=4096):
+    out = torch.zeros(n_blocks, dtype=torch.int32, device=DEV)
+    assert mgb.mgb_cu_trace_enqueue(stream, P(out), n_blocks) == 0
+    torch.cuda.synchronize()
+    return set(out.cpu().numpy().tolist())
+
+
+def test_placements_are_disjoint_sets_of_physical_cus():
+    s = mgb.Sched()
+    pls = []
+    for i, wgs in enumerate((512, 64, 1024, 8)):                      # 8, 1, 16, 1 granules
+        rc, pl = s.probe(i, 1 << 20, (wgs, 1, 1), (256, 1, 1))
+        assert rc == mgb.MGB_OK and pl.stream
+        pls.append(pl)
+    assert [pl.n_granules for pl in pls] == [8, 1, 16, 1]
+    sets = [_where(pl.stream) for pl in pls]
+    for pl, cus in zip(pls, sets):
+        assert len(cus) == 8 * pl.n_granules                          # one CU per XCD per granule
+        per_xcd = np.bincount([c >> 8 for c in cus], minlength=8)
+        assert np.all(per_xcd == pl.n_granules)
+    for i in range(4):
+        for j in range(i + 1, 4):
+            assert not (sets[i] & sets[j])                            # disjoint masks, disjoint CUs
+    assert len(_where(None)) == 256                                   # an unmasked stream reaches all CUs
+    for pl in pls:
+        assert s.complete(pl.ticket) == 0
+    rc, pl = s.probe(9, 1, (512, 1, 1), (256, 1, 1))                  # streams are cached per mask
+    assert pl.granule_mask == pls[0].granule_mask and pl.stream == pls[0].stream
+    assert s.stats().n_streams == 4
+    assert s.complete(pl.ticket) == 0
+    assert s.destroy() == 0
+
+
+def _mix4_buffers(spec):
+    bufs = {}
+    for t in spec["tasks"]:
+        if t.kind == "jacobi":
+            u = W.jacobi_field(t.seed + t.task_id, t.params["n"])
+            u0 = torch.from_numpy(u).to(DEV)
+            bufs[t.task_id] = dict(host=u, u0=u0, u1=u0.clone())
+        else:
+            a, b = W.gemm_operands_f32(t.seed + t.task_id, t.params["m"], t.params["n"], t.params["k"])
+            bufs[t.task_id] = dict(a=a, b=b, A=torch.from_numpy(a).to(DEV), B=torch.from_numpy(b).to(DEV),
+                                   C=torch.zeros(t.params["m"], t.params["n"], device=DEV))
+    return bufs
+
+
+def test_mix4_end_to_end_matches_checker_and_replay():
+    spec = W.mix4(seed=4)
+    s = mgb.Sched(mem_cap_bytes=spec["cap_bytes"])
+    bufs = _mix4_buffers(spec)
+    torch.cuda.synchronize()
+    errors, placed = [], {}
+
+    def worker(t):
+        try:
+            b = bufs[t.task_id]
+            if t.kind == "jacobi":
+                mem, grid, block = mgb.probe_of(mgb.mgb_jacobi_probe, t.params["n"], t.params["iters"])
+                assert mem == b["u0"].numel() * 4 * 2                 # footprint = sum of allocations
+                fn = lambda st: mgb.mgb_jacobi_enqueue(st, P(b["u0"]), P(b["u1"]), t.params["n"], t.params["iters"])
+            else:
+                m, n, k = t.params["m"], t.params["n"], t.params["k"]
+                mem, grid, block = mgb.probe_of(mgb.mgb_gemm_f32_probe, m, n, k)
+                assert mem == (b["A"].numel() + b["B"].numel() + b["C"].numel()) * 4
+                fn = lambda st: mgb.mgb_gemm_f32_enqueue(st, P(b["A"]), P(b["B"]), P(b["C"]), m, n, k)
+            rc, pl = s.probe(t.task_id, mem, grid, block)
+            if rc == mgb.MGB_WAIT:
+                rc, pl = s.wait(pl.ticket)
+            assert rc == mgb.MGB_OK and pl.stream
+            placed[t.task_id] = (pl.granule_mask, pl.n_granules)
+            assert s.launch(pl.ticket, fn) == 0
+            rc, ms = s.sync(pl.ticket)
+            assert rc == 0 and ms > 0
+            assert s.complete(pl.ticket) == 0
+        except Exception as e:  # noqa: BLE001
+            errors.append((t.task_id, e))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in spec["tasks"]]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=100)
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for t in spec["tasks"]:
+        b = bufs[t.task_id]
+        if t.kind == "jacobi":
+            it = t.params["iters"]
+            got = (b["u0"] if it % 2 == 0 else b["u1"]).cpu().numpy()
+            assert np.array_equal(got, oracle.jacobi_f32(b["host"], it))
+            ref = oracle.jacobi_f64(b["host"], it)
+            assert (np.abs(got - ref)[1:-1, 1:-1] / ref[1:-1, 1:-1]).max() <= 1e-5
+        else:
+            got = b["C"].cpu().numpy().astype(np.float64)
+            ref, den = oracle.gemm_f32(b["a"], b["b"]), oracle.gemm_abs_f32(b["a"], b["b"])
+            assert (np.abs(got - ref) / den).max() <= 1e-4
+    # every task is small: one granule each, all four resident together
+    assert all(g == 1 for _, g in placed.values())
+    trace = s.trace()
+    dec = assert_trace_matches_replay(s.desc, trace)
+    assert (dec["kind"] == oracle.D_ADMIT).sum() == 4 and (dec["kind"] == oracle.D_WAIT).sum() == 0
+    assert s.stats().free_bytes == spec["cap_bytes"]
+    assert s.destroy() == 0
+
+
+def test_memory_pressure_queues_and_worst_wait_matches_replay():
+    # scaled-down pressure mix: summed footprints = 1.5 x cap, so admission must queue
+    spec = W.pressure32(seed=3, scale=1 / 32)
+    s = mgb.Sched(mem_cap_bytes=spec["cap_bytes"])
+    errors = []
+    bufs = {}
+    for t in spec["tasks"]:
+        if t.kind == "jacobi":
+            n = t.params["n"]
+            u0 = torch.from_numpy(W.jacobi_field(t.seed, n)).to(DEV)
+            bufs[t.task_id] = (u0, u0.clone())
+        else:
+            n = t.params["n"]
+            bufs[t.task_id] = (torch.randn(n, n, device=DEV), torch.randn(n, n, device=DEV),
+                               torch.zeros(n, n, device=DEV))
+    torch.cuda.synchronize()
+    # all 32 tasks arrive at t = 0: their probes are issued back to back in task-id order before
+    # anything runs, so those that do not fit must queue
+    jobs = []
+    for t in spec["tasks"]:
+        b = bufs[t.task_id]
+        if t.kind == "jacobi":
+            n, it = t.params["n"], t.params["iters"]
+            mem, grid, block = mgb.probe_of(mgb.mgb_jacobi_probe, n, it)
+            fn = (lambda b, n, it: lambda st: mgb.mgb_jacobi_enqueue(st, P(b[0]), P(b[1]), n, it))(b, n, it)
+        else:
+            n = t.params["n"]
+            mem, grid, block = mgb.probe_of(mgb.mgb_gemm_f32_probe, n, n, n)
+            fn = (lambda b, n: lambda st: mgb.mgb_gemm_f32_enqueue(st, P(b[0]), P(b[1]), P(b[2]), n, n, n))(b, n)
+        rc, pl = s.probe(t.task_id, mem, grid, block)
+        assert rc in (mgb.MGB_OK, mgb.MGB_WAIT)
+        jobs.append((t, rc, pl, fn))
+    assert s.stats().n_waiting > 0
+
+    def worker(t, rc, pl, fn):
+        try:
+            if rc == mgb.MGB_WAIT:
+                rc, pl = s.wait(pl.ticket)
+            assert rc == mgb.MGB_OK
+            assert s.launch(pl.ticket, fn) == 0
+            assert s.sync(pl.ticket)[0] == 0
+            assert s.complete(pl.ticket) == 0
+        except Exception as e:  # noqa: BLE001
+            errors.append((t.task_id, e))
+
+    threads = [threading.Thread(target=worker, args=j) for j in jobs]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=100)
+    assert not errors, errors
+    trace = s.trace()
+    dec = assert_trace_matches_replay(s.desc, trace)
+    assert (dec["kind"] == oracle.D_WAIT).sum() > 0                    # admission did queue
+    # the ledger never exceeded the cap, and every waiter was admitted at some release
+    assert trace["free_bytes"].max() <= spec["cap_bytes"]
+    admits = trace[trace["kind"] == mgb.MGB_EV_ADMIT]
+    assert len(admits) == 32
+    # worst waiting time, counted in events between a task's probe and its admission, agrees
+    # between the library's log and the replayed schedule (they are the same sequence)
+    probe_seq = {int(r["task_id"]): int(r["seq"]) for r in trace if r["kind"] == mgb.MGB_EV_PROBE}
+    waits_lib = {int(r["task_id"]): int(r["cause_seq"]) - probe_seq[int(r["task_id"])] for r in admits}
+    assert max(waits_lib.values()) > 0
+    assert s.destroy() == 0
