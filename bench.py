@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Bench: one "step" = one pass of a whole task mix (default Mix-16: 16 tasks, Poisson arrivals,
+Jacobi 4096^2 x100 / fp32 GEMM 4096^3 / BFS 2^20) through probe -> admit -> CU partition ->
+launch -> complete on one MI355X, inputs resident in HBM.  Prints ONE JSON line."""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--mix", default="mix16", choices=["mix4", "mix16", "cnn8", "mixed128"])
+    ap.add_argument("--policy", default="hard", choices=["hard", "soft", "serial"])
+    ap.add_argument("--queue", default="backfill", choices=["backfill", "fifo"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip serialised / alone / batch comparisons")
+    ap.add_argument("--seed", type=int, default=None)
+    return ap.parse_args()
+
+
+def cpu_baseline(spec):
+    """Serial CPU checker timed on a bounded sample of the same workload, scaled by work."""
+    import numpy as np
+    import oracle
+    import workloads as W
+    per_kind, sample = {}, []
+    kinds = {}
+    for t in spec["tasks"]:
+        kinds.setdefault((t.kind, tuple(sorted(t.params.items()))), t)
+    for (kind, _), t in kinds.items():
+        p = t.params
+        if kind == "jacobi":
+            it = max(1, min(p["iters"], int(3e8 // (p["n"] * p["n"]))))
+            u = W.jacobi_field(1, p["n"])
+            t0 = time.perf_counter(); oracle.jacobi_f32(u, it); dt = time.perf_counter() - t0
+            per_kind[(kind, tuple(sorted(p.items())))] = dt * p["iters"] / it
+            sample.append("jacobi %d^2 x%d of %d sweeps" % (p["n"], it, p["iters"]))
+        elif kind in ("gemm_f32", "gemm_bf16"):
+            s = min(p["m"], 1024)
+            a, b = W.gemm_operands_f32(1, s, s, s)
+            t0 = time.perf_counter(); oracle.gemm_f32(a, b); dt = time.perf_counter() - t0
+            per_kind[(kind, tuple(sorted(p.items())))] = dt * (p["m"] * p["n"] * p["k"]) / float(s) ** 3
+            sample.append("gemm %d^3 scaled by flops to %dx%dx%d (extrapolated)" % (s, p["m"], p["n"], p["k"]))
+        elif kind == "bfs":
+            n = min(p["n"], 1 << 20)
+            rp, ci = W.er_graph_csr(1, n, p["degree"])
+            t0 = time.perf_counter(); oracle.bfs(rp, ci, 0); dt = time.perf_counter() - t0
+            per_kind[(kind, tuple(sorted(p.items())))] = dt * p["n"] / n
+            sample.append("bfs n=%d degree %d" % (n, p["degree"]))
+        elif kind == "cnn":
+            h = 52
+            layers = W.cnn_layers(h, h)
+            wts = W.cnn_weights(1, layers)
+            x = W.cnn_input(1, 1, h, h)
+            t0 = time.perf_counter(); oracle.cnn_forward(x, wts, [L["stride"] for L in layers]); dt = time.perf_counter() - t0
+            per_kind[(kind, tuple(sorted(p.items())))] = dt * p["batch"] * (p["h"] * p["w"]) / float(h * h)
+            sample.append("cnn %dx%d batch 1 scaled by pixels (extrapolated)" % (h, h))
+    total = sum(per_kind[(t.kind, tuple(sorted(t.params.items())))] for t in spec["tasks"])
+    # serial FIFO on one core: task i starts when it has arrived and the previous one is done
+    clock, turn = 0.0, []
+    for t in spec["tasks"]:
+        clock = max(clock, t.arrival_s) + per_kind[(t.kind, tuple(sorted(t.params.items())))]
+        turn.append(clock - t.arrival_s)
+    return dict(value=len(spec["tasks"]) / clock, unit="tasks/s", cores=1, kind="oracle",
+                sample="; ".join(sample), est_seconds_per_mix=total,
+                mean_turnaround_ms=1e3 * sum(turn) / len(turn), nproc=os.cpu_count())
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures the one-GPU co-execution path only: run with --gpus 1 "
+              "(tasks never communicate; more GPUs would be more independent schedulers)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("no GPU visible: the HIP path cannot run and there is no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    if not os.path.exists(os.path.join(ROOT, "paper_2107_08538_amd", "libmgb.so")):
+        import __graft_entry__
+        __graft_entry__.build()
+    import paper_2107_08538_amd as mgb
+    from paper_2107_08538_amd import harness
+    import workloads as W
+
+    mixfn = W.MIXES[args.mix]
+    spec = mixfn(args.seed) if args.seed is not None else mixfn()
+    tasks = []
+    t_gen = time.perf_counter()
+    for t in spec["tasks"]:
+        tasks.append(harness.build_task(t, W.task_data(t)))
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    pol = dict(hard=mgb.MGB_POLICY_HARD, soft=mgb.MGB_POLICY_SOFT, serial=mgb.MGB_POLICY_SERIAL)[args.policy]
+    qm = dict(backfill=mgb.MGB_QUEUE_BACKFILL, fifo=mgb.MGB_QUEUE_FIFO)[args.queue]
+    free_b, total_b = torch.cuda.mem_get_info()
+    cap = min(spec["cap_bytes"], total_b)
+    sched = mgb.Sched(policy=pol, queue_mode=qm, mem_cap_bytes=cap)
+
+    for _ in range(args.warmup):
+        harness.run_mix(sched, tasks)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    runs = []
+    for _ in range(args.steps):
+        runs.append(harness.run_mix(sched, tasks))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_tasks = len(tasks)
+    sums = [harness.summarize(r, m) for r, m in runs]
+    value = n_tasks * args.steps / elapsed
+    mean_turn = sum(s["mean_turnaround_ms"] for s in sums) / len(sums)
+
+    # per-kernel figures from the timed region (HIP events bracket each task on its own stream)
+    kern = {}
+    for rec, _ in runs:
+        for r, t in zip(rec, tasks):
+            k = kern.setdefault(t.kernel_name, dict(ms=0.0, launches=0, tasks=0, bytes=0.0, flops=0.0))
+            launches = t.launches if t.launches is not None else max(1, int(t.depth.value))
+            k["ms"] += r["gpu_ms"]; k["launches"] += launches; k["tasks"] += 1
+            k["bytes"] += t.alg_bytes; k["flops"] += t.alg_flops
+    dominant = max(kern, key=lambda n: kern[n]["ms"])
+    kd = kern[dominant]
+    peaks = dict(jacobi_sweep=("hbm", 8000.0, "GB/s"), bfs_level=("hbm", 8000.0, "GB/s"),
+                 gemm_f32_kernel=("mfma", 157.3, "TFLOP/s"), gemm_bf16_kernel=("mfma", 2500.0, "TFLOP/s"),
+                 conv3x3_kernel=("mfma", 2500.0, "TFLOP/s"))
+
+    def roof(name, k):
+        bound, peak, unit = peaks[name]
+        work = k["bytes"] / 1e9 if bound == "hbm" else k["flops"] / 1e12
+        ach = work / (k["ms"] / 1e3)
+        return dict(kernel=name, bound=bound, achieved=round(ach, 2), peak=peak, unit=unit,
+                    frac=round(ach / peak, 4), traffic=None,
+                    avg_launch_us=round(1e3 * k["ms"] / k["launches"], 2), launches=k["launches"])
+
+    out = dict(metric="aggregate tasks/s through probe+admit+partition+launch+complete (with mean turnaround, max slowdown)",
+               value=round(value, 2), unit="tasks/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=round(1e3 * elapsed / args.steps, 3), higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype="f32", data="synthetic",
+               config=dict(workload="%s: %s" % (spec["name"], ", ".join(sorted({t.kind for t in spec["tasks"]}))),
+                           policy=args.policy, queue=args.queue, tasks=n_tasks, workers=n_tasks,
+                           cap_bytes=cap, granule_cus=8, n_cu=256),
+               mean_turnaround_ms=round(mean_turn, 3),
+               mean_wait_ms=round(sum(s["mean_wait_ms"] for s in sums) / len(sums), 3),
+               input_gen_s=round(t_gen, 1))
+    out["roofline"] = roof(dominant, kd)
+    out["kernels"] = [roof(n, k) for n, k in kern.items() if n != dominant]
+
+    if not args.no_extras:
+        # the same mix, serialised: one task at a time on all 256 CUs in arrival order
+        ser = mgb.Sched(policy=mgb.MGB_POLICY_SERIAL, queue_mode=mgb.MGB_QUEUE_FIFO, mem_cap_bytes=cap)
+        harness.run_mix(ser, tasks)
+        t1 = time.perf_counter()
+        sruns = [harness.run_mix(ser, tasks) for _ in range(max(2, args.steps // 2))]
+        torch.cuda.synchronize()
+        sel = time.perf_counter() - t1
+        ssum = [harness.summarize(r, m) for r, m in sruns]
+        out["serialised_gpu"] = dict(tasks_per_s=round(n_tasks * len(sruns) / sel, 2),
+                                     mean_turnaround_ms=round(sum(s["mean_turnaround_ms"] for s in ssum) / len(ssum), 3))
+        # each task alone on the whole device -> slowdown of the co-run
+        alone = []
+        for t in tasks:
+            best = None
+            for _ in range(3):
+                rec, _m = harness.run_mix(ser, [t], use_arrivals=False)
+                best = rec[0]["gpu_ms"] if best is None else min(best, rec[0]["gpu_ms"])
+            alone.append(best)
+        co = [sum(run[0][i]["gpu_ms"] for run in runs) / len(runs) for i in range(n_tasks)]
+        slow = [c / a - 1.0 for c, a in zip(co, alone)]
+        out["max_slowdown_pct"] = round(100 * max(slow), 2)
+        out["mean_slowdown_pct"] = round(100 * sum(slow) / len(slow), 2)
+        out["slowdown_by_kind_pct"] = {k: round(100 * max(s for s, t in zip(slow, tasks) if t.spec.kind == k), 2)
+                                       for k in sorted({t.spec.kind for t in tasks})}
+        out["alone_gpu_ms"] = {k: round(min(a for a, t in zip(alone, tasks) if t.spec.kind == k), 4)
+                               for k in sorted({t.spec.kind for t in tasks})}
+        out["speedup_vs_serialised"] = dict(
+            throughput=round(value / out["serialised_gpu"]["tasks_per_s"], 4),
+            turnaround=round(out["serialised_gpu"]["mean_turnaround_ms"] / mean_turn, 4))
+        # batch variant (all tasks queued at t = 0, the paper's setting): capacity rather than arrival bound
+        harness.run_mix(sched, tasks, use_arrivals=False)
+        b = [harness.summarize(*harness.run_mix(sched, tasks, use_arrivals=False)) for _ in range(3)]
+        bs = [harness.summarize(*harness.run_mix(ser, tasks, use_arrivals=False)) for _ in range(3)]
+        out["batch_t0"] = dict(tasks_per_s=round(sum(x["tasks_per_s"] for x in b) / 3, 2),
+                               mean_turnaround_ms=round(sum(x["mean_turnaround_ms"] for x in b) / 3, 3),
+                               serialised_tasks_per_s=round(sum(x["tasks_per_s"] for x in bs) / 3, 2),
+                               serialised_mean_turnaround_ms=round(sum(x["mean_turnaround_ms"] for x in bs) / 3, 3))
+        ser.destroy()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(spec)
+    sched.destroy()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

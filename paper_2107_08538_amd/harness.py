@@ -1,0 +1,164 @@
+"""Worker-pool harness that pushes a task mix through the scheduler (Sec. V-A of the paper: a pool
+of workers, each taking a job, running it and pulling the next; jobs either all queued at t = 0 or
+arriving over time).  Pure orchestration: every call below is one C-ABI entry point."""
+import ctypes as C
+import threading
+import time
+
+import torch
+
+from . import binding as mgb
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr())
+
+
+class Task:
+    """Device-resident buffers of one task plus its probe (footprint and geometry)."""
+
+    def __init__(self, spec, tensors, probe, enqueue, kernel_name, launches, alg_bytes=0.0, alg_flops=0.0):
+        self.spec = spec
+        self.tensors = tensors          # keeps the device buffers alive
+        self.mem, self.grid, self.block = probe
+        self.enqueue = enqueue          # fn(stream) -> status
+        self.kernel_name = kernel_name
+        self.launches = launches        # kernel launches per task (None if data dependent)
+        self.alg_bytes = alg_bytes      # algorithmic HBM bytes of the whole task
+        self.alg_flops = alg_flops
+
+
+def build_task(spec, data, device="cuda:0"):
+    """Upload one task's inputs (numpy arrays from the workload generators) and bind its entry points."""
+    k, p = spec.kind, spec.params
+    if k == "jacobi":
+        n, it = p["n"], p["iters"]
+        u0 = torch.from_numpy(data["u"]).to(device)
+        u1 = u0.clone()
+        probe = mgb.probe_of(mgb.mgb_jacobi_probe, n, it)
+        fn = lambda st: mgb.mgb_jacobi_enqueue(st, _ptr(u0), _ptr(u1), n, it)
+        return Task(spec, dict(u0=u0, u1=u1), probe, fn, "jacobi_sweep", it,
+                    alg_bytes=8.0 * (n - 2) * (n - 2) * it, alg_flops=4.0 * (n - 2) * (n - 2) * it)
+    if k == "gemm_f32":
+        m, n, kk = p["m"], p["n"], p["k"]
+        A, B = torch.from_numpy(data["a"]).to(device), torch.from_numpy(data["b"]).to(device)
+        Cc = torch.zeros(m, n, device=device)
+        probe = mgb.probe_of(mgb.mgb_gemm_f32_probe, m, n, kk)
+        fn = lambda st: mgb.mgb_gemm_f32_enqueue(st, _ptr(A), _ptr(B), _ptr(Cc), m, n, kk)
+        return Task(spec, dict(A=A, B=B, C=Cc), probe, fn, "gemm_f32_kernel", 1,
+                    alg_bytes=4.0 * (m * kk + kk * n + m * n), alg_flops=2.0 * m * n * kk)
+    if k == "gemm_bf16":
+        m, n, kk = p["m"], p["n"], p["k"]
+        A = torch.from_numpy(data["a"].view("int16")).to(device)
+        B = torch.from_numpy(data["b"].view("int16")).to(device)
+        Cc = torch.zeros(m, n, device=device)
+        probe = mgb.probe_of(mgb.mgb_gemm_bf16_probe, m, n, kk)
+        fn = lambda st: mgb.mgb_gemm_bf16_enqueue(st, _ptr(A), _ptr(B), _ptr(Cc), m, n, kk)
+        return Task(spec, dict(A=A, B=B, C=Cc), probe, fn, "gemm_bf16_kernel", 1,
+                    alg_bytes=2.0 * (m * kk + kk * n) + 4.0 * m * n, alg_flops=2.0 * m * n * kk)
+    if k == "bfs":
+        n = p["n"]
+        rp = torch.from_numpy(data["row_ptr"]).to(device)
+        ci = torch.from_numpy(data["col_idx"]).to(device)
+        m_edges = int(data["col_idx"].size)
+        level = torch.empty(n, dtype=torch.int32, device=device)
+        work = torch.zeros(mgb.mgb_bfs_work_bytes(n), dtype=torch.uint8, device=device)
+        probe = mgb.probe_of(mgb.mgb_bfs_probe, n, m_edges)
+        depth = C.c_uint32(0)
+        fn = lambda st: mgb.mgb_bfs_enqueue(st, _ptr(rp), _ptr(ci), n, 0, _ptr(level), _ptr(work), C.byref(depth))
+        t = Task(spec, dict(rp=rp, ci=ci, level=level, work=work), probe, fn, "bfs_level", None,
+                 alg_bytes=8.0 * m_edges + 24.0 * n)
+        t.depth = depth
+        return t
+    if k == "cnn":
+        layers = data["layers"]
+        arr = (mgb.mgb_conv_layer * len(layers))(*[mgb.mgb_conv_layer(L["c_in"], L["c_out"], L["stride"]) for L in layers])
+        b, h, w = p["batch"], p["h"], p["w"]
+        mem, act, ob = C.c_uint64(), C.c_uint64(), C.c_uint64()
+        g, blk = mgb.mgb_dim3(), mgb.mgb_dim3()
+        mgb.check(mgb.mgb_cnn_probe(arr, len(layers), b, h, w, C.byref(mem), C.byref(act), C.byref(ob),
+                                    C.byref(g), C.byref(blk)), "mgb_cnn_probe")
+        X = torch.from_numpy(data["x"].view("int16")).to(device)
+        Wd = [torch.from_numpy(x.view("int16")).to(device) for x in data["weights"]]
+        ptrs = (C.c_void_p * len(Wd))(*[t.data_ptr() for t in Wd])
+        a0 = torch.zeros(act.value // 2, dtype=torch.int16, device=device)
+        a1 = torch.zeros(act.value // 2, dtype=torch.int16, device=device)
+        out = torch.zeros(ob.value // 4, dtype=torch.float32, device=device)
+        fn = lambda st: mgb.mgb_cnn_enqueue(st, arr, len(layers), _ptr(X), ptrs, _ptr(a0), _ptr(a1), _ptr(out), b, h, w)
+        flops = sum(2.0 * b * L["h_out"] * L["w_out"] * L["c_out"] * 9 * L["c_in"] for L in layers)
+        return Task(spec, dict(X=X, W=Wd, a0=a0, a1=a1, out=out, arr=arr, ptrs=ptrs), (mem.value, g, blk), fn,
+                    "conv3x3_kernel", len(layers), alg_bytes=float(mem.value - act.value), alg_flops=flops)
+    raise ValueError(k)
+
+
+def run_mix(sched, tasks, use_arrivals=True, time_scale=1.0):
+    """Push every task through probe -> (wait) -> launch -> sync -> complete, one worker per task.
+
+    With use_arrivals the worker of task i issues its probe at t0 + arrival_i; otherwise all probes
+    are issued back to back in task-id order before anything runs (batch at t = 0).
+    Returns per-task records (times in seconds relative to t0) and the makespan."""
+    n = len(tasks)
+    rec = [dict(task_id=t.spec.task_id, kind=t.spec.kind) for t in tasks]
+    errors = []
+    placements = [None] * n
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+
+    if not use_arrivals:
+        for i, t in enumerate(tasks):
+            rec[i]["arrival"] = 0.0
+            rc, pl = sched.probe(t.spec.task_id, t.mem, t.grid, t.block)
+            mgb.check(rc, "mgb_task_probe")
+            rec[i]["probe"] = time.perf_counter() - t0
+            placements[i] = (rc, pl)
+
+    def worker(i):
+        t = tasks[i]
+        try:
+            if use_arrivals:
+                due = t0 + t.spec.arrival_s * time_scale
+                while True:
+                    dt = due - time.perf_counter()
+                    if dt <= 0:
+                        break
+                    time.sleep(dt if dt > 2e-4 else 0)
+                rec[i]["arrival"] = t.spec.arrival_s * time_scale
+                rc, pl = sched.probe(t.spec.task_id, t.mem, t.grid, t.block)
+                mgb.check(rc, "mgb_task_probe")
+                rec[i]["probe"] = time.perf_counter() - t0
+            else:
+                rc, pl = placements[i]
+            if rc == mgb.MGB_WAIT:
+                rc, pl = sched.wait(pl.ticket)
+                mgb.check(rc, "mgb_task_wait")
+            rec[i]["admit"] = time.perf_counter() - t0
+            rec[i]["granules"] = pl.n_granules
+            mgb.check(sched.launch(pl.ticket, t.enqueue), "mgb_task_launch")
+            rc, ms = sched.sync(pl.ticket)
+            mgb.check(rc, "mgb_task_sync")
+            rec[i]["gpu_ms"] = ms
+            rec[i]["done"] = time.perf_counter() - t0
+            mgb.check(sched.complete(pl.ticket), "mgb_task_complete")
+        except Exception as e:   # noqa: BLE001
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(n)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    makespan = time.perf_counter() - t0
+    if errors:
+        raise RuntimeError("mix failed: %r" % errors[:3])
+    return rec, makespan
+
+
+def summarize(rec, makespan):
+    n = len(rec)
+    turn = [r["done"] - r["arrival"] for r in rec]
+    last = max(r["done"] for r in rec)
+    first = min(r["arrival"] for r in rec)
+    return dict(tasks=n, tasks_per_s=n / (last - first), mean_turnaround_ms=1e3 * sum(turn) / n,
+                max_turnaround_ms=1e3 * max(turn), makespan_ms=1e3 * makespan,
+                mean_wait_ms=1e3 * sum(r["admit"] - r["probe"] for r in rec) / n)

@@ -90,3 +90,23 @@ def cnn_input(seed, batch, h=416, w=416, c=3):
     """NHWC input U[0,1) rounded to bf16 bits."""
     x = uniform01(seed ^ 0x77, batch * h * w * c).reshape(batch, h, w, c)
     return f32_to_bf16_bits(x)
+
+
+def task_data(spec):
+    """All host inputs of one task of a mix, keyed as the harness expects them."""
+    k, p, seed = spec.kind, spec.params, spec.seed
+    if k == "jacobi":
+        return dict(u=jacobi_field(seed, p["n"]))
+    if k == "gemm_f32":
+        a, b = gemm_operands_f32(seed, p["m"], p["n"], p["k"])
+        return dict(a=a, b=b)
+    if k == "gemm_bf16":
+        a, b = gemm_operands_bf16(seed, p["m"], p["n"], p["k"])
+        return dict(a=a, b=b)
+    if k == "bfs":
+        rp, ci = er_graph_csr(seed, p["n"], p["degree"])
+        return dict(row_ptr=rp, col_idx=ci)
+    if k == "cnn":
+        layers = cnn_layers(p["h"], p["w"])
+        return dict(layers=layers, weights=cnn_weights(seed, layers), x=cnn_input(seed, p["batch"], p["h"], p["w"]))
+    raise ValueError(k)
