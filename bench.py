@@ -93,12 +93,30 @@ def main():
 
     mixfn = W.MIXES[args.mix]
     spec = mixfn(args.seed) if args.seed is not None else mixfn()
-    tasks = []
     t_gen = time.perf_counter()
-    for t in spec["tasks"]:
-        tasks.append(harness.build_task(t, W.task_data(t)))
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:   # numpy releases the GIL
+        data = list(ex.map(W.task_data, spec["tasks"]))
+    tasks = [harness.build_task(t, d) for t, d in zip(spec["tasks"], data)]
+    del data
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
+
+    # measured stream-copy ceiling (plain copy kernel of known size, also the counter calibration point)
+    import ctypes as C
+    cbytes = 1 << 30
+    csrc = torch.empty(cbytes, dtype=torch.uint8, device="cuda:0")
+    cdst = torch.empty(cbytes, dtype=torch.uint8, device="cuda:0")
+    cs = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    mgb.mgb_copy_enqueue(cs, C.c_void_p(cdst.data_ptr()), C.c_void_p(csrc.data_ptr()), cbytes)
+    e0.record()
+    for _ in range(5):
+        mgb.mgb_copy_enqueue(cs, C.c_void_p(cdst.data_ptr()), C.c_void_p(csrc.data_ptr()), cbytes)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * cbytes / (e0.elapsed_time(e1) / 1e3) / 1e9
+    del csrc, cdst
 
     pol = dict(hard=mgb.MGB_POLICY_HARD, soft=mgb.MGB_POLICY_SOFT, serial=mgb.MGB_POLICY_SERIAL)[args.policy]
     qm = dict(backfill=mgb.MGB_QUEUE_BACKFILL, fifo=mgb.MGB_QUEUE_FIFO)[args.queue]
@@ -151,7 +169,7 @@ def main():
                            cap_bytes=cap, granule_cus=8, n_cu=256),
                mean_turnaround_ms=round(mean_turn, 3),
                mean_wait_ms=round(sum(s["mean_wait_ms"] for s in sums) / len(sums), 3),
-               input_gen_s=round(t_gen, 1))
+               input_gen_s=round(t_gen, 1), stream_copy_gbps=round(copy_gbps, 1))
     out["roofline"] = roof(dominant, kd)
     out["kernels"] = [roof(n, k) for n, k in kern.items() if n != dominant]
 
@@ -169,11 +187,9 @@ def main():
         # each task alone on the whole device -> slowdown of the co-run
         alone = []
         for t in tasks:
-            best = None
-            for _ in range(3):
-                rec, _m = harness.run_mix(ser, [t], use_arrivals=False)
-                best = rec[0]["gpu_ms"] if best is None else min(best, rec[0]["gpu_ms"])
-            alone.append(best)
+            harness.run_mix(ser, [t], use_arrivals=False)
+            vals = [harness.run_mix(ser, [t], use_arrivals=False)[0][0]["gpu_ms"] for _ in range(4)]
+            alone.append(sum(vals) / len(vals))
         co = [sum(run[0][i]["gpu_ms"] for run in runs) / len(runs) for i in range(n_tasks)]
         slow = [c / a - 1.0 for c, a in zip(co, alone)]
         out["max_slowdown_pct"] = round(100 * max(slow), 2)
@@ -181,6 +197,8 @@ def main():
         out["slowdown_by_kind_pct"] = {k: round(100 * max(s for s, t in zip(slow, tasks) if t.spec.kind == k), 2)
                                        for k in sorted({t.spec.kind for t in tasks})}
         out["alone_gpu_ms"] = {k: round(min(a for a, t in zip(alone, tasks) if t.spec.kind == k), 4)
+                               for k in sorted({t.spec.kind for t in tasks})}
+        out["corun_gpu_ms"] = {k: round(max(c for c, t in zip(co, tasks) if t.spec.kind == k), 4)
                                for k in sorted({t.spec.kind for t in tasks})}
         out["speedup_vs_serialised"] = dict(
             throughput=round(value / out["serialised_gpu"]["tasks_per_s"], 4),
@@ -193,6 +211,21 @@ def main():
                                mean_turnaround_ms=round(sum(x["mean_turnaround_ms"] for x in b) / 3, 3),
                                serialised_tasks_per_s=round(sum(x["tasks_per_s"] for x in bs) / 3, 2),
                                serialised_mean_turnaround_ms=round(sum(x["mean_turnaround_ms"] for x in bs) / 3, 3))
+        # the other policies on the same mix (Alg. 3 analogue with overlapping masks; FIFO queue)
+        sweep = {}
+        for name, pol2, q2 in (("soft_backfill", mgb.MGB_POLICY_SOFT, mgb.MGB_QUEUE_BACKFILL),
+                               ("hard_fifo", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_FIFO)):
+            s2 = mgb.Sched(policy=pol2, queue_mode=q2, mem_cap_bytes=cap)
+            harness.run_mix(s2, tasks)
+            a = [harness.summarize(*harness.run_mix(s2, tasks)) for _ in range(3)]
+            harness.run_mix(s2, tasks, use_arrivals=False)
+            bb = [harness.summarize(*harness.run_mix(s2, tasks, use_arrivals=False)) for _ in range(3)]
+            sweep[name] = dict(tasks_per_s=round(sum(x["tasks_per_s"] for x in a) / 3, 2),
+                               mean_turnaround_ms=round(sum(x["mean_turnaround_ms"] for x in a) / 3, 3),
+                               batch_tasks_per_s=round(sum(x["tasks_per_s"] for x in bb) / 3, 2),
+                               batch_mean_turnaround_ms=round(sum(x["mean_turnaround_ms"] for x in bb) / 3, 3))
+            s2.destroy()
+        out["other_policies"] = sweep
         ser.destroy()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(spec)

@@ -258,6 +258,12 @@ int mgb_bfs_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx
  * stream reaches.  n_blocks in [1, 2^20].                                    */
 int mgb_cu_trace_enqueue(void* stream, uint32_t* out, uint32_t n_blocks);
 
+/* Diagnostic: plain device-to-device copy of `bytes` (multiple of 16, both
+ * pointers 16-byte aligned) by a grid-stride kernel.  Moves exactly 2*bytes
+ * through HBM: the measured bandwidth ceiling and the calibration point for
+ * hardware traffic counters.                                                */
+int mgb_copy_enqueue(void* stream, void* dst, const void* src, uint64_t bytes);
+
 #ifdef __cplusplus
 }
 #endif

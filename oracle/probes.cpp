@@ -29,10 +29,65 @@ void orc_jacobi_probe(uint64_t n, uint64_t out[7]) {
   out[4] = 256; out[5] = 1; out[6] = 1;
 }
 
-// fp32 GEMM: A, B, C in fp32; one 256-thread workgroup per 128 x 128 tile of C.
+// fp32 GEMM: A, B, C in fp32; one 512-thread workgroup (8 waves) per 128 x 128 tile of C.
 void orc_gemm_f32_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
   out[0] = (m * k + k * n + m * n) * 4;
   out[1] = round8(ceil_div(m, 128) * ceil_div(n, 128)); out[2] = 1; out[3] = 1;
+  out[4] = 512; out[5] = 1; out[6] = 1;
+}
+
+// bf16 GEMM: bf16 A and B, fp32 C; one 256-thread workgroup per 128 x 128 tile of C.
+void orc_gemm_bf16_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
+  out[0] = (m * k + k * n) * 2 + m * n * 4;
+  out[1] = round8(ceil_div(m, 128) * ceil_div(n, 128)); out[2] = 1; out[3] = 1;
+  out[4] = 256; out[5] = 1; out[6] = 1;
+}
+
+// One 3x3 conv layer (pad 1): bf16 input, weights and output.  A 256-thread workgroup
+// covers 128 output pixels x 64 output channels (128 channels when c_out > 64).
+void orc_conv3x3_probe(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, uint64_t c_out,
+                       uint64_t stride, uint64_t out[7]) {
+  uint64_t ho = (h + 2 - 3) / stride + 1, wo = (w + 2 - 3) / stride + 1;
+  uint64_t pixels = batch * ho * wo;
+  uint64_t bn = c_out <= 64 ? 64 : 128;
+  out[0] = (batch * h * w * c_in + 9 * c_in * c_out + pixels * c_out) * 2;
+  out[1] = round8(ceil_div(pixels, 128) * ceil_div(c_out, bn)); out[2] = 1; out[3] = 1;
+  out[4] = 256; out[5] = 1; out[6] = 1;
+}
+
+// A chain of conv layers run as one task (launches that share buffers are merged into one
+// task): footprint = bf16 input + all weights + two ping-pong buffers of the largest
+// intermediate activation + the fp32 output of the last layer; geometry = the largest launch.
+// c[3*i..3*i+2] = {c_in, c_out, stride} of layer i.
+void orc_cnn_probe(const uint64_t* c, uint64_t n_layers, uint64_t batch, uint64_t h, uint64_t w,
+                   uint64_t out[7]) {
+  uint64_t mem = batch * h * w * c[0] * 2, act_max = 0, grid = 0, last = 0;
+  for (uint64_t i = 0; i < n_layers; ++i) {
+    uint64_t one[7];
+    orc_conv3x3_probe(batch, h, w, c[3 * i], c[3 * i + 1], c[3 * i + 2], one);
+    uint64_t ho = (h - 1) / c[3 * i + 2] + 1, wo = (w - 1) / c[3 * i + 2] + 1;
+    uint64_t elems = batch * ho * wo * c[3 * i + 1];
+    mem += 9 * c[3 * i] * c[3 * i + 1] * 2;
+    if (i + 1 < n_layers) { if (elems * 2 > act_max) act_max = elems * 2; }
+    else last = elems * 4;
+    if (one[1] > grid) grid = one[1];
+    h = ho; w = wo;
+  }
+  out[0] = mem + 2 * act_max + last;
+  out[1] = grid; out[2] = 1; out[3] = 1;
+  out[4] = 256; out[5] = 1; out[6] = 1;
+}
+
+// BFS: CSR (n+1 row pointers, m column indices), the level array, two frontier queues of n
+// entries (each rounded up to 256 bytes) and a 256-byte control block.  One 256-thread
+// workgroup per 1024 vertices, at least 8 and at most 2048.
+void orc_bfs_probe(uint64_t n, uint64_t m, uint64_t out[7]) {
+  uint64_t queue = ceil_div(n * 4, 256) * 256;
+  uint64_t wg = ceil_div(n, 1024);
+  if (wg < 8) wg = 8;
+  if (wg > 2048) wg = 2048;
+  out[0] = (n + 1 + m) * 4 + n * 4 + 256 + 2 * queue;
+  out[1] = round8(wg); out[2] = 1; out[3] = 1;
   out[4] = 256; out[5] = 1; out[6] = 1;
 }
 

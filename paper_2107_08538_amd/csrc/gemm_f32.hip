@@ -1,11 +1,17 @@
 // fp32 GEMM C = A * B (all row-major) on the fp32 matrix cores.
 //
 // MFMA-bound for all but tiny shapes (2*m*n*k flop over 4*(mk + kn + mn)
-// bytes).  One workgroup of 4 waves owns a 128 x 128 tile of C; each wave a
-// 64 x 64 quadrant as 2 x 2 blocks of v_mfma_f32_32x32x2_f32.  A and B tiles
-// of depth 16 are staged through LDS (double buffered, one barrier per step);
-// A is transposed on the way in so that both operands are read from LDS as
-// 32 consecutive floats per half-wave (no bank conflicts).
+// bytes).  One workgroup of 8 waves owns a 128 x 128 tile of C; each wave a
+// 32 x 64 piece as 1 x 2 blocks of v_mfma_f32_32x32x2_f32.  A and B tiles of
+// depth 16 are staged through LDS (double buffered, one barrier per step, next
+// tile prefetched into registers during the MFMAs); A is transposed on the
+// way in so that both operands are read from LDS as 32 consecutive floats per
+// half-wave (no bank conflicts).  Operand fragments for the next k pair are
+// fetched from LDS while the MFMAs of the current pair run.
+//
+// Eight waves per 128 x 128 tile keep the accumulators at 32 registers per
+// lane, so eight waves fit a SIMD and a CU holds four workgroups: wave slots,
+// not registers or LDS (32 KiB per workgroup), limit residency.
 //
 // MFMA 32x32x2 operand layout (lane l of 64): a = A[l % 32][l / 32],
 // b = B[l / 32][l % 32], acc[r] = C[8*(r/4) + 4*(l/32) + r%4][l % 32].
@@ -14,11 +20,19 @@
 
 #include <hip/hip_runtime.h>
 
+#ifndef GF_WAVES_M
+#define GF_WAVES_M 4     // waves along m: 4 -> wave tile 32 x 64, 2 -> 64 x 64
+#endif
+
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr uint32_t GF_BM = 128, GF_BN = 128, GF_BK = 16, GF_THREADS = 256;
+constexpr uint32_t GF_BM = 128, GF_BN = 128, GF_BK = 16;
+constexpr uint32_t GF_WM = GF_WAVES_M, GF_WN = 2;                  // wave grid
+constexpr uint32_t GF_TM = GF_BM / (32u * GF_WM), GF_TN = GF_BN / (32u * GF_WN);   // MFMA blocks per wave
+constexpr uint32_t GF_THREADS = 64u * GF_WM * GF_WN;
+constexpr uint32_t GF_LOADS = 512u / GF_THREADS;                   // float4 per thread per operand tile
 
 // FAST: m % 128 == 0, n % 128 == 0, k % 16 == 0 -> unguarded 16-byte loads.
 // otherwise every global access is guarded and scalar.
@@ -42,20 +56,18 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
 
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wave = tid >> 6;
-  const uint32_t wm = (wave >> 1) * 64u, wn = (wave & 1u) * 64u;
+  const uint32_t wm = (wave / GF_WN) * (32u * GF_TM), wn = (wave % GF_WN) * (32u * GF_TN);
   const uint32_t l32 = lane & 31u, lhi = lane >> 5;
 
-  // global -> register staging: A: row = tid % 128, k-quads {tid/128, tid/128 + 2}
-  //                             B: rows {tid/32, tid/32 + 8}, column quad tid % 32
-  const uint32_t a_row = tid & 127u, a_kq = tid >> 7;
-  const uint32_t b_row = tid >> 5, b_cq = tid & 31u;
-  float4 ra[2], rb[2];
+  // global -> register staging.  Operand tiles are 512 float4 each.
+  //   A: float4 index f -> row f % 128, k-quad f / 128;  B: row f / 32, column quad f % 32.
+  float4 ra[GF_LOADS], rb[GF_LOADS];
 
   auto load_tiles = [&](uint32_t k0) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const uint32_t kq = a_kq + 2u * h;
-      const uint32_t gr = bm + a_row, gk = k0 + 4u * kq;
+    for (uint32_t h = 0; h < GF_LOADS; ++h) {
+      const uint32_t f = tid + GF_THREADS * h;
+      const uint32_t gr = bm + (f & 127u), gk = k0 + 4u * (f >> 7);
       if (FAST) {
         ra[h] = *reinterpret_cast<const float4*>(A + (size_t)gr * K + gk);
       } else {
@@ -64,7 +76,7 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
         for (int i = 0; i < 4; ++i) t[i] = (gr < M && gk + i < K) ? A[(size_t)gr * K + gk + i] : 0.f;
         ra[h] = make_float4(t[0], t[1], t[2], t[3]);
       }
-      const uint32_t gkb = k0 + b_row + 8u * h, gc = bn + 4u * b_cq;
+      const uint32_t gkb = k0 + (f >> 5), gc = bn + 4u * (f & 31u);
       if (FAST) {
         rb[h] = *reinterpret_cast<const float4*>(B + (size_t)gkb * N + gc);
       } else {
@@ -77,21 +89,22 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
   };
   auto store_tiles = [&](uint32_t buf) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const uint32_t kq = a_kq + 2u * h;
-      As[buf][4u * kq + 0u][a_row] = ra[h].x;
-      As[buf][4u * kq + 1u][a_row] = ra[h].y;
-      As[buf][4u * kq + 2u][a_row] = ra[h].z;
-      As[buf][4u * kq + 3u][a_row] = ra[h].w;
-      *reinterpret_cast<float4*>(&Bs[buf][b_row + 8u * h][4u * b_cq]) = rb[h];
+    for (uint32_t h = 0; h < GF_LOADS; ++h) {
+      const uint32_t f = tid + GF_THREADS * h;
+      const uint32_t row = f & 127u, kq = f >> 7;
+      As[buf][4u * kq + 0u][row] = ra[h].x;
+      As[buf][4u * kq + 1u][row] = ra[h].y;
+      As[buf][4u * kq + 2u][row] = ra[h].z;
+      As[buf][4u * kq + 3u][row] = ra[h].w;
+      *reinterpret_cast<float4*>(&Bs[buf][f >> 5][4u * (f & 31u)]) = rb[h];
     }
   };
 
-  f32x16 acc[2][2];
+  f32x16 acc[GF_TM][GF_TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (uint32_t i = 0; i < GF_TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (uint32_t j = 0; j < GF_TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -102,25 +115,32 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
   for (uint32_t kt = 0; kt < nk; ++kt) {
     const uint32_t buf = kt & 1u;
     if (kt + 1u < nk) load_tiles((kt + 1u) * GF_BK);
+    float fa[2][GF_TM], fb[2][GF_TN];
+    auto fetch = [&](uint32_t kk, uint32_t slot) {
+#pragma unroll
+      for (uint32_t i = 0; i < GF_TM; ++i) fa[slot][i] = As[buf][kk + lhi][wm + 32u * i + l32];
+#pragma unroll
+      for (uint32_t j = 0; j < GF_TN; ++j) fb[slot][j] = Bs[buf][kk + lhi][wn + 32u * j + l32];
+    };
+    fetch(0, 0);
 #pragma unroll
     for (uint32_t kk = 0; kk < GF_BK; kk += 2u) {
-      const float a0 = As[buf][kk + lhi][wm + l32];
-      const float a1 = As[buf][kk + lhi][wm + 32u + l32];
-      const float b0 = Bs[buf][kk + lhi][wn + l32];
-      const float b1 = Bs[buf][kk + lhi][wn + 32u + l32];
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+      const uint32_t cur = (kk >> 1) & 1u;
+      if (kk + 2u < GF_BK) fetch(kk + 2u, cur ^ 1u);
+#pragma unroll
+      for (uint32_t i = 0; i < GF_TM; ++i)
+#pragma unroll
+        for (uint32_t j = 0; j < GF_TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1u < nk) store_tiles(buf ^ 1u);
     __syncthreads();
   }
 
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (uint32_t i = 0; i < GF_TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (uint32_t j = 0; j < GF_TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const uint32_t row = bm + wm + 32u * i + 8u * (r >> 2) + 4u * lhi + (r & 3);

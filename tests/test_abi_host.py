@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "mgb.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(mgb_[a-z0-9_]+)\s*\(", hdr))
-    assert len(declared) >= 27
+    assert len(declared) >= 28
     for name in declared:
         assert hasattr(mgb.lib, name), name
     assert declared == set(mgb.EXPORTS)
@@ -195,6 +195,30 @@ def test_probe_functions_agree_with_checker_formulas():
         mem, grid, block = mgb.probe_of(mgb.mgb_gemm_f32_probe, m, n, k)
         oracle.lib().orc_gemm_f32_probe(C.c_uint64(m), C.c_uint64(n), C.c_uint64(k), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (m, n, k)
+    for m, n, k in ((1, 1, 1), (129, 257, 17), (4096, 4096, 4096), (8192, 1024, 64)):
+        mem, grid, block = mgb.probe_of(mgb.mgb_gemm_bf16_probe, m, n, k)
+        oracle.lib().orc_gemm_bf16_probe(C.c_uint64(m), C.c_uint64(n), C.c_uint64(k), out)
+        assert [mem, *grid.tuple(), *block.tuple()] == list(out), (m, n, k)
+    for b, h, w, ci, co, st in ((1, 416, 416, 3, 32, 1), (8, 416, 416, 32, 64, 2), (2, 13, 11, 512, 512, 2),
+                                (1, 5, 6, 5, 7, 1), (3, 26, 26, 40, 200, 1)):
+        mem, grid, block = mgb.probe_of(mgb.mgb_conv3x3_probe, b, h, w, ci, co, st)
+        oracle.lib().orc_conv3x3_probe(*[C.c_uint64(x) for x in (b, h, w, ci, co, st)], out)
+        assert [mem, *grid.tuple(), *block.tuple()] == list(out), (b, h, w, ci, co, st)
+    import workloads as W
+    for b, h in ((1, 416), (8, 416), (2, 104), (1, 17)):
+        layers = W.cnn_layers(h, h)
+        arr = (mgb.mgb_conv_layer * 10)(*[mgb.mgb_conv_layer(L["c_in"], L["c_out"], L["stride"]) for L in layers])
+        mem, act, ob = C.c_uint64(), C.c_uint64(), C.c_uint64()
+        g, blk = mgb.mgb_dim3(), mgb.mgb_dim3()
+        assert mgb.mgb_cnn_probe(arr, 10, b, h, h, C.byref(mem), C.byref(act), C.byref(ob), C.byref(g), C.byref(blk)) == 0
+        flat = (C.c_uint64 * 30)(*[x for L in layers for x in (L["c_in"], L["c_out"], L["stride"])])
+        oracle.lib().orc_cnn_probe(flat, C.c_uint64(10), C.c_uint64(b), C.c_uint64(h), C.c_uint64(h), out)
+        assert [mem.value, *g.tuple(), *blk.tuple()] == list(out), (b, h)
+    for n, m in ((1, 0), (100, 300), (1 << 16, 1 << 19), (1 << 20, 16777208), (1 << 22, 1 << 26), (5000000, 10)):
+        mem, grid, block = mgb.probe_of(mgb.mgb_bfs_probe, n, m)
+        oracle.lib().orc_bfs_probe(C.c_uint64(n), C.c_uint64(m), out)
+        assert [mem, *grid.tuple(), *block.tuple()] == list(out), (n, m)
+        assert mem == (n + 1 + m) * 4 + n * 4 + mgb.mgb_bfs_work_bytes(n)
     mem, grid, block = mgb.mgb_dim3(), None, None
     assert mgb.mgb_jacobi_probe(2, 1, C.byref(C.c_uint64()), C.byref(mgb.mgb_dim3()),
                                 C.byref(mgb.mgb_dim3())) == mgb.MGB_E_UNSUPPORTED
