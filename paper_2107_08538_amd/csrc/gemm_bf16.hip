@@ -2,12 +2,22 @@
 // the bf16 matrix cores (v_mfma_f32_32x32x16_bf16).
 //
 // MFMA-bound above n ~ 1.3k, HBM-bound below.  One workgroup of 4 waves owns a
-// 128 x 128 tile of C, each wave a 64 x 64 quadrant (2 x 2 MFMA blocks).  The
-// MFMA wants, per lane, 8 consecutive k of one A row and 8 consecutive k of
-// one B column.  A is row-major, so its tile is copied to LDS as is; B is
-// k-major in memory, so its tile is transposed on the way into LDS (two k rows
-// are zipped into 32-bit {k, k+1} pairs per column) and both operands are then
-// fetched with one 16-byte LDS read per MFMA operand.
+// 128 x 256 tile of C, each wave a 64 x 128 piece (2 x 4 MFMA blocks): at the
+// bf16 MFMA rate a smaller wave tile would be bound by LDS read bandwidth
+// (a 64 x 128 piece reads 6 KiB of operands per 8 MFMAs).
+//
+// The MFMA wants, per lane, 8 consecutive k of one A row and 8 consecutive k
+// of one B column.  A is row-major, so its tile is copied to LDS as is and read
+// back 16 bytes per lane.  B is k-major in memory; its tile is also copied to
+// LDS as is (no shuffling in registers) and the k-contiguous operand is formed
+// by the LDS transpose read of gfx950, ds_read_b64_tr_b16: within each group of
+// 16 lanes, lane i receives element (i % 4) of the four 8-byte rows addressed by
+// lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  With lane s of a group pointing at
+// B[k0 + s/4][n0 + 4*(s%4) ..], lane i gets B[k0 .. k0+3][n0 + i].
+//
+// LDS pitches: A rows 80 bytes (conflict-free 16-byte reads), B rows
+// 2*256 + 64 bytes so that the four k rows one transpose read touches fall in
+// different bank quarters.
 //
 // MFMA 32x32x16 layout (lane l): a = A[l % 32][8*(l/32) .. +7],
 // b = B[8*(l/32) .. +7][l % 32], acc[r] = C[8*(r/4) + 4*(l/32) + r%4][l % 32].
@@ -19,80 +29,102 @@
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr uint32_t GB_BM = 128, GB_BN = 128, GB_BK = 32, GB_THREADS = 256;
-constexpr uint32_t GB_LD = GB_BK + 8;   // LDS row pitch in elements (80 bytes, keeps 16-byte alignment)
+constexpr uint32_t GB_BM = 128, GB_BN = 256, GB_BK = 32, GB_THREADS = 256;
+constexpr uint32_t GB_LDA = GB_BK + 8;      // A pitch in elements (80 bytes)
+constexpr uint32_t GB_LDB = GB_BN + 32;     // B pitch in elements (576 bytes)
 
-union Frag {
-  uint4 q;
-  uint32_t d[4];
-  uint16_t h[8];
-  bf16x8 v;
-};
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte chunk (native vector: bit casts stay in registers)
+
+// guarded element-wise gather of 8 consecutive bf16 into one 16-byte chunk (ragged shapes)
+__device__ __forceinline__ u32x4 gather8(const uint16_t* __restrict__ p, bool row_ok, uint32_t first,
+                                         uint32_t limit) {
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t lo = (row_ok && first + 2u * i < limit) ? p[2 * i] : 0u;
+    const uint32_t hi = (row_ok && first + 2u * i + 1u < limit) ? p[2 * i + 1] : 0u;
+    w[i] = lo | (hi << 16);
+  }
+  return u32x4{w[0], w[1], w[2], w[3]};
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 q) { return __builtin_bit_cast(bf16x8, q); }
+__device__ __forceinline__ bf16x8 join_bf16x8(s16x4 lo, s16x4 hi) {
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
 
 template <bool FAST>
-__global__ __launch_bounds__(GB_THREADS) void gemm_bf16_kernel(const uint16_t* __restrict__ A,
+__global__ __launch_bounds__(GB_THREADS, 2) void gemm_bf16_kernel(const uint16_t* __restrict__ A,
                                                               const uint16_t* __restrict__ B,
                                                               float* __restrict__ C, uint32_t M,
                                                               uint32_t N, uint32_t K,
                                                               uint32_t tiles_n, uint32_t tiles_total) {
-  __shared__ __attribute__((aligned(16))) uint16_t As[2][GB_BM][GB_LD];   // [m][k]
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[2][GB_BN][GB_LD];   // [n][k]
+  __shared__ __attribute__((aligned(16))) uint16_t As[2][GB_BM][GB_LDA];   // [m][k]
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[2][GB_BK][GB_LDB];   // [k][n]
 
+  // XCD-aware tile order (see the fp32 GEMM): bands of 8 tile rows, down the band first.
   const uint32_t per_xcd = (tiles_total + 7u) / 8u;
-  const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-  if ((blockIdx.x >> 3) >= per_xcd || tile >= tiles_total) return;
-  const uint32_t bm = (tile / tiles_n) * GB_BM;
-  const uint32_t bn = (tile % tiles_n) * GB_BN;
+  const uint32_t seq = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || seq >= tiles_total) return;
+  const uint32_t tiles_m = tiles_total / tiles_n;
+  const uint32_t band = seq / (8u * tiles_n);
+  const uint32_t band_rows = min(8u, tiles_m - 8u * band);
+  const uint32_t in_band = seq - band * 8u * tiles_n;
+  const uint32_t bm = (8u * band + in_band % band_rows) * GB_BM;
+  const uint32_t bn = (in_band / band_rows) * GB_BN;
 
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wave = tid >> 6;
-  const uint32_t wm = (wave >> 1) * 64u, wn = (wave & 1u) * 64u;
+  const uint32_t wm = (wave >> 1) * 64u, wn = (wave & 1u) * 128u;
   const uint32_t l32 = lane & 31u, lhi = lane >> 5;
+  // transpose-read roles: 16-lane group q, lane s within it
+  const uint32_t tq = lane >> 4, ts = lane & 15u;
+  const uint32_t tr_row = 8u * (tq >> 1) + (ts >> 2);            // + ks + 4*r
+  const uint32_t tr_col = 16u * (tq & 1u) + 4u * (ts & 3u);      // + wn + 32*j
 
-  // staging roles.  A: rows {tid/4, tid/4 + 64}, 8-element chunk tid % 4.
-  //                 B: k pair tid / 16 (rows 2p, 2p+1), 8 columns starting at 8 * (tid % 16).
-  const uint32_t a_row = tid >> 2, a_ch = tid & 3u;
-  const uint32_t b_kp = tid >> 4, b_ng = tid & 15u;
-  Frag ra[2], rb[2];
-
+  // staging: A tile = 512 chunks of 8 elements (row f/4, chunk f%4), 2 per thread;
+  //          B tile = 1024 chunks (k row f/32, chunk f%32), 4 per thread.
+  u32x4 ra[2], rb[4];
   auto load_tiles = [&](uint32_t k0) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const uint32_t gr = bm + a_row + 64u * h, gk = k0 + 8u * a_ch;
-      if (FAST) {
-        ra[h].q = *reinterpret_cast<const uint4*>(A + (size_t)gr * K + gk);
-      } else {
+    for (uint32_t h = 0; h < 2; ++h) {
+      const uint32_t f = tid + GB_THREADS * h;
+      const uint32_t gr = bm + (f >> 2), gk = k0 + 8u * (f & 3u);
+      if (FAST) ra[h] = *reinterpret_cast<const u32x4*>(A + (size_t)gr * K + gk);
+      else ra[h] = gather8(A + (size_t)gr * K + gk, gr < M, gk, K);
+    }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) ra[h].h[i] = (gr < M && gk + i < K) ? A[(size_t)gr * K + gk + i] : (uint16_t)0;
-      }
-      const uint32_t gkb = k0 + 2u * b_kp + h, gc = bn + 8u * b_ng;
-      if (FAST) {
-        rb[h].q = *reinterpret_cast<const uint4*>(B + (size_t)gkb * N + gc);
-      } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) rb[h].h[i] = (gkb < K && gc + i < N) ? B[(size_t)gkb * N + gc + i] : (uint16_t)0;
-      }
+    for (uint32_t h = 0; h < 4; ++h) {
+      const uint32_t f = tid + GB_THREADS * h;
+      const uint32_t gk = k0 + (f >> 5), gc = bn + 8u * (f & 31u);
+      if (FAST) rb[h] = *reinterpret_cast<const u32x4*>(B + (size_t)gk * N + gc);
+      else rb[h] = gather8(B + (size_t)gk * N + gc, gk < K, gc, N);
     }
   };
   auto store_tiles = [&](uint32_t buf) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-      *reinterpret_cast<uint4*>(&As[buf][a_row + 64u * h][8u * a_ch]) = ra[h].q;
-    // zip rows k (rb[0]) and k+1 (rb[1]): column i gets the pair {B[k][i], B[k+1][i]}
+    for (uint32_t h = 0; h < 2; ++h) {
+      const uint32_t f = tid + GB_THREADS * h;
+      *reinterpret_cast<u32x4*>(&As[buf][f >> 2][8u * (f & 3u)]) = ra[h];
+    }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const uint32_t pair = (uint32_t)rb[0].h[i] | ((uint32_t)rb[1].h[i] << 16);
-      *reinterpret_cast<uint32_t*>(&Bs[buf][8u * b_ng + i][2u * b_kp]) = pair;
+    for (uint32_t h = 0; h < 4; ++h) {
+      const uint32_t f = tid + GB_THREADS * h;
+      *reinterpret_cast<u32x4*>(&Bs[buf][f >> 5][8u * (f & 31u)]) = rb[h];
     }
   };
 
-  f32x16 acc[2][2];
+  f32x16 acc[2][4];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -105,24 +137,32 @@ __global__ __launch_bounds__(GB_THREADS) void gemm_bf16_kernel(const uint16_t* _
     if (kt + 1u < nk) load_tiles((kt + 1u) * GB_BK);
 #pragma unroll
     for (uint32_t ks = 0; ks < GB_BK; ks += 16u) {
-      Frag a0, a1, b0, b1;
-      a0.q = *reinterpret_cast<const uint4*>(&As[buf][wm + l32][ks + 8u * lhi]);
-      a1.q = *reinterpret_cast<const uint4*>(&As[buf][wm + 32u + l32][ks + 8u * lhi]);
-      b0.q = *reinterpret_cast<const uint4*>(&Bs[buf][wn + l32][ks + 8u * lhi]);
-      b1.q = *reinterpret_cast<const uint4*>(&Bs[buf][wn + 32u + l32][ks + 8u * lhi]);
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0.v, b0.v, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0.v, b1.v, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1.v, b0.v, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1.v, b1.v, acc[1][1], 0, 0, 0);
+      bf16x8 fa[2], fb[4];
+#pragma unroll
+      for (uint32_t i = 0; i < 2; ++i)
+        fa[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(&As[buf][wm + 32u * i + l32][ks + 8u * lhi]));
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4_ptr)&Bs[buf][ks + tr_row][wn + 32u * j + tr_col]);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4_ptr)&Bs[buf][ks + 4u + tr_row][wn + 32u * j + tr_col]);
+        fb[j] = join_bf16x8(lo, hi);
+      }
+#pragma unroll
+      for (uint32_t i = 0; i < 2; ++i)
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1u < nk) store_tiles(buf ^ 1u);
     __syncthreads();
   }
 
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (uint32_t i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (uint32_t j = 0; j < 4; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const uint32_t row = bm + wm + 32u * i + 8u * (r >> 2) + 4u * lhi + (r & 3);

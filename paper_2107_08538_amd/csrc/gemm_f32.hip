@@ -23,6 +23,9 @@
 #ifndef GF_WAVES_M
 #define GF_WAVES_M 4     // waves along m: 4 -> wave tile 32 x 64, 2 -> 64 x 64
 #endif
+#ifndef GF_BAND
+#define GF_BAND 8        // tile rows per band of the tile sequence
+#endif
 
 namespace {
 
@@ -45,14 +48,20 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
   __shared__ float As[2][GF_BK][GF_BM];   // [k][m]
   __shared__ float Bs[2][GF_BK][GF_BN];   // [k][n]
 
-  // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so
-  // give each XCD a contiguous run of tiles (neighbours share A rows / B cols
-  // in that XCD's L2).
+  // XCD-aware tile order.  Consecutive workgroup ids go to different XCDs, so XCD x takes the
+  // contiguous run [x * per_xcd, (x+1) * per_xcd) of a tile sequence that walks C in bands of GF_BAND
+  // tile rows, down the band first: the tiles resident in one XCD at a time then form a
+  // squarish block and share both their A row slabs and their B column slabs in that XCD's L2.
   const uint32_t per_xcd = (tiles_total + 7u) / 8u;
-  const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-  if ((blockIdx.x >> 3) >= per_xcd || tile >= tiles_total) return;
-  const uint32_t bm = (tile / tiles_n) * GF_BM;
-  const uint32_t bn = (tile % tiles_n) * GF_BN;
+  const uint32_t seq = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || seq >= tiles_total) return;
+  const uint32_t tiles_m = tiles_total / tiles_n;
+  constexpr uint32_t BAND = GF_BAND;
+  const uint32_t band = seq / (BAND * tiles_n);
+  const uint32_t band_rows = min(BAND, tiles_m - BAND * band);
+  const uint32_t in_band = seq - band * BAND * tiles_n;
+  const uint32_t bm = (BAND * band + in_band % band_rows) * GF_BM;
+  const uint32_t bn = (in_band / band_rows) * GF_BN;
 
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wave = tid >> 6;
