@@ -7,9 +7,13 @@
 // neither needs a transpose, the A tile is gathered straight from the input
 // image (zeros outside it) into LDS, 8 channels per 16-byte load when c_in is
 // a multiple of 8, element-wise otherwise (the 3-channel first layer).
-// A workgroup of 4 waves owns 128 pixels x BN channels; a wave owns 32 pixels.
+// A workgroup of 4 waves (2 x 2) owns 128 pixels x BN channels, depth 64 per
+// step.  The late layers of a small batch have only a handful of workgroups, so
+// a step's memory latency cannot be hidden by other workgroups: the tiles of
+// the next TWO steps are kept in flight in registers while the MFMAs of the
+// current step run from LDS.
 // Wide layers are MFMA-bound; the first layer and the small late layers of a
-// small batch are bandwidth / launch bound.
+// small batch are bandwidth / latency bound.
 #include "../../include/mgb.h"
 #include "launch_util.h"
 
@@ -19,15 +23,9 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte chunk of 8 bf16
 
-constexpr uint32_t CV_BM = 128, CV_BK = 32, CV_THREADS = 256;
-constexpr uint32_t CV_LD = CV_BK + 8;
-
-union Frag {
-  uint4 q;
-  uint16_t h[8];
-  bf16x8 v;
-};
+constexpr uint32_t CV_BM = 128, CV_THREADS = 256;
 
 struct ConvArgs {
   const uint16_t* x;
@@ -38,17 +36,35 @@ struct ConvArgs {
   uint32_t tiles_n, tiles_total, out_f32;
 };
 
+// 16 bytes of zeros in device memory: the source of every padded / out-of-range operand chunk
+__device__ __attribute__((aligned(16))) uint32_t g_zero16[4];
+
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   uint32_t w = __float_as_uint(f);
   return (uint16_t)((w + 0x7fffu + ((w >> 16) & 1u)) >> 16);
 }
 
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 q) { return __builtin_bit_cast(bf16x8, q); }
+
+// p if ok (0 or 1) else z, by integer arithmetic: the compiler cannot turn it into a branch
+__device__ __forceinline__ const uint16_t* pick(const uint16_t* p, const uint16_t* z, uint32_t ok) {
+  const uintptr_t pz = (uintptr_t)z;
+  return (const uint16_t*)(pz + (((uintptr_t)p - pz) & (uintptr_t)(0 - (int64_t)ok)));
+}
+
+// VEC (c_in % 8 == 0) runs depth 64 per step; the element-wise path (3-channel first layer,
+// total depth 27) runs depth 32 per step.
 template <uint32_t BN, bool VEC>
-__global__ __launch_bounds__(CV_THREADS) void conv3x3_kernel(ConvArgs a) {
+__global__ __launch_bounds__(CV_THREADS, 2) void conv3x3_kernel(ConvArgs a) {
+  constexpr uint32_t CV_BK = VEC ? 64u : 32u;
+  constexpr uint32_t CV_LD = CV_BK + 8u;            // LDS pitch in elements
+  constexpr uint32_t CPR = CV_BK / 8u;              // 8-element chunks per tile row
+  constexpr uint32_t RSTEP = CV_THREADS / CPR;      // rows covered by one pass of the workgroup
   __shared__ __attribute__((aligned(16))) uint16_t As[2][CV_BM][CV_LD];   // [pixel][k]
   __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN][CV_LD];      // [channel][k]
-  constexpr uint32_t NT = BN / 32u;          // MFMA blocks per wave along the channels
-  constexpr uint32_t BCH = BN * 4u / CV_THREADS;   // weight chunks per thread
+  constexpr uint32_t NT = BN / 64u;                 // MFMA blocks per wave along the channels
+  constexpr uint32_t ACH = CV_BM / RSTEP;           // A chunks per thread per step
+  constexpr uint32_t BCH = BN / RSTEP;              // weight chunks per thread per step
 
   const uint32_t per_xcd = (a.tiles_total + 7u) / 8u;
   const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
@@ -58,16 +74,18 @@ __global__ __launch_bounds__(CV_THREADS) void conv3x3_kernel(ConvArgs a) {
 
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wave = tid >> 6;
+  const uint32_t wm = (wave >> 1) * 64u, wn = (wave & 1u) * (BN / 2u);
   const uint32_t l32 = lane & 31u, lhi = lane >> 5;
-  const uint32_t a_row = tid >> 2, ch = tid & 3u;
+  // staging roles: 8-element chunk ch of rows row0, row0 + RSTEP, ...
+  const uint32_t ch = tid % CPR, row0 = tid / CPR;
 
-  // the two pixels this thread gathers for
-  int32_t ih0[2], iw0[2];
-  size_t img[2];
-  bool pv[2];
+  // the pixels this thread gathers for
+  int32_t ih0[ACH], iw0[ACH];
+  uint32_t img[ACH];
+  bool pv[ACH];
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const uint32_t p = bm + a_row + 64u * h;
+  for (uint32_t h = 0; h < ACH; ++h) {
+    const uint32_t p = bm + row0 + RSTEP * h;
     pv[h] = p < a.pixels;
     const uint32_t pp = pv[h] ? p : 0u;
     const uint32_t b = pp / (a.Ho * a.Wo);
@@ -75,105 +93,140 @@ __global__ __launch_bounds__(CV_THREADS) void conv3x3_kernel(ConvArgs a) {
     const uint32_t oh = rem / a.Wo, ow = rem - oh * a.Wo;
     ih0[h] = (int32_t)(oh * a.stride) - 1;
     iw0[h] = (int32_t)(ow * a.stride) - 1;
-    img[h] = (size_t)b * a.H * a.W * a.C;
+    img[h] = b * a.H * a.W;                          // pixel index of the image origin
   }
 
-  Frag ra[2], rb[BCH];
-  auto load_tiles = [&](uint32_t k0) {
+  // Taps outside the image, pixels / channels past the end and depth padding read from a
+  // 16-byte block of zeros instead of the tensors: every load is unconditional and its
+  // result goes to LDS untouched, so no branch or select sits between a load and its use and
+  // the loads of two steps can stay in flight across the MFMAs.
+  const uint16_t* zeros = reinterpret_cast<const uint16_t*>(g_zero16);
+  auto load_tiles = [&](uint32_t k0, u32x4 (&ra)[ACH], u32x4 (&rb)[BCH]) {
     const uint32_t k = k0 + 8u * ch;
     if (VEC) {
-      // the 8 k-values share one filter tap
+      // the 8 k-values share one filter tap (c_in % 8 == 0, so depth % 8 == 0)
+      const bool kok = k < a.depth;
       const uint32_t tap = k / a.C, c = k - tap * a.C;
       const int32_t r = (int32_t)(tap / 3u), s = (int32_t)(tap - 3u * (tap / 3u));
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
+      for (uint32_t h = 0; h < ACH; ++h) {
         const int32_t ih = ih0[h] + r, iw = iw0[h] + s;
-        const bool ok = pv[h] && k < a.depth && ih >= 0 && iw >= 0 && ih < (int32_t)a.H && iw < (int32_t)a.W;
-        ra[h].q = ok ? *reinterpret_cast<const uint4*>(a.x + img[h] + ((size_t)ih * a.W + iw) * a.C + c)
-                     : make_uint4(0, 0, 0, 0);
+        const uint32_t ok = (uint32_t)pv[h] & (uint32_t)kok & (uint32_t)((uint32_t)ih < a.H) & (uint32_t)((uint32_t)iw < a.W);
+        const uint16_t* in_img = a.x + ((int64_t)img[h] + (int64_t)ih * a.W + iw) * a.C + c;
+        ra[h] = *reinterpret_cast<const u32x4*>(pick(in_img, zeros, ok));
+      }
+#pragma unroll
+      for (uint32_t j = 0; j < BCH; ++j) {
+        const uint32_t n = bn + row0 + RSTEP * j;
+        const uint16_t* in_w = a.w + (size_t)n * a.depth + k;
+        rb[j] = *reinterpret_cast<const u32x4*>(pick(in_w, zeros, (uint32_t)(n < a.K) & (uint32_t)kok));
       }
     } else {
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
+      for (uint32_t h = 0; h < ACH; ++h) {
+        uint32_t wd[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (uint32_t i = 0; i < 8; ++i) {
           const uint32_t kk = k + i;
           const uint32_t tap = kk / a.C, c = kk - tap * a.C;
           const int32_t r = (int32_t)(tap / 3u), s = (int32_t)(tap - 3u * (tap / 3u));
           const int32_t ih = ih0[h] + r, iw = iw0[h] + s;
-          const bool ok = pv[h] && kk < a.depth && ih >= 0 && iw >= 0 && ih < (int32_t)a.H && iw < (int32_t)a.W;
-          ra[h].h[i] = ok ? a.x[img[h] + ((size_t)ih * a.W + iw) * a.C + c] : (uint16_t)0;
+          const uint32_t ok = (uint32_t)pv[h] & (uint32_t)(kk < a.depth) & (uint32_t)((uint32_t)ih < a.H) & (uint32_t)((uint32_t)iw < a.W);
+          const uint16_t* in_img = a.x + ((int64_t)img[h] + (int64_t)ih * a.W + iw) * a.C + c;
+          wd[i >> 1] |= (uint32_t)*pick(in_img, zeros, ok) << (16u * (i & 1u));
         }
-    }
+        ra[h] = u32x4{wd[0], wd[1], wd[2], wd[3]};
+      }
 #pragma unroll
-    for (uint32_t j = 0; j < BCH; ++j) {
-      const uint32_t idx = tid + CV_THREADS * j;
-      const uint32_t n = bn + (idx >> 2);
-      const uint32_t kb = k0 + 8u * (idx & 3u);
-      if (VEC) {
-        rb[j].q = (n < a.K && kb < a.depth) ? *reinterpret_cast<const uint4*>(a.w + (size_t)n * a.depth + kb)
-                                           : make_uint4(0, 0, 0, 0);
-      } else {
+      for (uint32_t j = 0; j < BCH; ++j) {
+        const uint32_t n = bn + row0 + RSTEP * j;
+        uint32_t wd[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-          rb[j].h[i] = (n < a.K && kb + i < a.depth) ? a.w[(size_t)n * a.depth + kb + i] : (uint16_t)0;
+        for (uint32_t i = 0; i < 8; ++i) {
+          const uint16_t* in_w = a.w + (size_t)n * a.depth + k + i;
+          wd[i >> 1] |= (uint32_t)*pick(in_w, zeros, (uint32_t)(n < a.K) & (uint32_t)(k + i < a.depth)) << (16u * (i & 1u));
+        }
+        rb[j] = u32x4{wd[0], wd[1], wd[2], wd[3]};
       }
     }
   };
-  auto store_tiles = [&](uint32_t buf) {
+  auto store_tiles = [&](uint32_t buf, const u32x4 (&ra)[ACH], const u32x4 (&rb)[BCH]) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-      *reinterpret_cast<uint4*>(&As[buf][a_row + 64u * h][8u * ch]) = ra[h].q;
+    for (uint32_t h = 0; h < ACH; ++h)
+      *reinterpret_cast<u32x4*>(&As[buf][row0 + RSTEP * h][8u * ch]) = ra[h];
 #pragma unroll
-    for (uint32_t j = 0; j < BCH; ++j) {
-      const uint32_t idx = tid + CV_THREADS * j;
-      *reinterpret_cast<uint4*>(&Bs[buf][idx >> 2][8u * (idx & 3u)]) = rb[j].q;
-    }
+    for (uint32_t j = 0; j < BCH; ++j)
+      *reinterpret_cast<u32x4*>(&Bs[buf][row0 + RSTEP * j][8u * ch]) = rb[j];
   };
 
-  f32x16 acc[NT];
+  f32x16 acc[2][NT];
 #pragma unroll
-  for (uint32_t j = 0; j < NT; ++j)
+  for (uint32_t i = 0; i < 2; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    for (uint32_t j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const uint32_t nk = (a.depth + CV_BK - 1u) / CV_BK;
-  load_tiles(0);
-  store_tiles(0);
-  __syncthreads();
-  for (uint32_t kt = 0; kt < nk; ++kt) {
-    const uint32_t buf = kt & 1u;
-    if (kt + 1u < nk) load_tiles((kt + 1u) * CV_BK);
+  auto compute = [&](uint32_t buf) {
 #pragma unroll
     for (uint32_t ks = 0; ks < CV_BK; ks += 16u) {
-      Frag fa;
-      fa.q = *reinterpret_cast<const uint4*>(&As[buf][32u * wave + l32][ks + 8u * lhi]);
+      bf16x8 fa[2], fb[NT];
 #pragma unroll
-      for (uint32_t j = 0; j < NT; ++j) {
-        Frag fb;
-        fb.q = *reinterpret_cast<const uint4*>(&Bs[buf][32u * j + l32][ks + 8u * lhi]);
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa.v, fb.v, acc[j], 0, 0, 0);
-      }
+      for (uint32_t i = 0; i < 2; ++i)
+        fa[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(&As[buf][wm + 32u * i + l32][ks + 8u * lhi]));
+#pragma unroll
+      for (uint32_t j = 0; j < NT; ++j)
+        fb[j] = as_bf16x8(*reinterpret_cast<const u32x4*>(&Bs[buf][wn + 32u * j + l32][ks + 8u * lhi]));
+#pragma unroll
+      for (uint32_t i = 0; i < 2; ++i)
+#pragma unroll
+        for (uint32_t j = 0; j < NT; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1u < nk) store_tiles(buf ^ 1u);
+  };
+
+  // Software pipeline, two steps deep: while step kt computes from LDS[kt & 1], the tiles of
+  // step kt+1 sit in one register set (stored to LDS at the end of the step) and the loads of
+  // step kt+2 are in flight into the other.  The loop body handles two steps so that the
+  // register sets keep fixed names.
+  const uint32_t nk = (a.depth + CV_BK - 1u) / CV_BK;
+  const uint32_t last = (nk - 1u) * CV_BK;          // loads issued past the end re-read the last step
+  u32x4 ra0[ACH], rb0[BCH], ra1[ACH], rb1[BCH];
+  load_tiles(0, ra0, rb0);
+  store_tiles(0, ra0, rb0);
+  load_tiles(min(CV_BK, last), ra1, rb1);
+  __syncthreads();
+  for (uint32_t kt = 0; kt < nk; kt += 2u) {
+    // step kt: LDS[0]; set 1 holds step kt+1; set 0 receives step kt+2
+    load_tiles(min((kt + 2u) * CV_BK, last), ra0, rb0);
+    compute(0);
+    store_tiles(1, ra1, rb1);                        // unused if kt+1 == nk
+    __syncthreads();
+    if (kt + 1u >= nk) break;
+    // step kt+1: LDS[1]; set 0 holds step kt+2; set 1 receives step kt+3
+    load_tiles(min((kt + 3u) * CV_BK, last), ra1, rb1);
+    compute(1);
+    store_tiles(0, ra0, rb0);                        // unused if kt+2 == nk
     __syncthreads();
   }
 
   // ReLU, then bf16 (nearest even) or fp32
 #pragma unroll
-  for (uint32_t j = 0; j < NT; ++j)
+  for (uint32_t i = 0; i < 2; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const uint32_t p = bm + 32u * wave + 8u * (r >> 2) + 4u * lhi + (r & 3);
-      const uint32_t col = bn + 32u * j + l32;
-      if (p < a.pixels && col < a.K) {
-        const float v = fmaxf(acc[j][r], 0.f);
-        if (a.out_f32)
-          reinterpret_cast<float*>(a.y)[(size_t)p * a.K + col] = v;
-        else
-          reinterpret_cast<uint16_t*>(a.y)[(size_t)p * a.K + col] = f32_to_bf16_rne(v);
+    for (uint32_t j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t p = bm + wm + 32u * i + 8u * (r >> 2) + 4u * lhi + (r & 3);
+        const uint32_t col = bn + wn + 32u * j + l32;
+        if (p < a.pixels && col < a.K) {
+          const float v = fmaxf(acc[i][j][r], 0.f);
+          if (a.out_f32)
+            reinterpret_cast<float*>(a.y)[(size_t)p * a.K + col] = v;
+          else
+            reinterpret_cast<uint16_t*>(a.y)[(size_t)p * a.K + col] = f32_to_bf16_rne(v);
+        }
       }
-    }
 }
 
 struct Geometry {
@@ -186,7 +239,7 @@ bool shape_ok(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_
   if (h > 16384u || w > 16384u || c_in > 8192u || c_out > 8192u || batch > 65536u) return false;
   const uint64_t ho = (h - 1u) / stride + 1u, wo = (w - 1u) / stride + 1u;
   if ((uint64_t)batch * ho * wo > 0x7fffffffull) return false;
-  if ((uint64_t)batch * h * w * c_in > 0xffffffffull * 16ull) return false;
+  if ((uint64_t)batch * h * w > 0x7fffffffull) return false;     // pixel indices are 32-bit
   return true;
 }
 
