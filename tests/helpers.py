@@ -64,3 +64,61 @@ def gemm_componentwise_error(c_gpu, ref, den):
 def frobenius_rel(x, ref):
     x = np.asarray(x, dtype=np.float64)
     return float(np.linalg.norm((x - ref).ravel()) / np.linalg.norm(ref.ravel()))
+
+
+def verify_task_output(task, data, full_gemm_limit=512):
+    """Compare one finished harness task with the CPU checker (tolerances as in the kernel tests)."""
+    import workloads as W
+    spec, p = task.spec, task.spec.params
+    if spec.kind == "jacobi":
+        it = p["iters"]
+        got = (task.tensors["u0"] if it % 2 == 0 else task.tensors["u1"]).cpu().numpy()
+        assert np.array_equal(got, oracle.jacobi_f32(data["u"], it)), ("jacobi", spec.task_id)
+    elif spec.kind in ("gemm_f32", "gemm_bf16"):
+        got = task.tensors["C"].cpu().numpy().astype(np.float64)
+        m, n = got.shape
+        if spec.kind == "gemm_f32":
+            if max(m, n, p["k"]) <= full_gemm_limit:
+                ref, den = oracle.gemm_f32(data["a"], data["b"]), oracle.gemm_abs_f32(data["a"], data["b"])
+                assert (np.abs(got - ref) / den).max() <= 1e-4, ("gemm_f32", spec.task_id)
+            else:
+                rng = np.random.default_rng(spec.task_id)
+                rows = rng.integers(0, m, 1024).astype(np.uint32)
+                cols = rng.integers(0, n, 1024).astype(np.uint32)
+                ref, den = oracle.gemm_f32_entries(data["a"], data["b"], rows, cols)
+                assert (np.abs(got[rows, cols] - ref) / den).max() <= 1e-4, ("gemm_f32", spec.task_id)
+        else:
+            if max(m, n, p["k"]) <= full_gemm_limit:
+                assert frobenius_rel(got, oracle.gemm_bf16(data["a"], data["b"])) <= 1e-2, ("gemm_bf16", spec.task_id)
+            else:
+                rng = np.random.default_rng(spec.task_id)
+                rows = rng.integers(0, m, 1024).astype(np.uint32)
+                cols = rng.integers(0, n, 1024).astype(np.uint32)
+                ref = oracle.gemm_bf16_entries(data["a"], data["b"], rows, cols)
+                assert np.linalg.norm(got[rows, cols] - ref) <= 1e-2 * np.linalg.norm(ref), ("gemm_bf16", spec.task_id)
+    elif spec.kind == "bfs":
+        got = task.tensors["level"].cpu().numpy()
+        assert np.array_equal(got, oracle.bfs(data["row_ptr"], data["col_idx"], 0)), ("bfs", spec.task_id)
+    elif spec.kind == "cnn":
+        L = data["layers"]
+        got = task.tensors["out"].cpu().numpy().reshape(p["batch"], L[-1]["h_out"], L[-1]["w_out"], L[-1]["c_out"])
+        ref = oracle.cnn_forward(data["x"], data["weights"], [l["stride"] for l in L])
+        assert frobenius_rel(got, ref) <= 1e-2, ("cnn", spec.task_id)
+    else:
+        raise ValueError(spec.kind)
+
+
+def check_ledger_invariants(desc, trace):
+    """Resident footprints never exceed the cap; HARD partitions stay pairwise disjoint."""
+    running = {}
+    for r in trace:
+        k = int(r["kind"])
+        if k == mgb.MGB_EV_ADMIT:
+            for g in running.values():
+                if desc.policy != mgb.MGB_POLICY_SOFT:
+                    assert g[1] & int(r["granule_mask"]) == 0
+            running[int(r["ticket"])] = (int(r["mem_bytes"]), int(r["granule_mask"]))
+        elif k == mgb.MGB_EV_RELEASE:
+            del running[int(r["ticket"])]
+        assert sum(m for m, _ in running.values()) + int(r["free_bytes"]) == desc.mem_cap_bytes
+    assert not running

@@ -54,13 +54,14 @@ def mix16(seed=16):
     return dict(name="Mix-16", cap_bytes=288 * 10 ** 9, tasks=tasks)
 
 
-def cnn8(seed=8):
-    """8 inference jobs of the 10-layer conv net, batch in {1,2,4,8}, mean gap 10 ms."""
+def cnn8(seed=8, h=416, w=416):
+    """8 inference jobs of the 10-layer conv net, batch in {1,2,4,8}, mean gap 10 ms.
+    (h, w smaller than 416 gives the reduced instances the tests recompute on the CPU.)"""
     arr = _arrivals(seed, 8, 10e-3)
     tasks = []
     for i in range(8):
         b = (1, 2, 4, 8)[int(_u(seed ^ 0xBA7C, i) * 4)]
-        tasks.append(TaskSpec(i, "cnn", dict(batch=b, h=416, w=416), arr[i], task_seed(seed, i)))
+        tasks.append(TaskSpec(i, "cnn", dict(batch=b, h=h, w=w), arr[i], task_seed(seed, i)))
     return dict(name="CNN-8", cap_bytes=288 * 10 ** 9, tasks=tasks)
 
 
@@ -84,8 +85,9 @@ def _logu(u, lo, hi):
     return math.exp(math.log(lo) + u * (math.log(hi) - math.log(lo)))
 
 
-def mixed128(seed=128, n_tasks=128):
-    """128 tasks, mean gap 2 ms, log-uniform sizes rounded to multiples of 64."""
+def mixed128(seed=128, n_tasks=128, shrink=1):
+    """128 tasks, mean gap 2 ms, log-uniform sizes rounded to multiples of 64.
+    shrink > 1 divides the linear sizes (and BFS vertex counts by shrink^2) for CPU-checkable runs."""
     arr = _arrivals(seed, n_tasks, 2e-3)
     tasks = []
     for i in range(n_tasks):
@@ -94,14 +96,14 @@ def mixed128(seed=128, n_tasks=128):
         u2 = _u(seed ^ 0x52, i)
         ts = task_seed(seed, i)
         if k == 0:
-            n = int(round(_logu(u1, 1024, 8192) / 64)) * 64
+            n = max(64, int(round(_logu(u1, 1024, 8192) / shrink / 64)) * 64)
             tasks.append(TaskSpec(i, "jacobi", dict(n=n, iters=50), arr[i], ts))
         elif k == 1:
-            n = int(round(_logu(u1, 1024, 8192) / 64)) * 64
+            n = max(64, int(round(_logu(u1, 1024, 8192) / shrink / 64)) * 64)
             kind = "gemm_f32" if u2 < 0.5 else "gemm_bf16"
             tasks.append(TaskSpec(i, kind, dict(m=n, n=n, k=n), arr[i], ts))
         else:
-            n = int(round(_logu(u1, 1 << 16, 1 << 22)))
+            n = max(64, int(round(_logu(u1, 1 << 16, 1 << 22) / (shrink * shrink))))
             d = int(round(_logu(u2, 8, 32)))
             tasks.append(TaskSpec(i, "bfs", dict(n=n, degree=d), arr[i], ts))
     return dict(name="Mixed-128", cap_bytes=288 * 10 ** 9, tasks=tasks)
