@@ -26,6 +26,10 @@ def parse():
     return ap.parse_args()
 
 
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
 def cpu_baseline(spec):
     """Serial CPU checker timed on a bounded sample of the same workload, scaled by work."""
     import numpy as np
@@ -124,8 +128,10 @@ def main():
     cap = min(spec["cap_bytes"], total_b)
     sched = mgb.Sched(policy=pol, queue_mode=qm, mem_cap_bytes=cap)
 
+    log("inputs resident (%d tasks, %.1f s); stream copy %.0f GB/s" % (len(tasks), t_gen, copy_gbps))
     for _ in range(args.warmup):
         harness.run_mix(sched, tasks)
+    log("warm-up done, %d masked streams" % sched.stats().n_streams)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     runs = []
@@ -134,6 +140,7 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     n_tasks = len(tasks)
+    log("timed region done: %d steps in %.3f s, %d masked streams" % (args.steps, elapsed, sched.stats().n_streams))
     sums = [harness.summarize(r, m) for r, m in runs]
     value = n_tasks * args.steps / elapsed
     mean_turn = sum(s["mean_turnaround_ms"] for s in sums) / len(sums)
@@ -165,7 +172,7 @@ def main():
                ms_per_step=round(1e3 * elapsed / args.steps, 3), higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="f32", data="synthetic",
                config=dict(workload="%s: %s" % (spec["name"], ", ".join(sorted({t.kind for t in spec["tasks"]}))),
-                           policy=args.policy, queue=args.queue, tasks=n_tasks, workers=n_tasks,
+                           policy=args.policy, queue=args.queue, tasks=n_tasks, workers=min(n_tasks, harness.MAX_WORKERS),
                            cap_bytes=cap, granule_cus=8, n_cu=256),
                mean_turnaround_ms=round(mean_turn, 3),
                mean_wait_ms=round(sum(s["mean_wait_ms"] for s in sums) / len(sums), 3),
@@ -175,6 +182,7 @@ def main():
 
     if not args.no_extras:
         # the same mix, serialised: one task at a time on all 256 CUs in arrival order
+        log("serialised comparator")
         ser = mgb.Sched(policy=mgb.MGB_POLICY_SERIAL, queue_mode=mgb.MGB_QUEUE_FIFO, mem_cap_bytes=cap)
         harness.run_mix(ser, tasks)
         t1 = time.perf_counter()
@@ -197,6 +205,7 @@ def main():
         out["corun_gpu_ms"] = {k: round(max(c for c, t in zip(co, tasks) if t.spec.kind == k), 4) for k in kinds}
         out["serialised_gpu_ms"] = {k: round(max(c for c, t in zip(sa, tasks) if t.spec.kind == k), 4) for k in kinds}
         # each task alone, back to back on a busy (clocked-up) device: the kernels' own speed
+        log("tasks alone")
         alone = []
         for t in tasks:
             harness.run_mix(ser, [t], use_arrivals=False)
@@ -208,6 +217,7 @@ def main():
             throughput=round(value / out["serialised_gpu"]["tasks_per_s"], 4),
             turnaround=round(out["serialised_gpu"]["mean_turnaround_ms"] / mean_turn, 4))
         # batch variant (all tasks queued at t = 0, the paper's setting): capacity rather than arrival bound
+        log("batch at t=0")
         harness.run_mix(sched, tasks, use_arrivals=False)
         b = [harness.summarize(*harness.run_mix(sched, tasks, use_arrivals=False)) for _ in range(3)]
         bs = [harness.summarize(*harness.run_mix(ser, tasks, use_arrivals=False)) for _ in range(3)]
@@ -215,11 +225,17 @@ def main():
                                mean_turnaround_ms=round(sum(x["mean_turnaround_ms"] for x in b) / 3, 3),
                                serialised_tasks_per_s=round(sum(x["tasks_per_s"] for x in bs) / 3, 2),
                                serialised_mean_turnaround_ms=round(sum(x["mean_turnaround_ms"] for x in bs) / 3, 3))
-        # the other policies on the same mix (Alg. 3 analogue with overlapping masks; FIFO queue)
+        # the other policies on the same mix: Alg. 3 analogue (overlapping masks), FIFO queue, and
+        # HARD with one workgroup per CU as the residency limit ("spread": a task gets as many
+        # CUs as it has workgroups, so only tasks that cannot fill the device share it)
+        sched.destroy()
+        sched = None
         sweep = {}
-        for name, pol2, q2 in (("soft_backfill", mgb.MGB_POLICY_SOFT, mgb.MGB_QUEUE_BACKFILL),
-                               ("hard_fifo", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_FIFO)):
-            s2 = mgb.Sched(policy=pol2, queue_mode=q2, mem_cap_bytes=cap)
+        for name, pol2, q2, wgcu in (("soft_backfill", mgb.MGB_POLICY_SOFT, mgb.MGB_QUEUE_BACKFILL, 32),
+                                     ("hard_fifo", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_FIFO, 32),
+                                     ("hard_spread", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_BACKFILL, 1)):
+            log("policy sweep: " + name)
+            s2 = mgb.Sched(policy=pol2, queue_mode=q2, mem_cap_bytes=cap, max_wg_per_cu=wgcu)
             harness.run_mix(s2, tasks)
             a = [harness.summarize(*harness.run_mix(s2, tasks)) for _ in range(3)]
             harness.run_mix(s2, tasks, use_arrivals=False)
@@ -232,8 +248,10 @@ def main():
         out["other_policies"] = sweep
         ser.destroy()
     if not args.no_cpu_baseline:
+        log("cpu baseline")
         out["cpu_baseline"] = cpu_baseline(spec)
-    sched.destroy()
+    if sched is not None:
+        sched.destroy()
     print(json.dumps(out))
 
 

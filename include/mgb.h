@@ -75,16 +75,18 @@ typedef struct {
   uint32_t queue_mode;         /* MGB_QUEUE_*                               */
   uint32_t backend;            /* MGB_BACKEND_*                             */
   int32_t  device;             /* HIP device ordinal (HIP backend)          */
-  uint32_t reserved;
+  uint32_t max_running;        /* most tasks resident at once, 0 = no limit (16) */
 } mgb_device_desc;
 
 /* Answer to a probe.  `stream` is a hipStream_t owned by the library (NULL
  * with the null backend); it is valid until mgb_task_complete(ticket).
- * Granule k owns CU-mask bits [k*granule_cus, (k+1)*granule_cus).            */
+ * Granule k owns CU-mask bits [k*granule_cus, (k+1)*granule_cus).  Granted
+ * granules form a buddy block: the demand rounded up to a power of two b, a
+ * run of b granules starting at a multiple of b.                             */
 typedef struct {
   uint64_t ticket;             /* handle of this task inside the scheduler  */
   uint32_t granule_mask;       /* bit k set = granule k granted             */
-  uint32_t n_granules;         /* granules demanded (= granted)             */
+  uint32_t n_granules;         /* granules demanded (granted: next power of two) */
   uint32_t cu_mask[8];         /* 256-bit CU mask derived from granule_mask */
   void*    stream;
 } mgb_placement;
@@ -132,7 +134,7 @@ typedef struct {
 /* ---- scheduler ----------------------------------------------------------
  * Fill `out` with the defaults for one MI355X: 256 CUs in granules of 8,
  * 64-lane waves, 32 waves and 32 workgroups per CU, cap 288e9 bytes, HARD,
- * BACKFILL, HIP backend, device 0.                                          */
+ * BACKFILL, HIP backend, device 0, at most 16 resident tasks.                */
 void mgb_device_desc_default(mgb_device_desc* out);
 
 /* Create a scheduler for one device.  Errors: MGB_E_INVAL (bad descriptor),
@@ -153,7 +155,11 @@ int mgb_sched_destroy(mgb_sched* s);
  * Compute demand (Algorithm 2's per-SM residency limits, per CU here):
  *   waves/wg = ceil(threads / wave_size);
  *   wg/CU    = max(1, min(max_wg_per_cu, max_waves_per_cu / waves/wg));
- *   CUs      = min(n_cu, ceil(workgroups / wg/CU)); granules = ceil(CUs / granule_cus). */
+ *   CUs      = min(n_cu, ceil(workgroups / wg/CU)); granules = ceil(CUs / granule_cus).
+ * Admission: mem_bytes <= free bytes, fewer than max_running tasks resident,
+ * and (HARD) a free aligned block of next_pow2(granules) granules, the lowest
+ * such block being taken; SOFT takes the aligned block with the fewest in-use
+ * waves instead and never waits for compute.                                */
 int mgb_task_probe(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 grid,
                    mgb_dim3 block, mgb_placement* out);
 

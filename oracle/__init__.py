@@ -147,7 +147,8 @@ def bfs(row_ptr, col_idx, source=0):
 class Device(C.Structure):
     _fields_ = [("cap_bytes", C.c_uint64), ("n_cu", C.c_uint32), ("granule_cus", C.c_uint32),
                 ("wave_size", C.c_uint32), ("max_waves_per_cu", C.c_uint32),
-                ("max_wg_per_cu", C.c_uint32), ("policy", C.c_uint32), ("queue_mode", C.c_uint32)]
+                ("max_wg_per_cu", C.c_uint32), ("policy", C.c_uint32), ("queue_mode", C.c_uint32),
+                ("max_running", C.c_uint32)]
 
 
 INPUT_DT = np.dtype([("kind", "<u4"), ("pad", "<u4"), ("id", "<u8"), ("mem", "<u8"),
@@ -163,9 +164,9 @@ Q_BACKFILL, Q_FIFO = 0, 1
 
 
 def device(cap_bytes, n_cu=256, granule_cus=8, wave_size=64, max_waves_per_cu=32,
-           max_wg_per_cu=32, policy=POL_HARD, queue_mode=Q_BACKFILL):
+           max_wg_per_cu=32, policy=POL_HARD, queue_mode=Q_BACKFILL, max_running=0):
     return Device(cap_bytes, n_cu, granule_cus, wave_size, max_waves_per_cu, max_wg_per_cu,
-                  policy, queue_mode)
+                  policy, queue_mode, max_running)
 
 
 def demand(dev, grid, block):

@@ -15,10 +15,15 @@
 //   * HARD compute (Algorithm 2): the task's thread blocks must all be
 //     resident at once; the number of CUs that needs follows from the
 //     per-CU limits on resident waves and workgroups; the task gets that many
-//     CUs (rounded up to granules) exclusively, or it waits;
+//     CUs exclusively, or it waits.  Partitions are buddy blocks: the demand
+//     in granules is rounded up to a power of two b and the task receives the
+//     lowest-indexed free run of b granules that starts at a multiple of b;
 //   * SOFT compute (Algorithm 3): compute never blocks; the task is put on
-//     the least-loaded compute (here: the granules with the fewest in-use
-//     waves, lowest index first) and its waves are added to their load;
+//     the least-loaded compute (here: the aligned block of b granules with
+//     the smallest total of in-use waves, lowest index first) and its waves
+//     are added to the load of those granules;
+//   * at most max_running tasks are resident at a time when that field is
+//     non-zero (every resident task holds one hardware queue);
 //   * SERIAL (single-assignment baseline, Sec. IV): one task owns the whole
 //     device at a time;
 //   * on every release the waiting tasks are retried in arrival order.
@@ -50,6 +55,7 @@ extern "C" {
 struct orc_device {
   uint64_t cap_bytes;
   uint32_t n_cu, granule_cus, wave_size, max_waves_per_cu, max_wg_per_cu, policy, queue_mode;
+  uint32_t max_running;   // 0 = no limit
 };
 
 struct orc_input {
@@ -129,29 +135,46 @@ int64_t orc_sched_replay(const orc_device* dev, const orc_input* in, uint64_t n_
           d.cu_mask[bit / 32] |= 1u << (bit % 32);
         }
   };
+  uint32_t n_running = 0;
   auto try_admit = [&](Task& t) -> bool {
     if (t.mem > free_bytes) return false;
+    if (dev->max_running != 0 && n_running >= dev->max_running) return false;
+    uint32_t b = 1;                      // block size: demand rounded up to a power of two
+    while (b < t.demand) b <<= 1;
+    if (b > G) b = G;                    // a device whose granule count is not a power of two
     uint32_t pick = 0;
     if (dev->policy == POL_SOFT) {
-      // the `demand` least-loaded granules, lowest index first among equals
-      std::vector<uint32_t> order(G);
-      for (uint32_t g = 0; g < G; ++g) order[g] = g;
-      std::stable_sort(order.begin(), order.end(),
-                       [&](uint32_t a, uint32_t b) { return load[a] < load[b]; });
-      for (uint32_t i = 0; i < t.demand; ++i) pick |= 1u << order[i];
-      t.share = (t.waves + t.demand - 1) / t.demand;
+      uint64_t best_load = 0;
+      bool have = false;
+      for (uint32_t start = 0; start + b <= G; start += b) {
+        uint64_t sum = 0;
+        for (uint32_t g = start; g < start + b; ++g) sum += load[g];
+        if (!have || sum < best_load) {
+          have = true;
+          best_load = sum;
+          pick = (b >= 32 ? 0xffffffffu : ((1u << b) - 1u)) << start;
+        }
+      }
+      if (!have) return false;
+      t.share = (t.waves + b - 1) / b;
       for (uint32_t g = 0; g < G; ++g)
         if (pick >> g & 1u) load[g] += t.share;
     } else {
-      uint32_t have = 0;
-      for (uint32_t g = 0; g < G && have < t.demand; ++g)
-        if (free_map >> g & 1u) { pick |= 1u << g; ++have; }
-      if (have < t.demand) return false;
+      bool have = false;
+      for (uint32_t start = 0; start + b <= G && !have; start += b) {
+        uint32_t block = (b >= 32 ? 0xffffffffu : ((1u << b) - 1u)) << start;
+        if ((free_map & block) == block) {
+          pick = block;
+          have = true;
+        }
+      }
+      if (!have) return false;
       free_map &= ~pick;
     }
     free_bytes -= t.mem;
     t.granted = pick;
     t.running = true;
+    ++n_running;
     return true;
   };
   auto rescan = [&](uint32_t idx) {
@@ -203,6 +226,7 @@ int64_t orc_sched_replay(const orc_device* dev, const orc_input* in, uint64_t n_
       } else {
         free_map |= t->granted;
       }
+      --n_running;
       emit(idx, D_RELEASE, t, t->granted, 0, 0);
       uint64_t ticket = t->ticket;
       live.erase(std::find_if(live.begin(), live.end(), [&](const Task& x) { return x.ticket == ticket; }));

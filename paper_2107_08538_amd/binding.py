@@ -42,7 +42,7 @@ class mgb_device_desc(C.Structure):
     _fields_ = [("mem_cap_bytes", C.c_uint64), ("n_cu", C.c_uint32), ("granule_cus", C.c_uint32),
                 ("wave_size", C.c_uint32), ("max_waves_per_cu", C.c_uint32),
                 ("max_wg_per_cu", C.c_uint32), ("policy", C.c_uint32), ("queue_mode", C.c_uint32),
-                ("backend", C.c_uint32), ("device", C.c_int32), ("reserved", C.c_uint32)]
+                ("backend", C.c_uint32), ("device", C.c_int32), ("max_running", C.c_uint32)]
 
 
 class mgb_placement(C.Structure):

@@ -5,6 +5,14 @@
 // (Algorithm 2: memory and compute both hard; Algorithm 3: memory hard,
 // compute placed by load) with the device's SMs replaced by granules of CUs
 // that are handed out exclusively (HARD) and realised as CU-masked streams.
+//
+// Partitions are buddy blocks (power-of-two runs of granules, aligned to their
+// size).  That keeps the set of CU masks small (63 for 32 granules), which
+// matters because a masked stream is a hardware queue: creating one costs
+// milliseconds, and beyond about 24 live queues the device time-slices them and
+// every launch slows down a hundredfold.  The library therefore keeps few
+// masked streams alive, reuses them by mask, never lets more than max_running
+// tasks be resident, and creates the masks of the large blocks up front.
 #include "../../include/mgb.h"
 #include "launch_util.h"
 
@@ -12,12 +20,12 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <condition_variable>
 #include <cstdio>
 #include <cstring>
 #include <deque>
-#include <map>
 #include <mutex>
 #include <string>
 #include <unordered_map>
@@ -36,6 +44,13 @@ uint64_t now_ns() {
              std::chrono::steady_clock::now().time_since_epoch())
       .count();
 }
+
+// Live masked streams of the whole process.  Launch cost is flat up to 24 live queues and
+// jumps from ~15 us to milliseconds at 28 (measured), and the process also owns the queues of
+// its ordinary streams, so idle streams are destroyed (least recently used first) before the
+// count would pass kStreamsAlive; only streams of resident tasks may push it higher.
+constexpr uint32_t kStreamsAlive = 20;
+std::atomic<uint32_t> g_live_streams{0};
 
 enum class State { Waiting, Running };
 
@@ -66,11 +81,15 @@ struct mgb_sched {
   std::unordered_map<uint64_t, Task> tasks;   // live tasks by ticket
   std::deque<uint64_t> waitq;                 // tickets in arrival order
   uint64_t next_ticket = 0;
+  uint32_t n_running_now = 0;
   std::vector<mgb_trace_rec> trace;
-  // backend: idle masked streams by granule mask, idle timing events
-  std::multimap<uint32_t, hipStream_t> idle_streams;
+  // backend: idle masked streams (mask, stream, when last used), idle timing events
+  struct IdleStream { uint32_t mask; hipStream_t stream; uint64_t stamp; };
+  std::vector<IdleStream> idle_streams;
+  uint64_t stamp = 0;
   std::vector<hipEvent_t> idle_events;
-  uint32_t n_streams = 0;
+  uint32_t n_streams = 0;   // created so far
+  uint32_t n_alive = 0;     // created and not destroyed
 
   void cu_mask_of(uint32_t gmask, uint32_t out[8]) const {
     std::memset(out, 0, 8 * sizeof(uint32_t));
@@ -106,44 +125,54 @@ struct mgb_sched {
     return r.seq;
   }
 
-  // Memory first (hard in every policy), then compute.
+  static uint32_t block_bits(uint32_t b) { return b >= 32u ? 0xffffffffu : ((1u << b) - 1u); }
+
+  // Memory first (hard in every policy), then the resident-task limit, then compute.
+  // Compute is granted in buddy blocks: demand rounded up to a power of two b, block = b
+  // granules starting at a multiple of b.
   bool try_admit(Task& t) {
     if (t.mem > free_bytes) return false;
+    if (d.max_running != 0u && n_running_now >= d.max_running) return false;
+    uint32_t b = 1;
+    while (b < t.demand) b <<= 1;
+    if (b > G) b = G;
     uint32_t pick = 0;
     if (d.policy == MGB_POLICY_SOFT) {
-      // never blocks on compute: the `demand` granules carrying the fewest
-      // in-use waves, lower index winning ties
-      uint32_t taken = 0;
-      for (uint32_t n = 0; n < t.demand; ++n) {
-        uint32_t best = G;
-        for (uint32_t g = 0; g < G; ++g) {
-          if (taken >> g & 1u) continue;
-          if (best == G || load[g] < load[best]) best = g;
+      // never blocks on compute: the aligned block carrying the fewest in-use waves,
+      // the lower block winning ties
+      uint64_t best = 0;
+      for (uint32_t start = 0; start + b <= G; start += b) {
+        uint64_t sum = 0;
+        for (uint32_t g = start; g < start + b; ++g) sum += load[g];
+        if (pick == 0u || sum < best) {
+          best = sum;
+          pick = block_bits(b) << start;
         }
-        taken |= 1u << best;
       }
-      pick = taken;
-      t.share = (t.waves + t.demand - 1) / t.demand;
+      t.share = (t.waves + b - 1) / b;
       for (uint32_t g = 0; g < G; ++g)
         if (pick >> g & 1u) load[g] += t.share;
     } else {
-      if ((uint32_t)__builtin_popcount(free_map) < t.demand) return false;
-      uint32_t m = free_map;
-      for (uint32_t n = 0; n < t.demand; ++n) {
-        uint32_t low = m & (~m + 1u);  // lowest free granule
-        pick |= low;
-        m &= ~low;
+      for (uint32_t start = 0; start + b <= G; start += b) {
+        const uint32_t block = block_bits(b) << start;
+        if ((free_map & block) == block) {
+          pick = block;
+          break;
+        }
       }
+      if (pick == 0u) return false;
       free_map &= ~pick;
     }
     free_bytes -= t.mem;
     t.granted = pick;
     t.state = State::Running;
+    ++n_running_now;
     return true;
   }
 
   void release(Task& t) {
     free_bytes += t.mem;
+    --n_running_now;
     if (d.policy == MGB_POLICY_SOFT) {
       for (uint32_t g = 0; g < G; ++g)
         if (t.granted >> g & 1u) load[g] -= t.share;
@@ -171,24 +200,42 @@ struct mgb_sched {
   }
 
   // ---- backend -----------------------------------------------------------
+  int create_stream(uint32_t gmask, hipStream_t* out) {
+    // make room first: idle streams of other masks are the cheapest thing to give up
+    while (!idle_streams.empty() && g_live_streams.load() >= kStreamsAlive) {
+      size_t victim = 0;
+      for (size_t i = 1; i < idle_streams.size(); ++i)
+        if (idle_streams[i].stamp < idle_streams[victim].stamp) victim = i;
+      (void)hipStreamDestroy(idle_streams[victim].stream);
+      idle_streams.erase(idle_streams.begin() + (long)victim);
+      --g_live_streams;
+    }
+    uint32_t cu[8];
+    cu_mask_of(gmask, cu);
+    hipError_t e = hipSetDevice(d.device);
+    if (e == hipSuccess) e = hipExtStreamCreateWithCUMask(out, 8, cu);
+    if (e != hipSuccess) {
+      set_error("hipExtStreamCreateWithCUMask", e);
+      *out = nullptr;
+      return MGB_E_BACKEND;
+    }
+    ++n_streams;
+    ++g_live_streams;
+    return MGB_OK;
+  }
+
   int bind_stream(Task& t) {
     if (d.backend != MGB_BACKEND_HIP) return MGB_OK;
     if (t.stream) return MGB_OK;
-    auto it = idle_streams.find(t.granted);
-    if (it != idle_streams.end()) {
-      t.stream = it->second;
-      idle_streams.erase(it);
-    } else {
-      uint32_t cu[8];
-      cu_mask_of(t.granted, cu);
-      hipError_t e = hipSetDevice(d.device);
-      if (e == hipSuccess) e = hipExtStreamCreateWithCUMask(&t.stream, 8, cu);
-      if (e != hipSuccess) {
-        set_error("hipExtStreamCreateWithCUMask", e);
-        t.stream = nullptr;
-        return MGB_E_BACKEND;
+    for (size_t i = 0; i < idle_streams.size(); ++i)
+      if (idle_streams[i].mask == t.granted) {
+        t.stream = idle_streams[i].stream;
+        idle_streams.erase(idle_streams.begin() + (long)i);
+        break;
       }
-      ++n_streams;
+    if (!t.stream) {
+      int rc = create_stream(t.granted, &t.stream);
+      if (rc != MGB_OK) return rc;
     }
     for (hipEvent_t* ev : {&t.ev_start, &t.ev_stop}) {
       if (!idle_events.empty()) {
@@ -206,7 +253,7 @@ struct mgb_sched {
   }
 
   void unbind_stream(Task& t) {
-    if (t.stream) idle_streams.emplace(t.granted, t.stream);
+    if (t.stream) idle_streams.push_back({t.granted, t.stream, ++stamp});
     if (t.ev_start) idle_events.push_back(t.ev_start);
     if (t.ev_stop) idle_events.push_back(t.ev_stop);
     t.stream = nullptr;
@@ -241,6 +288,7 @@ void mgb_device_desc_default(mgb_device_desc* out) {
   out->queue_mode = MGB_QUEUE_BACKFILL;
   out->backend = MGB_BACKEND_HIP;
   out->device = 0;
+  out->max_running = 16;
 }
 
 int mgb_sched_create(const mgb_device_desc* desc, mgb_sched** out) {
@@ -280,6 +328,19 @@ int mgb_sched_create(const mgb_device_desc* desc, mgb_sched** out) {
   s->free_bytes = d.mem_cap_bytes;
   s->free_map = s->all_mask;
   s->load.assign(s->G, 0);
+  if (d.backend == MGB_BACKEND_HIP) {
+    // the masks of the large blocks (whole device, halves, quarters) are created now, not on
+    // the first task that needs them
+    for (uint32_t b = s->G; b >= 1u && b * 4u >= s->G; b >>= 1)
+      for (uint32_t start = 0; start + b <= s->G; start += b) {
+        hipStream_t st = nullptr;
+        if (s->create_stream(mgb_sched::block_bits(b) << start, &st) != MGB_OK) {
+          mgb_sched_destroy(s);
+          return MGB_E_BACKEND;
+        }
+        s->idle_streams.push_back({mgb_sched::block_bits(b) << start, st, ++s->stamp});
+      }
+  }
   *out = s;
   return MGB_OK;
 }
@@ -289,7 +350,10 @@ int mgb_sched_destroy(mgb_sched* s) {
   {
     std::lock_guard<std::mutex> lk(s->mu);
     if (!s->tasks.empty()) return MGB_E_BUSY;
-    for (auto& kv : s->idle_streams) (void)hipStreamDestroy(kv.second);
+    for (auto& is : s->idle_streams) {
+      (void)hipStreamDestroy(is.stream);
+      --g_live_streams;
+    }
     for (hipEvent_t e : s->idle_events) (void)hipEventDestroy(e);
     s->idle_streams.clear();
     s->idle_events.clear();
@@ -483,7 +547,7 @@ int mgb_sched_stats(mgb_sched* s, mgb_stats* out) {
   out->free_bytes = s->free_bytes;
   out->free_granules = s->free_map;
   out->n_waiting = (uint32_t)s->waitq.size();
-  out->n_running = (uint32_t)(s->tasks.size() - s->waitq.size());
+  out->n_running = s->n_running_now;
   out->n_streams = s->n_streams;
   out->n_events = s->trace.size();
   return MGB_OK;

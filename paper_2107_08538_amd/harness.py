@@ -91,20 +91,32 @@ def build_task(spec, data, device="cuda:0"):
     raise ValueError(k)
 
 
-def run_mix(sched, tasks, use_arrivals=True, time_scale=1.0):
-    """Push every task through probe -> (wait) -> launch -> sync -> complete, one worker per task.
+MAX_WORKERS = 32      # the paper's pool for its largest (128-job) mix, Sec. V-E
 
-    With use_arrivals the worker of task i issues its probe at t0 + arrival_i; otherwise all probes
-    are issued back to back in task-id order before anything runs (batch at t = 0).
+
+def run_mix(sched, tasks, use_arrivals=True, time_scale=1.0, workers=None):
+    """Push every task through probe -> (wait) -> launch -> sync -> complete with a pool of
+    workers, each taking the next job in arrival order, running it to completion and pulling
+    another (Sec. V-A).  The pool holds min(#tasks, 32) workers.
+
+    With use_arrivals a job is not probed before t0 + arrival_i (it may additionally wait for a
+    free worker; turnaround counts from its arrival either way); otherwise all probes are issued
+    back to back in task-id order before anything runs (batch at t = 0) when the pool is as
+    large as the mix, else as workers become free.
     Returns per-task records (times in seconds relative to t0) and the makespan."""
     n = len(tasks)
+    n_workers = min(n, workers or MAX_WORKERS)
     rec = [dict(task_id=t.spec.task_id, kind=t.spec.kind) for t in tasks]
     errors = []
     placements = [None] * n
+    order = sorted(range(n), key=lambda i: (tasks[i].spec.arrival_s, i)) if use_arrivals else list(range(n))
+    cursor = [0]
+    take = threading.Lock()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
 
-    if not use_arrivals:
+    pre_probed = (not use_arrivals) and n_workers >= n
+    if pre_probed:
         for i, t in enumerate(tasks):
             rec[i]["arrival"] = 0.0
             rc, pl = sched.probe(t.spec.task_id, t.mem, t.grid, t.block)
@@ -112,9 +124,11 @@ def run_mix(sched, tasks, use_arrivals=True, time_scale=1.0):
             rec[i]["probe"] = time.perf_counter() - t0
             placements[i] = (rc, pl)
 
-    def worker(i):
+    def run_one(i):
         t = tasks[i]
-        try:
+        if pre_probed:
+            rc, pl = placements[i]
+        else:
             if use_arrivals:
                 due = t0 + t.spec.arrival_s * time_scale
                 while True:
@@ -123,26 +137,39 @@ def run_mix(sched, tasks, use_arrivals=True, time_scale=1.0):
                         break
                     time.sleep(dt if dt > 2e-4 else 0)
                 rec[i]["arrival"] = t.spec.arrival_s * time_scale
-                rc, pl = sched.probe(t.spec.task_id, t.mem, t.grid, t.block)
-                mgb.check(rc, "mgb_task_probe")
-                rec[i]["probe"] = time.perf_counter() - t0
             else:
-                rc, pl = placements[i]
-            if rc == mgb.MGB_WAIT:
-                rc, pl = sched.wait(pl.ticket)
-                mgb.check(rc, "mgb_task_wait")
-            rec[i]["admit"] = time.perf_counter() - t0
-            rec[i]["granules"] = pl.n_granules
-            mgb.check(sched.launch(pl.ticket, t.enqueue), "mgb_task_launch")
-            rc, ms = sched.sync(pl.ticket)
-            mgb.check(rc, "mgb_task_sync")
-            rec[i]["gpu_ms"] = ms
-            rec[i]["done"] = time.perf_counter() - t0
-            mgb.check(sched.complete(pl.ticket), "mgb_task_complete")
-        except Exception as e:   # noqa: BLE001
-            errors.append((i, repr(e)))
+                rec[i]["arrival"] = 0.0
+            rc, pl = sched.probe(t.spec.task_id, t.mem, t.grid, t.block)
+            mgb.check(rc, "mgb_task_probe")
+            rec[i]["probe"] = time.perf_counter() - t0
+        if rc == mgb.MGB_WAIT:
+            rc, pl = sched.wait(pl.ticket)
+            mgb.check(rc, "mgb_task_wait")
+        rec[i]["admit"] = time.perf_counter() - t0
+        rec[i]["granules"] = pl.n_granules
+        mgb.check(sched.launch(pl.ticket, t.enqueue), "mgb_task_launch")
+        rc, ms = sched.sync(pl.ticket)
+        mgb.check(rc, "mgb_task_sync")
+        rec[i]["gpu_ms"] = ms
+        rec[i]["done"] = time.perf_counter() - t0
+        mgb.check(sched.complete(pl.ticket), "mgb_task_complete")
 
-    threads = [threading.Thread(target=worker, args=(i,)) for i in range(n)]
+    def worker(w):
+        try:
+            if pre_probed:                     # one worker per job, job w
+                run_one(w)
+                return
+            while True:
+                with take:
+                    if cursor[0] >= n:
+                        return
+                    i = order[cursor[0]]
+                    cursor[0] += 1
+                run_one(i)
+        except Exception as e:   # noqa: BLE001
+            errors.append((w, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(w,)) for w in range(n_workers)]
     for th in threads:
         th.start()
     for th in threads:

@@ -15,7 +15,7 @@ def oracle_device(desc):
     return oracle.device(desc.mem_cap_bytes, n_cu=desc.n_cu, granule_cus=desc.granule_cus,
                          wave_size=desc.wave_size, max_waves_per_cu=desc.max_waves_per_cu,
                          max_wg_per_cu=desc.max_wg_per_cu, policy=desc.policy,
-                         queue_mode=desc.queue_mode)
+                         queue_mode=desc.queue_mode, max_running=desc.max_running)
 
 
 def split_trace(trace):

@@ -86,13 +86,36 @@ def test_stuck_task_does_not_block_tasks_that_fit():
     assert rc == mgb.MGB_OK and big.granule_mask == 0xFFFFFFFF
     rc, w = s.probe(2, 50, (1, 1, 1), (64, 1, 1))
     assert rc == mgb.MGB_WAIT                                         # compute is hard: must wait
-    s2 = _null(mem_cap_bytes=1000)
+    s2 = _null(mem_cap_bytes=1000, max_running=0)
     rc, half = s2.probe(1, 900, (1024, 1, 1), (256, 1, 1))            # half the device, never completes
     assert rc == mgb.MGB_OK and half.granule_mask == 0x0000FFFF
     for i in range(16):
         rc, pl = s2.probe(10 + i, 5, (8, 1, 1), (256, 1, 1))
         assert rc == mgb.MGB_OK and pl.granule_mask == 1 << (16 + i)
         assert list(pl.cu_mask) == [0] * (4 + i // 4) + [0xFF << (8 * (i % 4))] + [0] * (3 - i // 4)
+
+
+def test_resident_task_limit():
+    s = _null(mem_cap_bytes=10 ** 6)                                  # default: 16 resident tasks
+    assert s.desc.max_running == 16
+    pls = [s.probe(i, 1, (8, 1, 1), (256, 1, 1)) for i in range(17)]
+    assert [rc for rc, _ in pls] == [mgb.MGB_OK] * 16 + [mgb.MGB_WAIT]
+    assert s.stats().free_granules == 0xFFFF0000                      # granules are free, queues are not
+    assert s.complete(pls[3][1].ticket) == 0
+    rc, pl = s.wait(pls[16][1].ticket, 0)
+    assert rc == mgb.MGB_OK and pl.granule_mask == 1 << 3
+    assert_trace_matches_replay(s.desc, s.trace())
+
+
+def test_buddy_blocks_in_the_library():
+    s = _null(mem_cap_bytes=10 ** 6, n_cu=64)                         # 8 granules
+    wg = lambda g: (64 * g, 1, 1)
+    got = []
+    for i, g in enumerate((3, 1, 2, 2, 1)):
+        rc, pl = s.probe(i, 1, wg(g), (256, 1, 1))
+        got.append((rc, pl.granule_mask, pl.n_granules))
+    assert got == [(0, 0x0F, 3), (0, 0x10, 1), (0, 0xC0, 2), (1, 0, 2), (0, 0x20, 1)]
+    assert_trace_matches_replay(s.desc, s.trace())
 
 
 def _random_storm(s, rng, n_ops):
@@ -121,7 +144,7 @@ def _random_storm(s, rng, n_ops):
 @pytest.mark.parametrize("mode", [mgb.MGB_QUEUE_BACKFILL, mgb.MGB_QUEUE_FIFO])
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_library_decisions_equal_replay_on_random_streams(policy, mode, seed):
-    s = _null(mem_cap_bytes=10_000, policy=policy, queue_mode=mode)
+    s = _null(mem_cap_bytes=10_000, policy=policy, queue_mode=mode, max_running=[0, 16, 5][seed])
     left = _random_storm(s, np.random.default_rng(seed), 400)
     assert not left
     dec = assert_trace_matches_replay(s.desc, s.trace())

@@ -49,7 +49,7 @@ def test_placements_are_disjoint_sets_of_physical_cus():
         assert s.complete(pl.ticket) == 0
     rc, pl = s.probe(9, 1, (512, 1, 1), (256, 1, 1))                  # streams are cached per mask
     assert pl.granule_mask == pls[0].granule_mask and pl.stream == pls[0].stream
-    assert s.stats().n_streams == 4
+    assert s.stats().n_streams == 9      # 7 created up front (whole, halves, quarters) + two single granules
     assert s.complete(pl.ticket) == 0
     assert s.destroy() == 0
 

@@ -145,7 +145,13 @@ def test_invariants_after_every_event(policy, mode, seed):
                 mem_of[t] = ev[2]
             waiting.discard(t)
             running[t] = (mem_of[t], int(d["granule_mask"]))
-            assert bin(d["granule_mask"]).count("1") == d["demand"]
+            # buddy block: demand rounded up to a power of two, contiguous, aligned to its size
+            b = 1
+            while b < d["demand"]:
+                b *= 2
+            gm = int(d["granule_mask"])
+            low = (gm & -gm).bit_length() - 1
+            assert gm == ((1 << b) - 1) << low and low % b == 0
             if policy == POL_SERIAL:
                 assert d["granule_mask"] == 0xFFFFFFFF and len(running) == 1
         elif k == D_WAIT:
@@ -281,6 +287,34 @@ def test_all_orders_of_four_tasks_on_four_granules():
             assert sum(1 for d in d2 if d["kind"] == D_RELEASE) == 4
             assert d2[-1]["free_bytes"] == 100 or any(
                 d["kind"] == D_RELEASE and d["free_bytes"] == 100 for d in d2)
+
+
+def test_buddy_blocks_alignment_rounding_and_resident_limit():
+    """Hand-worked: 8 granules (64 CUs), 256-thread workgroups (8 per CU, 64 per granule).
+      t1 wants 3 granules -> block of 4 at [0,4).            free map 11110000
+      t2 wants 1          -> [4,5).                           free map 11100000
+      t3 wants 2          -> lowest aligned free pair [6,8) ([4,6) is broken by t2).  free 00100000
+      t4 wants 2          -> no aligned pair left (only granule 5) -> waits
+      t5 wants 1          -> [5,6) (backfill)                 free 00000000
+      complete t2         -> granule 4 free; t4 still has no pair ([4,6) half busy) -> keeps waiting
+      complete t5         -> [4,6) free -> t4 admitted there
+    and with max_running = 2 the third task must wait although granules are free."""
+    dev = oracle.device(1 << 30, n_cu=64, granule_cus=8)
+    wg = lambda g: (64 * g, 1, 1)
+    ev = [("probe", 1, 1, wg(3), (256, 1, 1)), ("probe", 2, 1, wg(1), (256, 1, 1)),
+          ("probe", 3, 1, wg(2), (256, 1, 1)), ("probe", 4, 1, wg(2), (256, 1, 1)),
+          ("probe", 5, 1, wg(1), (256, 1, 1)), ("complete", 2), ("complete", 5)]
+    dec = oracle.sched_replay(dev, oracle.make_inputs(ev))
+    got = [(int(d["in_index"]), int(d["kind"]), int(d["ticket"]), int(d["granule_mask"]), int(d["free_granules"]))
+           for d in dec]
+    assert got == [(0, D_ADMIT, 1, 0x0F, 0xF0), (1, D_ADMIT, 2, 0x10, 0xE0), (2, D_ADMIT, 3, 0xC0, 0x20),
+                   (3, D_WAIT, 4, 0, 0x20), (4, D_ADMIT, 5, 0x20, 0x00),
+                   (5, D_RELEASE, 2, 0x10, 0x10), (6, D_RELEASE, 5, 0x20, 0x30), (6, D_ADMIT, 4, 0x30, 0x00)]
+    assert [int(d["demand"]) for d in dec[:5]] == [3, 1, 2, 2, 1]
+    dev2 = oracle.device(1 << 30, n_cu=64, granule_cus=8, max_running=2)
+    dec2 = oracle.sched_replay(dev2, oracle.make_inputs(ev[:3] + [("complete", 1)]))
+    assert [int(d["kind"]) for d in dec2] == [D_ADMIT, D_ADMIT, D_WAIT, D_RELEASE, D_ADMIT]
+    assert int(dec2[4]["ticket"]) == 3 and int(dec2[4]["granule_mask"]) == 0x03   # lowest aligned pair now free
 
 
 def test_probe_formulas_match_stated_footprints():
