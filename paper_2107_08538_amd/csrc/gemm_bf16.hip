@@ -64,7 +64,8 @@ __global__ __launch_bounds__(GB_THREADS, 2) void gemm_bf16_kernel(const uint16_t
                                                               const uint16_t* __restrict__ B,
                                                               float* __restrict__ C, uint32_t M,
                                                               uint32_t N, uint32_t K,
-                                                              uint32_t tiles_n, uint32_t tiles_total) {
+                                                              uint32_t tiles_n, uint32_t tiles_total,
+                                                              uint32_t vec_ok) {
   __shared__ __attribute__((aligned(16))) uint16_t As[2][GB_BM][GB_LDA];   // [m][k]
   __shared__ __attribute__((aligned(16))) uint16_t Bs[2][GB_BK][GB_LDB];   // [k][n]
 
@@ -78,6 +79,11 @@ __global__ __launch_bounds__(GB_THREADS, 2) void gemm_bf16_kernel(const uint16_t
   const uint32_t in_band = seq - band * 8u * tiles_n;
   const uint32_t bm = (8u * band + in_band % band_rows) * GB_BM;
   const uint32_t bn = (in_band / band_rows) * GB_BN;
+
+  // FAST: every tile is full and aligned.  Otherwise tiles that lie fully inside C still take
+  // the 16-byte path when the shape allows it (vec_ok: k % 32 == 0, n % 8 == 0, aligned
+  // pointers); only ragged edge tiles gather element-wise.  Workgroup-uniform.
+  const bool vec = FAST || (vec_ok != 0u && bm + GB_BM <= M && bn + GB_BN <= N);
 
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wave = tid >> 6;
@@ -96,14 +102,15 @@ __global__ __launch_bounds__(GB_THREADS, 2) void gemm_bf16_kernel(const uint16_t
     for (uint32_t h = 0; h < 2; ++h) {
       const uint32_t f = tid + GB_THREADS * h;
       const uint32_t gr = bm + (f >> 2), gk = k0 + 8u * (f & 3u);
-      if (FAST) ra[h] = *reinterpret_cast<const u32x4*>(A + (size_t)gr * K + gk);
+      // edge tiles: a chunk that lies fully inside the matrix is still one 16-byte load
+      if (vec || (vec_ok != 0u && gr < M && gk + 8u <= K)) ra[h] = *reinterpret_cast<const u32x4*>(A + (size_t)gr * K + gk);
       else ra[h] = gather8(A + (size_t)gr * K + gk, gr < M, gk, K);
     }
 #pragma unroll
     for (uint32_t h = 0; h < 4; ++h) {
       const uint32_t f = tid + GB_THREADS * h;
       const uint32_t gk = k0 + (f >> 5), gc = bn + 8u * (f & 31u);
-      if (FAST) rb[h] = *reinterpret_cast<const u32x4*>(B + (size_t)gk * N + gc);
+      if (vec || (vec_ok != 0u && gk < K && gc + 8u <= N)) rb[h] = *reinterpret_cast<const u32x4*>(B + (size_t)gk * N + gc);
       else rb[h] = gather8(B + (size_t)gk * N + gc, gk < K, gc, N);
     }
   };
@@ -167,7 +174,7 @@ __global__ __launch_bounds__(GB_THREADS, 2) void gemm_bf16_kernel(const uint16_t
       for (int r = 0; r < 16; ++r) {
         const uint32_t row = bm + wm + 32u * i + 8u * (r >> 2) + 4u * lhi + (r & 3);
         const uint32_t col = bn + wn + 32u * j + l32;
-        if (FAST || (row < M && col < N)) C[(size_t)row * N + col] = acc[i][j][r];
+        if (vec || (row < M && col < N)) C[(size_t)row * N + col] = acc[i][j][r];
       }
 }
 
@@ -212,12 +219,13 @@ int mgb_gemm_bf16_enqueue(void* stream, const uint16_t* A, const uint16_t* B, fl
   const Geometry g = geometry(m, n, k);
   const bool aligned = (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15u) == 0u;
   hipStream_t st = (hipStream_t)stream;
+  const uint32_t vec_ok = (aligned && k % GB_BK == 0u && n % 8u == 0u) ? 1u : 0u;
   if (g.fast && aligned)
     hipLaunchKernelGGL(gemm_bf16_kernel<true>, dim3(g.blocks), dim3(GB_THREADS), 0, st, A, B, C, m,
-                       n, k, g.tiles_n, g.total);
+                       n, k, g.tiles_n, g.total, 1u);
   else
     hipLaunchKernelGGL(gemm_bf16_kernel<false>, dim3(g.blocks), dim3(GB_THREADS), 0, st, A, B, C, m,
-                       n, k, g.tiles_n, g.total);
+                       n, k, g.tiles_n, g.total, vec_ok);
   return mgb_check_launch("gemm_bf16_kernel");
 }
 

@@ -37,14 +37,17 @@ constexpr uint32_t GF_TM = GF_BM / (32u * GF_WM), GF_TN = GF_BN / (32u * GF_WN);
 constexpr uint32_t GF_THREADS = 64u * GF_WM * GF_WN;
 constexpr uint32_t GF_LOADS = 512u / GF_THREADS;                   // float4 per thread per operand tile
 
-// FAST: m % 128 == 0, n % 128 == 0, k % 16 == 0 -> unguarded 16-byte loads.
-// otherwise every global access is guarded and scalar.
+// FAST: m % 128 == 0, n % 128 == 0, k % 16 == 0, 16-byte aligned -> unguarded 16-byte
+// accesses everywhere.  Otherwise the decision is taken per workgroup: a tile that lies fully
+// inside C (and k % 16 == 0, n % 4 == 0, aligned pointers: `vec_ok`) still takes the 16-byte
+// path, only the ragged edge tiles fall back to guarded scalar accesses.
 template <bool FAST>
 __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __restrict__ A,
                                                              const float* __restrict__ B,
                                                              float* __restrict__ C, uint32_t M,
                                                              uint32_t N, uint32_t K,
-                                                             uint32_t tiles_n, uint32_t tiles_total) {
+                                                             uint32_t tiles_n, uint32_t tiles_total,
+                                                             uint32_t vec_ok) {
   __shared__ float As[2][GF_BK][GF_BM];   // [k][m]
   __shared__ float Bs[2][GF_BK][GF_BN];   // [k][n]
 
@@ -63,6 +66,8 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
   const uint32_t bm = (BAND * band + in_band % band_rows) * GF_BM;
   const uint32_t bn = (in_band / band_rows) * GF_BN;
 
+  const bool vec = FAST || (vec_ok != 0u && bm + GF_BM <= M && bn + GF_BN <= N);   // workgroup-uniform
+
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wave = tid >> 6;
   const uint32_t wm = (wave / GF_WN) * (32u * GF_TM), wn = (wave % GF_WN) * (32u * GF_TN);
@@ -77,7 +82,8 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
     for (uint32_t h = 0; h < GF_LOADS; ++h) {
       const uint32_t f = tid + GF_THREADS * h;
       const uint32_t gr = bm + (f & 127u), gk = k0 + 4u * (f >> 7);
-      if (FAST) {
+      // edge tiles: a quad that lies fully inside the matrix is still one 16-byte load
+      if (vec || (vec_ok != 0u && gr < M && gk + 4u <= K)) {
         ra[h] = *reinterpret_cast<const float4*>(A + (size_t)gr * K + gk);
       } else {
         float t[4];
@@ -86,7 +92,7 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
         ra[h] = make_float4(t[0], t[1], t[2], t[3]);
       }
       const uint32_t gkb = k0 + (f >> 5), gc = bn + 4u * (f & 31u);
-      if (FAST) {
+      if (vec || (vec_ok != 0u && gkb < K && gc + 4u <= N)) {
         rb[h] = *reinterpret_cast<const float4*>(B + (size_t)gkb * N + gc);
       } else {
         float t[4];
@@ -154,7 +160,7 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
       for (int r = 0; r < 16; ++r) {
         const uint32_t row = bm + wm + 32u * i + 8u * (r >> 2) + 4u * lhi + (r & 3);
         const uint32_t col = bn + wn + 32u * j + l32;
-        if (FAST || (row < M && col < N)) C[(size_t)row * N + col] = acc[i][j][r];
+        if (vec || (row < M && col < N)) C[(size_t)row * N + col] = acc[i][j][r];
       }
 }
 
@@ -199,12 +205,13 @@ int mgb_gemm_f32_enqueue(void* stream, const float* A, const float* B, float* C,
   const Geometry g = geometry(m, n, k);
   const bool aligned = (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15u) == 0u;
   hipStream_t st = (hipStream_t)stream;
+  const uint32_t vec_ok = (aligned && k % GF_BK == 0u && n % 4u == 0u) ? 1u : 0u;
   if (g.fast && aligned)
     hipLaunchKernelGGL(gemm_f32_kernel<true>, dim3(g.blocks), dim3(GF_THREADS), 0, st, A, B, C, m,
-                       n, k, g.tiles_n, g.total);
+                       n, k, g.tiles_n, g.total, 1u);
   else
     hipLaunchKernelGGL(gemm_f32_kernel<false>, dim3(g.blocks), dim3(GF_THREADS), 0, st, A, B, C, m,
-                       n, k, g.tiles_n, g.total);
+                       n, k, g.tiles_n, g.total, vec_ok);
   return mgb_check_launch("gemm_f32_kernel");
 }
 
