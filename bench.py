@@ -155,7 +155,7 @@ def main():
             k["bytes"] += t.alg_bytes; k["flops"] += t.alg_flops
     dominant = max(kern, key=lambda n: kern[n]["ms"])
     kd = kern[dominant]
-    peaks = dict(jacobi_sweep=("hbm", 8000.0, "GB/s"), bfs_level=("hbm", 8000.0, "GB/s"),
+    peaks = dict(jacobi_sweeps=("hbm", 8000.0, "GB/s"), bfs_level=("hbm", 8000.0, "GB/s"),
                  gemm_f32_kernel=("mfma", 157.3, "TFLOP/s"), gemm_bf16_kernel=("mfma", 2500.0, "TFLOP/s"),
                  conv3x3_kernel=("mfma", 2500.0, "TFLOP/s"))
 

@@ -18,14 +18,23 @@ extern "C" {
 
 // out = {mem_bytes, grid_x, grid_y, grid_z, block_x, block_y, block_z}
 
-// Jacobi n x n: two fp32 grids.  A workgroup of 256 threads sweeps 16 interior
-// rows of a column strip; a thread covers 4 columns when n is a multiple of 4
-// (strip = 1024 columns), else 1 column (strip = 256 columns).
+// Jacobi n x n: two fp32 grids.  n % 4 == 0: a wave sweeps a window of 256 columns x 8 output
+// rows; windows step by 248 columns (4 columns on each side of a window go stale, except next to
+// the grid's own boundary), so the first window yields columns 1..251 and each further one 248
+// more; four windows per 256-thread workgroup.  Otherwise one column per thread, 256 columns x
+// 8 rows per workgroup.
 void orc_jacobi_probe(uint64_t n, uint64_t out[7]) {
-  uint64_t strip = (n % 4 == 0) ? 1024 : 256;
-  uint64_t tiles = ceil_div(n, strip) * ceil_div(n - 2, 16);
+  uint64_t wg;
+  if (n % 4 == 0) {
+    uint64_t last = n - 2;                       // last interior column
+    uint64_t win_c = last <= 251 ? 1 : 1 + ceil_div(last - 251, 248);
+    uint64_t win_r = ceil_div(n - 2, 8);
+    wg = ceil_div(win_c * win_r, 4);
+  } else {
+    wg = ceil_div(n, 256) * ceil_div(n - 2, 8);
+  }
   out[0] = 2 * n * n * 4;
-  out[1] = round8(tiles); out[2] = 1; out[3] = 1;
+  out[1] = round8(wg); out[2] = 1; out[3] = 1;
   out[4] = 256; out[5] = 1; out[6] = 1;
 }
 

@@ -97,6 +97,7 @@ mgb_last_error = _sig("mgb_last_error", C.c_char_p)
 _probe_tail = (_P(_u64), _P(mgb_dim3), _P(mgb_dim3))
 mgb_jacobi_probe = _sig("mgb_jacobi_probe", C.c_int, _u32, _u32, *_probe_tail)
 mgb_jacobi_enqueue = _sig("mgb_jacobi_enqueue", C.c_int, _vp, _vp, _vp, _u32, _u32)
+mgb_jacobi_launch_count = _sig("mgb_jacobi_launch_count", _u32, _u32, _u32)
 mgb_gemm_f32_probe = _sig("mgb_gemm_f32_probe", C.c_int, _u32, _u32, _u32, *_probe_tail)
 mgb_gemm_f32_enqueue = _sig("mgb_gemm_f32_enqueue", C.c_int, _vp, _vp, _vp, _vp, _u32, _u32, _u32)
 mgb_gemm_bf16_probe = _sig("mgb_gemm_bf16_probe", C.c_int, _u32, _u32, _u32, *_probe_tail)
@@ -118,7 +119,7 @@ EXPORTS = [
     "mgb_device_desc_default", "mgb_sched_create", "mgb_sched_destroy", "mgb_task_probe",
     "mgb_task_wait", "mgb_task_cancel", "mgb_task_launch", "mgb_task_sync", "mgb_task_complete",
     "mgb_sched_stats", "mgb_trace_read", "mgb_trace_dump", "mgb_last_error",
-    "mgb_jacobi_probe", "mgb_jacobi_enqueue", "mgb_gemm_f32_probe", "mgb_gemm_f32_enqueue",
+    "mgb_jacobi_probe", "mgb_jacobi_enqueue", "mgb_jacobi_launch_count", "mgb_gemm_f32_probe", "mgb_gemm_f32_enqueue",
     "mgb_gemm_bf16_probe", "mgb_gemm_bf16_enqueue", "mgb_conv3x3_probe", "mgb_conv3x3_enqueue",
     "mgb_cnn_probe", "mgb_cnn_enqueue", "mgb_bfs_work_bytes", "mgb_bfs_probe", "mgb_bfs_enqueue",
     "mgb_cu_trace_enqueue", "mgb_copy_enqueue",

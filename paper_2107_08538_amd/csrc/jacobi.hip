@@ -1,81 +1,116 @@
-// fp32 5-point Jacobi relaxation, one kernel launch per sweep.
+// fp32 5-point Jacobi relaxation, up to four sweeps per kernel launch.
 //
-// HBM-bound: the ideal traffic is one read and one write of every cell per
-// sweep (8 bytes per cell update).  Each thread owns four adjacent columns
-// (one 16-byte access per row) and marches down JB_ROWS rows keeping the
-// north / centre / south rows in registers, so every cell is read from memory
-// once per workgroup plus a two-row halo.  West / east neighbours come from
-// the neighbouring lane through a wave shuffle; only the two edge lanes of a
-// wave issue an extra scalar load (an L1/L2 hit on a line the neighbouring
-// wave is streaming anyway).
+// One sweep per launch is HBM-bound at 8 bytes per cell update (one read and
+// one write of every cell).  Fusing T sweeps into a launch divides that traffic
+// by about T: a wave loads a window of (JB_ROWS + 2T) rows x 256 columns into
+// registers (each lane four adjacent columns, one 16-byte load per row), runs
+// T sweeps entirely in registers -- north / south neighbours are the lane's
+// own registers, west / east come from the neighbouring lane through a wave
+// shuffle -- and stores the JB_ROWS x 248 cells that are still exact.  Cells
+// next to a window edge go stale by one cell per sweep, which is why windows
+// overlap by four columns and T rows on each side; the fixed outer ring of the
+// grid is a true boundary and costs no overlap.  No LDS and no barriers: waves
+// are independent.  Eight output rows per window keep the register file small
+// enough for three waves per SIMD, which measured faster than taller windows
+// with less overlap (the kernel is latency-, not bandwidth-limited once fused).
 //
-// The arithmetic is exactly v = 0.25f * ((N + S) + (W + E)): two roundings of
-// pair sums, one rounding of their sum, an exact scaling.  No FMA can form.
+// The arithmetic of every update is exactly v = 0.25f * ((N + S) + (W + E)):
+// two roundings of pair sums, one rounding of their sum, an exact scaling, no
+// FMA can form.  Fusing sweeps changes which wave computes a cell, not what
+// is computed, so results are bit-identical to the one-sweep definition.
 #include "../../include/mgb.h"
 #include "launch_util.h"
 
 #include <hip/hip_runtime.h>
 
+#ifndef JB_ROWS_DEF
+#define JB_ROWS_DEF 8
+#endif
+
 namespace {
 
-constexpr uint32_t JB_THREADS = 256;   // 4 waves
-constexpr uint32_t JB_ROWS = 16;       // interior rows per workgroup
-constexpr uint32_t JB_COLS_V4 = JB_THREADS * 4;
+constexpr uint32_t JB_THREADS = 256;          // 4 waves, one window each
+constexpr uint32_t JB_ROWS = JB_ROWS_DEF;     // output rows per window
+constexpr uint32_t JB_WIN = 256;              // window width in columns (64 lanes x 4)
+constexpr uint32_t JB_HALO = 4;               // columns lost on each side of a window (>= max T, keeps 16-byte alignment)
+constexpr uint32_t JB_STEP = JB_WIN - 2u * JB_HALO;   // 248 exact columns per window
+constexpr uint32_t JB_MAXT = 4;
 
 // Workgroups are dealt round-robin to the 8 XCDs in launch order; give each
-// XCD one contiguous band of tiles so that the halo rows shared by vertically
-// adjacent tiles meet in the same L2.
-__device__ __forceinline__ bool tile_of_block(uint32_t tiles_x, uint32_t tiles_y, uint32_t* tx,
-                                              uint32_t* ty) {
-  const uint32_t total = tiles_x * tiles_y;
-  const uint32_t lin = blockIdx.x;
-  const uint32_t per_xcd = (total + 7u) / 8u;
-  const uint32_t tile = (lin & 7u) * per_xcd + (lin >> 3);
-  if ((lin >> 3) >= per_xcd || tile >= total) return false;
-  *tx = tile % tiles_x;
-  *ty = tile / tiles_x;
+// XCD one contiguous band of windows so that the rows shared by vertically
+// adjacent windows meet in the same L2.
+__device__ __forceinline__ bool window_of_wave(uint32_t tiles_c, uint32_t tiles_r, uint32_t* tc,
+                                               uint32_t* tr) {
+  const uint32_t total = tiles_c * tiles_r;
+  const uint32_t groups = (total + 3u) / 4u;              // workgroups that have work
+  const uint32_t per_xcd = (groups + 7u) / 8u;
+  const uint32_t grp = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || grp >= groups) return false;
+  const uint32_t w = grp * 4u + (threadIdx.x >> 6);
+  if (w >= total) return false;
+  *tc = w % tiles_c;
+  *tr = w / tiles_c;
   return true;
 }
 
-// n % 4 == 0: rows are 16-byte aligned, every thread's four columns are either
+// n % 4 == 0: rows are 16-byte aligned, every lane's four columns are either
 // all inside the grid or all outside.
-__global__ __launch_bounds__(JB_THREADS) void jacobi_sweep_v4(const float* __restrict__ u,
-                                                             float* __restrict__ v, uint32_t n,
-                                                             uint32_t tiles_x, uint32_t tiles_y) {
-  uint32_t tx, ty;
-  if (!tile_of_block(tiles_x, tiles_y, &tx, &ty)) return;
-  const uint32_t c0 = tx * JB_COLS_V4 + threadIdx.x * 4u;
-  const uint32_t r0 = 1u + ty * JB_ROWS;
-  if (c0 >= n) return;
-  const uint32_t r1 = min(r0 + JB_ROWS, n - 1u);  // exclusive
+template <uint32_t T>
+__global__ __launch_bounds__(JB_THREADS) void jacobi_sweeps(const float* __restrict__ u,
+                                                           float* __restrict__ v, uint32_t n,
+                                                           uint32_t tiles_c, uint32_t tiles_r) {
+  constexpr uint32_t NR = JB_ROWS + 2u * T;               // rows held in registers
+  uint32_t tc, tr;
+  if (!window_of_wave(tiles_c, tiles_r, &tc, &tr)) return;
   const uint32_t lane = threadIdx.x & 63u;
-  const bool has_w = c0 > 0u, has_e = c0 + 4u < n;
+  const uint32_t w0 = tc * JB_STEP;                       // first column of the window
+  const uint32_t c0 = w0 + 4u * lane;                     // this lane's first column
+  if (c0 >= n) return;
+  const int32_t g0 = 1 + (int32_t)(tr * JB_ROWS) - (int32_t)T;   // grid row of register row 0
   const bool first_col = c0 == 0u, last_col = c0 + 4u == n;
 
-  float4 north = *reinterpret_cast<const float4*>(u + (size_t)(r0 - 1u) * n + c0);
-  float4 centre = *reinterpret_cast<const float4*>(u + (size_t)r0 * n + c0);
-  // Fixed trip count so the loop unrolls fully and the row loads are issued
-  // ahead of use; on the ragged last tile row indices are clamped to stay in
-  // bounds and the stores are predicated.
+  // load the window; rows above / below the grid do not exist and are never needed
+  float4 cur[NR];
 #pragma unroll
-  for (uint32_t i = 0; i < JB_ROWS; ++i) {
-    const uint32_t r = r0 + i;
-    const float* pc = u + (size_t)min(r, n - 1u) * n + c0;
-    const float4 south = *reinterpret_cast<const float4*>(u + (size_t)min(r + 1u, n - 1u) * n + c0);
-    float west = __shfl_up(centre.w, 1);
-    float east = __shfl_down(centre.x, 1);
-    if (lane == 0u) west = has_w ? pc[-1] : 0.f;
-    if (lane == 63u) east = has_e ? pc[4] : 0.f;
-    float4 o;
-    o.x = 0.25f * ((north.x + south.x) + (west + centre.y));
-    o.y = 0.25f * ((north.y + south.y) + (centre.x + centre.z));
-    o.z = 0.25f * ((north.z + south.z) + (centre.y + centre.w));
-    o.w = 0.25f * ((north.w + south.w) + (centre.z + east));
-    if (first_col) o.x = centre.x;   // boundary columns keep their value
-    if (last_col) o.w = centre.w;
-    if (r < r1) *reinterpret_cast<float4*>(v + (size_t)r * n + c0) = o;
-    north = centre;
-    centre = south;
+  for (uint32_t i = 0; i < NR; ++i) {
+    const int32_t g = g0 + (int32_t)i;
+    const uint32_t gc = (uint32_t)min(max(g, 0), (int32_t)n - 1);
+    cur[i] = *reinterpret_cast<const float4*>(u + (size_t)gc * n + c0);
+  }
+
+#pragma unroll
+  for (uint32_t s = 1; s <= T; ++s) {
+    float4 north = cur[s - 1u];                           // value of the row above before this sweep
+#pragma unroll
+    for (uint32_t i = s; i + s < NR; ++i) {
+      const float4 c = cur[i];
+      const float4 south = cur[i + 1u];
+      const float west = __shfl_up(c.w, 1);
+      const float east = __shfl_down(c.x, 1);
+      float4 o;
+      o.x = 0.25f * ((north.x + south.x) + (west + c.y));
+      o.y = 0.25f * ((north.y + south.y) + (c.x + c.z));
+      o.z = 0.25f * ((north.z + south.z) + (c.y + c.w));
+      o.w = 0.25f * ((north.w + south.w) + (c.z + east));
+      if (first_col) o.x = c.x;                           // the ring keeps its value
+      if (last_col) o.w = c.w;
+      const int32_t g = g0 + (int32_t)i;
+      const bool interior_row = g >= 1 && g <= (int32_t)n - 2;
+      cur[i] = interior_row ? o : c;
+      north = c;
+    }
+  }
+
+  // store what is still exact: not the four columns next to a window edge (an edge that is
+  // the grid's own boundary loses nothing), rows JB_ROWS of this window that are interior
+  const bool left_ok = tc == 0u || lane >= 1u;
+  const bool right_ok = c0 + 4u <= w0 + JB_WIN - JB_HALO || w0 + JB_WIN >= n;
+  if (left_ok && right_ok) {
+#pragma unroll
+    for (uint32_t i = T; i < T + JB_ROWS; ++i) {
+      const int32_t g = g0 + (int32_t)i;
+      if (g <= (int32_t)n - 2) *reinterpret_cast<float4*>(v + (size_t)g * n + c0) = cur[i];
+    }
   }
 }
 
@@ -83,8 +118,11 @@ __global__ __launch_bounds__(JB_THREADS) void jacobi_sweep_v4(const float* __res
 __global__ __launch_bounds__(JB_THREADS) void jacobi_sweep_v1(const float* __restrict__ u,
                                                              float* __restrict__ v, uint32_t n,
                                                              uint32_t tiles_x, uint32_t tiles_y) {
-  uint32_t tx, ty;
-  if (!tile_of_block(tiles_x, tiles_y, &tx, &ty)) return;
+  const uint32_t total = tiles_x * tiles_y;
+  const uint32_t per_xcd = (total + 7u) / 8u;
+  const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || tile >= total) return;
+  const uint32_t tx = tile % tiles_x, ty = tile / tiles_x;
   const uint32_t c = tx * JB_THREADS + threadIdx.x;
   const uint32_t r0 = 1u + ty * JB_ROWS;
   if (c == 0u || c + 1u >= n) return;
@@ -110,11 +148,51 @@ struct Geometry {
 Geometry geometry(uint32_t n) {
   Geometry g;
   g.vec4 = (n % 4u) == 0u;
-  g.tiles_x = g.vec4 ? (n + JB_COLS_V4 - 1u) / JB_COLS_V4 : (n + JB_THREADS - 1u) / JB_THREADS;
-  g.tiles_y = (n - 2u + JB_ROWS - 1u) / JB_ROWS;
-  const uint32_t total = g.tiles_x * g.tiles_y;
-  g.blocks = ((total + 7u) / 8u) * 8u;   // whole rounds over the 8 XCDs
+  if (g.vec4) {
+    // windows step by 248 columns; the first one also covers columns 1..3 next to the ring
+    const uint32_t interior_last = n - 2u;
+    g.tiles_x = interior_last <= JB_WIN - JB_HALO - 1u
+                    ? 1u
+                    : 1u + (interior_last - (JB_WIN - JB_HALO - 1u) + JB_STEP - 1u) / JB_STEP;
+    g.tiles_y = (n - 2u + JB_ROWS - 1u) / JB_ROWS;
+    const uint32_t groups = (g.tiles_x * g.tiles_y + 3u) / 4u;       // four windows per workgroup
+    g.blocks = ((groups + 7u) / 8u) * 8u;                             // whole rounds over the 8 XCDs
+  } else {
+    g.tiles_x = (n + JB_THREADS - 1u) / JB_THREADS;
+    g.tiles_y = (n - 2u + JB_ROWS - 1u) / JB_ROWS;
+    g.blocks = ((g.tiles_x * g.tiles_y + 7u) / 8u) * 8u;
+  }
   return g;
+}
+
+// Split `iters` sweeps into launches of 1..4 sweeps such that the number of launches has the
+// parity of iters: the buffers swap once per launch and the result must end in buffer iters % 2.
+uint32_t plan_launches(uint32_t iters, uint32_t* plan, uint32_t cap) {
+  uint32_t n = 0;
+  uint32_t left = iters;
+  while (left > 0u && n < cap) {
+    const uint32_t t = left >= JB_MAXT ? JB_MAXT : left;
+    plan[n++] = t;
+    left -= t;
+  }
+  if (n % 2u != iters % 2u) {
+    // split one launch of >= 2 sweeps in two (exists: otherwise every launch is one sweep and
+    // the parities already agree)
+    for (uint32_t i = n; i-- > 0u;)
+      if (plan[i] >= 2u && n < cap) {
+        const uint32_t a = plan[i] / 2u;
+        plan[n++] = plan[i] - a;
+        plan[i] = a;
+        break;
+      }
+  }
+  return n;
+}
+
+template <uint32_t T>
+void launch_sweeps(hipStream_t st, const Geometry& g, const float* src, float* dst, uint32_t n) {
+  hipLaunchKernelGGL(jacobi_sweeps<T>, dim3(g.blocks), dim3(JB_THREADS), 0, st, src, dst, n, g.tiles_x,
+                     g.tiles_y);
 }
 
 }  // namespace
@@ -133,6 +211,19 @@ int mgb_jacobi_probe(uint32_t n, uint32_t iters, uint64_t* mem_bytes, mgb_dim3* 
   return MGB_OK;
 }
 
+uint32_t mgb_jacobi_launch_count(uint32_t n, uint32_t iters) {
+  if (n < 3u || n > 65536u) return 0u;
+  if (n % 4u != 0u) return iters;
+  uint32_t total = 0, done = 0;
+  while (done < iters) {
+    uint32_t plan[64];
+    const uint32_t chunk = iters - done > 128u ? 128u : iters - done;
+    total += plan_launches(chunk, plan, 64u);
+    done += chunk;
+  }
+  return total;
+}
+
 int mgb_jacobi_enqueue(void* stream, float* u0, float* u1, uint32_t n, uint32_t iters) {
   if (!u0 || !u1 || u0 == u1) return MGB_E_INVAL;
   if (n < 3u || n > 65536u) return MGB_E_UNSUPPORTED;
@@ -141,18 +232,35 @@ int mgb_jacobi_enqueue(void* stream, float* u0, float* u1, uint32_t n, uint32_t 
   hipStream_t st = (hipStream_t)stream;
   const float* src = u0;
   float* dst = u1;
-  for (uint32_t t = 0; t < iters; ++t) {
-    if (g.vec4)
-      hipLaunchKernelGGL(jacobi_sweep_v4, dim3(g.blocks), dim3(JB_THREADS), 0, st, src, dst, n,
-                         g.tiles_x, g.tiles_y);
-    else
+  if (!g.vec4) {
+    for (uint32_t t = 0; t < iters; ++t) {
       hipLaunchKernelGGL(jacobi_sweep_v1, dim3(g.blocks), dim3(JB_THREADS), 0, st, src, dst, n,
                          g.tiles_x, g.tiles_y);
-    float* tmp = const_cast<float*>(src);
-    src = dst;
-    dst = tmp;
+      float* tmp = const_cast<float*>(src);
+      src = dst;
+      dst = tmp;
+    }
+    return mgb_check_launch("jacobi_sweep");
   }
-  return mgb_check_launch("jacobi_sweep");
+  uint32_t done = 0;
+  while (done < iters) {
+    uint32_t plan[64];
+    const uint32_t chunk = iters - done > 128u ? 128u : iters - done;   // even chunks keep the parity rule
+    const uint32_t np = plan_launches(chunk, plan, 64u);
+    for (uint32_t i = 0; i < np; ++i) {
+      switch (plan[i]) {
+        case 1: launch_sweeps<1>(st, g, src, dst, n); break;
+        case 2: launch_sweeps<2>(st, g, src, dst, n); break;
+        case 3: launch_sweeps<3>(st, g, src, dst, n); break;
+        default: launch_sweeps<4>(st, g, src, dst, n); break;
+      }
+      float* tmp = const_cast<float*>(src);
+      src = dst;
+      dst = tmp;
+    }
+    done += chunk;
+  }
+  return mgb_check_launch("jacobi_sweeps");
 }
 
 }  // extern "C"

@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "mgb.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(mgb_[a-z0-9_]+)\s*\(", hdr))
-    assert len(declared) >= 28
+    assert len(declared) >= 29
     for name in declared:
         assert hasattr(mgb.lib, name), name
     assert declared == set(mgb.EXPORTS)
@@ -93,6 +93,15 @@ def test_stuck_task_does_not_block_tasks_that_fit():
         rc, pl = s2.probe(10 + i, 5, (8, 1, 1), (256, 1, 1))
         assert rc == mgb.MGB_OK and pl.granule_mask == 1 << (16 + i)
         assert list(pl.cu_mask) == [0] * (4 + i // 4) + [0xFF << (8 * (i % 4))] + [0] * (3 - i // 4)
+
+
+def test_jacobi_launch_plan_keeps_buffer_parity():
+    # the result must end in buffer iters % 2, so the number of (fused) launches has that parity
+    for it in list(range(0, 40)) + [100, 127, 128, 129, 1000]:
+        c = mgb.mgb_jacobi_launch_count(4096, it)
+        assert c % 2 == it % 2 and (it + 3) // 4 <= c <= (it + 3) // 4 + (it // 128 + 1)
+        assert mgb.mgb_jacobi_launch_count(77, it) == it             # n % 4 != 0: one sweep per launch
+    assert mgb.mgb_jacobi_launch_count(4096, 100) == 26 and mgb.mgb_jacobi_launch_count(2, 5) == 0
 
 
 def test_resident_task_limit():

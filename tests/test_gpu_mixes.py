@@ -33,8 +33,8 @@ def test_mix16_full_size_outputs_and_decisions():
     dec = assert_trace_matches_replay(s.desc, trace)
     check_ledger_invariants(s.desc, trace)
     assert (dec["kind"] == oracle.D_ADMIT).sum() == 16
-    # demand the probes carried: GEMM 4096^3 = the whole device, Jacobi 4096^2 and BFS 2^20 = half
-    want = {"gemm_f32": 32, "jacobi": 16, "bfs": 16}
+    # demand the probes carried: GEMM 4096^3 and Jacobi 4096^2 = the whole device, BFS 2^20 = half
+    want = {"gemm_f32": 32, "jacobi": 32, "bfs": 16}
     for r, t in zip(rec, tasks):
         assert r["granules"] == want[t.spec.kind]
     assert s.destroy() == 0
