@@ -26,6 +26,16 @@ def parse():
     return ap.parse_args()
 
 
+# HBM-side bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/mix16_hbm_traffic.md (each counter scaled by its reading for the 1 GiB stream copy).
+# Valid for the kernels as they stand in csrc/ and for the Mix-16 task shapes only.
+MEASURED_TRAFFIC_BYTES = {
+    ("mix16", "gemm_f32_kernel"): 881.9e6,     # per 4096^3 launch
+    ("mix16", "jacobi_sweeps"): 138.1e6,       # per launch (24 four-sweep + 2 two-sweep launches per task)
+    ("mix16", "bfs_level"): 20.6e6,            # per level launch, averaged over the 12 launches of a traversal
+}
+
+
 def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
@@ -164,7 +174,7 @@ def main():
         work = k["bytes"] / 1e9 if bound == "hbm" else k["flops"] / 1e12
         ach = work / (k["ms"] / 1e3)
         return dict(kernel=name, bound=bound, achieved=round(ach, 2), peak=peak, unit=unit,
-                    frac=round(ach / peak, 4), traffic=None,
+                    frac=round(ach / peak, 4), traffic=MEASURED_TRAFFIC_BYTES.get((args.mix, name)),
                     avg_launch_us=round(1e3 * k["ms"] / k["launches"], 2), launches=k["launches"])
 
     out = dict(metric="aggregate tasks/s through probe+admit+partition+launch+complete (with mean turnaround, max slowdown)",
