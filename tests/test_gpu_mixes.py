@@ -85,3 +85,83 @@ def test_mixed128_reduced_sizes():
     grids = sorted(int(r["grid"][0]) for r in trace if r["kind"] == mgb.MGB_EV_PROBE)
     assert grids[0] == 8 and grids[-1] > grids[0]     # a range of small grids that share the device
     assert s.destroy() == 0
+
+
+def test_pressure32_full_size_sampled():
+    """16 fp32 GEMM 32768^3 (12 GiB each) + 16 Jacobi 16384^2 x50 (2 GiB each), all at t = 0, cap =
+    summed footprints / 1.5 so that admission has to queue.  Inputs of this size are drawn on the
+    device (seeded torch generator); outputs are checked on sampled entries that the serial checker
+    recomputes one by one from rows / columns / patches copied back to the host."""
+    import ctypes as C
+    spec = W.pressure32(seed=5)
+    free_b, total_b = torch.cuda.mem_get_info()
+    need = sum(16 * 3 * 32768 * 32768 * 4 for _ in (0,)) + 16 * 2 * 16384 * 16384 * 4
+    if free_b < need + (8 << 30):
+        pytest.skip("device has less free memory than the 224 GiB the mix needs")
+    gen = torch.Generator(device="cuda:0")
+    rng = np.random.default_rng(7)
+    tasks, checks = [], {}
+    P = lambda t: C.c_void_p(t.data_ptr())
+    for t in spec["tasks"]:
+        gen.manual_seed(t.seed % (2 ** 63))
+        if t.kind == "gemm_f32":
+            n = t.params["n"]
+            A = torch.randn(n, n, device="cuda:0", generator=gen)
+            B = torch.randn(n, n, device="cuda:0", generator=gen)
+            Cc = torch.empty(n, n, device="cuda:0")
+            probe = mgb.probe_of(mgb.mgb_gemm_f32_probe, n, n, n)
+            assert probe[0] == 12 * 2 ** 30
+            fn = (lambda A, B, Cc, n: lambda st: mgb.mgb_gemm_f32_enqueue(st, P(A), P(B), P(Cc), n, n, n))(A, B, Cc, n)
+            rows, cols = rng.integers(0, n, 24), rng.integers(0, n, 24)
+            rows[:2], cols[:2] = [0, n - 1], [n - 1, 0]
+            checks[t.task_id] = ("gemm", A[rows].cpu().numpy(), B[:, cols].contiguous().cpu().numpy(), rows, cols)
+            tasks.append(harness.Task(t, dict(A=A, B=B, C=Cc), probe, fn, "gemm_f32_kernel", 1))
+        else:
+            n, it = t.params["n"], t.params["iters"]
+            u0 = torch.rand(n, n, device="cuda:0", generator=gen)
+            u0[0, :] = 0
+            u0[-1, :] = 0
+            u0[:, 0] = 0
+            u0[:, -1] = 0
+            u1 = u0.clone()
+            probe = mgb.probe_of(mgb.mgb_jacobi_probe, n, it)
+            assert probe[0] == 2 * 2 ** 30
+            fn = (lambda u0, u1, n, it: lambda st: mgb.mgb_jacobi_enqueue(st, P(u0), P(u1), n, it))(u0, u1, n, it)
+            # a cell after `it` sweeps depends on the initial cells within distance `it`: keep those patches
+            pts = [(1, 1), (n - 2, n - 2), (1, n // 2), (int(rng.integers(60, n - 60)), int(rng.integers(60, n - 60))),
+                   (int(rng.integers(1, n - 1)), int(rng.integers(1, n - 1)))]
+            patches = []
+            side = min(n, 2 * it + 3)                 # square window, shifted (not clipped) at the grid's rim
+            for (r, c) in pts:
+                r0 = min(max(0, r - it - 1), n - side)
+                c0 = min(max(0, c - it - 1), n - side)
+                patches.append((r, c, r0, c0, u0[r0:r0 + side, c0:c0 + side].cpu().numpy().copy()))
+            checks[t.task_id] = ("jacobi", patches, it)
+            tasks.append(harness.Task(t, dict(u0=u0, u1=u1), probe, fn, "jacobi_sweeps", 1))
+    s = mgb.Sched(mem_cap_bytes=spec["cap_bytes"])
+    rec, makespan = harness.run_mix(s, tasks, use_arrivals=False)
+    for t in tasks:
+        kind = checks[t.spec.task_id][0]
+        if kind == "gemm":
+            _, a_rows, b_cols, rows, cols = checks[t.spec.task_id]
+            got = t.tensors["C"][rows, cols].cpu().numpy().astype(np.float64)
+            idx = np.arange(len(rows), dtype=np.uint32)
+            ref, den = oracle.gemm_f32_entries(a_rows, b_cols, idx, idx)
+            assert (np.abs(got - ref) / den).max() <= 1e-4, t.spec.task_id
+        else:
+            _, patches, it = checks[t.spec.task_id]
+            res = t.tensors["u0"] if it % 2 == 0 else t.tensors["u1"]
+            for (r, c, r0, c0, patch) in patches:
+                # the window's rim is held fixed by the checker, which is only true where it is the grid's
+                # own ring; elsewhere the rim is at least it + 1 cells from (r, c), out of reach in `it` sweeps
+                want = oracle.jacobi_f32(np.ascontiguousarray(patch), it)[r - r0, c - c0]
+                assert float(res[r, c]) == float(want), (t.spec.task_id, r, c)
+    trace = s.trace()
+    dec = assert_trace_matches_replay(s.desc, trace)
+    check_ledger_invariants(s.desc, trace)
+    assert (dec["kind"] == oracle.D_WAIT).sum() > 0 and (dec["kind"] == oracle.D_ADMIT).sum() == 32
+    assert trace["free_bytes"].min() >= 0 and trace["free_bytes"].max() <= spec["cap_bytes"]
+    # worst wait: every GEMM (whole device) runs alone, so the last GEMM admitted waited for the 15 before it
+    waits = [r["admit"] - r["probe"] for r in rec]
+    assert max(waits) > 0
+    assert s.destroy() == 0
