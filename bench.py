@@ -235,17 +235,19 @@ def main():
                                mean_turnaround_ms=round(sum(x["mean_turnaround_ms"] for x in b) / 3, 3),
                                serialised_tasks_per_s=round(sum(x["tasks_per_s"] for x in bs) / 3, 2),
                                serialised_mean_turnaround_ms=round(sum(x["mean_turnaround_ms"] for x in bs) / 3, 3))
-        # the other policies on the same mix: Alg. 3 analogue (overlapping masks), FIFO queue, and
+        # the other policies on the same mix: Alg. 3 analogue (overlapping masks), FIFO queue,
         # HARD with one workgroup per CU as the residency limit ("spread": a task gets as many
-        # CUs as it has workgroups, so only tasks that cannot fill the device share it)
+        # CUs as it has workgroups, so only tasks that cannot fill the device share it), and the
+        # memory-blind CG baseline of Sec. IV at four jobs per device
         sched.destroy()
         sched = None
         sweep = {}
-        for name, pol2, q2, wgcu in (("soft_backfill", mgb.MGB_POLICY_SOFT, mgb.MGB_QUEUE_BACKFILL, 32),
-                                     ("hard_fifo", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_FIFO, 32),
-                                     ("hard_spread", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_BACKFILL, 1)):
+        for name, pol2, q2, wgcu, ratio in (("soft_backfill", mgb.MGB_POLICY_SOFT, mgb.MGB_QUEUE_BACKFILL, 32, 16),
+                                            ("hard_fifo", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_FIFO, 32, 16),
+                                            ("hard_spread", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_BACKFILL, 1, 16),
+                                            ("cg_ratio4", mgb.MGB_POLICY_CG, mgb.MGB_QUEUE_BACKFILL, 32, 4)):
             log("policy sweep: " + name)
-            s2 = mgb.Sched(policy=pol2, queue_mode=q2, mem_cap_bytes=cap, max_wg_per_cu=wgcu)
+            s2 = mgb.Sched(policy=pol2, queue_mode=q2, mem_cap_bytes=cap, max_wg_per_cu=wgcu, max_running=ratio)
             harness.run_mix(s2, tasks)
             a = [harness.summarize(*harness.run_mix(s2, tasks)) for _ in range(3)]
             harness.run_mix(s2, tasks, use_arrivals=False)

@@ -44,11 +44,15 @@ extern "C" {
 #define MGB_E_BUSY (-5)          /* destroy with tasks in flight            */
 #define MGB_E_BACKEND (-6)       /* HIP call failed; see mgb_last_error     */
 #define MGB_E_UNSUPPORTED (-7)   /* shape outside what a kernel accepts     */
+#define MGB_E_OOM (-8)           /* CG policy: the task would have run out of memory */
 
 /* ---- policies (Sec. III-B and Sec. IV) --------------------------------- */
 #define MGB_POLICY_HARD 0    /* Algorithm 2: memory and compute both hard   */
 #define MGB_POLICY_SOFT 1    /* Algorithm 3: memory hard, compute by load   */
 #define MGB_POLICY_SERIAL 2  /* single-assignment baseline: one task owns the device */
+#define MGB_POLICY_CG 3      /* core-to-GPU-ratio baseline: up to max_running tasks share the
+                                whole device, memory is not consulted; a task that does not
+                                fit when let in is rejected with MGB_E_OOM (counted, not run) */
 #define MGB_QUEUE_BACKFILL 0 /* on release retry every waiter in arrival order */
 #define MGB_QUEUE_FIFO 1     /* stop at the first waiter that does not fit  */
 #define MGB_BACKEND_NULL 0   /* bookkeeping only, no HIP call (host tests)  */

@@ -159,7 +159,7 @@ DECISION_DT = np.dtype([("in_index", "<u4"), ("kind", "<u4"), ("ticket", "<u8"),
 
 IN_PROBE, IN_COMPLETE, IN_CANCEL = 0, 1, 2
 D_ADMIT, D_WAIT, D_REJECT, D_RELEASE, D_CANCELLED = 1, 2, 3, 4, 5
-POL_HARD, POL_SOFT, POL_SERIAL = 0, 1, 2
+POL_HARD, POL_SOFT, POL_SERIAL, POL_CG = 0, 1, 2, 3
 Q_BACKFILL, Q_FIFO = 0, 1
 
 

@@ -24,6 +24,11 @@
 //     are added to the load of those granules;
 //   * at most max_running tasks are resident at a time when that field is
 //     non-zero (every resident task holds one hardware queue);
+//   * CG (the core-to-GPU-ratio baseline of Sec. IV): up to max_running tasks
+//     share the whole device and memory is NOT consulted; a task whose
+//     footprint does not fit at the moment it is let in is the job that would
+//     have died of an out-of-memory error: it is rejected with E_OOM and
+//     counted, never run;
 //   * SERIAL (single-assignment baseline, Sec. IV): one task owns the whole
 //     device at a time;
 //   * on every release the waiting tasks are retried in arrival order.
@@ -36,9 +41,9 @@ namespace {
 
 enum { IN_PROBE = 0, IN_COMPLETE = 1, IN_CANCEL = 2 };
 enum { D_ADMIT = 1, D_WAIT = 2, D_REJECT = 3, D_RELEASE = 4, D_CANCELLED = 5 };
-enum { POL_HARD = 0, POL_SOFT = 1, POL_SERIAL = 2 };
+enum { POL_HARD = 0, POL_SOFT = 1, POL_SERIAL = 2, POL_CG = 3 };
 enum { Q_BACKFILL = 0, Q_FIFO = 1 };
-enum { E_INVAL = -1, E_TOO_BIG = -2, E_UNKNOWN_TICKET = -3, E_BAD_STATE = -4 };
+enum { E_INVAL = -1, E_TOO_BIG = -2, E_UNKNOWN_TICKET = -3, E_BAD_STATE = -4, E_OOM = -8 };
 
 struct Task {
   uint64_t ticket, task_id, mem, waves;
@@ -136,7 +141,18 @@ int64_t orc_sched_replay(const orc_device* dev, const orc_input* in, uint64_t n_
         }
   };
   uint32_t n_running = 0;
+  bool crashed = false;                  // set by try_admit under CG when the task would have run out of memory
   auto try_admit = [&](Task& t) -> bool {
+    crashed = false;
+    if (dev->policy == POL_CG) {
+      if (dev->max_running != 0 && n_running >= dev->max_running) return false;
+      if (t.mem > free_bytes) { crashed = true; return false; }
+      free_bytes -= t.mem;
+      t.granted = all;
+      t.running = true;
+      ++n_running;
+      return true;
+    }
     if (t.mem > free_bytes) return false;
     if (dev->max_running != 0 && n_running >= dev->max_running) return false;
     uint32_t b = 1;                      // block size: demand rounded up to a power of two
@@ -184,6 +200,11 @@ int64_t orc_sched_replay(const orc_device* dev, const orc_input* in, uint64_t n_
       if (try_admit(*t)) {
         waitq.erase(waitq.begin() + i);
         emit(idx, D_ADMIT, t, t->granted, 0, 0);
+      } else if (crashed) {
+        emit(idx, D_REJECT, t, 0, E_OOM, 0);
+        uint64_t ticket = t->ticket;
+        waitq.erase(waitq.begin() + i);
+        live.erase(std::find_if(live.begin(), live.end(), [&](const Task& x) { return x.ticket == ticket; }));
       } else if (dev->queue_mode == Q_FIFO) {
         break;
       } else {
@@ -211,6 +232,9 @@ int64_t orc_sched_replay(const orc_device* dev, const orc_input* in, uint64_t n_
       bool blocked_by_queue = dev->queue_mode == Q_FIFO && !waitq.empty();
       if (!blocked_by_queue && try_admit(ref)) {
         emit(idx, D_ADMIT, &ref, ref.granted, 0, 0);
+      } else if (!blocked_by_queue && crashed) {
+        emit(idx, D_REJECT, &ref, 0, E_OOM, 0);
+        live.pop_back();
       } else {
         waitq.push_back(ref.ticket);
         emit(idx, D_WAIT, &ref, 0, 0, 0);
@@ -220,7 +244,9 @@ int64_t orc_sched_replay(const orc_device* dev, const orc_input* in, uint64_t n_
       if (!t) { emit(idx, D_REJECT, nullptr, 0, E_UNKNOWN_TICKET, 0); continue; }
       if (!t->running) { emit(idx, D_REJECT, t, 0, E_BAD_STATE, 0); continue; }
       free_bytes += t->mem;
-      if (dev->policy == POL_SOFT) {
+      if (dev->policy == POL_CG) {
+        // nothing to give back but the memory: the device is shared as a whole
+      } else if (dev->policy == POL_SOFT) {
         for (uint32_t g = 0; g < G; ++g)
           if (t->granted >> g & 1u) load[g] -= t->share;
       } else {

@@ -23,8 +23,8 @@ lib = C.CDLL(LIB_PATH)
 
 MGB_OK, MGB_WAIT, MGB_TIMEOUT = 0, 1, 2
 MGB_E_INVAL, MGB_E_TOO_BIG, MGB_E_UNKNOWN_TICKET, MGB_E_BAD_STATE = -1, -2, -3, -4
-MGB_E_BUSY, MGB_E_BACKEND, MGB_E_UNSUPPORTED = -5, -6, -7
-MGB_POLICY_HARD, MGB_POLICY_SOFT, MGB_POLICY_SERIAL = 0, 1, 2
+MGB_E_BUSY, MGB_E_BACKEND, MGB_E_UNSUPPORTED, MGB_E_OOM = -5, -6, -7, -8
+MGB_POLICY_HARD, MGB_POLICY_SOFT, MGB_POLICY_SERIAL, MGB_POLICY_CG = 0, 1, 2, 3
 MGB_QUEUE_BACKFILL, MGB_QUEUE_FIFO = 0, 1
 MGB_BACKEND_NULL, MGB_BACKEND_HIP = 0, 1
 MGB_EV_PROBE, MGB_EV_COMPLETE, MGB_EV_CANCEL = 0, 1, 2

@@ -82,6 +82,8 @@ struct mgb_sched {
   std::deque<uint64_t> waitq;                 // tickets in arrival order
   uint64_t next_ticket = 0;
   uint32_t n_running_now = 0;
+  bool oom = false;                          // try_admit: CG task that would have run out of memory
+  std::vector<uint64_t> crashed;             // tickets rejected while queued, until their waiter collects them
   std::vector<mgb_trace_rec> trace;
   // backend: idle masked streams (mask, stream, when last used), idle timing events
   struct IdleStream { uint32_t mask; hipStream_t stream; uint64_t stamp; };
@@ -131,6 +133,21 @@ struct mgb_sched {
   // Compute is granted in buddy blocks: demand rounded up to a power of two b, block = b
   // granules starting at a multiple of b.
   bool try_admit(Task& t) {
+    oom = false;
+    if (d.policy == MGB_POLICY_CG) {
+      // ratio-limited packing that never looks at memory (Sec. IV): the task that does not fit
+      // when it is let in is the one that would have crashed; it is reported, not run
+      if (d.max_running != 0u && n_running_now >= d.max_running) return false;
+      if (t.mem > free_bytes) {
+        oom = true;
+        return false;
+      }
+      free_bytes -= t.mem;
+      t.granted = all_mask;
+      t.state = State::Running;
+      ++n_running_now;
+      return true;
+    }
     if (t.mem > free_bytes) return false;
     if (d.max_running != 0u && n_running_now >= d.max_running) return false;
     uint32_t b = 1;
@@ -173,6 +190,7 @@ struct mgb_sched {
   void release(Task& t) {
     free_bytes += t.mem;
     --n_running_now;
+    if (d.policy == MGB_POLICY_CG) return;
     if (d.policy == MGB_POLICY_SOFT) {
       for (uint32_t g = 0; g < G; ++g)
         if (t.granted >> g & 1u) load[g] -= t.share;
@@ -190,6 +208,12 @@ struct mgb_sched {
         waitq.erase(waitq.begin() + (long)i);
         log(MGB_EV_ADMIT, &t, 0, 0, 0, {}, {}, t.granted, 0, cause);
         any = true;
+      } else if (oom) {
+        log(MGB_EV_REJECT, &t, 0, 0, 0, {}, {}, 0, MGB_E_OOM, cause);
+        crashed.push_back(t.ticket);
+        tasks.erase(waitq[i]);
+        waitq.erase(waitq.begin() + (long)i);
+        any = true;                                   // its waiter must wake up and collect the error
       } else if (d.queue_mode == MGB_QUEUE_FIFO) {
         break;
       } else {
@@ -298,7 +322,8 @@ int mgb_sched_create(const mgb_device_desc* desc, mgb_sched** out) {
   if (d.n_cu == 0 || d.granule_cus == 0 || d.n_cu % d.granule_cus != 0) return MGB_E_INVAL;
   if (d.n_cu > 256 || d.n_cu / d.granule_cus > 32) return MGB_E_INVAL;
   if (d.wave_size == 0 || d.max_waves_per_cu == 0 || d.max_wg_per_cu == 0) return MGB_E_INVAL;
-  if (d.policy > MGB_POLICY_SERIAL || d.queue_mode > MGB_QUEUE_FIFO) return MGB_E_INVAL;
+  if (d.policy > MGB_POLICY_CG || d.queue_mode > MGB_QUEUE_FIFO) return MGB_E_INVAL;
+  if (d.policy == MGB_POLICY_CG && d.max_running == 0u) return MGB_E_INVAL;   // CG is defined by its ratio
   if (d.backend > MGB_BACKEND_HIP) return MGB_E_INVAL;
   if (d.backend == MGB_BACKEND_HIP) {
     // a mask must keep at least one CU in each of the 8 XCDs
@@ -399,6 +424,11 @@ int mgb_task_probe(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 
     s->log(MGB_EV_ADMIT, &ref, 0, 0, 0, {}, {}, ref.granted, 0, cause);
     return s->fill(ref, out);
   }
+  if (!behind_queue && s->oom) {
+    s->log(MGB_EV_REJECT, &ref, 0, 0, 0, {}, {}, 0, MGB_E_OOM, cause);
+    s->tasks.erase(ref.ticket);
+    return MGB_E_OOM;
+  }
   s->waitq.push_back(ref.ticket);
   s->log(MGB_EV_QUEUED, &ref, 0, 0, 0, {}, {}, 0, 0, cause);
   out->ticket = ref.ticket;
@@ -413,6 +443,13 @@ int mgb_task_wait(mgb_sched* s, uint64_t ticket, int64_t timeout_ns, mgb_placeme
     auto it = s->tasks.find(ticket);
     return it == s->tasks.end() || it->second.state == State::Running;
   };
+  auto collect_crash = [&]() {
+    auto c = std::find(s->crashed.begin(), s->crashed.end(), ticket);
+    if (c == s->crashed.end()) return false;
+    s->crashed.erase(c);
+    return true;
+  };
+  if (collect_crash()) return MGB_E_OOM;
   if (s->tasks.find(ticket) == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;
   if (timeout_ns < 0) {
     s->cv.wait(lk, admitted);
@@ -420,7 +457,7 @@ int mgb_task_wait(mgb_sched* s, uint64_t ticket, int64_t timeout_ns, mgb_placeme
     return MGB_TIMEOUT;
   }
   auto it = s->tasks.find(ticket);
-  if (it == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;  // cancelled meanwhile
+  if (it == s->tasks.end()) return collect_crash() ? MGB_E_OOM : MGB_E_UNKNOWN_TICKET;  // rejected / cancelled meanwhile
   return s->fill(it->second, out);
 }
 

@@ -120,14 +120,25 @@ def run_mix(sched, tasks, use_arrivals=True, time_scale=1.0, workers=None):
         for i, t in enumerate(tasks):
             rec[i]["arrival"] = 0.0
             rc, pl = sched.probe(t.spec.task_id, t.mem, t.grid, t.block)
-            mgb.check(rc, "mgb_task_probe")
             rec[i]["probe"] = time.perf_counter() - t0
+            if rc != mgb.MGB_E_OOM:
+                mgb.check(rc, "mgb_task_probe")
             placements[i] = (rc, pl)
+
+    def crashed(i):
+        # memory-blind packing (the CG baseline) let the job in where it could not fit: the job is
+        # lost, which is the failure the paper's Sec. V-B counts
+        rec[i]["crashed"] = True
+        rec[i]["admit"] = rec[i]["done"] = time.perf_counter() - t0
+        rec[i]["gpu_ms"] = 0.0
+        rec[i]["granules"] = 0
 
     def run_one(i):
         t = tasks[i]
         if pre_probed:
             rc, pl = placements[i]
+            if rc == mgb.MGB_E_OOM:
+                return crashed(i)
         else:
             if use_arrivals:
                 due = t0 + t.spec.arrival_s * time_scale
@@ -140,10 +151,14 @@ def run_mix(sched, tasks, use_arrivals=True, time_scale=1.0, workers=None):
             else:
                 rec[i]["arrival"] = 0.0
             rc, pl = sched.probe(t.spec.task_id, t.mem, t.grid, t.block)
-            mgb.check(rc, "mgb_task_probe")
             rec[i]["probe"] = time.perf_counter() - t0
+            if rc == mgb.MGB_E_OOM:
+                return crashed(i)
+            mgb.check(rc, "mgb_task_probe")
         if rc == mgb.MGB_WAIT:
             rc, pl = sched.wait(pl.ticket)
+            if rc == mgb.MGB_E_OOM:
+                return crashed(i)
             mgb.check(rc, "mgb_task_wait")
         rec[i]["admit"] = time.perf_counter() - t0
         rec[i]["granules"] = pl.n_granules
@@ -182,10 +197,15 @@ def run_mix(sched, tasks, use_arrivals=True, time_scale=1.0, workers=None):
 
 
 def summarize(rec, makespan):
+    n_crashed = sum(1 for r in rec if r.get("crashed"))
+    rec = [r for r in rec if not r.get("crashed")]       # only finished jobs count as throughput
     n = len(rec)
+    if n == 0:
+        return dict(tasks=0, crashed=n_crashed, tasks_per_s=0.0, mean_turnaround_ms=0.0, max_turnaround_ms=0.0,
+                    makespan_ms=1e3 * makespan, mean_wait_ms=0.0)
     turn = [r["done"] - r["arrival"] for r in rec]
     last = max(r["done"] for r in rec)
     first = min(r["arrival"] for r in rec)
-    return dict(tasks=n, tasks_per_s=n / (last - first), mean_turnaround_ms=1e3 * sum(turn) / n,
+    return dict(tasks=n, crashed=n_crashed, tasks_per_s=n / (last - first), mean_turnaround_ms=1e3 * sum(turn) / n,
                 max_turnaround_ms=1e3 * max(turn), makespan_ms=1e3 * makespan,
                 mean_wait_ms=1e3 * sum(r["admit"] - r["probe"] for r in rec) / n)

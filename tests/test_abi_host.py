@@ -162,6 +162,38 @@ def test_library_decisions_equal_replay_on_random_streams(policy, mode, seed):
     assert s.destroy() == mgb.MGB_OK
 
 
+def test_cg_policy_equals_replay_and_wakes_the_waiter_of_a_dead_job():
+    h = C.c_void_p()
+    d = mgb.default_desc(backend=mgb.MGB_BACKEND_NULL, policy=mgb.MGB_POLICY_CG, max_running=0)
+    assert mgb.mgb_sched_create(C.byref(d), C.byref(h)) == mgb.MGB_E_INVAL     # CG needs its ratio
+    s = _null(mem_cap_bytes=1000, policy=mgb.MGB_POLICY_CG, max_running=2)
+    g, b = (4, 1, 1), (64, 1, 1)
+    rc, p1 = s.probe(1, 600, g, b)
+    assert rc == mgb.MGB_OK and p1.granule_mask == 0xFFFFFFFF
+    assert s.probe(2, 600, g, b)[0] == mgb.MGB_E_OOM                           # dies on arrival
+    rc, p3 = s.probe(3, 300, g, b)
+    assert rc == mgb.MGB_OK
+    rc, p4 = s.probe(4, 500, g, b)
+    assert rc == mgb.MGB_WAIT
+    got = []
+    th = threading.Thread(target=lambda: got.append(s.wait(p4.ticket)[0]))
+    th.start()
+    assert s.complete(p3.ticket) == mgb.MGB_OK                                 # slot opens, 400 < 500
+    th.join(10)
+    assert got == [mgb.MGB_E_OOM]
+    assert s.wait(p4.ticket)[0] == mgb.MGB_E_UNKNOWN_TICKET                    # collected once
+    st = s.stats()
+    assert (st.n_running, st.n_waiting, st.free_bytes) == (1, 0, 400)
+    assert s.complete(p1.ticket) == mgb.MGB_OK
+    assert_trace_matches_replay(s.desc, s.trace())
+    for seed, mode in ((0, mgb.MGB_QUEUE_BACKFILL), (1, mgb.MGB_QUEUE_FIFO)):
+        s = _null(mem_cap_bytes=10_000, policy=mgb.MGB_POLICY_CG, queue_mode=mode, max_running=4)
+        _random_storm(s, np.random.default_rng(seed), 400)
+        dec = assert_trace_matches_replay(s.desc, s.trace())
+        assert ((dec["kind"] == oracle.D_REJECT) & (dec["code"] == mgb.MGB_E_OOM)).sum() > 3
+        assert s.stats().free_bytes == 10_000 and s.stats().n_running == 0
+
+
 def test_small_device_and_other_granule_shapes_equal_replay():
     for n_cu, g in ((32, 8), (64, 2), (24, 1), (256, 64)):
         s = _null(mem_cap_bytes=5000, n_cu=n_cu, granule_cus=g, max_wg_per_cu=8, max_waves_per_cu=40)

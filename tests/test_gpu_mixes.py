@@ -60,6 +60,33 @@ def test_mix16_batch_at_t0_all_policies(policy):
     assert s.destroy() == 0
 
 
+def test_memory_blind_ratio_packing_loses_jobs_that_admission_control_finishes():
+    # Sec. V-B's contrast on a memory-tight mix: packing by a fixed jobs-per-device ratio without
+    # looking at footprints loses jobs to out-of-memory, the probe-driven ledger finishes all.
+    spec = W.pressure32(seed=9, scale=1 / 32)
+    data = [W.task_data(t) for t in spec["tasks"]]
+    tasks = [harness.build_task(t, d) for t, d in zip(spec["tasks"], data)]
+    cap = spec["cap_bytes"]
+    cg = mgb.Sched(policy=mgb.MGB_POLICY_CG, max_running=32, mem_cap_bytes=cap)
+    rec, mk = harness.run_mix(cg, tasks, use_arrivals=False)
+    lost = [r for r in rec if r.get("crashed")]
+    assert 0 < len(lost) < 32
+    trace = cg.trace()
+    dec = assert_trace_matches_replay(cg.desc, trace)
+    assert ((dec["kind"] == oracle.D_REJECT) & (dec["code"] == mgb.MGB_E_OOM)).sum() == len(lost)
+    done = {r["task_id"] for r in rec if not r.get("crashed")}
+    for t, d in zip(tasks, data):
+        if t.spec.task_id in done:
+            verify_task_output(t, d)
+    assert harness.summarize(rec, mk)["crashed"] == len(lost)
+    assert cg.destroy() == 0
+    s = mgb.Sched(policy=mgb.MGB_POLICY_HARD, mem_cap_bytes=cap)
+    rec, mk = harness.run_mix(s, tasks, use_arrivals=False)
+    assert not any(r.get("crashed") for r in rec) and harness.summarize(rec, mk)["tasks"] == 32
+    check_ledger_invariants(s.desc, s.trace())
+    assert s.destroy() == 0
+
+
 def test_cnn8_reduced_images():
     s, tasks, data, rec = _run(W.cnn8(h=52, w=52), time_scale=0.1)
     assert {t.spec.params["batch"] for t in tasks} <= {1, 2, 4, 8}

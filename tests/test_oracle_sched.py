@@ -10,7 +10,7 @@ import pytest
 
 import oracle
 from oracle import (D_ADMIT, D_WAIT, D_REJECT, D_RELEASE, D_CANCELLED, POL_HARD, POL_SOFT,
-                    POL_SERIAL, Q_BACKFILL, Q_FIFO)
+                    POL_SERIAL, POL_CG, Q_BACKFILL, Q_FIFO)
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "sched_hand_case.json")
 KIND = {"admit": D_ADMIT, "wait": D_WAIT, "reject": D_REJECT, "release": D_RELEASE}
@@ -315,6 +315,40 @@ def test_buddy_blocks_alignment_rounding_and_resident_limit():
     dec2 = oracle.sched_replay(dev2, oracle.make_inputs(ev[:3] + [("complete", 1)]))
     assert [int(d["kind"]) for d in dec2] == [D_ADMIT, D_ADMIT, D_WAIT, D_RELEASE, D_ADMIT]
     assert int(dec2[4]["ticket"]) == 3 and int(dec2[4]["granule_mask"]) == 0x03   # lowest aligned pair now free
+
+
+def test_cg_ratio_ignores_memory_and_reports_the_crash():
+    # Sec. IV's CG baseline: up to `ratio` jobs share the device, memory is never consulted, so
+    # the job that does not fit at the moment it is let in is the one that dies.
+    dev = oracle.device(1000, policy=POL_CG, max_running=2)
+    g, b = (4, 1, 1), (64, 1, 1)
+    ev = [("probe", 1, 600, g, b),      # t1 in, 400 free
+          ("probe", 2, 600, g, b),      # below the ratio, does not fit -> out of memory, gone
+          ("probe", 3, 300, g, b),      # t3 in, 100 free, ratio reached
+          ("probe", 4, 500, g, b),      # t4 waits for a slot, not for memory
+          ("probe", 5, 50, g, b),       # t5 waits behind it
+          ("complete", 3),              # slot free, 400 bytes free: t4 (500) dies, t5 gets in
+          ("complete", 2),              # the dead job's ticket is unknown
+          ("complete", 1), ("complete", 5)]
+    dec = oracle.sched_replay(dev, oracle.make_inputs(ev))
+    got = [(int(d["in_index"]), int(d["kind"]), int(d["ticket"]), int(d["code"]), int(d["free_bytes"])) for d in dec]
+    E_OOM, E_UNKNOWN = -8, -3
+    assert got == [(0, D_ADMIT, 1, 0, 400), (1, D_REJECT, 2, E_OOM, 400), (2, D_ADMIT, 3, 0, 100),
+                   (3, D_WAIT, 4, 0, 100), (4, D_WAIT, 5, 0, 100),
+                   (5, D_RELEASE, 3, 0, 400), (5, D_REJECT, 4, E_OOM, 400), (5, D_ADMIT, 5, 0, 350),
+                   (6, D_REJECT, 0, E_UNKNOWN, 350),
+                   (7, D_RELEASE, 1, 0, 950), (8, D_RELEASE, 5, 0, 1000)]
+    # every admitted job shares the whole device
+    assert all(d["granule_mask"] == 0xFFFFFFFF for d in dec if d["kind"] == D_ADMIT)
+    # with unbounded memory CG never rejects and never holds more than `ratio` jobs
+    dev = oracle.device(1 << 40, policy=POL_CG, max_running=3)
+    ev = [("probe", i, 1000, g, b) for i in range(1, 9)] + [("complete", i) for i in range(1, 9)]
+    dec = oracle.sched_replay(dev, oracle.make_inputs(ev))
+    assert (dec["kind"] == D_REJECT).sum() == 0 and (dec["kind"] == D_ADMIT).sum() == 8
+    running = 0
+    for d in dec:
+        running += int(d["kind"] == D_ADMIT) - int(d["kind"] == D_RELEASE)
+        assert running <= 3
 
 
 def test_probe_formulas_match_stated_footprints():
