@@ -1,10 +1,26 @@
 // bf16 GEMM C(fp32) = A(bf16) * B(bf16), all row-major, fp32 accumulation on
 // the bf16 matrix cores (v_mfma_f32_32x32x16_bf16).
 //
-// MFMA-bound above n ~ 1.3k, HBM-bound below.  One workgroup of 4 waves owns a
-// 128 x 256 tile of C, each wave a 64 x 128 piece (2 x 4 MFMA blocks): at the
-// bf16 MFMA rate a smaller wave tile would be bound by LDS read bandwidth
-// (a 64 x 128 piece reads 6 KiB of operands per 8 MFMAs).
+// Two kernels.
+//
+// gemm_bf16_dma_kernel (k % 32 == 0, n % 8 == 0, 16-byte aligned operands): one
+// workgroup of 4 waves owns a 256 x 256 tile of C, each wave a 128 x 128 piece
+// (4 x 4 MFMA blocks, 256 accumulator registers, one wave per SIMD).  At that
+// size a wave reads 128 bytes of operands from LDS per lane for every 16 MFMAs
+// and the workgroup pulls 32 KiB from L2 per 32 MFMAs per wave, which keeps
+// both LDS and the L2 -> CU path below the MFMA time.  Operand tiles of depth
+// 32 travel global -> LDS directly (global_load_lds_dwordx4, no register
+// staging) into a ring of four 32 KiB stages, so three tiles are in flight
+// while one is consumed and the latency of L2 misses is covered.  The LDS
+// layout is unpadded (a DMA instruction fills 1 KiB contiguously, 16 bytes per
+// lane) and XOR-swizzled through the choice of the global source chunk of each
+// lane.  With one wave per SIMD nothing hides a stalled instruction, so the
+// main loop is laid out by hand: after every MFMA exactly one memory
+// instruction is issued (a fragment read for the next 16 k, or one DMA
+// instruction of a later tile), pinned with scheduling barriers.
+//
+// gemm_bf16_kernel (any shape): 128 x 256 tiles, 4 waves of 64 x 128, register
+// staged; guarded element-wise gathers on ragged edge tiles.
 //
 // The MFMA wants, per lane, 8 consecutive k of one A row and 8 consecutive k
 // of one B column.  A is row-major, so its tile is copied to LDS as is and read
@@ -15,9 +31,9 @@
 // lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  With lane s of a group pointing at
 // B[k0 + s/4][n0 + 4*(s%4) ..], lane i gets B[k0 .. k0+3][n0 + i].
 //
-// LDS pitches: A rows 80 bytes (conflict-free 16-byte reads), B rows
-// 2*256 + 64 bytes so that the four k rows one transpose read touches fall in
-// different bank quarters.
+// LDS pitches of the register-staged kernel: A rows 80 bytes (conflict-free
+// 16-byte reads), B rows 2*256 + 64 bytes so that the four k rows one transpose
+// read touches fall in different bank quarters.
 //
 // MFMA 32x32x16 layout (lane l): a = A[l % 32][8*(l/32) .. +7],
 // b = B[8*(l/32) .. +7][l % 32], acc[r] = C[8*(r/4) + 4*(l/32) + r%4][l % 32].
@@ -25,6 +41,8 @@
 #include "launch_util.h"
 
 #include <hip/hip_runtime.h>
+
+#include <mutex>
 
 namespace {
 
@@ -178,13 +196,202 @@ __global__ __launch_bounds__(GB_THREADS, 2) void gemm_bf16_kernel(const uint16_t
       }
 }
 
+// ---- 256 x 256 x 32 tiles, global -> LDS DMA ring ---------------------------------------------
+constexpr uint32_t GD_BM = 256, GD_BN = 256, GD_BK = 32, GD_THREADS = 256, GD_NST = 4, GD_BAND = 4;
+constexpr uint32_t GD_A_BYTES = GD_BM * GD_BK * 2, GD_B_BYTES = GD_BK * GD_BN * 2;   // 16 KiB each
+constexpr uint32_t GD_STAGE = GD_A_BYTES + GD_B_BYTES;
+constexpr uint32_t GD_LDS = GD_NST * GD_STAGE;                                        // 128 KiB
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+// s_waitcnt immediate that waits for vmcnt <= n only
+constexpr uint32_t vm_wait(uint32_t n) { return (n & 15u) | ((n >> 4) << 14) | 0x0F70u; }
+
+// 16 bytes per lane from global memory straight into LDS at lds_addr + 16 * lane (lds_addr is
+// wave-uniform).  Written as asm so that the compiler does not serialise every later LDS read
+// behind it; completion is awaited with explicit vmcnt waits.
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_addr) : "memory", "m0");
+}
+
+// chunk swizzle of an A row (4 chunks of 16 bytes): 16 consecutive rows read at one logical chunk
+// hit 16 different 16-byte slots of a 256-byte bank sweep, 8 consecutive rows 8 different slots
+// of a 128-byte sweep
+__device__ __forceinline__ uint32_t a_swz(uint32_t row) { return ((row >> 2) & 3u) ^ (((row >> 1) & 1u) << 1); }
+// chunk swizzle of a B k-row (32 chunks): the four k rows of one transpose read land in different
+// 64-byte quarters
+__device__ __forceinline__ uint32_t b_swz(uint32_t k) { return (k & 3u) << 2; }
+
+__global__ __launch_bounds__(GD_THREADS, 1) void gemm_bf16_dma_kernel(const uint16_t* __restrict__ A,
+                                                                    const uint16_t* __restrict__ B,
+                                                                    float* __restrict__ C, uint32_t M,
+                                                                    uint32_t N, uint32_t K,
+                                                                    uint32_t tiles_n, uint32_t tiles_total) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+  // XCD-aware tile order (see the fp32 GEMM): bands of GD_BAND tile rows, down the band first.
+  const uint32_t per_xcd = (tiles_total + 7u) / 8u;
+  const uint32_t seq = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || seq >= tiles_total) return;
+  const uint32_t tiles_m = tiles_total / tiles_n;
+  const uint32_t band = seq / (GD_BAND * tiles_n);
+  const uint32_t band_rows = min(GD_BAND, tiles_m - GD_BAND * band);
+  const uint32_t in_band = seq - band * GD_BAND * tiles_n;
+  const uint32_t bm = (GD_BAND * band + in_band % band_rows) * GD_BM;
+  const uint32_t bn = (in_band / band_rows) * GD_BN;
+
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_ptr)smem);
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t wm = (wave >> 1) * 128u, wn = (wave & 1u) * 128u;
+  const uint32_t l32 = lane & 31u, lhi = lane >> 5;
+  const uint32_t tq = lane >> 4, ts = lane & 15u;
+  const uint32_t tr_row = 8u * (tq >> 1) + (ts >> 2);
+  const uint32_t tr_col = 16u * (tq & 1u) + 4u * (ts & 3u);
+
+  // DMA roles: wave w, instruction h fills the 1 KiB block b = 4w + h of the A part and of the B
+  // part of a stage.
+  //   A block b: rows 16b .. 16b+15 (64 bytes each); lane -> row 16b + lane/4, LDS chunk lane%4.
+  //   B block b: k rows 2b, 2b+1 (512 bytes each);   lane -> k 2b + lane/32,  LDS chunk lane%32.
+  // The lane fetches the global chunk whose swizzled position is its LDS chunk.  Rows beyond M
+  // and column chunks beyond N are clamped to the last valid one: what they deliver only feeds
+  // entries of C that are never stored.
+  const uint16_t* ga[4];
+  const uint16_t* gb[4];
+#pragma unroll
+  for (uint32_t h = 0; h < 4; ++h) {
+    const uint32_t b = 4u * wave + h;
+    const uint32_t ar = 16u * b + (lane >> 2);
+    ga[h] = A + (size_t)min(bm + ar, M - 1u) * K + 8u * ((lane & 3u) ^ a_swz(ar));
+    const uint32_t bk = 2u * b + (lane >> 5);
+    gb[h] = B + (size_t)bk * N + min(bn + 8u * ((lane & 31u) ^ b_swz(bk)), N - 8u);
+  }
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // fragment addresses inside a stage (bytes), for the two 16-wide k halves of a tile
+  uint32_t a_off[2][4], b_lo[2][4], b_hi[2][4];
+  auto b_off = [&](uint32_t krow, uint32_t col) -> uint32_t {
+    return GD_A_BYTES + krow * 512u + (((col >> 3) ^ b_swz(krow)) << 4) + (col & 7u) * 2u;
+  };
+#pragma unroll
+  for (uint32_t s = 0; s < 2; ++s) {
+#pragma unroll
+    for (uint32_t i = 0; i < 4; ++i) {
+      const uint32_t row = wm + 32u * i + l32;
+      a_off[s][i] = row * 64u + (((2u * s + lhi) ^ a_swz(row)) << 4);
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) {
+      b_lo[s][j] = b_off(16u * s + tr_row, wn + 32u * j + tr_col);
+      b_hi[s][j] = b_off(16u * s + 4u + tr_row, wn + 32u * j + tr_col);
+    }
+  }
+
+  u32x4 fa[2][4];
+  s16x4 blo[2][4], bhi[2][4];
+  const uint32_t nk = K / GD_BK;
+  // one fragment read: q = 0..11 -> a0, b0 lo, b0 hi, b1 lo, b1 hi, b2 lo, b2 hi, b3 lo, b3 hi, a1, a2, a3
+  // (the order in which the next 16 MFMAs need them)
+  auto frag_load = [&](const uint8_t* st, uint32_t s, uint32_t slot, uint32_t q) {
+    if (q == 0u || q >= 9u) {
+      const uint32_t i = q == 0u ? 0u : q - 8u;
+      fa[slot][i] = *reinterpret_cast<const u32x4*>(st + a_off[s][i]);
+    } else {
+      const uint32_t j = (q - 1u) >> 1;
+      if ((q - 1u) & 1u) bhi[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(st + b_hi[s][j]));
+      else blo[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(st + b_lo[s][j]));
+    }
+  };
+  // one DMA instruction of tile kt: part 0 = A, part 1 = B, h = 0..3.  The tile index is clamped
+  // so that every iteration issues the same number of loads (the vmcnt arithmetic below relies
+  // on it); the redundant loads of the last iterations land in stages nobody reads any more.
+  auto dma_one = [&](uint32_t kt, uint32_t part, uint32_t h) {
+    const uint32_t t = min(kt, nk - 1u);
+    const uint32_t st = lds_base + (kt % GD_NST) * GD_STAGE + (4u * wave + h) * 1024u;
+    if (part == 0u) dma16(ga[h] + (size_t)t * GD_BK, st);
+    else dma16(gb[h] + (size_t)t * GD_BK * N, st + GD_A_BYTES);
+  };
+  // 16 MFMAs on fragment slot `slot`; after each one memory instruction: the 12 fragment reads of
+  // (tile ft, half fs) into the other slot, then the 4 DMA instructions of (tile dt, part dpart)
+  auto block = [&](uint32_t slot, uint32_t ft, uint32_t fs, uint32_t dt, uint32_t dpart) {
+    const uint8_t* fst = smem + (ft % GD_NST) * GD_STAGE;
+#pragma unroll
+    for (uint32_t m = 0; m < 16u; ++m) {
+      const uint32_t i = m >> 2, j = m & 3u;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fa[slot][i]), join_bf16x8(blo[slot][j], bhi[slot][j]),
+                                                          acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (m < 12u) frag_load(fst, fs, slot ^ 1u, m);
+      else dma_one(dt, dpart, m - 12u);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // Order of DMA issue: A(0) B(0) .. A(NST-2) B(NST-2) A(NST-1) | B(NST-1) A(NST) | B(NST) A(NST+1) | ..
+  // (4 instructions each; one `|` per loop iteration).  Tile t is complete once B(t) has landed.
+#pragma unroll
+  for (uint32_t t = 0; t < GD_NST - 1u; ++t)
+#pragma unroll
+    for (uint32_t p = 0; p < 2u; ++p)
+#pragma unroll
+      for (uint32_t h = 0; h < 4u; ++h) dma_one(t, p, h);
+#pragma unroll
+  for (uint32_t h = 0; h < 4u; ++h) dma_one(GD_NST - 1u, 0u, h);
+  __builtin_amdgcn_s_waitcnt(vm_wait(8u * (GD_NST - 2u) + 4u));   // this wave's part of tile 0 has landed
+  __syncthreads();                                                // ... and everybody else's
+#pragma unroll
+  for (uint32_t q = 0; q < 12u; ++q) frag_load(smem, 0u, 0u, q);
+  for (uint32_t kt = 0; kt < nk; ++kt) {
+    block(0u, kt, 1u, kt + GD_NST - 1u, 1u);            // second half of tile kt's fragments; B(kt + NST - 1)
+    // 8 * (NST - 2) instructions were issued after B(kt + 1): tile kt+1 has landed when no more
+    // than that many are outstanding; the barrier extends that to every wave's part and tells
+    // that all reads of tile kt are done (its fragments are in registers), which frees its stage
+    __builtin_amdgcn_s_waitcnt(vm_wait(8u * (GD_NST - 2u)));
+    __syncthreads();
+    block(1u, kt + 1u, 0u, kt + GD_NST, 0u);            // first half of tile kt+1's fragments; A(kt + NST) into the freed stage
+  }
+  __builtin_amdgcn_s_waitcnt(vm_wait(0));               // no DMA may be in flight when the LDS is given back
+
+#pragma unroll
+  for (uint32_t i = 0; i < 4; ++i)
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t row = bm + wm + 32u * i + 8u * (r >> 2) + 4u * lhi + (r & 3);
+        const uint32_t col = bn + wn + 32u * j + l32;
+        if (row < M && col < N) C[(size_t)row * N + col] = acc[i][j][r];
+      }
+}
+
 struct Geometry {
   uint32_t tiles_m, tiles_n, total, blocks;
-  bool fast;
+  bool dma;    // shape fits the DMA kernel (operand alignment is checked at enqueue)
+  bool fast;   // register-staged kernel: every tile full
 };
 
 Geometry geometry(uint32_t m, uint32_t n, uint32_t k) {
   Geometry g;
+  g.dma = k % GD_BK == 0u && n % 8u == 0u;
+  const uint32_t bm = g.dma ? GD_BM : GB_BM, bn = g.dma ? GD_BN : GB_BN;
+  g.tiles_m = (m + bm - 1u) / bm;
+  g.tiles_n = (n + bn - 1u) / bn;
+  g.total = g.tiles_m * g.tiles_n;
+  g.blocks = ((g.total + 7u) / 8u) * 8u;
+  g.fast = m % GB_BM == 0u && n % GB_BN == 0u && k % GB_BK == 0u;
+  return g;
+}
+
+Geometry staged_geometry(uint32_t m, uint32_t n, uint32_t k) {
+  Geometry g;
+  g.dma = false;
   g.tiles_m = (m + GB_BM - 1u) / GB_BM;
   g.tiles_n = (n + GB_BN - 1u) / GB_BN;
   g.total = g.tiles_m * g.tiles_n;
@@ -216,9 +423,25 @@ int mgb_gemm_bf16_enqueue(void* stream, const uint16_t* A, const uint16_t* B, fl
                           uint32_t n, uint32_t k) {
   if (!A || !B || !C) return MGB_E_INVAL;
   if (!shape_ok(m, n, k)) return MGB_E_UNSUPPORTED;
-  const Geometry g = geometry(m, n, k);
   const bool aligned = (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15u) == 0u;
   hipStream_t st = (hipStream_t)stream;
+  Geometry g = geometry(m, n, k);
+  if (g.dma && aligned) {
+    static std::once_flag once;
+    static hipError_t attr = hipSuccess;
+    std::call_once(once, [] {
+      attr = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)GD_LDS);
+    });
+    if (attr != hipSuccess) {
+      mgb_internal_set_error("gemm_bf16_dma_kernel: dynamic LDS size", attr);
+      return MGB_E_BACKEND;
+    }
+    hipLaunchKernelGGL(gemm_bf16_dma_kernel, dim3(g.blocks), dim3(GD_THREADS), GD_LDS, st, A, B, C, m, n, k,
+                       g.tiles_n, g.total);
+    return mgb_check_launch("gemm_bf16_dma_kernel");
+  }
+  // any other shape, or operands that are not 16-byte aligned (the probe assumed they were)
+  g = staged_geometry(m, n, k);
   const uint32_t vec_ok = (aligned && k % GB_BK == 0u && n % 8u == 0u) ? 1u : 0u;
   if (g.fast && aligned)
     hipLaunchKernelGGL(gemm_bf16_kernel<true>, dim3(g.blocks), dim3(GB_THREADS), 0, st, A, B, C, m,

@@ -259,7 +259,8 @@ def test_probe_functions_agree_with_checker_formulas():
         mem, grid, block = mgb.probe_of(mgb.mgb_gemm_f32_probe, m, n, k)
         oracle.lib().orc_gemm_f32_probe(C.c_uint64(m), C.c_uint64(n), C.c_uint64(k), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (m, n, k)
-    for m, n, k in ((1, 1, 1), (129, 257, 17), (4096, 4096, 4096), (8192, 1024, 64)):
+    for m, n, k in ((1, 1, 1), (129, 257, 17), (4096, 4096, 4096), (8192, 1024, 64), (300, 520, 64), (300, 520, 48),
+                    (300, 524, 64), (1, 8, 32)):
         mem, grid, block = mgb.probe_of(mgb.mgb_gemm_bf16_probe, m, n, k)
         oracle.lib().orc_gemm_bf16_probe(C.c_uint64(m), C.c_uint64(n), C.c_uint64(k), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (m, n, k)

@@ -161,13 +161,29 @@ def run_gemm_bf16(ab, bb):
 
 
 @pytest.mark.parametrize("m,n,k", [(1, 1, 1), (128, 128, 32), (128, 128, 64), (100, 70, 33),
-                                   (129, 257, 17), (256, 256, 256), (384, 128, 96), (512, 384, 1000)])
+                                   (129, 257, 17), (256, 256, 256), (384, 128, 96), (512, 384, 1000),
+                                   # k % 32 == 0 and n % 8 == 0: the 256 x 256 DMA-ring kernel, with
+                                   # ragged rows / columns, fewer k tiles than ring stages, several tiles
+                                   (1, 8, 32), (256, 8, 64), (300, 520, 64), (513, 264, 2048),
+                                   (1024, 1024, 32), (768, 512, 96), (2000, 1096, 1056)])
 def test_gemm_bf16_frobenius_error(m, n, k):
     ab, bb = W.gemm_operands_bf16(m + 3 * k, m, n, k)
     got = run_gemm_bf16(ab, bb)
     ref = oracle.gemm_bf16(ab, bb)
     assert frobenius_rel(got, ref) <= 1e-2
     assert frobenius_rel(got, ref) <= 1e-5          # fp32 accumulation of exact products
+
+
+def test_gemm_bf16_unaligned_operands_take_the_staged_kernel():
+    m, n, k = 200, 264, 96
+    ab, bb = W.gemm_operands_bf16(11, m, n, k)
+    A = torch.zeros(m * k + 8, dtype=torch.int16, device=DEV)
+    A[1:1 + m * k] = torch.from_numpy(ab.view(np.int16).ravel()).to(DEV)      # 2-byte aligned only
+    B = torch.from_numpy(bb.view(np.int16)).to(DEV)
+    Cd = torch.full((m, n), float("nan"), device=DEV)
+    assert mgb.mgb_gemm_bf16_enqueue(None, C.c_void_p(A.data_ptr() + 2), P(B), P(Cd), m, n, k) == 0
+    sync()
+    assert frobenius_rel(Cd.cpu().numpy(), oracle.gemm_bf16(ab, bb)) <= 1e-5
 
 
 def test_gemm_bf16_layout_exact_small_integers():
