@@ -54,25 +54,37 @@ void orc_gemm_bf16_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
   out[4] = 256; out[5] = 1; out[6] = 1;
 }
 
-// One 3x3 conv layer (pad 1): bf16 input, weights and output.  A 256-thread workgroup
-// covers 128 output pixels x 64 output channels (128 channels when c_out > 64).
+// One 3x3 conv layer (pad 1): bf16 input, weights and output.  Workgroup shape by layer:
+//   c_in % 32 == 0 and c_out % 8 == 0: 256 threads per 128 pixels x 128 channels (256 x 64 when
+//     c_out <= 64); if that gives fewer than 256 workgroups, 64 threads per 64 x 64 instead;
+//   c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64: 256 threads per 256 pixels (all channels);
+//   otherwise 256 threads per 128 pixels x 64 channels (128 channels when c_out > 64).
 void orc_conv3x3_probe(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, uint64_t c_out,
                        uint64_t stride, uint64_t out[7]) {
   uint64_t ho = (h + 2 - 3) / stride + 1, wo = (w + 2 - 3) / stride + 1;
   uint64_t pixels = batch * ho * wo;
-  uint64_t bn = c_out <= 64 ? 64 : 128;
   out[0] = (batch * h * w * c_in + 9 * c_in * c_out + pixels * c_out) * 2;
-  out[1] = round8(ceil_div(pixels, 128) * ceil_div(c_out, bn)); out[2] = 1; out[3] = 1;
-  out[4] = 256; out[5] = 1; out[6] = 1;
+  uint64_t wgs, threads = 256;
+  if (c_in % 32 == 0 && c_out % 8 == 0) {
+    wgs = c_out > 64 ? ceil_div(pixels, 128) * ceil_div(c_out, 128) : ceil_div(pixels, 256) * ceil_div(c_out, 64);
+    if (wgs < 256) { wgs = ceil_div(pixels, 64) * ceil_div(c_out, 64); threads = 64; }
+  } else if (c_in == 3 && stride == 1 && c_out % 8 == 0 && c_out <= 64) {
+    wgs = ceil_div(pixels, 256);
+  } else {
+    wgs = ceil_div(pixels, 128) * ceil_div(c_out, c_out <= 64 ? 64 : 128);
+  }
+  out[1] = round8(wgs); out[2] = 1; out[3] = 1;
+  out[4] = threads; out[5] = 1; out[6] = 1;
 }
 
 // A chain of conv layers run as one task (launches that share buffers are merged into one
 // task): footprint = bf16 input + all weights + two ping-pong buffers of the largest
-// intermediate activation + the fp32 output of the last layer; geometry = the largest launch.
+// intermediate activation + the fp32 output of the last layer; geometry = the launch with the
+// most threads.
 // c[3*i..3*i+2] = {c_in, c_out, stride} of layer i.
 void orc_cnn_probe(const uint64_t* c, uint64_t n_layers, uint64_t batch, uint64_t h, uint64_t w,
                    uint64_t out[7]) {
-  uint64_t mem = batch * h * w * c[0] * 2, act_max = 0, grid = 0, last = 0;
+  uint64_t mem = batch * h * w * c[0] * 2, act_max = 0, grid = 0, threads = 256, last = 0;
   for (uint64_t i = 0; i < n_layers; ++i) {
     uint64_t one[7];
     orc_conv3x3_probe(batch, h, w, c[3 * i], c[3 * i + 1], c[3 * i + 2], one);
@@ -81,12 +93,12 @@ void orc_cnn_probe(const uint64_t* c, uint64_t n_layers, uint64_t batch, uint64_
     mem += 9 * c[3 * i] * c[3 * i + 1] * 2;
     if (i + 1 < n_layers) { if (elems * 2 > act_max) act_max = elems * 2; }
     else last = elems * 4;
-    if (one[1] > grid) grid = one[1];
+    if (one[1] * one[4] > grid * threads) { grid = one[1]; threads = one[4]; }
     h = ho; w = wo;
   }
   out[0] = mem + 2 * act_max + last;
   out[1] = grid; out[2] = 1; out[3] = 1;
-  out[4] = 256; out[5] = 1; out[6] = 1;
+  out[4] = threads; out[5] = 1; out[6] = 1;
 }
 
 // BFS: CSR (n+1 row pointers, m column indices), the level array, two frontier queues of n

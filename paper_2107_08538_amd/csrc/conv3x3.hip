@@ -19,6 +19,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -229,8 +231,348 @@ __global__ __launch_bounds__(CV_THREADS, 2) void conv3x3_kernel(ConvArgs a) {
       }
 }
 
+// ---- DMA-ring implicit GEMM (c_in % 32 == 0, c_out % 8 == 0, 16-byte aligned tensors) -----------
+//
+// Same pipeline as the DMA bf16 GEMM: operand tiles of depth 32 go global -> LDS directly
+// (global_load_lds_dwordx4) into a ring of four stages, three tiles in flight while one is
+// consumed; unpadded, XOR-swizzled LDS rows of 64 bytes; the main loop is laid out by hand, the
+// fragment reads and DMA instructions spread between the MFMAs and pinned with scheduling
+// barriers.  The gather of the activation operand is free with DMA: every lane names its own
+// source address (its pixel shifted by the filter tap), and a tap outside the image, or a pixel
+// past the end, names a 16-byte block of zeros instead.  With c_in % 32 == 0 a depth-32 tile
+// lies inside one filter tap, so the tap is uniform per tile.
+//
+// The weights are the MFMA's first operand and the pixels its second (out^T = w * patch^T): a
+// lane then owns 4 consecutive channels of one pixel per accumulator quad and stores them as
+// 8 bytes (bf16) or 16 bytes (fp32).
+//
+// WM x WN waves (64 threads each), every wave 64 pixels x 64 channels (2 x 2 MFMA blocks):
+//   2 x 2: 128 x 128 tile          4 x 1: 256 pixels x 64 channels (c_out <= 64)
+//   1 x 1: 64 x 64 tile, one wave per workgroup (layers too small to give every CU a big tile)
+constexpr uint32_t CD_BK = 32, CD_NST = 4;
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+constexpr uint32_t vm_wait(uint32_t n) { return (n & 15u) | ((n >> 4) << 14) | 0x0F70u; }   // s_waitcnt vmcnt(n) only
+
+// 16 bytes per lane from global memory straight into LDS at lds_addr + 16 * lane (lds_addr is
+// wave-uniform).  asm, so that the compiler does not serialise later LDS reads behind it;
+// completion is awaited with explicit vmcnt waits.
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_addr) : "memory", "m0");
+}
+// chunk swizzle of a 64-byte LDS row (4 chunks of 16 bytes): 16 consecutive rows read at one
+// logical chunk hit 16 different slots of a 256-byte bank sweep, 8 rows 8 slots of a 128-byte one
+__device__ __forceinline__ uint32_t row_swz(uint32_t row) { return ((row >> 2) & 3u) ^ (((row >> 1) & 1u) << 1); }
+
+template <uint32_t WM, uint32_t WN>
+__global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma_kernel(ConvArgs a) {
+  constexpr uint32_t NW = WM * WN;
+  constexpr uint32_t BMP = 64u * WM, BNC = 64u * WN;             // pixels x channels per workgroup
+  constexpr uint32_t A_BYTES = BMP * 64u, B_BYTES = BNC * 64u, STAGE = A_BYTES + B_BYTES;
+  constexpr uint32_t NA = BMP / 16u / NW, NB = BNC / 16u / NW;   // DMA instructions per wave per tile
+  static_assert(NA >= 1u && NB >= 1u, "every wave takes part in both operand copies");
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+  const uint32_t per_xcd = (a.tiles_total + 7u) / 8u;
+  const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || tile >= a.tiles_total) return;
+  const uint32_t bm = (tile / a.tiles_n) * BMP;
+  const uint32_t bn = (tile % a.tiles_n) * BNC;
+
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_ptr)smem);
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t wm = (wave / WN) * 64u, wn = (wave % WN) * 64u;
+  const uint32_t l32 = lane & 31u, lhi = lane >> 5;
+  const uint16_t* zeros = reinterpret_cast<const uint16_t*>(g_zero16);
+
+  // DMA roles.  Instruction h of wave w fills the 1 KiB block b = N*w + h of an operand part:
+  // rows 16b .. 16b+15, lane -> row 16b + lane/4, LDS chunk lane%4, source chunk swizzled.
+  //   pixels:   source = x[img][ih0 + r][iw0 + s][c0 + 8*chunk ..] for tap (r, s), or zeros
+  //   weights:  source = w[n][k0 + 8*chunk ..], rows past c_out clamped (they feed channels
+  //             that are never stored)
+  int64_t a_src[NA];        // element offset of the pixel's (ih0, iw0) corner, plus the chunk
+  uint32_t a_taps[NA];      // bit 3r+s: tap (r, s) lies inside the image (0 for pixels past the end)
+  const uint16_t* b_src[NB];
+#pragma unroll
+  for (uint32_t h = 0; h < NA; ++h) {
+    const uint32_t row = 16u * (NA * wave + h) + (lane >> 2);
+    const uint32_t p = bm + row;
+    const bool pv = p < a.pixels;
+    const uint32_t pp = pv ? p : 0u;
+    const uint32_t b = pp / (a.Ho * a.Wo);
+    const uint32_t rem = pp - b * a.Ho * a.Wo;
+    const uint32_t oh = rem / a.Wo, ow = rem - oh * a.Wo;
+    const int32_t ih0 = (int32_t)(oh * a.stride) - 1, iw0 = (int32_t)(ow * a.stride) - 1;
+    uint32_t taps = 0u;
+#pragma unroll
+    for (int32_t r = 0; r < 3; ++r)
+#pragma unroll
+      for (int32_t t = 0; t < 3; ++t)
+        if (pv && (uint32_t)(ih0 + r) < a.H && (uint32_t)(iw0 + t) < a.W) taps |= 1u << (3 * r + t);
+    a_taps[h] = taps;
+    a_src[h] = (((int64_t)b * a.H + ih0) * a.W + iw0) * a.C + 8u * ((lane & 3u) ^ row_swz(row));
+  }
+#pragma unroll
+  for (uint32_t h = 0; h < NB; ++h) {
+    const uint32_t row = 16u * (NB * wave + h) + (lane >> 2);
+    b_src[h] = a.w + (size_t)min(bn + row, a.K - 1u) * a.depth + 8u * ((lane & 3u) ^ row_swz(row));
+  }
+
+  const uint32_t nk = a.depth / CD_BK;
+  // cursors of the two DMA streams (tile index clamped to the last tile: the schedule issues the
+  // same number of loads in every iteration and the surplus lands in stages nobody reads)
+  uint32_t ta = 0u, a_tap = 0u, a_c0 = 0u;    // pixels: tile, its filter tap, first channel
+  uint32_t tb = 0u;                           // weights: tile
+  auto dma_pixels = [&](uint32_t h) {
+    const uint32_t r = (a_tap * 11u) >> 5, t = a_tap - 3u * r;
+    const int64_t delta = ((int64_t)r * a.W + t) * a.C + a_c0;
+    const uint32_t ok = (a_taps[h] >> a_tap) & 1u;
+    dma16(pick(a.x + a_src[h] + delta, zeros, ok), lds_base + (ta % CD_NST) * STAGE + (NA * wave + h) * 1024u);
+  };
+  auto next_pixels = [&]() {
+    if (ta + 1u < nk) {
+      a_c0 += CD_BK;
+      if (a_c0 == a.C) { a_c0 = 0u; ++a_tap; }
+    }
+    ++ta;                                    // the ring position advances even when the source is clamped
+  };
+  auto dma_weights = [&](uint32_t h) {
+    dma16(b_src[h] + (size_t)min(tb, nk - 1u) * CD_BK, lds_base + (tb % CD_NST) * STAGE + A_BYTES + (NB * wave + h) * 1024u);
+  };
+
+  f32x16 acc[2][2];                          // [pixel block][channel block]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // fragment addresses inside a stage, for the two 16-wide halves of a tile
+  uint32_t p_off[2][2], w_off[2][2];
+#pragma unroll
+  for (uint32_t s = 0; s < 2; ++s)
+#pragma unroll
+    for (uint32_t i = 0; i < 2; ++i) {
+      const uint32_t prow = wm + 32u * i + l32, wrow = wn + 32u * i + l32;
+      p_off[s][i] = prow * 64u + (((2u * s + lhi) ^ row_swz(prow)) << 4);
+      w_off[s][i] = A_BYTES + wrow * 64u + (((2u * s + lhi) ^ row_swz(wrow)) << 4);
+    }
+  u32x4 fp[2][2], fw[2][2];                  // [slot][block]
+  auto frag_load = [&](const uint8_t* st, uint32_t s, uint32_t slot, uint32_t q) {   // q: w0, p0, p1, w1
+    if (q == 0u) fw[slot][0] = *reinterpret_cast<const u32x4*>(st + w_off[s][0]);
+    else if (q == 3u) fw[slot][1] = *reinterpret_cast<const u32x4*>(st + w_off[s][1]);
+    else fp[slot][q - 1u] = *reinterpret_cast<const u32x4*>(st + p_off[s][q - 1u]);
+  };
+  // 4 MFMAs on fragment slot `slot` (order (j, i) = (0,0) (0,1) (1,0) (1,1)); spread between them
+  // the 4 fragment reads of (tile ft, half fs) into the other slot and one part of a tile's DMA
+  auto block = [&](uint32_t slot, uint32_t ft, uint32_t fs, bool weights_part) {
+    const uint8_t* fst = smem + (ft % CD_NST) * STAGE;
+    constexpr uint32_t ND = NA > NB ? NA : NB;
+#pragma unroll
+    for (uint32_t m = 0; m < 4u; ++m) {
+      const uint32_t j = m >> 1, i = m & 1u;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fw[slot][j]), as_bf16x8(fp[slot][i]), acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      frag_load(fst, fs, slot ^ 1u, m);
+#pragma unroll
+      for (uint32_t h = m * ND / 4u; h < (m + 1u) * ND / 4u; ++h) {
+        if (weights_part) { if (h < NB) dma_weights(h); }
+        else { if (h < NA) dma_pixels(h); }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (weights_part) ++tb; else next_pixels();
+  };
+
+  // DMA issue order: P(0) W(0) .. P(NST-2) W(NST-2) P(NST-1) | W(NST-1) P(NST) | W(NST) P(NST+1) | ..
+  // (`|` = one loop iteration); tile t is complete once W(t) has landed.
+#pragma unroll
+  for (uint32_t t = 0; t < CD_NST - 1u; ++t) {
+#pragma unroll
+    for (uint32_t h = 0; h < NA; ++h) dma_pixels(h);
+    next_pixels();
+#pragma unroll
+    for (uint32_t h = 0; h < NB; ++h) dma_weights(h);
+    ++tb;
+  }
+#pragma unroll
+  for (uint32_t h = 0; h < NA; ++h) dma_pixels(h);
+  next_pixels();
+  __builtin_amdgcn_s_waitcnt(vm_wait((CD_NST - 2u) * (NA + NB) + NA));   // this wave's part of tile 0 has landed
+  __syncthreads();
+#pragma unroll
+  for (uint32_t q = 0; q < 4u; ++q) frag_load(smem, 0u, 0u, q);
+  for (uint32_t kt = 0; kt < nk; ++kt) {
+    block(0u, kt, 1u, true);                 // second half of tile kt's fragments; W(kt + NST - 1)
+    // (NST-2) * (NA+NB) instructions were issued after W(kt+1): tile kt+1 has landed when no more
+    // are outstanding; the barrier extends that to every wave's part, and tells that tile kt's
+    // fragments are all in registers, which frees its stage
+    __builtin_amdgcn_s_waitcnt(vm_wait((CD_NST - 2u) * (NA + NB)));
+    __syncthreads();
+    block(1u, kt + 1u, 0u, false);           // first half of tile kt+1's fragments; P(kt + NST) into the freed stage
+  }
+  __builtin_amdgcn_s_waitcnt(vm_wait(0));    // no DMA may be in flight when the LDS is given back
+
+  // out^T quads: acc[i][j][4g .. 4g+3] = channels wn + 32j + 8g + 4*lhi + (0..3) of pixel wm + 32i + l32
+#pragma unroll
+  for (uint32_t i = 0; i < 2; ++i) {
+    const uint32_t p = bm + wm + 32u * i + l32;
+#pragma unroll
+    for (uint32_t j = 0; j < 2; ++j)
+#pragma unroll
+      for (uint32_t g = 0; g < 4; ++g) {
+        const uint32_t ch = bn + wn + 32u * j + 8u * g + 4u * lhi;
+        if (p < a.pixels && ch < a.K) {                   // c_out % 4 == 0: a quad is inside or outside as a whole
+          float v[4];
+#pragma unroll
+          for (uint32_t e = 0; e < 4; ++e) v[e] = fmaxf(acc[i][j][4u * g + e], 0.f);
+          if (a.out_f32) {
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.y) + (size_t)p * a.K + ch) = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+            uint2 q;
+            q.x = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
+            q.y = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.y) + (size_t)p * a.K + ch) = q;
+          }
+        }
+      }
+  }
+}
+
+// ---- 3-channel first layer (c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64) ------------------
+//
+// Depth 27: two MFMA steps, the kernel is bound by writing its output (c_out / 3 times the
+// input).  A workgroup owns 256 consecutive output pixels (n, oh, ow flattened).  With stride 1
+// the input pixel of tap (r, s) is the output pixel's flattened index + (r-1)*W + (s-1), so the
+// three input strips [first - 1 + (r-1)*W, + 258 pixels) hold every operand; they are copied to
+// LDS once (zeros outside the tensor), and every lane assembles its pixel fragment from 2-byte
+// LDS reads, with the taps that fall outside the image masked to zero.  The results are
+// rounded, transposed through LDS and written as 16 bytes per lane, 4 KiB contiguous per wave.
+constexpr uint32_t C3_PIX = 256, C3_STRIP = 776;      // 258 pixels x 3 channels, padded to a multiple of 8
+
+template <uint32_t NJ>    // 32-channel blocks: c_out <= 32 * NJ
+__global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
+  __shared__ __attribute__((aligned(16))) uint16_t strip[3u * C3_STRIP];
+  __shared__ __attribute__((aligned(16))) uint16_t outs[C3_PIX * 32u * NJ];
+  const uint32_t bm = blockIdx.x * C3_PIX;
+  if (bm >= a.pixels) return;
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const uint32_t l32 = lane & 31u, lhi = lane >> 5;
+
+  // input strips (H = Ho, W = Wo with stride 1: input and output pixels share their flattened index)
+  const int64_t total = (int64_t)a.pixels * 3;
+#pragma unroll
+  for (uint32_t r = 0; r < 3; ++r) {
+    const int64_t first = ((int64_t)bm - 1 + ((int64_t)r - 1) * a.W) * 3;
+    for (uint32_t e = tid; e < C3_STRIP; e += 256u) {
+      const int64_t g = first + e;
+      strip[r * C3_STRIP + e] = (g >= 0 && g < total && e < 774u) ? a.x[g] : (uint16_t)0;
+    }
+  }
+
+  // weight fragments: channel 32j + l32, k = 16*ks + 8*lhi + e
+  u32x4 fw[2][NJ];
+#pragma unroll
+  for (uint32_t ks = 0; ks < 2; ++ks)
+#pragma unroll
+    for (uint32_t j = 0; j < NJ; ++j) {
+      const uint32_t ch = 32u * j + l32;
+      uint32_t wd[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (uint32_t e = 0; e < 8; ++e) {
+        const uint32_t k = 16u * ks + 8u * lhi + e;
+        const uint32_t ok = (uint32_t)(k < 27u) & (uint32_t)(ch < a.K);
+        const uint32_t v = a.w[ok ? ch * 27u + k : 0u];
+        wd[e >> 1] |= (ok ? v : 0u) << (16u * (e & 1u));
+      }
+      fw[ks][j] = u32x4{wd[0], wd[1], wd[2], wd[3]};
+    }
+  __syncthreads();
+
+  f32x16 acc[2][NJ];
+#pragma unroll
+  for (uint32_t i = 0; i < 2; ++i) {
+    const uint32_t pl = 64u * wave + 32u * i + l32;            // pixel inside the workgroup's 256
+    const uint32_t p = bm + pl;
+    const uint32_t rem = p % (a.H * a.W);
+    const uint32_t oh = rem / a.W, ow = rem - oh * a.W;
+    uint32_t taps = 0u;
+#pragma unroll
+    for (int32_t r = 0; r < 3; ++r)
+#pragma unroll
+      for (int32_t t = 0; t < 3; ++t)
+        if (p < a.pixels && (uint32_t)((int32_t)oh + r - 1) < a.H && (uint32_t)((int32_t)ow + t - 1) < a.W)
+          taps |= 1u << (3 * r + t);
+#pragma unroll
+    for (uint32_t j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+    for (uint32_t ks = 0; ks < 2; ++ks) {
+      uint32_t wd[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (uint32_t e = 0; e < 8; ++e) {
+        const uint32_t k = 16u * ks + 8u * lhi + e;            // = 9r + 3s + c
+        const uint32_t tap = (k * 11u) >> 5;                   // k / 3
+        const uint32_t ka = min(k, 26u);                       // depth padding reads a valid address and is masked
+        const uint32_t r = (ka * 57u) >> 9;                    // ka / 9
+        const uint32_t ok = (taps >> tap) & 1u;                // bits 9, 10 are clear: k >= 27 gives zero
+        const uint32_t v = strip[r * C3_STRIP + pl * 3u + ka - 9u * r];
+        wd[e >> 1] |= (ok ? v : 0u) << (16u * (e & 1u));
+      }
+      const bf16x8 fp = as_bf16x8(u32x4{wd[0], wd[1], wd[2], wd[3]});
+#pragma unroll
+      for (uint32_t j = 0; j < NJ; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fw[ks][j]), fp, acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // ReLU + rounding; transpose through LDS: outs[pixel][channel], c_out values per pixel
+  const uint32_t Kc = a.K;
+  if (!a.out_f32) {
+#pragma unroll
+    for (uint32_t i = 0; i < 2; ++i)
+#pragma unroll
+      for (uint32_t j = 0; j < NJ; ++j)
+#pragma unroll
+        for (uint32_t g = 0; g < 4; ++g) {
+          const uint32_t pl = 64u * wave + 32u * i + l32, ch = 32u * j + 8u * g + 4u * lhi;
+          if (ch < Kc) {
+            uint2 q;
+            q.x = (uint32_t)f32_to_bf16_rne(fmaxf(acc[i][j][4u * g], 0.f)) | ((uint32_t)f32_to_bf16_rne(fmaxf(acc[i][j][4u * g + 1u], 0.f)) << 16);
+            q.y = (uint32_t)f32_to_bf16_rne(fmaxf(acc[i][j][4u * g + 2u], 0.f)) | ((uint32_t)f32_to_bf16_rne(fmaxf(acc[i][j][4u * g + 3u], 0.f)) << 16);
+            *reinterpret_cast<uint2*>(&outs[pl * Kc + ch]) = q;
+          }
+        }
+    __syncthreads();
+    const uint32_t chunks = C3_PIX * Kc / 8u;                  // 16-byte chunks of the workgroup's output
+    uint16_t* y = reinterpret_cast<uint16_t*>(a.y) + (size_t)bm * Kc;
+    const uint32_t valid = (min(a.pixels - bm, C3_PIX) * Kc) / 8u;
+    for (uint32_t q = tid; q < chunks; q += 256u)
+      if (q < valid) *reinterpret_cast<u32x4*>(y + 8u * (size_t)q) = *reinterpret_cast<const u32x4*>(&outs[8u * q]);
+  } else {
+#pragma unroll
+    for (uint32_t i = 0; i < 2; ++i)
+#pragma unroll
+      for (uint32_t j = 0; j < NJ; ++j)
+#pragma unroll
+        for (uint32_t g = 0; g < 4; ++g) {
+          const uint32_t p = bm + 64u * wave + 32u * i + l32, ch = 32u * j + 8u * g + 4u * lhi;
+          if (p < a.pixels && ch < Kc)
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.y) + (size_t)p * Kc + ch) =
+                make_float4(fmaxf(acc[i][j][4u * g], 0.f), fmaxf(acc[i][j][4u * g + 1u], 0.f),
+                            fmaxf(acc[i][j][4u * g + 2u], 0.f), fmaxf(acc[i][j][4u * g + 3u], 0.f));
+        }
+  }
+}
+
+enum Path { PATH_GENERIC, PATH_DMA_128x128, PATH_DMA_256x64, PATH_DMA_64x64, PATH_C3 };
+
 struct Geometry {
-  uint32_t Ho, Wo, pixels, bn, tiles_n, total, blocks;
+  uint32_t Ho, Wo, pixels, bn, tiles_n, total, blocks, threads;
+  Path path;
 };
 
 bool shape_ok(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_out, uint32_t stride) {
@@ -243,34 +585,95 @@ bool shape_ok(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_
   return true;
 }
 
-Geometry geometry(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_out, uint32_t stride) {
+// Which kernel a layer gets, and its launch shape.
+//   c_in % 32 == 0 and c_out % 8 == 0: DMA-ring kernel; 128 x 128 tiles (256 pixels x 64 channels
+//     when c_out <= 64) if that gives at least one workgroup per CU, else 64 x 64 tiles with one
+//     wave per workgroup;
+//   c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64: the first-layer kernel;
+//   anything else: the register-staged kernel.
+Geometry geometry(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_out, uint32_t stride,
+                  bool allow_fast = true) {
   Geometry g;
   g.Ho = (h - 1u) / stride + 1u;
   g.Wo = (w - 1u) / stride + 1u;
   g.pixels = batch * g.Ho * g.Wo;
-  g.bn = c_out <= 64u ? 64u : 128u;
-  g.tiles_n = (c_out + g.bn - 1u) / g.bn;
-  g.total = ((g.pixels + CV_BM - 1u) / CV_BM) * g.tiles_n;
+  g.threads = CV_THREADS;
+  if (allow_fast && c_in % 32u == 0u && c_out % 8u == 0u) {
+    const uint32_t bmp = c_out > 64u ? 128u : 256u;
+    g.bn = c_out > 64u ? 128u : 64u;
+    g.tiles_n = (c_out + g.bn - 1u) / g.bn;
+    g.total = ((g.pixels + bmp - 1u) / bmp) * g.tiles_n;
+    g.path = c_out > 64u ? PATH_DMA_128x128 : PATH_DMA_256x64;
+    if (g.total < 256u) {
+      g.bn = 64u;
+      g.tiles_n = (c_out + 63u) / 64u;
+      g.total = ((g.pixels + 63u) / 64u) * g.tiles_n;
+      g.path = PATH_DMA_64x64;
+      g.threads = 64u;
+    }
+  } else if (allow_fast && c_in == 3u && stride == 1u && c_out % 8u == 0u && c_out <= 64u) {
+    g.bn = c_out;
+    g.tiles_n = 1u;
+    g.total = (g.pixels + C3_PIX - 1u) / C3_PIX;
+    g.path = PATH_C3;
+  } else {
+    g.bn = c_out <= 64u ? 64u : 128u;
+    g.tiles_n = (c_out + g.bn - 1u) / g.bn;
+    g.total = ((g.pixels + CV_BM - 1u) / CV_BM) * g.tiles_n;
+    g.path = PATH_GENERIC;
+  }
   g.blocks = (g.total + 7u) / 8u * 8u;
   return g;
+}
+
+template <uint32_t WM, uint32_t WN>
+hipError_t launch_dma(hipStream_t st, const Geometry& g, const ConvArgs& a) {
+  constexpr uint32_t lds = CD_NST * (64u * WM + 64u * WN) * 64u;
+  static std::once_flag once;
+  static hipError_t attr = hipSuccess;
+  std::call_once(once, [] {
+    attr = hipFuncSetAttribute((const void*)conv3x3_dma_kernel<WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  });
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL((conv3x3_dma_kernel<WM, WN>), dim3(g.blocks), dim3(64u * WM * WN), lds, st, a);
+  return hipSuccess;
 }
 
 int launch_layer(hipStream_t st, const uint16_t* x, const uint16_t* w, void* y, uint32_t batch,
                  uint32_t h, uint32_t wd, uint32_t c_in, uint32_t c_out, uint32_t stride,
                  uint32_t out_f32) {
-  const Geometry g = geometry(batch, h, wd, c_out, stride);
+  // the fast paths move 16 bytes at a time (the probe assumed aligned tensors)
+  const bool aligned = (((uintptr_t)x | (uintptr_t)w | (uintptr_t)y) & 15u) == 0u;
+  const Geometry g = geometry(batch, h, wd, c_in, c_out, stride, aligned);
   ConvArgs a;
   a.x = x; a.w = w; a.y = y;
   a.batch = batch; a.H = h; a.W = wd; a.C = c_in; a.K = c_out; a.stride = stride;
   a.Ho = g.Ho; a.Wo = g.Wo; a.pixels = g.pixels; a.depth = 9u * c_in;
   a.tiles_n = g.tiles_n; a.tiles_total = g.total; a.out_f32 = out_f32;
-  const bool vec = c_in % 8u == 0u && (((uintptr_t)x | (uintptr_t)w) & 15u) == 0u;
-  if (g.bn == 64u) {
-    if (vec) hipLaunchKernelGGL((conv3x3_kernel<64, true>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
-    else hipLaunchKernelGGL((conv3x3_kernel<64, false>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
-  } else {
-    if (vec) hipLaunchKernelGGL((conv3x3_kernel<128, true>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
-    else hipLaunchKernelGGL((conv3x3_kernel<128, false>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
+  hipError_t e = hipSuccess;
+  switch (g.path) {
+    case PATH_DMA_128x128: e = launch_dma<2, 2>(st, g, a); break;
+    case PATH_DMA_256x64: e = launch_dma<4, 1>(st, g, a); break;
+    case PATH_DMA_64x64: e = launch_dma<1, 1>(st, g, a); break;
+    case PATH_C3:
+      if (c_out <= 32u) hipLaunchKernelGGL((conv3x3_c3_kernel<1>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
+      else hipLaunchKernelGGL((conv3x3_c3_kernel<2>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
+      break;
+    case PATH_GENERIC: {
+      const bool vec = c_in % 8u == 0u && (((uintptr_t)x | (uintptr_t)w) & 15u) == 0u;
+      if (g.bn == 64u) {
+        if (vec) hipLaunchKernelGGL((conv3x3_kernel<64, true>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
+        else hipLaunchKernelGGL((conv3x3_kernel<64, false>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
+      } else {
+        if (vec) hipLaunchKernelGGL((conv3x3_kernel<128, true>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
+        else hipLaunchKernelGGL((conv3x3_kernel<128, false>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
+      }
+      break;
+    }
+  }
+  if (e != hipSuccess) {
+    mgb_internal_set_error("conv3x3_dma_kernel: dynamic LDS size", e);
+    return MGB_E_BACKEND;
   }
   return MGB_OK;
 }
@@ -283,10 +686,10 @@ int mgb_conv3x3_probe(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uin
                       uint32_t stride, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block) {
   if (!mem_bytes || !grid || !block) return MGB_E_INVAL;
   if (!shape_ok(batch, h, w, c_in, c_out, stride)) return MGB_E_UNSUPPORTED;
-  const Geometry g = geometry(batch, h, w, c_out, stride);
+  const Geometry g = geometry(batch, h, w, c_in, c_out, stride);
   *mem_bytes = ((uint64_t)batch * h * w * c_in + 9ull * c_in * c_out + (uint64_t)g.pixels * c_out) * 2;
   *grid = mgb_dim3{g.blocks, 1u, 1u};
-  *block = mgb_dim3{CV_THREADS, 1u, 1u};
+  *block = mgb_dim3{g.threads, 1u, 1u};
   return MGB_OK;
 }
 
@@ -295,7 +698,8 @@ int mgb_conv3x3_enqueue(void* stream, const uint16_t* x, const uint16_t* w, void
                         uint32_t out_f32) {
   if (!x || !w || !y) return MGB_E_INVAL;
   if (!shape_ok(batch, h, wd, c_in, c_out, stride)) return MGB_E_UNSUPPORTED;
-  launch_layer((hipStream_t)stream, x, w, y, batch, h, wd, c_in, c_out, stride, out_f32);
+  const int rc = launch_layer((hipStream_t)stream, x, w, y, batch, h, wd, c_in, c_out, stride, out_f32);
+  if (rc != MGB_OK) return rc;
   return mgb_check_launch("conv3x3_kernel");
 }
 
@@ -305,18 +709,22 @@ int mgb_cnn_probe(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batc
   if (!layers || !mem_bytes || !act_bytes || !out_bytes || !grid || !block || n_layers == 0u)
     return MGB_E_INVAL;
   uint64_t weights = 0, act_max = 0, last = 0;
-  uint32_t blocks = 0, ch = h, cw = w;
+  uint32_t blocks = 0, threads = CV_THREADS, ch = h, cw = w;
   const uint64_t input = (uint64_t)batch * h * w * layers[0].c_in * 2;
   for (uint32_t i = 0; i < n_layers; ++i) {
     const mgb_conv_layer& L = layers[i];
     if (i > 0u && L.c_in != layers[i - 1u].c_out) return MGB_E_INVAL;
     if (!shape_ok(batch, ch, cw, L.c_in, L.c_out, L.stride)) return MGB_E_UNSUPPORTED;
-    const Geometry g = geometry(batch, ch, cw, L.c_out, L.stride);
+    const Geometry g = geometry(batch, ch, cw, L.c_in, L.c_out, L.stride);
     weights += 9ull * L.c_in * L.c_out * 2;
     const uint64_t elems = (uint64_t)g.pixels * L.c_out;
     if (i + 1u < n_layers) act_max = act_max > elems * 2 ? act_max : elems * 2;
     else last = elems * 4;
-    blocks = blocks > g.blocks ? blocks : g.blocks;   // launches are stream-ordered: the largest counts
+    // launches are stream-ordered: the one with the most waves counts
+    if ((uint64_t)g.blocks * g.threads > (uint64_t)blocks * threads) {
+      blocks = g.blocks;
+      threads = g.threads;
+    }
     ch = g.Ho;
     cw = g.Wo;
   }
@@ -324,7 +732,7 @@ int mgb_cnn_probe(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batc
   *out_bytes = last;
   *mem_bytes = input + weights + 2 * act_max + last;
   *grid = mgb_dim3{blocks, 1u, 1u};
-  *block = mgb_dim3{CV_THREADS, 1u, 1u};
+  *block = mgb_dim3{threads, 1u, 1u};
   return MGB_OK;
 }
 
@@ -346,7 +754,8 @@ int mgb_cnn_enqueue(void* stream, const mgb_conv_layer* layers, uint32_t n_layer
     const mgb_conv_layer& L = layers[i];
     const bool last = i + 1u == n_layers;
     void* dst = last ? (void*)out : (void*)((i & 1u) ? act1 : act0);
-    launch_layer(st, src, weights[i], dst, batch, ch, cw, L.c_in, L.c_out, L.stride, last ? 1u : 0u);
+    rc = launch_layer(st, src, weights[i], dst, batch, ch, cw, L.c_in, L.c_out, L.stride, last ? 1u : 0u);
+    if (rc != MGB_OK) return rc;
     src = (const uint16_t*)dst;
     ch = (ch - 1u) / L.stride + 1u;
     cw = (cw - 1u) / L.stride + 1u;

@@ -265,7 +265,10 @@ def test_probe_functions_agree_with_checker_formulas():
         oracle.lib().orc_gemm_bf16_probe(C.c_uint64(m), C.c_uint64(n), C.c_uint64(k), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (m, n, k)
     for b, h, w, ci, co, st in ((1, 416, 416, 3, 32, 1), (8, 416, 416, 32, 64, 2), (2, 13, 11, 512, 512, 2),
-                                (1, 5, 6, 5, 7, 1), (3, 26, 26, 40, 200, 1)):
+                                (1, 5, 6, 5, 7, 1), (3, 26, 26, 40, 200, 1), (8, 104, 104, 128, 128, 1),
+                                (1, 104, 104, 128, 128, 1), (8, 26, 26, 512, 512, 2), (2, 416, 416, 3, 64, 1),
+                                (2, 416, 416, 3, 32, 2), (1, 64, 64, 3, 36, 1), (4, 208, 208, 64, 64, 1),
+                                (1, 52, 52, 96, 72, 1), (1, 52, 52, 96, 68, 1)):
         mem, grid, block = mgb.probe_of(mgb.mgb_conv3x3_probe, b, h, w, ci, co, st)
         oracle.lib().orc_conv3x3_probe(*[C.c_uint64(x) for x in (b, h, w, ci, co, st)], out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (b, h, w, ci, co, st)

@@ -236,7 +236,14 @@ def _conv_inputs(seed, n, h, wd, c, k, sigma=0.2):
 @pytest.mark.parametrize("n,h,wd,c,k,stride", [
     (1, 8, 8, 3, 32, 1), (2, 13, 11, 3, 32, 2), (1, 16, 16, 8, 64, 1), (1, 17, 9, 32, 64, 2),
     (3, 12, 12, 64, 128, 1), (1, 26, 26, 40, 200, 2), (2, 7, 7, 128, 256, 1), (1, 5, 6, 5, 7, 1),
-    (1, 1, 1, 8, 8, 1), (1, 40, 40, 16, 48, 2)])
+    (1, 1, 1, 8, 8, 1), (1, 40, 40, 16, 48, 2),
+    # 3-channel first layer: several workgroups with a ragged tail, rows shorter and longer than a
+    # workgroup's 256 pixels, two images, 64 channels
+    (1, 40, 37, 3, 32, 1), (2, 9, 300, 3, 64, 1), (1, 3, 3, 3, 8, 1),
+    # DMA ring, 64 x 64 tiles: ragged pixels and channels, c_in = 32 (one tile per tap) and 96
+    (1, 1, 1, 32, 8, 1), (2, 9, 7, 96, 72, 2), (1, 20, 20, 256, 512, 1),
+    # DMA ring, 128 x 128 and 256 x 64 tiles (at least 256 workgroups), stride 1 and 2, ragged tails
+    (2, 130, 127, 32, 136, 1), (3, 150, 151, 32, 64, 1), (5, 141, 150, 64, 40, 2)])
 def test_conv_layer_fp32_and_bf16_outputs(n, h, wd, c, k, stride):
     x, w = _conv_inputs(n * 100 + c, n, h, wd, c, k)
     ref = oracle.conv3x3_relu(x, w, stride)
@@ -248,9 +255,15 @@ def test_conv_layer_fp32_and_bf16_outputs(n, h, wd, c, k, stride):
     want16 = oracle.round_bf16(ref)
     assert frobenius_rel(W.bf16_bits_to_f32(got16), ref) <= 1e-2
     # the rounding decision is taken from an fp32 value on both sides: at most one bf16 step apart,
-    # and only where the fp32 accumulations straddle a rounding boundary
+    # and only where the fp32 accumulations straddle a rounding boundary.  A sum that cancels to
+    # nearly zero keeps the absolute error of its terms (fp32 accumulation: a few 2^-24 of
+    # sum |x||w|), which there is many steps of the tiny result: such entries are held to that
+    # absolute bound instead.
     diff = np.abs(got16.astype(np.int32) - want16.astype(np.int32))
-    assert diff.max() <= 1 and (diff != 0).mean() <= 0.01
+    mag = oracle.conv3x3_relu(x, W.f32_to_bf16_bits(np.abs(W.bf16_bits_to_f32(w))), stride)   # sum |x||w| (x >= 0)
+    far = diff > 1
+    assert (np.abs(W.bf16_bits_to_f32(got16).astype(np.float64) - ref)[far] <= 1e-5 * mag[far]).all()
+    assert far.mean() <= 1e-3 and (diff != 0).mean() <= 0.01
 
 
 def _layer_structs(layers):
@@ -291,8 +304,9 @@ def test_cnn_ten_layer_chain_reduced_image():
     assert got.shape == ref.shape == (2, 4, 4, 512)
     assert np.linalg.norm(ref) > 0
     assert frobenius_rel(got, ref) <= 1e-2
-    # geometry of the task = the largest launch (layer 1: 2*104*104 pixels / 128 per workgroup)
-    assert (g.x, b.x) == (176, 256)        # ceil(169 / 8) * 8
+    # geometry of the task = the launch with the most threads: the first layer, 256 pixels per
+    # 256-thread workgroup (2*104*104 / 256 = 84.5 -> 85, rounded up to a multiple of 8)
+    assert (g.x, b.x) == (88, 256)
 
 
 def test_cnn_full_size_layers_sampled():
