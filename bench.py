@@ -183,7 +183,7 @@ def main():
                vs_baseline=None, dtype="f32", data="synthetic",
                config=dict(workload="%s: %s" % (spec["name"], ", ".join(sorted({t.kind for t in spec["tasks"]}))),
                            policy=args.policy, queue=args.queue, tasks=n_tasks, workers=min(n_tasks, harness.MAX_WORKERS),
-                           cap_bytes=cap, granule_cus=8, n_cu=256),
+                           cap_bytes=cap, granule_cus=int(sched.desc.granule_cus), n_cu=256),
                mean_turnaround_ms=round(mean_turn, 3),
                mean_wait_ms=round(sum(s["mean_wait_ms"] for s in sums) / len(sums), 3),
                input_gen_s=round(t_gen, 1), stream_copy_gbps=round(copy_gbps, 1))

@@ -71,7 +71,7 @@ typedef struct { uint32_t x, y, z; } mgb_dim3;
 typedef struct {
   uint64_t mem_cap_bytes;      /* ledger capacity                           */
   uint32_t n_cu;               /* 256                                       */
-  uint32_t granule_cus;        /* 8                                         */
+  uint32_t granule_cus;        /* 32 (a multiple of 8 with the HIP backend) */
   uint32_t wave_size;          /* 64                                        */
   uint32_t max_waves_per_cu;   /* 32                                        */
   uint32_t max_wg_per_cu;      /* 32                                        */
@@ -79,7 +79,7 @@ typedef struct {
   uint32_t queue_mode;         /* MGB_QUEUE_*                               */
   uint32_t backend;            /* MGB_BACKEND_*                             */
   int32_t  device;             /* HIP device ordinal (HIP backend)          */
-  uint32_t max_running;        /* most tasks resident at once, 0 = no limit (16) */
+  uint32_t max_running;        /* most tasks resident at once, 0 = no limit (8) */
 } mgb_device_desc;
 
 /* Answer to a probe.  `stream` is a hipStream_t owned by the library (NULL
@@ -136,9 +136,11 @@ typedef struct {
 } mgb_trace_rec;
 
 /* ---- scheduler ----------------------------------------------------------
- * Fill `out` with the defaults for one MI355X: 256 CUs in granules of 8,
- * 64-lane waves, 32 waves and 32 workgroups per CU, cap 288e9 bytes, HARD,
- * BACKFILL, HIP backend, device 0, at most 16 resident tasks.                */
+ * Fill `out` with the defaults for one MI355X: 256 CUs in granules of 32
+ * (8 granules, 15 possible partitions), 64-lane waves, 32 waves and 32
+ * workgroups per CU, cap 288e9 bytes, HARD, BACKFILL, HIP backend, device 0,
+ * at most 8 resident tasks.  granule_cus may be any multiple of 8 that
+ * divides n_cu (8 = one CU in every XCD, the finest partition).              */
 void mgb_device_desc_default(mgb_device_desc* out);
 
 /* Create a scheduler for one device.  Errors: MGB_E_INVAL (bad descriptor),

@@ -7,12 +7,14 @@
 // that are handed out exclusively (HARD) and realised as CU-masked streams.
 //
 // Partitions are buddy blocks (power-of-two runs of granules, aligned to their
-// size).  That keeps the set of CU masks small (63 for 32 granules), which
-// matters because a masked stream is a hardware queue: creating one costs
-// milliseconds, and beyond about 24 live queues the device time-slices them and
-// every launch slows down a hundredfold.  The library therefore keeps few
-// masked streams alive, reuses them by mask, never lets more than max_running
-// tasks be resident, and creates the masks of the large blocks up front.
+// size).  That keeps the set of CU masks small (15 for the default 8 granules
+// of 32 CUs, 63 for 32 granules of 8), which matters because a masked stream is
+// a hardware queue: creating one costs milliseconds, and beyond about 24 live
+// queues the device time-slices them and every launch slows down a hundredfold.
+// The library therefore keeps few masked streams alive, reuses them by mask,
+// never lets more than max_running tasks be resident, creates the masks of the
+// large blocks up front, and creates the others on first use with the scheduler
+// lock released, so that only the task that needs a new queue waits for it.
 #include "../../include/mgb.h"
 #include "launch_util.h"
 
@@ -88,6 +90,7 @@ struct mgb_sched {
   // backend: idle masked streams (mask, stream, when last used), idle timing events
   struct IdleStream { uint32_t mask; hipStream_t stream; uint64_t stamp; };
   std::vector<IdleStream> idle_streams;
+  std::unordered_map<hipStream_t, uint32_t> stream_users;   // bound streams -> resident tasks on them
   uint64_t stamp = 0;
   std::vector<hipEvent_t> idle_events;
   uint32_t n_streams = 0;   // created so far
@@ -224,16 +227,8 @@ struct mgb_sched {
   }
 
   // ---- backend -----------------------------------------------------------
+  // Create a masked stream.  Touches no scheduler state: callable without the lock.
   int create_stream(uint32_t gmask, hipStream_t* out) {
-    // make room first: idle streams of other masks are the cheapest thing to give up
-    while (!idle_streams.empty() && g_live_streams.load() >= kStreamsAlive) {
-      size_t victim = 0;
-      for (size_t i = 1; i < idle_streams.size(); ++i)
-        if (idle_streams[i].stamp < idle_streams[victim].stamp) victim = i;
-      (void)hipStreamDestroy(idle_streams[victim].stream);
-      idle_streams.erase(idle_streams.begin() + (long)victim);
-      --g_live_streams;
-    }
     uint32_t cu[8];
     cu_mask_of(gmask, cu);
     hipError_t e = hipSetDevice(d.device);
@@ -243,25 +238,77 @@ struct mgb_sched {
       *out = nullptr;
       return MGB_E_BACKEND;
     }
-    ++n_streams;
     ++g_live_streams;
     return MGB_OK;
   }
 
-  int bind_stream(Task& t) {
+  // Give the task a stream of its mask and two timing events.  A cached idle stream is taken
+  // under the lock.  On a miss at the process's limit of live queues, a task whose mask is
+  // already in use by a resident task (overlapping placements: SOFT, CG) runs behind that task
+  // on its queue, the same CUs, in order, instead of paying for a new queue; otherwise the queue
+  // is created (the least recently used idle one destroyed first when at the limit) with the
+  // lock released: those runtime calls take milliseconds and only this task should wait for them.
+  int bind_stream(Task& t, std::unique_lock<std::mutex>& lk) {
     if (d.backend != MGB_BACKEND_HIP) return MGB_OK;
-    if (t.stream) return MGB_OK;
-    for (size_t i = 0; i < idle_streams.size(); ++i)
-      if (idle_streams[i].mask == t.granted) {
-        t.stream = idle_streams[i].stream;
-        idle_streams.erase(idle_streams.begin() + (long)i);
-        break;
-      }
-    if (!t.stream) {
-      int rc = create_stream(t.granted, &t.stream);
-      if (rc != MGB_OK) return rc;
+    Task* tp = &t;
+    if (!tp->stream) {
+      for (size_t i = 0; i < idle_streams.size(); ++i)
+        if (idle_streams[i].mask == tp->granted) {
+          tp->stream = idle_streams[i].stream;
+          idle_streams.erase(idle_streams.begin() + (long)i);
+          stream_users[tp->stream] = 1;
+          break;
+        }
     }
-    for (hipEvent_t* ev : {&t.ev_start, &t.ev_stop}) {
+    if (!tp->stream && g_live_streams.load() >= kStreamsAlive) {
+      hipStream_t share = nullptr;
+      uint32_t fewest = 0;
+      for (auto& kv : tasks) {
+        const Task& o = kv.second;
+        if (&o == tp || !o.stream || o.state != State::Running || o.granted != tp->granted) continue;
+        const uint32_t users = stream_users[o.stream];
+        if (!share || users < fewest) {
+          share = o.stream;
+          fewest = users;
+        }
+      }
+      if (share) {
+        tp->stream = share;
+        ++stream_users[share];
+      }
+    }
+    if (!tp->stream) {
+      hipStream_t victim = nullptr;
+      if (!idle_streams.empty() && g_live_streams.load() >= kStreamsAlive) {
+        size_t v = 0;
+        for (size_t i = 1; i < idle_streams.size(); ++i)
+          if (idle_streams[i].stamp < idle_streams[v].stamp) v = i;
+        victim = idle_streams[v].stream;
+        idle_streams.erase(idle_streams.begin() + (long)v);
+      }
+      const uint32_t mask = tp->granted;
+      const uint64_t ticket = tp->ticket;
+      lk.unlock();
+      if (victim) {
+        (void)hipStreamDestroy(victim);
+        --g_live_streams;
+      }
+      hipStream_t st = nullptr;
+      const int rc = create_stream(mask, &st);
+      lk.lock();
+      if (rc != MGB_OK) return rc;
+      ++n_streams;
+      auto it = tasks.find(ticket);
+      if (it == tasks.end()) {                       // the task went away meanwhile: keep the queue for later
+        idle_streams.push_back({mask, st, ++stamp});
+        return MGB_E_UNKNOWN_TICKET;
+      }
+      tp = &it->second;
+      tp->stream = st;
+      stream_users[st] = 1;
+    }
+    for (hipEvent_t* ev : {&tp->ev_start, &tp->ev_stop}) {
+      if (*ev) continue;
       if (!idle_events.empty()) {
         *ev = idle_events.back();
         idle_events.pop_back();
@@ -277,20 +324,25 @@ struct mgb_sched {
   }
 
   void unbind_stream(Task& t) {
-    if (t.stream) idle_streams.push_back({t.granted, t.stream, ++stamp});
+    if (t.stream && --stream_users[t.stream] == 0u) {
+      stream_users.erase(t.stream);
+      idle_streams.push_back({t.granted, t.stream, ++stamp});
+    }
     if (t.ev_start) idle_events.push_back(t.ev_start);
     if (t.ev_stop) idle_events.push_back(t.ev_stop);
     t.stream = nullptr;
     t.ev_start = t.ev_stop = nullptr;
   }
 
-  int fill(Task& t, mgb_placement* out) {
-    int rc = bind_stream(t);
+  int fill(Task& t, mgb_placement* out, std::unique_lock<std::mutex>& lk) {
     out->ticket = t.ticket;
     out->granule_mask = t.granted;
     out->n_granules = t.demand;
     cu_mask_of(t.granted, out->cu_mask);
-    out->stream = (void*)t.stream;
+    const uint64_t ticket = t.ticket;
+    int rc = bind_stream(t, lk);                     // may release and retake the lock
+    auto it = tasks.find(ticket);
+    out->stream = it == tasks.end() ? nullptr : (void*)it->second.stream;
     return rc;
   }
 };
@@ -304,7 +356,7 @@ void mgb_device_desc_default(mgb_device_desc* out) {
   std::memset(out, 0, sizeof *out);
   out->mem_cap_bytes = 288ull * 1000 * 1000 * 1000;
   out->n_cu = 256;
-  out->granule_cus = 8;
+  out->granule_cus = 32;
   out->wave_size = 64;
   out->max_waves_per_cu = 32;
   out->max_wg_per_cu = 32;
@@ -312,7 +364,7 @@ void mgb_device_desc_default(mgb_device_desc* out) {
   out->queue_mode = MGB_QUEUE_BACKFILL;
   out->backend = MGB_BACKEND_HIP;
   out->device = 0;
-  out->max_running = 16;
+  out->max_running = 8;
 }
 
 int mgb_sched_create(const mgb_device_desc* desc, mgb_sched** out) {
@@ -363,6 +415,7 @@ int mgb_sched_create(const mgb_device_desc* desc, mgb_sched** out) {
           mgb_sched_destroy(s);
           return MGB_E_BACKEND;
         }
+        ++s->n_streams;
         s->idle_streams.push_back({mgb_sched::block_bits(b) << start, st, ++s->stamp});
       }
   }
@@ -391,7 +444,7 @@ int mgb_task_probe(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 
                    mgb_dim3 block, mgb_placement* out) {
   if (!s || !out) return MGB_E_INVAL;
   std::memset(out, 0, sizeof *out);
-  std::lock_guard<std::mutex> lk(s->mu);
+  std::unique_lock<std::mutex> lk(s->mu);
   uint64_t cause = s->log(MGB_EV_PROBE, nullptr, task_id, 0, mem_bytes, grid, block, 0, 0, 0);
   s->trace.back().cause_seq = (uint32_t)cause;
   const uint64_t W = (uint64_t)grid.x * grid.y * grid.z;
@@ -422,7 +475,7 @@ int mgb_task_probe(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 
   const bool behind_queue = s->d.queue_mode == MGB_QUEUE_FIFO && !s->waitq.empty();
   if (!behind_queue && s->try_admit(ref)) {
     s->log(MGB_EV_ADMIT, &ref, 0, 0, 0, {}, {}, ref.granted, 0, cause);
-    return s->fill(ref, out);
+    return s->fill(ref, out, lk);
   }
   if (!behind_queue && s->oom) {
     s->log(MGB_EV_REJECT, &ref, 0, 0, 0, {}, {}, 0, MGB_E_OOM, cause);
@@ -458,7 +511,7 @@ int mgb_task_wait(mgb_sched* s, uint64_t ticket, int64_t timeout_ns, mgb_placeme
   }
   auto it = s->tasks.find(ticket);
   if (it == s->tasks.end()) return collect_crash() ? MGB_E_OOM : MGB_E_UNKNOWN_TICKET;  // rejected / cancelled meanwhile
-  return s->fill(it->second, out);
+  return s->fill(it->second, out, lk);
 }
 
 int mgb_task_cancel(mgb_sched* s, uint64_t ticket) {
@@ -490,14 +543,16 @@ int mgb_task_launch(mgb_sched* s, uint64_t ticket, int (*enqueue)(void* stream, 
   hipEvent_t e0 = nullptr, e1 = nullptr;
   bool hip = false;
   {
-    std::lock_guard<std::mutex> lk(s->mu);
+    std::unique_lock<std::mutex> lk(s->mu);
     auto it = s->tasks.find(ticket);
     if (it == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;
     if (it->second.state != State::Running) return MGB_E_BAD_STATE;
     hip = s->d.backend == MGB_BACKEND_HIP;
     if (hip) {
-      int rc = s->bind_stream(it->second);
+      int rc = s->bind_stream(it->second, lk);
       if (rc != MGB_OK) return rc;
+      it = s->tasks.find(ticket);
+      if (it == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;
     }
     stream = it->second.stream;
     e0 = it->second.ev_start;

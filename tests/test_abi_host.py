@@ -30,11 +30,12 @@ def test_struct_layouts_match_header():
     assert C.sizeof(mgb.mgb_placement) == 56
     assert mgb.TRACE_DT.itemsize == 128
     d = mgb.default_desc()
-    assert (d.mem_cap_bytes, d.n_cu, d.granule_cus, d.wave_size) == (288 * 10 ** 9, 256, 8, 64)
+    assert (d.mem_cap_bytes, d.n_cu, d.granule_cus, d.wave_size) == (288 * 10 ** 9, 256, 32, 64)
     assert (d.max_waves_per_cu, d.max_wg_per_cu, d.policy, d.queue_mode) == (32, 32, 0, 0)
 
 
 def _null(**kw):
+    kw.setdefault("granule_cus", 8)      # 32 granules: the finest partition the checker models
     return mgb.Sched(backend=mgb.MGB_BACKEND_NULL, **kw)
 
 
@@ -105,8 +106,8 @@ def test_jacobi_launch_plan_keeps_buffer_parity():
 
 
 def test_resident_task_limit():
-    s = _null(mem_cap_bytes=10 ** 6)                                  # default: 16 resident tasks
-    assert s.desc.max_running == 16
+    assert mgb.default_desc().max_running == 8                        # one per default partition
+    s = _null(mem_cap_bytes=10 ** 6, max_running=16)
     pls = [s.probe(i, 1, (8, 1, 1), (256, 1, 1)) for i in range(17)]
     assert [rc for rc, _ in pls] == [mgb.MGB_OK] * 16 + [mgb.MGB_WAIT]
     assert s.stats().free_granules == 0xFFFF0000                      # granules are free, queues are not

@@ -33,8 +33,9 @@ def test_mix16_full_size_outputs_and_decisions():
     dec = assert_trace_matches_replay(s.desc, trace)
     check_ledger_invariants(s.desc, trace)
     assert (dec["kind"] == oracle.D_ADMIT).sum() == 16
-    # demand the probes carried: GEMM 4096^3 and Jacobi 4096^2 = the whole device, BFS 2^20 = half
-    want = {"gemm_f32": 32, "jacobi": 32, "bfs": 16}
+    # demand the probes carried: GEMM 4096^3 and Jacobi 4096^2 = the whole device (8 granules of
+    # 32 CUs), BFS 2^20 = half
+    want = {"gemm_f32": 8, "jacobi": 8, "bfs": 4}
     for r, t in zip(rec, tasks):
         assert r["granules"] == want[t.spec.kind]
     assert s.destroy() == 0
@@ -43,7 +44,7 @@ def test_mix16_full_size_outputs_and_decisions():
 @pytest.mark.parametrize("policy", [mgb.MGB_POLICY_HARD, mgb.MGB_POLICY_SOFT, mgb.MGB_POLICY_SERIAL])
 def test_mix16_batch_at_t0_all_policies(policy):
     # all 16 probes issued before anything runs (the paper's batch setting): queues must form
-    s, tasks, data, rec = _run(W.mix16(seed=3), use_arrivals=False, policy=policy)
+    s, tasks, data, rec = _run(W.mix16(seed=3), use_arrivals=False, policy=policy, max_running=16)
     for t, d in zip(tasks, data):
         if t.spec.kind != "jacobi":             # Jacobi is covered at full size above
             verify_task_output(t, d)

@@ -28,8 +28,31 @@ def _where(stream, n_blocks=4096):
     return set(out.cpu().numpy().tolist())
 
 
-def test_placements_are_disjoint_sets_of_physical_cus():
+def test_default_partitions_are_eighths_of_the_device():
     s = mgb.Sched()
+    assert s.desc.granule_cus == 32 and s.stats().n_streams == 7      # whole, halves, quarters created up front
+    pls = []
+    for i, wgs in enumerate((8, 512, 1024, 100000)):                  # 1, 64, 128, 256 CUs at 8 workgroups per CU
+        rc, pl = s.probe(i, 1 << 20, (wgs, 1, 1), (256, 1, 1))
+        pls.append((rc, pl))
+    assert [rc for rc, _ in pls] == [mgb.MGB_OK, mgb.MGB_OK, mgb.MGB_OK, mgb.MGB_WAIT]
+    assert [pl.n_granules for _, pl in pls] == [1, 2, 4, 8]
+    assert [pl.granule_mask for _, pl in pls[:3]] == [0x01, 0x0C, 0xF0]
+    sets = [_where(pl.stream) for _, pl in pls[:3]]
+    assert [len(x) for x in sets] == [32, 64, 128]
+    for cus in sets:
+        assert len(set(np.bincount([c >> 8 for c in cus], minlength=8))) == 1     # the same share of every XCD
+    assert not (sets[0] & sets[1]) and not (sets[1] & sets[2]) and not (sets[0] & sets[2])
+    assert s.stats().n_streams == 8                                   # only the one-eighth mask was new
+    assert s.cancel(pls[3][1].ticket) == 0
+    for _, pl in pls[:3]:
+        assert s.complete(pl.ticket) == 0
+    assert_trace_matches_replay(s.desc, s.trace())
+    assert s.destroy() == 0
+
+
+def test_placements_are_disjoint_sets_of_physical_cus():
+    s = mgb.Sched(granule_cus=8)                                      # the finest partition: one CU per XCD
     pls = []
     for i, wgs in enumerate((512, 64, 1024, 8)):                      # 8, 1, 16, 1 granules
         rc, pl = s.probe(i, 1 << 20, (wgs, 1, 1), (256, 1, 1))
