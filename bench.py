@@ -242,9 +242,9 @@ def main():
         sched.destroy()
         sched = None
         sweep = {}
-        for name, pol2, q2, wgcu, ratio in (("soft_backfill", mgb.MGB_POLICY_SOFT, mgb.MGB_QUEUE_BACKFILL, 32, 16),
-                                            ("hard_fifo", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_FIFO, 32, 16),
-                                            ("hard_spread", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_BACKFILL, 1, 16),
+        for name, pol2, q2, wgcu, ratio in (("soft_backfill", mgb.MGB_POLICY_SOFT, mgb.MGB_QUEUE_BACKFILL, 32, 8),
+                                            ("hard_fifo", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_FIFO, 32, 8),
+                                            ("hard_spread", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_BACKFILL, 1, 8),
                                             ("cg_ratio4", mgb.MGB_POLICY_CG, mgb.MGB_QUEUE_BACKFILL, 32, 4)):
             log("policy sweep: " + name)
             s2 = mgb.Sched(policy=pol2, queue_mode=q2, mem_cap_bytes=cap, max_wg_per_cu=wgcu, max_running=ratio)
