@@ -17,7 +17,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--mix", default="mix16", choices=["mix4", "mix16", "cnn8", "mixed128"])
+    ap.add_argument("--mix", default="mix16", choices=["mix4", "mix16", "cnn8", "mixed128", "kinds5"])
     ap.add_argument("--policy", default="hard", choices=["hard", "soft", "serial"])
     ap.add_argument("--queue", default="backfill", choices=["backfill", "fifo"])
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -108,11 +108,13 @@ typedef struct {
 #define MGB_EV_PROBE 0       /* input: a probe arrived (mem, grid, block)   */
 #define MGB_EV_COMPLETE 1    /* input: mgb_task_complete(ticket)            */
 #define MGB_EV_CANCEL 2      /* input: mgb_task_cancel(ticket)              */
+#define MGB_EV_GROW 3        /* input: mgb_task_grow(ticket, extra bytes)   */
 #define MGB_EV_ADMIT 16      /* decision: placed (granule_mask, cu_mask)    */
 #define MGB_EV_QUEUED 17     /* decision: must wait                         */
 #define MGB_EV_REJECT 18     /* decision: refused, `code` says why          */
 #define MGB_EV_RELEASE 19    /* decision: resources credited back           */
 #define MGB_EV_CANCELLED 20  /* decision: waiter removed                    */
+#define MGB_EV_GROWN 21      /* decision: a resident task's footprint grew  */
 
 /* One record per event, in the total order in which the scheduler lock was
  * taken.  Input records carry what the caller passed; decision records carry
@@ -175,6 +177,15 @@ int mgb_task_wait(mgb_sched* s, uint64_t ticket, int64_t timeout_ns, mgb_placeme
 
 /* Remove a queued (not yet admitted) task.  MGB_E_BAD_STATE if it runs.      */
 int mgb_task_cancel(mgb_sched* s, uint64_t ticket);
+
+/* A resident task needs `extra_bytes` more device memory (a later kernel of
+ * the task touches memory objects that were not known at its probe: Sec.
+ * III-A, lazy runtime).  Never blocks -- a resident task that waited for
+ * memory while holding memory could deadlock: MGB_OK and the ledger debited
+ * if the bytes are free now, MGB_E_BUSY (nothing changed) if not,
+ * MGB_E_BAD_STATE for a task that is still queued.  The bytes are credited
+ * back with the rest of the task's footprint at mgb_task_complete.           */
+int mgb_task_grow(mgb_sched* s, uint64_t ticket, uint64_t extra_bytes);
 
 /* Run enqueue(stream, user) on the task's stream, bracketed by timing events
  * (HIP backend).  enqueue must only enqueue work on `stream` (it may

@@ -157,8 +157,8 @@ DECISION_DT = np.dtype([("in_index", "<u4"), ("kind", "<u4"), ("ticket", "<u8"),
                         ("free_bytes", "<u8"), ("granule_mask", "<u4"), ("free_granules", "<u4"),
                         ("demand", "<u4"), ("code", "<i4"), ("cu_mask", "<u4", (8,))])
 
-IN_PROBE, IN_COMPLETE, IN_CANCEL = 0, 1, 2
-D_ADMIT, D_WAIT, D_REJECT, D_RELEASE, D_CANCELLED = 1, 2, 3, 4, 5
+IN_PROBE, IN_COMPLETE, IN_CANCEL, IN_GROW = 0, 1, 2, 3
+D_ADMIT, D_WAIT, D_REJECT, D_RELEASE, D_CANCELLED, D_GROWN = 1, 2, 3, 4, 5, 6
 POL_HARD, POL_SOFT, POL_SERIAL, POL_CG = 0, 1, 2, 3
 Q_BACKFILL, Q_FIFO = 0, 1
 
@@ -190,7 +190,8 @@ def sched_replay(dev, inputs):
 
 
 def make_inputs(events):
-    """events: list of ("probe", task_id, mem, grid, block) | ("complete", ticket) | ("cancel", ticket)."""
+    """events: list of ("probe", task_id, mem, grid, block) | ("complete", ticket) | ("cancel", ticket)
+    | ("grow", ticket, extra_bytes)."""
     arr = np.zeros(len(events), dtype=INPUT_DT)
     for i, ev in enumerate(events):
         if ev[0] == "probe":
@@ -205,6 +206,10 @@ def make_inputs(events):
         elif ev[0] == "cancel":
             arr[i]["kind"] = IN_CANCEL
             arr[i]["id"] = ev[1]
+        elif ev[0] == "grow":
+            arr[i]["kind"] = IN_GROW
+            arr[i]["id"] = ev[1]
+            arr[i]["mem"] = ev[2]
         else:
             raise ValueError(ev[0])
     return arr

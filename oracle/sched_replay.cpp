@@ -31,6 +31,8 @@
 //     counted, never run;
 //   * SERIAL (single-assignment baseline, Sec. IV): one task owns the whole
 //     device at a time;
+//   * a resident task may ask for more memory (GROW): granted iff the bytes are free at that
+//     moment, refused (never queued) otherwise; they return with the task's release;
 //   * on every release the waiting tasks are retried in arrival order.
 #include <cstdint>
 #include <cstring>
@@ -39,11 +41,11 @@
 
 namespace {
 
-enum { IN_PROBE = 0, IN_COMPLETE = 1, IN_CANCEL = 2 };
-enum { D_ADMIT = 1, D_WAIT = 2, D_REJECT = 3, D_RELEASE = 4, D_CANCELLED = 5 };
+enum { IN_PROBE = 0, IN_COMPLETE = 1, IN_CANCEL = 2, IN_GROW = 3 };
+enum { D_ADMIT = 1, D_WAIT = 2, D_REJECT = 3, D_RELEASE = 4, D_CANCELLED = 5, D_GROWN = 6 };
 enum { POL_HARD = 0, POL_SOFT = 1, POL_SERIAL = 2, POL_CG = 3 };
 enum { Q_BACKFILL = 0, Q_FIFO = 1 };
-enum { E_INVAL = -1, E_TOO_BIG = -2, E_UNKNOWN_TICKET = -3, E_BAD_STATE = -4, E_OOM = -8 };
+enum { E_INVAL = -1, E_TOO_BIG = -2, E_UNKNOWN_TICKET = -3, E_BAD_STATE = -4, E_BUSY = -5, E_OOM = -8 };
 
 struct Task {
   uint64_t ticket, task_id, mem, waves;
@@ -266,6 +268,14 @@ int64_t orc_sched_replay(const orc_device* dev, const orc_input* in, uint64_t n_
       waitq.erase(std::find(waitq.begin(), waitq.end(), ticket));
       live.erase(std::find_if(live.begin(), live.end(), [&](const Task& x) { return x.ticket == ticket; }));
       rescan(idx);
+    } else if (ev.kind == IN_GROW) {
+      Task* t = find(ev.id);
+      if (!t) { emit(idx, D_REJECT, nullptr, 0, E_UNKNOWN_TICKET, 0); continue; }
+      if (!t->running) { emit(idx, D_REJECT, t, 0, E_BAD_STATE, 0); continue; }
+      if (ev.mem > free_bytes) { emit(idx, D_REJECT, t, 0, E_BUSY, 0); continue; }
+      free_bytes -= ev.mem;
+      t->mem += ev.mem;
+      emit(idx, D_GROWN, t, t->granted, 0, 0);
     } else {
       emit(idx, D_REJECT, nullptr, 0, E_INVAL, ev.id);
     }

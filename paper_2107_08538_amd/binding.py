@@ -27,8 +27,8 @@ MGB_E_BUSY, MGB_E_BACKEND, MGB_E_UNSUPPORTED, MGB_E_OOM = -5, -6, -7, -8
 MGB_POLICY_HARD, MGB_POLICY_SOFT, MGB_POLICY_SERIAL, MGB_POLICY_CG = 0, 1, 2, 3
 MGB_QUEUE_BACKFILL, MGB_QUEUE_FIFO = 0, 1
 MGB_BACKEND_NULL, MGB_BACKEND_HIP = 0, 1
-MGB_EV_PROBE, MGB_EV_COMPLETE, MGB_EV_CANCEL = 0, 1, 2
-MGB_EV_ADMIT, MGB_EV_QUEUED, MGB_EV_REJECT, MGB_EV_RELEASE, MGB_EV_CANCELLED = 16, 17, 18, 19, 20
+MGB_EV_PROBE, MGB_EV_COMPLETE, MGB_EV_CANCEL, MGB_EV_GROW = 0, 1, 2, 3
+MGB_EV_ADMIT, MGB_EV_QUEUED, MGB_EV_REJECT, MGB_EV_RELEASE, MGB_EV_CANCELLED, MGB_EV_GROWN = 16, 17, 18, 19, 20, 21
 
 
 class mgb_dim3(C.Structure):
@@ -86,6 +86,7 @@ mgb_sched_destroy = _sig("mgb_sched_destroy", C.c_int, _vp)
 mgb_task_probe = _sig("mgb_task_probe", C.c_int, _vp, _u64, _u64, mgb_dim3, mgb_dim3, _P(mgb_placement))
 mgb_task_wait = _sig("mgb_task_wait", C.c_int, _vp, _u64, _i64, _P(mgb_placement))
 mgb_task_cancel = _sig("mgb_task_cancel", C.c_int, _vp, _u64)
+mgb_task_grow = _sig("mgb_task_grow", C.c_int, _vp, _u64, _u64)
 mgb_task_launch = _sig("mgb_task_launch", C.c_int, _vp, _u64, ENQUEUE_FN, _vp)
 mgb_task_sync = _sig("mgb_task_sync", C.c_int, _vp, _u64, _P(C.c_double))
 mgb_task_complete = _sig("mgb_task_complete", C.c_int, _vp, _u64)
@@ -117,7 +118,7 @@ mgb_copy_enqueue = _sig("mgb_copy_enqueue", C.c_int, _vp, _vp, _vp, _u64)
 
 EXPORTS = [
     "mgb_device_desc_default", "mgb_sched_create", "mgb_sched_destroy", "mgb_task_probe",
-    "mgb_task_wait", "mgb_task_cancel", "mgb_task_launch", "mgb_task_sync", "mgb_task_complete",
+    "mgb_task_wait", "mgb_task_cancel", "mgb_task_grow", "mgb_task_launch", "mgb_task_sync", "mgb_task_complete",
     "mgb_sched_stats", "mgb_trace_read", "mgb_trace_dump", "mgb_last_error",
     "mgb_jacobi_probe", "mgb_jacobi_enqueue", "mgb_jacobi_launch_count", "mgb_gemm_f32_probe", "mgb_gemm_f32_enqueue",
     "mgb_gemm_bf16_probe", "mgb_gemm_bf16_enqueue", "mgb_conv3x3_probe", "mgb_conv3x3_enqueue",
@@ -183,6 +184,9 @@ class Sched:
 
     def cancel(self, ticket):
         return mgb_task_cancel(self.h, ticket)
+
+    def grow(self, ticket, extra_bytes):
+        return mgb_task_grow(self.h, ticket, extra_bytes)
 
     def launch(self, ticket, fn):
         """fn(stream_void_p) -> int enqueues the task's kernels."""

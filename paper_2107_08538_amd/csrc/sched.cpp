@@ -536,6 +536,31 @@ int mgb_task_cancel(mgb_sched* s, uint64_t ticket) {
   return MGB_OK;
 }
 
+int mgb_task_grow(mgb_sched* s, uint64_t ticket, uint64_t extra_bytes) {
+  if (!s) return MGB_E_INVAL;
+  std::lock_guard<std::mutex> lk(s->mu);
+  uint64_t cause = s->log(MGB_EV_GROW, nullptr, 0, ticket, extra_bytes, {}, {}, 0, 0, 0);
+  s->trace.back().cause_seq = (uint32_t)cause;
+  auto it = s->tasks.find(ticket);
+  if (it == s->tasks.end()) {
+    s->log(MGB_EV_REJECT, nullptr, 0, ticket, extra_bytes, {}, {}, 0, MGB_E_UNKNOWN_TICKET, cause);
+    return MGB_E_UNKNOWN_TICKET;
+  }
+  Task& t = it->second;
+  if (t.state != State::Running) {
+    s->log(MGB_EV_REJECT, &t, 0, 0, 0, {}, {}, 0, MGB_E_BAD_STATE, cause);
+    return MGB_E_BAD_STATE;
+  }
+  if (extra_bytes > s->free_bytes) {
+    s->log(MGB_EV_REJECT, &t, 0, 0, 0, {}, {}, 0, MGB_E_BUSY, cause);
+    return MGB_E_BUSY;
+  }
+  s->free_bytes -= extra_bytes;
+  t.mem += extra_bytes;
+  s->log(MGB_EV_GROWN, &t, 0, 0, 0, {}, {}, t.granted, 0, cause);
+  return MGB_OK;
+}
+
 int mgb_task_launch(mgb_sched* s, uint64_t ticket, int (*enqueue)(void* stream, void* user),
                     void* user) {
   if (!s || !enqueue) return MGB_E_INVAL;

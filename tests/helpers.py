@@ -6,9 +6,9 @@ import paper_2107_08538_amd as mgb
 
 _KIND = {mgb.MGB_EV_ADMIT: oracle.D_ADMIT, mgb.MGB_EV_QUEUED: oracle.D_WAIT,
          mgb.MGB_EV_REJECT: oracle.D_REJECT, mgb.MGB_EV_RELEASE: oracle.D_RELEASE,
-         mgb.MGB_EV_CANCELLED: oracle.D_CANCELLED}
+         mgb.MGB_EV_CANCELLED: oracle.D_CANCELLED, mgb.MGB_EV_GROWN: oracle.D_GROWN}
 _IN = {mgb.MGB_EV_PROBE: oracle.IN_PROBE, mgb.MGB_EV_COMPLETE: oracle.IN_COMPLETE,
-       mgb.MGB_EV_CANCEL: oracle.IN_CANCEL}
+       mgb.MGB_EV_CANCEL: oracle.IN_CANCEL, mgb.MGB_EV_GROW: oracle.IN_GROW}
 
 
 def oracle_device(desc):

@@ -96,6 +96,22 @@ def test_stuck_task_does_not_block_tasks_that_fit():
         assert list(pl.cu_mask) == [0] * (4 + i // 4) + [0xFF << (8 * (i % 4))] + [0] * (3 - i // 4)
 
 
+def test_grow_in_the_library():
+    s = _null(mem_cap_bytes=1000)
+    rc, p1 = s.probe(1, 400, (4, 1, 1), (64, 1, 1))
+    rc, p2 = s.probe(2, 700, (4, 1, 1), (64, 1, 1))
+    assert rc == mgb.MGB_WAIT
+    assert s.grow(p1.ticket, 500) == mgb.MGB_OK and s.stats().free_bytes == 100
+    assert s.grow(p1.ticket, 101) == mgb.MGB_E_BUSY and s.stats().free_bytes == 100
+    assert s.grow(p2.ticket, 1) == mgb.MGB_E_BAD_STATE
+    assert s.grow(99, 1) == mgb.MGB_E_UNKNOWN_TICKET
+    assert s.complete(p1.ticket) == mgb.MGB_OK
+    rc, pl = s.wait(p2.ticket, 0)
+    assert rc == mgb.MGB_OK and s.stats().free_bytes == 300
+    assert s.complete(p2.ticket) == mgb.MGB_OK and s.stats().free_bytes == 1000
+    assert_trace_matches_replay(s.desc, s.trace())
+
+
 def test_jacobi_launch_plan_keeps_buffer_parity():
     # the result must end in buffer iters % 2, so the number of (fused) launches has that parity
     for it in list(range(0, 40)) + [100, 127, 128, 129, 1000]:
@@ -131,7 +147,9 @@ def test_buddy_blocks_in_the_library():
 def _random_storm(s, rng, n_ops):
     live = []
     for i in range(n_ops):
-        if not live or rng.random() < 0.5:
+        if live and rng.random() < 0.1:
+            s.grow(live[int(rng.integers(0, len(live)))], int(rng.integers(0, 1500)))   # any outcome is fine
+        elif not live or rng.random() < 0.5:
             mem = int(rng.integers(1, 6000))
             grid = (int(rng.integers(0 if rng.random() < 0.02 else 1, 4000)), int(rng.integers(1, 3)), 1)
             block = (int(rng.choice([64, 192, 256, 1024])), 1, 1)

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import (D_ADMIT, D_WAIT, D_REJECT, D_RELEASE, D_CANCELLED, POL_HARD, POL_SOFT,
+from oracle import (D_ADMIT, D_WAIT, D_REJECT, D_RELEASE, D_CANCELLED, D_GROWN, POL_HARD, POL_SOFT,
                     POL_SERIAL, POL_CG, Q_BACKFILL, Q_FIFO)
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "sched_hand_case.json")
@@ -349,6 +349,26 @@ def test_cg_ratio_ignores_memory_and_reports_the_crash():
     for d in dec:
         running += int(d["kind"] == D_ADMIT) - int(d["kind"] == D_RELEASE)
         assert running <= 3
+
+
+def test_grow_is_granted_only_from_free_bytes_and_returns_with_the_task():
+    dev = oracle.device(1000)
+    g, b = (4, 1, 1), (64, 1, 1)
+    ev = [("probe", 1, 400, g, b),      # t1 in, 600 free
+          ("probe", 2, 700, g, b),      # t2 waits for memory
+          ("grow", 1, 500),             # 500 <= 600: granted, 100 free
+          ("grow", 1, 101),             # refused, nothing changes
+          ("grow", 2, 1),               # a queued task cannot grow
+          ("grow", 9, 1),               # unknown ticket
+          ("grow", 1, 100),             # exact fit, 0 free
+          ("complete", 1),              # the whole grown footprint (1000) comes back; t2 gets in
+          ("complete", 2)]
+    dec = oracle.sched_replay(dev, oracle.make_inputs(ev))
+    got = [(int(d["in_index"]), int(d["kind"]), int(d["ticket"]), int(d["code"]), int(d["free_bytes"])) for d in dec]
+    assert got == [(0, D_ADMIT, 1, 0, 600), (1, D_WAIT, 2, 0, 600), (2, D_GROWN, 1, 0, 100),
+                   (3, D_REJECT, 1, -5, 100), (4, D_REJECT, 2, -4, 100), (5, D_REJECT, 0, -3, 100),
+                   (6, D_GROWN, 1, 0, 0), (7, D_RELEASE, 1, 0, 1000), (7, D_ADMIT, 2, 0, 300),
+                   (8, D_RELEASE, 2, 0, 1000)]
 
 
 def test_probe_formulas_match_stated_footprints():

@@ -81,6 +81,20 @@ def pressure32(seed=32, scale=1.0):
     return dict(name="Pressure-32", cap_bytes=int(total / 1.5), tasks=tasks)
 
 
+def kinds5(seed=5):
+    """One task of every kind at its full size, all at t=0: Jacobi 4096^2 x100, fp32 GEMM 4096^3,
+    bf16 GEMM 8192^3, the conv net on a batch of 8, BFS on 2^20 vertices.  Not one of the paper's
+    mixes: run serialised, it gives every kernel's time alone on the device."""
+    tasks = [
+        TaskSpec(0, "jacobi", dict(n=4096, iters=100), 0.0, task_seed(seed, 0)),
+        TaskSpec(1, "gemm_f32", dict(m=4096, n=4096, k=4096), 0.0, task_seed(seed, 1)),
+        TaskSpec(2, "gemm_bf16", dict(m=8192, n=8192, k=8192), 0.0, task_seed(seed, 2)),
+        TaskSpec(3, "cnn", dict(batch=8, h=416, w=416), 0.0, task_seed(seed, 3)),
+        TaskSpec(4, "bfs", dict(n=1 << 20, degree=16), 0.0, task_seed(seed, 4)),
+    ]
+    return dict(name="Kinds-5", cap_bytes=288 * 10 ** 9, tasks=tasks)
+
+
 def _logu(u, lo, hi):
     return math.exp(math.log(lo) + u * (math.log(hi) - math.log(lo)))
 
@@ -110,4 +124,4 @@ def mixed128(seed=128, n_tasks=128, shrink=1):
 
 
 MIXES = {"mix4": mix4, "mix16": mix16, "cnn8": cnn8, "pressure32": pressure32,
-         "mixed128": mixed128}
+         "mixed128": mixed128, "kinds5": kinds5}
