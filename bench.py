@@ -88,6 +88,44 @@ def cpu_baseline(spec):
                 mean_turnaround_ms=1e3 * sum(turn) / len(turn), nproc=os.cpu_count())
 
 
+def lazy_leg(mgb, cap):
+    """One fp32 GEMM 1024^3 task built through the lazy runtime (Sec. III-A): host time of each
+    stage.  Host buffers cross PCIe here, unlike the timed region of the bench."""
+    import ctypes as C
+    import numpy as np
+    import workloads as W
+    n = 1024
+    a, b = W.gemm_operands_f32(1, n, n, n)
+    out = np.empty((n, n), np.float32)
+    s = mgb.Sched(mem_cap_bytes=cap)
+    z = mgb.Lazy(s)
+    mem, grid, block = mgb.probe_of(mgb.mgb_gemm_f32_probe, n, n, n)
+    stages = dict(record_ms=0.0, prepare_ms=0.0, kernel_and_copy_back_ms=0.0, free_ms=0.0)
+    reps = 5
+    for rep in range(reps + 1):
+        t0 = time.perf_counter()
+        pa, pb, pc = (z.malloc(n * n * 4)[1] for _ in range(3))
+        z.memcpy_h2d(pa, a.ctypes.data, a.nbytes)
+        z.memcpy_h2d(pb, b.ctypes.data, b.nbytes)
+        t1 = time.perf_counter()
+        rc, real, pl = z.launch_prepare(rep, [pa, pb, pc], grid, block)
+        mgb.check(rc, "mgb_lazy_launch_prepare")
+        t2 = time.perf_counter()
+        mgb.check(mgb.mgb_gemm_f32_enqueue(pl.stream, real[0], real[1], real[2], n, n, n), "mgb_gemm_f32_enqueue")
+        mgb.check(z.memcpy_d2h(out.ctypes.data, pc, out.nbytes), "mgb_lazy_memcpy_d2h")
+        t3 = time.perf_counter()
+        for p in (pa, pb, pc):
+            mgb.check(z.free(p), "mgb_lazy_free")
+        t4 = time.perf_counter()
+        if rep:                                   # the first pass warms the allocator
+            for k, dt in zip(stages, (t1 - t0, t2 - t1, t3 - t2, t4 - t3)):
+                stages[k] += 1e3 * dt / reps
+    z.destroy()
+    s.destroy()
+    return dict(task="gemm_f32 1024^3, 12 MiB footprint discovered at the launch", footprint_bytes=mem,
+                **{k: round(v, 3) for k, v in stages.items()})
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -259,6 +297,8 @@ def main():
             s2.destroy()
         out["other_policies"] = sweep
         ser.destroy()
+        log("lazy runtime")
+        out["lazy_runtime"] = lazy_leg(mgb, cap)
     if not args.no_cpu_baseline:
         log("cpu baseline")
         out["cpu_baseline"] = cpu_baseline(spec)

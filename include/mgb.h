@@ -210,6 +210,65 @@ int mgb_trace_dump(mgb_sched* s, const char* path);
 /* Text of the last backend error seen by this thread ("" if none).          */
 const char* mgb_last_error(void);
 
+/* ---- lazy runtime (Sec. III-A, "Lazy Runtime") ------------------------------
+ * For programs whose allocations, copies and launches cannot be tied to a task
+ * statically.  Device-memory calls are redirected to these: an allocation hands
+ * out a pseudo address and allocates nothing; copies and fills to an object that
+ * is not on the device yet are recorded in the object's queue (a host-to-device
+ * copy keeps the bytes as they are at the call); mgb_lazy_launch_prepare is the
+ * paper's kernelLaunchPrepare.  All pointers are host pointers; pseudo
+ * addresses are opaque 64-bit values (object + byte offset, offsets may be
+ * added by the caller).  An mgb_lazy serves one client: its calls are
+ * serialised, and a launch that waits for admission holds the instance.
+ * Unknown pseudo addresses give MGB_E_UNKNOWN_TICKET, ranges outside an object
+ * MGB_E_INVAL; runtime failures MGB_E_BACKEND (mgb_last_error has the text).    */
+typedef struct mgb_lazy mgb_lazy;
+
+typedef struct {
+  uint64_t n_objects;      /* memory objects alive                            */
+  uint64_t n_bound;        /* of these, on the device                         */
+  uint64_t n_tasks;        /* tasks alive (admitted, some object not freed)   */
+  uint64_t recorded_ops;   /* copies / fills recorded so far                  */
+  uint64_t replayed_ops;   /* of these, replayed at a launch                  */
+  uint64_t staged_bytes;   /* host bytes held for recorded copies right now   */
+} mgb_lazy_stats;
+
+int mgb_lazy_create(mgb_sched* s, mgb_lazy** out);
+/* MGB_E_BUSY while memory objects are alive.                                   */
+int mgb_lazy_destroy(mgb_lazy* z);
+/* Stand-in for a device allocation of `bytes` (< 2^40).                        */
+int mgb_lazy_malloc(mgb_lazy* z, uint64_t bytes, uint64_t* pseudo);
+/* Stand-ins for host-to-device copy and fill.  Recorded if the object is not on
+ * the device yet; otherwise executed on its task's stream, complete on return.  */
+int mgb_lazy_memcpy_h2d(mgb_lazy* z, uint64_t dst_pseudo, const void* src_host, uint64_t bytes);
+int mgb_lazy_memset(mgb_lazy* z, uint64_t dst_pseudo, int value, uint64_t bytes);
+/* Before a kernel launch: `pseudo_args[0..n_args)` are the memory objects the
+ * kernel accesses (n_args >= 1), grid / block its geometry.
+ *  - none of the objects is on the device: a new task.  Its footprint is the
+ *    sum of the objects' sizes; mgb_task_probe(task_id, footprint, grid, block)
+ *    is issued and, if the task is queued, waited for up to timeout_ns (< 0:
+ *    forever; on MGB_TIMEOUT the probe is cancelled and nothing has changed).
+ *  - some are: the launch joins their task (launches that share memory objects
+ *    form one task, Alg. 1); the sizes of the new objects are asked for with
+ *    mgb_task_grow (MGB_E_BUSY: nothing has changed).  Objects of several tasks:
+ *    the task with the oldest ticket absorbs the others and its stream waits
+ *    for theirs.
+ * Then every new object is allocated and its recorded operations are replayed
+ * in order on the task's stream.  real_args[i] receives the device address for
+ * pseudo_args[i]; placement->stream is the stream to launch on (ticket: the
+ * task's first ticket; masks are filled for a new task only).                  */
+int mgb_lazy_launch_prepare(mgb_lazy* z, uint64_t task_id, const uint64_t* pseudo_args, uint32_t n_args,
+                            mgb_dim3 grid, mgb_dim3 block, int64_t timeout_ns, void** real_args,
+                            mgb_placement* placement);
+/* Stand-in for a device-to-host copy; waits for the task's stream first.  For an
+ * object no kernel has used yet the bytes are those the recorded writes left
+ * (unwritten bytes read as zero).                                               */
+int mgb_lazy_memcpy_d2h(mgb_lazy* z, void* dst_host, uint64_t src_pseudo, uint64_t bytes);
+/* Stand-in for freeing a device allocation (pseudo must be the object's base).
+ * Freeing the last object of a task drains its stream and completes it.         */
+int mgb_lazy_free(mgb_lazy* z, uint64_t pseudo);
+int mgb_lazy_stats_get(mgb_lazy* z, mgb_lazy_stats* out);
+
 /* ---- task kernels ---------------------------------------------------------
  * Each task kind has a *probe* -- the requirement derivation a compiler pass
  * would have inserted (Sec. III-A: footprint = sum of the task's allocations,

@@ -87,6 +87,23 @@ mgb_task_probe = _sig("mgb_task_probe", C.c_int, _vp, _u64, _u64, mgb_dim3, mgb_
 mgb_task_wait = _sig("mgb_task_wait", C.c_int, _vp, _u64, _i64, _P(mgb_placement))
 mgb_task_cancel = _sig("mgb_task_cancel", C.c_int, _vp, _u64)
 mgb_task_grow = _sig("mgb_task_grow", C.c_int, _vp, _u64, _u64)
+
+
+class mgb_lazy_stats(C.Structure):
+    _fields_ = [("n_objects", C.c_uint64), ("n_bound", C.c_uint64), ("n_tasks", C.c_uint64),
+                ("recorded_ops", C.c_uint64), ("replayed_ops", C.c_uint64), ("staged_bytes", C.c_uint64)]
+
+
+mgb_lazy_create = _sig("mgb_lazy_create", C.c_int, _vp, C.POINTER(C.c_void_p))
+mgb_lazy_destroy = _sig("mgb_lazy_destroy", C.c_int, _vp)
+mgb_lazy_malloc = _sig("mgb_lazy_malloc", C.c_int, _vp, _u64, C.POINTER(C.c_uint64))
+mgb_lazy_memcpy_h2d = _sig("mgb_lazy_memcpy_h2d", C.c_int, _vp, _u64, _vp, _u64)
+mgb_lazy_memset = _sig("mgb_lazy_memset", C.c_int, _vp, _u64, C.c_int, _u64)
+mgb_lazy_launch_prepare = _sig("mgb_lazy_launch_prepare", C.c_int, _vp, _u64, C.POINTER(C.c_uint64), _u32,
+                               mgb_dim3, mgb_dim3, C.c_int64, C.POINTER(C.c_void_p), C.POINTER(mgb_placement))
+mgb_lazy_memcpy_d2h = _sig("mgb_lazy_memcpy_d2h", C.c_int, _vp, _vp, _u64, _u64)
+mgb_lazy_free = _sig("mgb_lazy_free", C.c_int, _vp, _u64)
+mgb_lazy_stats_get = _sig("mgb_lazy_stats_get", C.c_int, _vp, C.POINTER(mgb_lazy_stats))
 mgb_task_launch = _sig("mgb_task_launch", C.c_int, _vp, _u64, ENQUEUE_FN, _vp)
 mgb_task_sync = _sig("mgb_task_sync", C.c_int, _vp, _u64, _P(C.c_double))
 mgb_task_complete = _sig("mgb_task_complete", C.c_int, _vp, _u64)
@@ -118,7 +135,9 @@ mgb_copy_enqueue = _sig("mgb_copy_enqueue", C.c_int, _vp, _vp, _vp, _u64)
 
 EXPORTS = [
     "mgb_device_desc_default", "mgb_sched_create", "mgb_sched_destroy", "mgb_task_probe",
-    "mgb_task_wait", "mgb_task_cancel", "mgb_task_grow", "mgb_task_launch", "mgb_task_sync", "mgb_task_complete",
+    "mgb_task_wait", "mgb_task_cancel", "mgb_task_grow", "mgb_lazy_create", "mgb_lazy_destroy", "mgb_lazy_malloc",
+    "mgb_lazy_memcpy_h2d", "mgb_lazy_memset", "mgb_lazy_launch_prepare", "mgb_lazy_memcpy_d2h", "mgb_lazy_free",
+    "mgb_lazy_stats_get", "mgb_task_launch", "mgb_task_sync", "mgb_task_complete",
     "mgb_sched_stats", "mgb_trace_read", "mgb_trace_dump", "mgb_last_error",
     "mgb_jacobi_probe", "mgb_jacobi_enqueue", "mgb_jacobi_launch_count", "mgb_gemm_f32_probe", "mgb_gemm_f32_enqueue",
     "mgb_gemm_bf16_probe", "mgb_gemm_bf16_enqueue", "mgb_conv3x3_probe", "mgb_conv3x3_enqueue",
@@ -159,6 +178,53 @@ def probe_of(fn, *shape):
     mem, grid, block = _u64(0), mgb_dim3(), mgb_dim3()
     check(fn(*shape, C.byref(mem), C.byref(grid), C.byref(block)), fn.__name__)
     return int(mem.value), grid, block
+
+
+class Lazy:
+    """Owns one mgb_lazy handle; methods are 1:1 with the C entry points."""
+
+    def __init__(self, sched):
+        h = _vp()
+        check(mgb_lazy_create(sched.h, C.byref(h)), "mgb_lazy_create")
+        self.h = h
+
+    def malloc(self, nbytes):
+        p = C.c_uint64()
+        rc = mgb_lazy_malloc(self.h, nbytes, C.byref(p))
+        return rc, p.value
+
+    def memcpy_h2d(self, dst_pseudo, host_ptr, nbytes):
+        return mgb_lazy_memcpy_h2d(self.h, dst_pseudo, host_ptr, nbytes)
+
+    def memset(self, dst_pseudo, value, nbytes):
+        return mgb_lazy_memset(self.h, dst_pseudo, value, nbytes)
+
+    def launch_prepare(self, task_id, pseudo_args, grid, block, timeout_ns=-1):
+        n = len(pseudo_args)
+        args = (C.c_uint64 * n)(*pseudo_args)
+        real = (C.c_void_p * n)()
+        pl = mgb_placement()
+        grid = grid if isinstance(grid, mgb_dim3) else mgb_dim3(*grid)
+        block = block if isinstance(block, mgb_dim3) else mgb_dim3(*block)
+        rc = mgb_lazy_launch_prepare(self.h, task_id, args, n, grid, block, timeout_ns, real, C.byref(pl))
+        return rc, [int(x or 0) for x in real], pl
+
+    def memcpy_d2h(self, host_ptr, src_pseudo, nbytes):
+        return mgb_lazy_memcpy_d2h(self.h, host_ptr, src_pseudo, nbytes)
+
+    def free(self, pseudo):
+        return mgb_lazy_free(self.h, pseudo)
+
+    def stats(self):
+        st = mgb_lazy_stats()
+        check(mgb_lazy_stats_get(self.h, C.byref(st)), "mgb_lazy_stats_get")
+        return st
+
+    def destroy(self):
+        rc = mgb_lazy_destroy(self.h)
+        if rc == MGB_OK:
+            self.h = None
+        return rc
 
 
 class Sched:
@@ -227,4 +293,4 @@ class Sched:
 
 __all__ = [n for n in dir() if n.startswith(("mgb_", "MGB_"))] + [
     "lib", "LIB_PATH", "TRACE_DT", "ENQUEUE_FN", "EXPORTS", "MgbError", "check", "default_desc",
-    "dev_ptr", "probe_of", "Sched"]
+    "dev_ptr", "probe_of", "Sched", "Lazy"]

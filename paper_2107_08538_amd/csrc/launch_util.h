@@ -13,3 +13,8 @@ static inline int mgb_check_launch(const char* what) {
   mgb_internal_set_error(what, e);
   return -6;                       // MGB_E_BACKEND
 }
+
+// Scheduler facts the other translation units need (the struct itself is private to sched.cpp).
+struct mgb_sched;
+unsigned mgb_internal_backend(const mgb_sched* s);   // MGB_BACKEND_*
+int mgb_internal_device(const mgb_sched* s);         // HIP device ordinal

@@ -347,6 +347,9 @@ struct mgb_sched {
   }
 };
 
+unsigned mgb_internal_backend(const mgb_sched* s) { return s->d.backend; }
+int mgb_internal_device(const mgb_sched* s) { return s->d.device; }
+
 extern "C" {
 
 const char* mgb_last_error(void) { return g_last_error.c_str(); }
