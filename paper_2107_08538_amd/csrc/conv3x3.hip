@@ -16,6 +16,7 @@
 // small batch are bandwidth / latency bound.
 #include "../../include/mgb.h"
 #include "launch_util.h"
+#include "lds_dma.h"
 
 #include <hip/hip_runtime.h>
 
@@ -251,19 +252,6 @@ __global__ __launch_bounds__(CV_THREADS, 2) void conv3x3_kernel(ConvArgs a) {
 //   1 x 1: 64 x 64 tile, one wave per workgroup (layers too small to give every CU a big tile)
 constexpr uint32_t CD_BK = 32, CD_NST = 4;
 
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-constexpr uint32_t vm_wait(uint32_t n) { return (n & 15u) | ((n >> 4) << 14) | 0x0F70u; }   // s_waitcnt vmcnt(n) only
-
-// 16 bytes per lane from global memory straight into LDS at lds_addr + 16 * lane (lds_addr is
-// wave-uniform).  asm, so that the compiler does not serialise later LDS reads behind it;
-// completion is awaited with explicit vmcnt waits.
-__device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_addr) : "memory", "m0");
-}
-// chunk swizzle of a 64-byte LDS row (4 chunks of 16 bytes): 16 consecutive rows read at one
-// logical chunk hit 16 different slots of a 256-byte bank sweep, 8 rows 8 slots of a 128-byte one
-__device__ __forceinline__ uint32_t row_swz(uint32_t row) { return ((row >> 2) & 3u) ^ (((row >> 1) & 1u) << 1); }
-
 template <uint32_t WM, uint32_t WN>
 __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma_kernel(ConvArgs a) {
   constexpr uint32_t NW = WM * WN;
@@ -279,7 +267,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma_kernel(ConvArgs a
   const uint32_t bm = (tile / a.tiles_n) * BMP;
   const uint32_t bn = (tile % a.tiles_n) * BNC;
 
-  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_ptr)smem);
+  const uint32_t lds_base = lds_address_of(smem);
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t wm = (wave / WN) * 64u, wn = (wave % WN) * 64u;

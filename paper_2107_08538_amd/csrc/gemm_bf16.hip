@@ -39,6 +39,7 @@
 // b = B[8*(l/32) .. +7][l % 32], acc[r] = C[8*(r/4) + 4*(l/32) + r%4][l % 32].
 #include "../../include/mgb.h"
 #include "launch_util.h"
+#include "lds_dma.h"
 
 #include <hip/hip_runtime.h>
 
@@ -202,22 +203,6 @@ constexpr uint32_t GD_A_BYTES = GD_BM * GD_BK * 2, GD_B_BYTES = GD_BK * GD_BN * 
 constexpr uint32_t GD_STAGE = GD_A_BYTES + GD_B_BYTES;
 constexpr uint32_t GD_LDS = GD_NST * GD_STAGE;                                        // 128 KiB
 
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-
-// s_waitcnt immediate that waits for vmcnt <= n only
-constexpr uint32_t vm_wait(uint32_t n) { return (n & 15u) | ((n >> 4) << 14) | 0x0F70u; }
-
-// 16 bytes per lane from global memory straight into LDS at lds_addr + 16 * lane (lds_addr is
-// wave-uniform).  Written as asm so that the compiler does not serialise every later LDS read
-// behind it; completion is awaited with explicit vmcnt waits.
-__device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_addr) : "memory", "m0");
-}
-
-// chunk swizzle of an A row (4 chunks of 16 bytes): 16 consecutive rows read at one logical chunk
-// hit 16 different 16-byte slots of a 256-byte bank sweep, 8 consecutive rows 8 different slots
-// of a 128-byte sweep
-__device__ __forceinline__ uint32_t a_swz(uint32_t row) { return ((row >> 2) & 3u) ^ (((row >> 1) & 1u) << 1); }
 // chunk swizzle of a B k-row (32 chunks): the four k rows of one transpose read land in different
 // 64-byte quarters
 __device__ __forceinline__ uint32_t b_swz(uint32_t k) { return (k & 3u) << 2; }
@@ -240,7 +225,7 @@ __global__ __launch_bounds__(GD_THREADS, 1) void gemm_bf16_dma_kernel(const uint
   const uint32_t bm = (GD_BAND * band + in_band % band_rows) * GD_BM;
   const uint32_t bn = (in_band / band_rows) * GD_BN;
 
-  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_ptr)smem);
+  const uint32_t lds_base = lds_address_of(smem);
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t wm = (wave >> 1) * 128u, wn = (wave & 1u) * 128u;
@@ -262,7 +247,7 @@ __global__ __launch_bounds__(GD_THREADS, 1) void gemm_bf16_dma_kernel(const uint
   for (uint32_t h = 0; h < 4; ++h) {
     const uint32_t b = 4u * wave + h;
     const uint32_t ar = 16u * b + (lane >> 2);
-    ga[h] = A + (size_t)min(bm + ar, M - 1u) * K + 8u * ((lane & 3u) ^ a_swz(ar));
+    ga[h] = A + (size_t)min(bm + ar, M - 1u) * K + 8u * ((lane & 3u) ^ row_swz(ar));
     const uint32_t bk = 2u * b + (lane >> 5);
     gb[h] = B + (size_t)bk * N + min(bn + 8u * ((lane & 31u) ^ b_swz(bk)), N - 8u);
   }
@@ -285,7 +270,7 @@ __global__ __launch_bounds__(GD_THREADS, 1) void gemm_bf16_dma_kernel(const uint
 #pragma unroll
     for (uint32_t i = 0; i < 4; ++i) {
       const uint32_t row = wm + 32u * i + l32;
-      a_off[s][i] = row * 64u + (((2u * s + lhi) ^ a_swz(row)) << 4);
+      a_off[s][i] = row * 64u + (((2u * s + lhi) ^ row_swz(row)) << 4);
     }
 #pragma unroll
     for (uint32_t j = 0; j < 4; ++j) {
