@@ -126,6 +126,30 @@ def lazy_leg(mgb, cap):
                 **{k: round(v, 3) for k, v in stages.items()})
 
 
+def ipc_leg(mgb):
+    """Cost of reaching the scheduler through the shared-memory front end (Sec. IV): probe +
+    complete of a small task, through a client connection and directly.  Decisions only (null
+    backend), the client sits in this process; a client in another process pays the same two
+    semaphore hand-offs per call."""
+    s = mgb.Sched(backend=mgb.MGB_BACKEND_NULL)
+    sv = mgb.Server(s, "bench%d" % os.getpid(), 2)
+    c = mgb.Client("bench%d" % os.getpid())
+    n = 2000
+
+    def loop(obj):
+        t0 = time.perf_counter()
+        for i in range(n):
+            rc, pl = obj.probe(i, 1 << 20, (64, 1, 1), (256, 1, 1))
+            obj.complete(pl.ticket)
+        return 1e6 * (time.perf_counter() - t0) / n
+    loop(c)
+    via, direct = loop(c), loop(s)
+    c.disconnect()
+    sv.stop()
+    s.destroy()
+    return dict(probe_plus_complete_us=round(via, 2), in_process_us=round(direct, 2))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -299,6 +323,8 @@ def main():
         ser.destroy()
         log("lazy runtime")
         out["lazy_runtime"] = lazy_leg(mgb, cap)
+        log("multi-process front end")
+        out["ipc_front_end"] = ipc_leg(mgb)
     if not args.no_cpu_baseline:
         log("cpu baseline")
         out["cpu_baseline"] = cpu_baseline(spec)

@@ -269,6 +269,36 @@ int mgb_lazy_memcpy_d2h(mgb_lazy* z, void* dst_host, uint64_t src_pseudo, uint64
 int mgb_lazy_free(mgb_lazy* z, uint64_t pseudo);
 int mgb_lazy_stats_get(mgb_lazy* z, mgb_lazy_stats* out);
 
+/* ---- multi-process front end (Sec. IV: processes reach the scheduler over
+ * shared memory) ---------------------------------------------------------------
+ * Server side: mgb_server_start publishes scheduler `s` under `name` (a POSIX
+ * shared-memory segment "/mgb.<name>", at most 64 client slots) and serves it
+ * with one thread per slot until mgb_server_stop.  The scheduler may use the
+ * null backend: the server only takes decisions.  MGB_E_BUSY if the name is in
+ * use.  A client whose process has died has its queued probes withdrawn and its
+ * resident tasks completed (mgb_server_reclaimed counts such tasks).
+ * Client side (any process): the mgb_client_* calls mirror mgb_task_*; the
+ * placement carries ticket, granules and CU mask, its stream field is NULL.
+ * mgb_client_stream gives the calling process's own CU-masked hipStream_t for
+ * the placement's mask (created on first use, cached, destroyed at
+ * disconnect).  mgb_client_disconnect refuses (MGB_E_BUSY) while the client
+ * still holds tasks.  MGB_E_BACKEND if the server has gone away.               */
+typedef struct mgb_server mgb_server;
+typedef struct mgb_client mgb_client;
+int mgb_server_start(mgb_sched* s, const char* name, uint32_t n_slots, mgb_server** out);
+int mgb_server_stop(mgb_server* sv);
+uint64_t mgb_server_reclaimed(mgb_server* sv);
+int mgb_client_connect(const char* name, mgb_client** out);
+int mgb_client_disconnect(mgb_client* c);
+int mgb_client_probe(mgb_client* c, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 grid, mgb_dim3 block,
+                     mgb_placement* out);
+int mgb_client_wait(mgb_client* c, uint64_t ticket, int64_t timeout_ns, mgb_placement* out);
+int mgb_client_cancel(mgb_client* c, uint64_t ticket);
+int mgb_client_grow(mgb_client* c, uint64_t ticket, uint64_t extra_bytes);
+int mgb_client_complete(mgb_client* c, uint64_t ticket);
+int mgb_client_stats(mgb_client* c, mgb_stats* out);
+int mgb_client_stream(mgb_client* c, const mgb_placement* placement, void** stream);
+
 /* ---- task kernels ---------------------------------------------------------
  * Each task kind has a *probe* -- the requirement derivation a compiler pass
  * would have inserted (Sec. III-A: footprint = sum of the task's allocations,

@@ -137,7 +137,9 @@ EXPORTS = [
     "mgb_device_desc_default", "mgb_sched_create", "mgb_sched_destroy", "mgb_task_probe",
     "mgb_task_wait", "mgb_task_cancel", "mgb_task_grow", "mgb_lazy_create", "mgb_lazy_destroy", "mgb_lazy_malloc",
     "mgb_lazy_memcpy_h2d", "mgb_lazy_memset", "mgb_lazy_launch_prepare", "mgb_lazy_memcpy_d2h", "mgb_lazy_free",
-    "mgb_lazy_stats_get", "mgb_task_launch", "mgb_task_sync", "mgb_task_complete",
+    "mgb_lazy_stats_get", "mgb_server_start", "mgb_server_stop", "mgb_server_reclaimed", "mgb_client_connect",
+    "mgb_client_disconnect", "mgb_client_probe", "mgb_client_wait", "mgb_client_cancel", "mgb_client_grow",
+    "mgb_client_complete", "mgb_client_stats", "mgb_client_stream", "mgb_task_launch", "mgb_task_sync", "mgb_task_complete",
     "mgb_sched_stats", "mgb_trace_read", "mgb_trace_dump", "mgb_last_error",
     "mgb_jacobi_probe", "mgb_jacobi_enqueue", "mgb_jacobi_launch_count", "mgb_gemm_f32_probe", "mgb_gemm_f32_enqueue",
     "mgb_gemm_bf16_probe", "mgb_gemm_bf16_enqueue", "mgb_conv3x3_probe", "mgb_conv3x3_enqueue",
@@ -178,6 +180,83 @@ def probe_of(fn, *shape):
     mem, grid, block = _u64(0), mgb_dim3(), mgb_dim3()
     check(fn(*shape, C.byref(mem), C.byref(grid), C.byref(block)), fn.__name__)
     return int(mem.value), grid, block
+
+
+mgb_server_start = _sig("mgb_server_start", C.c_int, _vp, C.c_char_p, _u32, C.POINTER(C.c_void_p))
+mgb_server_stop = _sig("mgb_server_stop", C.c_int, _vp)
+mgb_server_reclaimed = _sig("mgb_server_reclaimed", C.c_uint64, _vp)
+mgb_client_connect = _sig("mgb_client_connect", C.c_int, C.c_char_p, C.POINTER(C.c_void_p))
+mgb_client_disconnect = _sig("mgb_client_disconnect", C.c_int, _vp)
+mgb_client_probe = _sig("mgb_client_probe", C.c_int, _vp, _u64, _u64, mgb_dim3, mgb_dim3, C.POINTER(mgb_placement))
+mgb_client_wait = _sig("mgb_client_wait", C.c_int, _vp, _u64, C.c_int64, C.POINTER(mgb_placement))
+mgb_client_cancel = _sig("mgb_client_cancel", C.c_int, _vp, _u64)
+mgb_client_grow = _sig("mgb_client_grow", C.c_int, _vp, _u64, _u64)
+mgb_client_complete = _sig("mgb_client_complete", C.c_int, _vp, _u64)
+mgb_client_stats = _sig("mgb_client_stats", C.c_int, _vp, C.POINTER(mgb_stats))
+mgb_client_stream = _sig("mgb_client_stream", C.c_int, _vp, C.POINTER(mgb_placement), C.POINTER(C.c_void_p))
+
+
+class Server:
+    """Publishes a scheduler to other processes; methods are 1:1 with the C entry points."""
+
+    def __init__(self, sched, name, n_slots=16):
+        h = _vp()
+        check(mgb_server_start(sched.h, name.encode(), n_slots, C.byref(h)), "mgb_server_start")
+        self.h = h
+
+    def reclaimed(self):
+        return int(mgb_server_reclaimed(self.h))
+
+    def stop(self):
+        rc = mgb_server_stop(self.h)
+        self.h = None
+        return rc
+
+
+class Client:
+    """One connection to a published scheduler; methods are 1:1 with the C entry points."""
+
+    def __init__(self, name):
+        h = _vp()
+        check(mgb_client_connect(name.encode(), C.byref(h)), "mgb_client_connect")
+        self.h = h
+
+    def probe(self, task_id, mem_bytes, grid, block):
+        grid = grid if isinstance(grid, mgb_dim3) else mgb_dim3(*grid)
+        block = block if isinstance(block, mgb_dim3) else mgb_dim3(*block)
+        pl = mgb_placement()
+        rc = mgb_client_probe(self.h, task_id, mem_bytes, grid, block, C.byref(pl))
+        return rc, pl
+
+    def wait(self, ticket, timeout_ns=-1):
+        pl = mgb_placement()
+        rc = mgb_client_wait(self.h, ticket, timeout_ns, C.byref(pl))
+        return rc, pl
+
+    def cancel(self, ticket):
+        return mgb_client_cancel(self.h, ticket)
+
+    def grow(self, ticket, extra_bytes):
+        return mgb_client_grow(self.h, ticket, extra_bytes)
+
+    def complete(self, ticket):
+        return mgb_client_complete(self.h, ticket)
+
+    def stats(self):
+        st = mgb_stats()
+        check(mgb_client_stats(self.h, C.byref(st)), "mgb_client_stats")
+        return st
+
+    def stream(self, placement):
+        st = C.c_void_p()
+        rc = mgb_client_stream(self.h, C.byref(placement), C.byref(st))
+        return rc, st
+
+    def disconnect(self):
+        rc = mgb_client_disconnect(self.h)
+        if rc == MGB_OK:
+            self.h = None
+        return rc
 
 
 class Lazy:
@@ -293,4 +372,4 @@ class Sched:
 
 __all__ = [n for n in dir() if n.startswith(("mgb_", "MGB_"))] + [
     "lib", "LIB_PATH", "TRACE_DT", "ENQUEUE_FN", "EXPORTS", "MgbError", "check", "default_desc",
-    "dev_ptr", "probe_of", "Sched", "Lazy"]
+    "dev_ptr", "probe_of", "Sched", "Lazy", "Server", "Client"]

@@ -8,10 +8,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmgb.so")
-SOURCES = ["sched.cpp", "lazy.cpp", "jacobi.hip", "gemm_f32.hip", "gemm_bf16.hip", "conv3x3.hip", "bfs.hip", "cu_trace.hip"]
+SOURCES = ["sched.cpp", "lazy.cpp", "ipc.cpp", "jacobi.hip", "gemm_f32.hip", "gemm_bf16.hip", "conv3x3.hip", "bfs.hip", "cu_trace.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-value", "-Wno-unused-command-line-argument"]
+         "-Wno-unused-value", "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
 
 
 def _compile(src):
@@ -34,7 +34,7 @@ def build(verbose=False):
         if verbose and log.strip():
             print(log)
         objs.append(obj)
-    subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs)
+    subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs + ["-lpthread", "-lrt"])
     return LIB
 
 

@@ -14,7 +14,9 @@ constexpr uint32_t vm_wait(uint32_t n) { return (n & 15u) | ((n >> 4) << 14) | 0
 // 16 bytes per lane from global memory straight into LDS at lds_addr + 16 * lane (lds_addr is
 // wave-uniform, no register staging).  Written as asm so that the compiler does not serialise
 // every later LDS read behind it (it would put vmcnt(0) before each one); completion is awaited
-// with explicit vmcnt waits, and the kernel must drain them before it ends.
+// with explicit vmcnt waits, and the kernel must drain them before it ends.  The asm writes M0
+// (the LDS base of the transfer); M0 is reserved by the compiler, which uses it for nothing else
+// in these kernels (the build silences its note that such a clobber is not modelled).
 __device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_addr) : "memory", "m0");
 }

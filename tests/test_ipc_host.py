@@ -1,0 +1,111 @@
+"""Multi-process front end (Sec. IV) without a GPU: clients in threads and in separate processes
+reach one scheduler over shared memory; every decision replays; a dead client's tasks come back."""
+import os
+import subprocess
+import sys
+import threading
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2107_08538_amd as mgb
+from helpers import assert_trace_matches_replay
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CHILD = os.path.join(HERE, "ipc_children.py")
+
+
+def _name(tag):
+    return "t%d_%s" % (os.getpid(), tag)
+
+
+def _sched(**kw):
+    kw.setdefault("granule_cus", 8)
+    return mgb.Sched(backend=mgb.MGB_BACKEND_NULL, **kw)
+
+
+def test_protocol_in_one_process():
+    s = _sched(mem_cap_bytes=1000)
+    name = _name("proto")
+    sv = mgb.Server(s, name, 2)
+    with pytest.raises(mgb.MgbError):
+        mgb.Server(s, name, 2)                               # the name is taken
+    with pytest.raises(mgb.MgbError):
+        mgb.Client(_name("nobody"))
+    c1, c2 = mgb.Client(name), mgb.Client(name)
+    with pytest.raises(mgb.MgbError):
+        mgb.Client(name)                                     # both slots are taken
+    rc, p1 = c1.probe(1, 700, (512, 1, 1), (256, 1, 1))
+    assert rc == mgb.MGB_OK and p1.n_granules == 8 and p1.granule_mask == 0xFF and p1.cu_mask[0] == 0xFFFFFFFF
+    assert p1.stream is None
+    rc, p2 = c2.probe(2, 700, (8, 1, 1), (64, 1, 1))
+    assert rc == mgb.MGB_WAIT
+    assert c2.wait(p2.ticket, 1_000_000)[0] == mgb.MGB_TIMEOUT
+    assert c1.grow(p1.ticket, 300) == mgb.MGB_OK and c1.grow(p1.ticket, 1) == mgb.MGB_E_BUSY
+    assert c2.stats().free_bytes == 0 and c2.stats().n_waiting == 1
+    assert c1.disconnect() == mgb.MGB_E_BUSY                 # still holds a task
+    got = []
+    th = threading.Thread(target=lambda: got.append(c2.wait(p2.ticket)))
+    th.start()
+    time.sleep(0.05)
+    assert c1.complete(p1.ticket) == mgb.MGB_OK
+    th.join(10)
+    assert got and got[0][0] == mgb.MGB_OK and got[0][1].ticket == p2.ticket
+    assert c2.complete(p2.ticket) == mgb.MGB_OK and c2.complete(p2.ticket) == mgb.MGB_E_UNKNOWN_TICKET
+    assert c1.disconnect() == mgb.MGB_OK and c2.disconnect() == mgb.MGB_OK
+    c3 = mgb.Client(name)                                    # a freed slot can be claimed again
+    assert c3.disconnect() == mgb.MGB_OK
+    assert sv.stop() == mgb.MGB_OK
+    assert_trace_matches_replay(s.desc, s.trace())
+    assert s.stats().free_bytes == 1000 and s.destroy() == mgb.MGB_OK
+
+
+def test_independent_processes_share_one_scheduler():
+    s = _sched(mem_cap_bytes=1500)
+    name = _name("procs")
+    sv = mgb.Server(s, name, 8)
+    procs = [subprocess.Popen([sys.executable, CHILD, "storm", name, str(seed), "40"]) for seed in (1, 2, 3, 4)]
+    for p in procs:
+        assert p.wait(timeout=120) == 0
+    assert sv.reclaimed() == 0
+    assert sv.stop() == mgb.MGB_OK
+    tr = s.trace()
+    dec = assert_trace_matches_replay(s.desc, tr)
+    assert (dec["kind"] == oracle.D_ADMIT).sum() == 160 and (dec["kind"] == oracle.D_RELEASE).sum() == 160
+    assert s.stats().free_bytes == 1500 and s.stats().n_running == 0
+    assert s.destroy() == mgb.MGB_OK
+
+
+def test_a_dead_client_gives_everything_back():
+    s = _sched(mem_cap_bytes=1000)
+    name = _name("dead")
+    sv = mgb.Server(s, name, 4)
+    p = subprocess.Popen([sys.executable, CHILD, "hold_and_die", name, "600"], stdout=subprocess.PIPE, text=True)
+    assert p.stdout.readline().strip() == "holding"
+    c = mgb.Client(name)
+    st = c.stats()
+    assert (st.free_bytes, st.n_running, st.n_waiting) == (400, 1, 1)
+    rc, pl = c.probe(1, 900, (8, 1, 1), (64, 1, 1))          # waits behind what the other process holds
+    assert rc == mgb.MGB_WAIT
+    assert p.wait(timeout=30) == 0
+    rc, pl = c.wait(pl.ticket, 5_000_000_000)                # admitted once the server has noticed the death
+    assert rc == mgb.MGB_OK
+    assert sv.reclaimed() == 2                               # one resident task completed, one queued probe withdrawn
+    assert c.complete(pl.ticket) == mgb.MGB_OK and c.disconnect() == mgb.MGB_OK
+    assert sv.stop() == mgb.MGB_OK
+    assert s.stats().free_bytes == 1000 and s.stats().n_running == 0 and s.stats().n_waiting == 0
+    assert_trace_matches_replay(s.desc, s.trace())
+    assert s.destroy() == mgb.MGB_OK
+
+
+def test_clients_notice_a_server_that_stopped():
+    s = _sched(mem_cap_bytes=1000)
+    name = _name("stop")
+    sv = mgb.Server(s, name, 2)
+    c = mgb.Client(name)
+    assert sv.stop() == mgb.MGB_OK
+    rc, pl = c.probe(1, 10, (1, 1, 1), (64, 1, 1))
+    assert rc == mgb.MGB_E_BACKEND
+    assert s.destroy() == mgb.MGB_OK
