@@ -357,6 +357,9 @@ int mgb_cnn_enqueue(void* stream, const mgb_conv_layer* layers, uint32_t n_layer
                     uint16_t* act1, float* out, uint32_t batch, uint32_t h, uint32_t w);
 
 /* Level-synchronous BFS on a CSR graph (row_ptr int32[n+1], col_idx int32[m]).
+ * mgb_bfs_enqueue expects a symmetric graph (every edge stored in both
+ * directions: it may expand a level from the unvisited side);
+ * mgb_bfs_directed_enqueue follows the stored edges as out-edges of any graph.
  * level[v] = hop distance from `source`, -1 if unreachable.  `work` is scratch
  * of mgb_bfs_work_bytes(n) bytes (two frontier queues and per-level counters).
  * The call enqueues batches of level kernels and synchronises the stream
@@ -367,6 +370,8 @@ uint64_t mgb_bfs_work_bytes(uint32_t n);
 int mgb_bfs_probe(uint32_t n, uint64_t m, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block);
 int mgb_bfs_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
                     uint32_t source, int32_t* level, void* work, uint32_t* depth);
+int mgb_bfs_directed_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
+                             uint32_t source, int32_t* level, void* work, uint32_t* depth);
 
 /* Diagnostic: launch n_blocks one-wave workgroups on `stream`; workgroup i
  * stores where it ran in out[i] (device, uint32): (xcd << 8) | (shader engine

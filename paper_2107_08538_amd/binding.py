@@ -130,6 +130,7 @@ mgb_cnn_enqueue = _sig("mgb_cnn_enqueue", C.c_int, _vp, _P(mgb_conv_layer), _u32
 mgb_bfs_work_bytes = _sig("mgb_bfs_work_bytes", _u64, _u32)
 mgb_bfs_probe = _sig("mgb_bfs_probe", C.c_int, _u32, _u64, *_probe_tail)
 mgb_bfs_enqueue = _sig("mgb_bfs_enqueue", C.c_int, _vp, _vp, _vp, _u32, _u32, _vp, _vp, _P(_u32))
+mgb_bfs_directed_enqueue = _sig("mgb_bfs_directed_enqueue", C.c_int, _vp, _vp, _vp, _u32, _u32, _vp, _vp, _P(_u32))
 mgb_cu_trace_enqueue = _sig("mgb_cu_trace_enqueue", C.c_int, _vp, _vp, _u32)
 mgb_copy_enqueue = _sig("mgb_copy_enqueue", C.c_int, _vp, _vp, _vp, _u64)
 
@@ -143,7 +144,7 @@ EXPORTS = [
     "mgb_sched_stats", "mgb_trace_read", "mgb_trace_dump", "mgb_last_error",
     "mgb_jacobi_probe", "mgb_jacobi_enqueue", "mgb_jacobi_launch_count", "mgb_gemm_f32_probe", "mgb_gemm_f32_enqueue",
     "mgb_gemm_bf16_probe", "mgb_gemm_bf16_enqueue", "mgb_conv3x3_probe", "mgb_conv3x3_enqueue",
-    "mgb_cnn_probe", "mgb_cnn_enqueue", "mgb_bfs_work_bytes", "mgb_bfs_probe", "mgb_bfs_enqueue",
+    "mgb_cnn_probe", "mgb_cnn_enqueue", "mgb_bfs_work_bytes", "mgb_bfs_probe", "mgb_bfs_enqueue", "mgb_bfs_directed_enqueue",
     "mgb_cu_trace_enqueue", "mgb_copy_enqueue",
 ]
 

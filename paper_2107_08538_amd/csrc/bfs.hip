@@ -111,7 +111,8 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
                                                         const int32_t* __restrict__ q_in,
                                                         int32_t* __restrict__ q_out,
                                                         uint32_t* __restrict__ ctrl, uint32_t j,
-                                                        int32_t next_level, uint32_t n) {
+                                                        int32_t next_level, uint32_t n,
+                                                        uint32_t symmetric) {
   __shared__ uint32_t s_excl[BFS_WAVES][64];
   __shared__ int32_t s_start[BFS_WAVES][64];
   __shared__ int32_t s_stage[BFS_WAVES][BFS_STAGE];
@@ -134,7 +135,8 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
   const float m = (float)row_ptr[n];      // number of stored (directed) edges
   const float td_cost = (float)n_in * (float)n_in * m;
   const float bu_cost = (float)unvisited * (float)n * (float)n;
-  if (td_cost > bu_cost) {
+  // (bottom-up reads a vertex's stored edges as its in-edges: only right for a symmetric graph)
+  if (symmetric != 0u && td_cost > bu_cost) {
     // bottom-up: two vertices per lane and four neighbours per step in flight, so that the
     // dependent column -> level reads of different vertices and neighbours overlap
     const int32_t cur = next_level - 1;
@@ -276,8 +278,8 @@ int mgb_bfs_probe(uint32_t n, uint64_t m, uint64_t* mem_bytes, mgb_dim3* grid, m
   return MGB_OK;
 }
 
-int mgb_bfs_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
-                    uint32_t source, int32_t* level, void* work, uint32_t* depth) {
+static int bfs_run(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
+                   uint32_t source, int32_t* level, void* work, uint32_t* depth, uint32_t symmetric) {
   if (!row_ptr || !col_idx || !level || !work) return MGB_E_INVAL;
   if (n == 0u || n > 0x7fffffffu || source >= n) return MGB_E_INVAL;
   if ((uintptr_t)work & 255u) return MGB_E_INVAL;
@@ -292,7 +294,7 @@ int mgb_bfs_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx
     for (uint32_t j = 0; j < BFS_BATCH; ++j)
       hipLaunchKernelGGL(bfs_level, dim3(blocks), dim3(BFS_THREADS), 0, st, row_ptr, col_idx, level,
                          w.queue[j & 1u], w.queue[(j + 1u) & 1u], w.ctrl, j,
-                         (int32_t)(levels_done + j + 1u), n);
+                         (int32_t)(levels_done + j + 1u), n, symmetric);
     int rc = mgb_check_launch("bfs_level");
     if (rc != MGB_OK) return rc;
     hipError_t e = hipMemcpyAsync(host_counts, w.ctrl, sizeof host_counts, hipMemcpyDeviceToHost, st);
@@ -312,6 +314,16 @@ int mgb_bfs_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx
     if (levels_done >= n) return MGB_OK;        // cannot happen: depth < n
     hipLaunchKernelGGL(bfs_roll, dim3(1), dim3(64), 0, st, w.ctrl);
   }
+}
+
+int mgb_bfs_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
+                    uint32_t source, int32_t* level, void* work, uint32_t* depth) {
+  return bfs_run(stream, row_ptr, col_idx, n, source, level, work, depth, 1u);
+}
+
+int mgb_bfs_directed_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
+                             uint32_t source, int32_t* level, void* work, uint32_t* depth) {
+  return bfs_run(stream, row_ptr, col_idx, n, source, level, work, depth, 0u);
 }
 
 }  // extern "C"

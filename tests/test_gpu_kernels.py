@@ -345,7 +345,7 @@ def test_conv_rejects_bad_arguments():
 
 
 # ------------------------------------------------------------------ BFS
-def run_bfs(rp, ci, source=0):
+def run_bfs(rp, ci, source=0, directed=False):
     n = rp.size - 1
     RP = torch.from_numpy(rp).to(DEV)
     CI = torch.from_numpy(ci if ci.size else np.zeros(1, np.int32)).to(DEV)
@@ -353,7 +353,8 @@ def run_bfs(rp, ci, source=0):
     work = torch.zeros(mgb.mgb_bfs_work_bytes(n), dtype=torch.uint8, device=DEV)
     depth = u32(0)
     st = torch.cuda.current_stream().cuda_stream
-    rc = mgb.mgb_bfs_enqueue(C.c_void_p(st), P(RP), P(CI), n, source, P(lev), P(work), C.byref(depth))
+    fn = mgb.mgb_bfs_directed_enqueue if directed else mgb.mgb_bfs_enqueue
+    rc = fn(C.c_void_p(st), P(RP), P(CI), n, source, P(lev), P(work), C.byref(depth))
     assert rc == 0, mgb.mgb_last_error()
     sync()
     return lev.cpu().numpy(), depth.value
@@ -378,6 +379,25 @@ def test_bfs_random_graphs_bit_exact(seed, n, deg):
     want = oracle.bfs(rp, ci, 0)
     assert np.array_equal(got, want)
     assert depth == want.max() + 1
+
+
+@pytest.mark.parametrize("seed,n,deg", [(1, 1000, 3), (2, 40000, 2), (3, 200000, 8), (4, 5000, 0.7)])
+def test_bfs_directed_graphs_bit_exact(seed, n, deg):
+    # arcs stored once: reachability is one-way, and expanding a level from the unvisited side
+    # (which reads stored edges as in-edges) would be wrong here
+    rp, ci = W.er_digraph_csr(seed, n, deg)
+    got, depth = run_bfs(rp, ci, source=seed % n, directed=True)
+    ref = oracle.bfs(rp, ci, seed % n)
+    assert np.array_equal(got, ref)
+    assert depth == ref.max() + 1
+    # a one-way chain: only the vertices downstream of the source are reached
+    m = 300
+    rp = np.arange(m + 1, dtype=np.int32)
+    rp[-1] = m - 1
+    ci = np.arange(1, m, dtype=np.int32)
+    got, depth = run_bfs(rp, ci, source=100, directed=True)
+    want = np.where(np.arange(m) >= 100, np.arange(m) - 100, -1).astype(np.int32)
+    assert np.array_equal(got, want) and depth == 200
 
 
 def test_bfs_degenerate_graphs():

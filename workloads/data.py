@@ -53,6 +53,24 @@ def er_graph_csr(seed, n, mean_degree):
     return row_ptr.astype(np.int32), d.astype(np.int32)
 
 
+def er_digraph_csr(seed, n, mean_out_degree):
+    """Directed counterpart: n*mean_out_degree arcs with i.i.d. uniform endpoints, self-loops
+    dropped, duplicates kept, each arc stored once (at its tail), adjacency lists sorted."""
+    m = int(n * mean_out_degree)
+    idx = np.arange(m, dtype=np.uint64)
+    src = (raw64(seed, idx * np.uint64(2)) % np.uint64(n)).astype(np.int64)
+    dst = (raw64(seed, idx * np.uint64(2) + np.uint64(1)) % np.uint64(n)).astype(np.int64)
+    keep = src != dst
+    key = src[keep] * np.int64(n) + dst[keep]
+    key.sort(kind="stable")
+    s = key // n
+    d = key - s * n
+    row_ptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(np.bincount(s, minlength=n), out=row_ptr[1:])
+    assert row_ptr[-1] < 2 ** 31
+    return row_ptr.astype(np.int32), d.astype(np.int32)
+
+
 def cnn_layers(h=416, w=416, c_in=3):
     """Layer table of the 10-layer 3x3 conv+ReLU net: stride alternates 1,2 and
     the channel count doubles on stride-2 layers up to a cap of 512.
