@@ -45,12 +45,19 @@ void orc_gemm_f32_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
   out[4] = 512; out[5] = 1; out[6] = 1;
 }
 
-// bf16 GEMM: bf16 A and B, fp32 C; one 256-thread workgroup per 256 x 256 tile of C when
-// k is a multiple of 32 and n a multiple of 8, per 128 x 256 tile otherwise.
+// bf16 GEMM: bf16 A and B, fp32 C.  When k is a multiple of 32 and n a multiple of 8: one
+// 256-thread workgroup per 256 x 256 tile of C, or per 128 x 128 tile if there would be fewer than
+// 128 of the big ones; otherwise per 128 x 256 tile.
 void orc_gemm_bf16_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
   out[0] = (m * k + k * n) * 2 + m * n * 4;
-  const uint64_t tile_m = (k % 32 == 0 && n % 8 == 0) ? 256 : 128;
-  out[1] = round8(ceil_div(m, tile_m) * ceil_div(n, 256)); out[2] = 1; out[3] = 1;
+  uint64_t wgs;
+  if (k % 32 == 0 && n % 8 == 0) {
+    wgs = ceil_div(m, 256) * ceil_div(n, 256);
+    if (wgs < 128) wgs = ceil_div(m, 128) * ceil_div(n, 128);
+  } else {
+    wgs = ceil_div(m, 128) * ceil_div(n, 256);
+  }
+  out[1] = round8(wgs); out[2] = 1; out[3] = 1;
   out[4] = 256; out[5] = 1; out[6] = 1;
 }
 

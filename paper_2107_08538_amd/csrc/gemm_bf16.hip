@@ -197,21 +197,28 @@ __global__ __launch_bounds__(GB_THREADS, 2) void gemm_bf16_kernel(const uint16_t
       }
 }
 
-// ---- 256 x 256 x 32 tiles, global -> LDS DMA ring ---------------------------------------------
-constexpr uint32_t GD_BM = 256, GD_BN = 256, GD_BK = 32, GD_THREADS = 256, GD_NST = 4, GD_BAND = 4;
-constexpr uint32_t GD_A_BYTES = GD_BM * GD_BK * 2, GD_B_BYTES = GD_BK * GD_BN * 2;   // 16 KiB each
-constexpr uint32_t GD_STAGE = GD_A_BYTES + GD_B_BYTES;
-constexpr uint32_t GD_LDS = GD_NST * GD_STAGE;                                        // 128 KiB
+// ---- global -> LDS DMA ring kernel: 2 x 2 waves of (32 WT) x (32 WT), WT = 4 or 2 -------------
+constexpr uint32_t GD_BK = 32, GD_THREADS = 256, GD_NST = 4, GD_BAND = 4;
+constexpr uint32_t gd_lds_bytes(uint32_t wt) { return GD_NST * (64u * wt * GD_BK * 2u) * 2u; }   // 128 / 64 KiB
 
-// chunk swizzle of a B k-row (32 chunks): the four k rows of one transpose read land in different
-// 64-byte quarters
+// chunk swizzle of a B k-row (16-byte chunks): the four k rows of one transpose read land in
+// different 64-byte quarters
 __device__ __forceinline__ uint32_t b_swz(uint32_t k) { return (k & 3u) << 2; }
 
-__global__ __launch_bounds__(GD_THREADS, 1) void gemm_bf16_dma_kernel(const uint16_t* __restrict__ A,
-                                                                    const uint16_t* __restrict__ B,
-                                                                    float* __restrict__ C, uint32_t M,
-                                                                    uint32_t N, uint32_t K,
-                                                                    uint32_t tiles_n, uint32_t tiles_total) {
+template <uint32_t WT>
+__global__ __launch_bounds__(GD_THREADS, WT == 4u ? 1 : 2) void gemm_bf16_dma_kernel(const uint16_t* __restrict__ A,
+                                                                                   const uint16_t* __restrict__ B,
+                                                                                   float* __restrict__ C, uint32_t M,
+                                                                                   uint32_t N, uint32_t K,
+                                                                                   uint32_t tiles_n,
+                                                                                   uint32_t tiles_total) {
+  constexpr uint32_t BM = 64u * WT, BN = 64u * WT;             // workgroup tile
+  constexpr uint32_t A_BYTES = BM * GD_BK * 2u, B_BYTES = GD_BK * BN * 2u, STAGE = A_BYTES + B_BYTES;
+  constexpr uint32_t ND = BM / 64u;                            // DMA instructions per wave per operand per tile
+  constexpr uint32_t B_ROW = BN * 2u;                          // bytes of a B k-row in LDS
+  constexpr uint32_t B_CPR = BN / 8u;                          // 16-byte chunks of a B k-row
+  constexpr uint32_t NF = 3u * WT;                             // fragment reads per half tile
+  constexpr uint32_t NM = WT * WT;                             // MFMAs per half tile
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
   // XCD-aware tile order (see the fp32 GEMM): bands of GD_BAND tile rows, down the band first.
@@ -222,71 +229,71 @@ __global__ __launch_bounds__(GD_THREADS, 1) void gemm_bf16_dma_kernel(const uint
   const uint32_t band = seq / (GD_BAND * tiles_n);
   const uint32_t band_rows = min(GD_BAND, tiles_m - GD_BAND * band);
   const uint32_t in_band = seq - band * GD_BAND * tiles_n;
-  const uint32_t bm = (GD_BAND * band + in_band % band_rows) * GD_BM;
-  const uint32_t bn = (in_band / band_rows) * GD_BN;
+  const uint32_t bm = (GD_BAND * band + in_band % band_rows) * BM;
+  const uint32_t bn = (in_band / band_rows) * BN;
 
   const uint32_t lds_base = lds_address_of(smem);
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint32_t wm = (wave >> 1) * 128u, wn = (wave & 1u) * 128u;
+  const uint32_t wm = (wave >> 1) * (32u * WT), wn = (wave & 1u) * (32u * WT);
   const uint32_t l32 = lane & 31u, lhi = lane >> 5;
   const uint32_t tq = lane >> 4, ts = lane & 15u;
   const uint32_t tr_row = 8u * (tq >> 1) + (ts >> 2);
   const uint32_t tr_col = 16u * (tq & 1u) + 4u * (ts & 3u);
 
-  // DMA roles: wave w, instruction h fills the 1 KiB block b = 4w + h of the A part and of the B
+  // DMA roles: wave w, instruction h fills the 1 KiB block b = ND*w + h of the A part and of the B
   // part of a stage.
   //   A block b: rows 16b .. 16b+15 (64 bytes each); lane -> row 16b + lane/4, LDS chunk lane%4.
-  //   B block b: k rows 2b, 2b+1 (512 bytes each);   lane -> k 2b + lane/32,  LDS chunk lane%32.
+  //   B block b: 1024 / B_ROW consecutive k rows;    lane -> k row and LDS chunk of its 16 bytes.
   // The lane fetches the global chunk whose swizzled position is its LDS chunk.  Rows beyond M
   // and column chunks beyond N are clamped to the last valid one: what they deliver only feeds
   // entries of C that are never stored.
-  const uint16_t* ga[4];
-  const uint16_t* gb[4];
+  const uint16_t* ga[ND];
+  const uint16_t* gb[ND];
 #pragma unroll
-  for (uint32_t h = 0; h < 4; ++h) {
-    const uint32_t b = 4u * wave + h;
+  for (uint32_t h = 0; h < ND; ++h) {
+    const uint32_t b = ND * wave + h;
     const uint32_t ar = 16u * b + (lane >> 2);
     ga[h] = A + (size_t)min(bm + ar, M - 1u) * K + 8u * ((lane & 3u) ^ row_swz(ar));
-    const uint32_t bk = 2u * b + (lane >> 5);
-    gb[h] = B + (size_t)bk * N + min(bn + 8u * ((lane & 31u) ^ b_swz(bk)), N - 8u);
+    const uint32_t bk = (1024u / B_ROW) * b + lane / B_CPR;
+    gb[h] = B + (size_t)bk * N + min(bn + 8u * ((lane % B_CPR) ^ b_swz(bk)), N - 8u);
   }
 
-  f32x16 acc[4][4];
+  f32x16 acc[WT][WT];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (uint32_t i = 0; i < WT; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (uint32_t j = 0; j < WT; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // fragment addresses inside a stage (bytes), for the two 16-wide k halves of a tile
-  uint32_t a_off[2][4], b_lo[2][4], b_hi[2][4];
+  uint32_t a_off[2][WT], b_lo[2][WT], b_hi[2][WT];
   auto b_off = [&](uint32_t krow, uint32_t col) -> uint32_t {
-    return GD_A_BYTES + krow * 512u + (((col >> 3) ^ b_swz(krow)) << 4) + (col & 7u) * 2u;
+    return A_BYTES + krow * B_ROW + (((col >> 3) ^ b_swz(krow)) << 4) + (col & 7u) * 2u;
   };
 #pragma unroll
   for (uint32_t s = 0; s < 2; ++s) {
 #pragma unroll
-    for (uint32_t i = 0; i < 4; ++i) {
+    for (uint32_t i = 0; i < WT; ++i) {
       const uint32_t row = wm + 32u * i + l32;
       a_off[s][i] = row * 64u + (((2u * s + lhi) ^ row_swz(row)) << 4);
     }
 #pragma unroll
-    for (uint32_t j = 0; j < 4; ++j) {
+    for (uint32_t j = 0; j < WT; ++j) {
       b_lo[s][j] = b_off(16u * s + tr_row, wn + 32u * j + tr_col);
       b_hi[s][j] = b_off(16u * s + 4u + tr_row, wn + 32u * j + tr_col);
     }
   }
 
-  u32x4 fa[2][4];
-  s16x4 blo[2][4], bhi[2][4];
+  u32x4 fa[2][WT];
+  s16x4 blo[2][WT], bhi[2][WT];
   const uint32_t nk = K / GD_BK;
-  // one fragment read: q = 0..11 -> a0, b0 lo, b0 hi, b1 lo, b1 hi, b2 lo, b2 hi, b3 lo, b3 hi, a1, a2, a3
-  // (the order in which the next 16 MFMAs need them)
+  // one fragment read: q = 0 -> a0; 1 .. 2 WT -> b0 lo, b0 hi, b1 lo, ..; then a1, a2, ..
+  // (the order in which the next WT * WT MFMAs, row by row, need them)
   auto frag_load = [&](const uint8_t* st, uint32_t s, uint32_t slot, uint32_t q) {
-    if (q == 0u || q >= 9u) {
-      const uint32_t i = q == 0u ? 0u : q - 8u;
+    if (q == 0u || q > 2u * WT) {
+      const uint32_t i = q == 0u ? 0u : q - 2u * WT;
       fa[slot][i] = *reinterpret_cast<const u32x4*>(st + a_off[s][i]);
     } else {
       const uint32_t j = (q - 1u) >> 1;
@@ -294,60 +301,64 @@ __global__ __launch_bounds__(GD_THREADS, 1) void gemm_bf16_dma_kernel(const uint
       else blo[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(st + b_lo[s][j]));
     }
   };
-  // one DMA instruction of tile kt: part 0 = A, part 1 = B, h = 0..3.  The tile index is clamped
-  // so that every iteration issues the same number of loads (the vmcnt arithmetic below relies
-  // on it); the redundant loads of the last iterations land in stages nobody reads any more.
+  // one DMA instruction of tile kt: part 0 = A, part 1 = B, h = 0 .. ND-1.  The tile index is
+  // clamped so that every iteration issues the same number of loads (the vmcnt arithmetic below
+  // relies on it); the redundant loads of the last iterations land in stages nobody reads any more.
   auto dma_one = [&](uint32_t kt, uint32_t part, uint32_t h) {
     const uint32_t t = min(kt, nk - 1u);
-    const uint32_t st = lds_base + (kt % GD_NST) * GD_STAGE + (4u * wave + h) * 1024u;
+    const uint32_t st = lds_base + (kt % GD_NST) * STAGE + (ND * wave + h) * 1024u;
     if (part == 0u) dma16(ga[h] + (size_t)t * GD_BK, st);
-    else dma16(gb[h] + (size_t)t * GD_BK * N, st + GD_A_BYTES);
+    else dma16(gb[h] + (size_t)t * GD_BK * N, st + A_BYTES);
   };
-  // 16 MFMAs on fragment slot `slot`; after each one memory instruction: the 12 fragment reads of
-  // (tile ft, half fs) into the other slot, then the 4 DMA instructions of (tile dt, part dpart)
+  // NM MFMAs on fragment slot `slot`; spread evenly between them NF + ND memory instructions: the
+  // fragment reads of (tile ft, half fs) into the other slot, then the DMA instructions of
+  // (tile dt, part dpart).  WT = 4: one after every MFMA; WT = 2: two.
   auto block = [&](uint32_t slot, uint32_t ft, uint32_t fs, uint32_t dt, uint32_t dpart) {
-    const uint8_t* fst = smem + (ft % GD_NST) * GD_STAGE;
+    const uint8_t* fst = smem + (ft % GD_NST) * STAGE;
 #pragma unroll
-    for (uint32_t m = 0; m < 16u; ++m) {
-      const uint32_t i = m >> 2, j = m & 3u;
+    for (uint32_t m = 0; m < NM; ++m) {
+      const uint32_t i = m / WT, j = m % WT;
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fa[slot][i]), join_bf16x8(blo[slot][j], bhi[slot][j]),
                                                           acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (m < 12u) frag_load(fst, fs, slot ^ 1u, m);
-      else dma_one(dt, dpart, m - 12u);
+#pragma unroll
+      for (uint32_t x = m * (NF + ND) / NM; x < (m + 1u) * (NF + ND) / NM; ++x) {
+        if (x < NF) frag_load(fst, fs, slot ^ 1u, x);
+        else dma_one(dt, dpart, x - NF);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
 
   // Order of DMA issue: A(0) B(0) .. A(NST-2) B(NST-2) A(NST-1) | B(NST-1) A(NST) | B(NST) A(NST+1) | ..
-  // (4 instructions each; one `|` per loop iteration).  Tile t is complete once B(t) has landed.
+  // (ND instructions each; one `|` per loop iteration).  Tile t is complete once B(t) has landed.
 #pragma unroll
   for (uint32_t t = 0; t < GD_NST - 1u; ++t)
 #pragma unroll
     for (uint32_t p = 0; p < 2u; ++p)
 #pragma unroll
-      for (uint32_t h = 0; h < 4u; ++h) dma_one(t, p, h);
+      for (uint32_t h = 0; h < ND; ++h) dma_one(t, p, h);
 #pragma unroll
-  for (uint32_t h = 0; h < 4u; ++h) dma_one(GD_NST - 1u, 0u, h);
-  __builtin_amdgcn_s_waitcnt(vm_wait(8u * (GD_NST - 2u) + 4u));   // this wave's part of tile 0 has landed
-  __syncthreads();                                                // ... and everybody else's
+  for (uint32_t h = 0; h < ND; ++h) dma_one(GD_NST - 1u, 0u, h);
+  __builtin_amdgcn_s_waitcnt(vm_wait(2u * ND * (GD_NST - 2u) + ND));   // this wave's part of tile 0 has landed
+  __syncthreads();                                                     // ... and everybody else's
 #pragma unroll
-  for (uint32_t q = 0; q < 12u; ++q) frag_load(smem, 0u, 0u, q);
+  for (uint32_t q = 0; q < NF; ++q) frag_load(smem, 0u, 0u, q);
   for (uint32_t kt = 0; kt < nk; ++kt) {
     block(0u, kt, 1u, kt + GD_NST - 1u, 1u);            // second half of tile kt's fragments; B(kt + NST - 1)
-    // 8 * (NST - 2) instructions were issued after B(kt + 1): tile kt+1 has landed when no more
+    // 2 ND (NST - 2) instructions were issued after B(kt + 1): tile kt+1 has landed when no more
     // than that many are outstanding; the barrier extends that to every wave's part and tells
     // that all reads of tile kt are done (its fragments are in registers), which frees its stage
-    __builtin_amdgcn_s_waitcnt(vm_wait(8u * (GD_NST - 2u)));
+    __builtin_amdgcn_s_waitcnt(vm_wait(2u * ND * (GD_NST - 2u)));
     __syncthreads();
     block(1u, kt + 1u, 0u, kt + GD_NST, 0u);            // first half of tile kt+1's fragments; A(kt + NST) into the freed stage
   }
   __builtin_amdgcn_s_waitcnt(vm_wait(0));               // no DMA may be in flight when the LDS is given back
 
 #pragma unroll
-  for (uint32_t i = 0; i < 4; ++i)
+  for (uint32_t i = 0; i < WT; ++i)
 #pragma unroll
-    for (uint32_t j = 0; j < 4; ++j)
+    for (uint32_t j = 0; j < WT; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const uint32_t row = bm + wm + 32u * i + 8u * (r >> 2) + 4u * lhi + (r & 3);
@@ -358,14 +369,21 @@ __global__ __launch_bounds__(GD_THREADS, 1) void gemm_bf16_dma_kernel(const uint
 
 struct Geometry {
   uint32_t tiles_m, tiles_n, total, blocks;
-  bool dma;    // shape fits the DMA kernel (operand alignment is checked at enqueue)
-  bool fast;   // register-staged kernel: every tile full
+  bool dma;        // shape fits the DMA kernel (operand alignment is checked at enqueue)
+  uint32_t wt;     // DMA kernel: wave tile 32 wt x 32 wt, workgroup tile 64 wt x 64 wt
+  bool fast;       // register-staged kernel: every tile full
 };
+
+// 256 x 256 tiles unless they would leave half of the 256 CUs without one; then 128 x 128
+// (measured crossover: 2816^2 runs at 804 TFLOP/s on small tiles, 3072^2 at 880 on big ones).
+constexpr uint32_t GD_MIN_BIG_TILES = 128;
 
 Geometry geometry(uint32_t m, uint32_t n, uint32_t k) {
   Geometry g;
   g.dma = k % GD_BK == 0u && n % 8u == 0u;
-  const uint32_t bm = g.dma ? GD_BM : GB_BM, bn = g.dma ? GD_BN : GB_BN;
+  g.wt = 4u;
+  if (g.dma && ((m + 255u) / 256u) * ((n + 255u) / 256u) < GD_MIN_BIG_TILES) g.wt = 2u;
+  const uint32_t bm = g.dma ? 64u * g.wt : GB_BM, bn = g.dma ? 64u * g.wt : GB_BN;
   g.tiles_m = (m + bm - 1u) / bm;
   g.tiles_n = (n + bn - 1u) / bn;
   g.total = g.tiles_m * g.tiles_n;
@@ -377,6 +395,7 @@ Geometry geometry(uint32_t m, uint32_t n, uint32_t k) {
 Geometry staged_geometry(uint32_t m, uint32_t n, uint32_t k) {
   Geometry g;
   g.dma = false;
+  g.wt = 0u;
   g.tiles_m = (m + GB_BM - 1u) / GB_BM;
   g.tiles_n = (n + GB_BN - 1u) / GB_BN;
   g.total = g.tiles_m * g.tiles_n;
@@ -415,14 +434,22 @@ int mgb_gemm_bf16_enqueue(void* stream, const uint16_t* A, const uint16_t* B, fl
     static std::once_flag once;
     static hipError_t attr = hipSuccess;
     std::call_once(once, [] {
-      attr = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)GD_LDS);
+      attr = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 (int)gd_lds_bytes(4));
+      if (attr == hipSuccess)
+        attr = hipFuncSetAttribute((const void*)gemm_bf16_dma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)gd_lds_bytes(2));
     });
     if (attr != hipSuccess) {
       mgb_internal_set_error("gemm_bf16_dma_kernel: dynamic LDS size", attr);
       return MGB_E_BACKEND;
     }
-    hipLaunchKernelGGL(gemm_bf16_dma_kernel, dim3(g.blocks), dim3(GD_THREADS), GD_LDS, st, A, B, C, m, n, k,
-                       g.tiles_n, g.total);
+    if (g.wt == 4u)
+      hipLaunchKernelGGL(gemm_bf16_dma_kernel<4>, dim3(g.blocks), dim3(GD_THREADS), gd_lds_bytes(4), st, A, B, C, m,
+                         n, k, g.tiles_n, g.total);
+    else
+      hipLaunchKernelGGL(gemm_bf16_dma_kernel<2>, dim3(g.blocks), dim3(GD_THREADS), gd_lds_bytes(2), st, A, B, C, m,
+                         n, k, g.tiles_n, g.total);
     return mgb_check_launch("gemm_bf16_dma_kernel");
   }
   // any other shape, or operands that are not 16-byte aligned (the probe assumed they were)

@@ -279,7 +279,7 @@ def test_probe_functions_agree_with_checker_formulas():
         oracle.lib().orc_gemm_f32_probe(C.c_uint64(m), C.c_uint64(n), C.c_uint64(k), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (m, n, k)
     for m, n, k in ((1, 1, 1), (129, 257, 17), (4096, 4096, 4096), (8192, 1024, 64), (300, 520, 64), (300, 520, 48),
-                    (300, 524, 64), (1, 8, 32)):
+                    (300, 524, 64), (1, 8, 32), (2560, 2560, 2560), (2816, 2816, 64), (3072, 2816, 64), (8192, 8192, 8192)):
         mem, grid, block = mgb.probe_of(mgb.mgb_gemm_bf16_probe, m, n, k)
         oracle.lib().orc_gemm_bf16_probe(C.c_uint64(m), C.c_uint64(n), C.c_uint64(k), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (m, n, k)

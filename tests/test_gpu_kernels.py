@@ -165,7 +165,9 @@ def run_gemm_bf16(ab, bb):
                                    # k % 32 == 0 and n % 8 == 0: the 256 x 256 DMA-ring kernel, with
                                    # ragged rows / columns, fewer k tiles than ring stages, several tiles
                                    (1, 8, 32), (256, 8, 64), (300, 520, 64), (513, 264, 2048),
-                                   (1024, 1024, 32), (768, 512, 96), (2000, 1096, 1056)])
+                                   (1024, 1024, 32), (768, 512, 96), (2000, 1096, 1056),
+                                   # at least 128 tiles of 256 x 256: the big-tile variant (the others above take 128 x 128)
+                                   (2816, 2824, 64), (3000, 2816, 96)])
 def test_gemm_bf16_frobenius_error(m, n, k):
     ab, bb = W.gemm_operands_bf16(m + 3 * k, m, n, k)
     got = run_gemm_bf16(ab, bb)
