@@ -38,11 +38,15 @@ void orc_jacobi_probe(uint64_t n, uint64_t out[7]) {
   out[4] = 256; out[5] = 1; out[6] = 1;
 }
 
-// fp32 GEMM: A, B, C in fp32; one 512-thread workgroup (8 waves) per 128 x 128 tile of C.
+// fp32 GEMM: A, B, C in fp32; one 512-thread workgroup (8 waves) per 128 x 128 tile of C.  When k
+// is a multiple of 16, n a multiple of 4 and there would be fewer than 128 such tiles: one
+// 256-thread workgroup per 64 x 64 tile instead.
 void orc_gemm_f32_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
   out[0] = (m * k + k * n + m * n) * 4;
-  out[1] = round8(ceil_div(m, 128) * ceil_div(n, 128)); out[2] = 1; out[3] = 1;
-  out[4] = 512; out[5] = 1; out[6] = 1;
+  uint64_t wgs = ceil_div(m, 128) * ceil_div(n, 128), threads = 512;
+  if (k % 16 == 0 && n % 4 == 0 && wgs < 128) { wgs = ceil_div(m, 64) * ceil_div(n, 64); threads = 256; }
+  out[1] = round8(wgs); out[2] = 1; out[3] = 1;
+  out[4] = threads; out[5] = 1; out[6] = 1;
 }
 
 // bf16 GEMM: bf16 A and B, fp32 C.  When k is a multiple of 32 and n a multiple of 8: one

@@ -1,5 +1,8 @@
 // fp32 GEMM C = A * B (all row-major) on the fp32 matrix cores.
 //
+// Two kernels: gemm_f32_dma_kernel (k % 16 == 0, n % 4 == 0, 16-byte aligned operands; described
+// where it is defined) and the register-staged gemm_f32_kernel for every other shape:
+//
 // MFMA-bound for all but tiny shapes (2*m*n*k flop over 4*(mk + kn + mn)
 // bytes).  One workgroup of 8 waves owns a 128 x 128 tile of C; each wave a
 // 32 x 64 piece as 1 x 2 blocks of v_mfma_f32_32x32x2_f32.  A and B tiles of
@@ -17,8 +20,11 @@
 // b = B[l / 32][l % 32], acc[r] = C[8*(r/4) + 4*(l/32) + r%4][l % 32].
 #include "../../include/mgb.h"
 #include "launch_util.h"
+#include "lds_dma.h"
 
 #include <hip/hip_runtime.h>
+
+#include <mutex>
 
 #ifndef GF_WAVES_M
 #define GF_WAVES_M 4     // waves along m: 4 -> wave tile 32 x 64, 2 -> 64 x 64
@@ -164,17 +170,202 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
       }
 }
 
+// ---- global -> LDS DMA ring kernel (k % 16 == 0, n % 4 == 0, 16-byte aligned operands) ---------
+//
+// The fp32 MFMA needs only 128 bytes of operands from L2 per instruction at 128 x 128 tiles, so
+// the kernel is bound by MFMA issue alone; what the register-staged kernel loses is issue slots
+// (global loads, the transposing LDS stores, a barrier per 16 k).  Here the tiles go global -> LDS
+// by DMA into a ring of four stages and the loop is laid out by hand: the LDS reads and DMA
+// instructions are spread between the MFMAs and pinned.
+//
+// WGM x WGN waves, each TM x TN MFMA blocks of 32 x 32:
+//   2 x 4 waves of 64 x 32: 128 x 128 tile, 512 threads (as many waves per tile as the
+//                           register-staged kernel, so a task asks for the same share of the device)
+//   2 x 2 waves of 32 x 32: 64 x 64 tile, 256 threads, for shapes with few big tiles
+// Depth 16 per tile: an A row is 64 bytes, the same byte geometry (and swizzle) as the bf16 kernels.
+//
+// k order inside a tile: the MFMA's two k slots (lane / 32) take k = 8 * (lane / 32) + s in step
+// s = 0..7, so a lane's A operands of four steps are 16 contiguous bytes (one ds_read_b128), and
+// its B operand of step s is the float at k row 8 * (lane / 32) + s.  (Any assignment of the 16 k
+// of a tile to steps and slots gives the same sum up to rounding order.)
+constexpr uint32_t FD_BK = 16, FD_NST = 4, FD_BAND = 8;
+constexpr uint32_t fd_lds_bytes(uint32_t bm, uint32_t bn) { return FD_NST * (bm + bn) * FD_BK * 4u; }
+
+template <uint32_t WGM, uint32_t WGN, uint32_t TM, uint32_t TN>
+__global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_f32_dma_kernel(const float* __restrict__ A,
+                                                                       const float* __restrict__ B,
+                                                                       float* __restrict__ C, uint32_t M,
+                                                                       uint32_t N, uint32_t K, uint32_t tiles_n,
+                                                                       uint32_t tiles_total) {
+  constexpr uint32_t NW = WGM * WGN;
+  constexpr uint32_t BM = 32u * TM * WGM, BN = 32u * TN * WGN;
+  constexpr uint32_t A_BYTES = BM * 64u, B_BYTES = FD_BK * BN * 4u, STAGE = A_BYTES + B_BYTES;
+  constexpr uint32_t NDA = BM / 16u / NW, NDB = BN / 16u / NW;   // DMA instructions per wave per tile
+  static_assert(NDA >= 1u && NDB >= 1u, "every wave takes part in both operand copies");
+  constexpr uint32_t B_ROW = BN * 4u;                // bytes of a B k-row in LDS
+  constexpr uint32_t B_CPR = BN / 4u;                // 16-byte chunks of a B k-row
+  constexpr uint32_t NF = TM + 2u * TN;              // fragment reads per half tile (4 steps; B two steps at a time)
+  constexpr uint32_t NM = 4u * TM * TN;              // MFMAs per half tile
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+  const uint32_t per_xcd = (tiles_total + 7u) / 8u;
+  const uint32_t seq = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || seq >= tiles_total) return;
+  const uint32_t tiles_m = tiles_total / tiles_n;
+  const uint32_t band = seq / (FD_BAND * tiles_n);
+  const uint32_t band_rows = min(FD_BAND, tiles_m - FD_BAND * band);
+  const uint32_t in_band = seq - band * FD_BAND * tiles_n;
+  const uint32_t bm = (FD_BAND * band + in_band % band_rows) * BM;
+  const uint32_t bn = (in_band / band_rows) * BN;
+
+  const uint32_t lds_base = lds_address_of(smem);
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t wm = (wave / WGN) * (32u * TM), wn = (wave % WGN) * (32u * TN);
+  const uint32_t l32 = lane & 31u, lhi = lane >> 5;
+
+  // chunk swizzle of a B k-row: rows 8..15 are shifted by 128 bytes against rows 0..7, so that the
+  // two halves of a wave (k rows s and 8 + s) read different banks
+  auto b_swz = [](uint32_t k) -> uint32_t { return ((k >> 3) & 1u) << 3; };
+
+  // DMA roles: wave w, instruction h fills the 1 KiB block b = ND*w + h of an operand part.
+  //   A block b: rows 16b .. 16b+15 (64 bytes = 16 k each); lane -> row 16b + lane/4, chunk lane%4
+  //   B block b: 1024 / B_ROW consecutive k rows;             lane -> its k row and chunk
+  // Rows beyond M and column chunks beyond N are clamped: they only feed entries never stored.
+  const float* ga[NDA];
+  const float* gb[NDB];
+#pragma unroll
+  for (uint32_t h = 0; h < NDA; ++h) {
+    const uint32_t ar = 16u * (NDA * wave + h) + (lane >> 2);
+    ga[h] = A + (size_t)min(bm + ar, M - 1u) * K + 4u * ((lane & 3u) ^ row_swz(ar));
+  }
+#pragma unroll
+  for (uint32_t h = 0; h < NDB; ++h) {
+    const uint32_t bk = (1024u / B_ROW) * (NDB * wave + h) + lane / B_CPR;
+    gb[h] = B + (size_t)bk * N + min(bn + 4u * ((lane % B_CPR) ^ b_swz(bk)), N - 4u);
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (uint32_t i = 0; i < TM; ++i)
+#pragma unroll
+    for (uint32_t j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // fragment addresses inside a stage: half hf covers steps 4 hf .. 4 hf + 3
+  uint32_t a_off[2][TM], b_off[2][4][TN];
+#pragma unroll
+  for (uint32_t hf = 0; hf < 2; ++hf) {
+#pragma unroll
+    for (uint32_t i = 0; i < TM; ++i) {
+      const uint32_t row = wm + 32u * i + l32;
+      a_off[hf][i] = row * 64u + (((2u * lhi + hf) ^ row_swz(row)) << 4);      // k = 8 lhi + 4 hf .. + 3
+    }
+#pragma unroll
+    for (uint32_t s = 0; s < 4; ++s)
+#pragma unroll
+      for (uint32_t j = 0; j < TN; ++j) {
+        const uint32_t krow = 8u * lhi + 4u * hf + s, col = wn + 32u * j + l32;
+        b_off[hf][s][j] = A_BYTES + krow * B_ROW + (((col >> 2) ^ b_swz(krow)) << 4) + (col & 3u) * 4u;
+      }
+  }
+
+  float4 fa[2][TM];            // [slot][block row]: A operands of four steps
+  float fb[2][4][TN];          // [slot][step][block column]
+  const uint32_t nk = K / FD_BK;
+  // one fragment read of a half tile, in the order the MFMAs need them: the A operands (one read
+  // serves four steps), then the B operands, two steps (two k rows, one two-address LDS read) at a time
+  auto frag_load = [&](const uint8_t* st, uint32_t hf, uint32_t slot, uint32_t q) {
+    if (q < TM) fa[slot][q] = *reinterpret_cast<const float4*>(st + a_off[hf][q]);
+    else {
+      const uint32_t x = q - TM, s2 = 2u * (x / TN), j = x % TN;
+      fb[slot][s2][j] = *reinterpret_cast<const float*>(st + b_off[hf][s2][j]);
+      fb[slot][s2 + 1u][j] = *reinterpret_cast<const float*>(st + b_off[hf][s2 + 1u][j]);
+    }
+  };
+  auto dma_one = [&](uint32_t kt, uint32_t part, uint32_t h) {
+    const uint32_t t = min(kt, nk - 1u);              // clamped: the schedule never changes, see the wait counts
+    const uint32_t st = lds_base + (kt % FD_NST) * STAGE;
+    if (part == 0u) dma16(ga[h] + (size_t)t * FD_BK, st + (NDA * wave + h) * 1024u);
+    else dma16(gb[h] + (size_t)t * FD_BK * N, st + A_BYTES + (NDB * wave + h) * 1024u);
+  };
+  // NM MFMAs (4 steps) on fragment slot `slot`; spread between them: the NF fragment reads of
+  // (tile ft, half fh) into the other slot, then the DMA instructions of (tile dt, part dpart)
+  auto block = [&](uint32_t slot, uint32_t ft, uint32_t fh, uint32_t dt, uint32_t dpart) {
+    const uint8_t* fst = smem + (ft % FD_NST) * STAGE;
+    const uint32_t nd = dpart == 0u ? NDA : NDB;
+#pragma unroll
+    for (uint32_t m = 0; m < NM; ++m) {
+      const uint32_t s = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
+      const float a = s == 0u ? fa[slot][i].x : s == 1u ? fa[slot][i].y : s == 2u ? fa[slot][i].z : fa[slot][i].w;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, fb[slot][s][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (uint32_t x = m * (NF + nd) / NM; x < (m + 1u) * (NF + nd) / NM; ++x) {
+        if (x < NF) frag_load(fst, fh, slot ^ 1u, x);
+        else dma_one(dt, dpart, x - NF);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // DMA issue order: A(0) B(0) .. A(NST-2) B(NST-2) A(NST-1) | B(NST-1) A(NST) | B(NST) A(NST+1) | ..
+#pragma unroll
+  for (uint32_t t = 0; t < FD_NST - 1u; ++t) {
+#pragma unroll
+    for (uint32_t h = 0; h < NDA; ++h) dma_one(t, 0u, h);
+#pragma unroll
+    for (uint32_t h = 0; h < NDB; ++h) dma_one(t, 1u, h);
+  }
+#pragma unroll
+  for (uint32_t h = 0; h < NDA; ++h) dma_one(FD_NST - 1u, 0u, h);
+  __builtin_amdgcn_s_waitcnt(vm_wait((NDA + NDB) * (FD_NST - 2u) + NDA));   // this wave's part of tile 0 has landed
+  __syncthreads();
+#pragma unroll
+  for (uint32_t q = 0; q < NF; ++q) frag_load(smem, 0u, 0u, q);
+  for (uint32_t kt = 0; kt < nk; ++kt) {
+    block(0u, kt, 1u, kt + FD_NST - 1u, 1u);          // reads the second half of tile kt; B(kt + NST - 1)
+    // tile kt+1 has landed when no more than the (NDA + NDB)(NST-2) instructions issued after it
+    // are outstanding; the barrier makes that true for every wave and frees tile kt's stage
+    __builtin_amdgcn_s_waitcnt(vm_wait((NDA + NDB) * (FD_NST - 2u)));
+    __syncthreads();
+    block(1u, kt + 1u, 0u, kt + FD_NST, 0u);          // reads the first half of tile kt+1; A(kt + NST)
+  }
+  __builtin_amdgcn_s_waitcnt(vm_wait(0));             // no DMA may be in flight when the LDS is given back
+
+#pragma unroll
+  for (uint32_t i = 0; i < TM; ++i)
+#pragma unroll
+    for (uint32_t j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t row = bm + wm + 32u * i + 8u * (r >> 2) + 4u * lhi + (r & 3);
+        const uint32_t col = bn + wn + 32u * j + l32;
+        if (row < M && col < N) C[(size_t)row * N + col] = acc[i][j][r];
+      }
+}
+
 struct Geometry {
-  uint32_t tiles_m, tiles_n, total, blocks;
-  bool fast;
+  uint32_t tiles_m, tiles_n, total, blocks, threads;
+  bool dma;     // shape fits the DMA kernel (operand alignment is checked at enqueue)
+  bool small;   // DMA kernel on 64 x 64 tiles
+  bool fast;    // register-staged kernel: every tile full
 };
 
-Geometry geometry(uint32_t m, uint32_t n, uint32_t k) {
+// 64 x 64 tiles when 128 x 128 ones would leave half of the 256 CUs without a tile
+constexpr uint32_t FD_MIN_BIG_TILES = 128;
+
+Geometry geometry(uint32_t m, uint32_t n, uint32_t k, bool allow_dma = true) {
   Geometry g;
-  g.tiles_m = (m + GF_BM - 1u) / GF_BM;
-  g.tiles_n = (n + GF_BN - 1u) / GF_BN;
+  g.dma = allow_dma && k % FD_BK == 0u && n % 4u == 0u;
+  g.small = g.dma && ((m + 127u) / 128u) * ((n + 127u) / 128u) < FD_MIN_BIG_TILES;
+  const uint32_t t = g.small ? 64u : 128u;
+  g.tiles_m = (m + t - 1u) / t;
+  g.tiles_n = (n + t - 1u) / t;
   g.total = g.tiles_m * g.tiles_n;
   g.blocks = ((g.total + 7u) / 8u) * 8u;
+  g.threads = g.small ? 256u : GF_THREADS;
   g.fast = m % GF_BM == 0u && n % GF_BN == 0u && k % GF_BK == 0u;
   return g;
 }
@@ -194,7 +385,7 @@ int mgb_gemm_f32_probe(uint32_t m, uint32_t n, uint32_t k, uint64_t* mem_bytes, 
   const Geometry g = geometry(m, n, k);
   *mem_bytes = ((uint64_t)m * k + (uint64_t)k * n + (uint64_t)m * n) * sizeof(float);
   *grid = mgb_dim3{g.blocks, 1u, 1u};
-  *block = mgb_dim3{GF_THREADS, 1u, 1u};
+  *block = mgb_dim3{g.threads, 1u, 1u};
   return MGB_OK;
 }
 
@@ -202,9 +393,31 @@ int mgb_gemm_f32_enqueue(void* stream, const float* A, const float* B, float* C,
                          uint32_t n, uint32_t k) {
   if (!A || !B || !C) return MGB_E_INVAL;
   if (!shape_ok(m, n, k)) return MGB_E_UNSUPPORTED;
-  const Geometry g = geometry(m, n, k);
   const bool aligned = (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15u) == 0u;
+  const Geometry g = geometry(m, n, k, aligned);     // the probe assumed aligned operands
   hipStream_t st = (hipStream_t)stream;
+  if (g.dma) {
+    static std::once_flag once;
+    static hipError_t attr = hipSuccess;
+    std::call_once(once, [] {
+      attr = hipFuncSetAttribute((const void*)gemm_f32_dma_kernel<2, 4, 2, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 (int)fd_lds_bytes(128, 128));
+      if (attr == hipSuccess)
+        attr = hipFuncSetAttribute((const void*)gemm_f32_dma_kernel<2, 2, 1, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)fd_lds_bytes(64, 64));
+    });
+    if (attr != hipSuccess) {
+      mgb_internal_set_error("gemm_f32_dma_kernel: dynamic LDS size", attr);
+      return MGB_E_BACKEND;
+    }
+    if (g.small)
+      hipLaunchKernelGGL((gemm_f32_dma_kernel<2, 2, 1, 1>), dim3(g.blocks), dim3(g.threads), fd_lds_bytes(64, 64), st,
+                         A, B, C, m, n, k, g.tiles_n, g.total);
+    else
+      hipLaunchKernelGGL((gemm_f32_dma_kernel<2, 4, 2, 1>), dim3(g.blocks), dim3(g.threads), fd_lds_bytes(128, 128), st,
+                         A, B, C, m, n, k, g.tiles_n, g.total);
+    return mgb_check_launch("gemm_f32_dma_kernel");
+  }
   const uint32_t vec_ok = (aligned && k % GF_BK == 0u && n % 4u == 0u) ? 1u : 0u;
   if (g.fast && aligned)
     hipLaunchKernelGGL(gemm_f32_kernel<true>, dim3(g.blocks), dim3(GF_THREADS), 0, st, A, B, C, m,

@@ -45,7 +45,7 @@ def build_task(spec, data, device="cuda:0"):
         Cc = torch.zeros(m, n, device=device)
         probe = mgb.probe_of(mgb.mgb_gemm_f32_probe, m, n, kk)
         fn = lambda st: mgb.mgb_gemm_f32_enqueue(st, _ptr(A), _ptr(B), _ptr(Cc), m, n, kk)
-        return Task(spec, dict(A=A, B=B, C=Cc), probe, fn, "gemm_f32_kernel", 1,
+        return Task(spec, dict(A=A, B=B, C=Cc), probe, fn, "gemm_f32_dma_kernel", 1,
                     alg_bytes=4.0 * (m * kk + kk * n + m * n), alg_flops=2.0 * m * n * kk)
     if k == "gemm_bf16":
         m, n, kk = p["m"], p["n"], p["k"]
@@ -54,7 +54,7 @@ def build_task(spec, data, device="cuda:0"):
         Cc = torch.zeros(m, n, device=device)
         probe = mgb.probe_of(mgb.mgb_gemm_bf16_probe, m, n, kk)
         fn = lambda st: mgb.mgb_gemm_bf16_enqueue(st, _ptr(A), _ptr(B), _ptr(Cc), m, n, kk)
-        return Task(spec, dict(A=A, B=B, C=Cc), probe, fn, "gemm_bf16_kernel", 1,
+        return Task(spec, dict(A=A, B=B, C=Cc), probe, fn, "gemm_bf16_dma_kernel", 1,
                     alg_bytes=2.0 * (m * kk + kk * n) + 4.0 * m * n, alg_flops=2.0 * m * n * kk)
     if k == "bfs":
         n = p["n"]

@@ -112,13 +112,31 @@ def run_gemm_f32(a, b):
 
 @pytest.mark.parametrize("m,n,k", [(1, 1, 1), (128, 128, 16), (100, 70, 33), (129, 257, 17),
                                    (256, 256, 256), (384, 128, 48), (512, 384, 1000), (130, 128, 16),
-                                   (128, 128, 15), (31, 513, 64)])
+                                   (128, 128, 15), (31, 513, 64),
+                                   # k % 16 == 0 and n % 4 == 0: the DMA-ring kernel.  64 x 64 tiles with ragged
+                                   # rows / columns and fewer k tiles than ring stages ...
+                                   (1, 4, 16), (64, 64, 16), (200, 132, 48), (1000, 1004, 160),
+                                   # ... and 128 x 128 tiles (at least 128 of them), ragged and full
+                                   (1408, 1540, 64), (1500, 1412, 112), (2048, 1024, 256)])
 def test_gemm_f32_componentwise_error(m, n, k):
     a, b = W.gemm_operands_f32(m * 7 + k, m, n, k)
     got = run_gemm_f32(a, b)
     ref, den = oracle.gemm_f32(a, b), oracle.gemm_abs_f32(a, b)
     assert (np.abs(got.astype(np.float64) - ref) / den).max() <= 1e-4
     assert np.abs(got - ref).max() / np.abs(ref).max() <= 1e-5
+
+
+def test_gemm_f32_unaligned_operands_take_the_staged_kernel():
+    m, n, k = 200, 132, 48
+    a, b = W.gemm_operands_f32(12, m, n, k)
+    A = torch.zeros(m * k + 4, device=DEV)
+    A[1:1 + m * k] = torch.from_numpy(a.ravel()).to(DEV)                  # 4-byte aligned only
+    B = torch.from_numpy(b).to(DEV)
+    Cd = torch.full((m, n), float("nan"), device=DEV)
+    assert mgb.mgb_gemm_f32_enqueue(None, C.c_void_p(A.data_ptr() + 4), P(B), P(Cd), m, n, k) == 0
+    sync()
+    ref, den = oracle.gemm_f32(a, b), oracle.gemm_abs_f32(a, b)
+    assert (np.abs(Cd.cpu().numpy().astype(np.float64) - ref) / den).max() <= 1e-4
 
 
 def test_gemm_f32_identity_and_permutation_exact():

@@ -143,7 +143,7 @@ def test_pressure32_full_size_sampled():
             rows, cols = rng.integers(0, n, 24), rng.integers(0, n, 24)
             rows[:2], cols[:2] = [0, n - 1], [n - 1, 0]
             checks[t.task_id] = ("gemm", A[rows].cpu().numpy(), B[:, cols].contiguous().cpu().numpy(), rows, cols)
-            tasks.append(harness.Task(t, dict(A=A, B=B, C=Cc), probe, fn, "gemm_f32_kernel", 1))
+            tasks.append(harness.Task(t, dict(A=A, B=B, C=Cc), probe, fn, "gemm_f32_dma_kernel", 1))
         else:
             n, it = t.params["n"], t.params["iters"]
             u0 = torch.rand(n, n, device="cuda:0", generator=gen)

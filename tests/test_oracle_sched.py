@@ -383,4 +383,4 @@ def test_probe_formulas_match_stated_footprints():
     oracle.lib().orc_jacobi_probe(C.c_uint64(512), out)
     assert out[0] == 2 * 512 * 512 * 4 and out[1] == 48   # 3 x 64 windows, four per workgroup
     oracle.lib().orc_gemm_f32_probe(C.c_uint64(256), C.c_uint64(256), C.c_uint64(256), out)
-    assert out[0] == 768 * 1024 and out[1] == 8
+    assert out[0] == 768 * 1024 and out[1] == 16 and out[4] == 256   # 4 x 4 tiles of 64 x 64 (too few 128 x 128 ones)
