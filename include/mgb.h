@@ -162,7 +162,7 @@ int mgb_sched_destroy(mgb_sched* s);
  *   MGB_E_TOO_BIG  mem_bytes exceeds the cap; the task is never queued.
  * Compute demand (Algorithm 2's per-SM residency limits, per CU here):
  *   waves/wg = ceil(threads / wave_size);
- *   wg/CU    = max(1, min(max_wg_per_cu, max_waves_per_cu / waves/wg));
+ *   wg/CU    = max(1, min(max_wg_per_cu, max_waves_per_cu / waves/wg [, wg_per_cu of the probe]));
  *   CUs      = min(n_cu, ceil(workgroups / wg/CU)); granules = ceil(CUs / granule_cus).
  * Admission: mem_bytes <= free bytes, fewer than max_running tasks resident,
  * and (HARD) a free aligned block of next_pow2(granules) granules, the lowest
@@ -170,6 +170,14 @@ int mgb_sched_destroy(mgb_sched* s);
  * waves instead and never waits for compute.                                */
 int mgb_task_probe(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 grid,
                    mgb_dim3 block, mgb_placement* out);
+
+/* The same with one more fact the compiler has about the task's kernels: wg_per_cu = how many of
+ * its workgroups one CU can hold at once given their registers and LDS (the hardware dispatcher
+ * stops at whichever resource runs out first, Sec. II-A).  It enters the demand rule as one more
+ * upper limit on workgroups per CU; 0 = not known (mgb_task_probe).  The probe's trace record
+ * carries it in its `demand` field.                                            */
+int mgb_task_probe_ex(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 grid,
+                      mgb_dim3 block, uint32_t wg_per_cu, mgb_placement* out);
 
 /* Block until the queued task is admitted (MGB_OK, *out filled) or
  * timeout_ns elapsed (MGB_TIMEOUT, task stays queued; < 0 waits forever).    */
@@ -322,6 +330,11 @@ uint32_t mgb_jacobi_launch_count(uint32_t n, uint32_t iters);
 
 /* fp32 GEMM C = A * B, row-major A (m x k), B (k x n), C (m x n), fp32 MFMA
  * accumulation.  Footprint (m*k + k*n + m*n)*4.                              */
+/* *_residency: workgroups of the task's (largest) kernel that one CU can hold given their registers
+ * and LDS -- the wg_per_cu of mgb_task_probe_ex; 0 for a shape the kernel does not accept.       */
+uint32_t mgb_gemm_f32_residency(uint32_t m, uint32_t n, uint32_t k);
+uint32_t mgb_gemm_bf16_residency(uint32_t m, uint32_t n, uint32_t k);
+uint32_t mgb_conv3x3_residency(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_out, uint32_t stride);
 int mgb_gemm_f32_probe(uint32_t m, uint32_t n, uint32_t k, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block);
 int mgb_gemm_f32_enqueue(void* stream, const float* A, const float* B, float* C, uint32_t m, uint32_t n, uint32_t k);
 
@@ -349,6 +362,8 @@ int mgb_conv3x3_enqueue(void* stream, const uint16_t* x, const uint16_t* w, void
  * pointer of layer i's K,3,3,C tensor (host array of device pointers).
  * Footprint = input + all weights + 2 * largest intermediate + fp32 output;
  * geometry = the largest over the layers.                                    */
+uint32_t mgb_cnn_residency(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, uint32_t h,
+                           uint32_t w);
 int mgb_cnn_probe(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, uint32_t h,
                   uint32_t w, uint64_t* mem_bytes, uint64_t* act_bytes, uint64_t* out_bytes,
                   mgb_dim3* grid, mgb_dim3* block);

@@ -151,7 +151,7 @@ class Device(C.Structure):
                 ("max_running", C.c_uint32)]
 
 
-INPUT_DT = np.dtype([("kind", "<u4"), ("pad", "<u4"), ("id", "<u8"), ("mem", "<u8"),
+INPUT_DT = np.dtype([("kind", "<u4"), ("wg_per_cu", "<u4"), ("id", "<u8"), ("mem", "<u8"),
                      ("grid", "<u4", (3,)), ("block", "<u4", (3,))])
 DECISION_DT = np.dtype([("in_index", "<u4"), ("kind", "<u4"), ("ticket", "<u8"), ("task_id", "<u8"),
                         ("free_bytes", "<u8"), ("granule_mask", "<u4"), ("free_granules", "<u4"),
@@ -169,11 +169,13 @@ def device(cap_bytes, n_cu=256, granule_cus=8, wave_size=64, max_waves_per_cu=32
                   policy, queue_mode, max_running)
 
 
-def demand(dev, grid, block):
+def demand(dev, grid, block, wg_per_cu=0):
+    """Granules demanded by a launch geometry (and, optionally, the number of workgroups per CU
+    the task's own registers / LDS allow), and its waves."""
     g = (C.c_uint32 * 3)(*grid)
     b = (C.c_uint32 * 3)(*block)
     waves = C.c_uint64(0)
-    d = lib().orc_demand(C.byref(dev), g, b, C.byref(waves))
+    d = lib().orc_demand_ex(C.byref(dev), g, b, C.c_uint32(wg_per_cu), C.byref(waves))
     return int(d), int(waves.value)
 
 
@@ -190,8 +192,8 @@ def sched_replay(dev, inputs):
 
 
 def make_inputs(events):
-    """events: list of ("probe", task_id, mem, grid, block) | ("complete", ticket) | ("cancel", ticket)
-    | ("grow", ticket, extra_bytes)."""
+    """events: list of ("probe", task_id, mem, grid, block[, wg_per_cu]) | ("complete", ticket) |
+    ("cancel", ticket) | ("grow", ticket, extra_bytes)."""
     arr = np.zeros(len(events), dtype=INPUT_DT)
     for i, ev in enumerate(events):
         if ev[0] == "probe":
@@ -200,6 +202,7 @@ def make_inputs(events):
             arr[i]["mem"] = ev[2]
             arr[i]["grid"] = ev[3]
             arr[i]["block"] = ev[4]
+            arr[i]["wg_per_cu"] = ev[5] if len(ev) > 5 else 0
         elif ev[0] == "complete":
             arr[i]["kind"] = IN_COMPLETE
             arr[i]["id"] = ev[1]

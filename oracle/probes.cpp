@@ -112,6 +112,41 @@ void orc_cnn_probe(const uint64_t* c, uint64_t n_layers, uint64_t batch, uint64_
   out[4] = threads; out[5] = 1; out[6] = 1;
 }
 
+// Workgroups per CU that each kernel's own resources allow (what the probe adds to grid and block).
+// A CU has 160 KiB of LDS, 4 SIMDs of 512 registers per lane, 32 wave slots.
+//   fp32 GEMM: the DMA kernels keep a four-stage ring of (tile_m + tile_n) x 16 floats; the
+//   register-staged one is limited by its 8 waves per workgroup.
+uint64_t orc_gemm_f32_residency(uint64_t m, uint64_t n, uint64_t k) {
+  if (k % 16 == 0 && n % 4 == 0) {
+    uint64_t tile = ceil_div(m, 128) * ceil_div(n, 128) < 128 ? 64 : 128;
+    return (160 * 1024) / (4 * (tile + tile) * 16 * 4);
+  }
+  return 32 / 8;
+}
+//   bf16 GEMM: ring of (tile_m + tile_n) x 32 bf16 x 4 stages; the 256 x 256 kernel also needs all
+//   512 registers of a lane; the register-staged kernel 207 registers (2 waves per SIMD, 4-wave groups).
+uint64_t orc_gemm_bf16_residency(uint64_t m, uint64_t n, uint64_t k) {
+  if (k % 32 == 0 && n % 8 == 0) {
+    uint64_t tile = ceil_div(m, 256) * ceil_div(n, 256) < 128 ? 128 : 256;
+    return (160 * 1024) / (4 * (tile + tile) * 32 * 2);
+  }
+  return 2;
+}
+//   conv: ring of (pixels + channels) x 32 bf16 x 4 stages; first-layer kernel: 3 strips of 776 bf16 +
+//   256 x c_out' bf16 of output staging (c_out' = c_out rounded up to 32); register-staged: 2.
+uint64_t orc_conv3x3_residency(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, uint64_t c_out,
+                               uint64_t stride) {
+  uint64_t ho = (h - 1) / stride + 1, wo = (w - 1) / stride + 1, pixels = batch * ho * wo;
+  if (c_in % 32 == 0 && c_out % 8 == 0) {
+    uint64_t tp = c_out > 64 ? 128 : 256, tc = c_out > 64 ? 128 : 64;
+    if (ceil_div(pixels, tp) * ceil_div(c_out, tc) < 256) tp = tc = 64;
+    return (160 * 1024) / (4 * (tp + tc) * 32 * 2);
+  }
+  if (c_in == 3 && stride == 1 && c_out % 8 == 0 && c_out <= 64)
+    return (160 * 1024) / (3 * 776 * 2 + 256 * ceil_div(c_out, 32) * 32 * 2);
+  return 2;
+}
+
 // BFS: CSR (n+1 row pointers, m column indices), the level array, two frontier queues of n
 // entries (each rounded up to 256 bytes) and a 256-byte control block.  One 256-thread
 // workgroup per 1024 vertices, at least 8 and at most 2048.

@@ -67,7 +67,7 @@ struct orc_device {
 
 struct orc_input {
   uint32_t kind;        // IN_*
-  uint32_t pad;
+  uint32_t wg_per_cu;   // PROBE: workgroups per CU the task's own resources allow, 0 = not known
   uint64_t id;          // PROBE: task id; COMPLETE / CANCEL: ticket
   uint64_t mem;
   uint32_t grid[3], block[3];
@@ -88,13 +88,22 @@ struct orc_decision {
 
 // granules demanded by a launch geometry: how many CUs are needed to hold all
 // workgroups at once given the per-CU wave and workgroup limits.
+uint32_t orc_demand_ex(const orc_device* dev, const uint32_t grid[3], const uint32_t block[3],
+                       uint32_t wg_per_cu_task, uint64_t* waves_out);
+
 uint32_t orc_demand(const orc_device* dev, const uint32_t grid[3], const uint32_t block[3],
                     uint64_t* waves_out) {
+  return orc_demand_ex(dev, grid, block, 0, waves_out);
+}
+
+uint32_t orc_demand_ex(const orc_device* dev, const uint32_t grid[3], const uint32_t block[3],
+                       uint32_t wg_per_cu_task, uint64_t* waves_out) {
   uint64_t W = (uint64_t)grid[0] * grid[1] * grid[2];
   uint64_t T = (uint64_t)block[0] * block[1] * block[2];
   uint64_t wpw = (T + dev->wave_size - 1) / dev->wave_size;
   uint64_t per_cu = dev->max_waves_per_cu / wpw;
   if (per_cu > dev->max_wg_per_cu) per_cu = dev->max_wg_per_cu;
+  if (wg_per_cu_task != 0 && per_cu > wg_per_cu_task) per_cu = wg_per_cu_task;
   if (per_cu < 1) per_cu = 1;
   uint64_t cus = (W + per_cu - 1) / per_cu;
   if (cus > dev->n_cu) cus = dev->n_cu;
@@ -227,7 +236,7 @@ int64_t orc_sched_replay(const orc_device* dev, const orc_input* in, uint64_t n_
       t.ticket = ++next_ticket;
       t.task_id = ev.id;
       t.mem = ev.mem;
-      t.demand = orc_demand(dev, ev.grid, ev.block, &t.waves);
+      t.demand = orc_demand_ex(dev, ev.grid, ev.block, ev.wg_per_cu, &t.waves);
       if (dev->policy == POL_SERIAL) t.demand = G;
       live.push_back(t);
       Task& ref = live.back();

@@ -84,6 +84,7 @@ mgb_device_desc_default = _sig("mgb_device_desc_default", None, _P(mgb_device_de
 mgb_sched_create = _sig("mgb_sched_create", C.c_int, _P(mgb_device_desc), _P(_vp))
 mgb_sched_destroy = _sig("mgb_sched_destroy", C.c_int, _vp)
 mgb_task_probe = _sig("mgb_task_probe", C.c_int, _vp, _u64, _u64, mgb_dim3, mgb_dim3, _P(mgb_placement))
+mgb_task_probe_ex = _sig("mgb_task_probe_ex", C.c_int, _vp, _u64, _u64, mgb_dim3, mgb_dim3, _u32, _P(mgb_placement))
 mgb_task_wait = _sig("mgb_task_wait", C.c_int, _vp, _u64, _i64, _P(mgb_placement))
 mgb_task_cancel = _sig("mgb_task_cancel", C.c_int, _vp, _u64)
 mgb_task_grow = _sig("mgb_task_grow", C.c_int, _vp, _u64, _u64)
@@ -116,6 +117,10 @@ _probe_tail = (_P(_u64), _P(mgb_dim3), _P(mgb_dim3))
 mgb_jacobi_probe = _sig("mgb_jacobi_probe", C.c_int, _u32, _u32, *_probe_tail)
 mgb_jacobi_enqueue = _sig("mgb_jacobi_enqueue", C.c_int, _vp, _vp, _vp, _u32, _u32)
 mgb_jacobi_launch_count = _sig("mgb_jacobi_launch_count", _u32, _u32, _u32)
+mgb_gemm_f32_residency = _sig("mgb_gemm_f32_residency", _u32, _u32, _u32, _u32)
+mgb_gemm_bf16_residency = _sig("mgb_gemm_bf16_residency", _u32, _u32, _u32, _u32)
+mgb_conv3x3_residency = _sig("mgb_conv3x3_residency", _u32, _u32, _u32, _u32, _u32, _u32, _u32)
+mgb_cnn_residency = _sig("mgb_cnn_residency", _u32, _P(mgb_conv_layer), _u32, _u32, _u32, _u32)
 mgb_gemm_f32_probe = _sig("mgb_gemm_f32_probe", C.c_int, _u32, _u32, _u32, *_probe_tail)
 mgb_gemm_f32_enqueue = _sig("mgb_gemm_f32_enqueue", C.c_int, _vp, _vp, _vp, _vp, _u32, _u32, _u32)
 mgb_gemm_bf16_probe = _sig("mgb_gemm_bf16_probe", C.c_int, _u32, _u32, _u32, *_probe_tail)
@@ -136,7 +141,8 @@ mgb_copy_enqueue = _sig("mgb_copy_enqueue", C.c_int, _vp, _vp, _vp, _u64)
 
 EXPORTS = [
     "mgb_device_desc_default", "mgb_sched_create", "mgb_sched_destroy", "mgb_task_probe",
-    "mgb_task_wait", "mgb_task_cancel", "mgb_task_grow", "mgb_lazy_create", "mgb_lazy_destroy", "mgb_lazy_malloc",
+    "mgb_task_probe_ex", "mgb_gemm_f32_residency", "mgb_gemm_bf16_residency", "mgb_conv3x3_residency",
+    "mgb_cnn_residency", "mgb_task_wait", "mgb_task_cancel", "mgb_task_grow", "mgb_lazy_create", "mgb_lazy_destroy", "mgb_lazy_malloc",
     "mgb_lazy_memcpy_h2d", "mgb_lazy_memset", "mgb_lazy_launch_prepare", "mgb_lazy_memcpy_d2h", "mgb_lazy_free",
     "mgb_lazy_stats_get", "mgb_server_start", "mgb_server_stop", "mgb_server_reclaimed", "mgb_client_connect",
     "mgb_client_disconnect", "mgb_client_probe", "mgb_client_wait", "mgb_client_cancel", "mgb_client_grow",
@@ -316,11 +322,14 @@ class Sched:
         check(mgb_sched_create(C.byref(self.desc), C.byref(h)), "mgb_sched_create")
         self.h = h
 
-    def probe(self, task_id, mem_bytes, grid, block):
+    def probe(self, task_id, mem_bytes, grid, block, wg_per_cu=0):
         grid = grid if isinstance(grid, mgb_dim3) else mgb_dim3(*grid)
         block = block if isinstance(block, mgb_dim3) else mgb_dim3(*block)
         pl = mgb_placement()
-        rc = mgb_task_probe(self.h, task_id, mem_bytes, grid, block, C.byref(pl))
+        if wg_per_cu:
+            rc = mgb_task_probe_ex(self.h, task_id, mem_bytes, grid, block, wg_per_cu, C.byref(pl))
+        else:
+            rc = mgb_task_probe(self.h, task_id, mem_bytes, grid, block, C.byref(pl))
         return rc, pl
 
     def wait(self, ticket, timeout_ns=-1):

@@ -681,6 +681,44 @@ int mgb_conv3x3_probe(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uin
   return MGB_OK;
 }
 
+// workgroups of a layer's kernel that fit one CU (LDS of the ring / the strips; registers of the
+// register-staged kernel)
+static uint32_t residency_of(const Geometry& g, uint32_t c_out) {
+  switch (g.path) {
+    case PATH_DMA_128x128: return 2u;                 // 64 KiB ring
+    case PATH_DMA_256x64: return 2u;                  // 80 KiB ring
+    case PATH_DMA_64x64: return 5u;                   // 32 KiB ring
+    case PATH_C3: return c_out <= 32u ? 7u : 4u;      // 21 / 37 KiB of strips and output staging
+    case PATH_GENERIC: return 2u;                     // 162 - 244 registers per lane
+  }
+  return 0u;
+}
+
+uint32_t mgb_conv3x3_residency(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_out,
+                               uint32_t stride) {
+  if (!shape_ok(batch, h, w, c_in, c_out, stride)) return 0u;
+  return residency_of(geometry(batch, h, w, c_in, c_out, stride), c_out);
+}
+
+uint32_t mgb_cnn_residency(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, uint32_t h,
+                           uint32_t w) {
+  if (!layers || n_layers == 0u) return 0u;
+  uint32_t blocks = 0, threads = CV_THREADS, res = 0, ch = h, cw = w;
+  for (uint32_t i = 0; i < n_layers; ++i) {
+    const mgb_conv_layer& L = layers[i];
+    if (!shape_ok(batch, ch, cw, L.c_in, L.c_out, L.stride)) return 0u;
+    const Geometry g = geometry(batch, ch, cw, L.c_in, L.c_out, L.stride);
+    if ((uint64_t)g.blocks * g.threads > (uint64_t)blocks * threads) {   // the launch that gives the task its geometry
+      blocks = g.blocks;
+      threads = g.threads;
+      res = residency_of(g, L.c_out);
+    }
+    ch = g.Ho;
+    cw = g.Wo;
+  }
+  return res;
+}
+
 int mgb_conv3x3_enqueue(void* stream, const uint16_t* x, const uint16_t* w, void* y, uint32_t batch,
                         uint32_t h, uint32_t wd, uint32_t c_in, uint32_t c_out, uint32_t stride,
                         uint32_t out_f32) {

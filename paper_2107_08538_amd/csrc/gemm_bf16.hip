@@ -423,6 +423,14 @@ int mgb_gemm_bf16_probe(uint32_t m, uint32_t n, uint32_t k, uint64_t* mem_bytes,
   return MGB_OK;
 }
 
+uint32_t mgb_gemm_bf16_residency(uint32_t m, uint32_t n, uint32_t k) {
+  if (!shape_ok(m, n, k)) return 0u;
+  const Geometry g = geometry(m, n, k);
+  // 256 x 256 tiles: 512 registers per lane and a 128 KiB ring, one workgroup per CU; 128 x 128: a
+  // 64 KiB ring; the register-staged kernel: 207 registers per lane, two waves per SIMD
+  return g.dma ? (g.wt == 4u ? 1u : 2u) : 2u;
+}
+
 int mgb_gemm_bf16_enqueue(void* stream, const uint16_t* A, const uint16_t* B, float* C, uint32_t m,
                           uint32_t n, uint32_t k) {
   if (!A || !B || !C) return MGB_E_INVAL;

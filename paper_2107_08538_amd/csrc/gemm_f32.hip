@@ -389,6 +389,14 @@ int mgb_gemm_f32_probe(uint32_t m, uint32_t n, uint32_t k, uint64_t* mem_bytes, 
   return MGB_OK;
 }
 
+uint32_t mgb_gemm_f32_residency(uint32_t m, uint32_t n, uint32_t k) {
+  if (!shape_ok(m, n, k)) return 0u;
+  const Geometry g = geometry(m, n, k);
+  // LDS: the ring takes 64 KiB (128 x 128 tiles) or 32 KiB (64 x 64) of a CU's 160 KiB; the
+  // register-staged kernel is limited by its 8 waves per workgroup
+  return g.dma ? (g.small ? 5u : 2u) : 4u;
+}
+
 int mgb_gemm_f32_enqueue(void* stream, const float* A, const float* B, float* C, uint32_t m,
                          uint32_t n, uint32_t k) {
   if (!A || !B || !C) return MGB_E_INVAL;

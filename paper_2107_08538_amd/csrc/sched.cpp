@@ -445,11 +445,17 @@ int mgb_sched_destroy(mgb_sched* s) {
 
 int mgb_task_probe(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 grid,
                    mgb_dim3 block, mgb_placement* out) {
+  return mgb_task_probe_ex(s, task_id, mem_bytes, grid, block, 0u, out);
+}
+
+int mgb_task_probe_ex(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 grid,
+                      mgb_dim3 block, uint32_t wg_per_cu_task, mgb_placement* out) {
   if (!s || !out) return MGB_E_INVAL;
   std::memset(out, 0, sizeof *out);
   std::unique_lock<std::mutex> lk(s->mu);
   uint64_t cause = s->log(MGB_EV_PROBE, nullptr, task_id, 0, mem_bytes, grid, block, 0, 0, 0);
   s->trace.back().cause_seq = (uint32_t)cause;
+  s->trace.back().demand = wg_per_cu_task;           // input records carry what the caller passed
   const uint64_t W = (uint64_t)grid.x * grid.y * grid.z;
   const uint64_t T = (uint64_t)block.x * block.y * block.z;
   if (W == 0 || T == 0 || T > 1024) {
@@ -460,10 +466,13 @@ int mgb_task_probe(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 
     s->log(MGB_EV_REJECT, nullptr, task_id, 0, mem_bytes, grid, block, 0, MGB_E_TOO_BIG, cause);
     return MGB_E_TOO_BIG;
   }
-  // residency-based compute demand (per-CU wave and workgroup limits)
+  // residency-based compute demand (per-CU wave and workgroup limits, and what the task's own
+  // registers and LDS allow if the probe says so)
   const uint64_t waves_per_wg = (T + s->d.wave_size - 1) / s->d.wave_size;
   uint64_t wg_per_cu = s->d.max_waves_per_cu / waves_per_wg;
-  wg_per_cu = std::max<uint64_t>(1, std::min<uint64_t>(wg_per_cu, s->d.max_wg_per_cu));
+  wg_per_cu = std::min<uint64_t>(wg_per_cu, s->d.max_wg_per_cu);
+  if (wg_per_cu_task != 0u) wg_per_cu = std::min<uint64_t>(wg_per_cu, wg_per_cu_task);
+  wg_per_cu = std::max<uint64_t>(1, wg_per_cu);
   const uint64_t cus = std::min<uint64_t>(s->d.n_cu, (W + wg_per_cu - 1) / wg_per_cu);
   Task t;
   t.ticket = ++s->next_ticket;

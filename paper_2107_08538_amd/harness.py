@@ -17,7 +17,9 @@ def _ptr(t):
 class Task:
     """Device-resident buffers of one task plus its probe (footprint and geometry)."""
 
-    def __init__(self, spec, tensors, probe, enqueue, kernel_name, launches, alg_bytes=0.0, alg_flops=0.0):
+    def __init__(self, spec, tensors, probe, enqueue, kernel_name, launches, alg_bytes=0.0, alg_flops=0.0,
+                 wg_per_cu=0):
+        self.wg_per_cu = wg_per_cu      # workgroups per CU the kernel's registers and LDS allow (0: not known)
         self.spec = spec
         self.tensors = tensors          # keeps the device buffers alive
         self.mem, self.grid, self.block = probe
@@ -46,7 +48,8 @@ def build_task(spec, data, device="cuda:0"):
         probe = mgb.probe_of(mgb.mgb_gemm_f32_probe, m, n, kk)
         fn = lambda st: mgb.mgb_gemm_f32_enqueue(st, _ptr(A), _ptr(B), _ptr(Cc), m, n, kk)
         return Task(spec, dict(A=A, B=B, C=Cc), probe, fn, "gemm_f32_dma_kernel", 1,
-                    alg_bytes=4.0 * (m * kk + kk * n + m * n), alg_flops=2.0 * m * n * kk)
+                    alg_bytes=4.0 * (m * kk + kk * n + m * n), alg_flops=2.0 * m * n * kk,
+                    wg_per_cu=int(mgb.mgb_gemm_f32_residency(m, n, kk)))
     if k == "gemm_bf16":
         m, n, kk = p["m"], p["n"], p["k"]
         A = torch.from_numpy(data["a"].view("int16")).to(device)
@@ -55,7 +58,8 @@ def build_task(spec, data, device="cuda:0"):
         probe = mgb.probe_of(mgb.mgb_gemm_bf16_probe, m, n, kk)
         fn = lambda st: mgb.mgb_gemm_bf16_enqueue(st, _ptr(A), _ptr(B), _ptr(Cc), m, n, kk)
         return Task(spec, dict(A=A, B=B, C=Cc), probe, fn, "gemm_bf16_dma_kernel", 1,
-                    alg_bytes=2.0 * (m * kk + kk * n) + 4.0 * m * n, alg_flops=2.0 * m * n * kk)
+                    alg_bytes=2.0 * (m * kk + kk * n) + 4.0 * m * n, alg_flops=2.0 * m * n * kk,
+                    wg_per_cu=int(mgb.mgb_gemm_bf16_residency(m, n, kk)))
     if k == "bfs":
         n = p["n"]
         rp = torch.from_numpy(data["row_ptr"]).to(device)
@@ -87,7 +91,8 @@ def build_task(spec, data, device="cuda:0"):
         fn = lambda st: mgb.mgb_cnn_enqueue(st, arr, len(layers), _ptr(X), ptrs, _ptr(a0), _ptr(a1), _ptr(out), b, h, w)
         flops = sum(2.0 * b * L["h_out"] * L["w_out"] * L["c_out"] * 9 * L["c_in"] for L in layers)
         return Task(spec, dict(X=X, W=Wd, a0=a0, a1=a1, out=out, arr=arr, ptrs=ptrs), (mem.value, g, blk), fn,
-                    "conv3x3_kernel", len(layers), alg_bytes=float(mem.value - act.value), alg_flops=flops)
+                    "conv3x3_kernel", len(layers), alg_bytes=float(mem.value - act.value), alg_flops=flops,
+                    wg_per_cu=int(mgb.mgb_cnn_residency(arr, len(layers), b, h, w)))
     raise ValueError(k)
 
 
@@ -119,7 +124,7 @@ def run_mix(sched, tasks, use_arrivals=True, time_scale=1.0, workers=None):
     if pre_probed:
         for i, t in enumerate(tasks):
             rec[i]["arrival"] = 0.0
-            rc, pl = sched.probe(t.spec.task_id, t.mem, t.grid, t.block)
+            rc, pl = sched.probe(t.spec.task_id, t.mem, t.grid, t.block, t.wg_per_cu)
             rec[i]["probe"] = time.perf_counter() - t0
             if rc != mgb.MGB_E_OOM:
                 mgb.check(rc, "mgb_task_probe")
@@ -150,7 +155,7 @@ def run_mix(sched, tasks, use_arrivals=True, time_scale=1.0, workers=None):
                 rec[i]["arrival"] = t.spec.arrival_s * time_scale
             else:
                 rec[i]["arrival"] = 0.0
-            rc, pl = sched.probe(t.spec.task_id, t.mem, t.grid, t.block)
+            rc, pl = sched.probe(t.spec.task_id, t.mem, t.grid, t.block, t.wg_per_cu)
             rec[i]["probe"] = time.perf_counter() - t0
             if rc == mgb.MGB_E_OOM:
                 return crashed(i)

@@ -31,6 +31,7 @@ def split_trace(trace):
         inputs[i]["mem"] = r["mem_bytes"]
         inputs[i]["grid"] = r["grid"]
         inputs[i]["block"] = r["block"]
+        inputs[i]["wg_per_cu"] = r["demand"] if r["kind"] == mgb.MGB_EV_PROBE else 0    # the probe's residency fact
         seq_to_index[int(r["seq"])] = i
     return inputs, trace[~is_in], seq_to_index
 

@@ -96,6 +96,30 @@ def test_stuck_task_does_not_block_tasks_that_fit():
         assert list(pl.cu_mask) == [0] * (4 + i // 4) + [0xFF << (8 * (i % 4))] + [0] * (3 - i // 4)
 
 
+def test_residency_fact_enters_the_demand_and_the_trace():
+    s = _null(mem_cap_bytes=10 ** 6)                                  # 32 granules of 8 CUs
+    g, b = (256, 1, 1), (256, 1, 1)                                   # 4 waves per workgroup: 8 per CU by wave slots
+    want = {0: 4, 8: 4, 5: 7, 2: 16, 1: 32}                           # 256 / (8 | 8 | 5 | 2 | 1) CUs in granules of 8
+    for hint, granules in want.items():
+        rc, pl = s.probe(hint, 1, g, b, hint)
+        assert rc == mgb.MGB_OK and pl.n_granules == granules, (hint, pl.n_granules)
+        assert s.complete(pl.ticket) == mgb.MGB_OK
+    tr = s.trace()
+    assert [int(r["demand"]) for r in tr if r["kind"] == mgb.MGB_EV_PROBE] == list(want)
+    assert_trace_matches_replay(s.desc, tr)
+    # the kernels' own facts against the checker's formulas
+    lib = oracle.lib()
+    lib.orc_gemm_f32_residency.restype = lib.orc_gemm_bf16_residency.restype = lib.orc_conv3x3_residency.restype = C.c_uint64
+    U = C.c_uint64
+    for m, n, k in ((4096, 4096, 4096), (1024, 1024, 1024), (1000, 3000, 50), (2816, 2816, 64), (1, 8, 32), (129, 257, 17)):
+        assert mgb.mgb_gemm_f32_residency(m, n, k) == lib.orc_gemm_f32_residency(U(m), U(n), U(k)), (m, n, k)
+        assert mgb.mgb_gemm_bf16_residency(m, n, k) == lib.orc_gemm_bf16_residency(U(m), U(n), U(k)), (m, n, k)
+    for shp in ((1, 416, 416, 3, 32, 1), (8, 416, 416, 32, 64, 2), (8, 104, 104, 128, 128, 1), (1, 104, 104, 128, 128, 1),
+                (2, 416, 416, 3, 64, 1), (1, 5, 6, 5, 7, 1), (8, 208, 208, 64, 64, 1)):
+        assert mgb.mgb_conv3x3_residency(*shp) == lib.orc_conv3x3_residency(*[U(x) for x in shp]), shp
+    assert mgb.mgb_gemm_f32_residency(0, 1, 1) == 0
+
+
 def test_grow_in_the_library():
     s = _null(mem_cap_bytes=1000)
     rc, p1 = s.probe(1, 400, (4, 1, 1), (64, 1, 1))
@@ -153,7 +177,7 @@ def _random_storm(s, rng, n_ops):
             mem = int(rng.integers(1, 6000))
             grid = (int(rng.integers(0 if rng.random() < 0.02 else 1, 4000)), int(rng.integers(1, 3)), 1)
             block = (int(rng.choice([64, 192, 256, 1024])), 1, 1)
-            rc, pl = s.probe(i, mem, grid, block)
+            rc, pl = s.probe(i, mem, grid, block, int(rng.choice([0, 0, 1, 2, 5])))    # with or without a residency fact
             if rc >= 0:
                 live.append(pl.ticket)
         else:

@@ -85,6 +85,23 @@ def test_demand_is_smallest_device_that_holds_all_blocks(threads, max_tb, max_wa
         assert d == want, (threads, blocks, d, want)
 
 
+@pytest.mark.parametrize("hint", [1, 2, 3, 5, 40])
+def test_demand_with_the_tasks_own_residency_limit(hint):
+    # a task whose registers / LDS allow `hint` workgroups per CU: the thread-block-by-thread-block
+    # emulation with that limit on resident blocks, against the rule
+    n_cu, max_tb, max_warps = 24, 16, 32
+    dev = oracle.device(1 << 30, n_cu=n_cu, granule_cus=1, max_waves_per_cu=max_warps, max_wg_per_cu=max_tb)
+    for threads in (64, 256, 512):
+        wpb = -(-threads // 64)
+        for blocks in (1, 2, 7, 24, 25, 48, 49, 100, 383, 384, 385, 1000):
+            d, _ = oracle.demand(dev, (blocks, 1, 1), (threads, 1, 1), wg_per_cu=hint)
+            tb = min(max_tb, hint)
+            smallest = next((c for c in range(1, n_cu + 1) if _alg2_places_all(c, blocks, wpb, tb, max_warps)), n_cu)
+            assert d == smallest, (threads, blocks, d, smallest)
+    # 0 = not known = the device limits alone
+    assert oracle.demand(dev, (100, 1, 1), (256, 1, 1), wg_per_cu=0) == oracle.demand(dev, (100, 1, 1), (256, 1, 1))
+
+
 def test_demand_uses_all_three_dimensions_and_granule_rounding():
     dev = oracle.device(1 << 30)               # 256 CUs, granules of 8, 256 threads -> 8 wg/CU
     assert oracle.demand(dev, (4, 4, 4), (16, 4, 4))[0] == 1         # 64 wg -> 8 CUs -> 1 granule
