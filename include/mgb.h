@@ -251,9 +251,10 @@ int mgb_lazy_malloc(mgb_lazy* z, uint64_t bytes, uint64_t* pseudo);
 int mgb_lazy_memcpy_h2d(mgb_lazy* z, uint64_t dst_pseudo, const void* src_host, uint64_t bytes);
 int mgb_lazy_memset(mgb_lazy* z, uint64_t dst_pseudo, int value, uint64_t bytes);
 /* Before a kernel launch: `pseudo_args[0..n_args)` are the memory objects the
- * kernel accesses (n_args >= 1), grid / block its geometry.
+ * kernel accesses (n_args >= 1), grid / block its geometry, wg_per_cu its residency (0 = not
+ * known), as in mgb_task_probe_ex.
  *  - none of the objects is on the device: a new task.  Its footprint is the
- *    sum of the objects' sizes; mgb_task_probe(task_id, footprint, grid, block)
+ *    sum of the objects' sizes; mgb_task_probe_ex(task_id, footprint, grid, block, wg_per_cu)
  *    is issued and, if the task is queued, waited for up to timeout_ns (< 0:
  *    forever; on MGB_TIMEOUT the probe is cancelled and nothing has changed).
  *  - some are: the launch joins their task (launches that share memory objects
@@ -266,8 +267,8 @@ int mgb_lazy_memset(mgb_lazy* z, uint64_t dst_pseudo, int value, uint64_t bytes)
  * pseudo_args[i]; placement->stream is the stream to launch on (ticket: the
  * task's first ticket; masks are filled for a new task only).                  */
 int mgb_lazy_launch_prepare(mgb_lazy* z, uint64_t task_id, const uint64_t* pseudo_args, uint32_t n_args,
-                            mgb_dim3 grid, mgb_dim3 block, int64_t timeout_ns, void** real_args,
-                            mgb_placement* placement);
+                            mgb_dim3 grid, mgb_dim3 block, uint32_t wg_per_cu, int64_t timeout_ns,
+                            void** real_args, mgb_placement* placement);
 /* Stand-in for a device-to-host copy; waits for the task's stream first.  For an
  * object no kernel has used yet the bytes are those the recorded writes left
  * (unwritten bytes read as zero).                                               */
@@ -285,7 +286,8 @@ int mgb_lazy_stats_get(mgb_lazy* z, mgb_lazy_stats* out);
  * null backend: the server only takes decisions.  MGB_E_BUSY if the name is in
  * use.  A client whose process has died has its queued probes withdrawn and its
  * resident tasks completed (mgb_server_reclaimed counts such tasks).
- * Client side (any process): the mgb_client_* calls mirror mgb_task_*; the
+ * Client side (any process): the mgb_client_* calls mirror mgb_task_* (mgb_client_probe takes the
+ * residency fact of mgb_task_probe_ex, 0 = not known); the
  * placement carries ticket, granules and CU mask, its stream field is NULL.
  * mgb_client_stream gives the calling process's own CU-masked hipStream_t for
  * the placement's mask (created on first use, cached, destroyed at
@@ -299,7 +301,7 @@ uint64_t mgb_server_reclaimed(mgb_server* sv);
 int mgb_client_connect(const char* name, mgb_client** out);
 int mgb_client_disconnect(mgb_client* c);
 int mgb_client_probe(mgb_client* c, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 grid, mgb_dim3 block,
-                     mgb_placement* out);
+                     uint32_t wg_per_cu, mgb_placement* out);
 int mgb_client_wait(mgb_client* c, uint64_t ticket, int64_t timeout_ns, mgb_placement* out);
 int mgb_client_cancel(mgb_client* c, uint64_t ticket);
 int mgb_client_grow(mgb_client* c, uint64_t ticket, uint64_t extra_bytes);

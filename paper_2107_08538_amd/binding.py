@@ -101,7 +101,7 @@ mgb_lazy_malloc = _sig("mgb_lazy_malloc", C.c_int, _vp, _u64, C.POINTER(C.c_uint
 mgb_lazy_memcpy_h2d = _sig("mgb_lazy_memcpy_h2d", C.c_int, _vp, _u64, _vp, _u64)
 mgb_lazy_memset = _sig("mgb_lazy_memset", C.c_int, _vp, _u64, C.c_int, _u64)
 mgb_lazy_launch_prepare = _sig("mgb_lazy_launch_prepare", C.c_int, _vp, _u64, C.POINTER(C.c_uint64), _u32,
-                               mgb_dim3, mgb_dim3, C.c_int64, C.POINTER(C.c_void_p), C.POINTER(mgb_placement))
+                               mgb_dim3, mgb_dim3, _u32, C.c_int64, C.POINTER(C.c_void_p), C.POINTER(mgb_placement))
 mgb_lazy_memcpy_d2h = _sig("mgb_lazy_memcpy_d2h", C.c_int, _vp, _vp, _u64, _u64)
 mgb_lazy_free = _sig("mgb_lazy_free", C.c_int, _vp, _u64)
 mgb_lazy_stats_get = _sig("mgb_lazy_stats_get", C.c_int, _vp, C.POINTER(mgb_lazy_stats))
@@ -194,7 +194,7 @@ mgb_server_stop = _sig("mgb_server_stop", C.c_int, _vp)
 mgb_server_reclaimed = _sig("mgb_server_reclaimed", C.c_uint64, _vp)
 mgb_client_connect = _sig("mgb_client_connect", C.c_int, C.c_char_p, C.POINTER(C.c_void_p))
 mgb_client_disconnect = _sig("mgb_client_disconnect", C.c_int, _vp)
-mgb_client_probe = _sig("mgb_client_probe", C.c_int, _vp, _u64, _u64, mgb_dim3, mgb_dim3, C.POINTER(mgb_placement))
+mgb_client_probe = _sig("mgb_client_probe", C.c_int, _vp, _u64, _u64, mgb_dim3, mgb_dim3, _u32, C.POINTER(mgb_placement))
 mgb_client_wait = _sig("mgb_client_wait", C.c_int, _vp, _u64, C.c_int64, C.POINTER(mgb_placement))
 mgb_client_cancel = _sig("mgb_client_cancel", C.c_int, _vp, _u64)
 mgb_client_grow = _sig("mgb_client_grow", C.c_int, _vp, _u64, _u64)
@@ -228,11 +228,11 @@ class Client:
         check(mgb_client_connect(name.encode(), C.byref(h)), "mgb_client_connect")
         self.h = h
 
-    def probe(self, task_id, mem_bytes, grid, block):
+    def probe(self, task_id, mem_bytes, grid, block, wg_per_cu=0):
         grid = grid if isinstance(grid, mgb_dim3) else mgb_dim3(*grid)
         block = block if isinstance(block, mgb_dim3) else mgb_dim3(*block)
         pl = mgb_placement()
-        rc = mgb_client_probe(self.h, task_id, mem_bytes, grid, block, C.byref(pl))
+        rc = mgb_client_probe(self.h, task_id, mem_bytes, grid, block, wg_per_cu, C.byref(pl))
         return rc, pl
 
     def wait(self, ticket, timeout_ns=-1):
@@ -285,14 +285,14 @@ class Lazy:
     def memset(self, dst_pseudo, value, nbytes):
         return mgb_lazy_memset(self.h, dst_pseudo, value, nbytes)
 
-    def launch_prepare(self, task_id, pseudo_args, grid, block, timeout_ns=-1):
+    def launch_prepare(self, task_id, pseudo_args, grid, block, timeout_ns=-1, wg_per_cu=0):
         n = len(pseudo_args)
         args = (C.c_uint64 * n)(*pseudo_args)
         real = (C.c_void_p * n)()
         pl = mgb_placement()
         grid = grid if isinstance(grid, mgb_dim3) else mgb_dim3(*grid)
         block = block if isinstance(block, mgb_dim3) else mgb_dim3(*block)
-        rc = mgb_lazy_launch_prepare(self.h, task_id, args, n, grid, block, timeout_ns, real, C.byref(pl))
+        rc = mgb_lazy_launch_prepare(self.h, task_id, args, n, grid, block, wg_per_cu, timeout_ns, real, C.byref(pl))
         return rc, [int(x or 0) for x in real], pl
 
     def memcpy_d2h(self, host_ptr, src_pseudo, nbytes):

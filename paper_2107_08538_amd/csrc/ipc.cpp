@@ -50,6 +50,7 @@ struct Slot {
   sem_t req, resp;
   uint32_t op;
   int32_t rc;
+  uint32_t wg_per_cu;
   uint64_t task_id, ticket, bytes;
   int64_t timeout_ns;
   mgb_dim3 grid, block;
@@ -120,7 +121,7 @@ struct mgb_server {
       if (seg->stopping.load()) break;
       switch (sl.op) {
         case OP_PROBE:
-          sl.rc = mgb_task_probe(s, sl.task_id, sl.bytes, sl.grid, sl.block, &sl.placement);
+          sl.rc = mgb_task_probe_ex(s, sl.task_id, sl.bytes, sl.grid, sl.block, sl.wg_per_cu, &sl.placement);
           if (sl.rc == MGB_OK || sl.rc == MGB_WAIT) held[i].push_back(sl.placement.ticket);
           break;
         case OP_WAIT: {
@@ -312,7 +313,7 @@ int mgb_client_disconnect(mgb_client* c) {
 }
 
 int mgb_client_probe(mgb_client* c, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 grid, mgb_dim3 block,
-                     mgb_placement* out) {
+                     uint32_t wg_per_cu, mgb_placement* out) {
   if (!c || !out) return MGB_E_INVAL;
   std::lock_guard<std::mutex> lk(c->mu);
   Slot& sl = c->seg->slots[c->slot];
@@ -320,6 +321,7 @@ int mgb_client_probe(mgb_client* c, uint64_t task_id, uint64_t mem_bytes, mgb_di
   sl.bytes = mem_bytes;
   sl.grid = grid;
   sl.block = block;
+  sl.wg_per_cu = wg_per_cu;
   const int rc = c->call(OP_PROBE);
   *out = sl.placement;
   return rc;

@@ -221,8 +221,8 @@ int mgb_lazy_memset(mgb_lazy* z, uint64_t dst_pseudo, int value, uint64_t bytes)
 }
 
 int mgb_lazy_launch_prepare(mgb_lazy* z, uint64_t task_id, const uint64_t* pseudo_args, uint32_t n_args,
-                            mgb_dim3 grid, mgb_dim3 block, int64_t timeout_ns, void** real_args,
-                            mgb_placement* placement) {
+                            mgb_dim3 grid, mgb_dim3 block, uint32_t wg_per_cu, int64_t timeout_ns,
+                            void** real_args, mgb_placement* placement) {
   if (!z || !pseudo_args || !real_args || !placement || n_args == 0u) return MGB_E_INVAL;
   std::lock_guard<std::mutex> lk(z->mu);
   // the memory objects the kernel names
@@ -245,7 +245,7 @@ int mgb_lazy_launch_prepare(mgb_lazy* z, uint64_t task_id, const uint64_t* pseud
   if (owners.empty()) {
     // a new task: its footprint is what the kernel's objects add up to
     mgb_placement pl;
-    int rc = mgb_task_probe(z->s, task_id, extra, grid, block, &pl);
+    int rc = mgb_task_probe_ex(z->s, task_id, extra, grid, block, wg_per_cu, &pl);
     if (rc == MGB_WAIT) {
       const uint64_t ticket = pl.ticket;
       rc = mgb_task_wait(z->s, ticket, timeout_ns, &pl);

@@ -37,7 +37,7 @@ def test_gemm_task_built_lazily_matches_checker_and_declared_footprint():
     a[:] = 0                                           # the copy kept its own bytes
     assert len(s.trace()) == 0
     mem, grid, block = mgb.probe_of(mgb.mgb_gemm_f32_probe, m, n, k)
-    rc, real, pl = z.launch_prepare(11, [pa, pb, pc], grid, block)
+    rc, real, pl = z.launch_prepare(11, [pa, pb, pc], grid, block, wg_per_cu=mgb.mgb_gemm_f32_residency(m, n, k))
     assert rc == 0 and pl.stream and all(real)
     assert mgb.mgb_gemm_f32_enqueue(pl.stream, real[0], real[1], real[2], m, n, k) == 0
     got = _d2h(z, pc, (m, n), np.float32).astype(np.float64)

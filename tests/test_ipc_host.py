@@ -37,7 +37,7 @@ def test_protocol_in_one_process():
     c1, c2 = mgb.Client(name), mgb.Client(name)
     with pytest.raises(mgb.MgbError):
         mgb.Client(name)                                     # both slots are taken
-    rc, p1 = c1.probe(1, 700, (512, 1, 1), (256, 1, 1))
+    rc, p1 = c1.probe(1, 700, (128, 1, 1), (256, 1, 1), wg_per_cu=2)          # 8 per CU by wave slots, 2 by its own resources
     assert rc == mgb.MGB_OK and p1.n_granules == 8 and p1.granule_mask == 0xFF and p1.cu_mask[0] == 0xFFFFFFFF
     assert p1.stream is None
     rc, p2 = c2.probe(2, 700, (8, 1, 1), (64, 1, 1))
