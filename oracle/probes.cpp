@@ -38,15 +38,20 @@ void orc_jacobi_probe(uint64_t n, uint64_t out[7]) {
   out[4] = 256; out[5] = 1; out[6] = 1;
 }
 
-// fp32 GEMM: A, B, C in fp32; one 512-thread workgroup (8 waves) per 128 x 128 tile of C.  When k
-// is a multiple of 16, n a multiple of 4 and there would be fewer than 128 such tiles: one
-// 256-thread workgroup per 64 x 64 tile instead.
+// fp32 GEMM: A, B, C in fp32.  When k is a multiple of 16 and n a multiple of 4 the tile is the
+// 256 x 256 (256 threads) if that gives at least 256 workgroups, else 128 x 128 (512 threads) if
+// that gives at least 128, else 64 x 64 (256 threads); otherwise 128 x 128 with 512 threads.
+static uint64_t f32_tile(uint64_t m, uint64_t n, uint64_t k) {
+  if (k % 16 != 0 || n % 4 != 0) return 128;
+  if (ceil_div(m, 256) * ceil_div(n, 256) >= 256) return 256;
+  if (ceil_div(m, 128) * ceil_div(n, 128) >= 128) return 128;
+  return 64;
+}
 void orc_gemm_f32_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
   out[0] = (m * k + k * n + m * n) * 4;
-  uint64_t wgs = ceil_div(m, 128) * ceil_div(n, 128), threads = 512;
-  if (k % 16 == 0 && n % 4 == 0 && wgs < 128) { wgs = ceil_div(m, 64) * ceil_div(n, 64); threads = 256; }
-  out[1] = round8(wgs); out[2] = 1; out[3] = 1;
-  out[4] = threads; out[5] = 1; out[6] = 1;
+  uint64_t t = f32_tile(m, n, k);
+  out[1] = round8(ceil_div(m, t) * ceil_div(n, t)); out[2] = 1; out[3] = 1;
+  out[4] = t == 128 ? 512 : 256; out[5] = 1; out[6] = 1;
 }
 
 // bf16 GEMM: bf16 A and B, fp32 C.  When k is a multiple of 32 and n a multiple of 8: one
@@ -118,7 +123,7 @@ void orc_cnn_probe(const uint64_t* c, uint64_t n_layers, uint64_t batch, uint64_
 //   register-staged one is limited by its 8 waves per workgroup.
 uint64_t orc_gemm_f32_residency(uint64_t m, uint64_t n, uint64_t k) {
   if (k % 16 == 0 && n % 4 == 0) {
-    uint64_t tile = ceil_div(m, 128) * ceil_div(n, 128) < 128 ? 64 : 128;
+    uint64_t tile = f32_tile(m, n, k);
     return (160 * 1024) / (4 * (tile + tile) * 16 * 4);
   }
   return 32 / 8;

@@ -179,9 +179,10 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
 // instructions are spread between the MFMAs and pinned.
 //
 // WGM x WGN waves, each TM x TN MFMA blocks of 32 x 32:
-//   2 x 4 waves of 64 x 32: 128 x 128 tile, 512 threads (as many waves per tile as the
-//                           register-staged kernel, so a task asks for the same share of the device)
-//   2 x 2 waves of 32 x 32: 64 x 64 tile, 256 threads, for shapes with few big tiles
+//   2 x 2 waves of 128 x 128: 256 x 256 tile, 256 threads, 256 accumulator registers, one workgroup
+//                             per CU (12 LDS reads and 4 DMA instructions per 64 MFMAs)
+//   2 x 4 waves of 64 x 32:   128 x 128 tile, 512 threads, when there are too few 256 x 256 tiles
+//   2 x 2 waves of 32 x 32:   64 x 64 tile, 256 threads, when there are too few 128 x 128 tiles
 // Depth 16 per tile: an A row is 64 bytes, the same byte geometry (and swizzle) as the bf16 kernels.
 //
 // k order inside a tile: the MFMA's two k slots (lane / 32) take k = 8 * (lane / 32) + s in step
@@ -192,7 +193,7 @@ constexpr uint32_t FD_BK = 16, FD_NST = 4, FD_BAND = 8;
 constexpr uint32_t fd_lds_bytes(uint32_t bm, uint32_t bn) { return FD_NST * (bm + bn) * FD_BK * 4u; }
 
 template <uint32_t WGM, uint32_t WGN, uint32_t TM, uint32_t TN>
-__global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_f32_dma_kernel(const float* __restrict__ A,
+__global__ __launch_bounds__(64 * WGM * WGN, TM * TN >= 16 ? 1 : 2) void gemm_f32_dma_kernel(const float* __restrict__ A,
                                                                        const float* __restrict__ B,
                                                                        float* __restrict__ C, uint32_t M,
                                                                        uint32_t N, uint32_t K, uint32_t tiles_n,
@@ -348,24 +349,29 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_f32_dma_kernel(const f
 
 struct Geometry {
   uint32_t tiles_m, tiles_n, total, blocks, threads;
-  bool dma;     // shape fits the DMA kernel (operand alignment is checked at enqueue)
-  bool small;   // DMA kernel on 64 x 64 tiles
-  bool fast;    // register-staged kernel: every tile full
+  bool dma;        // shape fits the DMA kernel (operand alignment is checked at enqueue)
+  uint32_t tile;   // 256, 128 or 64 (DMA kernel); 128 (register-staged kernel)
+  bool fast;       // register-staged kernel: every tile full
 };
 
-// 64 x 64 tiles when 128 x 128 ones would leave half of the 256 CUs without a tile
-constexpr uint32_t FD_MIN_BIG_TILES = 128;
+// 256 x 256 tiles if every CU gets one (139 against 136 TFLOP/s at 4096^3; with fewer tiles than
+// CUs the smaller tile wins: 3072^3 runs at 97 TFLOP/s on 128 x 128 tiles, 78 on 256 x 256), else
+// 128 x 128 tiles if they give at least half of the CUs a workgroup, else 64 x 64
+constexpr uint32_t FD_MIN_TILES_256 = 256, FD_MIN_TILES_128 = 128;
 
 Geometry geometry(uint32_t m, uint32_t n, uint32_t k, bool allow_dma = true) {
   Geometry g;
   g.dma = allow_dma && k % FD_BK == 0u && n % 4u == 0u;
-  g.small = g.dma && ((m + 127u) / 128u) * ((n + 127u) / 128u) < FD_MIN_BIG_TILES;
-  const uint32_t t = g.small ? 64u : 128u;
-  g.tiles_m = (m + t - 1u) / t;
-  g.tiles_n = (n + t - 1u) / t;
+  g.tile = 128u;
+  if (g.dma) {
+    if (((m + 255u) / 256u) * ((n + 255u) / 256u) >= FD_MIN_TILES_256) g.tile = 256u;
+    else if (((m + 127u) / 128u) * ((n + 127u) / 128u) < FD_MIN_TILES_128) g.tile = 64u;
+  }
+  g.tiles_m = (m + g.tile - 1u) / g.tile;
+  g.tiles_n = (n + g.tile - 1u) / g.tile;
   g.total = g.tiles_m * g.tiles_n;
   g.blocks = ((g.total + 7u) / 8u) * 8u;
-  g.threads = g.small ? 256u : GF_THREADS;
+  g.threads = g.dma && g.tile != 128u ? 256u : GF_THREADS;
   g.fast = m % GF_BM == 0u && n % GF_BN == 0u && k % GF_BK == 0u;
   return g;
 }
@@ -392,9 +398,10 @@ int mgb_gemm_f32_probe(uint32_t m, uint32_t n, uint32_t k, uint64_t* mem_bytes, 
 uint32_t mgb_gemm_f32_residency(uint32_t m, uint32_t n, uint32_t k) {
   if (!shape_ok(m, n, k)) return 0u;
   const Geometry g = geometry(m, n, k);
-  // LDS: the ring takes 64 KiB (128 x 128 tiles) or 32 KiB (64 x 64) of a CU's 160 KiB; the
-  // register-staged kernel is limited by its 8 waves per workgroup
-  return g.dma ? (g.small ? 5u : 2u) : 4u;
+  // LDS: the ring takes 128 KiB (256 x 256 tiles, which also need all 512 registers of a lane),
+  // 64 KiB (128 x 128) or 32 KiB (64 x 64) of a CU's 160 KiB; the register-staged kernel is limited
+  // by its 8 waves per workgroup
+  return g.dma ? (g.tile == 256u ? 1u : g.tile == 128u ? 2u : 5u) : 4u;
 }
 
 int mgb_gemm_f32_enqueue(void* stream, const float* A, const float* B, float* C, uint32_t m,
@@ -408,8 +415,11 @@ int mgb_gemm_f32_enqueue(void* stream, const float* A, const float* B, float* C,
     static std::once_flag once;
     static hipError_t attr = hipSuccess;
     std::call_once(once, [] {
-      attr = hipFuncSetAttribute((const void*)gemm_f32_dma_kernel<2, 4, 2, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 (int)fd_lds_bytes(128, 128));
+      attr = hipFuncSetAttribute((const void*)gemm_f32_dma_kernel<2, 2, 4, 4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 (int)fd_lds_bytes(256, 256));
+      if (attr == hipSuccess)
+        attr = hipFuncSetAttribute((const void*)gemm_f32_dma_kernel<2, 4, 2, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)fd_lds_bytes(128, 128));
       if (attr == hipSuccess)
         attr = hipFuncSetAttribute((const void*)gemm_f32_dma_kernel<2, 2, 1, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (int)fd_lds_bytes(64, 64));
@@ -418,11 +428,14 @@ int mgb_gemm_f32_enqueue(void* stream, const float* A, const float* B, float* C,
       mgb_internal_set_error("gemm_f32_dma_kernel: dynamic LDS size", attr);
       return MGB_E_BACKEND;
     }
-    if (g.small)
-      hipLaunchKernelGGL((gemm_f32_dma_kernel<2, 2, 1, 1>), dim3(g.blocks), dim3(g.threads), fd_lds_bytes(64, 64), st,
+    if (g.tile == 256u)
+      hipLaunchKernelGGL((gemm_f32_dma_kernel<2, 2, 4, 4>), dim3(g.blocks), dim3(g.threads), fd_lds_bytes(256, 256), st,
+                         A, B, C, m, n, k, g.tiles_n, g.total);
+    else if (g.tile == 128u)
+      hipLaunchKernelGGL((gemm_f32_dma_kernel<2, 4, 2, 1>), dim3(g.blocks), dim3(g.threads), fd_lds_bytes(128, 128), st,
                          A, B, C, m, n, k, g.tiles_n, g.total);
     else
-      hipLaunchKernelGGL((gemm_f32_dma_kernel<2, 4, 2, 1>), dim3(g.blocks), dim3(g.threads), fd_lds_bytes(128, 128), st,
+      hipLaunchKernelGGL((gemm_f32_dma_kernel<2, 2, 1, 1>), dim3(g.blocks), dim3(g.threads), fd_lds_bytes(64, 64), st,
                          A, B, C, m, n, k, g.tiles_n, g.total);
     return mgb_check_launch("gemm_f32_dma_kernel");
   }

@@ -111,7 +111,8 @@ def test_residency_fact_enters_the_demand_and_the_trace():
     lib = oracle.lib()
     lib.orc_gemm_f32_residency.restype = lib.orc_gemm_bf16_residency.restype = lib.orc_conv3x3_residency.restype = C.c_uint64
     U = C.c_uint64
-    for m, n, k in ((4096, 4096, 4096), (1024, 1024, 1024), (1000, 3000, 50), (2816, 2816, 64), (1, 8, 32), (129, 257, 17)):
+    for m, n, k in ((4096, 4096, 4096), (1024, 1024, 1024), (1000, 3000, 50), (2816, 2816, 64), (1, 8, 32), (129, 257, 17),
+                    (2048, 2048, 64)):
         assert mgb.mgb_gemm_f32_residency(m, n, k) == lib.orc_gemm_f32_residency(U(m), U(n), U(k)), (m, n, k)
         assert mgb.mgb_gemm_bf16_residency(m, n, k) == lib.orc_gemm_bf16_residency(U(m), U(n), U(k)), (m, n, k)
     for shp in ((1, 416, 416, 3, 32, 1), (8, 416, 416, 32, 64, 2), (8, 104, 104, 128, 128, 1), (1, 104, 104, 128, 128, 1),
@@ -299,7 +300,7 @@ def test_probe_functions_agree_with_checker_formulas():
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), n
     for m, n, k in ((1, 1, 1), (128, 128, 16), (129, 257, 17), (256, 256, 256), (4096, 4096, 4096),
                     (32768, 32768, 32768), (1000, 3000, 50), (1024, 1024, 1024), (1408, 1536, 64), (1408, 1408, 64),
-                    (1000, 3000, 48), (1000, 3002, 48)):
+                    (1000, 3000, 48), (1000, 3002, 48), (2816, 2816, 64), (4096, 4096, 64), (4096, 3840, 64), (8192, 8192, 16)):
         mem, grid, block = mgb.probe_of(mgb.mgb_gemm_f32_probe, m, n, k)
         oracle.lib().orc_gemm_f32_probe(C.c_uint64(m), C.c_uint64(n), C.c_uint64(k), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (m, n, k)

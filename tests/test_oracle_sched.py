@@ -396,7 +396,7 @@ def test_probe_formulas_match_stated_footprints():
     assert out[1] == 34304 and out[4] == 256           # 67 x 2048 windows, four per workgroup
     oracle.lib().orc_gemm_f32_probe(C.c_uint64(32768), C.c_uint64(32768), C.c_uint64(32768), out)
     assert out[0] == 12 * 2 ** 30                    # "about 12 GiB" per GEMM 32768^3 task
-    assert out[1] == 256 * 256
+    assert out[1] == 128 * 128 and out[4] == 256       # 256 x 256 tiles, four waves each
     oracle.lib().orc_jacobi_probe(C.c_uint64(512), out)
     assert out[0] == 2 * 512 * 512 * 4 and out[1] == 48   # 3 x 64 windows, four per workgroup
     oracle.lib().orc_gemm_f32_probe(C.c_uint64(256), C.c_uint64(256), C.c_uint64(256), out)
