@@ -255,7 +255,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, TM * TN >= 16 ? 1 : 2) void gemm_f3
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // fragment addresses inside a stage: half hf covers steps 4 hf .. 4 hf + 3
-  uint32_t a_off[2][TM], b_off[2][4][TN];
+  uint32_t a_off[2][TM], b_off[2][2][TN];   // B: steps 0 and 2 of a half; steps 1 and 3 are one row further
 #pragma unroll
   for (uint32_t hf = 0; hf < 2; ++hf) {
 #pragma unroll
@@ -264,10 +264,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, TM * TN >= 16 ? 1 : 2) void gemm_f3
       a_off[hf][i] = row * 64u + (((2u * lhi + hf) ^ row_swz(row)) << 4);      // k = 8 lhi + 4 hf .. + 3
     }
 #pragma unroll
-    for (uint32_t s = 0; s < 4; ++s)
+    for (uint32_t s = 0; s < 2; ++s)
 #pragma unroll
       for (uint32_t j = 0; j < TN; ++j) {
-        const uint32_t krow = 8u * lhi + 4u * hf + s, col = wn + 32u * j + l32;
+        const uint32_t krow = 8u * lhi + 4u * hf + 2u * s, col = wn + 32u * j + l32;
         b_off[hf][s][j] = A_BYTES + krow * B_ROW + (((col >> 2) ^ b_swz(krow)) << 4) + (col & 3u) * 4u;
       }
   }
@@ -280,9 +280,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, TM * TN >= 16 ? 1 : 2) void gemm_f3
   auto frag_load = [&](const uint8_t* st, uint32_t hf, uint32_t slot, uint32_t q) {
     if (q < TM) fa[slot][q] = *reinterpret_cast<const float4*>(st + a_off[hf][q]);
     else {
+      // the next step's k row is the next LDS row (same swizzle: a half never crosses k = 8), a
+      // constant distance away, so the pair becomes one two-address read
       const uint32_t x = q - TM, s2 = 2u * (x / TN), j = x % TN;
-      fb[slot][s2][j] = *reinterpret_cast<const float*>(st + b_off[hf][s2][j]);
-      fb[slot][s2 + 1u][j] = *reinterpret_cast<const float*>(st + b_off[hf][s2 + 1u][j]);
+      const uint8_t* p = st + b_off[hf][s2 / 2u][j];
+      fb[slot][s2][j] = *reinterpret_cast<const float*>(p);
+      fb[slot][s2 + 1u][j] = *reinterpret_cast<const float*>(p + B_ROW);
     }
   };
   auto dma_one = [&](uint32_t kt, uint32_t part, uint32_t h) {
