@@ -72,7 +72,8 @@ void orc_gemm_bf16_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
 
 // One 3x3 conv layer (pad 1): bf16 input, weights and output.  Workgroup shape by layer:
 //   c_in % 32 == 0 and c_out % 8 == 0: 256 threads per 128 pixels x 128 channels (256 x 64 when
-//     c_out <= 64); if that gives fewer than 256 workgroups, 64 threads per 64 x 64 instead;
+//     c_out <= 64); if that gives fewer than 256 workgroups, 64 x 64 tiles instead, with 256
+//     threads (the depth split four ways) when c_in % 64 == 0, else 64 threads;
 //   c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64: 256 threads per 256 pixels (all channels);
 //   otherwise 256 threads per 128 pixels x 64 channels (128 channels when c_out > 64).
 void orc_conv3x3_probe(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, uint64_t c_out,
@@ -83,7 +84,7 @@ void orc_conv3x3_probe(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, ui
   uint64_t wgs, threads = 256;
   if (c_in % 32 == 0 && c_out % 8 == 0) {
     wgs = c_out > 64 ? ceil_div(pixels, 128) * ceil_div(c_out, 128) : ceil_div(pixels, 256) * ceil_div(c_out, 64);
-    if (wgs < 256) { wgs = ceil_div(pixels, 64) * ceil_div(c_out, 64); threads = 64; }
+    if (wgs < 256) { wgs = ceil_div(pixels, 64) * ceil_div(c_out, 64); threads = c_in % 64 == 0 ? 256 : 64; }
   } else if (c_in == 3 && stride == 1 && c_out % 8 == 0 && c_out <= 64) {
     wgs = ceil_div(pixels, 256);
   } else {
@@ -137,15 +138,16 @@ uint64_t orc_gemm_bf16_residency(uint64_t m, uint64_t n, uint64_t k) {
   }
   return 2;
 }
-//   conv: ring of (pixels + channels) x 32 bf16 x 4 stages; first-layer kernel: 3 strips of 776 bf16 +
+//   conv: ring of (pixels + channels) x 32 bf16 x 4 stages (x 64 bf16 for the depth-split tiles); first-layer kernel: 3 strips of 776 bf16 +
 //   256 x c_out' bf16 of output staging (c_out' = c_out rounded up to 32); register-staged: 2.
 uint64_t orc_conv3x3_residency(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, uint64_t c_out,
                                uint64_t stride) {
   uint64_t ho = (h - 1) / stride + 1, wo = (w - 1) / stride + 1, pixels = batch * ho * wo;
   if (c_in % 32 == 0 && c_out % 8 == 0) {
     uint64_t tp = c_out > 64 ? 128 : 256, tc = c_out > 64 ? 128 : 64;
-    if (ceil_div(pixels, tp) * ceil_div(c_out, tc) < 256) tp = tc = 64;
-    return (160 * 1024) / (4 * (tp + tc) * 32 * 2);
+    uint64_t bk = 32;
+    if (ceil_div(pixels, tp) * ceil_div(c_out, tc) < 256) { tp = tc = 64; bk = c_in % 64 == 0 ? 64 : 32; }
+    return (160 * 1024) / (4 * (tp + tc) * bk * 2);
   }
   if (c_in == 3 && stride == 1 && c_out % 8 == 0 && c_out <= 64)
     return (160 * 1024) / (3 * 776 * 2 + 256 * ceil_div(c_out, 32) * 32 * 2);

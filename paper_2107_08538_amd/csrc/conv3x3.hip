@@ -429,6 +429,182 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma_kernel(ConvArgs a
   }
 }
 
+// ---- DMA-ring implicit GEMM with the depth split over the waves of a workgroup ------------------
+//
+// For layers too small to give every CU a 128 x 128 tile (c_in % 64 == 0, c_out % 8 == 0).  A
+// workgroup of four waves owns a 64 x 64 output tile; ring stages hold depth-64 operand tiles
+// (rows of 128 bytes, 8 chunks, XOR-swizzled), and wave w multiplies only the w-th 16-deep slice
+// of every stage, so the four matrix units of a CU work on one small tile at once.  The four
+// partial accumulators are added through LDS (in the fixed order w = 0, 1, 2, 3) before ReLU.
+constexpr uint32_t KS_BK = 64, KS_NST = 4, KS_PART = 64u * 128u, KS_STAGE = 2u * KS_PART;
+constexpr uint32_t KS_LDS = KS_NST * KS_STAGE;
+
+__device__ __forceinline__ uint32_t row_swz8(uint32_t row) {
+  return ((row >> 1) & 3u) | (((row ^ (row >> 3)) & 1u) << 2);
+}
+
+__global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+  const uint32_t per_xcd = (a.tiles_total + 7u) / 8u;
+  const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || tile >= a.tiles_total) return;
+  const uint32_t bm = (tile / a.tiles_n) * 64u;
+  const uint32_t bn = (tile % a.tiles_n) * 64u;
+
+  const uint32_t lds_base = lds_address_of(smem);
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t l32 = lane & 31u, lhi = lane >> 5;
+  const uint16_t* zeros = reinterpret_cast<const uint16_t*>(g_zero16);
+
+  // DMA roles: instruction h of wave w fills the 1 KiB block b = 2w + h of an operand part
+  // (rows 8b .. 8b+7; lane -> row 8b + lane/8, LDS chunk lane%8, source chunk swizzled)
+  int64_t a_src[2];
+  uint32_t a_taps[2];
+  const uint16_t* b_src[2];
+#pragma unroll
+  for (uint32_t h = 0; h < 2; ++h) {
+    const uint32_t row = 8u * (2u * wave + h) + (lane >> 3);
+    const uint32_t p = bm + row;
+    const bool pv = p < a.pixels;
+    const uint32_t pp = pv ? p : 0u;
+    const uint32_t b = pp / (a.Ho * a.Wo);
+    const uint32_t rem = pp - b * a.Ho * a.Wo;
+    const uint32_t oh = rem / a.Wo, ow = rem - oh * a.Wo;
+    const int32_t ih0 = (int32_t)(oh * a.stride) - 1, iw0 = (int32_t)(ow * a.stride) - 1;
+    uint32_t taps = 0u;
+#pragma unroll
+    for (int32_t r = 0; r < 3; ++r)
+#pragma unroll
+      for (int32_t t = 0; t < 3; ++t)
+        if (pv && (uint32_t)(ih0 + r) < a.H && (uint32_t)(iw0 + t) < a.W) taps |= 1u << (3 * r + t);
+    a_taps[h] = taps;
+    const uint32_t chunk = (lane & 7u) ^ row_swz8(row);
+    a_src[h] = (((int64_t)b * a.H + ih0) * a.W + iw0) * a.C + 8u * chunk;
+    b_src[h] = a.w + (size_t)min(bn + row, a.K - 1u) * a.depth + 8u * chunk;
+  }
+
+  const uint32_t nk = a.depth / KS_BK;
+  uint32_t td = 0u, a_tap = 0u, a_c0 = 0u;   // DMA cursor: tile (clamped source), its tap, first channel
+  auto dma_tile_part = [&](uint32_t q) {     // q = 0, 1: pixel blocks; 2, 3: weight blocks
+    const uint32_t stage = lds_base + (td % KS_NST) * KS_STAGE;
+    if (q < 2u) {
+      const uint32_t r = (a_tap * 11u) >> 5, t = a_tap - 3u * r;
+      const int64_t delta = ((int64_t)r * a.W + t) * a.C + a_c0;
+      const uint32_t ok = (a_taps[q] >> a_tap) & 1u;
+      dma16(pick(a.x + a_src[q] + delta, zeros, ok), stage + (2u * wave + q) * 1024u);
+    } else {
+      dma16(b_src[q - 2u] + (size_t)min(td, nk - 1u) * KS_BK, stage + KS_PART + (2u * wave + q - 2u) * 1024u);
+    }
+  };
+  auto next_tile = [&]() {
+    if (td + 1u < nk) {
+      a_c0 += KS_BK;
+      if (a_c0 == a.C) { a_c0 = 0u; ++a_tap; }
+    }
+    ++td;
+  };
+
+  f32x16 acc[2][2];                          // [pixel block][channel block]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  uint32_t p_off[2], w_off[2];               // this wave's 16-deep slice: chunks 2*wave, 2*wave + 1
+#pragma unroll
+  for (uint32_t i = 0; i < 2; ++i) {
+    const uint32_t row = 32u * i + l32;
+    p_off[i] = row * 128u + (((2u * wave + lhi) ^ row_swz8(row)) << 4);
+    w_off[i] = KS_PART + p_off[i];
+  }
+  u32x4 fp[2][2], fw[2][2];                  // [slot][block]
+  auto frag_load = [&](const uint8_t* st, uint32_t slot, uint32_t q) {   // q: w0, p0, p1, w1
+    if (q == 0u) fw[slot][0] = *reinterpret_cast<const u32x4*>(st + w_off[0]);
+    else if (q == 3u) fw[slot][1] = *reinterpret_cast<const u32x4*>(st + w_off[1]);
+    else fp[slot][q - 1u] = *reinterpret_cast<const u32x4*>(st + p_off[q - 1u]);
+  };
+  // tile kt: 4 MFMAs on slot `slot`; between them the fragment reads of tile kt+1 into the other
+  // slot and this wave's part of tile kt + NST, which goes into the stage tile kt leaves
+  auto step = [&](uint32_t slot, uint32_t kt) {
+    // 2 tiles' worth of instructions were issued after tile kt+1's: it has landed when no more
+    // are outstanding; the barrier extends that to every wave's part and tells that tile kt's
+    // fragments are in registers everywhere
+    __builtin_amdgcn_s_waitcnt(vm_wait((KS_NST - 2u) * 4u));
+    __syncthreads();
+    const uint8_t* fst = smem + ((kt + 1u) % KS_NST) * KS_STAGE;
+#pragma unroll
+    for (uint32_t m = 0; m < 4u; ++m) {
+      const uint32_t j = m >> 1, i = m & 1u;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fw[slot][j]), as_bf16x8(fp[slot][i]), acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      frag_load(fst, slot ^ 1u, m);
+      dma_tile_part(m);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    next_tile();
+  };
+
+#pragma unroll
+  for (uint32_t t = 0; t < KS_NST; ++t) {
+#pragma unroll
+    for (uint32_t q = 0; q < 4u; ++q) dma_tile_part(q);
+    next_tile();
+  }
+  __builtin_amdgcn_s_waitcnt(vm_wait((KS_NST - 1u) * 4u));   // this wave's part of tile 0
+  __syncthreads();
+#pragma unroll
+  for (uint32_t q = 0; q < 4u; ++q) frag_load(smem, 0u, q);
+  for (uint32_t kt = 0; kt < nk; kt += 2u) {
+    step(0u, kt);
+    if (kt + 1u >= nk) break;
+    step(1u, kt + 1u);
+  }
+  __builtin_amdgcn_s_waitcnt(vm_wait(0));    // no DMA in flight, then the ring becomes the reduction buffer
+  __syncthreads();
+
+  // partial of wave w: floats [w][pixel][quad ^ (pixel & 15)][4], quad = 4 consecutive channels
+  float* part = reinterpret_cast<float*>(smem);
+#pragma unroll
+  for (uint32_t i = 0; i < 2; ++i) {
+    const uint32_t px = 32u * i + l32;
+#pragma unroll
+    for (uint32_t j = 0; j < 2; ++j)
+#pragma unroll
+      for (uint32_t g = 0; g < 4; ++g) {
+        const uint32_t quad = 8u * j + 2u * g + lhi;
+        *reinterpret_cast<float4*>(part + wave * 4096u + px * 64u + ((quad ^ (px & 15u)) << 2)) =
+            make_float4(acc[i][j][4u * g], acc[i][j][4u * g + 1u], acc[i][j][4u * g + 2u], acc[i][j][4u * g + 3u]);
+      }
+  }
+  __syncthreads();
+#pragma unroll
+  for (uint32_t r = 0; r < 4; ++r) {
+    const uint32_t px = (tid >> 4) + 16u * r, quad = tid & 15u;
+    const float* src = part + px * 64u + ((quad ^ (px & 15u)) << 2);
+    float4 v = *reinterpret_cast<const float4*>(src);
+#pragma unroll
+    for (uint32_t w = 1; w < 4; ++w) {
+      const float4 u = *reinterpret_cast<const float4*>(src + w * 4096u);
+      v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+    }
+    const uint32_t p = bm + px, ch = bn + 4u * quad;
+    if (p < a.pixels && ch < a.K) {                       // c_out % 4 == 0: a quad is inside or outside as a whole
+      v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+      if (a.out_f32) {
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.y) + (size_t)p * a.K + ch) = v;
+      } else {
+        uint2 q;
+        q.x = (uint32_t)f32_to_bf16_rne(v.x) | ((uint32_t)f32_to_bf16_rne(v.y) << 16);
+        q.y = (uint32_t)f32_to_bf16_rne(v.z) | ((uint32_t)f32_to_bf16_rne(v.w) << 16);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.y) + (size_t)p * a.K + ch) = q;
+      }
+    }
+  }
+}
+
 // ---- 3-channel first layer (c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64) ------------------
 //
 // Depth 27: two MFMA steps, the kernel is bound by writing its output (c_out / 3 times the
@@ -556,7 +732,7 @@ __global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
   }
 }
 
-enum Path { PATH_GENERIC, PATH_DMA_128x128, PATH_DMA_256x64, PATH_DMA_64x64, PATH_C3 };
+enum Path { PATH_GENERIC, PATH_DMA_128x128, PATH_DMA_256x64, PATH_DMA_64x64, PATH_DMA_KSPLIT, PATH_C3 };
 
 struct Geometry {
   uint32_t Ho, Wo, pixels, bn, tiles_n, total, blocks, threads;
@@ -575,8 +751,8 @@ bool shape_ok(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_
 
 // Which kernel a layer gets, and its launch shape.
 //   c_in % 32 == 0 and c_out % 8 == 0: DMA-ring kernel; 128 x 128 tiles (256 pixels x 64 channels
-//     when c_out <= 64) if that gives at least one workgroup per CU, else 64 x 64 tiles with one
-//     wave per workgroup;
+//     when c_out <= 64) if that gives at least one workgroup per CU, else 64 x 64 tiles: four
+//     waves that split the depth when c_in % 64 == 0, one wave per workgroup otherwise;
 //   c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64: the first-layer kernel;
 //   anything else: the register-staged kernel.
 Geometry geometry(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_out, uint32_t stride,
@@ -596,8 +772,8 @@ Geometry geometry(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_
       g.bn = 64u;
       g.tiles_n = (c_out + 63u) / 64u;
       g.total = ((g.pixels + 63u) / 64u) * g.tiles_n;
-      g.path = PATH_DMA_64x64;
-      g.threads = 64u;
+      g.path = c_in % 64u == 0u ? PATH_DMA_KSPLIT : PATH_DMA_64x64;
+      g.threads = c_in % 64u == 0u ? 256u : 64u;
     }
   } else if (allow_fast && c_in == 3u && stride == 1u && c_out % 8u == 0u && c_out <= 64u) {
     g.bn = c_out;
@@ -643,6 +819,16 @@ int launch_layer(hipStream_t st, const uint16_t* x, const uint16_t* w, void* y, 
     case PATH_DMA_128x128: e = launch_dma<2, 2>(st, g, a); break;
     case PATH_DMA_256x64: e = launch_dma<4, 1>(st, g, a); break;
     case PATH_DMA_64x64: e = launch_dma<1, 1>(st, g, a); break;
+    case PATH_DMA_KSPLIT: {
+      static std::once_flag once;
+      static hipError_t attr = hipSuccess;
+      std::call_once(once, [] {
+        attr = hipFuncSetAttribute((const void*)conv3x3_dma_ksplit_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)KS_LDS);
+      });
+      e = attr;
+      if (e == hipSuccess) hipLaunchKernelGGL(conv3x3_dma_ksplit_kernel, dim3(g.blocks), dim3(256), KS_LDS, st, a);
+      break;
+    }
     case PATH_C3:
       if (c_out <= 32u) hipLaunchKernelGGL((conv3x3_c3_kernel<1>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
       else hipLaunchKernelGGL((conv3x3_c3_kernel<2>), dim3(g.blocks), dim3(CV_THREADS), 0, st, a);
@@ -688,6 +874,7 @@ static uint32_t residency_of(const Geometry& g, uint32_t c_out) {
     case PATH_DMA_128x128: return 2u;                 // 64 KiB ring
     case PATH_DMA_256x64: return 2u;                  // 80 KiB ring
     case PATH_DMA_64x64: return 5u;                   // 32 KiB ring
+    case PATH_DMA_KSPLIT: return 2u;                  // 64 KiB ring
     case PATH_C3: return c_out <= 32u ? 7u : 4u;      // 21 / 37 KiB of strips and output staging
     case PATH_GENERIC: return 2u;                     // 162 - 244 registers per lane
   }

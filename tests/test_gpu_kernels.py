@@ -264,6 +264,8 @@ def _conv_inputs(seed, n, h, wd, c, k, sigma=0.2):
     (1, 40, 37, 3, 32, 1), (2, 9, 300, 3, 64, 1), (1, 3, 3, 3, 8, 1),
     # DMA ring, 64 x 64 tiles: ragged pixels and channels, c_in = 32 (one tile per tap) and 96
     (1, 1, 1, 32, 8, 1), (2, 9, 7, 96, 72, 2), (1, 20, 20, 256, 512, 1),
+    # 64 x 64 tiles with the depth split over four waves (c_in % 64 == 0): odd and even tile counts
+    (1, 1, 1, 64, 8, 1), (2, 9, 7, 192, 72, 2), (1, 13, 13, 512, 520, 1), (2, 31, 29, 64, 136, 1),
     # DMA ring, 128 x 128 and 256 x 64 tiles (at least 256 workgroups), stride 1 and 2, ragged tails
     (2, 130, 127, 32, 136, 1), (3, 150, 151, 32, 64, 1), (5, 141, 150, 64, 40, 2)])
 def test_conv_layer_fp32_and_bf16_outputs(n, h, wd, c, k, stride):
