@@ -363,7 +363,9 @@ int mgb_conv3x3_enqueue(void* stream, const uint16_t* x, const uint16_t* w, void
  * activation); the last layer writes fp32 to `out`.  weights[i] is the device
  * pointer of layer i's K,3,3,C tensor (host array of device pointers).
  * Footprint = input + all weights + 2 * largest intermediate + fp32 output;
- * geometry = the largest over the layers.                                    */
+ * geometry = the largest over the layers.  act0 and act1 are scratch for the
+ * whole call: a small, deep layer also keeps fp32 partial sums in the part of
+ * them its activations leave idle.                                            */
 uint32_t mgb_cnn_residency(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, uint32_t h,
                            uint32_t w);
 int mgb_cnn_probe(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, uint32_t h,

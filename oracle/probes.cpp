@@ -76,20 +76,34 @@ void orc_gemm_bf16_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
 //     threads (the depth split four ways) when c_in % 64 == 0, else 64 threads;
 //   c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64: 256 threads per 256 pixels (all channels);
 //   otherwise 256 threads per 128 pixels x 64 channels (128 channels when c_out > 64).
-void orc_conv3x3_probe(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, uint64_t c_out,
-                       uint64_t stride, uint64_t out[7]) {
-  uint64_t ho = (h + 2 - 3) / stride + 1, wo = (w + 2 - 3) / stride + 1;
-  uint64_t pixels = batch * ho * wo;
-  out[0] = (batch * h * w * c_in + 9 * c_in * c_out + pixels * c_out) * 2;
-  uint64_t wgs, threads = 256;
+static uint64_t conv_workgroups(uint64_t pixels, uint64_t c_in, uint64_t c_out, uint64_t stride,
+                                uint64_t* threads, bool* depth_split) {
+  uint64_t wgs;
+  *threads = 256;
+  *depth_split = false;
   if (c_in % 32 == 0 && c_out % 8 == 0) {
     wgs = c_out > 64 ? ceil_div(pixels, 128) * ceil_div(c_out, 128) : ceil_div(pixels, 256) * ceil_div(c_out, 64);
-    if (wgs < 256) { wgs = ceil_div(pixels, 64) * ceil_div(c_out, 64); threads = c_in % 64 == 0 ? 256 : 64; }
+    if (wgs < 256) {
+      wgs = ceil_div(pixels, 64) * ceil_div(c_out, 64);
+      *depth_split = c_in % 64 == 0;
+      *threads = *depth_split ? 256 : 64;
+    }
   } else if (c_in == 3 && stride == 1 && c_out % 8 == 0 && c_out <= 64) {
     wgs = ceil_div(pixels, 256);
   } else {
     wgs = ceil_div(pixels, 128) * ceil_div(c_out, c_out <= 64 ? 64 : 128);
   }
+  return wgs;
+}
+
+void orc_conv3x3_probe(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, uint64_t c_out,
+                       uint64_t stride, uint64_t out[7]) {
+  uint64_t ho = (h + 2 - 3) / stride + 1, wo = (w + 2 - 3) / stride + 1;
+  uint64_t pixels = batch * ho * wo;
+  out[0] = (batch * h * w * c_in + 9 * c_in * c_out + pixels * c_out) * 2;
+  uint64_t threads;
+  bool split;
+  uint64_t wgs = conv_workgroups(pixels, c_in, c_out, stride, &threads, &split);
   out[1] = round8(wgs); out[2] = 1; out[3] = 1;
   out[4] = threads; out[5] = 1; out[6] = 1;
 }
@@ -99,19 +113,41 @@ void orc_conv3x3_probe(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, ui
 // intermediate activation + the fp32 output of the last layer; geometry = the launch with the
 // most threads.
 // c[3*i..3*i+2] = {c_in, c_out, stride} of layer i.
+//
+// Inside a chain a depth-split layer of at most 96 tiles with c_in >= 512 is split further, over
+// min(16, 512 / tiles, (9 c_in / 64) / 4) workgroups per tile, as far as the fp32 partial sums fit the
+// idle part of a ping-pong buffer (behind the layer's own output rounded up to 256 bytes; the
+// whole buffer for the last layer); fewer than 2 means no further split.
 void orc_cnn_probe(const uint64_t* c, uint64_t n_layers, uint64_t batch, uint64_t h, uint64_t w,
                    uint64_t out[7]) {
   uint64_t mem = batch * h * w * c[0] * 2, act_max = 0, grid = 0, threads = 256, last = 0;
+  uint64_t hh = h, ww = w;
   for (uint64_t i = 0; i < n_layers; ++i) {
-    uint64_t one[7];
-    orc_conv3x3_probe(batch, h, w, c[3 * i], c[3 * i + 1], c[3 * i + 2], one);
-    uint64_t ho = (h - 1) / c[3 * i + 2] + 1, wo = (w - 1) / c[3 * i + 2] + 1;
+    uint64_t ho = (hh - 1) / c[3 * i + 2] + 1, wo = (ww - 1) / c[3 * i + 2] + 1;
     uint64_t elems = batch * ho * wo * c[3 * i + 1];
     mem += 9 * c[3 * i] * c[3 * i + 1] * 2;
     if (i + 1 < n_layers) { if (elems * 2 > act_max) act_max = elems * 2; }
     else last = elems * 4;
-    if (one[1] * one[4] > grid * threads) { grid = one[1]; threads = one[4]; }
-    h = ho; w = wo;
+    hh = ho; ww = wo;
+  }
+  hh = h; ww = w;
+  for (uint64_t i = 0; i < n_layers; ++i) {
+    uint64_t c_in = c[3 * i], c_out = c[3 * i + 1], stride = c[3 * i + 2];
+    uint64_t ho = (hh - 1) / stride + 1, wo = (ww - 1) / stride + 1;
+    uint64_t pixels = batch * ho * wo, elems = pixels * c_out, th;
+    bool split;
+    uint64_t wgs = conv_workgroups(pixels, c_in, c_out, stride, &th, &split);
+    if (split && wgs <= 96 && c_in >= 512) {
+      uint64_t own = i + 1 < n_layers ? ceil_div(elems * 2, 256) * 256 : 0;
+      uint64_t spare = act_max > own ? act_max - own : 0;
+      uint64_t ways = 512 / wgs;
+      if (ways > 16) ways = 16;
+      if (ways > 9 * c_in / 64 / 4) ways = 9 * c_in / 64 / 4;
+      if (ways > spare / (elems * 4)) ways = spare / (elems * 4);
+      if (ways >= 2) wgs *= ways;
+    }
+    if (round8(wgs) * th > grid * threads) { grid = round8(wgs); threads = th; }
+    hh = ho; ww = wo;
   }
   out[0] = mem + 2 * act_max + last;
   out[1] = grid; out[2] = 1; out[3] = 1;

@@ -37,6 +37,8 @@ struct ConvArgs {
   uint32_t batch, H, W, C, K, stride, Ho, Wo;
   uint32_t pixels, depth;      // batch*Ho*Wo, 9*C
   uint32_t tiles_n, tiles_total, out_f32;
+  uint32_t splits;             // depth-split kernel only: workgroups that share one output tile
+  float* work;                 // splits > 1: fp32 partial sums [split][pixel][channel]
 };
 
 // 16 bytes of zeros in device memory: the source of every padded / out-of-range operand chunk
@@ -436,6 +438,10 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma_kernel(ConvArgs a
 // (rows of 128 bytes, 8 chunks, XOR-swizzled), and wave w multiplies only the w-th 16-deep slice
 // of every stage, so the four matrix units of a CU work on one small tile at once.  The four
 // partial accumulators are added through LDS (in the fixed order w = 0, 1, 2, 3) before ReLU.
+//
+// A layer with so few tiles that most CUs would still idle is split once more: `splits`
+// workgroups share a tile, each takes a contiguous range of the depth and writes its fp32 partial
+// sums to a workspace; conv_split_reduce_kernel adds them in split order and applies ReLU.
 constexpr uint32_t KS_BK = 64, KS_NST = 4, KS_PART = 64u * 128u, KS_STAGE = 2u * KS_PART;
 constexpr uint32_t KS_LDS = KS_NST * KS_STAGE;
 
@@ -447,9 +453,12 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   const uint32_t per_xcd = (a.tiles_total + 7u) / 8u;
   const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-  if ((blockIdx.x >> 3) >= per_xcd || tile >= a.tiles_total) return;
-  const uint32_t bm = (tile / a.tiles_n) * 64u;
-  const uint32_t bn = (tile % a.tiles_n) * 64u;
+  if ((blockIdx.x >> 3) >= per_xcd || tile >= a.tiles_total) return;    // tiles_total counts (tile, split) pairs
+  const uint32_t split = tile % a.splits, otile = tile / a.splits;
+  const uint32_t bm = (otile / a.tiles_n) * 64u;
+  const uint32_t bn = (otile % a.tiles_n) * 64u;
+  const uint32_t kt0 = split * (a.depth / KS_BK) / a.splits;             // this workgroup's depth tiles [kt0, kt0 + nk)
+  const uint32_t nk = (split + 1u) * (a.depth / KS_BK) / a.splits - kt0;
 
   const uint32_t lds_base = lds_address_of(smem);
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
@@ -481,11 +490,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
     a_taps[h] = taps;
     const uint32_t chunk = (lane & 7u) ^ row_swz8(row);
     a_src[h] = (((int64_t)b * a.H + ih0) * a.W + iw0) * a.C + 8u * chunk;
-    b_src[h] = a.w + (size_t)min(bn + row, a.K - 1u) * a.depth + 8u * chunk;
+    b_src[h] = a.w + (size_t)min(bn + row, a.K - 1u) * a.depth + (size_t)kt0 * KS_BK + 8u * chunk;
   }
 
-  const uint32_t nk = a.depth / KS_BK;
-  uint32_t td = 0u, a_tap = 0u, a_c0 = 0u;   // DMA cursor: tile (clamped source), its tap, first channel
+  // DMA cursor: tile relative to kt0 (source clamped to the last one), its tap, first channel
+  uint32_t td = 0u, a_tap = kt0 * KS_BK / a.C, a_c0 = kt0 * KS_BK - a_tap * a.C;
   auto dma_tile_part = [&](uint32_t q) {     // q = 0, 1: pixel blocks; 2, 3: weight blocks
     const uint32_t stage = lds_base + (td % KS_NST) * KS_STAGE;
     if (q < 2u) {
@@ -592,6 +601,10 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
     }
     const uint32_t p = bm + px, ch = bn + 4u * quad;
     if (p < a.pixels && ch < a.K) {                       // c_out % 4 == 0: a quad is inside or outside as a whole
+      if (a.splits > 1u) {
+        *reinterpret_cast<float4*>(a.work + ((size_t)split * a.pixels + p) * a.K + ch) = v;
+        continue;
+      }
       v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
       if (a.out_f32) {
         *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.y) + (size_t)p * a.K + ch) = v;
@@ -602,6 +615,29 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
         *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.y) + (size_t)p * a.K + ch) = q;
       }
     }
+  }
+}
+
+// y = ReLU(sum over splits of work[split]) for 4 consecutive outputs per thread
+__global__ __launch_bounds__(256) void conv_split_reduce_kernel(const float* __restrict__ work, void* y, uint32_t splits,
+                                                                uint32_t quads, uint32_t out_f32) {
+  const uint32_t q = blockIdx.x * 256u + threadIdx.x;
+  if (q >= quads) return;
+  const float4* src = reinterpret_cast<const float4*>(work) + q;
+  float4 v = src[0];
+#pragma unroll 4
+  for (uint32_t s = 1; s < splits; ++s) {
+    const float4 u = src[(size_t)s * quads];
+    v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+  }
+  v.x = fmaxf(v.x, 0.f); v.y = fmaxf(v.y, 0.f); v.z = fmaxf(v.z, 0.f); v.w = fmaxf(v.w, 0.f);
+  if (out_f32) {
+    reinterpret_cast<float4*>(y)[q] = v;
+  } else {
+    uint2 o;
+    o.x = (uint32_t)f32_to_bf16_rne(v.x) | ((uint32_t)f32_to_bf16_rne(v.y) << 16);
+    o.y = (uint32_t)f32_to_bf16_rne(v.z) | ((uint32_t)f32_to_bf16_rne(v.w) << 16);
+    reinterpret_cast<uint2*>(y)[q] = o;
   }
 }
 
@@ -790,6 +826,59 @@ Geometry geometry(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_
   return g;
 }
 
+// A chain of layers: every layer's kernel and launch shape, and how many ways its depth is split
+// across workgroups.  A depth-split layer of at most 96 tiles and c_in >= 512 (the second launch
+// costs about 4 us, shallower layers do not win that back) is split further when its fp32
+// partial sums fit the idle part of the ping-pong buffers: behind the layer's own bf16 output in
+// its destination buffer, or, for the last layer (which writes to `out`), the buffer it does
+// not read.  splits = min(16, 512 / tiles, depth tiles / 4, what fits); 1 if that is below 2.
+struct LayerPlan {
+  Geometry g;
+  uint32_t splits;
+  uint64_t work_off;     // byte offset of the partial sums in that buffer
+};
+
+int plan_chain(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, uint32_t h, uint32_t w,
+               bool allow_fast, LayerPlan* plan, uint64_t* weights, uint64_t* act_max, uint64_t* last) {
+  *weights = 0; *act_max = 0; *last = 0;
+  uint32_t ch = h, cw = w;
+  for (uint32_t i = 0; i < n_layers; ++i) {
+    const mgb_conv_layer& L = layers[i];
+    if (i > 0u && L.c_in != layers[i - 1u].c_out) return MGB_E_INVAL;
+    if (!shape_ok(batch, ch, cw, L.c_in, L.c_out, L.stride)) return MGB_E_UNSUPPORTED;
+    plan[i].g = geometry(batch, ch, cw, L.c_in, L.c_out, L.stride, allow_fast);
+    plan[i].splits = 1u;
+    plan[i].work_off = 0u;
+    *weights += 9ull * L.c_in * L.c_out * 2;
+    const uint64_t elems = (uint64_t)plan[i].g.pixels * L.c_out;
+    if (i + 1u < n_layers) *act_max = *act_max > elems * 2 ? *act_max : elems * 2;
+    else *last = elems * 4;
+    ch = plan[i].g.Ho;
+    cw = plan[i].g.Wo;
+  }
+  for (uint32_t i = 0; i < n_layers; ++i) {
+    Geometry& g = plan[i].g;
+    if (g.path != PATH_DMA_KSPLIT || g.total > 96u || layers[i].c_in < 512u) continue;
+    const uint64_t elems = (uint64_t)g.pixels * layers[i].c_out;
+    const bool is_last = i + 1u == n_layers;
+    const uint64_t own = is_last ? 0u : (elems * 2 + 255u) / 256u * 256u;
+    const uint64_t spare = *act_max > own ? *act_max - own : 0u;
+    uint64_t s = 512u / g.total;
+    s = s < 16u ? s : 16u;
+    const uint64_t nk = 9ull * layers[i].c_in / KS_BK;
+    s = s < nk / 4u ? s : nk / 4u;
+    s = s < spare / (elems * 4) ? s : spare / (elems * 4);
+    if (s < 2u) continue;
+    plan[i].splits = (uint32_t)s;
+    plan[i].work_off = own;
+    g.total *= (uint32_t)s;
+    g.blocks = (g.total + 7u) / 8u * 8u;
+  }
+  return MGB_OK;
+}
+
+constexpr uint32_t MAX_LAYERS = 64;
+
 template <uint32_t WM, uint32_t WN>
 hipError_t launch_dma(hipStream_t st, const Geometry& g, const ConvArgs& a) {
   constexpr uint32_t lds = CD_NST * (64u * WM + 64u * WN) * 64u;
@@ -803,17 +892,22 @@ hipError_t launch_dma(hipStream_t st, const Geometry& g, const ConvArgs& a) {
   return hipSuccess;
 }
 
+// `splits` > 1 (depth-split path only): `work` holds splits * pixels * c_out floats
 int launch_layer(hipStream_t st, const uint16_t* x, const uint16_t* w, void* y, uint32_t batch,
                  uint32_t h, uint32_t wd, uint32_t c_in, uint32_t c_out, uint32_t stride,
-                 uint32_t out_f32) {
+                 uint32_t out_f32, uint32_t splits = 1u, float* work = nullptr) {
   // the fast paths move 16 bytes at a time (the probe assumed aligned tensors)
-  const bool aligned = (((uintptr_t)x | (uintptr_t)w | (uintptr_t)y) & 15u) == 0u;
-  const Geometry g = geometry(batch, h, wd, c_in, c_out, stride, aligned);
+  const bool aligned = (((uintptr_t)x | (uintptr_t)w | (uintptr_t)y | (uintptr_t)work) & 15u) == 0u;
+  Geometry g = geometry(batch, h, wd, c_in, c_out, stride, aligned);
+  if (splits > 1u && (g.path != PATH_DMA_KSPLIT || !work)) splits = 1u;
+  g.total *= splits;
+  g.blocks = (g.total + 7u) / 8u * 8u;
   ConvArgs a;
   a.x = x; a.w = w; a.y = y;
   a.batch = batch; a.H = h; a.W = wd; a.C = c_in; a.K = c_out; a.stride = stride;
   a.Ho = g.Ho; a.Wo = g.Wo; a.pixels = g.pixels; a.depth = 9u * c_in;
   a.tiles_n = g.tiles_n; a.tiles_total = g.total; a.out_f32 = out_f32;
+  a.splits = splits; a.work = work;
   hipError_t e = hipSuccess;
   switch (g.path) {
     case PATH_DMA_128x128: e = launch_dma<2, 2>(st, g, a); break;
@@ -826,7 +920,13 @@ int launch_layer(hipStream_t st, const uint16_t* x, const uint16_t* w, void* y, 
         attr = hipFuncSetAttribute((const void*)conv3x3_dma_ksplit_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)KS_LDS);
       });
       e = attr;
-      if (e == hipSuccess) hipLaunchKernelGGL(conv3x3_dma_ksplit_kernel, dim3(g.blocks), dim3(256), KS_LDS, st, a);
+      if (e == hipSuccess) {
+        hipLaunchKernelGGL(conv3x3_dma_ksplit_kernel, dim3(g.blocks), dim3(256), KS_LDS, st, a);
+        if (splits > 1u) {
+          const uint32_t quads = g.pixels * (c_out / 4u);
+          hipLaunchKernelGGL(conv_split_reduce_kernel, dim3((quads + 255u) / 256u), dim3(256), 0, st, work, y, splits, quads, out_f32);
+        }
+      }
       break;
     }
     case PATH_C3:
@@ -889,19 +989,18 @@ uint32_t mgb_conv3x3_residency(uint32_t batch, uint32_t h, uint32_t w, uint32_t 
 
 uint32_t mgb_cnn_residency(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, uint32_t h,
                            uint32_t w) {
-  if (!layers || n_layers == 0u) return 0u;
-  uint32_t blocks = 0, threads = CV_THREADS, res = 0, ch = h, cw = w;
+  if (!layers || n_layers == 0u || n_layers > MAX_LAYERS) return 0u;
+  LayerPlan plan[MAX_LAYERS];
+  uint64_t weights, act_max, last;
+  if (plan_chain(layers, n_layers, batch, h, w, true, plan, &weights, &act_max, &last) != MGB_OK) return 0u;
+  uint32_t blocks = 0, threads = CV_THREADS, res = 0;
   for (uint32_t i = 0; i < n_layers; ++i) {
-    const mgb_conv_layer& L = layers[i];
-    if (!shape_ok(batch, ch, cw, L.c_in, L.c_out, L.stride)) return 0u;
-    const Geometry g = geometry(batch, ch, cw, L.c_in, L.c_out, L.stride);
+    const Geometry& g = plan[i].g;
     if ((uint64_t)g.blocks * g.threads > (uint64_t)blocks * threads) {   // the launch that gives the task its geometry
       blocks = g.blocks;
       threads = g.threads;
-      res = residency_of(g, L.c_out);
+      res = residency_of(g, layers[i].c_out);
     }
-    ch = g.Ho;
-    cw = g.Wo;
   }
   return res;
 }
@@ -921,25 +1020,20 @@ int mgb_cnn_probe(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batc
                   mgb_dim3* grid, mgb_dim3* block) {
   if (!layers || !mem_bytes || !act_bytes || !out_bytes || !grid || !block || n_layers == 0u)
     return MGB_E_INVAL;
-  uint64_t weights = 0, act_max = 0, last = 0;
-  uint32_t blocks = 0, threads = CV_THREADS, ch = h, cw = w;
+  if (n_layers > MAX_LAYERS) return MGB_E_UNSUPPORTED;
+  LayerPlan plan[MAX_LAYERS];
+  uint64_t weights, act_max, last;
+  const int prc = plan_chain(layers, n_layers, batch, h, w, true, plan, &weights, &act_max, &last);
+  if (prc != MGB_OK) return prc;
+  uint32_t blocks = 0, threads = CV_THREADS;
   const uint64_t input = (uint64_t)batch * h * w * layers[0].c_in * 2;
   for (uint32_t i = 0; i < n_layers; ++i) {
-    const mgb_conv_layer& L = layers[i];
-    if (i > 0u && L.c_in != layers[i - 1u].c_out) return MGB_E_INVAL;
-    if (!shape_ok(batch, ch, cw, L.c_in, L.c_out, L.stride)) return MGB_E_UNSUPPORTED;
-    const Geometry g = geometry(batch, ch, cw, L.c_in, L.c_out, L.stride);
-    weights += 9ull * L.c_in * L.c_out * 2;
-    const uint64_t elems = (uint64_t)g.pixels * L.c_out;
-    if (i + 1u < n_layers) act_max = act_max > elems * 2 ? act_max : elems * 2;
-    else last = elems * 4;
+    const Geometry& g = plan[i].g;
     // launches are stream-ordered: the one with the most waves counts
     if ((uint64_t)g.blocks * g.threads > (uint64_t)blocks * threads) {
       blocks = g.blocks;
       threads = g.threads;
     }
-    ch = g.Ho;
-    cw = g.Wo;
   }
   *act_bytes = act_max;
   *out_bytes = last;
@@ -960,14 +1054,21 @@ int mgb_cnn_enqueue(void* stream, const mgb_conv_layer* layers, uint32_t n_layer
   if (rc != MGB_OK) return rc;
   for (uint32_t i = 0; i < n_layers; ++i)
     if (!weights[i]) return MGB_E_INVAL;
+  LayerPlan plan[MAX_LAYERS];
+  uint64_t wb, act_max, lb;
+  rc = plan_chain(layers, n_layers, batch, h, w, true, plan, &wb, &act_max, &lb);
+  if (rc != MGB_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   const uint16_t* src = x;
   uint32_t ch = h, cw = w;
   for (uint32_t i = 0; i < n_layers; ++i) {
     const mgb_conv_layer& L = layers[i];
     const bool last = i + 1u == n_layers;
-    void* dst = last ? (void*)out : (void*)((i & 1u) ? act1 : act0);
-    rc = launch_layer(st, src, weights[i], dst, batch, ch, cw, L.c_in, L.c_out, L.stride, last ? 1u : 0u);
+    uint16_t* pong = (i & 1u) ? act1 : act0;           // the buffer this layer does not read
+    void* dst = last ? (void*)out : (void*)pong;
+    float* work = plan[i].splits > 1u ? reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(pong) + plan[i].work_off) : nullptr;
+    rc = launch_layer(st, src, weights[i], dst, batch, ch, cw, L.c_in, L.c_out, L.stride, last ? 1u : 0u,
+                      plan[i].splits, work);
     if (rc != MGB_OK) return rc;
     src = (const uint16_t*)dst;
     ch = (ch - 1u) / L.stride + 1u;

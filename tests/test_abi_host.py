@@ -318,7 +318,7 @@ def test_probe_functions_agree_with_checker_formulas():
         oracle.lib().orc_conv3x3_probe(*[C.c_uint64(x) for x in (b, h, w, ci, co, st)], out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (b, h, w, ci, co, st)
     import workloads as W
-    for b, h in ((1, 416), (8, 416), (2, 104), (1, 17)):
+    for b, h in ((1, 416), (8, 416), (2, 104), (1, 17), (4, 208), (3, 64), (2, 416)):
         layers = W.cnn_layers(h, h)
         arr = (mgb.mgb_conv_layer * 10)(*[mgb.mgb_conv_layer(L["c_in"], L["c_out"], L["stride"]) for L in layers])
         mem, act, ob = C.c_uint64(), C.c_uint64(), C.c_uint64()

@@ -328,9 +328,10 @@ def test_cnn_ten_layer_chain_reduced_image():
     assert got.shape == ref.shape == (2, 4, 4, 512)
     assert np.linalg.norm(ref) > 0
     assert frobenius_rel(got, ref) <= 1e-2
-    # geometry of the task = the launch with the most threads: the first layer, 256 pixels per
-    # 256-thread workgroup (2*104*104 / 256 = 84.5 -> 85, rounded up to a multiple of 8)
-    assert (g.x, b.x) == (88, 256)
+    # geometry of the task = the launch with the most threads: the last layer, 8 tiles of 64 x 64
+    # (2*4*4 pixels x 512 channels) whose depth is split over 16 workgroups of 256 threads each
+    # (the first layer has 2*104*104 / 256 -> 85 -> 88 workgroups)
+    assert (g.x, b.x) == (128, 256)
 
 
 def test_cnn_full_size_layers_sampled():
