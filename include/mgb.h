@@ -380,12 +380,15 @@ int mgb_cnn_enqueue(void* stream, const mgb_conv_layer* layers, uint32_t n_layer
  * directions: it may expand a level from the unvisited side);
  * mgb_bfs_directed_enqueue follows the stored edges as out-edges of any graph.
  * level[v] = hop distance from `source`, -1 if unreachable.  `work` is scratch
- * of mgb_bfs_work_bytes(n) bytes (two frontier queues and per-level counters).
+ * of mgb_bfs_work_bytes(n) bytes (two frontier queues, three frontier bitmaps
+ * and per-level counters).  mgb_bfs_residency(n) = workgroups of the level
+ * kernel one CU holds (the fact a probe may add to grid and block).
  * The call enqueues batches of level kernels and synchronises the stream
  * between batches to learn whether the frontier is empty; on return `level` is
  * complete.  *depth (host, may be NULL) receives the number of levels.
  * Footprint (n+1+m)*4 + n*4 + work.                                          */
 uint64_t mgb_bfs_work_bytes(uint32_t n);
+uint32_t mgb_bfs_residency(uint32_t n);
 int mgb_bfs_probe(uint32_t n, uint64_t m, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block);
 int mgb_bfs_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
                     uint32_t source, int32_t* level, void* work, uint32_t* depth);

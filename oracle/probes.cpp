@@ -191,16 +191,25 @@ uint64_t orc_conv3x3_residency(uint64_t batch, uint64_t h, uint64_t w, uint64_t 
 }
 
 // BFS: CSR (n+1 row pointers, m column indices), the level array, two frontier queues of n
-// entries (each rounded up to 256 bytes) and a 256-byte control block.  One 256-thread
-// workgroup per 1024 vertices, at least 8 and at most 2048.
+// entries (each rounded up to 256 bytes), three frontier bitmaps of one bit per vertex (each
+// rounded up to 256 bytes) and a 256-byte control block.  One 512-thread workgroup per 4096
+// vertices, at least 8 and at most 512.
+static uint64_t bfs_bitmap_bytes(uint64_t n) { return ceil_div(ceil_div(n, 32), 64) * 64 * 4; }
 void orc_bfs_probe(uint64_t n, uint64_t m, uint64_t out[7]) {
   uint64_t queue = ceil_div(n * 4, 256) * 256;
-  uint64_t wg = ceil_div(n, 1024);
+  uint64_t wg = ceil_div(n, 4096);
   if (wg < 8) wg = 8;
-  if (wg > 2048) wg = 2048;
-  out[0] = (n + 1 + m) * 4 + n * 4 + 256 + 2 * queue;
+  if (wg > 512) wg = 512;
+  out[0] = (n + 1 + m) * 4 + n * 4 + 256 + 2 * queue + 3 * bfs_bitmap_bytes(n);
   out[1] = round8(wg); out[2] = 1; out[3] = 1;
-  out[4] = 256; out[5] = 1; out[6] = 1;
+  out[4] = 512; out[5] = 1; out[6] = 1;
+}
+// The level kernel keeps 29184 bytes of LDS for staging and, for graphs of up to 2^20 vertices,
+// one frontier bitmap; a workgroup is 8 waves.
+uint64_t orc_bfs_residency(uint64_t n) {
+  uint64_t lds = 29184 + (n <= (1ull << 20) ? bfs_bitmap_bytes(n) : 0);
+  uint64_t by_lds = (160 * 1024) / lds, by_waves = 32 / 8;
+  return by_lds < by_waves ? by_lds : by_waves;
 }
 
 }  // extern "C"

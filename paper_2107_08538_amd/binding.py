@@ -121,6 +121,7 @@ mgb_gemm_f32_residency = _sig("mgb_gemm_f32_residency", _u32, _u32, _u32, _u32)
 mgb_gemm_bf16_residency = _sig("mgb_gemm_bf16_residency", _u32, _u32, _u32, _u32)
 mgb_conv3x3_residency = _sig("mgb_conv3x3_residency", _u32, _u32, _u32, _u32, _u32, _u32, _u32)
 mgb_cnn_residency = _sig("mgb_cnn_residency", _u32, _P(mgb_conv_layer), _u32, _u32, _u32, _u32)
+mgb_bfs_residency = _sig("mgb_bfs_residency", _u32, _u32)
 mgb_gemm_f32_probe = _sig("mgb_gemm_f32_probe", C.c_int, _u32, _u32, _u32, *_probe_tail)
 mgb_gemm_f32_enqueue = _sig("mgb_gemm_f32_enqueue", C.c_int, _vp, _vp, _vp, _vp, _u32, _u32, _u32)
 mgb_gemm_bf16_probe = _sig("mgb_gemm_bf16_probe", C.c_int, _u32, _u32, _u32, *_probe_tail)
@@ -142,7 +143,7 @@ mgb_copy_enqueue = _sig("mgb_copy_enqueue", C.c_int, _vp, _vp, _vp, _u64)
 EXPORTS = [
     "mgb_device_desc_default", "mgb_sched_create", "mgb_sched_destroy", "mgb_task_probe",
     "mgb_task_probe_ex", "mgb_gemm_f32_residency", "mgb_gemm_bf16_residency", "mgb_conv3x3_residency",
-    "mgb_cnn_residency", "mgb_task_wait", "mgb_task_cancel", "mgb_task_grow", "mgb_lazy_create", "mgb_lazy_destroy", "mgb_lazy_malloc",
+    "mgb_cnn_residency", "mgb_bfs_residency", "mgb_task_wait", "mgb_task_cancel", "mgb_task_grow", "mgb_lazy_create", "mgb_lazy_destroy", "mgb_lazy_malloc",
     "mgb_lazy_memcpy_h2d", "mgb_lazy_memset", "mgb_lazy_launch_prepare", "mgb_lazy_memcpy_d2h", "mgb_lazy_free",
     "mgb_lazy_stats_get", "mgb_server_start", "mgb_server_stop", "mgb_server_reclaimed", "mgb_client_connect",
     "mgb_client_disconnect", "mgb_client_probe", "mgb_client_wait", "mgb_client_cancel", "mgb_client_grow",

@@ -10,9 +10,15 @@
 //     LDS), four edges per lane in flight.  Newly reached vertices are claimed
 //     with one compare-and-swap on level[] (levels are unique, so the result
 //     does not depend on who wins);
-//   * bottom-up (frontier large against what is still unvisited): one thread
+//   * bottom-up (frontier large against what is still unvisited): one lane
 //     per unvisited vertex scans its own adjacency list until it meets a
-//     vertex of the current level; no atomics on level[], early exit.
+//     vertex of the current frontier; no atomics on level[], early exit.
+//     Frontier membership is a bitmap (one bit per vertex, three of them in
+//     rotation: read / written / cleared by a level); for graphs of up to
+//     2^20 vertices every workgroup first copies it into LDS (128 KiB), so
+//     the probes - the bulk of the work - never leave the CU.  Top-down
+//     levels set the bits of what they discover with one more atomic each;
+//     bottom-up levels own whole bitmap words and store them.
 // Either way the new frontier is appended to the next queue with one atomic
 // per wave: ballot of the winners, the leader reserves popcount slots, each
 // winner writes at its rank among the winners.
@@ -26,18 +32,30 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+#include <type_traits>
+
 namespace {
 
-constexpr uint32_t BFS_THREADS = 256;
+constexpr uint32_t BFS_THREADS = 512;
 constexpr uint32_t BFS_WAVES = BFS_THREADS / 64;
-constexpr uint32_t BFS_BATCH = 12;            // levels per host round trip (even: keeps queue parity)
+constexpr uint32_t BFS_BATCH0 = 8;            // levels before the first host round trip, doubled after each
+constexpr uint32_t BFS_BATCH = 32;            // up to this many (all even: keeps queue parity)
 constexpr uint32_t BFS_CUM = BFS_BATCH + 1;   // control word: vertices reached before this batch's first frontier
+constexpr uint32_t BFS_BU_SPAN = 256;         // vertices a wave scans per bottom-up pass (4 per lane)
+constexpr uint32_t BFS_BU_UNROLL = 8;         // neighbours per unvisited vertex in flight (bottom-up)
+constexpr uint32_t BFS_LDS_BITS = 1u << 20;   // the frontier bitmap is kept in LDS up to this many vertices
+constexpr float BFS_TD_WEIGHT = 4.f;          // LDS bitmap: cost of a top-down edge (probe + claim) against reading one unvisited vertex's row
 constexpr uint32_t BFS_UNROLL = 4;            // edges per lane in flight (top-down)
 constexpr uint32_t BFS_STAGE = 512;           // per-wave LDS staging of discovered vertices
+
+typedef int32_t i32x4_u __attribute__((ext_vector_type(4), aligned(4)));
 
 struct Work {                                  // layout of the caller's scratch buffer
   uint32_t* ctrl;                              // [0..BATCH] frontier sizes of the batch, [BFS_CUM] see above
   int32_t* queue[2];                           // n entries each
+  uint32_t* bitmap[3];                         // one bit per vertex each
+  uint32_t words;                              // 32-bit words per bitmap (a multiple of 64)
 };
 
 __host__ __device__ inline uint64_t ctrl_bytes() { return 256; }
@@ -50,25 +68,35 @@ Work carve(void* work, uint32_t n) {
   w.queue[0] = (int32_t*)p;
   p += ((uint64_t)n * 4 + 255) / 256 * 256;
   w.queue[1] = (int32_t*)p;
+  p += ((uint64_t)n * 4 + 255) / 256 * 256;
+  w.words = (uint32_t)((((uint64_t)n + 31) / 32 + 63) / 64 * 64);
+  for (int i = 0; i < 3; ++i) {
+    w.bitmap[i] = (uint32_t*)p;
+    p += (uint64_t)w.words * 4;
+  }
   return w;
 }
 
 __global__ __launch_bounds__(BFS_THREADS) void bfs_init(int32_t* __restrict__ level, uint32_t n,
                                                        uint32_t source, int32_t* __restrict__ q0,
-                                                       uint32_t* __restrict__ ctrl) {
+                                                       uint32_t* __restrict__ ctrl,
+                                                       uint32_t* __restrict__ bitmaps, uint32_t words) {
   const uint32_t stride = gridDim.x * BFS_THREADS;
   for (uint32_t v = blockIdx.x * BFS_THREADS + threadIdx.x; v < n; v += stride)
     level[v] = (v == source) ? 0 : -1;
+  // the three bitmaps are contiguous; the first is the frontier of level 0
+  for (uint32_t i = blockIdx.x * BFS_THREADS + threadIdx.x; i < 3u * words; i += stride)
+    bitmaps[i] = i == (source >> 5) ? 1u << (source & 31u) : 0u;
   if (blockIdx.x == 0 && threadIdx.x <= BFS_CUM) ctrl[threadIdx.x] = threadIdx.x == 0 ? 1u : 0u;
   if (blockIdx.x == 0 && threadIdx.x == 0) q0[0] = (int32_t)source;
 }
 
-// start of the next batch: its first frontier is the last one of the previous batch
-__global__ void bfs_roll(uint32_t* __restrict__ ctrl) {
+// start of the next batch: its first frontier is the last one of the previous batch of nb levels
+__global__ void bfs_roll(uint32_t* __restrict__ ctrl, uint32_t nb) {
   const uint32_t t = threadIdx.x;
-  uint32_t carry = ctrl[BFS_BATCH];
+  uint32_t carry = ctrl[nb];
   uint32_t cum = ctrl[BFS_CUM];
-  for (uint32_t i = 0; i < BFS_BATCH; ++i) cum += ctrl[i];
+  for (uint32_t i = 0; i < nb; ++i) cum += ctrl[i];
   __syncthreads();
   if (t <= BFS_BATCH) ctrl[t] = t == 0 ? carry : 0u;
   if (t == BFS_CUM) ctrl[t] = cum;
@@ -112,10 +140,16 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
                                                         int32_t* __restrict__ q_out,
                                                         uint32_t* __restrict__ ctrl, uint32_t j,
                                                         int32_t next_level, uint32_t n,
-                                                        uint32_t symmetric) {
+                                                        uint32_t symmetric,
+                                                        const uint32_t* __restrict__ bm_in,
+                                                        uint32_t* __restrict__ bm_out,
+                                                        uint32_t* __restrict__ bm_clr, uint32_t words) {
+  extern __shared__ __attribute__((aligned(16))) uint32_t s_bitmap[];   // `words` entries when n <= BFS_LDS_BITS, else none
   __shared__ uint32_t s_excl[BFS_WAVES][64];
   __shared__ int32_t s_start[BFS_WAVES][64];
   __shared__ int32_t s_stage[BFS_WAVES][BFS_STAGE];
+  __shared__ int32_t s_list[BFS_WAVES][BFS_BU_SPAN];
+  __shared__ uint32_t s_out[BFS_WAVES][BFS_BU_SPAN / 32u];
   __shared__ uint32_t s_cnt[BFS_WAVES];
   __shared__ uint32_t s_base;
   const uint32_t n_in = ctrl[j];
@@ -129,57 +163,126 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
   const uint32_t gwave = blockIdx.x * BFS_WAVES + wave;
   const uint32_t total_waves = gridDim.x * BFS_WAVES;
   Stage stage{&s_stage[wave][0], 0u};
+  // the bitmap this level's successor will write must be empty by then
+  if (symmetric != 0u)
+    for (uint32_t i = blockIdx.x * BFS_THREADS + threadIdx.x; i < words; i += gridDim.x * BFS_THREADS) bm_clr[i] = 0u;
+  const bool in_lds = n <= BFS_LDS_BITS;
 
-  // Top-down touches about n_in * (m/n) edges; bottom-up makes every unvisited vertex look at
-  // about n/n_in neighbours before it meets the frontier.  Go bottom-up when the first is larger.
-  const float m = (float)row_ptr[n];      // number of stored (directed) edges
-  const float td_cost = (float)n_in * (float)n_in * m;
-  const float bu_cost = (float)unvisited * (float)n * (float)n;
+  // Top-down touches about n_in * (m/n) edges, each a random probe of level[] and, for most, an
+  // atomic claim.  Bottom-up reads level[] once and the row of every unvisited vertex; with the
+  // bitmap in LDS its probes are almost free, otherwise an unvisited vertex makes about n/n_in
+  // of them through L2 before it meets the frontier.  Go bottom-up when top-down costs more.
+  const int32_t m_edges = row_ptr[n];     // number of stored (directed) edges
+  const float m = (float)m_edges;
+  const float td_edges_n = (float)n_in * m;                     // top-down edges, times n
+  const bool bottom_up = in_lds ? BFS_TD_WEIGHT * td_edges_n > (float)unvisited * (float)n
+                                : td_edges_n * (float)n_in > (float)unvisited * (float)n * (float)n;
   // (bottom-up reads a vertex's stored edges as its in-edges: only right for a symmetric graph)
-  if (symmetric != 0u && td_cost > bu_cost) {
-    // bottom-up: two vertices per lane and four neighbours per step in flight, so that the
-    // dependent column -> level reads of different vertices and neighbours overlap
-    const int32_t cur = next_level - 1;
-    for (uint32_t v0 = gwave * 128u; v0 < n; v0 += total_waves * 128u) {
-      int32_t e[2], e1[2];
-      bool open[2], found[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const uint32_t v = v0 + 64u * u + lane;
-        open[u] = v < n && level[v] < 0;
-        found[u] = false;
-        e[u] = e1[u] = 0;
-      }
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-        if (open[u]) {
-          const uint32_t v = v0 + 64u * u + lane;
-          e[u] = row_ptr[v];
-          e1[u] = row_ptr[v + 1u];
-        }
-      while (__any((open[0] && e[0] < e1[0]) || (open[1] && e[1] < e1[1]))) {
-        int32_t nb[2][4];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) nb[u][i] = (open[u] && e[u] + i < e1[u]) ? col_idx[e[u] + i] : -1;
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          bool hit = false;
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (nb[u][i] >= 0) hit |= level[nb[u][i]] == cur;
-          if (hit) { found[u] = true; open[u] = false; }
-          e[u] += 4;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const uint32_t v = v0 + 64u * u + lane;
-        if (found[u]) level[v] = next_level;
-        stage_append(stage, found[u], (int32_t)v, q_out, cnt_out, lane);
-      }
+  if (symmetric != 0u && bottom_up) {
+    // Most vertices are already reached when this direction pays, so a wave first packs the
+    // unvisited ones of its span into LDS (coalesced level reads, ballot ranks) and then works on
+    // full lanes: one unvisited vertex per lane, eight of its neighbours in flight per step,
+    // until one of them is in the frontier or the list ends.
+    // (a handful of unvisited vertices do not pay for the copy: they probe the bitmap in memory)
+    const bool copy = in_lds && (uint64_t)unvisited * 64u >= n;
+    if (copy) {
+      const uint4* src = reinterpret_cast<const uint4*>(bm_in);
+      uint4* dst = reinterpret_cast<uint4*>(s_bitmap);
+      for (uint32_t i = threadIdx.x; i < words / 4u; i += BFS_THREADS) dst[i] = src[i];
+      __syncthreads();
     }
+    // (two instantiations of the loop: a pointer that may be LDS or memory would turn every probe
+    // into a flat load)
+    // The loads below are unconditional (indices clamped into the arrays, results masked): a
+    // load under a per-lane condition becomes a branch, and the compiler then waits for every
+    // load before it issues the next.
+    int32_t* list = &s_list[wave][0];
+    const int32_t last_edge = m_edges - 1;         // m_edges > 0: bottom-up is never chosen for an empty graph
+    // one round for the first NQ * 64 entries of the list: NQ vertices per lane, eight neighbours
+    // of each in flight
+    auto rounds = [&](auto lds_probe, auto nq_tag, uint32_t v0, uint32_t cnt) {
+      constexpr bool LDS_PROBE = decltype(lds_probe)::value;
+      constexpr uint32_t NQ = decltype(nq_tag)::value;
+      int32_t vq[NQ], e[NQ], e1[NQ];
+      bool open[NQ], found[NQ];
+#pragma unroll
+      for (uint32_t q = 0; q < NQ; ++q) {
+        open[q] = 64u * q + lane < cnt;
+        vq[q] = list[min(64u * q + lane, BFS_BU_SPAN - 1u)];
+        if (!open[q]) vq[q] = 0;
+        found[q] = false;
+      }
+#pragma unroll
+      for (uint32_t q = 0; q < NQ; ++q) {
+        e[q] = row_ptr[vq[q]];
+        e1[q] = row_ptr[vq[q] + 1];
+      }
+#pragma unroll
+      for (uint32_t q = 0; q < NQ; ++q) open[q] = open[q] && e[q] < e1[q];
+      for (;;) {
+        bool any_open = false;
+#pragma unroll
+        for (uint32_t q = 0; q < NQ; ++q) any_open |= open[q];
+        if (!__any(any_open)) break;
+        int32_t nb[NQ][BFS_BU_UNROLL];
+#pragma unroll
+        for (uint32_t q = 0; q < NQ; ++q)
+#pragma unroll
+          for (uint32_t i = 0; i < BFS_BU_UNROLL; ++i) nb[q][i] = col_idx[min(e[q] + (int32_t)i, last_edge)];
+        uint32_t word[NQ][BFS_BU_UNROLL];
+#pragma unroll
+        for (uint32_t q = 0; q < NQ; ++q)
+#pragma unroll
+          for (uint32_t i = 0; i < BFS_BU_UNROLL; ++i)
+            word[q][i] = LDS_PROBE ? s_bitmap[(uint32_t)nb[q][i] >> 5] : bm_in[(uint32_t)nb[q][i] >> 5];
+#pragma unroll
+        for (uint32_t q = 0; q < NQ; ++q) {
+          uint32_t hit = 0u;
+#pragma unroll
+          for (uint32_t i = 0; i < BFS_BU_UNROLL; ++i)
+            hit |= (word[q][i] >> ((uint32_t)nb[q][i] & 31u)) & (uint32_t)(e[q] + (int32_t)i < e1[q]);
+          hit &= (uint32_t)open[q];
+          e[q] += (int32_t)BFS_BU_UNROLL;
+          found[q] = found[q] || hit != 0u;
+          open[q] = open[q] && hit == 0u && e[q] < e1[q];
+        }
+      }
+#pragma unroll
+      for (uint32_t q = 0; q < NQ; ++q) {
+        if (found[q]) {
+          level[vq[q]] = next_level;
+          atomicOr(&s_out[wave][((uint32_t)vq[q] - v0) >> 5], 1u << ((uint32_t)vq[q] & 31u));
+        }
+        stage_append(stage, found[q], vq[q], q_out, cnt_out, lane);
+      }
+    };
+    // (two instantiations per width: a pointer that may be LDS or memory would turn every probe
+    // into a flat load)
+    auto scan = [&](auto lds_probe) {
+    constexpr uint32_t Q = BFS_BU_SPAN / 64u;
+    for (uint32_t v0 = gwave * BFS_BU_SPAN; v0 < n; v0 += total_waves * BFS_BU_SPAN) {
+      int32_t lv[Q];
+#pragma unroll
+      for (uint32_t u = 0; u < Q; ++u) lv[u] = level[min(v0 + 64u * u + lane, n - 1u)];
+      uint32_t cnt = 0;
+#pragma unroll
+      for (uint32_t u = 0; u < Q; ++u) {
+        const bool unv = lv[u] < 0 && v0 + 64u * u + lane < n;
+        const uint64_t mask = __ballot(unv);
+        if (unv) list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = (int32_t)(v0 + 64u * u + lane);
+        cnt += (uint32_t)__popcll(mask);
+      }
+      if (lane < BFS_BU_SPAN / 32u) s_out[wave][lane] = 0u;
+      __builtin_amdgcn_wave_barrier();
+      if (cnt > 128u) rounds(lds_probe, std::integral_constant<uint32_t, 4>{}, v0, cnt);
+      else if (cnt > 64u) rounds(lds_probe, std::integral_constant<uint32_t, 2>{}, v0, cnt);
+      else if (cnt > 0u) rounds(lds_probe, std::integral_constant<uint32_t, 1>{}, v0, cnt);
+      __builtin_amdgcn_wave_barrier();
+      // the span's bitmap words belong to this wave alone (v0 is a multiple of 256)
+      if (lane < BFS_BU_SPAN / 32u && (v0 >> 5) + lane < words) bm_out[(v0 >> 5) + lane] = s_out[wave][lane];
+    }
+    };
+    if (copy) scan(std::true_type{}); else scan(std::false_type{});
   } else {
 
   // top-down.  Small frontiers are split into chunks of fewer than 64 vertices so that
@@ -207,31 +310,32 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
     __builtin_amdgcn_wave_barrier();
 
     for (uint32_t e0 = 0; e0 < total; e0 += 64u * BFS_UNROLL) {
+      // (unconditional loads, edge index clamped and the result masked: see bottom-up)
       int32_t nb[BFS_UNROLL];
       bool live[BFS_UNROLL];
 #pragma unroll
       for (uint32_t u = 0; u < BFS_UNROLL; ++u) {
-        const uint32_t e = e0 + 64u * u + lane;
-        live[u] = e < total;
-        nb[u] = 0;
-        if (live[u]) {
-          // owner = last lane whose exclusive prefix is <= e
-          uint32_t lo = 0, hi = 63;
+        const uint32_t e = min(e0 + 64u * u + lane, total - 1u);
+        live[u] = e0 + 64u * u + lane < total;
+        // owner = last lane whose exclusive prefix is <= e
+        uint32_t lo = 0, hi = 63;
 #pragma unroll
-          for (int it = 0; it < 6; ++it) {
-            const uint32_t mid = (lo + hi + 1u) >> 1;
-            if (s_excl[wave][mid] <= e) lo = mid; else hi = mid - 1u;
-          }
-          nb[u] = col_idx[s_start[wave][lo] + (int32_t)(e - s_excl[wave][lo])];
+        for (int it = 0; it < 6; ++it) {
+          const uint32_t mid = (lo + hi + 1u) >> 1;
+          const bool up = s_excl[wave][mid] <= e;
+          lo = up ? mid : lo;
+          hi = up ? hi : mid - 1u;
         }
+        nb[u] = col_idx[s_start[wave][lo] + (int32_t)(e - s_excl[wave][lo])];
       }
       int32_t seen[BFS_UNROLL];
 #pragma unroll
-      for (uint32_t u = 0; u < BFS_UNROLL; ++u) seen[u] = live[u] ? level[nb[u]] : 0;
+      for (uint32_t u = 0; u < BFS_UNROLL; ++u) seen[u] = level[nb[u]];
 #pragma unroll
       for (uint32_t u = 0; u < BFS_UNROLL; ++u) {
         bool won = false;
         if (live[u] && seen[u] < 0) won = atomicCAS(&level[nb[u]], -1, next_level) == -1;
+        if (won && symmetric != 0u) atomicOr(&bm_out[(uint32_t)nb[u] >> 5], 1u << ((uint32_t)nb[u] & 31u));
         stage_append(stage, won, nb[u], q_out, cnt_out, lane);
       }
     }
@@ -253,12 +357,17 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
   for (uint32_t i = lane; i < stage.count; i += 64u) q_out[off + i] = stage.buf[i];
 }
 
-// one workgroup per 1024 vertices, between 8 and 2048 workgroups
+// one workgroup per 4096 vertices, between 8 and 512 workgroups
 uint32_t blocks_for(uint32_t n) {
-  uint32_t b = (n + 1023u) / 1024u;
+  uint32_t b = (n + 4095u) / 4096u;
   if (b < 8u) b = 8u;
-  if (b > 2048u) b = 2048u;
+  if (b > 512u) b = 512u;
   return (b + 7u) / 8u * 8u;
+}
+
+// dynamic LDS of a level kernel: the frontier bitmap, when it fits
+uint32_t lds_bitmap_bytes(uint32_t n, uint32_t words, uint32_t symmetric) {
+  return symmetric != 0u && n <= BFS_LDS_BITS ? words * 4u : 0u;
 }
 
 }  // namespace
@@ -266,7 +375,17 @@ uint32_t blocks_for(uint32_t n) {
 extern "C" {
 
 uint64_t mgb_bfs_work_bytes(uint32_t n) {
-  return ctrl_bytes() + 2ull * (((uint64_t)n * 4 + 255) / 256 * 256);
+  return ctrl_bytes() + 2ull * (((uint64_t)n * 4 + 255) / 256 * 256) + 3ull * ((((uint64_t)n + 31) / 32 + 63) / 64 * 64) * 4;
+}
+
+// workgroups of the level kernel that fit one CU: LDS (the frontier bitmap on top of the
+// kernel's own 29184 bytes of staging) or the 8 waves of a workgroup against 32 wave slots
+uint32_t mgb_bfs_residency(uint32_t n) {
+  if (n == 0u || n > 0x7fffffffu) return 0u;
+  const uint32_t words = (uint32_t)((((uint64_t)n + 31) / 32 + 63) / 64 * 64);
+  const uint32_t by_lds = (160u * 1024u) / (29184u + lds_bitmap_bytes(n, words, 1u));
+  const uint32_t by_waves = 32u / BFS_WAVES;
+  return by_lds < by_waves ? by_lds : by_waves;
 }
 
 int mgb_bfs_probe(uint32_t n, uint64_t m, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block) {
@@ -286,18 +405,31 @@ static int bfs_run(void* stream, const int32_t* row_ptr, const int32_t* col_idx,
   hipStream_t st = (hipStream_t)stream;
   const Work w = carve(work, n);
   const uint32_t blocks = blocks_for(n);
+  const uint32_t lds = lds_bitmap_bytes(n, w.words, symmetric);
+  static std::once_flag once;
+  static hipError_t attr = hipSuccess;
+  std::call_once(once, [] {
+    attr = hipFuncSetAttribute((const void*)bfs_level, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(BFS_LDS_BITS / 8u));
+  });
+  if (attr != hipSuccess) {
+    mgb_internal_set_error("bfs_level: dynamic LDS size", attr);
+    return MGB_E_BACKEND;
+  }
   hipLaunchKernelGGL(bfs_init, dim3(blocks), dim3(BFS_THREADS), 0, st, level, n, source, w.queue[0],
-                     w.ctrl);
-  uint32_t levels_done = 0;
+                     w.ctrl, w.bitmap[0], w.words);
+  uint32_t levels_done = 0, nb = BFS_BATCH0;
   uint32_t host_counts[BFS_BATCH + 1];
   for (;;) {
-    for (uint32_t j = 0; j < BFS_BATCH; ++j)
-      hipLaunchKernelGGL(bfs_level, dim3(blocks), dim3(BFS_THREADS), 0, st, row_ptr, col_idx, level,
-                         w.queue[j & 1u], w.queue[(j + 1u) & 1u], w.ctrl, j,
-                         (int32_t)(levels_done + j + 1u), n, symmetric);
+    for (uint32_t j = 0; j < nb; ++j) {
+      const uint32_t lv = levels_done + j;             // bitmap lv % 3 holds frontier lv
+      hipLaunchKernelGGL(bfs_level, dim3(blocks), dim3(BFS_THREADS), lds, st, row_ptr, col_idx, level,
+                         w.queue[j & 1u], w.queue[(j + 1u) & 1u], w.ctrl, j, (int32_t)(lv + 1u), n,
+                         symmetric, w.bitmap[lv % 3u], w.bitmap[(lv + 1u) % 3u], w.bitmap[(lv + 2u) % 3u],
+                         w.words);
+    }
     int rc = mgb_check_launch("bfs_level");
     if (rc != MGB_OK) return rc;
-    hipError_t e = hipMemcpyAsync(host_counts, w.ctrl, sizeof host_counts, hipMemcpyDeviceToHost, st);
+    hipError_t e = hipMemcpyAsync(host_counts, w.ctrl, (nb + 1u) * sizeof(uint32_t), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) {
       mgb_internal_set_error("bfs counter read-back", e);
@@ -305,14 +437,15 @@ static int bfs_run(void* stream, const int32_t* row_ptr, const int32_t* col_idx,
     }
     // host_counts[j] = size of the frontier at depth levels_done + j
     uint32_t j = 0;
-    while (j <= BFS_BATCH && host_counts[j] != 0u) ++j;
-    if (j <= BFS_BATCH) {                       // an empty frontier was reached
+    while (j <= nb && host_counts[j] != 0u) ++j;
+    if (j <= nb) {                              // an empty frontier was reached
       if (depth) *depth = levels_done + j;      // number of non-empty levels (source level included)
       return MGB_OK;
     }
-    levels_done += BFS_BATCH;
+    levels_done += nb;
     if (levels_done >= n) return MGB_OK;        // cannot happen: depth < n
-    hipLaunchKernelGGL(bfs_roll, dim3(1), dim3(64), 0, st, w.ctrl);
+    hipLaunchKernelGGL(bfs_roll, dim3(1), dim3(64), 0, st, w.ctrl, nb);
+    if (nb < BFS_BATCH) nb *= 2u;
   }
 }
 

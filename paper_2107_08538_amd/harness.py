@@ -71,7 +71,7 @@ def build_task(spec, data, device="cuda:0"):
         depth = C.c_uint32(0)
         fn = lambda st: mgb.mgb_bfs_enqueue(st, _ptr(rp), _ptr(ci), n, 0, _ptr(level), _ptr(work), C.byref(depth))
         t = Task(spec, dict(rp=rp, ci=ci, level=level, work=work), probe, fn, "bfs_level", None,
-                 alg_bytes=8.0 * m_edges + 24.0 * n)
+                 alg_bytes=8.0 * m_edges + 24.0 * n, wg_per_cu=int(mgb.mgb_bfs_residency(n)))
         t.depth = depth
         return t
     if k == "cnn":

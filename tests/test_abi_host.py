@@ -118,6 +118,10 @@ def test_residency_fact_enters_the_demand_and_the_trace():
     for shp in ((1, 416, 416, 3, 32, 1), (8, 416, 416, 32, 64, 2), (8, 104, 104, 128, 128, 1), (1, 104, 104, 128, 128, 1),
                 (2, 416, 416, 3, 64, 1), (1, 5, 6, 5, 7, 1), (8, 208, 208, 64, 64, 1)):
         assert mgb.mgb_conv3x3_residency(*shp) == lib.orc_conv3x3_residency(*[U(x) for x in shp]), shp
+    lib.orc_bfs_residency.restype = C.c_uint64
+    for n in (1, 1000, 1 << 16, 1 << 18, (1 << 18) + 1, 1 << 19, 1 << 20, (1 << 20) + 1, 1 << 24):
+        assert mgb.mgb_bfs_residency(n) == lib.orc_bfs_residency(U(n)), n
+    assert (mgb.mgb_bfs_residency(1 << 20), mgb.mgb_bfs_residency(1 << 16), mgb.mgb_bfs_residency(1 << 22)) == (1, 4, 4)
     assert mgb.mgb_gemm_f32_residency(0, 1, 1) == 0
 
 

@@ -397,7 +397,10 @@ def _csr(n, edges):
 
 
 @pytest.mark.parametrize("seed,n,deg", [(1, 1000, 3), (2, 5000, 1), (3, 1 << 16, 8), (4, 70000, 16),
-                                        (5, 100, 30), (6, 1 << 18, 32)])
+                                        (5, 100, 30), (6, 1 << 18, 32),
+                                        # more than 2^20 vertices: the frontier bitmap stays in memory;
+                                        # a span of 256 vertices that ends ragged; 37 levels in three batches
+                                        ((1 << 20) + 777, (1 << 20) + 777, 6), (8, 300001, 2.2)])
 def test_bfs_random_graphs_bit_exact(seed, n, deg):
     rp, ci = W.er_graph_csr(seed, n, deg)
     got, depth = run_bfs(rp, ci)
