@@ -160,6 +160,8 @@ int mgb_sched_destroy(mgb_sched* s);
  *   MGB_WAIT  queued: out->ticket valid, call mgb_task_wait.
  *   MGB_E_INVAL  grid or block has a zero dimension or block > 1024 threads.
  *   MGB_E_TOO_BIG  mem_bytes exceeds the cap; the task is never queued.
+ *   MGB_E_BACKEND  admitted, but no stream could be made for its CU mask: the
+ *                  placement has been given back (nothing is held, *out zeroed).
  * Compute demand (Algorithm 2's per-SM residency limits, per CU here):
  *   waves/wg = ceil(threads / wave_size);
  *   wg/CU    = max(1, min(max_wg_per_cu, max_waves_per_cu / waves/wg [, wg_per_cu of the probe]));
@@ -211,7 +213,10 @@ int mgb_task_complete(mgb_sched* s, uint64_t ticket);
 
 int mgb_sched_stats(mgb_sched* s, mgb_stats* out);
 /* Copy up to `cap` trace records starting at sequence number `first` into
- * `out` (host); returns the number copied or < 0.                           */
+ * `out` (host); returns the number copied or < 0.  A scheduler keeps its last
+ * 2^20 records at most (when that many are held the older half is dropped):
+ * a `first` below the oldest record kept starts at that record, and the `seq`
+ * fields show the gap.                                                       */
 int64_t mgb_trace_read(mgb_sched* s, uint64_t first, mgb_trace_rec* out, uint64_t cap);
 /* Write the whole trace as JSON lines to `path`.                             */
 int mgb_trace_dump(mgb_sched* s, const char* path);
@@ -257,6 +262,9 @@ int mgb_lazy_memset(mgb_lazy* z, uint64_t dst_pseudo, int value, uint64_t bytes)
  *    sum of the objects' sizes; mgb_task_probe_ex(task_id, footprint, grid, block, wg_per_cu)
  *    is issued and, if the task is queued, waited for up to timeout_ns (< 0:
  *    forever; on MGB_TIMEOUT the probe is cancelled and nothing has changed).
+ *    Other threads may use the runtime during that wait (freeing objects is
+ *    what lets a queued task in); if one of them frees or binds an object this
+ *    launch names, the placement is given back and MGB_E_BAD_STATE returned.
  *  - some are: the launch joins their task (launches that share memory objects
  *    form one task, Alg. 1); the sizes of the new objects are asked for with
  *    mgb_task_grow (MGB_E_BUSY: nothing has changed).  Objects of several tasks:

@@ -107,6 +107,10 @@ struct mgb_server {
       if (mgb_task_cancel(s, t) != MGB_OK) (void)mgb_task_complete(s, t);
     reclaimed += held[i].size();
     held[i].clear();
+    // a request the dead client never posted, or an answer it never collected, must not greet
+    // the slot's next owner
+    while (sem_trywait(&seg->slots[i].req) == 0) {}
+    while (sem_trywait(&seg->slots[i].resp) == 0) {}
     seg->slots[i].owner.store(0);
   }
   void serve(uint32_t i) {
@@ -327,15 +331,29 @@ int mgb_client_probe(mgb_client* c, uint64_t task_id, uint64_t mem_bytes, mgb_di
   return rc;
 }
 
+// A connection carries one request at a time, and a wait for admission ends only when some task
+// is completed - possibly by another thread of this process, over this connection.  The wait
+// therefore goes to the server in slices of 20 ms and gives the connection up between them (a
+// task admitted between two slices is found admitted by the next one at once).
 int mgb_client_wait(mgb_client* c, uint64_t ticket, int64_t timeout_ns, mgb_placement* out) {
   if (!c || !out) return MGB_E_INVAL;
-  std::lock_guard<std::mutex> lk(c->mu);
-  Slot& sl = c->seg->slots[c->slot];
-  sl.ticket = ticket;
-  sl.timeout_ns = timeout_ns;
-  const int rc = c->call(OP_WAIT);
-  *out = sl.placement;
-  return rc;
+  const int64_t slice = 20 * 1000 * 1000;
+  int64_t left = timeout_ns;
+  for (;;) {
+    const int64_t step = (timeout_ns < 0 || left > slice) ? slice : left;
+    int rc;
+    {
+      std::lock_guard<std::mutex> lk(c->mu);
+      Slot& sl = c->seg->slots[c->slot];
+      sl.ticket = ticket;
+      sl.timeout_ns = step;
+      rc = c->call(OP_WAIT);
+      *out = sl.placement;
+    }
+    if (rc != MGB_TIMEOUT) return rc;
+    if (timeout_ns >= 0 && (left -= step) <= 0) return MGB_TIMEOUT;
+    std::this_thread::yield();
+  }
 }
 
 static int ticket_call(mgb_client* c, Op op, uint64_t ticket, uint64_t bytes) {

@@ -224,32 +224,50 @@ int mgb_lazy_launch_prepare(mgb_lazy* z, uint64_t task_id, const uint64_t* pseud
                             mgb_dim3 grid, mgb_dim3 block, uint32_t wg_per_cu, int64_t timeout_ns,
                             void** real_args, mgb_placement* placement) {
   if (!z || !pseudo_args || !real_args || !placement || n_args == 0u) return MGB_E_INVAL;
-  std::lock_guard<std::mutex> lk(z->mu);
+  std::unique_lock<std::mutex> lk(z->mu);
   // the memory objects the kernel names
   std::vector<uint32_t> ids(n_args);
   std::vector<uint64_t> offs(n_args);
   std::vector<uint32_t> fresh;                       // not yet on the device, each once
   std::vector<std::shared_ptr<LTask>> owners;        // tasks whose objects are named, each once
   uint64_t extra = 0;
-  for (uint32_t i = 0; i < n_args; ++i) {
-    Obj* o = z->lookup(pseudo_args[i], &ids[i], &offs[i]);
-    if (!o || offs[i] > o->bytes) return MGB_E_UNKNOWN_TICKET;
-    if (o->real) {
-      if (std::find(owners.begin(), owners.end(), o->task) == owners.end()) owners.push_back(o->task);
-    } else if (std::find(fresh.begin(), fresh.end(), ids[i]) == fresh.end()) {
-      fresh.push_back(ids[i]);
-      extra += o->bytes;
+  auto classify = [&]() {
+    fresh.clear();
+    owners.clear();
+    extra = 0;
+    for (uint32_t i = 0; i < n_args; ++i) {
+      Obj* o = z->lookup(pseudo_args[i], &ids[i], &offs[i]);
+      if (!o || offs[i] > o->bytes) return false;
+      if (o->real) {
+        if (std::find(owners.begin(), owners.end(), o->task) == owners.end()) owners.push_back(o->task);
+      } else if (std::find(fresh.begin(), fresh.end(), ids[i]) == fresh.end()) {
+        fresh.push_back(ids[i]);
+        extra += o->bytes;
+      }
     }
-  }
+    return true;
+  };
+  if (!classify()) return MGB_E_UNKNOWN_TICKET;
   std::shared_ptr<LTask> task;
   if (owners.empty()) {
     // a new task: its footprint is what the kernel's objects add up to
     mgb_placement pl;
     int rc = mgb_task_probe_ex(z->s, task_id, extra, grid, block, wg_per_cu, &pl);
     if (rc == MGB_WAIT) {
+      // The wait may be long and ends only when some task gives resources back, which other
+      // threads do through this runtime (mgb_lazy_free): wait with the runtime unlocked, then
+      // look at the objects again.  If another thread freed or bound one of them meanwhile the
+      // footprint that was admitted is no longer this launch's: give the placement back.
       const uint64_t ticket = pl.ticket;
+      const uint64_t asked = extra;
+      lk.unlock();
       rc = mgb_task_wait(z->s, ticket, timeout_ns, &pl);
       if (rc == MGB_TIMEOUT) (void)mgb_task_cancel(z->s, ticket);
+      lk.lock();
+      if (rc == MGB_OK && (!classify() || !owners.empty() || extra != asked)) {
+        (void)mgb_task_complete(z->s, ticket);
+        return MGB_E_BAD_STATE;
+      }
     }
     if (rc != MGB_OK) return rc;
     task = std::make_shared<LTask>();
@@ -342,13 +360,15 @@ int mgb_lazy_memcpy_d2h(mgb_lazy* z, void* dst_host, uint64_t src_pseudo, uint64
   if (bytes == 0) return MGB_OK;
   if (!o->real) {
     // never used by a kernel so far: what the copy would read is what the recorded writes left
-    // (bytes nobody wrote read as zero)
-    std::vector<uint8_t> image(o->bytes, 0);
+    // in [off, off + bytes), in their order (bytes nobody wrote read as zero)
+    uint8_t* dst = (uint8_t*)dst_host;
+    std::memset(dst, 0, bytes);
     for (const Op& op : o->queue) {
-      if (op.kind == OP_H2D) std::memcpy(image.data() + op.offset, op.data.data(), op.bytes);
-      else std::memset(image.data() + op.offset, op.value, op.bytes);
+      const uint64_t lo = std::max(op.offset, off), hi = std::min(op.offset + op.bytes, off + bytes);
+      if (lo >= hi) continue;
+      if (op.kind == OP_H2D) std::memcpy(dst + (lo - off), op.data.data() + (lo - op.offset), hi - lo);
+      else std::memset(dst + (lo - off), op.value, hi - lo);
     }
-    std::memcpy(dst_host, image.data() + off, bytes);
     return MGB_OK;
   }
   if (!z->hip) {

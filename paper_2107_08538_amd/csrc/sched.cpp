@@ -52,6 +52,8 @@ uint64_t now_ns() {
 // its ordinary streams, so idle streams are destroyed (least recently used first) before the
 // count would pass kStreamsAlive; only streams of resident tasks may push it higher.
 constexpr uint32_t kStreamsAlive = 20;
+// Trace records kept per scheduler (120 bytes each); at the cap the older half is dropped.
+constexpr size_t kTraceCap = 1u << 20;
 std::atomic<uint32_t> g_live_streams{0};
 
 enum class State { Waiting, Running };
@@ -86,7 +88,8 @@ struct mgb_sched {
   uint32_t n_running_now = 0;
   bool oom = false;                          // try_admit: CG task that would have run out of memory
   std::vector<uint64_t> crashed;             // tickets rejected while queued, until their waiter collects them
-  std::vector<mgb_trace_rec> trace;
+  std::vector<mgb_trace_rec> trace;          // records trace_base .. trace_base + size - 1
+  uint64_t trace_base = 0;                   // seq of trace[0]: the oldest records are dropped at kTraceCap
   // backend: idle masked streams (mask, stream, when last used), idle timing events
   struct IdleStream { uint32_t mask; hipStream_t stream; uint64_t stamp; };
   std::vector<IdleStream> idle_streams;
@@ -109,9 +112,13 @@ struct mgb_sched {
 
   uint64_t log(uint32_t kind, const Task* t, uint64_t task_id, uint64_t ticket, uint64_t mem,
                mgb_dim3 grid, mgb_dim3 block, uint32_t gmask, int32_t code, uint64_t cause) {
+    if (trace.size() >= kTraceCap) {
+      trace.erase(trace.begin(), trace.begin() + (long)(kTraceCap / 2));
+      trace_base += kTraceCap / 2;
+    }
     mgb_trace_rec r;
     std::memset(&r, 0, sizeof r);
-    r.seq = trace.size();
+    r.seq = trace_base + trace.size();
     r.t_ns = now_ns();
     r.task_id = t ? t->task_id : task_id;
     r.ticket = t ? t->ticket : ticket;
@@ -334,6 +341,31 @@ struct mgb_sched {
     t.ev_start = t.ev_stop = nullptr;
   }
 
+  // The body of mgb_task_complete: input record, release, re-pack.  Lock held.
+  int complete_locked(uint64_t ticket) {
+    uint64_t cause = log(MGB_EV_COMPLETE, nullptr, 0, ticket, 0, {}, {}, 0, 0, 0);
+    trace.back().cause_seq = (uint32_t)cause;
+    auto it = tasks.find(ticket);
+    if (it == tasks.end()) {
+      log(MGB_EV_REJECT, nullptr, 0, ticket, 0, {}, {}, 0, MGB_E_UNKNOWN_TICKET, cause);
+      return MGB_E_UNKNOWN_TICKET;
+    }
+    Task& t = it->second;
+    if (t.state != State::Running) {
+      log(MGB_EV_REJECT, &t, 0, 0, 0, {}, {}, 0, MGB_E_BAD_STATE, cause);
+      return MGB_E_BAD_STATE;
+    }
+    release(t);
+    log(MGB_EV_RELEASE, &t, 0, 0, 0, {}, {}, t.granted, 0, cause);
+    unbind_stream(t);
+    tasks.erase(it);
+    if (rescan(cause)) cv.notify_all();
+    return MGB_OK;
+  }
+
+  // Hand an admitted task to its caller.  If the backend cannot give it a stream the placement
+  // is useless: the task is completed on the caller's behalf (the trace shows an ordinary
+  // completion right after the admission) and the error is returned with nothing held.
   int fill(Task& t, mgb_placement* out, std::unique_lock<std::mutex>& lk) {
     out->ticket = t.ticket;
     out->granule_mask = t.granted;
@@ -343,6 +375,10 @@ struct mgb_sched {
     int rc = bind_stream(t, lk);                     // may release and retake the lock
     auto it = tasks.find(ticket);
     out->stream = it == tasks.end() ? nullptr : (void*)it->second.stream;
+    if (rc != MGB_OK) {
+      if (it != tasks.end()) (void)complete_locked(ticket);
+      std::memset(out, 0, sizeof *out);
+    }
     return rc;
   }
 };
@@ -650,24 +686,7 @@ int mgb_task_sync(mgb_sched* s, uint64_t ticket, double* gpu_ms) {
 int mgb_task_complete(mgb_sched* s, uint64_t ticket) {
   if (!s) return MGB_E_INVAL;
   std::lock_guard<std::mutex> lk(s->mu);
-  uint64_t cause = s->log(MGB_EV_COMPLETE, nullptr, 0, ticket, 0, {}, {}, 0, 0, 0);
-  s->trace.back().cause_seq = (uint32_t)cause;
-  auto it = s->tasks.find(ticket);
-  if (it == s->tasks.end()) {
-    s->log(MGB_EV_REJECT, nullptr, 0, ticket, 0, {}, {}, 0, MGB_E_UNKNOWN_TICKET, cause);
-    return MGB_E_UNKNOWN_TICKET;
-  }
-  Task& t = it->second;
-  if (t.state != State::Running) {
-    s->log(MGB_EV_REJECT, &t, 0, 0, 0, {}, {}, 0, MGB_E_BAD_STATE, cause);
-    return MGB_E_BAD_STATE;
-  }
-  s->release(t);
-  s->log(MGB_EV_RELEASE, &t, 0, 0, 0, {}, {}, t.granted, 0, cause);
-  s->unbind_stream(t);
-  s->tasks.erase(it);
-  if (s->rescan(cause)) s->cv.notify_all();
-  return MGB_OK;
+  return s->complete_locked(ticket);
 }
 
 int mgb_sched_stats(mgb_sched* s, mgb_stats* out) {
@@ -678,16 +697,18 @@ int mgb_sched_stats(mgb_sched* s, mgb_stats* out) {
   out->n_waiting = (uint32_t)s->waitq.size();
   out->n_running = s->n_running_now;
   out->n_streams = s->n_streams;
-  out->n_events = s->trace.size();
+  out->n_events = s->trace_base + s->trace.size();
   return MGB_OK;
 }
 
 int64_t mgb_trace_read(mgb_sched* s, uint64_t first, mgb_trace_rec* out, uint64_t cap) {
   if (!s || (!out && cap)) return MGB_E_INVAL;
   std::lock_guard<std::mutex> lk(s->mu);
-  if (first >= s->trace.size()) return 0;
-  uint64_t n = std::min<uint64_t>(cap, s->trace.size() - first);
-  std::memcpy(out, s->trace.data() + first, n * sizeof(mgb_trace_rec));
+  if (first < s->trace_base) first = s->trace_base;            // older records were dropped
+  if (first - s->trace_base >= s->trace.size()) return 0;
+  const uint64_t at = first - s->trace_base;
+  uint64_t n = std::min<uint64_t>(cap, s->trace.size() - at);
+  std::memcpy(out, s->trace.data() + at, n * sizeof(mgb_trace_rec));
   return (int64_t)n;
 }
 

@@ -341,3 +341,25 @@ def test_probe_functions_agree_with_checker_formulas():
                                 C.byref(mgb.mgb_dim3())) == mgb.MGB_E_UNSUPPORTED
     assert mgb.mgb_gemm_f32_probe(0, 1, 1, C.byref(C.c_uint64()), C.byref(mgb.mgb_dim3()),
                                   C.byref(mgb.mgb_dim3())) == mgb.MGB_E_UNSUPPORTED
+
+
+def test_trace_keeps_the_last_million_records():
+    # 2^20 records are kept at most; at the cap the older half goes.  A probe + complete pair
+    # logs four records (two inputs, two decisions).
+    s = _null()
+    pairs = (1 << 18) + 1000
+    for i in range(pairs):
+        rc, pl = s.probe(i, 1, (1, 1, 1), (64, 1, 1))
+        assert rc == mgb.MGB_OK
+        assert s.complete(pl.ticket) == mgb.MGB_OK
+    st = s.stats()
+    assert st.n_events == 4 * pairs > (1 << 20)
+    tr = s.trace()                                   # reads from seq 0: starts at the oldest record kept
+    assert len(tr) == st.n_events - (1 << 19)
+    assert np.array_equal(tr["seq"], np.arange(1 << 19, st.n_events, dtype=np.uint64))
+    assert tr["kind"][-1] == mgb.MGB_EV_RELEASE
+    tail = np.zeros(8, dtype=mgb.TRACE_DT)
+    vp = C.c_void_p(tail.ctypes.data)
+    assert mgb.mgb_trace_read(s.h, st.n_events - 2, vp, 8) == 2 and tail["seq"][1] == st.n_events - 1
+    assert mgb.mgb_trace_read(s.h, st.n_events, vp, 8) == 0
+    assert s.destroy() == 0

@@ -109,3 +109,29 @@ def test_clients_notice_a_server_that_stopped():
     rc, pl = c.probe(1, 10, (1, 1, 1), (64, 1, 1))
     assert rc == mgb.MGB_E_BACKEND
     assert s.destroy() == mgb.MGB_OK
+
+
+def test_two_threads_share_one_connection_while_one_waits():
+    # the waiter must not keep the connection to itself: the completion that lets it in comes
+    # from another thread of the same process, over the same connection
+    s = _sched(mem_cap_bytes=1000)
+    name = _name("share")
+    sv = mgb.Server(s, name, 1)
+    c = mgb.Client(name)
+    rc, p1 = c.probe(1, 700, (8, 1, 1), (64, 1, 1))
+    assert rc == mgb.MGB_OK
+    rc, p2 = c.probe(2, 700, (8, 1, 1), (64, 1, 1))
+    assert rc == mgb.MGB_WAIT
+    got = []
+    th = threading.Thread(target=lambda: got.append(c.wait(p2.ticket, 20_000_000_000)))
+    th.start()
+    time.sleep(0.1)                                          # the waiter is inside its wait
+    assert c.stats().n_waiting == 1
+    assert c.complete(p1.ticket) == mgb.MGB_OK
+    th.join(30)
+    assert not th.is_alive() and got[0][0] == mgb.MGB_OK and got[0][1].ticket == p2.ticket
+    assert c.complete(p2.ticket) == mgb.MGB_OK
+    assert c.disconnect() == mgb.MGB_OK
+    sv.stop()
+    assert_trace_matches_replay(s.desc, s.trace())
+    assert s.destroy() == 0

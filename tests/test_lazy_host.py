@@ -342,3 +342,50 @@ def test_two_clients_contend_for_memory_through_the_scheduler():
     tr = s.trace()
     dec = assert_trace_matches_replay(s.desc, tr)
     assert (dec["kind"] == oracle.D_ADMIT).sum() == 3 and s.stats().free_bytes == 1000
+
+
+def test_threads_of_one_runtime_do_not_block_each_other_while_one_waits():
+    # one runtime, two threads: the second launch does not fit until the first task's object is
+    # freed, and the free has to get through the runtime while the launch is waiting in it
+    s = mgb.Sched(backend=mgb.MGB_BACKEND_NULL, mem_cap_bytes=1000, granule_cus=8)
+    z = mgb.Lazy(s)
+    rc, a = z.malloc(800)
+    rc, b = z.malloc(800)
+    rc, real, pl = z.launch_prepare(1, [a], (1, 1, 1), (64, 1, 1))
+    assert rc == 0
+    out = {}
+
+    def second():
+        out["rc"], out["real"], out["pl"] = z.launch_prepare(2, [b], (1, 1, 1), (64, 1, 1), timeout_ns=20_000_000_000)
+
+    th = threading.Thread(target=second)
+    th.start()
+    for _ in range(2000):                       # until the second probe is queued
+        if s.stats().n_waiting == 1:
+            break
+        threading.Event().wait(0.001)
+    assert s.stats().n_waiting == 1
+    assert z.free(a) == 0                       # would wait forever if the waiter held the runtime's lock
+    th.join(30)
+    assert not th.is_alive() and out["rc"] == 0 and out["real"][0] != 0
+    assert z.free(b) == 0 and z.destroy() == 0
+    assert_trace_matches_replay(s.desc, s.trace())
+    assert s.destroy() == 0
+
+
+def test_copy_back_of_a_window_of_an_unbound_object():
+    # reads of a never-bound object see the recorded writes clipped to the window asked for
+    s = mgb.Sched(backend=mgb.MGB_BACKEND_NULL, granule_cus=8)
+    z = mgb.Lazy(s)
+    rc, a = z.malloc(1 << 30)                   # large: the read must not materialise the object
+    src = np.arange(64, dtype=np.uint8)
+    assert z.memset(a, 7, 1 << 30) == 0
+    assert z.memcpy_h2d(a + 100, src.ctypes.data, 64) == 0
+    assert z.memset(a + 120, 9, 8) == 0
+    got = np.zeros(80, np.uint8)
+    assert z.memcpy_d2h(got.ctypes.data, a + 90, 80) == 0
+    want = np.full(80, 7, np.uint8)
+    want[10:74] = src
+    want[30:38] = 9
+    assert np.array_equal(got, want)
+    assert z.free(a) == 0 and z.destroy() == 0 and s.destroy() == 0
