@@ -28,6 +28,7 @@
 #include <unistd.h>
 
 #include <atomic>
+#include <chrono>
 #include <cerrno>
 #include <cstdio>
 #include <cstring>
@@ -169,11 +170,24 @@ struct mgb_server {
   }
 };
 
+struct mgb_client;
+namespace {
+// Takes the connection for one request.  A mutex is not fair: a waiter that takes it again at
+// once for its next slice could starve everybody else, so other requests announce themselves
+// and the waiter stays away while any are announced.
+struct Turn {
+  explicit Turn(mgb_client* c);
+  ~Turn();
+  mgb_client* c;
+};
+}  // namespace
+
 struct mgb_client {
   Segment* seg = nullptr;
   size_t bytes = 0;
   uint32_t slot = 0;
   std::mutex mu;                                   // one request at a time per connection
+  std::atomic<int> callers{0};                     // threads inside or queued for a request other than a wait slice
   std::map<std::vector<uint32_t>, hipStream_t> streams;   // CU mask -> this process's masked stream
 
   int gone() {
@@ -193,6 +207,17 @@ struct mgb_client {
     }
   }
 };
+
+namespace {
+Turn::Turn(mgb_client* cl) : c(cl) {
+  ++c->callers;
+  c->mu.lock();
+}
+Turn::~Turn() {
+  c->mu.unlock();
+  --c->callers;
+}
+}  // namespace
 
 extern "C" {
 
@@ -319,7 +344,7 @@ int mgb_client_disconnect(mgb_client* c) {
 int mgb_client_probe(mgb_client* c, uint64_t task_id, uint64_t mem_bytes, mgb_dim3 grid, mgb_dim3 block,
                      uint32_t wg_per_cu, mgb_placement* out) {
   if (!c || !out) return MGB_E_INVAL;
-  std::lock_guard<std::mutex> lk(c->mu);
+  Turn turn(c);
   Slot& sl = c->seg->slots[c->slot];
   sl.task_id = task_id;
   sl.bytes = mem_bytes;
@@ -352,13 +377,13 @@ int mgb_client_wait(mgb_client* c, uint64_t ticket, int64_t timeout_ns, mgb_plac
     }
     if (rc != MGB_TIMEOUT) return rc;
     if (timeout_ns >= 0 && (left -= step) <= 0) return MGB_TIMEOUT;
-    std::this_thread::yield();
+    while (c->callers.load() > 0) std::this_thread::sleep_for(std::chrono::microseconds(50));
   }
 }
 
 static int ticket_call(mgb_client* c, Op op, uint64_t ticket, uint64_t bytes) {
   if (!c) return MGB_E_INVAL;
-  std::lock_guard<std::mutex> lk(c->mu);
+  Turn turn(c);
   Slot& sl = c->seg->slots[c->slot];
   sl.ticket = ticket;
   sl.bytes = bytes;
@@ -371,7 +396,7 @@ int mgb_client_complete(mgb_client* c, uint64_t ticket) { return ticket_call(c, 
 
 int mgb_client_stats(mgb_client* c, mgb_stats* out) {
   if (!c || !out) return MGB_E_INVAL;
-  std::lock_guard<std::mutex> lk(c->mu);
+  Turn turn(c);
   const int rc = c->call(OP_STATS);
   *out = c->seg->slots[c->slot].stats;
   return rc;
@@ -383,7 +408,7 @@ int mgb_client_stream(mgb_client* c, const mgb_placement* placement, void** stre
   bool any = false;
   for (uint32_t w : key) any = any || w != 0u;
   if (!any) return MGB_E_INVAL;
-  std::lock_guard<std::mutex> lk(c->mu);
+  Turn turn(c);
   auto it = c->streams.find(key);
   if (it == c->streams.end()) {
     hipStream_t st = nullptr;
