@@ -32,7 +32,7 @@ def parse():
 MEASURED_TRAFFIC_BYTES = {
     ("mix16", "gemm_f32_dma_kernel"): 470.4e6,  # per 4096^3 launch
     ("mix16", "jacobi_sweeps"): 138.2e6,       # per launch (24 four-sweep + 2 two-sweep launches per task)
-    ("mix16", "bfs_level"): 20.6e6,            # per level launch, averaged over the 12 launches of a traversal
+    ("mix16", "bfs_level"): 22.2e6,            # per level launch, averaged over the 8 launches of a traversal
 }
 
 

@@ -446,8 +446,9 @@ int mgb_sched_create(const mgb_device_desc* desc, mgb_sched** out) {
   s->load.assign(s->G, 0);
   if (d.backend == MGB_BACKEND_HIP) {
     // the masks of the large blocks (whole device, halves, quarters) are created now, not on
-    // the first task that needs them
-    for (uint32_t b = s->G; b >= 1u && b * 4u >= s->G; b >>= 1)
+    // the first task that needs them; SERIAL and CG only ever grant the whole device
+    const bool whole_only = d.policy == MGB_POLICY_SERIAL || d.policy == MGB_POLICY_CG;
+    for (uint32_t b = s->G; b >= 1u && b * 4u >= s->G && (b == s->G || !whole_only); b >>= 1)
       for (uint32_t start = 0; start + b <= s->G; start += b) {
         hipStream_t st = nullptr;
         if (s->create_stream(mgb_sched::block_bits(b) << start, &st) != MGB_OK) {

@@ -28,6 +28,17 @@ def _where(stream, n_blocks=4096):
     return set(out.cpu().numpy().tolist())
 
 
+def test_whole_device_policies_create_one_stream():
+    # SERIAL and CG only ever grant the whole device: one masked stream, not the seven of HARD
+    for kw in (dict(policy=mgb.MGB_POLICY_SERIAL), dict(policy=mgb.MGB_POLICY_CG, max_running=4)):
+        s = mgb.Sched(**kw)
+        assert s.stats().n_streams == 1
+        rc, pl = s.probe(1, 1 << 20, (8, 1, 1), (64, 1, 1))
+        assert rc == mgb.MGB_OK and pl.granule_mask == 0xFF and pl.stream
+        assert s.complete(pl.ticket) == mgb.MGB_OK and s.stats().n_streams == 1
+        assert s.destroy() == 0
+
+
 def test_default_partitions_are_eighths_of_the_device():
     s = mgb.Sched()
     assert s.desc.granule_cus == 32 and s.stats().n_streams == 7      # whole, halves, quarters created up front
