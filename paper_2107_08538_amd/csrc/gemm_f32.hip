@@ -357,19 +357,30 @@ struct Geometry {
   bool fast;       // register-staged kernel: every tile full
 };
 
-// 256 x 256 tiles if every CU gets one (139 against 136 TFLOP/s at 4096^3; with fewer tiles than
+// 256 x 256 tiles if every CU gets one (142 against 136 TFLOP/s at 4096^3; with fewer tiles than
 // CUs the smaller tile wins: 3072^3 runs at 97 TFLOP/s on 128 x 128 tiles, 78 on 256 x 256), else
-// 128 x 128 tiles if they give at least half of the CUs a workgroup, else 64 x 64
+// 128 x 128 tiles if they give at least half of the CUs a workgroup, else 64 x 64.
+// The big tile runs one workgroup per CU, in rounds of 256 tiles; a shape that spills a few
+// tiles into one more round (4544^3: 324 tiles, two rounds, 87 TFLOP/s) is better served by the
+// small tile, which runs in rounds of 512 at about 0.95 of the big tile's rate: the small tile
+// is taken when rounds_128 * 32768 / 0.95 < rounds_256 * 65536.
 constexpr uint32_t FD_MIN_TILES_256 = 256, FD_MIN_TILES_128 = 128;
+
+uint32_t pick_tile(uint32_t m, uint32_t n) {
+  const uint64_t t256 = (uint64_t)((m + 255u) / 256u) * ((n + 255u) / 256u);
+  const uint64_t t128 = (uint64_t)((m + 127u) / 128u) * ((n + 127u) / 128u);
+  if (t256 >= FD_MIN_TILES_256) {
+    const uint64_t rounds256 = (t256 + 255u) / 256u, rounds128 = (t128 + 511u) / 512u;
+    return rounds128 * 100u < rounds256 * 190u ? 128u : 256u;
+  }
+  return t128 >= FD_MIN_TILES_128 ? 128u : 64u;
+}
 
 Geometry geometry(uint32_t m, uint32_t n, uint32_t k, bool allow_dma = true) {
   Geometry g;
   g.dma = allow_dma && k % FD_BK == 0u && n % 4u == 0u;
   g.tile = 128u;
-  if (g.dma) {
-    if (((m + 255u) / 256u) * ((n + 255u) / 256u) >= FD_MIN_TILES_256) g.tile = 256u;
-    else if (((m + 127u) / 128u) * ((n + 127u) / 128u) < FD_MIN_TILES_128) g.tile = 64u;
-  }
+  if (g.dma) g.tile = pick_tile(m, n);
   g.tiles_m = (m + g.tile - 1u) / g.tile;
   g.tiles_n = (n + g.tile - 1u) / g.tile;
   g.total = g.tiles_m * g.tiles_n;

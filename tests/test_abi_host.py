@@ -304,7 +304,8 @@ def test_probe_functions_agree_with_checker_formulas():
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), n
     for m, n, k in ((1, 1, 1), (128, 128, 16), (129, 257, 17), (256, 256, 256), (4096, 4096, 4096),
                     (32768, 32768, 32768), (1000, 3000, 50), (1024, 1024, 1024), (1408, 1536, 64), (1408, 1408, 64),
-                    (1000, 3000, 48), (1000, 3002, 48), (2816, 2816, 64), (4096, 4096, 64), (4096, 3840, 64), (8192, 8192, 16)):
+                    (1000, 3000, 48), (1000, 3002, 48), (2816, 2816, 64), (4096, 4096, 64), (4096, 3840, 64), (8192, 8192, 16),
+                    (4544, 4544, 64), (6528, 6528, 16), (7552, 7552, 16), (5504, 5504, 32), (4096, 4100, 32)):
         mem, grid, block = mgb.probe_of(mgb.mgb_gemm_f32_probe, m, n, k)
         oracle.lib().orc_gemm_f32_probe(C.c_uint64(m), C.c_uint64(n), C.c_uint64(k), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (m, n, k)

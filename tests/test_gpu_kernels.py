@@ -118,8 +118,9 @@ def run_gemm_f32(a, b):
                                    (1, 4, 16), (64, 64, 16), (200, 132, 48), (1000, 1004, 160),
                                    # ... and 128 x 128 tiles (at least 128 of them), ragged and full
                                    (1408, 1540, 64), (1500, 1412, 112), (2048, 1024, 256),
-                                   # ... and 256 x 256 tiles (at least 256 of them)
-                                   (4096, 4100, 32), (4000, 4352, 48)])
+                                   # ... and 256 x 256 tiles (exactly one round of 256 of them, ragged); with a
+                                   # few tiles more than a round the 128 x 128 kernel is taken (the last two)
+                                   (3900, 4092, 32), (4000, 4096, 48), (4096, 4100, 32), (4000, 4352, 48)])
 def test_gemm_f32_componentwise_error(m, n, k):
     a, b = W.gemm_operands_f32(m * 7 + k, m, n, k)
     got = run_gemm_f32(a, b)
