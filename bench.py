@@ -290,6 +290,15 @@ def main():
             alone.append(sum(vals) / len(vals))
         out["alone_back_to_back_gpu_ms"] = {k: round(min(a for a, t in zip(alone, tasks) if t.spec.kind == k), 4)
                                             for k in kinds}
+        # the dominant kernel's own speed: the same figure as `roofline`, from the back-to-back launches
+        # (the timed region above has idle gaps between arrivals, and the clocks ramp after each)
+        da = [(a, t) for a, t in zip(alone, tasks) if t.kernel_name == dominant]
+        if da:
+            bound, peak, unit = peaks[dominant]
+            work = sum((t.alg_bytes / 1e9 if bound == "hbm" else t.alg_flops / 1e12) for _, t in da)
+            ach = work / (sum(a for a, _ in da) / 1e3)
+            out["roofline_back_to_back"] = dict(kernel=dominant, bound=bound, achieved=round(ach, 2), peak=peak,
+                                                unit=unit, frac=round(ach / peak, 4))
         out["speedup_vs_serialised"] = dict(
             throughput=round(value / out["serialised_gpu"]["tasks_per_s"], 4),
             turnaround=round(out["serialised_gpu"]["mean_turnaround_ms"] / mean_turn, 4))
@@ -306,6 +315,10 @@ def main():
                                tasks_per_s_min_max=[round(min(x["tasks_per_s"] for x in b), 1), round(max(x["tasks_per_s"] for x in b), 1)],
                                serialised_tasks_per_s=round(med(bs, "tasks_per_s"), 2),
                                serialised_mean_turnaround_ms=round(med(bs, "mean_turnaround_ms"), 3))
+        # what the co-run sustains as a whole: the tasks' algorithmic HBM bytes and flops over the makespan
+        mk = 1e-3 * med(b, "makespan_ms")
+        out["batch_t0"]["corun_algorithmic_hbm_gbs"] = round(sum(t.alg_bytes for t in tasks) / mk / 1e9, 1)
+        out["batch_t0"]["corun_tflops"] = round(sum(t.alg_flops for t in tasks) / mk / 1e12, 2)
         # the other policies on the same mix: Alg. 3 analogue (overlapping masks), FIFO queue,
         # HARD with one workgroup per CU as the residency limit ("spread": a task gets as many
         # CUs as it has workgroups, so only tasks that cannot fill the device share it), and the
