@@ -358,11 +358,11 @@ int mgb_client_probe(mgb_client* c, uint64_t task_id, uint64_t mem_bytes, mgb_di
 
 // A connection carries one request at a time, and a wait for admission ends only when some task
 // is completed - possibly by another thread of this process, over this connection.  The wait
-// therefore goes to the server in slices of 20 ms and gives the connection up between them (a
+// therefore goes to the server in slices of 2 ms and gives the connection up between them (a
 // task admitted between two slices is found admitted by the next one at once).
 int mgb_client_wait(mgb_client* c, uint64_t ticket, int64_t timeout_ns, mgb_placement* out) {
   if (!c || !out) return MGB_E_INVAL;
-  const int64_t slice = 20 * 1000 * 1000;
+  const int64_t slice = 2 * 1000 * 1000;
   int64_t left = timeout_ns;
   for (;;) {
     const int64_t step = (timeout_ns < 0 || left > slice) ? slice : left;
