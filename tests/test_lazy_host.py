@@ -389,3 +389,28 @@ def test_copy_back_of_a_window_of_an_unbound_object():
     want[30:38] = 9
     assert np.array_equal(got, want)
     assert z.free(a) == 0 and z.destroy() == 0 and s.destroy() == 0
+
+
+def test_allocation_failure_after_admission_rolls_the_ledger_back():
+    # the task is admitted (the cap allows it), then binding its second object fails in the
+    # allocator: what was bound is released, the ticket completed, the ledger whole again
+    cap = 1 << 41
+    s = mgb.Sched(backend=mgb.MGB_BACKEND_NULL, granule_cus=8, mem_cap_bytes=cap)
+    z = mgb.Lazy(s)
+    rc, small = z.malloc(1000)
+    rc, huge = z.malloc((1 << 40) - 1)                   # no host gives this to the null backend
+    src = np.arange(250, dtype=np.float32)
+    assert z.memcpy_h2d(small, src.ctypes.data, 1000) == 0
+    rc, real, pl = z.launch_prepare(1, [small, huge], (1, 1, 1), (64, 1, 1))
+    if rc == 0:
+        pytest.skip("the host handed out a terabyte of address space")
+    assert rc == mgb.MGB_E_BACKEND
+    st, zs = s.stats(), z.stats()
+    assert (st.free_bytes, st.n_running, st.n_waiting) == (cap, 0, 0)
+    assert (zs.n_bound, zs.n_tasks, zs.n_objects) == (0, 0, 2)
+    # the objects are still there, unbound, with their recorded writes: a smaller launch works
+    rc, real, pl = z.launch_prepare(2, [small], (1, 1, 1), (64, 1, 1))
+    assert rc == 0 and np.array_equal(_f32(_real_view(real[0], 1000), 250), src)
+    assert z.free(small) == 0 and z.free(huge) == 0 and z.destroy() == 0
+    assert_trace_matches_replay(s.desc, s.trace())
+    assert s.destroy() == 0
