@@ -177,14 +177,16 @@ uint32_t plan_launches(uint32_t iters, uint32_t* plan, uint32_t cap) {
   }
   if (n % 2u != iters % 2u) {
     // split one launch of >= 2 sweeps in two (exists: otherwise every launch is one sweep and
-    // the parities already agree)
-    for (uint32_t i = n; i-- > 0u;)
-      if (plan[i] >= 2u && n < cap) {
-        const uint32_t a = plan[i] / 2u;
-        plan[n++] = plan[i] - a;
-        plan[i] = a;
-        break;
-      }
+    // the parities already agree); the largest one, because two launches of two sweeps cost less
+    // than one of four plus two of one
+    uint32_t pick = n;
+    for (uint32_t i = 0; i < n; ++i)
+      if (plan[i] >= 2u && (pick == n || plan[i] > plan[pick])) pick = i;
+    if (pick < n && n < cap) {
+      const uint32_t a = plan[pick] / 2u;
+      plan[n++] = plan[pick] - a;
+      plan[pick] = a;
+    }
   }
   return n;
 }
