@@ -177,7 +177,7 @@ uint64_t orc_gemm_bf16_residency(uint64_t m, uint64_t n, uint64_t k) {
   }
   return 2;
 }
-//   conv: ring of (pixels + channels) x 32 bf16 x 4 stages (x 64 bf16 for the depth-split tiles); first-layer kernel: 3 strips of 776 bf16 +
+//   conv: ring of (pixels + channels) x 32 bf16 x 4 stages (x 64 bf16 for the depth-split tiles); first-layer kernel: 3 strips of 260 pixels padded to 4 bf16 +
 //   256 x c_out' bf16 of output staging (c_out' = c_out rounded up to 32); register-staged: 2.
 uint64_t orc_conv3x3_residency(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, uint64_t c_out,
                                uint64_t stride) {
@@ -189,7 +189,7 @@ uint64_t orc_conv3x3_residency(uint64_t batch, uint64_t h, uint64_t w, uint64_t 
     return (160 * 1024) / (4 * (tp + tc) * bk * 2);
   }
   if (c_in == 3 && stride == 1 && c_out % 8 == 0 && c_out <= 64)
-    return (160 * 1024) / (3 * 776 * 2 + 256 * ceil_div(c_out, 32) * 32 * 2);
+    return (160 * 1024) / (3 * 260 * 8 + 256 * ceil_div(c_out, 32) * 32 * 2);
   return 2;
 }
 

@@ -643,18 +643,21 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(const float* __r
 
 // ---- 3-channel first layer (c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64) ------------------
 //
-// Depth 27: two MFMA steps, the kernel is bound by writing its output (c_out / 3 times the
-// input).  A workgroup owns 256 consecutive output pixels (n, oh, ow flattened).  With stride 1
-// the input pixel of tap (r, s) is the output pixel's flattened index + (r-1)*W + (s-1), so the
-// three input strips [first - 1 + (r-1)*W, + 258 pixels) hold every operand; they are copied to
-// LDS once (zeros outside the tensor), and every lane assembles its pixel fragment from 2-byte
-// LDS reads, with the taps that fall outside the image masked to zero.  The results are
-// rounded, transposed through LDS and written as 16 bytes per lane, 4 KiB contiguous per wave.
-constexpr uint32_t C3_PIX = 256, C3_STRIP = 776;      // 258 pixels x 3 channels, padded to a multiple of 8
+// Depth 27: the kernel is bound by writing its output (c_out / 3 times the input).  A workgroup
+// owns 256 consecutive output pixels (n, oh, ow flattened).  With stride 1 the input pixel of tap
+// (r, s) is the output pixel's flattened index + (r-1)*W + (s-1), so the three input strips
+// [first - 1 + (r-1)*W, + 260 pixels) hold every operand; they are copied to LDS once, each pixel
+// padded to four channels (8 bytes, zeros outside the tensor).  The depth is laid out as
+// (r, s, c) with s and c padded to 4: 16 per filter row, one MFMA step per row, and a lane's
+// eight operands of a step are two adjacent padded pixels = 16 contiguous, 8-byte aligned bytes
+// of LDS (one two-address read), with the taps that fall outside the image masked to zero.  The
+// padding positions meet zero weights.  The results are rounded, transposed through LDS and
+// written as 16 bytes per lane, 4 KiB contiguous per wave.
+constexpr uint32_t C3_PIX = 256, C3_STRIP_PIX = 260;   // 256 + 2 halo pixels + the padded tap s = 3
 
 template <uint32_t NJ>    // 32-channel blocks: c_out <= 32 * NJ
 __global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
-  __shared__ __attribute__((aligned(16))) uint16_t strip[3u * C3_STRIP];
+  __shared__ __attribute__((aligned(16))) uint2 strip[3u * C3_STRIP_PIX];
   __shared__ __attribute__((aligned(16))) uint16_t outs[C3_PIX * 32u * NJ];
   const uint32_t bm = blockIdx.x * C3_PIX;
   if (bm >= a.pixels) return;
@@ -662,32 +665,32 @@ __global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
   const uint32_t l32 = lane & 31u, lhi = lane >> 5;
 
   // input strips (H = Ho, W = Wo with stride 1: input and output pixels share their flattened index)
-  const int64_t total = (int64_t)a.pixels * 3;
-#pragma unroll
-  for (uint32_t r = 0; r < 3; ++r) {
-    const int64_t first = ((int64_t)bm - 1 + ((int64_t)r - 1) * a.W) * 3;
-    for (uint32_t e = tid; e < C3_STRIP; e += 256u) {
-      const int64_t g = first + e;
-      strip[r * C3_STRIP + e] = (g >= 0 && g < total && e < 774u) ? a.x[g] : (uint16_t)0;
-    }
+  const int64_t total = (int64_t)a.pixels;
+  for (uint32_t idx = tid; idx < 3u * C3_STRIP_PIX; idx += 256u) {
+    const uint32_t r = idx / C3_STRIP_PIX, e = idx - r * C3_STRIP_PIX;
+    const int64_t g = (int64_t)bm - 1 + ((int64_t)r - 1) * a.W + e;
+    const bool ok = g >= 0 && g < total;
+    const int64_t gc = ok ? g : 0;
+    const uint32_t c0 = a.x[gc * 3], c1 = a.x[gc * 3 + 1], c2 = a.x[gc * 3 + 2];
+    strip[idx] = ok ? make_uint2(c0 | (c1 << 16), c2) : make_uint2(0u, 0u);
   }
 
-  // weight fragments: channel 32j + l32, k = 16*ks + 8*lhi + e
-  u32x4 fw[2][NJ];
+  // weight fragments of filter row r: channel 32j + l32, operand e = (s, c) = (2*lhi + e/4, e%4)
+  u32x4 fw[3][NJ];
 #pragma unroll
-  for (uint32_t ks = 0; ks < 2; ++ks)
+  for (uint32_t r = 0; r < 3; ++r)
 #pragma unroll
     for (uint32_t j = 0; j < NJ; ++j) {
       const uint32_t ch = 32u * j + l32;
       uint32_t wd[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
       for (uint32_t e = 0; e < 8; ++e) {
-        const uint32_t k = 16u * ks + 8u * lhi + e;
-        const uint32_t ok = (uint32_t)(k < 27u) & (uint32_t)(ch < a.K);
-        const uint32_t v = a.w[ok ? ch * 27u + k : 0u];
+        const uint32_t t = 2u * lhi + (e >> 2), c = e & 3u;
+        const uint32_t ok = (uint32_t)(t < 3u) & (uint32_t)(c < 3u) & (uint32_t)(ch < a.K);
+        const uint32_t v = a.w[ok ? ch * 27u + r * 9u + t * 3u + c : 0u];
         wd[e >> 1] |= (ok ? v : 0u) << (16u * (e & 1u));
       }
-      fw[ks][j] = u32x4{wd[0], wd[1], wd[2], wd[3]};
+      fw[r][j] = u32x4{wd[0], wd[1], wd[2], wd[3]};
     }
   __syncthreads();
 
@@ -710,22 +713,17 @@ __global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 #pragma unroll
-    for (uint32_t ks = 0; ks < 2; ++ks) {
-      uint32_t wd[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-      for (uint32_t e = 0; e < 8; ++e) {
-        const uint32_t k = 16u * ks + 8u * lhi + e;            // = 9r + 3s + c
-        const uint32_t tap = (k * 11u) >> 5;                   // k / 3
-        const uint32_t ka = min(k, 26u);                       // depth padding reads a valid address and is masked
-        const uint32_t r = (ka * 57u) >> 9;                    // ka / 9
-        const uint32_t ok = (taps >> tap) & 1u;                // bits 9, 10 are clear: k >= 27 gives zero
-        const uint32_t v = strip[r * C3_STRIP + pl * 3u + ka - 9u * r];
-        wd[e >> 1] |= (ok ? v : 0u) << (16u * (e & 1u));
-      }
-      const bf16x8 fp = as_bf16x8(u32x4{wd[0], wd[1], wd[2], wd[3]});
+    for (uint32_t r = 0; r < 3; ++r) {
+      // taps s = 2*lhi and 2*lhi + 1 of row r: input pixels pl + s - 1 = strip entries pl + s
+      const uint2 d0 = strip[r * C3_STRIP_PIX + pl + 2u * lhi];
+      const uint2 d1 = strip[r * C3_STRIP_PIX + pl + 2u * lhi + 1u];
+      const uint32_t ok0 = (taps >> (3u * r + 2u * lhi)) & 1u;
+      const uint32_t ok1 = lhi ? 0u : (taps >> (3u * r + 1u)) & 1u;       // s = 3 is padding
+      const uint32_t m0 = 0u - ok0, m1 = 0u - ok1;
+      const bf16x8 fp = as_bf16x8(u32x4{d0.x & m0, d0.y & m0, d1.x & m1, d1.y & m1});
 #pragma unroll
       for (uint32_t j = 0; j < NJ; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fw[ks][j]), fp, acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fw[r][j]), fp, acc[i][j], 0, 0, 0);
     }
   }
 
@@ -975,7 +973,7 @@ static uint32_t residency_of(const Geometry& g, uint32_t c_out) {
     case PATH_DMA_256x64: return 2u;                  // 80 KiB ring
     case PATH_DMA_64x64: return 5u;                   // 32 KiB ring
     case PATH_DMA_KSPLIT: return 2u;                  // 64 KiB ring
-    case PATH_C3: return c_out <= 32u ? 7u : 4u;      // 21 / 37 KiB of strips and output staging
+    case PATH_C3: return c_out <= 32u ? 7u : 4u;      // 22 / 38 KiB of strips and output staging
     case PATH_GENERIC: return 2u;                     // 162 - 244 registers per lane
   }
   return 0u;
