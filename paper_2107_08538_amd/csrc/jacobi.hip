@@ -12,7 +12,10 @@
 // grid is a true boundary and costs no overlap.  No LDS and no barriers: waves
 // are independent.  Eight output rows per window keep the register file small
 // enough for three waves per SIMD, which measured faster than taller windows
-// with less overlap (the kernel is latency-, not bandwidth-limited once fused).
+// with less overlap: once fused the kernel is bound by its vector instructions
+// (about 1200 per wave and launch at T = 4, the four sweeps' adds and
+// multiplies), not by bandwidth.  A quarter of them were the selects that keep
+// the grid's ring fixed; only the windows that touch the ring execute those.
 //
 // The arithmetic of every update is exactly v = 0.25f * ((N + S) + (W + E)):
 // two roundings of pair sums, one rounding of their sum, an exact scaling, no
@@ -53,10 +56,44 @@ __device__ __forceinline__ bool window_of_wave(uint32_t tiles_c, uint32_t tiles_
   return true;
 }
 
+// T sweeps over the window held in `cur` (register rows; row i is grid row g0 + i).  EDGE: the
+// window contains cells of the grid's fixed ring, which keep their value.
+template <uint32_t T, bool EDGE>
+__device__ __forceinline__ void run_sweeps(float4 (&cur)[JB_ROWS + 2u * T], int32_t g0, uint32_t n,
+                                           bool first_col, bool last_col) {
+  constexpr uint32_t NR = JB_ROWS + 2u * T;
+#pragma unroll
+  for (uint32_t s = 1; s <= T; ++s) {
+    float4 north = cur[s - 1u];                           // value of the row above before this sweep
+#pragma unroll
+    for (uint32_t i = s; i + s < NR; ++i) {
+      const float4 c = cur[i];
+      const float4 south = cur[i + 1u];
+      const float west = __shfl_up(c.w, 1);
+      const float east = __shfl_down(c.x, 1);
+      float4 o;
+      o.x = 0.25f * ((north.x + south.x) + (west + c.y));
+      o.y = 0.25f * ((north.y + south.y) + (c.x + c.z));
+      o.z = 0.25f * ((north.z + south.z) + (c.y + c.w));
+      o.w = 0.25f * ((north.w + south.w) + (c.z + east));
+      if (EDGE) {
+        if (first_col) o.x = c.x;                         // the ring keeps its value
+        if (last_col) o.w = c.w;
+        const int32_t g = g0 + (int32_t)i;
+        const bool interior_row = g >= 1 && g <= (int32_t)n - 2;
+        cur[i] = interior_row ? o : c;
+      } else {
+        cur[i] = o;
+      }
+      north = c;
+    }
+  }
+}
+
 // n % 4 == 0: rows are 16-byte aligned, every lane's four columns are either
 // all inside the grid or all outside.
 template <uint32_t T>
-__global__ __launch_bounds__(JB_THREADS) void jacobi_sweeps(const float* __restrict__ u,
+__global__ __launch_bounds__(JB_THREADS, 3) void jacobi_sweeps(const float* __restrict__ u,
                                                            float* __restrict__ v, uint32_t n,
                                                            uint32_t tiles_c, uint32_t tiles_r) {
   constexpr uint32_t NR = JB_ROWS + 2u * T;               // rows held in registers
@@ -78,28 +115,11 @@ __global__ __launch_bounds__(JB_THREADS) void jacobi_sweeps(const float* __restr
     cur[i] = *reinterpret_cast<const float4*>(u + (size_t)gc * n + c0);
   }
 
-#pragma unroll
-  for (uint32_t s = 1; s <= T; ++s) {
-    float4 north = cur[s - 1u];                           // value of the row above before this sweep
-#pragma unroll
-    for (uint32_t i = s; i + s < NR; ++i) {
-      const float4 c = cur[i];
-      const float4 south = cur[i + 1u];
-      const float west = __shfl_up(c.w, 1);
-      const float east = __shfl_down(c.x, 1);
-      float4 o;
-      o.x = 0.25f * ((north.x + south.x) + (west + c.y));
-      o.y = 0.25f * ((north.y + south.y) + (c.x + c.z));
-      o.z = 0.25f * ((north.z + south.z) + (c.y + c.w));
-      o.w = 0.25f * ((north.w + south.w) + (c.z + east));
-      if (first_col) o.x = c.x;                           // the ring keeps its value
-      if (last_col) o.w = c.w;
-      const int32_t g = g0 + (int32_t)i;
-      const bool interior_row = g >= 1 && g <= (int32_t)n - 2;
-      cur[i] = interior_row ? o : c;
-      north = c;
-    }
-  }
+  // Only windows that touch the grid's ring need the per-cell selects that keep the ring fixed;
+  // every other window (most of them) runs the plain update, a quarter fewer instructions.
+  const bool edge = g0 < 1 || g0 + (int32_t)NR - 1 > (int32_t)n - 2 || tc == 0u || w0 + JB_WIN >= n;
+  if (edge) run_sweeps<T, true>(cur, g0, n, first_col, last_col);
+  else run_sweeps<T, false>(cur, g0, n, first_col, last_col);
 
   // store what is still exact: not the four columns next to a window edge (an edge that is
   // the grid's own boundary loses nothing), rows JB_ROWS of this window that are interior
