@@ -32,6 +32,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <chrono>
 #include <mutex>
 #include <type_traits>
 
@@ -430,7 +431,20 @@ static int bfs_run(void* stream, const int32_t* row_ptr, const int32_t* col_idx,
     int rc = mgb_check_launch("bfs_level");
     if (rc != MGB_OK) return rc;
     hipError_t e = hipMemcpyAsync(host_counts, w.ctrl, (nb + 1u) * sizeof(uint32_t), hipMemcpyDeviceToHost, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    // The traversal is a few hundred microseconds of GPU work: poll for the counters instead of
+    // sleeping on the stream (a blocking wait wakes up tens of microseconds late), and fall back
+    // to the blocking wait if they are not there after a few milliseconds (a deep or huge graph).
+    if (e == hipSuccess) {
+      const auto t0 = std::chrono::steady_clock::now();
+      for (;;) {
+        e = hipStreamQuery(st);
+        if (e != hipErrorNotReady) break;
+        if (std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(3)) {
+          e = hipStreamSynchronize(st);
+          break;
+        }
+      }
+    }
     if (e != hipSuccess) {
       mgb_internal_set_error("bfs counter read-back", e);
       return MGB_E_BACKEND;
