@@ -444,6 +444,7 @@ static int bfs_run(void* stream, const int32_t* row_ptr, const int32_t* col_idx,
           break;
         }
       }
+      (void)hipGetLastError();     // "not ready" is an answer, not an error to find at the next launch check
     }
     if (e != hipSuccess) {
       mgb_internal_set_error("bfs counter read-back", e);
