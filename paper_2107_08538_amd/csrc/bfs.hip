@@ -19,14 +19,15 @@
 //     the probes - the bulk of the work - never leave the CU.  Top-down
 //     levels set the bits of what they discover with one more atomic each;
 //     bottom-up levels own whole bitmap words and store them.
-// Either way the new frontier is appended to the next queue with one atomic
-// per wave: ballot of the winners, the leader reserves popcount slots, each
-// winner writes at its rank among the winners.
+// Either way the new frontier is staged per wave in LDS (ballot of the winners,
+// each winner writes at its rank among them) and appended to the next queue
+// with one atomic on the queue tail per workgroup, or per full staging buffer.
 //
 // The host does not know the depth in advance: it enqueues a batch of level
 // kernels whose grids do not depend on the frontier size (the kernels read the
 // size from device memory and exit at once on an empty frontier), then reads
-// the per-level counters back once per batch.
+// the per-level counters back once per batch (8 levels, then 16, then 32 at a
+// time; the read-back polls the stream rather than sleeping on it).
 #include "../../include/mgb.h"
 #include "launch_util.h"
 
