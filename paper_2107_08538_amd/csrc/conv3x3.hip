@@ -1,6 +1,12 @@
 // 3x3 convolution + ReLU (padding 1, stride 1 or 2) as an implicit GEMM on the
 // bf16 matrix cores, and a chain of such layers run as one task.
 //
+// Kernels (each described where it is defined): conv3x3_dma_kernel (c_in % 32 == 0, c_out % 8 == 0:
+// global -> LDS DMA ring, tiles 128 x 128 / 256 x 64 / 64 x 64), conv3x3_dma_ksplit_kernel
+// (c_in % 64 == 0, layers with few tiles: the depth split over the waves of a workgroup and,
+// inside a chain, over workgroups, with conv_split_reduce_kernel), conv3x3_c3_kernel (the
+// 3-channel first layer) and the register-staged conv3x3_kernel for every other shape:
+//
 // GEMM view: rows = output pixels (n, oh, ow), columns = output channels,
 // depth = (r, s, c) = 9 * c_in.  Activations are N,H,W,C and weights K,3,3,C,
 // so for a fixed filter tap the channel run is contiguous for both operands:
