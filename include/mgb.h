@@ -415,6 +415,18 @@ int mgb_cu_trace_enqueue(void* stream, uint32_t* out, uint32_t n_blocks);
  * hardware traffic counters.                                                */
 int mgb_copy_enqueue(void* stream, void* dst, const void* src, uint64_t bytes);
 
+/* Diagnostic: n_blocks workgroups of four waves run `iters` rounds of 16
+ * independent matrix instructions on registers (v_mfma_f32_32x32x2_f32, or
+ * v_mfma_f32_32x32x16_bf16 if bf16 != 0) and store one float per thread to
+ * out (device, n_blocks * 256 floats).  The operands are a fixed hash of
+ * (accumulator block, lane, element) in [-1, 1), so that the matrix units see
+ * changing full-width mantissas as in a GEMM on real data (constant operands
+ * draw less power and clock higher).  *flops (host, may be NULL) receives the
+ * flop count of the launch.  The rate it reaches is the measured ceiling of the
+ * MFMA-bound kernels on this part.  n_blocks <= 65536, iters in [1, 2^24].     */
+int mgb_mfma_loop_enqueue(void* stream, uint32_t bf16, uint32_t n_blocks, uint32_t iters, float* out,
+                          double* flops);
+
 #ifdef __cplusplus
 }
 #endif

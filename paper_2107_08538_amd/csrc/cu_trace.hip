@@ -4,6 +4,9 @@
 //    are disjoint sets of physical CUs.
 //  * stream_copy: a plain 16-byte-per-lane device copy of known size; the measured ceiling the
 //    HBM-bound kernels are compared with, and the calibration point for traffic counters.
+//  * mfma_loop: matrix instructions on registers only, 16 independent accumulator blocks per
+//    wave, one wave per SIMD on every CU; the rate the matrix cores sustain on this part (clocks
+//    included) when nothing else is in the way, the measured ceiling of the MFMA-bound kernels.
 #include "../../include/mgb.h"
 #include "launch_util.h"
 
@@ -31,7 +34,62 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(uint4* __restrict__ ds
   for (size_t i = (size_t)blockIdx.x * 256u + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// Operand values of the MFMA loop: a fixed integer hash of (block, lane, element) mapped to
+// [-1, 1) in steps of 2^-23, so that successive instructions see unrelated full-width mantissas
+// as they do in a GEMM on real data (constant operands draw less power and clock higher).
+__device__ __forceinline__ float loop_operand(uint32_t b, uint32_t lane, uint32_t e) {
+  uint32_t h = lane * 2654435761u + b * 40503u + e * 9973u + 12345u;
+  h ^= h >> 15;
+  h *= 0x2c1b3c6du;
+  h ^= h >> 12;
+  return (float)(h >> 8) * (1.0f / 8388608.0f) - 1.0f;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256, 1) void mfma_loop_kernel(float* __restrict__ out, uint32_t iters) {
+  f32x16 acc[16];
+#pragma unroll
+  for (int b = 0; b < 16; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+  const uint32_t lane = threadIdx.x & 63u;
+  float x[16];
+  bf16x8 hx[16];
+#pragma unroll
+  for (int b = 0; b < 16; ++b) {
+    x[b] = loop_operand(b, lane, 0);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) hx[b][e] = (__bf16)loop_operand(b, lane, e);
+  }
+  for (uint32_t i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int b = 0; b < 16; ++b) {
+      if (BF16) acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hx[b], hx[b], acc[b], 0, 0, 0);
+      else acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(x[b], x[b], acc[b], 0, 0, 0);
+    }
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int b = 0; b < 16; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += acc[b][r];
+  out[(size_t)blockIdx.x * 256u + threadIdx.x] = sum;      // keeps the loop alive
+}
+
 }  // namespace
+
+extern "C" int mgb_mfma_loop_enqueue(void* stream, uint32_t bf16, uint32_t n_blocks, uint32_t iters,
+                                     float* out, double* flops) {
+  if (!out || n_blocks == 0u || n_blocks > 65536u || iters == 0u || iters > (1u << 24)) return MGB_E_INVAL;
+  // per wave and iteration: 16 blocks of 32 x 32 x (16 | 2) multiply-adds
+  if (flops) *flops = (double)n_blocks * 4.0 * (double)iters * 16.0 * 2.0 * 32.0 * 32.0 * (bf16 ? 16.0 : 2.0);
+  if (bf16) hipLaunchKernelGGL(mfma_loop_kernel<true>, dim3(n_blocks), dim3(256), 0, (hipStream_t)stream, out, iters);
+  else hipLaunchKernelGGL(mfma_loop_kernel<false>, dim3(n_blocks), dim3(256), 0, (hipStream_t)stream, out, iters);
+  return mgb_check_launch("mfma_loop_kernel");
+}
 
 extern "C" int mgb_cu_trace_enqueue(void* stream, uint32_t* out, uint32_t n_blocks) {
   if (!out || n_blocks == 0u || n_blocks > (1u << 20)) return MGB_E_INVAL;

@@ -225,3 +225,42 @@ def test_memory_pressure_queues_and_worst_wait_matches_replay():
     waits_lib = {int(r["task_id"]): int(r["cause_seq"]) - probe_seq[int(r["task_id"])] for r in admits}
     assert max(waits_lib.values()) > 0
     assert s.destroy() == 0
+
+
+def _loop_operand(b, lane, e):
+    h = (lane.astype(np.uint64) * 2654435761 + b * 40503 + e * 9973 + 12345) & 0xFFFFFFFF
+    h ^= h >> 15
+    h = (h * 0x2C1B3C6D) & 0xFFFFFFFF
+    h ^= h >> 12
+    return ((h >> 8).astype(np.float64) / 8388608.0 - 1.0).astype(np.float32)
+
+
+@pytest.mark.parametrize("bf16", [0, 1])
+def test_mfma_loop_diagnostic_sums_what_its_operands_give(bf16):
+    # block b multiplies the 32 x depth matrix A_b by its own transpose `iters` times; lane l holds row
+    # l % 32 and the depth indices of half l / 32 (one fp32 value, or eight bf16 values), all values a
+    # fixed hash of (b, l, element).  A wave's 64 stored floats add up to every entry of all 16 products.
+    n_blocks, iters, depth = 8, 5, (16 if bf16 else 2)
+    per_lane = depth // 2
+    out = torch.zeros(n_blocks * 256, dtype=torch.float32, device=DEV)
+    fl = C.c_double(0.0)
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    assert mgb.mgb_mfma_loop_enqueue(st, bf16, n_blocks, iters, P(out), C.byref(fl)) == 0
+    torch.cuda.synchronize()
+    assert fl.value == n_blocks * 4 * iters * 16 * 2 * 32 * 32 * depth
+    want = mag = 0.0
+    rows = np.arange(32)
+    for b in range(16):
+        a = np.empty((32, depth), dtype=np.float32)
+        for k in range(depth):
+            a[:, k] = _loop_operand(b, rows + 32 * (k // per_lane), k % per_lane)
+        if bf16:
+            a = torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
+        a = a.astype(np.float64)
+        want += iters * (a @ a.T).sum()
+        mag += iters * (np.abs(a) @ np.abs(a).T).sum()
+    got = out.cpu().numpy().astype(np.float64).reshape(n_blocks * 4, 64).sum(axis=1)
+    assert np.abs(got - want).max() <= 1e-5 * mag
+    assert mgb.mgb_mfma_loop_enqueue(st, bf16, 0, iters, P(out), None) == mgb.MGB_E_INVAL
+    assert mgb.mgb_mfma_loop_enqueue(st, bf16, n_blocks, 0, P(out), None) == mgb.MGB_E_INVAL
+    assert mgb.mgb_mfma_loop_enqueue(st, bf16, n_blocks, iters, None, None) == mgb.MGB_E_INVAL
