@@ -208,11 +208,11 @@ void orc_bfs_probe(uint64_t n, uint64_t m, uint64_t out[7]) {
   out[4] = 512; out[5] = 1; out[6] = 1;
 }
 // The level kernel keeps 29184 bytes of LDS for staging and, for graphs of up to 2^20 vertices,
-// one frontier bitmap; a workgroup is 8 waves.
+// one frontier bitmap; its 128 registers per lane leave room for two 8-wave workgroups per CU.
 uint64_t orc_bfs_residency(uint64_t n) {
   uint64_t lds = 29184 + (n <= (1ull << 20) ? bfs_bitmap_bytes(n) : 0);
-  uint64_t by_lds = (160 * 1024) / lds, by_waves = 32 / 8;
-  return by_lds < by_waves ? by_lds : by_waves;
+  uint64_t by_lds = (160 * 1024) / lds, by_regs = 2;
+  return by_lds < by_regs ? by_lds : by_regs;
 }
 
 }  // extern "C"

@@ -16,7 +16,10 @@
 //     Frontier membership is a bitmap (one bit per vertex, three of them in
 //     rotation: read / written / cleared by a level); for graphs of up to
 //     2^20 vertices every workgroup first copies it into LDS (128 KiB), so
-//     the probes - the bulk of the work - never leave the CU.  Top-down
+//     the probes - the bulk of the work - never leave the CU.  On the level
+//     where the frontier explodes (three quarters of a 256-vertex span still
+//     unvisited) the span's rows are read edge-parallel instead, as one
+//     contiguous piece of col_idx, and each vertex tests its row's bits.  Top-down
 //     levels set the bits of what they discover with one more atomic each;
 //     bottom-up levels own whole bitmap words and store them.
 // Either way the new frontier is staged per wave in LDS (ballot of the winners,
@@ -48,6 +51,11 @@ constexpr uint32_t BFS_BU_SPAN = 256;         // vertices a wave scans per botto
 constexpr uint32_t BFS_BU_UNROLL = 8;         // neighbours per unvisited vertex in flight (bottom-up)
 constexpr uint32_t BFS_LDS_BITS = 1u << 20;   // the frontier bitmap is kept in LDS up to this many vertices
 constexpr float BFS_TD_WEIGHT = 4.f;          // LDS bitmap: cost of a top-down edge (probe + claim) against reading one unvisited vertex's row
+struct __attribute__((packed, aligned(4))) Int4 { int32_t v[4]; };   // four consecutive column indices
+static_assert(BFS_BU_UNROLL % 4u == 0u, "neighbours are fetched four at a time");
+constexpr uint32_t BFS_DENSE_BITS = BFS_BU_SPAN * 32u;   // edges of a span read edge-parallel (one bit each in the list's LDS)
+constexpr uint32_t BFS_DENSE_BATCH = 16;      // loads per lane in flight on that path
+static_assert((BFS_DENSE_BITS / 64u) % BFS_DENSE_BATCH == 0u, "whole batches fit the bit array");
 constexpr uint32_t BFS_UNROLL = 4;            // edges per lane in flight (top-down)
 constexpr uint32_t BFS_STAGE = 512;           // per-wave LDS staging of discovered vertices
 
@@ -135,7 +143,7 @@ __device__ __forceinline__ void stage_append(Stage& st, bool won, int32_t v,
   st.count += k;
 }
 
-__global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restrict__ row_ptr,
+__global__ __launch_bounds__(BFS_THREADS, 2) void bfs_level(const int32_t* __restrict__ row_ptr,
                                                         const int32_t* __restrict__ col_idx,
                                                         int32_t* __restrict__ level,
                                                         const int32_t* __restrict__ q_in,
@@ -180,7 +188,7 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
   const bool bottom_up = in_lds ? BFS_TD_WEIGHT * td_edges_n > (float)unvisited * (float)n
                                 : td_edges_n * (float)n_in > (float)unvisited * (float)n * (float)n;
   // (bottom-up reads a vertex's stored edges as its in-edges: only right for a symmetric graph)
-  if (symmetric != 0u && bottom_up) {
+  if (symmetric != 0u && bottom_up && m_edges >= (int32_t)BFS_BU_UNROLL) {
     // Most vertices are already reached when this direction pays, so a wave first packs the
     // unvisited ones of its span into LDS (coalesced level reads, ballot ranks) and then works on
     // full lanes: one unvisited vertex per lane, eight of its neighbours in flight per step,
@@ -188,9 +196,19 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
     // (a handful of unvisited vertices do not pay for the copy: they probe the bitmap in memory)
     const bool copy = in_lds && (uint64_t)unvisited * 64u >= n;
     if (copy) {
-      const uint4* src = reinterpret_cast<const uint4*>(bm_in);
-      uint4* dst = reinterpret_cast<uint4*>(s_bitmap);
-      for (uint32_t i = threadIdx.x; i < words / 4u; i += BFS_THREADS) dst[i] = src[i];
+      typedef uint32_t Quad __attribute__((ext_vector_type(4)));
+      const Quad* src = reinterpret_cast<const Quad*>(bm_in);
+      Quad* dst = reinterpret_cast<Quad*>(s_bitmap);
+      // (eight loads in flight per lane: written as a plain loop the compiler waits for each
+      // load before its LDS store, sixteen memory round trips for the 128 KiB bitmap)
+      const uint32_t quads = words / 4u;          // > 0, a multiple of 16
+      for (uint32_t base = 0; base < quads; base += 8u * BFS_THREADS) {
+        Quad t[8];            // (lanes past the end copy the last quad once more: no branches)
+#pragma unroll
+        for (uint32_t k = 0; k < 8u; ++k) t[k] = src[min(base + k * BFS_THREADS + threadIdx.x, quads - 1u)];
+#pragma unroll
+        for (uint32_t k = 0; k < 8u; ++k) dst[min(base + k * BFS_THREADS + threadIdx.x, quads - 1u)] = t[k];
+      }
       __syncthreads();
     }
     // (two instantiations of the loop: a pointer that may be LDS or memory would turn every probe
@@ -199,7 +217,7 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
     // load under a per-lane condition becomes a branch, and the compiler then waits for every
     // load before it issues the next.
     int32_t* list = &s_list[wave][0];
-    const int32_t last_edge = m_edges - 1;         // m_edges > 0: bottom-up is never chosen for an empty graph
+    const int32_t last_block = m_edges - (int32_t)BFS_BU_UNROLL;   // >= 0: see the choice of direction
     // one round for the first NQ * 64 entries of the list: NQ vertices per lane, eight neighbours
     // of each in flight
     auto rounds = [&](auto lds_probe, auto nq_tag, uint32_t v0, uint32_t cnt) {
@@ -226,11 +244,20 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
 #pragma unroll
         for (uint32_t q = 0; q < NQ; ++q) any_open |= open[q];
         if (!__any(any_open)) break;
-        int32_t nb[NQ][BFS_BU_UNROLL];
+        // (16-byte loads that need only 4-byte alignment: a lane's eight neighbours are two memory
+        // instructions instead of eight, and it is the number of cache-line requests of these
+        // row-per-lane gathers, not their bytes, that bounds this loop)
+        int32_t nb[NQ][BFS_BU_UNROLL], b0[NQ];
 #pragma unroll
-        for (uint32_t q = 0; q < NQ; ++q)
+        for (uint32_t q = 0; q < NQ; ++q) {
+          b0[q] = min(e[q], last_block);
 #pragma unroll
-          for (uint32_t i = 0; i < BFS_BU_UNROLL; ++i) nb[q][i] = col_idx[min(e[q] + (int32_t)i, last_edge)];
+          for (uint32_t i = 0; i < BFS_BU_UNROLL; i += 4u) {
+            const Int4 four = *reinterpret_cast<const Int4*>(col_idx + b0[q] + (int32_t)i);
+#pragma unroll
+            for (uint32_t k = 0; k < 4u; ++k) nb[q][i + k] = four.v[k];
+          }
+        }
         uint32_t word[NQ][BFS_BU_UNROLL];
 #pragma unroll
         for (uint32_t q = 0; q < NQ; ++q)
@@ -242,7 +269,8 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
           uint32_t hit = 0u;
 #pragma unroll
           for (uint32_t i = 0; i < BFS_BU_UNROLL; ++i)
-            hit |= (word[q][i] >> ((uint32_t)nb[q][i] & 31u)) & (uint32_t)(e[q] + (int32_t)i < e1[q]);
+            hit |= (word[q][i] >> ((uint32_t)nb[q][i] & 31u)) &
+                   (uint32_t)(b0[q] + (int32_t)i >= e[q] && b0[q] + (int32_t)i < e1[q]);
           hit &= (uint32_t)open[q];
           e[q] += (int32_t)BFS_BU_UNROLL;
           found[q] = found[q] || hit != 0u;
@@ -260,25 +288,110 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
     };
     // (two instantiations per width: a pointer that may be LDS or memory would turn every probe
     // into a flat load)
+    // While most vertices are still unvisited (the level on which the frontier explodes) the
+    // rows of a span are one almost contiguous piece of col_idx.  A span of which at least three
+    // quarters are unvisited is then read edge-parallel: lane l takes edges l, 64 + l, ... of the
+    // piece (coalesced, no dependent rounds, up to 16 loads in flight), a ballot per load leaves
+    // one bit per edge in LDS (the list's storage: 8192 bits), and each unvisited vertex tests
+    // the bits of its own row.  Rows of visited vertices are read too and their bits ignored.
+    const bool dense_level = (uint64_t)unvisited * 4u >= (uint64_t)n * 3u;
     auto scan = [&](auto lds_probe) {
+    constexpr bool LDS_PROBE = decltype(lds_probe)::value;
     constexpr uint32_t Q = BFS_BU_SPAN / 64u;
     for (uint32_t v0 = gwave * BFS_BU_SPAN; v0 < n; v0 += total_waves * BFS_BU_SPAN) {
-      int32_t lv[Q];
+      int32_t lv[Q], row0[Q], row1[Q];
 #pragma unroll
       for (uint32_t u = 0; u < Q; ++u) lv[u] = level[min(v0 + 64u * u + lane, n - 1u)];
-      uint32_t cnt = 0;
 #pragma unroll
       for (uint32_t u = 0; u < Q; ++u) {
-        const bool unv = lv[u] < 0 && v0 + 64u * u + lane < n;
-        const uint64_t mask = __ballot(unv);
-        if (unv) list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = (int32_t)(v0 + 64u * u + lane);
-        cnt += (uint32_t)__popcll(mask);
+        row0[u] = row1[u] = 0;
+        if (dense_level) {                 // uniform over the grid
+          const uint32_t v = min(v0 + 64u * u + lane, n - 1u);
+          row0[u] = row_ptr[v];
+          row1[u] = row_ptr[v + 1u];
+        }
       }
-      if (lane < BFS_BU_SPAN / 32u) s_out[wave][lane] = 0u;
-      __builtin_amdgcn_wave_barrier();
-      if (cnt > 128u) rounds(lds_probe, std::integral_constant<uint32_t, 4>{}, v0, cnt);
-      else if (cnt > 64u) rounds(lds_probe, std::integral_constant<uint32_t, 2>{}, v0, cnt);
-      else if (cnt > 0u) rounds(lds_probe, std::integral_constant<uint32_t, 1>{}, v0, cnt);
+      const int32_t piece_end = dense_level ? row_ptr[min(v0 + BFS_BU_SPAN, n)] : 0;
+      uint32_t cnt = 0;
+      bool unv[Q];
+      uint64_t unv_mask[Q];
+#pragma unroll
+      for (uint32_t u = 0; u < Q; ++u) {
+        unv[u] = lv[u] < 0 && v0 + 64u * u + lane < n;
+        unv_mask[u] = __ballot(unv[u]);
+        cnt += (uint32_t)__popcll(unv_mask[u]);
+      }
+      bool dense = false;
+      int32_t bit0 = 0;                    // the piece of col_idx: [bit0, piece_end), bit0 a multiple of 64
+      if (dense_level && cnt * 4u >= BFS_BU_SPAN * 3u) {
+        bit0 = __builtin_amdgcn_readfirstlane(row0[0]) & ~63;
+        dense = piece_end - bit0 <= (int32_t)BFS_DENSE_BITS;
+      }
+      if (dense) {
+        uint32_t* hits = reinterpret_cast<uint32_t*>(list);
+        const uint32_t loads = (uint32_t)(piece_end - bit0 + 63) >> 6;      // <= BFS_DENSE_BITS / 64
+        // (the next batch's loads are issued before this batch is probed)
+        int32_t nb[BFS_DENSE_BATCH], ahead[BFS_DENSE_BATCH];
+#pragma unroll
+        for (uint32_t i = 0; i < BFS_DENSE_BATCH; ++i)
+          ahead[i] = col_idx[min((uint32_t)bit0 + i * 64u + lane, (uint32_t)m_edges - 1u)];
+        for (uint32_t r0 = 0; r0 < loads; r0 += BFS_DENSE_BATCH) {
+          uint32_t word[BFS_DENSE_BATCH];
+#pragma unroll
+          for (uint32_t i = 0; i < BFS_DENSE_BATCH; ++i) nb[i] = ahead[i];
+#pragma unroll
+          for (uint32_t i = 0; i < BFS_DENSE_BATCH; ++i)
+            ahead[i] = col_idx[min((uint32_t)bit0 + (r0 + BFS_DENSE_BATCH + i) * 64u + lane, (uint32_t)m_edges - 1u)];
+#pragma unroll
+          for (uint32_t i = 0; i < BFS_DENSE_BATCH; ++i)
+            word[i] = LDS_PROBE ? s_bitmap[(uint32_t)nb[i] >> 5] : bm_in[(uint32_t)nb[i] >> 5];
+#pragma unroll
+          for (uint32_t i = 0; i < BFS_DENSE_BATCH; ++i) {
+            const uint64_t hit = __ballot(((word[i] >> ((uint32_t)nb[i] & 31u)) & 1u) != 0u);
+            if (lane == 0u) {
+              hits[2u * (r0 + i)] = (uint32_t)hit;
+              hits[2u * (r0 + i) + 1u] = (uint32_t)(hit >> 32);
+            }
+          }
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (uint32_t u = 0; u < Q; ++u) {
+          bool found = false;
+          const uint32_t s = (uint32_t)(row0[u] - bit0), t = (uint32_t)(row1[u] - bit0);
+          if (unv[u] && s < t) {
+            const uint32_t w0 = s >> 5, w1 = (t - 1u) >> 5;
+            uint32_t any = 0u;
+            for (uint32_t w = w0; w <= w1; ++w) {
+              uint32_t m = 0xffffffffu;
+              if (w == w0) m &= 0xffffffffu << (s & 31u);
+              if (w == w1) m &= 0xffffffffu >> (31u - ((t - 1u) & 31u));
+              any |= hits[w] & m;
+            }
+            found = any != 0u;
+          }
+          const int32_t v = (int32_t)(v0 + 64u * u + lane);
+          if (found) level[v] = next_level;
+          const uint64_t fm = __ballot(found);
+          if (lane == 0u) {
+            s_out[wave][2u * u] = (uint32_t)fm;
+            s_out[wave][2u * u + 1u] = (uint32_t)(fm >> 32);
+          }
+          stage_append(stage, found, v, q_out, cnt_out, lane);
+        }
+      } else {
+        uint32_t at = 0;
+#pragma unroll
+        for (uint32_t u = 0; u < Q; ++u) {
+          if (unv[u]) list[at + __popcll(unv_mask[u] & ((1ull << lane) - 1ull))] = (int32_t)(v0 + 64u * u + lane);
+          at += (uint32_t)__popcll(unv_mask[u]);
+        }
+        if (lane < BFS_BU_SPAN / 32u) s_out[wave][lane] = 0u;
+        __builtin_amdgcn_wave_barrier();
+        if (cnt > 128u) rounds(lds_probe, std::integral_constant<uint32_t, 4>{}, v0, cnt);
+        else if (cnt > 64u) rounds(lds_probe, std::integral_constant<uint32_t, 2>{}, v0, cnt);
+        else if (cnt > 0u) rounds(lds_probe, std::integral_constant<uint32_t, 1>{}, v0, cnt);
+      }
       __builtin_amdgcn_wave_barrier();
       // the span's bitmap words belong to this wave alone (v0 is a multiple of 256)
       if (lane < BFS_BU_SPAN / 32u && (v0 >> 5) + lane < words) bm_out[(v0 >> 5) + lane] = s_out[wave][lane];
@@ -289,6 +402,7 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
 
   // top-down.  Small frontiers are split into chunks of fewer than 64 vertices so that
   // every wave of the grid gets some of the edges.
+  const bool look_first = (uint64_t)reached * 8u >= n;       // uniform over the grid
   uint32_t chunk = (n_in + total_waves - 1u) / total_waves;
   if (chunk > 64u) chunk = 64u;
   for (uint32_t base = gwave * chunk; base < n_in; base += total_waves * chunk) {
@@ -330,9 +444,15 @@ __global__ __launch_bounds__(BFS_THREADS) void bfs_level(const int32_t* __restri
         }
         nb[u] = col_idx[s_start[wave][lo] + (int32_t)(e - s_excl[wave][lo])];
       }
+      // (while few vertices are reached nearly every neighbour is new: the claim goes out at once,
+      // without the round trip of looking first)
       int32_t seen[BFS_UNROLL];
 #pragma unroll
-      for (uint32_t u = 0; u < BFS_UNROLL; ++u) seen[u] = level[nb[u]];
+      for (uint32_t u = 0; u < BFS_UNROLL; ++u) seen[u] = -1;
+      if (look_first) {
+#pragma unroll
+        for (uint32_t u = 0; u < BFS_UNROLL; ++u) seen[u] = level[nb[u]];
+      }
 #pragma unroll
       for (uint32_t u = 0; u < BFS_UNROLL; ++u) {
         bool won = false;
@@ -381,13 +501,14 @@ uint64_t mgb_bfs_work_bytes(uint32_t n) {
 }
 
 // workgroups of the level kernel that fit one CU: LDS (the frontier bitmap on top of the
-// kernel's own 29184 bytes of staging) or the 8 waves of a workgroup against 32 wave slots
+// kernel's own 29184 bytes of staging) or registers (the launch bounds hold the kernel to 128
+// vector registers per lane: four waves per SIMD, two workgroups of eight waves per CU)
 uint32_t mgb_bfs_residency(uint32_t n) {
   if (n == 0u || n > 0x7fffffffu) return 0u;
   const uint32_t words = (uint32_t)((((uint64_t)n + 31) / 32 + 63) / 64 * 64);
   const uint32_t by_lds = (160u * 1024u) / (29184u + lds_bitmap_bytes(n, words, 1u));
-  const uint32_t by_waves = 32u / BFS_WAVES;
-  return by_lds < by_waves ? by_lds : by_waves;
+  const uint32_t by_regs = 2u;
+  return by_lds < by_regs ? by_lds : by_regs;
 }
 
 int mgb_bfs_probe(uint32_t n, uint64_t m, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block) {

@@ -447,10 +447,24 @@ def test_bfs_degenerate_graphs():
     rp, ci = _csr(1, [])                                            # single vertex
     got, depth = run_bfs(rp, ci, 0)
     assert list(got) == [0] and depth == 1
-    for n in (16, 17, 18, 32, 33, 34):                              # depths around the batch size
+    for n in (16, 17, 18, 32, 33, 34, 56, 57, 58):                  # depths around the batch sizes (8, then 16, then 32)
         rp, ci = _csr(n, [(i, i + 1) for i in range(n - 1)])
         got, depth = run_bfs(rp, ci, 0)
         assert np.array_equal(got, np.arange(n)) and depth == n
+    # a hub as the source and as the second level; a wide second level whose vertices have one edge each
+    rp, ci = _csr(20000, [(0, i) for i in range(1, 20000)])
+    got, depth = run_bfs(rp, ci, 0)
+    assert np.array_equal(got, np.r_[0, np.ones(19999, dtype=np.int32)]) and depth == 2
+    got, depth = run_bfs(rp, ci, 9)
+    assert got[0] == 1 and got[9] == 0 and (np.delete(got, [0, 9]) == 2).all() and depth == 3
+    edges = [(0, i) for i in range(1, 3001)] + [(i, i + 3000) for i in range(1, 3001)] + [(6000, 6001)]
+    rp, ci = _csr(6002, edges)
+    got, depth = run_bfs(rp, ci, 0)
+    want = oracle.bfs(rp, ci, 0)
+    assert np.array_equal(got, want) and depth == want.max() + 1 == 4
+    got, depth = run_bfs(rp, ci, 6001)
+    want = oracle.bfs(rp, ci, 6001)
+    assert np.array_equal(got, want) and depth == want.max() + 1
 
 
 def test_bfs_full_size_mix16_task():
