@@ -30,9 +30,9 @@ def parse():
 # profiles/mix16_hbm_traffic.md (each counter scaled by its reading for the 1 GiB stream copy).
 # Valid for the kernels as they stand in csrc/ and for the Mix-16 task shapes only.
 MEASURED_TRAFFIC_BYTES = {
-    ("mix16", "gemm_f32_dma_kernel"): 470.3e6,  # per 4096^3 launch
+    ("mix16", "gemm_f32_dma_kernel"): 470.4e6,  # per 4096^3 launch
     ("mix16", "jacobi_sweeps"): 135.4e6,       # per launch (24 four-sweep + 2 two-sweep launches per task)
-    ("mix16", "bfs_level"): 22.2e6,            # per level launch, averaged over the 8 launches of a traversal
+    ("mix16", "bfs_level"): 20.7e6,            # per level launch, averaged over the 8 launches of a traversal
 }
 
 
