@@ -83,9 +83,18 @@ def cpu_baseline(spec):
     for t in spec["tasks"]:
         clock = max(clock, t.arrival_s) + per_kind[(t.kind, tuple(sorted(t.params.items())))]
         turn.append(clock - t.arrival_s)
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
     return dict(value=len(spec["tasks"]) / clock, unit="tasks/s", cores=1, kind="oracle",
                 sample="; ".join(sample), est_seconds_per_mix=total,
-                mean_turnaround_ms=1e3 * sum(turn) / len(turn), nproc=os.cpu_count())
+                mean_turnaround_ms=1e3 * sum(turn) / len(turn), nproc=os.cpu_count(), cpu_model=model)
 
 
 def lazy_leg(mgb, cap):
@@ -236,10 +245,10 @@ def main():
     kern = {}
     for rec, _ in runs:
         for r, t in zip(rec, tasks):
-            k = kern.setdefault(t.kernel_name, dict(ms=0.0, launches=0, tasks=0, bytes=0.0, flops=0.0))
+            k = kern.setdefault(t.kernel_name, dict(ms=0.0, launches=0, tasks=0, bytes=0.0, flops=0.0, edges=0))
             launches = t.launches if t.launches is not None else max(1, int(t.depth.value))
             k["ms"] += r["gpu_ms"]; k["launches"] += launches; k["tasks"] += 1
-            k["bytes"] += t.alg_bytes; k["flops"] += t.alg_flops
+            k["bytes"] += t.alg_bytes; k["flops"] += t.alg_flops; k["edges"] += t.edges
     dominant = max(kern, key=lambda n: kern[n]["ms"])
     kd = kern[dominant]
     peaks = dict(jacobi_sweeps=("hbm", 8000.0, "GB/s"), bfs_level=("hbm", 8000.0, "GB/s"),
@@ -257,10 +266,13 @@ def main():
         bound, peak, unit = peaks[name]
         work = k["bytes"] / 1e9 if bound == "hbm" else k["flops"] / 1e12
         ach = work / (k["ms"] / 1e3)
-        return dict(kernel=name, bound=bound, achieved=round(ach, 2), peak=peak, unit=unit,
-                    frac=round(ach / peak, 4), measured_ceiling=round(measured_ceiling(name), 1),
-                    frac_of_measured=round(ach / measured_ceiling(name), 4), traffic=MEASURED_TRAFFIC_BYTES.get((args.mix, name)),
-                    avg_launch_us=round(1e3 * k["ms"] / k["launches"], 2), launches=k["launches"])
+        out = dict(kernel=name, bound=bound, achieved=round(ach, 2), peak=peak, unit=unit,
+                   frac=round(ach / peak, 4), measured_ceiling=round(measured_ceiling(name), 1),
+                   frac_of_measured=round(ach / measured_ceiling(name), 4), traffic=MEASURED_TRAFFIC_BYTES.get((args.mix, name)),
+                   avg_launch_us=round(1e3 * k["ms"] / k["launches"], 2), launches=k["launches"])
+        if k["edges"]:
+            out["gteps"] = round(k["edges"] / (k["ms"] / 1e3) / 1e9, 2)      # stored directed edges per second of traversal
+        return out
 
     out = dict(metric="aggregate tasks/s through probe+admit+partition+launch+complete (with mean turnaround, max slowdown)",
                value=round(value, 2), unit="tasks/s", n_gpus=1, steps=args.steps, warmup=args.warmup,

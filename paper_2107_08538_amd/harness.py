@@ -28,6 +28,7 @@ class Task:
         self.launches = launches        # kernel launches per task (None if data dependent)
         self.alg_bytes = alg_bytes      # algorithmic HBM bytes of the whole task
         self.alg_flops = alg_flops
+        self.edges = 0                  # stored (directed) edges of a graph task
 
 
 def build_task(spec, data, device="cuda:0"):
@@ -73,6 +74,7 @@ def build_task(spec, data, device="cuda:0"):
         t = Task(spec, dict(rp=rp, ci=ci, level=level, work=work), probe, fn, "bfs_level", None,
                  alg_bytes=8.0 * m_edges + 24.0 * n, wg_per_cu=int(mgb.mgb_bfs_residency(n)))
         t.depth = depth
+        t.edges = m_edges
         return t
     if k == "cnn":
         layers = data["layers"]

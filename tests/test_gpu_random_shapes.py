@@ -86,3 +86,44 @@ def test_random_jacobi_and_bfs(seed):
         got, depth = K.run_bfs(rp, ci)
         want = oracle.bfs(rp, ci, 0)
         assert np.array_equal(got, want) and depth == want.max() + 1, (n, d)
+
+
+def _sym_csr(n, s, d):
+    s2, d2 = np.concatenate([s, d]), np.concatenate([d, s])
+    order = np.lexsort((d2, s2))
+    s2, d2 = s2[order], d2[order]
+    rp = np.zeros(n + 1, dtype=np.int32)
+    np.cumsum(np.bincount(s2, minlength=n), out=rp[1:])
+    return rp, d2.astype(np.int32)
+
+
+@pytest.mark.parametrize("seed", [31])
+def test_random_skewed_graphs(seed):
+    """Degree distributions far from the benchmark's: a few rows of thousands of entries (spans of the
+    bottom-up scan whose edges do not fit its bit array), blocks of isolated vertices between dense
+    ones (zero-length rows inside a span), more than 2^20 vertices (frontier bitmap in memory), any source."""
+    rng = np.random.default_rng(seed)
+    for i in range(9):
+        kind = i % 3
+        if kind == 0:
+            n = _r(rng, 1000, 600000)
+            m = int(n * rng.uniform(2, 12))
+            s = (n * rng.random(m) ** 3).astype(np.int64)
+            d = rng.integers(0, n, m)
+            src = _r(rng, 0, n - 1)
+        elif kind == 1:
+            n = _r(rng, 1000, 500000)
+            m = int(n * rng.uniform(4, 20))
+            ids = np.flatnonzero(rng.random(n) < 0.5)
+            s, d = ids[rng.integers(0, ids.size, m)], ids[rng.integers(0, ids.size, m)]
+            src = int(ids[0])
+        else:
+            n = _r(rng, 1 << 20, 2 << 20)
+            m = int(n * rng.uniform(1.0, 5.0))
+            s, d = rng.integers(0, n, m), rng.integers(0, n, m)
+            src = _r(rng, 0, n - 1)
+        keep = s != d
+        rp, ci = _sym_csr(n, s[keep], d[keep])
+        got, depth = K.run_bfs(rp, ci, src)
+        want = oracle.bfs(rp, ci, src)
+        assert np.array_equal(got, want) and depth == want.max() + 1, (kind, n, m, src)
