@@ -269,6 +269,48 @@ def test_soft_compute_is_memory_only_admission_on_least_loaded_granules():
     assert adm["in_index"] == 3 and adm["granule_mask"] == 2
 
 
+def test_soft_load_is_the_tasks_waves_spread_over_its_block():
+    # hand-worked: 4 CUs in granules of one, 64 wave slots each.  A (100 waves on a block of two)
+    # adds ceil(100 / 2) = 50 to granules 0 and 1; B and C (60 waves, one granule each) go to the
+    # empty granules 2 and 3; D then finds 50, 50, 60, 60 and takes granule 0.  Were A's 100 waves
+    # charged to each of its granules, D would go to granule 2.
+    dev = oracle.device(1 << 30, n_cu=4, granule_cus=1, max_waves_per_cu=64, max_wg_per_cu=64, policy=POL_SOFT)
+    ev = [("probe", 0, 1, (100, 1, 1), (64, 1, 1)), ("probe", 1, 1, (60, 1, 1), (64, 1, 1)),
+          ("probe", 2, 1, (60, 1, 1), (64, 1, 1)), ("probe", 3, 1, (10, 1, 1), (64, 1, 1))]
+    dec = oracle.sched_replay(dev, oracle.make_inputs(ev))
+    assert [d["kind"] for d in dec] == [D_ADMIT] * 4
+    assert [d["demand"] for d in dec] == [2, 1, 1, 1]
+    assert [d["granule_mask"] for d in dec] == [0b0011, 0b0100, 0b1000, 0b0001]
+
+
+def test_fifo_release_stops_at_a_head_that_does_not_fit():
+    # hand-worked: 4 granules.  A and B hold two each, C wants all four and waits, D wants one and
+    # queues behind it.  When A leaves, C still does not fit: a FIFO queue admits nobody (D stays
+    # behind C although two granules are free), a backfilling queue admits D at once.
+    dev_kw = dict(n_cu=4, granule_cus=1, max_waves_per_cu=32, max_wg_per_cu=32, policy=POL_HARD)
+    ev = [("probe", 0, 1, (64, 1, 1), (64, 1, 1)), ("probe", 1, 1, (64, 1, 1), (64, 1, 1)),
+          ("probe", 2, 1, (128, 1, 1), (64, 1, 1)), ("probe", 3, 1, (1, 1, 1), (64, 1, 1)),
+          ("complete", 1), ("complete", 2), ("complete", 3)]
+    dec = oracle.sched_replay(oracle.device(1 << 30, queue_mode=Q_FIFO, **dev_kw), oracle.make_inputs(ev))
+    got = [(int(d["in_index"]), int(d["kind"]), int(d["ticket"]), int(d["granule_mask"])) for d in dec]
+    assert got == [(0, D_ADMIT, 1, 0b0011), (1, D_ADMIT, 2, 0b1100), (2, D_WAIT, 3, 0), (3, D_WAIT, 4, 0),
+                   (4, D_RELEASE, 1, 0b0011),
+                   (5, D_RELEASE, 2, 0b1100), (5, D_ADMIT, 3, 0b1111),
+                   (6, D_RELEASE, 3, 0b1111), (6, D_ADMIT, 4, 0b0001)]
+    dec = oracle.sched_replay(oracle.device(1 << 30, queue_mode=Q_BACKFILL, **dev_kw), oracle.make_inputs(ev))
+    got = [(int(d["in_index"]), int(d["kind"]), int(d["ticket"]), int(d["granule_mask"])) for d in dec]
+    assert got[4:6] == [(4, D_RELEASE, 1, 0b0011), (4, D_ADMIT, 4, 0b0001)]
+
+
+def test_a_workgroup_has_at_most_1024_threads():
+    dev = oracle.device(1 << 30)
+    ev = [("probe", 0, 1, (1, 1, 1), (1024, 1, 1)), ("probe", 1, 1, (1, 1, 1), (1025, 1, 1)),
+          ("probe", 2, 1, (1, 1, 1), (32, 33, 1)), ("probe", 3, 1, (1, 1, 1), (16, 8, 8))]
+    dec = oracle.sched_replay(dev, oracle.make_inputs(ev))
+    assert [int(d["kind"]) for d in dec] == [D_ADMIT, D_REJECT, D_REJECT, D_ADMIT]
+    assert dec[1]["code"] == dec[2]["code"] == -1          # invalid argument
+
+
 def test_memory_is_hard_in_every_policy_and_exact_fit_is_admitted():
     for pol in (POL_HARD, POL_SOFT, POL_SERIAL):
         dev = oracle.device(100, policy=pol)
