@@ -21,13 +21,16 @@ extern "C" {
 // Jacobi n x n: two fp32 grids.  n % 4 == 0: a wave sweeps a window of 256 columns x 8 output
 // rows; windows step by 248 columns (4 columns on each side of a window go stale, except next to
 // the grid's own boundary), so the first window yields columns 1..251 and each further one 248
-// more; four windows per 256-thread workgroup.  Otherwise one column per thread, 256 columns x
+// more; four windows per 256-thread workgroup.  Grids of 8192 or more fuse up to six sweeps per
+// launch and then lose 8 columns per side (steps of 240); a task's grid is that of its largest launch.  Otherwise one column per thread, 256 columns x
 // 8 rows per workgroup.
-void orc_jacobi_probe(uint64_t n, uint64_t out[7]) {
+void orc_jacobi_probe(uint64_t n, uint64_t iters, uint64_t out[7]) {
   uint64_t wg;
   if (n % 4 == 0) {
+    // launches of more than four sweeps (only on grids of 8192 or more) lose 8 columns per window side, else 4
+    uint64_t halo = (n >= 8192 && iters > 4) ? 8 : 4;
     uint64_t last = n - 2;                       // last interior column
-    uint64_t win_c = last <= 251 ? 1 : 1 + ceil_div(last - 251, 248);
+    uint64_t win_c = last <= 255 - halo ? 1 : 1 + ceil_div(last - (255 - halo), 256 - 2 * halo);
     uint64_t win_r = ceil_div(n - 2, 8);
     wg = ceil_div(win_c * win_r, 4);
   } else {

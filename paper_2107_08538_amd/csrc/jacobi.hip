@@ -1,4 +1,5 @@
-// fp32 5-point Jacobi relaxation, up to four sweeps per kernel launch.
+// fp32 5-point Jacobi relaxation, up to four sweeps per kernel launch (six on grids that do not
+// fit the last-level cache).
 //
 // One sweep per launch is HBM-bound at 8 bytes per cell update (one read and
 // one write of every cell).  Fusing T sweeps into a launch divides that traffic
@@ -8,7 +9,7 @@
 // own registers, west / east come from the neighbouring lane through a wave
 // shuffle -- and stores the JB_ROWS x 248 cells that are still exact.  Cells
 // next to a window edge go stale by one cell per sweep, which is why windows
-// overlap by four columns and T rows on each side; the fixed outer ring of the
+// overlap by four columns (eight when T > 4) and T rows on each side; the fixed outer ring of the
 // grid is a true boundary and costs no overlap.  No LDS and no barriers: waves
 // are independent.  Eight output rows per window keep the register file small
 // enough for three waves per SIMD, which measured faster than taller windows
@@ -35,9 +36,14 @@ namespace {
 constexpr uint32_t JB_THREADS = 256;          // 4 waves, one window each
 constexpr uint32_t JB_ROWS = JB_ROWS_DEF;     // output rows per window
 constexpr uint32_t JB_WIN = 256;              // window width in columns (64 lanes x 4)
-constexpr uint32_t JB_HALO = 4;               // columns lost on each side of a window (>= max T, keeps 16-byte alignment)
-constexpr uint32_t JB_STEP = JB_WIN - 2u * JB_HALO;   // 248 exact columns per window
-constexpr uint32_t JB_MAXT = 4;
+constexpr uint32_t JB_MAXT = 6;
+// Sweeps fused per launch.  A grid pair that fits the 256 MB last-level cache (n < 8192) gains
+// nothing from more than four (measured: the same time at 4096^2, 5 % slower at 2048^2); beyond
+// it the launch is bound by HBM and six sweeps per pass are 12 % (8192^2) to 23 % (16384^2) faster.
+constexpr uint32_t fused_sweeps(uint32_t n) { return n >= 8192u ? JB_MAXT : 4u; }
+// columns lost on each side of a window: at least the sweeps of the launch, a multiple of 4 (16-byte alignment)
+constexpr uint32_t halo_of(uint32_t t) { return t > 4u ? 8u : 4u; }
+constexpr uint32_t step_of(uint32_t halo) { return JB_WIN - 2u * halo; }   // exact columns per window: 248 or 240
 
 // Workgroups are dealt round-robin to the 8 XCDs in launch order; give each
 // XCD one contiguous band of windows so that the rows shared by vertically
@@ -93,10 +99,11 @@ __device__ __forceinline__ void run_sweeps(float4 (&cur)[JB_ROWS + 2u * T], int3
 // n % 4 == 0: rows are 16-byte aligned, every lane's four columns are either
 // all inside the grid or all outside.
 template <uint32_t T>
-__global__ __launch_bounds__(JB_THREADS, 3) void jacobi_sweeps(const float* __restrict__ u,
+__global__ __launch_bounds__(JB_THREADS, T > 4u ? 2 : 3) void jacobi_sweeps(const float* __restrict__ u,
                                                            float* __restrict__ v, uint32_t n,
                                                            uint32_t tiles_c, uint32_t tiles_r) {
   constexpr uint32_t NR = JB_ROWS + 2u * T;               // rows held in registers
+  constexpr uint32_t JB_HALO = halo_of(T), JB_STEP = step_of(JB_HALO);
   uint32_t tc, tr;
   if (!window_of_wave(tiles_c, tiles_r, &tc, &tr)) return;
   const uint32_t lane = threadIdx.x & 63u;
@@ -121,9 +128,9 @@ __global__ __launch_bounds__(JB_THREADS, 3) void jacobi_sweeps(const float* __re
   if (edge) run_sweeps<T, true>(cur, g0, n, first_col, last_col);
   else run_sweeps<T, false>(cur, g0, n, first_col, last_col);
 
-  // store what is still exact: not the four columns next to a window edge (an edge that is
+  // store what is still exact: not the JB_HALO columns next to a window edge (an edge that is
   // the grid's own boundary loses nothing), rows JB_ROWS of this window that are interior
-  const bool left_ok = tc == 0u || lane >= 1u;
+  const bool left_ok = tc == 0u || 4u * lane >= JB_HALO;
   const bool right_ok = c0 + 4u <= w0 + JB_WIN - JB_HALO || w0 + JB_WIN >= n;
   if (left_ok && right_ok) {
 #pragma unroll
@@ -165,7 +172,8 @@ struct Geometry {
   bool vec4;
 };
 
-Geometry geometry(uint32_t n) {
+Geometry geometry(uint32_t n, uint32_t JB_HALO) {
+  const uint32_t JB_STEP = step_of(JB_HALO);
   Geometry g;
   g.vec4 = (n % 4u) == 0u;
   if (g.vec4) {
@@ -185,13 +193,13 @@ Geometry geometry(uint32_t n) {
   return g;
 }
 
-// Split `iters` sweeps into launches of 1..4 sweeps such that the number of launches has the
+// Split `iters` sweeps into launches of 1..maxt sweeps such that the number of launches has the
 // parity of iters: the buffers swap once per launch and the result must end in buffer iters % 2.
-uint32_t plan_launches(uint32_t iters, uint32_t* plan, uint32_t cap) {
+uint32_t plan_launches(uint32_t iters, uint32_t maxt, uint32_t* plan, uint32_t cap) {
   uint32_t n = 0;
   uint32_t left = iters;
   while (left > 0u && n < cap) {
-    const uint32_t t = left >= JB_MAXT ? JB_MAXT : left;
+    const uint32_t t = left >= maxt ? maxt : left;
     plan[n++] = t;
     left -= t;
   }
@@ -212,7 +220,8 @@ uint32_t plan_launches(uint32_t iters, uint32_t* plan, uint32_t cap) {
 }
 
 template <uint32_t T>
-void launch_sweeps(hipStream_t st, const Geometry& g, const float* src, float* dst, uint32_t n) {
+void launch_sweeps(hipStream_t st, const float* src, float* dst, uint32_t n) {
+  const Geometry g = geometry(n, halo_of(T));
   hipLaunchKernelGGL(jacobi_sweeps<T>, dim3(g.blocks), dim3(JB_THREADS), 0, st, src, dst, n, g.tiles_x,
                      g.tiles_y);
 }
@@ -226,7 +235,8 @@ int mgb_jacobi_probe(uint32_t n, uint32_t iters, uint64_t* mem_bytes, mgb_dim3* 
   (void)iters;
   if (!mem_bytes || !grid || !block) return MGB_E_INVAL;
   if (n < 3u || n > 65536u) return MGB_E_UNSUPPORTED;
-  const Geometry g = geometry(n);
+  // the largest grid among the task's launches: the one with the most sweeps (widest halo)
+  const Geometry g = geometry(n, halo_of(iters < fused_sweeps(n) ? iters : fused_sweeps(n)));
   *mem_bytes = 2ull * n * n * sizeof(float);
   *grid = mgb_dim3{g.blocks, 1u, 1u};
   *block = mgb_dim3{JB_THREADS, 1u, 1u};
@@ -240,7 +250,7 @@ uint32_t mgb_jacobi_launch_count(uint32_t n, uint32_t iters) {
   while (done < iters) {
     uint32_t plan[64];
     const uint32_t chunk = iters - done > 128u ? 128u : iters - done;
-    total += plan_launches(chunk, plan, 64u);
+    total += plan_launches(chunk, fused_sweeps(n), plan, 64u);
     done += chunk;
   }
   return total;
@@ -250,7 +260,7 @@ int mgb_jacobi_enqueue(void* stream, float* u0, float* u1, uint32_t n, uint32_t 
   if (!u0 || !u1 || u0 == u1) return MGB_E_INVAL;
   if (n < 3u || n > 65536u) return MGB_E_UNSUPPORTED;
   if (((uintptr_t)u0 | (uintptr_t)u1) & 15u) return MGB_E_INVAL;
-  const Geometry g = geometry(n);
+  const Geometry g = geometry(n, 4u);
   hipStream_t st = (hipStream_t)stream;
   const float* src = u0;
   float* dst = u1;
@@ -268,13 +278,15 @@ int mgb_jacobi_enqueue(void* stream, float* u0, float* u1, uint32_t n, uint32_t 
   while (done < iters) {
     uint32_t plan[64];
     const uint32_t chunk = iters - done > 128u ? 128u : iters - done;   // even chunks keep the parity rule
-    const uint32_t np = plan_launches(chunk, plan, 64u);
+    const uint32_t np = plan_launches(chunk, fused_sweeps(n), plan, 64u);
     for (uint32_t i = 0; i < np; ++i) {
       switch (plan[i]) {
-        case 1: launch_sweeps<1>(st, g, src, dst, n); break;
-        case 2: launch_sweeps<2>(st, g, src, dst, n); break;
-        case 3: launch_sweeps<3>(st, g, src, dst, n); break;
-        default: launch_sweeps<4>(st, g, src, dst, n); break;
+        case 1: launch_sweeps<1>(st, src, dst, n); break;
+        case 2: launch_sweeps<2>(st, src, dst, n); break;
+        case 3: launch_sweeps<3>(st, src, dst, n); break;
+        case 4: launch_sweeps<4>(st, src, dst, n); break;
+        case 5: launch_sweeps<5>(st, src, dst, n); break;
+        default: launch_sweeps<6>(st, src, dst, n); break;
       }
       float* tmp = const_cast<float*>(src);
       src = dst;

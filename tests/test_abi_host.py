@@ -148,6 +148,11 @@ def test_jacobi_launch_plan_keeps_buffer_parity():
         assert c % 2 == it % 2 and (it + 3) // 4 <= c <= (it + 3) // 4 + (it // 128 + 1)
         assert mgb.mgb_jacobi_launch_count(77, it) == it             # n % 4 != 0: one sweep per launch
     assert mgb.mgb_jacobi_launch_count(4096, 100) == 26 and mgb.mgb_jacobi_launch_count(2, 5) == 0
+    # grids that do not fit the last-level cache fuse up to six sweeps
+    for it in list(range(0, 40)) + [50, 100, 127, 128, 129, 1000]:
+        c = mgb.mgb_jacobi_launch_count(16384, it)
+        assert c % 2 == it % 2 and (it + 5) // 6 <= c <= (it + 5) // 6 + (it // 128 + 1)
+    assert mgb.mgb_jacobi_launch_count(16384, 50) == 10 and mgb.mgb_jacobi_launch_count(8192, 6) == 2
 
 
 def test_resident_task_limit():
@@ -300,8 +305,12 @@ def test_probe_functions_agree_with_checker_formulas():
     out = (C.c_uint64 * 7)()
     for n in (3, 4, 5, 64, 77, 512, 1023, 1024, 1025, 4096, 16384):
         mem, grid, block = mgb.probe_of(mgb.mgb_jacobi_probe, n, 10)
-        oracle.lib().orc_jacobi_probe(C.c_uint64(n), out)
+        oracle.lib().orc_jacobi_probe(C.c_uint64(n), C.c_uint64(10), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), n
+    for n, it in ((8192, 1), (8192, 4), (8192, 5), (8192, 6), (8192, 100), (8188, 50), (16384, 50), (65536, 7), (4096, 6)):
+        mem, grid, block = mgb.probe_of(mgb.mgb_jacobi_probe, n, it)
+        oracle.lib().orc_jacobi_probe(C.c_uint64(n), C.c_uint64(it), out)
+        assert [mem, *grid.tuple(), *block.tuple()] == list(out), (n, it)
     for m, n, k in ((1, 1, 1), (128, 128, 16), (129, 257, 17), (256, 256, 256), (4096, 4096, 4096),
                     (32768, 32768, 32768), (1000, 3000, 50), (1024, 1024, 1024), (1408, 1536, 64), (1408, 1408, 64),
                     (1000, 3000, 48), (1000, 3002, 48), (2816, 2816, 64), (4096, 4096, 64), (4096, 3840, 64), (8192, 8192, 16),

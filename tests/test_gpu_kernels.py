@@ -74,6 +74,16 @@ def test_jacobi_full_size_mix16_task():
     assert np.array_equal(got, oracle.jacobi_f32(u, iters))
 
 
+@pytest.mark.parametrize("n,iters", [(8200, 5), (8192, 12), (8444, 17)])
+def test_jacobi_deeper_fusion_on_grids_beyond_the_last_level_cache(n, iters):
+    # from 8192 columns on, launches fuse five or six sweeps (windows that lose eight columns per side):
+    # 5 = one launch of five; 12 = six + six; 17 = 6 + 6 + 5 sweeps; ragged last windows in both directions
+    u = W.jacobi_field(321, n)
+    assert mgb.mgb_jacobi_launch_count(n, iters) == {5: 1, 12: 2, 17: 3}[iters]
+    got = run_jacobi(u, iters)
+    assert np.array_equal(got, oracle.jacobi_f32(u, iters))
+
+
 def test_jacobi_large_eigenmode_property():
     # 16384^2 (the largest task size): an eigenmode of the sweep must come back scaled by lambda^k
     n, k, p, q = 16384, 10, 3, 5

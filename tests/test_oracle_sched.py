@@ -433,13 +433,15 @@ def test_grow_is_granted_only_from_free_bytes_and_returns_with_the_task():
 def test_probe_formulas_match_stated_footprints():
     import ctypes as C
     out = (C.c_uint64 * 7)()
-    oracle.lib().orc_jacobi_probe(C.c_uint64(16384), out)
+    oracle.lib().orc_jacobi_probe(C.c_uint64(16384), C.c_uint64(4), out)
     assert out[0] == 2 * 2 ** 30                     # "about 2 GiB" per Jacobi 16384^2 task
     assert out[1] == 34304 and out[4] == 256           # 67 x 2048 windows, four per workgroup
+    oracle.lib().orc_jacobi_probe(C.c_uint64(16384), C.c_uint64(50), out)
+    assert out[0] == 2 * 2 ** 30 and out[1] == 35328   # six sweeps per launch: steps of 240 columns, 69 x 2048 windows
     oracle.lib().orc_gemm_f32_probe(C.c_uint64(32768), C.c_uint64(32768), C.c_uint64(32768), out)
     assert out[0] == 12 * 2 ** 30                    # "about 12 GiB" per GEMM 32768^3 task
     assert out[1] == 128 * 128 and out[4] == 256       # 256 x 256 tiles, four waves each
-    oracle.lib().orc_jacobi_probe(C.c_uint64(512), out)
+    oracle.lib().orc_jacobi_probe(C.c_uint64(512), C.c_uint64(20), out)
     assert out[0] == 2 * 512 * 512 * 4 and out[1] == 48   # 3 x 64 windows, four per workgroup
     oracle.lib().orc_gemm_f32_probe(C.c_uint64(256), C.c_uint64(256), C.c_uint64(256), out)
     assert out[0] == 768 * 1024 and out[1] == 16 and out[4] == 256   # 4 x 4 tiles of 64 x 64 (too few 128 x 128 ones)
