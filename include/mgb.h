@@ -330,13 +330,16 @@ int mgb_client_stream(mgb_client* c, const mgb_placement* placement, void** stre
  * ring is a fixed boundary: v = 0.25f * ((N + S) + (W + E)) on the interior,
  * `iters` sweeps ping-ponging between u0 (initial state) and u1; the result is
  * in u0 if iters is even, else u1.  Both buffers must hold the same ring.
- * Up to four sweeps are fused into one launch, up to six for n >= 8192
- * (bit-identical to single sweeps).
+ * Up to four sweeps are fused into one launch, up to eight for n >= 4096
+ * (bit-identical to single sweeps).  The probe's grid is the largest among
+ * the task's launches.  mgb_jacobi_residency(n) = workgroups of these kernels
+ * that one CU holds (registers), 0 if n is unsupported.
  * Footprint 2*n*n*4 bytes.  n >= 3.                                         */
 int mgb_jacobi_probe(uint32_t n, uint32_t iters, uint64_t* mem_bytes, mgb_dim3* grid, mgb_dim3* block);
+uint32_t mgb_jacobi_residency(uint32_t n);
 int mgb_jacobi_enqueue(void* stream, float* u0, float* u1, uint32_t n, uint32_t iters);
 /* Number of kernel launches mgb_jacobi_enqueue issues for (n, iters): sweeps are fused up to
- * four (n >= 8192: six) per launch, with the launch count kept at the parity of iters (0 if n
+ * four (n >= 4096: eight) per launch, with the launch count kept at the parity of iters (0 if n
  * is unsupported). */
 uint32_t mgb_jacobi_launch_count(uint32_t n, uint32_t iters);
 

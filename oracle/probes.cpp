@@ -6,7 +6,9 @@
 // shared buffers is one task, Algorithm 1).  The functions below recompute
 // those figures from the published tiling rules of each task kind, written
 // out independently of the GPU library.
+#include <algorithm>
 #include <cstdint>
+#include <vector>
 
 namespace {
 uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
@@ -18,28 +20,47 @@ extern "C" {
 
 // out = {mem_bytes, grid_x, grid_y, grid_z, block_x, block_y, block_z}
 
-// Jacobi n x n: two fp32 grids.  n % 4 == 0: a wave sweeps a window of 256 columns x 8 output
-// rows; windows step by 248 columns (4 columns on each side of a window go stale, except next to
-// the grid's own boundary), so the first window yields columns 1..251 and each further one 248
-// more; four windows per 256-thread workgroup.  Grids of 8192 or more fuse up to six sweeps per
-// launch and then lose 8 columns per side (steps of 240); a task's grid is that of its largest launch.  Otherwise one column per thread, 256 columns x
-// 8 rows per workgroup.
+// Jacobi n x n: two fp32 grids.  n % 4 != 0: one column per thread, 256 columns x 8 rows per
+// workgroup, one sweep per launch.  n % 4 == 0: sweeps are fused, up to 4 per launch (up to 8
+// from n = 4096 on), planned in chunks of 128 sweeps: the fewest launches whose number has the
+// parity of the chunk, the sweeps spread evenly over them.  A launch of t <= 4 sweeps: a wave takes a window of 256 columns x 8 output
+// rows, windows step by 248 columns (4 stale columns on each side of a window, none next to the
+// grid's own boundary: the first window yields columns 1..251).  A launch of t > 4 sweeps: a wave
+// takes a strip of 256 columns stepping by 240 (8 stale columns per side) and runs of 40 output
+// rows.  Four waves per 256-thread workgroup, grids rounded up to a multiple of 8.  One probe
+// covers all launches of the task: its grid is the largest of them.
+static uint64_t jacobi_blocks(uint64_t n, uint64_t t) {
+  uint64_t halo = t > 4 ? 8 : 4, rows = t > 4 ? 40 : 8;
+  uint64_t last = n - 2;                       // last interior column
+  uint64_t win_c = last <= 255 - halo ? 1 : 1 + ceil_div(last - (255 - halo), 256 - 2 * halo);
+  uint64_t win_r = ceil_div(n - 2, rows);
+  return round8(ceil_div(win_c * win_r, 4));
+}
+static uint64_t jacobi_chunk_blocks(uint64_t n, uint64_t sweeps, uint64_t maxt) {
+  uint64_t launches = ceil_div(sweeps, maxt);
+  if (launches % 2 != sweeps % 2) ++launches;
+  // the launches get floor(sweeps / launches) sweeps, some of them one more
+  uint64_t lo = sweeps / launches, hi = lo + (sweeps % launches != 0 ? 1 : 0);
+  return std::max(jacobi_blocks(n, lo), jacobi_blocks(n, hi));
+}
 void orc_jacobi_probe(uint64_t n, uint64_t iters, uint64_t out[7]) {
   uint64_t wg;
-  if (n % 4 == 0) {
-    // launches of more than four sweeps (only on grids of 8192 or more) lose 8 columns per window side, else 4
-    uint64_t halo = (n >= 8192 && iters > 4) ? 8 : 4;
-    uint64_t last = n - 2;                       // last interior column
-    uint64_t win_c = last <= 255 - halo ? 1 : 1 + ceil_div(last - (255 - halo), 256 - 2 * halo);
-    uint64_t win_r = ceil_div(n - 2, 8);
-    wg = ceil_div(win_c * win_r, 4);
+  if (n % 4 != 0) {
+    wg = round8(ceil_div(n, 256) * ceil_div(n - 2, 8));
+  } else if (iters == 0) {
+    wg = jacobi_blocks(n, 4);
   } else {
-    wg = ceil_div(n, 256) * ceil_div(n - 2, 8);
+    uint64_t maxt = n >= 4096 ? 8 : 4;
+    wg = jacobi_chunk_blocks(n, iters > 128 ? 128 : iters, maxt);
+    if (iters > 128 && iters % 128 != 0) wg = std::max(wg, jacobi_chunk_blocks(n, iters % 128, maxt));
   }
   out[0] = 2 * n * n * 4;
-  out[1] = round8(wg); out[2] = 1; out[3] = 1;
+  out[1] = wg; out[2] = 1; out[3] = 1;
   out[4] = 256; out[5] = 1; out[6] = 1;
 }
+// Workgroups per CU: the fused kernels need up to 168 registers per lane (three waves per SIMD);
+// the one-sweep kernel is limited by the 32 wave slots (8 workgroups of 4 waves).
+uint64_t orc_jacobi_residency(uint64_t n) { return n % 4 == 0 ? 3 : 8; }
 
 // fp32 GEMM: A, B, C in fp32.  When k is a multiple of 16 and n a multiple of 4 the tile is the
 // 256 x 256 (256 threads) if that gives at least 256 workgroups, else 128 x 128 (512 threads) if

@@ -117,6 +117,7 @@ _probe_tail = (_P(_u64), _P(mgb_dim3), _P(mgb_dim3))
 mgb_jacobi_probe = _sig("mgb_jacobi_probe", C.c_int, _u32, _u32, *_probe_tail)
 mgb_jacobi_enqueue = _sig("mgb_jacobi_enqueue", C.c_int, _vp, _vp, _vp, _u32, _u32)
 mgb_jacobi_launch_count = _sig("mgb_jacobi_launch_count", _u32, _u32, _u32)
+mgb_jacobi_residency = _sig("mgb_jacobi_residency", _u32, _u32)
 mgb_gemm_f32_residency = _sig("mgb_gemm_f32_residency", _u32, _u32, _u32, _u32)
 mgb_gemm_bf16_residency = _sig("mgb_gemm_bf16_residency", _u32, _u32, _u32, _u32)
 mgb_conv3x3_residency = _sig("mgb_conv3x3_residency", _u32, _u32, _u32, _u32, _u32, _u32, _u32)
@@ -153,7 +154,7 @@ EXPORTS = [
     "mgb_jacobi_probe", "mgb_jacobi_enqueue", "mgb_jacobi_launch_count", "mgb_gemm_f32_probe", "mgb_gemm_f32_enqueue",
     "mgb_gemm_bf16_probe", "mgb_gemm_bf16_enqueue", "mgb_conv3x3_probe", "mgb_conv3x3_enqueue",
     "mgb_cnn_probe", "mgb_cnn_enqueue", "mgb_bfs_work_bytes", "mgb_bfs_probe", "mgb_bfs_enqueue", "mgb_bfs_directed_enqueue",
-    "mgb_cu_trace_enqueue", "mgb_copy_enqueue", "mgb_mfma_loop_enqueue",
+    "mgb_cu_trace_enqueue", "mgb_copy_enqueue", "mgb_mfma_loop_enqueue", "mgb_jacobi_residency",
 ]
 
 

@@ -1,5 +1,5 @@
-// fp32 5-point Jacobi relaxation, up to four sweeps per kernel launch (six on grids that do not
-// fit the last-level cache).
+// fp32 5-point Jacobi relaxation, up to four sweeps per kernel launch in the window form
+// described first, five to eight in the streaming form (grids of 4096 columns and more).
 //
 // One sweep per launch is HBM-bound at 8 bytes per cell update (one read and
 // one write of every cell).  Fusing T sweeps into a launch divides that traffic
@@ -36,11 +36,13 @@ namespace {
 constexpr uint32_t JB_THREADS = 256;          // 4 waves, one window each
 constexpr uint32_t JB_ROWS = JB_ROWS_DEF;     // output rows per window
 constexpr uint32_t JB_WIN = 256;              // window width in columns (64 lanes x 4)
-constexpr uint32_t JB_MAXT = 6;
-// Sweeps fused per launch.  A grid pair that fits the 256 MB last-level cache (n < 8192) gains
-// nothing from more than four (measured: the same time at 4096^2, 5 % slower at 2048^2); beyond
-// it the launch is bound by HBM and six sweeps per pass are 12 % (8192^2) to 23 % (16384^2) faster.
-constexpr uint32_t fused_sweeps(uint32_t n) { return n >= 8192u ? JB_MAXT : 4u; }
+constexpr uint32_t JB_MAXT = 8;
+constexpr uint32_t JS_ROWS = 40;              // output rows per run of the streaming form
+// Sweeps fused per launch.  Launches of up to four sweeps use the window form below; from 4096
+// columns on, launches of five to eight sweeps use the streaming form further down (measured:
+// 4096^2 8 %, 8192^2 9 %, 16384^2 24 % faster than windows of four / six sweeps; smaller grids
+// have too few strips to fill the device with long runs and are slower that way).
+constexpr uint32_t fused_sweeps(uint32_t n) { return n >= 4096u ? JB_MAXT : 4u; }
 // columns lost on each side of a window: at least the sweeps of the launch, a multiple of 4 (16-byte alignment)
 constexpr uint32_t halo_of(uint32_t t) { return t > 4u ? 8u : 4u; }
 constexpr uint32_t step_of(uint32_t halo) { return JB_WIN - 2u * halo; }   // exact columns per window: 248 or 240
@@ -99,7 +101,7 @@ __device__ __forceinline__ void run_sweeps(float4 (&cur)[JB_ROWS + 2u * T], int3
 // n % 4 == 0: rows are 16-byte aligned, every lane's four columns are either
 // all inside the grid or all outside.
 template <uint32_t T>
-__global__ __launch_bounds__(JB_THREADS, T > 4u ? 2 : 3) void jacobi_sweeps(const float* __restrict__ u,
+__global__ __launch_bounds__(JB_THREADS, 3) void jacobi_sweeps(const float* __restrict__ u,
                                                            float* __restrict__ v, uint32_t n,
                                                            uint32_t tiles_c, uint32_t tiles_r) {
   constexpr uint32_t NR = JB_ROWS + 2u * T;               // rows held in registers
@@ -139,6 +141,105 @@ __global__ __launch_bounds__(JB_THREADS, T > 4u ? 2 : 3) void jacobi_sweeps(cons
       if (g <= (int32_t)n - 2) *reinterpret_cast<float4*>(v + (size_t)g * n + c0) = cur[i];
     }
   }
+}
+
+
+// ---- streaming form ----------------------------------------------------------------------
+// A wave owns a strip of 256 columns and walks down `rows` output rows of it.  Row g of the
+// input enters at the top of a pipeline of T stages; stage s holds the two rows it saw last and
+// turns (row g - s - 1, row g - s, row g - s + 1) after s - 1 sweeps into row g - s after s
+// sweeps, so each input row costs T row updates and one row leaves the bottom per step: no row
+// is recomputed except the 2T that warm the pipeline up at the start of a run.  The state is 2T
+// rows (8T registers per lane), input rows are requested JS_PF steps before they are used.
+constexpr uint32_t JS_PF = 6;                 // rows in flight per lane = steps per pass of the loop
+
+// The neighbouring lane's value as a DPP wave shift: an operand modifier of the add that uses it,
+// not an instruction of its own.  Lane 0 / lane 63 have no such neighbour and get zero; what they
+// compute from it lies in the strip's halo.
+__device__ __forceinline__ float from_lane_below(float x) {      // lane l gets lane l - 1's value
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x138, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float from_lane_above(float x) {      // lane l gets lane l + 1's value
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x130, 0xF, 0xF, true));
+}
+
+template <uint32_t T, bool EDGE>
+__device__ __forceinline__ void stream_run(const float* __restrict__ u, float* __restrict__ v, uint32_t n,
+                                           uint32_t c0, int32_t r0, int32_t g_last, bool first_col,
+                                           bool last_col, bool col_ok) {
+  // The products by 0.25 must stay products: fused into the next stage's add they would round
+  // differently when they underflow.
+#pragma clang fp contract(off)
+  const int32_t g_first = r0 - (int32_t)T;                  // first input row of the run
+  const int32_t steps = g_last - r0 + 1 + 2 * (int32_t)T;   // input rows r0 - T .. g_last + T
+  const float* col = u + c0;
+  // Rows outside the grid are never needed, but they are requested: clamp them into it.  A run
+  // away from the grid's top and bottom (EDGE false) reads rows of the grid only.
+  auto row = [&](int32_t g) {
+    const uint32_t gc = EDGE ? (uint32_t)min(max(g, 0), (int32_t)n - 1) : (uint32_t)g;
+    return *reinterpret_cast<const float4*>(col + (size_t)gc * n);
+  };
+  float4 h[T][2];
+#pragma unroll
+  for (uint32_t s = 0; s < T; ++s) h[s][0] = h[s][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 pf[JS_PF];
+#pragma unroll
+  for (uint32_t k = 0; k < JS_PF; ++k) pf[k] = row(g_first + (int32_t)k);
+  for (int32_t jb = 0; jb < steps; jb += (int32_t)JS_PF) {
+#pragma unroll
+    for (uint32_t k = 0; k < JS_PF; ++k) {
+      const int32_t g_in = g_first + jb + (int32_t)k;
+      float4 newest = pf[k];
+      pf[k] = row(g_in + (int32_t)JS_PF);
+#pragma unroll
+      for (uint32_t s = 1; s <= T; ++s) {
+        const float4 north = h[s - 1u][0], c = h[s - 1u][1], south = newest;
+        const float west = from_lane_below(c.w);
+        const float east = from_lane_above(c.x);
+        float4 o;
+        o.x = 0.25f * ((north.x + south.x) + (west + c.y));
+        o.y = 0.25f * ((north.y + south.y) + (c.x + c.z));
+        o.z = 0.25f * ((north.z + south.z) + (c.y + c.w));
+        o.w = 0.25f * ((north.w + south.w) + (c.z + east));
+        if (EDGE) {
+          if (first_col) o.x = c.x;                         // the ring keeps its value
+          if (last_col) o.w = c.w;
+          const int32_t g = g_in - (int32_t)s;              // the row this stage produces
+          if (g <= 0 || g >= (int32_t)n - 1) o = c;
+        }
+        h[s - 1u][0] = c;
+        h[s - 1u][1] = south;
+        newest = o;
+      }
+      const int32_t g_out = g_in - (int32_t)T;
+      if (g_out >= r0 && g_out <= g_last && col_ok)
+        *reinterpret_cast<float4*>(v + (size_t)g_out * n + c0) = newest;
+    }
+  }
+}
+
+template <uint32_t T>
+__global__ __launch_bounds__(JB_THREADS) void jacobi_stream(const float* __restrict__ u, float* __restrict__ v,
+                                                            uint32_t n, uint32_t tiles_c, uint32_t tiles_r,
+                                                            uint32_t rows) {
+  constexpr uint32_t JB_HALO = halo_of(T), JB_STEP = step_of(JB_HALO);
+  uint32_t tc, tr;
+  if (!window_of_wave(tiles_c, tiles_r, &tc, &tr)) return;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t w0 = tc * JB_STEP;
+  const uint32_t c0 = w0 + 4u * lane;
+  if (c0 >= n) return;
+  const int32_t r0 = 1 + (int32_t)(tr * rows);
+  const int32_t g_last = min(r0 + (int32_t)rows - 1, (int32_t)n - 2);
+  const bool first_col = c0 == 0u, last_col = c0 + 4u == n;
+  const bool left_ok = tc == 0u || 4u * lane >= JB_HALO;
+  const bool right_ok = c0 + 4u <= w0 + JB_WIN - JB_HALO || w0 + JB_WIN >= n;
+  const bool col_ok = left_ok && right_ok;
+  // (the loop requests up to 2 * JS_PF rows past the last one it needs)
+  const bool edge = r0 - (int32_t)T <= 0 || g_last + (int32_t)(T + 2u * JS_PF) >= (int32_t)n - 1 || tc == 0u ||
+                    w0 + JB_WIN >= n;
+  if (edge) stream_run<T, true>(u, v, n, c0, r0, g_last, first_col, last_col, col_ok);
+  else stream_run<T, false>(u, v, n, c0, r0, g_last, first_col, last_col, col_ok);
 }
 
 // any n: one column per thread.
@@ -193,37 +294,39 @@ Geometry geometry(uint32_t n, uint32_t JB_HALO) {
   return g;
 }
 
-// Split `iters` sweeps into launches of 1..maxt sweeps such that the number of launches has the
-// parity of iters: the buffers swap once per launch and the result must end in buffer iters % 2.
+// Split `iters` sweeps into launches of 1..maxt sweeps: the fewest launches whose number has the
+// parity of iters (the buffers swap once per launch and the result must end in buffer
+// iters % 2), the sweeps spread evenly over them.
 uint32_t plan_launches(uint32_t iters, uint32_t maxt, uint32_t* plan, uint32_t cap) {
-  uint32_t n = 0;
-  uint32_t left = iters;
-  while (left > 0u && n < cap) {
-    const uint32_t t = left >= maxt ? maxt : left;
-    plan[n++] = t;
-    left -= t;
-  }
-  if (n % 2u != iters % 2u) {
-    // split one launch of >= 2 sweeps in two (exists: otherwise every launch is one sweep and
-    // the parities already agree); the largest one, because two launches of two sweeps cost less
-    // than one of four plus two of one
-    uint32_t pick = n;
-    for (uint32_t i = 0; i < n; ++i)
-      if (plan[i] >= 2u && (pick == n || plan[i] > plan[pick])) pick = i;
-    if (pick < n && n < cap) {
-      const uint32_t a = plan[pick] / 2u;
-      plan[n++] = plan[pick] - a;
-      plan[pick] = a;
-    }
-  }
-  return n;
+  if (iters == 0u) return 0u;
+  uint32_t launches = (iters + maxt - 1u) / maxt;
+  if (launches % 2u != iters % 2u) ++launches;            // then launches < iters: every launch still gets a sweep
+  if (launches > cap) launches = cap;                     // callers plan chunks that fit
+  const uint32_t base = iters / launches, extra = iters % launches;
+  for (uint32_t i = 0; i < launches; ++i) plan[i] = base + (i < extra ? 1u : 0u);
+  return launches;
+}
+
+// workgroups of a launch of t sweeps
+uint32_t blocks_of(uint32_t n, uint32_t t, uint32_t* tiles_x, uint32_t* tiles_y) {
+  const Geometry g = geometry(n, halo_of(t));
+  *tiles_x = g.tiles_x;
+  *tiles_y = g.tiles_y;
+  if (!g.vec4 || t <= 4u) return g.blocks;
+  *tiles_y = (n - 2u + JS_ROWS - 1u) / JS_ROWS;                       // runs per strip
+  const uint32_t groups = (g.tiles_x * *tiles_y + 3u) / 4u;             // four strips' runs per workgroup
+  return ((groups + 7u) / 8u) * 8u;
 }
 
 template <uint32_t T>
 void launch_sweeps(hipStream_t st, const float* src, float* dst, uint32_t n) {
-  const Geometry g = geometry(n, halo_of(T));
-  hipLaunchKernelGGL(jacobi_sweeps<T>, dim3(g.blocks), dim3(JB_THREADS), 0, st, src, dst, n, g.tiles_x,
-                     g.tiles_y);
+  uint32_t tiles_x, tiles_y;
+  const uint32_t blocks = blocks_of(n, T, &tiles_x, &tiles_y);
+  if constexpr (T <= 4u)
+    hipLaunchKernelGGL(jacobi_sweeps<T>, dim3(blocks), dim3(JB_THREADS), 0, st, src, dst, n, tiles_x, tiles_y);
+  else
+    hipLaunchKernelGGL(jacobi_stream<T>, dim3(blocks), dim3(JB_THREADS), 0, st, src, dst, n, tiles_x, tiles_y,
+                       JS_ROWS);
 }
 
 }  // namespace
@@ -235,12 +338,33 @@ int mgb_jacobi_probe(uint32_t n, uint32_t iters, uint64_t* mem_bytes, mgb_dim3* 
   (void)iters;
   if (!mem_bytes || !grid || !block) return MGB_E_INVAL;
   if (n < 3u || n > 65536u) return MGB_E_UNSUPPORTED;
-  // the largest grid among the task's launches: the one with the most sweeps (widest halo)
-  const Geometry g = geometry(n, halo_of(iters < fused_sweeps(n) ? iters : fused_sweeps(n)));
+  // the largest grid among the task's launches (one probe covers them all).  Sweeps are planned
+  // in chunks of 128: every chunk but the last has the plan of the first.
+  uint32_t blocks = geometry(n, 4u).blocks;
+  if (n % 4u == 0u && iters != 0u) {
+    blocks = 0u;
+    const uint32_t chunks[2] = {iters > 128u ? 128u : iters, iters > 128u ? iters % 128u : 0u};
+    for (uint32_t c = 0; c < 2u; ++c) {
+      uint32_t plan[64], tx, ty;
+      const uint32_t np = chunks[c] ? plan_launches(chunks[c], fused_sweeps(n), plan, 64u) : 0u;
+      for (uint32_t i = 0; i < np; ++i) {
+        const uint32_t b = blocks_of(n, plan[i], &tx, &ty);
+        if (b > blocks) blocks = b;
+      }
+    }
+  }
   *mem_bytes = 2ull * n * n * sizeof(float);
-  *grid = mgb_dim3{g.blocks, 1u, 1u};
+  *grid = mgb_dim3{blocks, 1u, 1u};
   *block = mgb_dim3{JB_THREADS, 1u, 1u};
   return MGB_OK;
+}
+
+// workgroups a CU holds: the fused kernels take 146-168 registers per lane (three waves per SIMD,
+// one workgroup's four waves on the four SIMDs); the one-sweep kernel for n % 4 != 0 is limited
+// by the 32 wave slots alone
+uint32_t mgb_jacobi_residency(uint32_t n) {
+  if (n < 3u || n > 65536u) return 0u;
+  return n % 4u == 0u ? 3u : 8u;
 }
 
 uint32_t mgb_jacobi_launch_count(uint32_t n, uint32_t iters) {
@@ -286,7 +410,9 @@ int mgb_jacobi_enqueue(void* stream, float* u0, float* u1, uint32_t n, uint32_t 
         case 3: launch_sweeps<3>(st, src, dst, n); break;
         case 4: launch_sweeps<4>(st, src, dst, n); break;
         case 5: launch_sweeps<5>(st, src, dst, n); break;
-        default: launch_sweeps<6>(st, src, dst, n); break;
+        case 6: launch_sweeps<6>(st, src, dst, n); break;
+        case 7: launch_sweeps<7>(st, src, dst, n); break;
+        default: launch_sweeps<8>(st, src, dst, n); break;
       }
       float* tmp = const_cast<float*>(src);
       src = dst;

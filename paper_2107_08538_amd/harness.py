@@ -41,7 +41,8 @@ def build_task(spec, data, device="cuda:0"):
         probe = mgb.probe_of(mgb.mgb_jacobi_probe, n, it)
         fn = lambda st: mgb.mgb_jacobi_enqueue(st, _ptr(u0), _ptr(u1), n, it)
         return Task(spec, dict(u0=u0, u1=u1), probe, fn, "jacobi_sweeps", int(mgb.mgb_jacobi_launch_count(n, it)),
-                    alg_bytes=8.0 * (n - 2) * (n - 2) * it, alg_flops=4.0 * (n - 2) * (n - 2) * it)
+                    alg_bytes=8.0 * (n - 2) * (n - 2) * it, alg_flops=4.0 * (n - 2) * (n - 2) * it,
+                    wg_per_cu=int(mgb.mgb_jacobi_residency(n)))
     if k == "gemm_f32":
         m, n, kk = p["m"], p["n"], p["k"]
         A, B = torch.from_numpy(data["a"]).to(device), torch.from_numpy(data["b"]).to(device)

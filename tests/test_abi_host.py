@@ -118,6 +118,10 @@ def test_residency_fact_enters_the_demand_and_the_trace():
     for shp in ((1, 416, 416, 3, 32, 1), (8, 416, 416, 32, 64, 2), (8, 104, 104, 128, 128, 1), (1, 104, 104, 128, 128, 1),
                 (2, 416, 416, 3, 64, 1), (1, 5, 6, 5, 7, 1), (8, 208, 208, 64, 64, 1)):
         assert mgb.mgb_conv3x3_residency(*shp) == lib.orc_conv3x3_residency(*[U(x) for x in shp]), shp
+    lib.orc_jacobi_residency.restype = C.c_uint64
+    for n in (3, 4, 77, 512, 4096, 4097, 65536):
+        assert mgb.mgb_jacobi_residency(n) == lib.orc_jacobi_residency(U(n)), n
+    assert (mgb.mgb_jacobi_residency(4096), mgb.mgb_jacobi_residency(77), mgb.mgb_jacobi_residency(2)) == (3, 8, 0)
     lib.orc_bfs_residency.restype = C.c_uint64
     for n in (1, 1000, 1 << 16, 1 << 18, (1 << 18) + 1, 1 << 19, 1 << 20, (1 << 20) + 1, 1 << 24):
         assert mgb.mgb_bfs_residency(n) == lib.orc_bfs_residency(U(n)), n
@@ -142,17 +146,18 @@ def test_grow_in_the_library():
 
 
 def test_jacobi_launch_plan_keeps_buffer_parity():
-    # the result must end in buffer iters % 2, so the number of (fused) launches has that parity
-    for it in list(range(0, 40)) + [100, 127, 128, 129, 1000]:
-        c = mgb.mgb_jacobi_launch_count(4096, it)
-        assert c % 2 == it % 2 and (it + 3) // 4 <= c <= (it + 3) // 4 + (it // 128 + 1)
-        assert mgb.mgb_jacobi_launch_count(77, it) == it             # n % 4 != 0: one sweep per launch
-    assert mgb.mgb_jacobi_launch_count(4096, 100) == 26 and mgb.mgb_jacobi_launch_count(2, 5) == 0
-    # grids that do not fit the last-level cache fuse up to six sweeps
-    for it in list(range(0, 40)) + [50, 100, 127, 128, 129, 1000]:
-        c = mgb.mgb_jacobi_launch_count(16384, it)
-        assert c % 2 == it % 2 and (it + 5) // 6 <= c <= (it + 5) // 6 + (it // 128 + 1)
-    assert mgb.mgb_jacobi_launch_count(16384, 50) == 10 and mgb.mgb_jacobi_launch_count(8192, 6) == 2
+    # the result must end in buffer iters % 2, so the number of (fused) launches has that parity;
+    # up to four sweeps per launch below 4096 columns, up to eight from there on
+    for n, maxt in ((2048, 4), (4096, 8), (16384, 8)):
+        for it in list(range(0, 40)) + [50, 100, 127, 128, 129, 1000]:
+            c = mgb.mgb_jacobi_launch_count(n, it)
+            fewest = (it + maxt - 1) // maxt
+            assert c % 2 == it % 2 and fewest <= c <= fewest + (it // 128 + 1), (n, it, c)
+    for it in (0, 1, 5, 100):
+        assert mgb.mgb_jacobi_launch_count(77, it) == it                 # n % 4 != 0: one sweep per launch
+    assert mgb.mgb_jacobi_launch_count(2048, 100) == 26 and mgb.mgb_jacobi_launch_count(2, 5) == 0
+    assert mgb.mgb_jacobi_launch_count(4096, 100) == 14 and mgb.mgb_jacobi_launch_count(16384, 50) == 8
+    assert mgb.mgb_jacobi_launch_count(8192, 8) == 2 and mgb.mgb_jacobi_launch_count(8192, 7) == 1
 
 
 def test_resident_task_limit():
@@ -307,7 +312,8 @@ def test_probe_functions_agree_with_checker_formulas():
         mem, grid, block = mgb.probe_of(mgb.mgb_jacobi_probe, n, 10)
         oracle.lib().orc_jacobi_probe(C.c_uint64(n), C.c_uint64(10), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), n
-    for n, it in ((8192, 1), (8192, 4), (8192, 5), (8192, 6), (8192, 100), (8188, 50), (16384, 50), (65536, 7), (4096, 6)):
+    for n, it in ((8192, 1), (8192, 4), (8192, 5), (8192, 6), (8192, 100), (8188, 50), (16384, 50), (65536, 7), (4096, 6),
+                  (4096, 96), (4096, 100), (4096, 8), (4096, 9), (4092, 7), (4100, 200), (2048, 100), (4096, 1000), (4096, 0)):
         mem, grid, block = mgb.probe_of(mgb.mgb_jacobi_probe, n, it)
         oracle.lib().orc_jacobi_probe(C.c_uint64(n), C.c_uint64(it), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (n, it)

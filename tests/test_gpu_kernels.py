@@ -74,12 +74,14 @@ def test_jacobi_full_size_mix16_task():
     assert np.array_equal(got, oracle.jacobi_f32(u, iters))
 
 
-@pytest.mark.parametrize("n,iters", [(8200, 5), (8192, 12), (8444, 17)])
-def test_jacobi_deeper_fusion_on_grids_beyond_the_last_level_cache(n, iters):
-    # from 8192 columns on, launches fuse five or six sweeps (windows that lose eight columns per side):
-    # 5 = one launch of five; 12 = six + six; 17 = 6 + 6 + 5 sweeps; ragged last windows in both directions
+@pytest.mark.parametrize("n,iters,launches", [(8200, 5, 1), (8192, 12, 2), (8444, 17, 3), (4100, 7, 1), (4096, 13, 3),
+                                              (5000, 21, 3), (4344, 32, 4), (4096, 6, 2)])
+def test_jacobi_streaming_launches_of_five_to_eight_sweeps(n, iters, launches):
+    # from 4096 columns on a launch fuses up to eight sweeps; launches of five and more stream down
+    # strips of 240 columns in runs of 40 rows (ragged last strips and runs in every case here),
+    # launches of up to four (13 = 5 + 4 + 4, 6 = 3 + 3) use the window kernel
     u = W.jacobi_field(321, n)
-    assert mgb.mgb_jacobi_launch_count(n, iters) == {5: 1, 12: 2, 17: 3}[iters]
+    assert mgb.mgb_jacobi_launch_count(n, iters) == launches
     got = run_jacobi(u, iters)
     assert np.array_equal(got, oracle.jacobi_f32(u, iters))
 

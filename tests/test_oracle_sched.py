@@ -437,7 +437,7 @@ def test_probe_formulas_match_stated_footprints():
     assert out[0] == 2 * 2 ** 30                     # "about 2 GiB" per Jacobi 16384^2 task
     assert out[1] == 34304 and out[4] == 256           # 67 x 2048 windows, four per workgroup
     oracle.lib().orc_jacobi_probe(C.c_uint64(16384), C.c_uint64(50), out)
-    assert out[0] == 2 * 2 ** 30 and out[1] == 35328   # six sweeps per launch: steps of 240 columns, 69 x 2048 windows
+    assert out[0] == 2 * 2 ** 30 and out[1] == 7080    # 8 launches of 6-7 sweeps: 69 strips of 240 columns x 410 runs of 40 rows
     oracle.lib().orc_gemm_f32_probe(C.c_uint64(32768), C.c_uint64(32768), C.c_uint64(32768), out)
     assert out[0] == 12 * 2 ** 30                    # "about 12 GiB" per GEMM 32768^3 task
     assert out[1] == 128 * 128 and out[4] == 256       # 256 x 256 tiles, four waves each
