@@ -25,14 +25,24 @@ extern "C" {
 // from n = 4096 on), planned in chunks of 128 sweeps: the fewest launches whose number has the
 // parity of the chunk, the sweeps spread evenly over them.  A launch of t <= 4 sweeps: a wave takes a window of 256 columns x 8 output
 // rows, windows step by 248 columns (4 stale columns on each side of a window, none next to the
-// grid's own boundary: the first window yields columns 1..251).  A launch of t > 4 sweeps: a wave
+// grid's own boundary).  A launch of t > 4 sweeps: a wave
 // takes a strip of 256 columns stepping by 240 (8 stale columns per side) and runs of 40 output
-// rows.  Four waves per 256-thread workgroup, grids rounded up to a multiple of 8.  One probe
+// rows (fewer or more on grids that give less than four rounds of 2048 waves, see below).  Four waves per 256-thread workgroup, grids rounded up to a multiple of 8.  One probe
 // covers all launches of the task: its grid is the largest of them.
 static uint64_t jacobi_blocks(uint64_t n, uint64_t t) {
   uint64_t halo = t > 4 ? 8 : 4, rows = t > 4 ? 40 : 8;
-  uint64_t last = n - 2;                       // last interior column
-  uint64_t win_c = last <= 255 - halo ? 1 : 1 + ceil_div(last - (255 - halo), 256 - 2 * halo);
+  // windows start every 256 - 2 * halo columns; the last one is the first that reaches column n - 1
+  uint64_t win_c = n <= 256 ? 1 : 1 + ceil_div(n - 256, 256 - 2 * halo);
+  if (t > 4) {
+    // runs of 40 rows, unless that gives fewer than 4 x 2048 waves: then as many runs per strip
+    // as make the waves a whole number (the nearest, at least one) of rounds of 2048
+    uint64_t waves = win_c * ceil_div(n - 2, 40);
+    if (waves < 4 * 2048) {
+      uint64_t rounds = std::max<uint64_t>(1, (waves + 1024) / 2048);
+      uint64_t runs = std::max<uint64_t>(1, rounds * 2048 / win_c);
+      rows = ceil_div(n - 2, runs);
+    }
+  }
   uint64_t win_r = ceil_div(n - 2, rows);
   return round8(ceil_div(win_c * win_r, 4));
 }
@@ -58,9 +68,10 @@ void orc_jacobi_probe(uint64_t n, uint64_t iters, uint64_t out[7]) {
   out[1] = wg; out[2] = 1; out[3] = 1;
   out[4] = 256; out[5] = 1; out[6] = 1;
 }
-// Workgroups per CU: the fused kernels need up to 168 registers per lane (three waves per SIMD);
-// the one-sweep kernel is limited by the 32 wave slots (8 workgroups of 4 waves).
-uint64_t orc_jacobi_residency(uint64_t n) { return n % 4 == 0 ? 3 : 8; }
+// Workgroups per CU: the window kernels need up to 168 registers per lane (three waves per SIMD),
+// the streaming kernels used from 4096 columns on up to 224 (two); the one-sweep kernel is limited
+// by the 32 wave slots (8 workgroups of 4 waves).
+uint64_t orc_jacobi_residency(uint64_t n) { return n % 4 != 0 ? 8 : (n >= 4096 ? 2 : 3); }
 
 // fp32 GEMM: A, B, C in fp32.  When k is a multiple of 16 and n a multiple of 4 the tile is the
 // 256 x 256 (256 threads) if that gives at least 256 workgroups, else 128 x 128 (512 threads) if

@@ -37,7 +37,7 @@ constexpr uint32_t JB_THREADS = 256;          // 4 waves, one window each
 constexpr uint32_t JB_ROWS = JB_ROWS_DEF;     // output rows per window
 constexpr uint32_t JB_WIN = 256;              // window width in columns (64 lanes x 4)
 constexpr uint32_t JB_MAXT = 8;
-constexpr uint32_t JS_ROWS = 40;              // output rows per run of the streaming form
+constexpr uint32_t JS_ROWS = 40;              // output rows per run of the streaming form (large grids)
 // Sweeps fused per launch.  Launches of up to four sweeps use the window form below; from 4096
 // columns on, launches of five to eight sweeps use the streaming form further down (measured:
 // 4096^2 8 %, 8192^2 9 %, 16384^2 24 % faster than windows of four / six sweeps; smaller grids
@@ -163,58 +163,70 @@ __device__ __forceinline__ float from_lane_above(float x) {      // lane l gets 
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x130, 0xF, 0xF, true));
 }
 
-template <uint32_t T, bool EDGE>
-__device__ __forceinline__ void stream_run(const float* __restrict__ u, float* __restrict__ v, uint32_t n,
-                                           uint32_t c0, int32_t r0, int32_t g_last, bool first_col,
-                                           bool last_col, bool col_ok) {
+// JS_PF steps of a run, starting with input row g_first + jb.  COLS: the strip touches the
+// grid's left or right ring column, whose cells keep their value.  ROWS: some row produced in
+// these steps may be the grid's top or bottom ring row (or lie outside the grid): tested per row.
+template <uint32_t T, bool COLS, bool ROWS>
+__device__ __forceinline__ void stream_steps(float4 (&h)[T][2], float4 (&pf)[JS_PF], const float* __restrict__ col,
+                                             float* __restrict__ v, uint32_t n, uint32_t c0, int32_t g_first,
+                                             int32_t jb, int32_t r0, int32_t g_last, bool first_col,
+                                             bool last_col, bool col_ok) {
   // The products by 0.25 must stay products: fused into the next stage's add they would round
   // differently when they underflow.
 #pragma clang fp contract(off)
+#pragma unroll
+  for (uint32_t k = 0; k < JS_PF; ++k) {
+    const int32_t g_in = g_first + jb + (int32_t)k;
+    float4 newest = pf[k];
+    // rows outside the grid are never needed, but they are requested: clamp them into it
+    pf[k] = *reinterpret_cast<const float4*>(col + (size_t)min(max(g_in + (int32_t)JS_PF, 0), (int32_t)n - 1) * n);
+#pragma unroll
+    for (uint32_t s = 1; s <= T; ++s) {
+      const float4 north = h[s - 1u][0], c = h[s - 1u][1], south = newest;
+      float4 o;
+      const int32_t g = g_in - (int32_t)s;                // the row this stage produces (wave-uniform)
+      if (ROWS && (g <= 0 || g >= (int32_t)n - 1)) {
+        o = c;                                            // the ring keeps its value
+      } else {
+        const float west = from_lane_below(c.w);
+        const float east = from_lane_above(c.x);
+        o.x = 0.25f * ((north.x + south.x) + (west + c.y));
+        o.y = 0.25f * ((north.y + south.y) + (c.x + c.z));
+        o.z = 0.25f * ((north.z + south.z) + (c.y + c.w));
+        o.w = 0.25f * ((north.w + south.w) + (c.z + east));
+        if (COLS) {
+          if (first_col) o.x = c.x;
+          if (last_col) o.w = c.w;
+        }
+      }
+      h[s - 1u][0] = c;
+      h[s - 1u][1] = south;
+      newest = o;
+    }
+    const int32_t g_out = g_in - (int32_t)T;
+    if (g_out >= r0 && g_out <= g_last && col_ok) *reinterpret_cast<float4*>(v + (size_t)g_out * n + c0) = newest;
+  }
+}
+
+template <uint32_t T, bool COLS>
+__device__ __forceinline__ void stream_run(const float* __restrict__ u, float* __restrict__ v, uint32_t n,
+                                           uint32_t c0, int32_t r0, int32_t g_last, bool first_col,
+                                           bool last_col, bool col_ok) {
   const int32_t g_first = r0 - (int32_t)T;                  // first input row of the run
   const int32_t steps = g_last - r0 + 1 + 2 * (int32_t)T;   // input rows r0 - T .. g_last + T
   const float* col = u + c0;
-  // Rows outside the grid are never needed, but they are requested: clamp them into it.  A run
-  // away from the grid's top and bottom (EDGE false) reads rows of the grid only.
-  auto row = [&](int32_t g) {
-    const uint32_t gc = EDGE ? (uint32_t)min(max(g, 0), (int32_t)n - 1) : (uint32_t)g;
-    return *reinterpret_cast<const float4*>(col + (size_t)gc * n);
-  };
   float4 h[T][2];
 #pragma unroll
   for (uint32_t s = 0; s < T; ++s) h[s][0] = h[s][1] = make_float4(0.f, 0.f, 0.f, 0.f);
   float4 pf[JS_PF];
 #pragma unroll
-  for (uint32_t k = 0; k < JS_PF; ++k) pf[k] = row(g_first + (int32_t)k);
+  for (uint32_t k = 0; k < JS_PF; ++k)
+    pf[k] = *reinterpret_cast<const float4*>(col + (size_t)min(max(g_first + (int32_t)k, 0), (int32_t)n - 1) * n);
   for (int32_t jb = 0; jb < steps; jb += (int32_t)JS_PF) {
-#pragma unroll
-    for (uint32_t k = 0; k < JS_PF; ++k) {
-      const int32_t g_in = g_first + jb + (int32_t)k;
-      float4 newest = pf[k];
-      pf[k] = row(g_in + (int32_t)JS_PF);
-#pragma unroll
-      for (uint32_t s = 1; s <= T; ++s) {
-        const float4 north = h[s - 1u][0], c = h[s - 1u][1], south = newest;
-        const float west = from_lane_below(c.w);
-        const float east = from_lane_above(c.x);
-        float4 o;
-        o.x = 0.25f * ((north.x + south.x) + (west + c.y));
-        o.y = 0.25f * ((north.y + south.y) + (c.x + c.z));
-        o.z = 0.25f * ((north.z + south.z) + (c.y + c.w));
-        o.w = 0.25f * ((north.w + south.w) + (c.z + east));
-        if (EDGE) {
-          if (first_col) o.x = c.x;                         // the ring keeps its value
-          if (last_col) o.w = c.w;
-          const int32_t g = g_in - (int32_t)s;              // the row this stage produces
-          if (g <= 0 || g >= (int32_t)n - 1) o = c;
-        }
-        h[s - 1u][0] = c;
-        h[s - 1u][1] = south;
-        newest = o;
-      }
-      const int32_t g_out = g_in - (int32_t)T;
-      if (g_out >= r0 && g_out <= g_last && col_ok)
-        *reinterpret_cast<float4*>(v + (size_t)g_out * n + c0) = newest;
-    }
+    // rows produced in this pass: g_first + jb - T (last stage, first step) .. g_first + jb + JS_PF - 2
+    const bool ring_rows = g_first + jb - (int32_t)T <= 0 || g_first + jb + (int32_t)JS_PF - 2 >= (int32_t)n - 1;
+    if (ring_rows) stream_steps<T, COLS, true>(h, pf, col, v, n, c0, g_first, jb, r0, g_last, first_col, last_col, col_ok);
+    else stream_steps<T, COLS, false>(h, pf, col, v, n, c0, g_first, jb, r0, g_last, first_col, last_col, col_ok);
   }
 }
 
@@ -225,6 +237,9 @@ __global__ __launch_bounds__(JB_THREADS) void jacobi_stream(const float* __restr
   constexpr uint32_t JB_HALO = halo_of(T), JB_STEP = step_of(JB_HALO);
   uint32_t tc, tr;
   if (!window_of_wave(tiles_c, tiles_r, &tc, &tr)) return;
+  // (the run is the same for the whole wave: said so, the tests on its rows are scalar)
+  tr = (uint32_t)__builtin_amdgcn_readfirstlane((int)tr);
+  tc = (uint32_t)__builtin_amdgcn_readfirstlane((int)tc);
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t w0 = tc * JB_STEP;
   const uint32_t c0 = w0 + 4u * lane;
@@ -235,10 +250,9 @@ __global__ __launch_bounds__(JB_THREADS) void jacobi_stream(const float* __restr
   const bool left_ok = tc == 0u || 4u * lane >= JB_HALO;
   const bool right_ok = c0 + 4u <= w0 + JB_WIN - JB_HALO || w0 + JB_WIN >= n;
   const bool col_ok = left_ok && right_ok;
-  // (the loop requests up to 2 * JS_PF rows past the last one it needs)
-  const bool edge = r0 - (int32_t)T <= 0 || g_last + (int32_t)(T + 2u * JS_PF) >= (int32_t)n - 1 || tc == 0u ||
-                    w0 + JB_WIN >= n;
-  if (edge) stream_run<T, true>(u, v, n, c0, r0, g_last, first_col, last_col, col_ok);
+  // only strips next to the grid's left / right ring pay for keeping it (two selects per row
+  // update); the top and bottom ring rows are tested for in the passes that can meet them
+  if (tc == 0u || w0 + JB_WIN >= n) stream_run<T, true>(u, v, n, c0, r0, g_last, first_col, last_col, col_ok);
   else stream_run<T, false>(u, v, n, c0, r0, g_last, first_col, last_col, col_ok);
 }
 
@@ -278,11 +292,9 @@ Geometry geometry(uint32_t n, uint32_t JB_HALO) {
   Geometry g;
   g.vec4 = (n % 4u) == 0u;
   if (g.vec4) {
-    // windows step by 248 columns; the first one also covers columns 1..3 next to the ring
-    const uint32_t interior_last = n - 2u;
-    g.tiles_x = interior_last <= JB_WIN - JB_HALO - 1u
-                    ? 1u
-                    : 1u + (interior_last - (JB_WIN - JB_HALO - 1u) + JB_STEP - 1u) / JB_STEP;
+    // windows step by 248 (240) columns; a window next to the grid's ring loses nothing on that
+    // side, so the last window is the first one that reaches the right edge
+    g.tiles_x = n <= JB_WIN ? 1u : 1u + (n - JB_WIN + JB_STEP - 1u) / JB_STEP;
     g.tiles_y = (n - 2u + JB_ROWS - 1u) / JB_ROWS;
     const uint32_t groups = (g.tiles_x * g.tiles_y + 3u) / 4u;       // four windows per workgroup
     g.blocks = ((groups + 7u) / 8u) * 8u;                             // whole rounds over the 8 XCDs
@@ -308,25 +320,40 @@ uint32_t plan_launches(uint32_t iters, uint32_t maxt, uint32_t* plan, uint32_t c
 }
 
 // workgroups of a launch of t sweeps
-uint32_t blocks_of(uint32_t n, uint32_t t, uint32_t* tiles_x, uint32_t* tiles_y) {
+// Output rows per run of the streaming form.  Its waves live as long as the launch and a SIMD
+// holds two of them (registers), so what counts is that every SIMD gets the same number: with
+// fewer than four rounds of 2048 waves at JS_ROWS rows per run, the rows are chosen to make the
+// waves a whole number of such rounds (4096^2: 35 rows, 17 strips x 117 runs = 1989 waves).
+uint32_t stream_rows(uint32_t n, uint32_t strips) {
+  const uint32_t waves = strips * ((n - 2u + JS_ROWS - 1u) / JS_ROWS);
+  if (waves >= 4u * 2048u) return JS_ROWS;
+  uint32_t rounds = (waves + 1024u) / 2048u;
+  if (rounds == 0u) rounds = 1u;
+  uint32_t runs = rounds * 2048u / strips;
+  if (runs == 0u) runs = 1u;
+  return (n - 2u + runs - 1u) / runs;
+}
+
+uint32_t blocks_of(uint32_t n, uint32_t t, uint32_t* tiles_x, uint32_t* tiles_y, uint32_t* rows) {
   const Geometry g = geometry(n, halo_of(t));
   *tiles_x = g.tiles_x;
   *tiles_y = g.tiles_y;
   if (!g.vec4 || t <= 4u) return g.blocks;
-  *tiles_y = (n - 2u + JS_ROWS - 1u) / JS_ROWS;                       // runs per strip
+  *rows = stream_rows(n, g.tiles_x);
+  *tiles_y = (n - 2u + *rows - 1u) / *rows;                           // runs per strip
   const uint32_t groups = (g.tiles_x * *tiles_y + 3u) / 4u;             // four strips' runs per workgroup
   return ((groups + 7u) / 8u) * 8u;
 }
 
 template <uint32_t T>
 void launch_sweeps(hipStream_t st, const float* src, float* dst, uint32_t n) {
-  uint32_t tiles_x, tiles_y;
-  const uint32_t blocks = blocks_of(n, T, &tiles_x, &tiles_y);
+  uint32_t tiles_x, tiles_y, rows = 0;
+  const uint32_t blocks = blocks_of(n, T, &tiles_x, &tiles_y, &rows);
   if constexpr (T <= 4u)
     hipLaunchKernelGGL(jacobi_sweeps<T>, dim3(blocks), dim3(JB_THREADS), 0, st, src, dst, n, tiles_x, tiles_y);
   else
     hipLaunchKernelGGL(jacobi_stream<T>, dim3(blocks), dim3(JB_THREADS), 0, st, src, dst, n, tiles_x, tiles_y,
-                       JS_ROWS);
+                       rows);
 }
 
 }  // namespace
@@ -345,10 +372,10 @@ int mgb_jacobi_probe(uint32_t n, uint32_t iters, uint64_t* mem_bytes, mgb_dim3* 
     blocks = 0u;
     const uint32_t chunks[2] = {iters > 128u ? 128u : iters, iters > 128u ? iters % 128u : 0u};
     for (uint32_t c = 0; c < 2u; ++c) {
-      uint32_t plan[64], tx, ty;
+      uint32_t plan[64], tx, ty, rows;
       const uint32_t np = chunks[c] ? plan_launches(chunks[c], fused_sweeps(n), plan, 64u) : 0u;
       for (uint32_t i = 0; i < np; ++i) {
-        const uint32_t b = blocks_of(n, plan[i], &tx, &ty);
+        const uint32_t b = blocks_of(n, plan[i], &tx, &ty, &rows);
         if (b > blocks) blocks = b;
       }
     }
@@ -359,12 +386,14 @@ int mgb_jacobi_probe(uint32_t n, uint32_t iters, uint64_t* mem_bytes, mgb_dim3* 
   return MGB_OK;
 }
 
-// workgroups a CU holds: the fused kernels take 146-168 registers per lane (three waves per SIMD,
-// one workgroup's four waves on the four SIMDs); the one-sweep kernel for n % 4 != 0 is limited
-// by the 32 wave slots alone
+// workgroups a CU holds (one workgroup's four waves go to the four SIMDs): the window kernels
+// take up to 168 registers per lane (three waves per SIMD), the streaming kernels of grids from
+// 4096 columns on up to 224 (two); the one-sweep kernel for n % 4 != 0 is limited by the 32 wave
+// slots alone
 uint32_t mgb_jacobi_residency(uint32_t n) {
   if (n < 3u || n > 65536u) return 0u;
-  return n % 4u == 0u ? 3u : 8u;
+  if (n % 4u != 0u) return 8u;
+  return n >= 4096u ? 2u : 3u;
 }
 
 uint32_t mgb_jacobi_launch_count(uint32_t n, uint32_t iters) {

@@ -121,7 +121,7 @@ def test_residency_fact_enters_the_demand_and_the_trace():
     lib.orc_jacobi_residency.restype = C.c_uint64
     for n in (3, 4, 77, 512, 4096, 4097, 65536):
         assert mgb.mgb_jacobi_residency(n) == lib.orc_jacobi_residency(U(n)), n
-    assert (mgb.mgb_jacobi_residency(4096), mgb.mgb_jacobi_residency(77), mgb.mgb_jacobi_residency(2)) == (3, 8, 0)
+    assert (mgb.mgb_jacobi_residency(4096), mgb.mgb_jacobi_residency(2048), mgb.mgb_jacobi_residency(77), mgb.mgb_jacobi_residency(2)) == (2, 3, 8, 0)
     lib.orc_bfs_residency.restype = C.c_uint64
     for n in (1, 1000, 1 << 16, 1 << 18, (1 << 18) + 1, 1 << 19, 1 << 20, (1 << 20) + 1, 1 << 24):
         assert mgb.mgb_bfs_residency(n) == lib.orc_bfs_residency(U(n)), n

@@ -33,10 +33,10 @@ def test_mix16_full_size_outputs_and_decisions():
     dec = assert_trace_matches_replay(s.desc, trace)
     check_ledger_invariants(s.desc, trace)
     assert (dec["kind"] == oracle.D_ADMIT).sum() == 16
-    # demand the probes carried: GEMM 4096^3 and BFS 2^20 (256 workgroups, one per CU because each
-    # keeps the 128 KiB frontier bitmap in LDS) = the whole device (8 granules of 32 CUs); Jacobi 4096^2
-    # (464 workgroups of long-running waves, three per CU) = 155 CUs = 5 granules, granted as a block of 8
-    want = {"gemm_f32": 8, "jacobi": 5, "bfs": 8}
+    # demand the probes carried: GEMM 4096^3, BFS 2^20 (256 workgroups, one per CU because each keeps
+    # the 128 KiB frontier bitmap in LDS) and Jacobi 4096^2 (504 workgroups of long-running waves, two
+    # per CU) = the whole device (8 granules of 32 CUs)
+    want = {"gemm_f32": 8, "jacobi": 8, "bfs": 8}
     for r, t in zip(rec, tasks):
         assert r["granules"] == want[t.spec.kind]
     assert s.destroy() == 0
