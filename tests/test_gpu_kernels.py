@@ -67,6 +67,17 @@ def test_jacobi_nonzero_ring_and_constant_field():
     assert np.array_equal(run_jacobi(u, 4), oracle.jacobi_f32(u, 4))
 
 
+def test_jacobi_streaming_keeps_a_nonzero_ring():
+    # the streaming launches (4096 columns and more, five to eight sweeps) with values on the ring
+    n = 4100
+    rng = np.random.default_rng(1)
+    u = rng.random((n, n), dtype=np.float32)
+    got = run_jacobi(u, 7)
+    want = oracle.jacobi_f32(u, 7)
+    assert np.array_equal(got, want)
+    assert np.array_equal(got[0], u[0]) and np.array_equal(got[:, -1], u[:, -1])
+
+
 def test_jacobi_full_size_mix16_task():
     n, iters = 4096, 100
     u = W.jacobi_field(123, n)
