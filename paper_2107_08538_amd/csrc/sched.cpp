@@ -88,6 +88,17 @@ struct mgb_sched {
   uint32_t n_running_now = 0;
   bool oom = false;                          // try_admit: CG task that would have run out of memory
   std::vector<uint64_t> crashed;             // tickets rejected while queued, until their waiter collects them
+  // A thread blocked in mgb_task_wait sleeps on a condition variable of its own, registered here
+  // under its ticket, so that a release wakes only the waiters it admits (with one shared
+  // variable every release woke all of them, and the admitted one queued for the lock behind the
+  // rest).  A second thread waiting on the same ticket uses the shared variable `cv`.
+  std::unordered_map<uint64_t, std::condition_variable*> waiters;
+  uint32_t shared_waiters = 0;
+  void wake(uint64_t ticket) {
+    auto w = waiters.find(ticket);
+    if (w != waiters.end()) w->second->notify_one();
+    if (shared_waiters != 0u) cv.notify_all();
+  }
   std::vector<mgb_trace_rec> trace;          // records trace_base .. trace_base + size - 1
   uint64_t trace_base = 0;                   // seq of trace[0]: the oldest records are dropped at kTraceCap
   // backend: idle masked streams (mask, stream, when last used), idle timing events
@@ -217,10 +228,12 @@ struct mgb_sched {
       if (try_admit(t)) {
         waitq.erase(waitq.begin() + (long)i);
         log(MGB_EV_ADMIT, &t, 0, 0, 0, {}, {}, t.granted, 0, cause);
+        wake(t.ticket);
         any = true;
       } else if (oom) {
         log(MGB_EV_REJECT, &t, 0, 0, 0, {}, {}, 0, MGB_E_OOM, cause);
         crashed.push_back(t.ticket);
+        wake(t.ticket);
         tasks.erase(waitq[i]);
         waitq.erase(waitq.begin() + (long)i);
         any = true;                                   // its waiter must wake up and collect the error
@@ -359,7 +372,7 @@ struct mgb_sched {
     log(MGB_EV_RELEASE, &t, 0, 0, 0, {}, {}, t.granted, 0, cause);
     unbind_stream(t);
     tasks.erase(it);
-    if (rescan(cause)) cv.notify_all();
+    rescan(cause);                              // wakes whom it admits
     return MGB_OK;
   }
 
@@ -553,11 +566,16 @@ int mgb_task_wait(mgb_sched* s, uint64_t ticket, int64_t timeout_ns, mgb_placeme
   };
   if (collect_crash()) return MGB_E_OOM;
   if (s->tasks.find(ticket) == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;
-  if (timeout_ns < 0) {
-    s->cv.wait(lk, admitted);
-  } else if (!s->cv.wait_for(lk, std::chrono::nanoseconds(timeout_ns), admitted)) {
-    return MGB_TIMEOUT;
-  }
+  std::condition_variable own;
+  const bool first = s->waiters.emplace(ticket, &own).second;
+  std::condition_variable& on = first ? own : s->cv;
+  if (!first) ++s->shared_waiters;
+  bool in_time = true;
+  if (timeout_ns < 0) on.wait(lk, admitted);
+  else in_time = on.wait_for(lk, std::chrono::nanoseconds(timeout_ns), admitted);
+  if (first) s->waiters.erase(ticket);
+  else --s->shared_waiters;
+  if (!in_time) return MGB_TIMEOUT;
   auto it = s->tasks.find(ticket);
   if (it == s->tasks.end()) return collect_crash() ? MGB_E_OOM : MGB_E_UNKNOWN_TICKET;  // rejected / cancelled meanwhile
   return s->fill(it->second, out, lk);
@@ -580,8 +598,8 @@ int mgb_task_cancel(mgb_sched* s, uint64_t ticket) {
   s->log(MGB_EV_CANCELLED, &it->second, 0, 0, 0, {}, {}, 0, 0, cause);
   s->waitq.erase(std::find(s->waitq.begin(), s->waitq.end(), ticket));
   s->tasks.erase(it);
+  s->wake(ticket);                              // a thread waiting for the cancelled task learns of it
   s->rescan(cause);
-  s->cv.notify_all();
   return MGB_OK;
 }
 
