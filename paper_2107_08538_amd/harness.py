@@ -156,7 +156,8 @@ def run_mix(sched, tasks, use_arrivals=True, time_scale=1.0, workers=None):
                     dt = due - time.perf_counter()
                     if dt <= 0:
                         break
-                    time.sleep(dt if dt > 2e-4 else 0)
+                    # (a sleep overshoots by 50-100 us: sleep short of the arrival, then yield in a loop)
+                    time.sleep(dt - 2e-4 if dt > 4e-4 else 0)
                 rec[i]["arrival"] = t.spec.arrival_s * time_scale
             else:
                 rec[i]["arrival"] = 0.0
