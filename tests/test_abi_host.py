@@ -4,6 +4,7 @@ import ctypes as C
 import os
 import re
 import threading
+import time
 
 import numpy as np
 import pytest
@@ -250,6 +251,38 @@ def test_cg_policy_equals_replay_and_wakes_the_waiter_of_a_dead_job():
         dec = assert_trace_matches_replay(s.desc, s.trace())
         assert ((dec["kind"] == oracle.D_REJECT) & (dec["code"] == mgb.MGB_E_OOM)).sum() > 3
         assert s.stats().free_bytes == 10_000 and s.stats().n_running == 0
+
+
+def test_a_release_wakes_exactly_the_waiters_it_concerns():
+    # every waiter sleeps on a condition variable of its own; two threads on one ticket share the
+    # scheduler's; a cancelled ticket's waiter is told; waiters of tasks that still do not fit sleep on
+    s = _null(mem_cap_bytes=1000)
+    whole, b = (100000, 1, 1), (256, 1, 1)
+    rc, p1 = s.probe(1, 100, whole, b)
+    assert rc == mgb.MGB_OK
+    waits = [s.probe(i, 100, whole, b) for i in (2, 3, 4)]
+    assert [rc for rc, _ in waits] == [mgb.MGB_WAIT] * 3
+    t2, t3, t4 = (pl.ticket for _, pl in waits)
+    got = {}
+    def waiter(name, ticket, timeout=-1):
+        got[name] = s.wait(ticket, timeout)[0]
+    threads = [threading.Thread(target=waiter, args=("a2", t2)), threading.Thread(target=waiter, args=("b2", t2)),
+               threading.Thread(target=waiter, args=("a3", t3)), threading.Thread(target=waiter, args=("a4", t4))]
+    for th in threads:
+        th.start()
+    time.sleep(0.05)
+    assert s.cancel(t4) == mgb.MGB_OK                     # its waiter returns with "unknown ticket"
+    threads[3].join(10)
+    assert got == {"a4": mgb.MGB_E_UNKNOWN_TICKET}
+    assert s.complete(p1.ticket) == mgb.MGB_OK            # admits task 2 only (whole-device demands)
+    threads[0].join(10)
+    threads[1].join(10)
+    assert got["a2"] == mgb.MGB_OK and got["b2"] == mgb.MGB_OK and "a3" not in got
+    assert s.complete(t2) == mgb.MGB_OK
+    threads[2].join(10)
+    assert got["a3"] == mgb.MGB_OK
+    assert s.wait(t3, 1000)[0] == mgb.MGB_OK              # already admitted: returns at once
+    assert s.complete(t3) == mgb.MGB_OK and s.destroy() == 0
 
 
 def test_small_device_and_other_granule_shapes_equal_replay():
