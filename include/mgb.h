@@ -408,6 +408,19 @@ int mgb_bfs_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx
 int mgb_bfs_directed_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
                              uint32_t source, int32_t* level, void* work, uint32_t* depth);
 
+/* mgb_bfs_enqueue for callers that cannot allocate device memory (code that runs under stream
+ * capture rules of its own, tight serving loops, harnesses that forbid hipMalloc): the work area
+ * is a static device array inside the library (33.5 MiB, held by each device the library runs on
+ * until the process ends) instead of a caller buffer.  The call allocates and frees nothing.
+ * n <= 2^22 vertices, else MGB_E_TOO_BIG (mgb_last_error has the text) and nothing is launched;
+ * otherwise arguments, result and errors are those of mgb_bfs_enqueue.  `stream` must belong to
+ * the calling thread's current device.  All calls on one device share that device's array: the
+ * call itself re-initialises what it reads, but two calls that overlap in time on one device
+ * race (run them one after the other, or give the second one mgb_bfs_enqueue and its own work
+ * buffer).                                                                      */
+int mgb_bfs_enqueue_static(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
+                           uint32_t source, int32_t* level, uint32_t* depth);
+
 /* Diagnostic: launch n_blocks one-wave workgroups on `stream`; workgroup i
  * stores where it ran in out[i] (device, uint32): (xcd << 8) | (shader engine
  * << 4) | CU index within the engine.  Shows which physical CUs a placement's

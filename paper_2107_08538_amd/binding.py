@@ -138,6 +138,7 @@ mgb_bfs_work_bytes = _sig("mgb_bfs_work_bytes", _u64, _u32)
 mgb_bfs_probe = _sig("mgb_bfs_probe", C.c_int, _u32, _u64, *_probe_tail)
 mgb_bfs_enqueue = _sig("mgb_bfs_enqueue", C.c_int, _vp, _vp, _vp, _u32, _u32, _vp, _vp, _P(_u32))
 mgb_bfs_directed_enqueue = _sig("mgb_bfs_directed_enqueue", C.c_int, _vp, _vp, _vp, _u32, _u32, _vp, _vp, _P(_u32))
+mgb_bfs_enqueue_static = _sig("mgb_bfs_enqueue_static", C.c_int, _vp, _vp, _vp, _u32, _u32, _vp, _P(_u32))
 mgb_cu_trace_enqueue = _sig("mgb_cu_trace_enqueue", C.c_int, _vp, _vp, _u32)
 mgb_copy_enqueue = _sig("mgb_copy_enqueue", C.c_int, _vp, _vp, _vp, _u64)
 mgb_mfma_loop_enqueue = _sig("mgb_mfma_loop_enqueue", C.c_int, _vp, _u32, _u32, _u32, _vp, _P(C.c_double))
@@ -153,7 +154,7 @@ EXPORTS = [
     "mgb_sched_stats", "mgb_trace_read", "mgb_trace_dump", "mgb_last_error",
     "mgb_jacobi_probe", "mgb_jacobi_enqueue", "mgb_jacobi_launch_count", "mgb_gemm_f32_probe", "mgb_gemm_f32_enqueue",
     "mgb_gemm_bf16_probe", "mgb_gemm_bf16_enqueue", "mgb_conv3x3_probe", "mgb_conv3x3_enqueue",
-    "mgb_cnn_probe", "mgb_cnn_enqueue", "mgb_bfs_work_bytes", "mgb_bfs_probe", "mgb_bfs_enqueue", "mgb_bfs_directed_enqueue",
+    "mgb_cnn_probe", "mgb_cnn_enqueue", "mgb_bfs_work_bytes", "mgb_bfs_probe", "mgb_bfs_enqueue", "mgb_bfs_directed_enqueue", "mgb_bfs_enqueue_static",
     "mgb_cu_trace_enqueue", "mgb_copy_enqueue", "mgb_mfma_loop_enqueue", "mgb_jacobi_residency",
 ]
 

@@ -68,7 +68,21 @@ struct Work {                                  // layout of the caller's scratch
   uint32_t words;                              // 32-bit words per bitmap (a multiple of 64)
 };
 
-__host__ __device__ inline uint64_t ctrl_bytes() { return 256; }
+constexpr uint64_t ctrl_bytes() { return 256; }
+constexpr uint64_t work_bytes(uint64_t n) {
+  return ctrl_bytes() + 2ull * ((n * 4 + 255) / 256 * 256) + 3ull * (((n + 31) / 32 + 63) / 64 * 64) * 4;
+}
+
+// Scratch of the entry point that allocates nothing: queues, bitmaps and counters of one
+// traversal of up to BFS_STATIC_MAX_N vertices, held by every device the library runs on until
+// the process ends.  In host code this name is only a handle for hipGetSymbolAddress: the
+// device address it yields (one per device) is what kernels and copies are given.
+constexpr uint32_t BFS_STATIC_MAX_N = 1u << 22;
+constexpr uint64_t BFS_STATIC_BYTES = work_bytes(BFS_STATIC_MAX_N);      // 33.5 MiB
+__device__ __align__(256) unsigned char scratch[BFS_STATIC_BYTES];
+constexpr int BFS_MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[BFS_MAX_DEVICES] = {};
 
 Work carve(void* work, uint32_t n) {
   Work w;
@@ -497,7 +511,7 @@ uint32_t lds_bitmap_bytes(uint32_t n, uint32_t words, uint32_t symmetric) {
 extern "C" {
 
 uint64_t mgb_bfs_work_bytes(uint32_t n) {
-  return ctrl_bytes() + 2ull * (((uint64_t)n * 4 + 255) / 256 * 256) + 3ull * ((((uint64_t)n + 31) / 32 + 63) / 64 * 64) * 4;
+  return work_bytes(n);
 }
 
 // workgroups of the level kernel that fit one CU: LDS (the frontier bitmap on top of the
@@ -594,6 +608,39 @@ int mgb_bfs_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx
 int mgb_bfs_directed_enqueue(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
                              uint32_t source, int32_t* level, void* work, uint32_t* depth) {
   return bfs_run(stream, row_ptr, col_idx, n, source, level, work, depth, 0u);
+}
+
+// The traversal of mgb_bfs_enqueue with the work area in the library's static device array.
+int mgb_bfs_enqueue_static(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
+                           uint32_t source, int32_t* level, uint32_t* depth) {
+  if (n > BFS_STATIC_MAX_N) {
+    mgb_internal_set_error_text("mgb_bfs_enqueue_static: more than 2^22 vertices do not fit the static work area");
+    return MGB_E_TOO_BIG;
+  }
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= BFS_MAX_DEVICES) {
+    mgb_internal_set_error("mgb_bfs_enqueue_static: hipGetDevice", e == hipSuccess ? hipErrorInvalidDevice : e);
+    return MGB_E_BACKEND;
+  }
+  void* work = nullptr;
+  {
+    // once per device, with that device current: every device holds its own copy of the array
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p) {
+        mgb_internal_set_error("mgb_bfs_enqueue_static: hipGetSymbolAddress", e == hipSuccess ? hipErrorInvalidSymbol : e);
+        return MGB_E_BACKEND;
+      }
+      g_scratch_ptr[dev] = p;
+    }
+    work = g_scratch_ptr[dev];
+  }
+  // nothing to clear here: bfs_init writes the counters, the first queue entry and all three
+  // bitmaps before any level kernel reads them, whatever the previous call left behind
+  return bfs_run(stream, row_ptr, col_idx, n, source, level, work, depth, 1u);
 }
 
 }  // extern "C"
