@@ -211,6 +211,70 @@ int mgb_task_sync(mgb_sched* s, uint64_t ticket, double* gpu_ms);
  * (Sec. IV).  The caller must have synchronised the task's work first.      */
 int mgb_task_complete(mgb_sched* s, uint64_t ticket);
 
+/* The same release, ordered on the device instead of observed by the host: to be called when the
+ * task's last kernel has been ENQUEUED (after the last mgb_task_launch), without waiting for it.
+ * The ledger is credited and the waiters retried at once (the same COMPLETE / RELEASE / ADMIT
+ * records as mgb_task_complete, so a trace replays unchanged); what the device must not see is
+ * enforced on the device: a task admitted into granules this one held (HARD, SERIAL) starts
+ * behind this task's stop event (hipStreamWaitEvent on its stream before its first kernel), and a
+ * task whose footprint needed bytes that tasks released this way may still be using starts
+ * behind all of them.  So in device time a granule still has one owner and the bytes one user,
+ * while the hand-over between two tasks (completion seen by the host, waiter woken, kernels
+ * launched) overlaps the finishing task's kernels.  For tasks whose buffers stay valid until
+ * their kernels end (allocated up front, or freed in stream order); a task that frees its memory
+ * from the host right after the call must use mgb_task_complete.
+ * Afterwards the ticket is gone for every call except mgb_task_sync, which waits for the task's
+ * kernels, reports their time and forgets the task (mgb_sched_destroy does so for tasks nobody
+ * synchronised).  Errors as mgb_task_complete.                                   */
+int mgb_task_complete_on_stream(mgb_sched* s, uint64_t ticket);
+
+/* Tickets of the released-on-stream tasks that the resident task `ticket` starts behind (those
+ * whose kernels were not known to have finished when it was admitted).  Copies up to `cap`
+ * tickets to `out` (host) and returns how many there are, or < 0.                 */
+int64_t mgb_task_deps(mgb_sched* s, uint64_t ticket, uint64_t* out, uint64_t cap);
+
+/* ---- accounting (Sec. V-A: throughput, turnaround = completion - arrival in the queue; Sec. V,
+ * kernel-slowdown table: time of a task's kernels when sharing over their time on a dedicated
+ * device) ----------------------------------------------------------------------
+ * One record per probe, kept by the scheduler (the last 2^20).  Host times are the monotonic
+ * clock of the trace, device times milliseconds since the scheduler was created.              */
+typedef struct {
+  uint64_t ticket, task_id, mem_bytes;
+  uint64_t probe_ns;           /* the probe arrived                                             */
+  uint64_t admit_ns;           /* it was admitted (0: never)                                    */
+  uint64_t release_ns;         /* its resources went back to the ledger                         */
+  uint64_t done_ns;            /* its work was seen finished: return of the wait in
+                                  mgb_task_sync if that was called, else release_ns             */
+  double   gpu_ms;             /* between the events around its launches (mgb_task_sync)        */
+  double   gpu_start_ms, gpu_stop_ms;  /* those events on the device clock                      */
+  uint32_t granule_mask, demand;
+  int32_t  status;             /* MGB_OK finished, MGB_WAIT not finished yet, MGB_TIMEOUT cancelled
+                                  while queued, MGB_E_OOM lost under the CG policy              */
+  uint32_t reserved;
+} mgb_task_record;
+
+typedef struct {
+  uint64_t n_done, n_crashed, n_unfinished;
+  double tasks_per_s;          /* n_done / (last completion - first arrival)                    */
+  double makespan_ms;          /* last completion - first arrival                               */
+  double mean_turnaround_ms, max_turnaround_ms;   /* completion - arrival                       */
+  double mean_wait_ms, max_wait_ms;               /* admission - probe                          */
+  double gpu_busy_ms;          /* sum of the tasks' gpu_ms                                      */
+  double max_slowdown, mean_slowdown;             /* gpu_ms / reference - 1 over the tasks given one */
+} mgb_summary;
+
+/* Copy up to `cap` records starting at ticket `first_ticket` (tickets count from 1) into `out`;
+ * returns the number copied or < 0.                                                            */
+int64_t mgb_task_records(mgb_sched* s, uint64_t first_ticket, mgb_task_record* out, uint64_t cap);
+
+/* Pure arithmetic on n records (host arrays).  arrival_ns[i] (NULL: the probe time) is when task
+ * i entered the queue; ref_gpu_ms[i] (NULL or <= 0: none) is the time of the same task's kernels
+ * on a dedicated device.  Tasks lost to MGB_E_OOM are counted, not timed; tasks not finished are
+ * counted in n_unfinished and otherwise ignored.  MGB_E_INVAL for a record that ends before it
+ * arrives.                                                                                     */
+int mgb_accounting(const mgb_task_record* recs, uint64_t n, const uint64_t* arrival_ns,
+                   const double* ref_gpu_ms, mgb_summary* out);
+
 int mgb_sched_stats(mgb_sched* s, mgb_stats* out);
 /* Copy up to `cap` trace records starting at sequence number `first` into
  * `out` (host); returns the number copied or < 0.  A scheduler keeps its last
@@ -420,6 +484,61 @@ int mgb_bfs_directed_enqueue(void* stream, const int32_t* row_ptr, const int32_t
  * buffer).                                                                      */
 int mgb_bfs_enqueue_static(void* stream, const int32_t* row_ptr, const int32_t* col_idx, uint32_t n,
                            uint32_t source, int32_t* level, uint32_t* depth);
+
+/* ---- worker pool (Sec. V-A: a queue of jobs, a pool of workers, each running one job to its end
+ * and pulling the next; jobs all queued at the start, or arriving over time) -------------------
+ * A job is one of the task kinds above, given by its device buffers and shape:
+ *   MGB_TASK_JACOBI     ptr = {u0, u1},                     dim = {n, iters}
+ *   MGB_TASK_GEMM_F32   ptr = {A, B, C},                    dim = {m, n, k}
+ *   MGB_TASK_GEMM_BF16  ptr = {A, B, C},                    dim = {m, n, k}
+ *   MGB_TASK_BFS        ptr = {row_ptr, col_idx, level, work}, dim = {n, source}, count = stored edges
+ *   MGB_TASK_CNN        ptr = {x, act0, act1, out},         dim = {batch, h, w}, count = n_layers,
+ *                       layers / weights as for mgb_cnn_enqueue (host arrays)
+ *   MGB_TASK_CUSTOM     the caller's own kernels: ptr = {int (*enqueue)(void* stream, void* user), user}
+ *                       (host pointers; enqueue as for mgb_task_launch), count = footprint in bytes,
+ *                       dim = {workgroups, threads per workgroup, workgroups per CU or 0}
+ * All buffers are device pointers owned by the caller and must stay valid until the call returns. */
+#define MGB_TASK_JACOBI 0
+#define MGB_TASK_GEMM_F32 1
+#define MGB_TASK_GEMM_BF16 2
+#define MGB_TASK_BFS 3
+#define MGB_TASK_CNN 4
+#define MGB_TASK_CUSTOM 5
+typedef struct {
+  uint32_t kind;               /* MGB_TASK_*                                                    */
+  uint32_t reserved;
+  uint64_t task_id;
+  uint64_t arrival_ns;         /* when the job enters the queue, from the start of the run       */
+  uint64_t count;
+  void*    ptr[4];
+  uint32_t dim[4];
+  const mgb_conv_layer* layers;
+  const uint16_t* const* weights;
+} mgb_task_desc;
+
+typedef struct {
+  int32_t  status;             /* MGB_OK, or what stopped the job (MGB_E_OOM: lost under CG)     */
+  uint32_t aux;                /* BFS: number of levels                                          */
+  uint64_t ticket;
+  uint64_t arrival_ns;         /* on the clock of the records                                    */
+  mgb_task_record record;      /* as mgb_task_records gives it after the job's end               */
+} mgb_pool_result;
+
+#define MGB_POOL_ARRIVALS 1u           /* a job is not probed before start + arrival_ns; otherwise all
+                                          jobs are in the queue at the start                     */
+#define MGB_POOL_RELEASE_ON_STREAM 2u  /* hand resources back with mgb_task_complete_on_stream   */
+
+/* Run the n jobs through scheduler `s` with min(n_workers, n) worker threads and return when all
+ * have ended.  Each worker: derive the job's requirements with its kind's probe and residency,
+ * mgb_task_probe_ex, mgb_task_wait if queued, mgb_task_launch of the kind's enqueue, then
+ * mgb_task_sync + mgb_task_complete (or mgb_task_complete_on_stream + mgb_task_sync).  Jobs are
+ * taken in arrival order; with all jobs queued at the start and a worker for each, all probes are
+ * issued in the order given before anything runs.  results[i] (host, n entries) describes job i;
+ * *start_ns (may be NULL) receives the clock value arrivals count from.  Returns MGB_OK, or the
+ * first error other than MGB_E_OOM that a job met (the other jobs still run), or an error of a
+ * probe derivation (then nothing has run).                                                     */
+int mgb_pool_run(mgb_sched* s, const mgb_task_desc* tasks, uint32_t n, uint32_t n_workers,
+                 uint32_t flags, mgb_pool_result* results, uint64_t* start_ns);
 
 /* Diagnostic: launch n_blocks one-wave workgroups on `stream`; workgroup i
  * stores where it ran in out[i] (device, uint32): (xcd << 8) | (shader engine

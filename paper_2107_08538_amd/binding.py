@@ -56,9 +56,43 @@ class mgb_stats(C.Structure):
                 ("n_events", C.c_uint64)]
 
 
+class mgb_task_record(C.Structure):
+    _fields_ = [("ticket", C.c_uint64), ("task_id", C.c_uint64), ("mem_bytes", C.c_uint64),
+                ("probe_ns", C.c_uint64), ("admit_ns", C.c_uint64), ("release_ns", C.c_uint64),
+                ("done_ns", C.c_uint64), ("gpu_ms", C.c_double), ("gpu_start_ms", C.c_double),
+                ("gpu_stop_ms", C.c_double), ("granule_mask", C.c_uint32), ("demand", C.c_uint32),
+                ("status", C.c_int32), ("reserved", C.c_uint32)]
+
+
+class mgb_summary(C.Structure):
+    _fields_ = [("n_done", C.c_uint64), ("n_crashed", C.c_uint64), ("n_unfinished", C.c_uint64),
+                ("tasks_per_s", C.c_double), ("makespan_ms", C.c_double),
+                ("mean_turnaround_ms", C.c_double), ("max_turnaround_ms", C.c_double),
+                ("mean_wait_ms", C.c_double), ("max_wait_ms", C.c_double), ("gpu_busy_ms", C.c_double),
+                ("max_slowdown", C.c_double), ("mean_slowdown", C.c_double)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
 class mgb_conv_layer(C.Structure):
     _fields_ = [("c_in", C.c_uint32), ("c_out", C.c_uint32), ("stride", C.c_uint32)]
 
+
+class mgb_task_desc(C.Structure):
+    _fields_ = [("kind", C.c_uint32), ("reserved", C.c_uint32), ("task_id", C.c_uint64),
+                ("arrival_ns", C.c_uint64), ("count", C.c_uint64), ("ptr", C.c_void_p * 4),
+                ("dim", C.c_uint32 * 4), ("layers", C.POINTER(mgb_conv_layer)),
+                ("weights", C.POINTER(C.c_void_p))]
+
+
+class mgb_pool_result(C.Structure):
+    _fields_ = [("status", C.c_int32), ("aux", C.c_uint32), ("ticket", C.c_uint64),
+                ("arrival_ns", C.c_uint64), ("record", mgb_task_record)]
+
+
+MGB_TASK_JACOBI, MGB_TASK_GEMM_F32, MGB_TASK_GEMM_BF16, MGB_TASK_BFS, MGB_TASK_CNN, MGB_TASK_CUSTOM = range(6)
+MGB_POOL_ARRIVALS, MGB_POOL_RELEASE_ON_STREAM = 1, 2
 
 TRACE_DT = np.dtype([("seq", "<u8"), ("t_ns", "<u8"), ("task_id", "<u8"), ("ticket", "<u8"),
                      ("mem_bytes", "<u8"), ("free_bytes", "<u8"), ("kind", "<u4"), ("code", "<i4"),
@@ -108,6 +142,11 @@ mgb_lazy_stats_get = _sig("mgb_lazy_stats_get", C.c_int, _vp, C.POINTER(mgb_lazy
 mgb_task_launch = _sig("mgb_task_launch", C.c_int, _vp, _u64, ENQUEUE_FN, _vp)
 mgb_task_sync = _sig("mgb_task_sync", C.c_int, _vp, _u64, _P(C.c_double))
 mgb_task_complete = _sig("mgb_task_complete", C.c_int, _vp, _u64)
+mgb_task_complete_on_stream = _sig("mgb_task_complete_on_stream", C.c_int, _vp, _u64)
+mgb_task_deps = _sig("mgb_task_deps", C.c_int64, _vp, _u64, _P(_u64), _u64)
+mgb_task_records = _sig("mgb_task_records", C.c_int64, _vp, _u64, _P(mgb_task_record), _u64)
+mgb_pool_run = _sig("mgb_pool_run", C.c_int, _vp, _P(mgb_task_desc), _u32, _u32, _u32, _P(mgb_pool_result), _P(_u64))
+mgb_accounting = _sig("mgb_accounting", C.c_int, _P(mgb_task_record), _u64, _P(_u64), _P(C.c_double), _P(mgb_summary))
 mgb_sched_stats = _sig("mgb_sched_stats", C.c_int, _vp, _P(mgb_stats))
 mgb_trace_read = _sig("mgb_trace_read", _i64, _vp, _u64, _vp, _u64)
 mgb_trace_dump = _sig("mgb_trace_dump", C.c_int, _vp, C.c_char_p)
@@ -151,6 +190,7 @@ EXPORTS = [
     "mgb_lazy_stats_get", "mgb_server_start", "mgb_server_stop", "mgb_server_reclaimed", "mgb_client_connect",
     "mgb_client_disconnect", "mgb_client_probe", "mgb_client_wait", "mgb_client_cancel", "mgb_client_grow",
     "mgb_client_complete", "mgb_client_stats", "mgb_client_stream", "mgb_task_launch", "mgb_task_sync", "mgb_task_complete",
+    "mgb_task_complete_on_stream", "mgb_task_deps", "mgb_task_records", "mgb_accounting", "mgb_pool_run",
     "mgb_sched_stats", "mgb_trace_read", "mgb_trace_dump", "mgb_last_error",
     "mgb_jacobi_probe", "mgb_jacobi_enqueue", "mgb_jacobi_launch_count", "mgb_gemm_f32_probe", "mgb_gemm_f32_enqueue",
     "mgb_gemm_bf16_probe", "mgb_gemm_bf16_enqueue", "mgb_conv3x3_probe", "mgb_conv3x3_enqueue",
@@ -359,6 +399,21 @@ class Sched:
 
     def complete(self, ticket):
         return mgb_task_complete(self.h, ticket)
+
+    def complete_on_stream(self, ticket):
+        return mgb_task_complete_on_stream(self.h, ticket)
+
+    def deps(self, ticket):
+        out = (_u64 * 64)()
+        n = int(mgb_task_deps(self.h, ticket, out, 64))
+        check(n, "mgb_task_deps")
+        return [int(out[i]) for i in range(min(n, 64))]
+
+    def records(self, first_ticket=1, cap=1 << 16):
+        out = (mgb_task_record * cap)()
+        n = int(mgb_task_records(self.h, first_ticket, out, cap))
+        check(n, "mgb_task_records")
+        return out, n
 
     def stats(self):
         st = mgb_stats()

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmgb.so")
-SOURCES = ["sched.cpp", "lazy.cpp", "ipc.cpp", "jacobi.hip", "gemm_f32.hip", "gemm_bf16.hip", "conv3x3.hip", "bfs.hip", "cu_trace.hip"]
+SOURCES = ["sched.cpp", "lazy.cpp", "ipc.cpp", "runner.cpp", "jacobi.hip", "gemm_f32.hip", "gemm_bf16.hip", "conv3x3.hip", "bfs.hip", "cu_trace.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-value", "-Wno-unused-command-line-argument", "-Wno-inline-asm"]

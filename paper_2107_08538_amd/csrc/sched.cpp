@@ -15,6 +15,13 @@
 // never lets more than max_running tasks be resident, creates the masks of the
 // large blocks up front, and creates the others on first use with the scheduler
 // lock released, so that only the task that needs a new queue waits for it.
+//
+// A release can be ordered on the device instead of being observed by the host
+// (mgb_task_complete_on_stream): the ledger is credited as soon as the task's
+// last kernel is enqueued, and whoever is admitted into what it held starts
+// behind the task's stop event (hipStreamWaitEvent), so that in device time a
+// granule still has one owner and the bytes one user, while the hand-over
+// between two tasks costs the device nothing.
 #include "../../include/mgb.h"
 #include "launch_util.h"
 
@@ -56,7 +63,14 @@ constexpr uint32_t kStreamsAlive = 20;
 constexpr size_t kTraceCap = 1u << 20;
 std::atomic<uint32_t> g_live_streams{0};
 
-enum class State { Waiting, Running };
+// Draining: released through mgb_task_complete_on_stream, its kernels possibly still running;
+// holds nothing in the ledger, only its timing events, until mgb_task_sync retires it.
+enum class State { Waiting, Running, Draining };
+
+struct Dep {
+  uint64_t ticket;     // the draining task whose stop event orders the start
+  hipEvent_t ev;       // (nullptr with the null backend)
+};
 
 struct Task {
   uint64_t ticket = 0, task_id = 0, mem = 0, waves = 0, share = 0;
@@ -66,6 +80,13 @@ struct Task {
   hipStream_t stream = nullptr;
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;
   bool launched = false;
+  std::vector<Dep> deps;        // draining tasks this one must start behind
+  bool deps_issued = false;     // the waits are on the task's stream
+};
+
+// What is known of a task from its probe to its end (mgb_task_records).
+struct Record {
+  mgb_task_record r;
 };
 
 }  // namespace
@@ -109,6 +130,59 @@ struct mgb_sched {
   std::vector<hipEvent_t> idle_events;
   uint32_t n_streams = 0;   // created so far
   uint32_t n_alive = 0;     // created and not destroyed
+  // stream-ordered releases: per granule the draining task that owned it last (exclusive
+  // policies), and every draining task with the bytes it may still be using
+  std::vector<Dep> gran_pending;
+  struct MemPending { uint64_t ticket; hipEvent_t ev; uint64_t mem; };
+  std::vector<MemPending> mem_pending;
+  uint64_t pending_mem = 0;
+  hipEvent_t epoch = nullptr;                 // device-clock origin of gpu_start_ms / gpu_stop_ms
+  // one record per ticket (tickets record_base + 1 ...); the older half is dropped at kTraceCap
+  std::deque<mgb_task_record> records;
+  uint64_t record_base = 0;
+  mgb_task_record* record_of(uint64_t ticket) {
+    if (ticket <= record_base || ticket - record_base > records.size()) return nullptr;
+    return &records[ticket - record_base - 1];
+  }
+
+  // Device-side ordering of a task admitted just now (ledger already debited; free_before = the
+  // free bytes before the debit).  Exclusive compute: behind the last draining owner of each of
+  // its granules.  Memory: if the task needed bytes that draining tasks may still be using,
+  // behind all of them.
+  void collect_deps(Task& t, uint64_t free_before) {
+    t.deps.clear();
+    auto add = [&](uint64_t ticket, hipEvent_t ev) {
+      for (const Dep& d0 : t.deps)
+        if (d0.ticket == ticket) return;
+      t.deps.push_back({ticket, ev});
+    };
+    if (d.policy == MGB_POLICY_HARD || d.policy == MGB_POLICY_SERIAL)
+      for (uint32_t g = 0; g < G; ++g)
+        if ((t.granted >> g & 1u) && gran_pending[g].ticket != 0u) add(gran_pending[g].ticket, gran_pending[g].ev);
+    if (d.policy != MGB_POLICY_CG && pending_mem != 0u && t.mem > free_before - std::min(free_before, pending_mem))
+      for (const MemPending& m : mem_pending) add(m.ticket, m.ev);
+  }
+
+  // A draining task's kernels are known to have finished: nothing needs to start behind it any more.
+  void forget_pending(uint64_t ticket) {
+    for (Dep& g : gran_pending)
+      if (g.ticket == ticket) g = Dep{0, nullptr};
+    for (size_t i = 0; i < mem_pending.size(); ++i)
+      if (mem_pending[i].ticket == ticket) {
+        pending_mem -= mem_pending[i].mem;
+        mem_pending.erase(mem_pending.begin() + (long)i);
+        break;
+      }
+    for (auto& kv : tasks) {
+      Task& o = kv.second;
+      if (o.deps_issued) continue;
+      for (size_t i = 0; i < o.deps.size(); ++i)
+        if (o.deps[i].ticket == ticket) {
+          o.deps.erase(o.deps.begin() + (long)i);
+          break;
+        }
+    }
+  }
 
   void cu_mask_of(uint32_t gmask, uint32_t out[8]) const {
     std::memset(out, 0, 8 * sizeof(uint32_t));
@@ -145,6 +219,24 @@ struct mgb_sched {
     r.block = t ? t->block : block;
     cu_mask_of(gmask, r.cu_mask);
     trace.push_back(r);
+    if (t)
+      if (mgb_task_record* a = record_of(t->ticket)) {
+        if (kind == MGB_EV_ADMIT) {
+          a->admit_ns = r.t_ns;
+          a->granule_mask = gmask;
+        } else if (kind == MGB_EV_RELEASE) {
+          a->release_ns = r.t_ns;
+          if (a->done_ns == 0u) a->done_ns = r.t_ns;
+          a->mem_bytes = t->mem;
+          a->status = MGB_OK;
+        } else if (kind == MGB_EV_CANCELLED) {
+          a->status = MGB_TIMEOUT;
+          a->release_ns = a->done_ns = r.t_ns;
+        } else if (kind == MGB_EV_REJECT && code == MGB_E_OOM) {
+          a->status = MGB_E_OOM;
+          a->release_ns = a->done_ns = r.t_ns;
+        }
+      }
     return r.seq;
   }
 
@@ -155,6 +247,7 @@ struct mgb_sched {
   // granules starting at a multiple of b.
   bool try_admit(Task& t) {
     oom = false;
+    const uint64_t free_before = free_bytes;
     if (d.policy == MGB_POLICY_CG) {
       // ratio-limited packing that never looks at memory (Sec. IV): the task that does not fit
       // when it is let in is the one that would have crashed; it is reported, not run
@@ -167,6 +260,7 @@ struct mgb_sched {
       t.granted = all_mask;
       t.state = State::Running;
       ++n_running_now;
+      collect_deps(t, free_before);
       return true;
     }
     if (t.mem > free_bytes) return false;
@@ -205,6 +299,7 @@ struct mgb_sched {
     t.granted = pick;
     t.state = State::Running;
     ++n_running_now;
+    collect_deps(t, free_before);
     return true;
   }
 
@@ -340,26 +435,43 @@ struct mgb_sched {
         }
       }
     }
+    // start behind the draining tasks whose granules or bytes this one took over
+    if (!tp->deps_issued) {
+      for (const Dep& dep : tp->deps) {
+        if (!dep.ev) continue;
+        hipError_t e = hipStreamWaitEvent(tp->stream, dep.ev, 0);
+        if (e != hipSuccess) {
+          set_error("hipStreamWaitEvent", e);
+          return MGB_E_BACKEND;
+        }
+      }
+      tp->deps_issued = true;
+    }
     return MGB_OK;
   }
 
-  void unbind_stream(Task& t) {
+  void unbind_stream(Task& t, bool keep_events = false) {
     if (t.stream && --stream_users[t.stream] == 0u) {
       stream_users.erase(t.stream);
       idle_streams.push_back({t.granted, t.stream, ++stamp});
     }
+    t.stream = nullptr;
+    if (keep_events) return;
     if (t.ev_start) idle_events.push_back(t.ev_start);
     if (t.ev_stop) idle_events.push_back(t.ev_stop);
-    t.stream = nullptr;
     t.ev_start = t.ev_stop = nullptr;
   }
 
   // The body of mgb_task_complete: input record, release, re-pack.  Lock held.
-  int complete_locked(uint64_t ticket) {
+  // on_stream: the task's kernels may still be running; it stays behind as a draining task and
+  // whatever takes over its granules or bytes is ordered behind its stop event.
+  int complete_locked(uint64_t ticket, bool on_stream = false) {
     uint64_t cause = log(MGB_EV_COMPLETE, nullptr, 0, ticket, 0, {}, {}, 0, 0, 0);
     trace.back().cause_seq = (uint32_t)cause;
     auto it = tasks.find(ticket);
-    if (it == tasks.end()) {
+    // (a draining task has been released already: to the ledger, and to whoever replays the
+    // trace, its ticket no longer exists)
+    if (it == tasks.end() || it->second.state == State::Draining) {
       log(MGB_EV_REJECT, nullptr, 0, ticket, 0, {}, {}, 0, MGB_E_UNKNOWN_TICKET, cause);
       return MGB_E_UNKNOWN_TICKET;
     }
@@ -370,10 +482,35 @@ struct mgb_sched {
     }
     release(t);
     log(MGB_EV_RELEASE, &t, 0, 0, 0, {}, {}, t.granted, 0, cause);
-    unbind_stream(t);
-    tasks.erase(it);
+    if (on_stream) {
+      hipEvent_t ev = t.launched ? t.ev_stop : nullptr;
+      if (t.launched || d.backend != MGB_BACKEND_HIP) {      // (never launched on a device: nothing to wait for)
+        if (d.policy == MGB_POLICY_HARD || d.policy == MGB_POLICY_SERIAL)
+          for (uint32_t g = 0; g < G; ++g)
+            if (t.granted >> g & 1u) gran_pending[g] = Dep{ticket, ev};
+        mem_pending.push_back({ticket, ev, t.mem});
+        pending_mem += t.mem;
+      }
+      unbind_stream(t, true);
+      t.state = State::Draining;
+      if (mgb_task_record* a = record_of(ticket)) a->done_ns = 0;      // set when its work is seen finished
+    } else {
+      unbind_stream(t);
+      tasks.erase(it);
+    }
     rescan(cause);                              // wakes whom it admits
     return MGB_OK;
+  }
+
+  // A draining task's work has finished (the caller waited for its stop event): drop it.
+  void retire(uint64_t ticket) {
+    auto it = tasks.find(ticket);
+    if (it == tasks.end() || it->second.state != State::Draining) return;
+    forget_pending(ticket);
+    Task& t = it->second;
+    if (t.ev_start) idle_events.push_back(t.ev_start);
+    if (t.ev_stop) idle_events.push_back(t.ev_stop);
+    tasks.erase(it);
   }
 
   // Hand an admitted task to its caller.  If the backend cannot give it a stream the placement
@@ -457,7 +594,17 @@ int mgb_sched_create(const mgb_device_desc* desc, mgb_sched** out) {
   s->free_bytes = d.mem_cap_bytes;
   s->free_map = s->all_mask;
   s->load.assign(s->G, 0);
+  s->gran_pending.assign(s->G, Dep{0, nullptr});
   if (d.backend == MGB_BACKEND_HIP) {
+    hipError_t e = hipSetDevice(d.device);
+    if (e == hipSuccess) e = hipEventCreate(&s->epoch);
+    if (e == hipSuccess) e = hipEventRecord(s->epoch, nullptr);
+    if (e == hipSuccess) e = hipEventSynchronize(s->epoch);
+    if (e != hipSuccess) {
+      set_error("hipEventRecord (clock origin)", e);
+      delete s;
+      return MGB_E_BACKEND;
+    }
     // the masks of the large blocks (whole device, halves, quarters) are created now, not on
     // the first task that needs them; SERIAL and CG only ever grant the whole device
     const bool whole_only = d.policy == MGB_POLICY_SERIAL || d.policy == MGB_POLICY_CG;
@@ -480,7 +627,17 @@ int mgb_sched_destroy(mgb_sched* s) {
   if (!s) return MGB_E_INVAL;
   {
     std::lock_guard<std::mutex> lk(s->mu);
-    if (!s->tasks.empty()) return MGB_E_BUSY;
+    for (auto& kv : s->tasks)
+      if (kv.second.state != State::Draining) return MGB_E_BUSY;
+    // draining tasks nobody waited for: their kernels must be done before their events go
+    for (auto& kv : s->tasks) {
+      Task& t = kv.second;
+      if (t.launched && t.ev_stop) (void)hipEventSynchronize(t.ev_stop);
+      if (t.ev_start) (void)hipEventDestroy(t.ev_start);
+      if (t.ev_stop) (void)hipEventDestroy(t.ev_stop);
+    }
+    s->tasks.clear();
+    if (s->epoch) (void)hipEventDestroy(s->epoch);
     for (auto& is : s->idle_streams) {
       (void)hipStreamDestroy(is.stream);
       --g_live_streams;
@@ -534,6 +691,21 @@ int mgb_task_probe_ex(mgb_sched* s, uint64_t task_id, uint64_t mem_bytes, mgb_di
   t.grid = grid;
   t.block = block;
   Task& ref = s->tasks.emplace(t.ticket, t).first->second;
+  {
+    if (s->records.size() >= kTraceCap) {
+      s->records.erase(s->records.begin(), s->records.begin() + (long)(kTraceCap / 2));
+      s->record_base += kTraceCap / 2;
+    }
+    mgb_task_record a;
+    std::memset(&a, 0, sizeof a);
+    a.ticket = t.ticket;
+    a.task_id = task_id;
+    a.mem_bytes = mem_bytes;
+    a.probe_ns = s->trace.back().t_ns;
+    a.demand = t.demand;
+    a.status = MGB_WAIT;                          // not finished yet
+    s->records.push_back(a);
+  }
   const bool behind_queue = s->d.queue_mode == MGB_QUEUE_FIFO && !s->waitq.empty();
   if (!behind_queue && s->try_admit(ref)) {
     s->log(MGB_EV_ADMIT, &ref, 0, 0, 0, {}, {}, ref.granted, 0, cause);
@@ -587,7 +759,7 @@ int mgb_task_cancel(mgb_sched* s, uint64_t ticket) {
   uint64_t cause = s->log(MGB_EV_CANCEL, nullptr, 0, ticket, 0, {}, {}, 0, 0, 0);
   s->trace.back().cause_seq = (uint32_t)cause;
   auto it = s->tasks.find(ticket);
-  if (it == s->tasks.end()) {
+  if (it == s->tasks.end() || it->second.state == State::Draining) {
     s->log(MGB_EV_REJECT, nullptr, 0, ticket, 0, {}, {}, 0, MGB_E_UNKNOWN_TICKET, cause);
     return MGB_E_UNKNOWN_TICKET;
   }
@@ -609,7 +781,7 @@ int mgb_task_grow(mgb_sched* s, uint64_t ticket, uint64_t extra_bytes) {
   uint64_t cause = s->log(MGB_EV_GROW, nullptr, 0, ticket, extra_bytes, {}, {}, 0, 0, 0);
   s->trace.back().cause_seq = (uint32_t)cause;
   auto it = s->tasks.find(ticket);
-  if (it == s->tasks.end()) {
+  if (it == s->tasks.end() || it->second.state == State::Draining) {
     s->log(MGB_EV_REJECT, nullptr, 0, ticket, extra_bytes, {}, {}, 0, MGB_E_UNKNOWN_TICKET, cause);
     return MGB_E_UNKNOWN_TICKET;
   }
@@ -673,39 +845,120 @@ int mgb_task_launch(mgb_sched* s, uint64_t ticket, int (*enqueue)(void* stream, 
 int mgb_task_sync(mgb_sched* s, uint64_t ticket, double* gpu_ms) {
   if (!s) return MGB_E_INVAL;
   hipEvent_t e0 = nullptr, e1 = nullptr;
-  bool launched = false;
+  bool launched = false, draining = false;
   {
     std::lock_guard<std::mutex> lk(s->mu);
     auto it = s->tasks.find(ticket);
     if (it == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;
-    if (it->second.state != State::Running) return MGB_E_BAD_STATE;
+    if (it->second.state == State::Waiting) return MGB_E_BAD_STATE;
+    draining = it->second.state == State::Draining;
     e0 = it->second.ev_start;
     e1 = it->second.ev_stop;
     launched = it->second.launched;
   }
   if (gpu_ms) *gpu_ms = 0.0;
-  if (s->d.backend != MGB_BACKEND_HIP || !launched) return MGB_OK;
-  hipError_t e = hipEventSynchronize(e1);
-  if (e != hipSuccess) {
-    set_error("hipEventSynchronize", e);
-    return MGB_E_BACKEND;
-  }
-  if (gpu_ms) {
-    float ms = 0.f;
-    e = hipEventElapsedTime(&ms, e0, e1);
+  double ms = 0.0, t_start = 0.0, t_stop = 0.0;
+  int rc = MGB_OK;
+  if (s->d.backend == MGB_BACKEND_HIP && launched) {
+    hipError_t e = hipEventSynchronize(e1);
+    float f = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&f, e0, e1);
+    ms = f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&f, s->epoch, e0);
+    t_start = f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&f, s->epoch, e1);
+    t_stop = f;
     if (e != hipSuccess) {
-      set_error("hipEventElapsedTime", e);
-      return MGB_E_BACKEND;
+      set_error("mgb_task_sync: wait for / read the task's events", e);
+      rc = MGB_E_BACKEND;
     }
-    *gpu_ms = ms;
   }
-  return MGB_OK;
+  const uint64_t seen = now_ns();
+  std::lock_guard<std::mutex> lk(s->mu);
+  if (rc == MGB_OK) {
+    if (mgb_task_record* a = s->record_of(ticket)) {
+      a->gpu_ms = ms;
+      a->gpu_start_ms = t_start;
+      a->gpu_stop_ms = t_stop;
+      a->done_ns = seen;
+    }
+    if (gpu_ms) *gpu_ms = ms;
+  }
+  if (draining) s->retire(ticket);              // (also after a failed wait: nothing more can be learnt)
+  return rc;
 }
 
 int mgb_task_complete(mgb_sched* s, uint64_t ticket) {
   if (!s) return MGB_E_INVAL;
   std::lock_guard<std::mutex> lk(s->mu);
   return s->complete_locked(ticket);
+}
+
+int mgb_task_complete_on_stream(mgb_sched* s, uint64_t ticket) {
+  if (!s) return MGB_E_INVAL;
+  std::lock_guard<std::mutex> lk(s->mu);
+  return s->complete_locked(ticket, true);
+}
+
+int64_t mgb_task_deps(mgb_sched* s, uint64_t ticket, uint64_t* out, uint64_t cap) {
+  if (!s || (!out && cap)) return MGB_E_INVAL;
+  std::lock_guard<std::mutex> lk(s->mu);
+  auto it = s->tasks.find(ticket);
+  if (it == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;
+  if (it->second.state != State::Running) return MGB_E_BAD_STATE;
+  const std::vector<Dep>& deps = it->second.deps;
+  for (size_t i = 0; i < deps.size() && i < cap; ++i) out[i] = deps[i].ticket;
+  return (int64_t)deps.size();
+}
+
+int64_t mgb_task_records(mgb_sched* s, uint64_t first_ticket, mgb_task_record* out, uint64_t cap) {
+  if (!s || (!out && cap)) return MGB_E_INVAL;
+  std::lock_guard<std::mutex> lk(s->mu);
+  if (first_ticket <= s->record_base) first_ticket = s->record_base + 1;
+  const uint64_t at = first_ticket - s->record_base - 1;
+  if (at >= s->records.size()) return 0;
+  const uint64_t n = std::min<uint64_t>(cap, s->records.size() - at);
+  for (uint64_t i = 0; i < n; ++i) out[i] = s->records[at + i];
+  return (int64_t)n;
+}
+
+int mgb_accounting(const mgb_task_record* recs, uint64_t n, const uint64_t* arrival_ns,
+                   const double* ref_gpu_ms, mgb_summary* out) {
+  if (!out || (!recs && n)) return MGB_E_INVAL;
+  std::memset(out, 0, sizeof *out);
+  uint64_t first = 0, last = 0;
+  double turn_sum = 0.0, wait_sum = 0.0, slow_sum = 0.0;
+  uint64_t n_slow = 0;
+  for (uint64_t i = 0; i < n; ++i) {
+    const mgb_task_record& r = recs[i];
+    if (r.status == MGB_E_OOM) { ++out->n_crashed; continue; }
+    if (r.status != MGB_OK) { ++out->n_unfinished; continue; }
+    const uint64_t arr = arrival_ns ? arrival_ns[i] : r.probe_ns;
+    if (r.done_ns < arr || r.admit_ns < r.probe_ns) return MGB_E_INVAL;
+    const double turn = 1e-6 * (double)(r.done_ns - arr), wait = 1e-6 * (double)(r.admit_ns - r.probe_ns);
+    if (out->n_done == 0u || arr < first) first = arr;
+    if (out->n_done == 0u || r.done_ns > last) last = r.done_ns;
+    ++out->n_done;
+    turn_sum += turn;
+    wait_sum += wait;
+    if (turn > out->max_turnaround_ms) out->max_turnaround_ms = turn;
+    if (wait > out->max_wait_ms) out->max_wait_ms = wait;
+    out->gpu_busy_ms += r.gpu_ms;
+    if (ref_gpu_ms && ref_gpu_ms[i] > 0.0) {
+      const double sl = r.gpu_ms / ref_gpu_ms[i] - 1.0;
+      if (n_slow == 0u || sl > out->max_slowdown) out->max_slowdown = sl;
+      slow_sum += sl;
+      ++n_slow;
+    }
+  }
+  if (out->n_done != 0u) {
+    out->makespan_ms = 1e-6 * (double)(last - first);
+    out->tasks_per_s = last > first ? (double)out->n_done / (1e-9 * (double)(last - first)) : 0.0;
+    out->mean_turnaround_ms = turn_sum / (double)out->n_done;
+    out->mean_wait_ms = wait_sum / (double)out->n_done;
+  }
+  if (n_slow != 0u) out->mean_slowdown = slow_sum / (double)n_slow;
+  return MGB_OK;
 }
 
 int mgb_sched_stats(mgb_sched* s, mgb_stats* out) {

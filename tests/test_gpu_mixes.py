@@ -15,13 +15,85 @@ import paper_2107_08538_amd as mgb  # noqa: E402
 from paper_2107_08538_amd import harness  # noqa: E402
 
 
-def _run(spec, use_arrivals=True, time_scale=1.0, **sched_kw):
+def _run(spec, use_arrivals=True, time_scale=1.0, release_on_stream=False, **sched_kw):
     data = [W.task_data(t) for t in spec["tasks"]]
     tasks = [harness.build_task(t, d) for t, d in zip(spec["tasks"], data)]
     cap = min(spec["cap_bytes"], torch.cuda.mem_get_info()[1])
     s = mgb.Sched(mem_cap_bytes=cap, **sched_kw)
-    rec, makespan = harness.run_mix(s, tasks, use_arrivals=use_arrivals, time_scale=time_scale)
+    rec, makespan = harness.run_mix(s, tasks, use_arrivals=use_arrivals, time_scale=time_scale,
+                                    release_on_stream=release_on_stream)
     return s, tasks, data, rec
+
+
+def _assert_one_owner_in_device_time(rec, exclusive=True):
+    """Tasks whose granule sets overlap must not overlap on the device clock (the events around
+    each task's kernels, read against the scheduler's clock origin)."""
+    iv = sorted((r["record"].gpu_start_ms, r["record"].gpu_stop_ms, r["record"].granule_mask, r["task_id"])
+                for r in rec if not r.get("crashed"))
+    pairs = 0
+    for i, (a0, a1, am, aid) in enumerate(iv):
+        assert a1 >= a0 > 0.0
+        for b0, b1, bm, bid in iv[i + 1:]:
+            if am & bm:
+                pairs += 1
+                if exclusive:
+                    assert b0 >= a1 - 2e-3, ("tasks %d and %d share granules and overlap in time" % (aid, bid), a0, a1, b0, b1)
+    return pairs
+
+
+@pytest.mark.parametrize("policy", [mgb.MGB_POLICY_HARD, mgb.MGB_POLICY_SERIAL])
+def test_mix16_batch_released_on_stream_outputs_decisions_and_device_time(policy):
+    # every task hands its granules and bytes back when its last kernel is enqueued; its successor
+    # is launched behind its stop event.  Outputs, decisions and the ledger are what they are with
+    # host-observed releases, and on the device no two tasks that share granules overlap.
+    s, tasks, data, rec = _run(W.mix16(seed=3), use_arrivals=False, release_on_stream=True, policy=policy,
+                               max_running=16)
+    for t, d in zip(tasks, data):
+        verify_task_output(t, d)
+    trace = s.trace()
+    dec = assert_trace_matches_replay(s.desc, trace)
+    check_ledger_invariants(s.desc, trace)
+    assert (dec["kind"] == oracle.D_ADMIT).sum() == 16
+    assert _assert_one_owner_in_device_time(rec) == 16 * 15 // 2          # every task asks for the whole device
+    sm = harness.summarize(rec, 0.0)
+    assert sm["tasks"] == 16 and sm["gpu_busy_ms"] <= sm["makespan_ms"] * 1.001
+    assert s.destroy() == 0
+
+
+@pytest.mark.parametrize("release_on_stream", [False, True])
+def test_mix16_and_cnn8_through_the_native_worker_pool(release_on_stream):
+    # the same jobs through mgb_pool_run (probe derivation, wait, launch, release inside the library)
+    for spec, kw in ((W.mix16(seed=5), dict(use_arrivals=False)), (W.cnn8(h=52, w=52), dict(time_scale=0.1))):
+        data = [W.task_data(t) for t in spec["tasks"]]
+        tasks = [harness.build_task(t, d) for t, d in zip(spec["tasks"], data)]
+        s = mgb.Sched(mem_cap_bytes=min(spec["cap_bytes"], torch.cuda.mem_get_info()[1]))
+        rec, _ = harness.run_mix_native(s, tasks, release_on_stream=release_on_stream, **kw)
+        for t, d in zip(tasks, data):
+            verify_task_output(t, d)
+        trace = s.trace()
+        assert_trace_matches_replay(s.desc, trace)
+        check_ledger_invariants(s.desc, trace)
+        _assert_one_owner_in_device_time(rec)
+        sm = harness.summarize(rec, 0.0)
+        assert sm["tasks"] == len(tasks) and sm["crashed"] == 0 and sm["tasks_per_s"] > 0
+        for r, t in zip(rec, tasks):
+            assert (r["record"].mem_bytes, r["granules"]) == (t.mem, -(-min(256, -(-t.grid.x // max(1, min(32 // -(-t.block.x // 64), t.wg_per_cu)))) // 32))
+        assert s.destroy() == 0
+
+
+def test_mixed128_reduced_released_on_stream_partitions_keep_one_owner():
+    # small tasks share the device in disjoint partitions; a partition changes hands on the device
+    s, tasks, data, rec = _run(W.mixed128(shrink=4), use_arrivals=False, release_on_stream=True)
+    for t, d in zip(tasks, data):
+        if t.spec.kind != "jacobi" or t.spec.params["n"] <= 1024:      # (the serial checker's time)
+            verify_task_output(t, d)
+    trace = s.trace()
+    assert_trace_matches_replay(s.desc, trace)
+    check_ledger_invariants(s.desc, trace)
+    sizes = {bin(r["record"].granule_mask).count("1") for r in rec}
+    assert sizes == {1, 2, 4, 8}                                     # eighths ... the whole device
+    assert _assert_one_owner_in_device_time(rec) > 128
+    assert s.destroy() == 0
 
 
 def test_mix16_full_size_outputs_and_decisions():
