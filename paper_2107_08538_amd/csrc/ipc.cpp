@@ -158,8 +158,9 @@ struct mgb_server {
           sl.rc = mgb_sched_stats(s, &sl.stats);
           break;
         case OP_BYE:
+          // (the client gives the slot up itself once it has this answer: were the slot freed
+          // here, a client connecting right now could take it and read this answer as its own)
           sl.rc = held[i].empty() ? MGB_OK : MGB_E_BUSY;
-          if (sl.rc == MGB_OK) sl.owner.store(0);
           break;
         default:
           sl.rc = MGB_E_INVAL;
@@ -333,6 +334,7 @@ int mgb_client_disconnect(mgb_client* c) {
     std::lock_guard<std::mutex> lk(c->mu);
     const int rc = c->call(OP_BYE);                 // MGB_E_BACKEND: the server is gone, nothing left to tell it
     if (rc == MGB_E_BUSY) return rc;                // tasks still held: complete or cancel them first
+    if (rc == MGB_OK) c->seg->slots[c->slot].owner.store(0);   // answer collected: the slot is free again
     for (auto& kv : c->streams) (void)hipStreamDestroy(kv.second);
     c->streams.clear();
     munmap(c->seg, c->bytes);
@@ -405,9 +407,16 @@ int mgb_client_stats(mgb_client* c, mgb_stats* out) {
 int mgb_client_stream(mgb_client* c, const mgb_placement* placement, void** stream) {
   if (!c || !placement || !stream) return MGB_E_INVAL;
   std::vector<uint32_t> key(placement->cu_mask, placement->cu_mask + 8);
-  bool any = false;
-  for (uint32_t w : key) any = any || w != 0u;
-  if (!any) return MGB_E_INVAL;
+  // Mask bit i selects a CU of XCD (i mod 8).  A mask that leaves one of the 8 XCDs without a CU is
+  // never handed to the runtime (creating a stream with a one-bit mask ended in a crash inside the
+  // runtime, on the host); a server on the null backend may legally grant such masks (granules of
+  // 1, 2 or 4 CUs), so the check belongs here.
+  uint32_t residues = 0;
+  for (uint32_t w : key) residues |= (w | w >> 8 | w >> 16 | w >> 24) & 0xffu;
+  if (residues != 0xffu) {
+    mgb_internal_set_error_text("mgb_client_stream: the CU mask leaves an XCD without a CU");
+    return MGB_E_INVAL;
+  }
   Turn turn(c);
   auto it = c->streams.find(key);
   if (it == c->streams.end()) {

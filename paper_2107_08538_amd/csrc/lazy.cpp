@@ -262,7 +262,9 @@ int mgb_lazy_launch_prepare(mgb_lazy* z, uint64_t task_id, const uint64_t* pseud
       const uint64_t asked = extra;
       lk.unlock();
       rc = mgb_task_wait(z->s, ticket, timeout_ns, &pl);
-      if (rc == MGB_TIMEOUT) (void)mgb_task_cancel(z->s, ticket);
+      // (a release may have admitted the task between the end of the wait and the withdrawal: then
+      // the scheduler refuses to cancel a resident task, and the placement is this launch's after all)
+      if (rc == MGB_TIMEOUT && mgb_task_cancel(z->s, ticket) == MGB_E_BAD_STATE) rc = mgb_task_wait(z->s, ticket, 0, &pl);
       lk.lock();
       if (rc == MGB_OK && (!classify() || !owners.empty() || extra != asked)) {
         (void)mgb_task_complete(z->s, ticket);
@@ -280,16 +282,19 @@ int mgb_lazy_launch_prepare(mgb_lazy* z, uint64_t task_id, const uint64_t* pseud
     std::sort(owners.begin(), owners.end(),
               [](const std::shared_ptr<LTask>& a, const std::shared_ptr<LTask>& b) { return a->tickets[0] < b->tickets[0]; });
     task = owners[0];
+    // (the stream order first: if it fails nothing has been debited, and an order that a refused
+    // growth leaves behind is harmless)
+    for (size_t k = 1; k < owners.size(); ++k)
+      for (void* st : owners[k]->streams) {
+        const int rc = z->order_after(task->streams[0], st);
+        if (rc != MGB_OK) return rc;
+      }
     if (extra) {
       const int rc = mgb_task_grow(z->s, task->tickets[0], extra);
       if (rc != MGB_OK) return rc;                   // MGB_E_BUSY: nothing has changed, the caller may retry
     }
     for (size_t k = 1; k < owners.size(); ++k) {
       const std::shared_ptr<LTask>& other = owners[k];
-      for (void* st : other->streams) {
-        const int rc = z->order_after(task->streams[0], st);
-        if (rc != MGB_OK) return rc;
-      }
       for (uint32_t id : other->objs) {
         z->objs[id].task = task;
         task->objs.insert(id);

@@ -12,7 +12,31 @@
 #include <unistd.h>
 #include <string>
 
+// The worker pool dispatches to the task kernels, which are GPU code and not part of this build:
+// stand-ins that refuse every shape (the pool is driven with caller-defined jobs below).
+extern "C" {
+uint32_t mgb_jacobi_residency(uint32_t) { return 0; }
+uint32_t mgb_gemm_f32_residency(uint32_t, uint32_t, uint32_t) { return 0; }
+uint32_t mgb_gemm_bf16_residency(uint32_t, uint32_t, uint32_t) { return 0; }
+uint32_t mgb_bfs_residency(uint32_t) { return 0; }
+uint32_t mgb_cnn_residency(const mgb_conv_layer*, uint32_t, uint32_t, uint32_t, uint32_t) { return 0; }
+int mgb_jacobi_probe(uint32_t, uint32_t, uint64_t*, mgb_dim3*, mgb_dim3*) { return MGB_E_UNSUPPORTED; }
+int mgb_gemm_f32_probe(uint32_t, uint32_t, uint32_t, uint64_t*, mgb_dim3*, mgb_dim3*) { return MGB_E_UNSUPPORTED; }
+int mgb_gemm_bf16_probe(uint32_t, uint32_t, uint32_t, uint64_t*, mgb_dim3*, mgb_dim3*) { return MGB_E_UNSUPPORTED; }
+int mgb_bfs_probe(uint32_t, uint64_t, uint64_t*, mgb_dim3*, mgb_dim3*) { return MGB_E_UNSUPPORTED; }
+int mgb_cnn_probe(const mgb_conv_layer*, uint32_t, uint32_t, uint32_t, uint32_t, uint64_t*, uint64_t*, uint64_t*, mgb_dim3*,
+                  mgb_dim3*) { return MGB_E_UNSUPPORTED; }
+int mgb_jacobi_enqueue(void*, float*, float*, uint32_t, uint32_t) { return MGB_E_UNSUPPORTED; }
+int mgb_gemm_f32_enqueue(void*, const float*, const float*, float*, uint32_t, uint32_t, uint32_t) { return MGB_E_UNSUPPORTED; }
+int mgb_gemm_bf16_enqueue(void*, const uint16_t*, const uint16_t*, float*, uint32_t, uint32_t, uint32_t) { return MGB_E_UNSUPPORTED; }
+int mgb_bfs_enqueue(void*, const int32_t*, const int32_t*, uint32_t, uint32_t, int32_t*, void*, uint32_t*) { return MGB_E_UNSUPPORTED; }
+int mgb_cnn_enqueue(void*, const mgb_conv_layer*, uint32_t, const uint16_t*, const uint16_t* const*, uint16_t*, uint16_t*, float*,
+                    uint32_t, uint32_t, uint32_t) { return MGB_E_UNSUPPORTED; }
+}
+
 static std::atomic<int> fails{0};
+static std::atomic<int> custom_calls{0};
+static int custom_enqueue(void*, void*) { ++custom_calls; return 0; }
 #define CHECK(c) do { if (!(c)) { std::fprintf(stderr, "CHECK failed %s:%d %s\n", __FILE__, __LINE__, #c); ++fails; } } while (0)
 
 int main() {
@@ -52,8 +76,56 @@ int main() {
           if (rng() % 4 == 0) (void)mgb_task_grow(s, pl.ticket, rng() % 2000);
           mgb_stats st;
           CHECK(mgb_sched_stats(s, &st) == MGB_OK);
-          CHECK(mgb_task_complete(s, pl.ticket) == MGB_OK);
+          uint64_t behind[8];
+          CHECK(mgb_task_deps(s, pl.ticket, behind, 8) >= 0);
+          // a third of the releases are ordered on the "device"; some of those are never waited for
+          const uint32_t how = rng() % 6;
+          if (how < 2) {
+            CHECK(mgb_task_launch(s, pl.ticket, custom_enqueue, nullptr) == MGB_OK);
+            CHECK(mgb_task_complete_on_stream(s, pl.ticket) == MGB_OK);
+            if (how == 0) CHECK(mgb_task_sync(s, pl.ticket, nullptr) == MGB_OK);
+          } else {
+            CHECK(mgb_task_complete(s, pl.ticket) == MGB_OK);
+          }
+          mgb_task_record one;
+          CHECK(mgb_task_records(s, pl.ticket, &one, 1) == 1 && one.ticket == pl.ticket);
         }
+      });
+    for (auto& t : th) t.join();
+    mgb_stats st;
+    CHECK(mgb_sched_stats(s, &st) == MGB_OK);
+    CHECK(st.free_bytes == d.mem_cap_bytes && st.n_running == 0 && st.n_waiting == 0);
+    CHECK(mgb_sched_destroy(s) == MGB_OK);
+  }
+  // worker pool: three pools at once on one scheduler, caller-defined jobs
+  {
+    d.policy = MGB_POLICY_HARD;
+    mgb_sched* s = nullptr;
+    CHECK(mgb_sched_create(&d, &s) == MGB_OK);
+    std::vector<std::thread> th;
+    for (int k = 0; k < 3; ++k)
+      th.emplace_back([&, k] {
+        std::mt19937 rng(900 + k);
+        const uint32_t n = 60;
+        std::vector<mgb_task_desc> jobs(n);
+        std::vector<mgb_pool_result> res(n);
+        for (uint32_t i = 0; i < n; ++i) {
+          jobs[i] = mgb_task_desc{};
+          jobs[i].kind = MGB_TASK_CUSTOM;
+          jobs[i].task_id = k * 1000 + i;
+          jobs[i].arrival_ns = (rng() % 2000) * 1000ull;
+          jobs[i].count = 1 + rng() % 30000;
+          jobs[i].ptr[0] = (void*)custom_enqueue;
+          jobs[i].dim[0] = 1 + rng() % 4000;
+          jobs[i].dim[1] = 64u << (rng() % 4);
+        }
+        const uint32_t flags = (k == 0 ? 0u : MGB_POOL_ARRIVALS) | (k == 2 ? 0u : MGB_POOL_RELEASE_ON_STREAM);
+        CHECK(mgb_pool_run(s, jobs.data(), n, k == 0 ? n : 7, flags, res.data(), nullptr) == MGB_OK);
+        for (uint32_t i = 0; i < n; ++i) CHECK(res[i].status == MGB_OK && res[i].record.status == MGB_OK);
+        mgb_summary sum;
+        std::vector<mgb_task_record> recs(n);
+        for (uint32_t i = 0; i < n; ++i) recs[i] = res[i].record;
+        CHECK(mgb_accounting(recs.data(), n, nullptr, nullptr, &sum) == MGB_OK && sum.n_done == n);
       });
     for (auto& t : th) t.join();
     mgb_stats st;

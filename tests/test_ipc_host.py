@@ -135,3 +135,54 @@ def test_two_threads_share_one_connection_while_one_waits():
     sv.stop()
     assert_trace_matches_replay(s.desc, s.trace())
     assert s.destroy() == 0
+
+
+@pytest.mark.parametrize("granule_cus", [1, 2, 4])
+def test_client_refuses_to_build_a_stream_for_a_mask_that_misses_an_xcd(granule_cus):
+    # mask bit i is a CU of XCD (i mod 8): a server that only decides may hand out granules of fewer
+    # than 8 CUs, and such a mask must be refused before the runtime sees it (no GPU call is reached)
+    s = mgb.Sched(backend=mgb.MGB_BACKEND_NULL, n_cu=32 * granule_cus, granule_cus=granule_cus)
+    name = _name("xcd%d" % granule_cus)
+    sv = mgb.Server(s, name, 1)
+    c = mgb.Client(name)
+    rc, pl = c.probe(1, 10, (1, 1, 1), (64, 1, 1))
+    assert rc == mgb.MGB_OK and pl.granule_mask == 1 and pl.cu_mask[0] == (1 << granule_cus) - 1
+    rc, st = c.stream(pl)
+    assert rc == mgb.MGB_E_INVAL and not st.value
+    assert b"XCD" in mgb.mgb_last_error()
+    # seven of the eight residues are not enough either; an empty mask was refused before
+    pl.cu_mask[0] = 0x7F7F7F7F
+    assert c.stream(pl)[0] == mgb.MGB_E_INVAL
+    for k in range(8):
+        pl.cu_mask[k] = 0
+    assert c.stream(pl)[0] == mgb.MGB_E_INVAL
+    assert c.complete(pl.ticket) == mgb.MGB_OK and c.disconnect() == mgb.MGB_OK
+    assert sv.stop() == mgb.MGB_OK and s.destroy() == mgb.MGB_OK
+
+
+def test_a_slot_is_free_only_after_its_owner_collected_the_goodbye():
+    # connect / disconnect in a tight loop from several threads on fewer slots than threads: a client
+    # that claimed a slot whose previous owner had not yet read its answer would see a stale status
+    s = _sched()
+    name = _name("bye")
+    sv = mgb.Server(s, name, 2)
+    bad = []
+
+    def churn(k):
+        for i in range(150):
+            try:
+                c = mgb.Client(name)
+            except mgb.MgbError:
+                continue                                            # both slots taken right now
+            rc, pl = c.probe(k * 1000 + i, 1, (1, 1, 1), (64, 1, 1))
+            if rc != mgb.MGB_OK or pl.ticket == 0:
+                bad.append(("probe", rc))
+            elif c.complete(pl.ticket) != mgb.MGB_OK:
+                bad.append(("complete", k, i))
+            if c.disconnect() != mgb.MGB_OK:
+                bad.append(("bye", k, i))
+    th = [threading.Thread(target=churn, args=(k,)) for k in range(4)]
+    [t.start() for t in th]
+    [t.join() for t in th]
+    assert not bad, bad[:5]
+    assert sv.stop() == mgb.MGB_OK and s.destroy() == mgb.MGB_OK

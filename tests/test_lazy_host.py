@@ -414,3 +414,35 @@ def test_allocation_failure_after_admission_rolls_the_ledger_back():
     assert z.free(small) == 0 and z.free(huge) == 0 and z.destroy() == 0
     assert_trace_matches_replay(s.desc, s.trace())
     assert s.destroy() == 0
+
+
+def test_a_launch_that_times_out_while_it_is_being_admitted_leaks_nothing():
+    # A launch waits for memory with a short timeout while another thread frees that memory at about
+    # the same moment.  Whichever way each round goes (timed out and withdrawn, admitted, or admitted
+    # in the gap between the two), the scheduler must end up empty.
+    import random
+    import time
+    s = mgb.Sched(backend=mgb.MGB_BACKEND_NULL, mem_cap_bytes=100)
+    z = mgb.Lazy(s)
+    rnd = random.Random(3)
+    got = {mgb.MGB_OK: 0, mgb.MGB_TIMEOUT: 0}
+    for it in range(300):
+        rc, x = z.malloc(60)
+        rc, real, pl = z.launch_prepare(2 * it, [x], (1, 1, 1), (64, 1, 1))
+        assert rc == mgb.MGB_OK
+        rc, y = z.malloc(60)
+        out = []
+        th = threading.Thread(target=lambda: out.append(z.launch_prepare(2 * it + 1, [y], (1, 1, 1), (64, 1, 1),
+                                                                         timeout_ns=rnd.choice([0, 20_000, 60_000, 200_000]))[0]))
+        th.start()
+        time.sleep(rnd.choice([0, 2e-5, 6e-5, 1e-4]))
+        assert z.free(x) == mgb.MGB_OK
+        th.join(10)
+        assert out and out[0] in (mgb.MGB_OK, mgb.MGB_TIMEOUT), out
+        got[out[0]] += 1
+        assert z.free(y) == mgb.MGB_OK
+        st = s.stats()
+        assert (st.n_running, st.n_waiting, st.free_bytes) == (0, 0, 100), (it, out)
+    assert got[mgb.MGB_OK] > 0
+    assert_trace_matches_replay(s.desc, s.trace())
+    assert z.destroy() == mgb.MGB_OK and s.destroy() == mgb.MGB_OK

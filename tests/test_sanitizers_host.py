@@ -1,4 +1,4 @@
-"""The host side of the library (scheduler core, lazy runtime, shared-memory front end) under
+"""The host side of the library (scheduler core, worker pool, lazy runtime, shared-memory front end) under
 ThreadSanitizer and under AddressSanitizer + UBSan: tests/native/sched_stress.cpp drives them from
 many threads on the null backend (no GPU code runs; sanitizers see host code only)."""
 import os
@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CLANG = "/opt/rocm/llvm/bin/clang++"
 SRCS = [os.path.join(HERE, "native", "sched_stress.cpp")] + [
-    os.path.join(ROOT, "paper_2107_08538_amd", "csrc", f) for f in ("sched.cpp", "lazy.cpp", "ipc.cpp")]
+    os.path.join(ROOT, "paper_2107_08538_amd", "csrc", f) for f in ("sched.cpp", "lazy.cpp", "ipc.cpp", "runner.cpp")]
 
 
 def _build_and_run(tmp_path, name, flags, env=None):
