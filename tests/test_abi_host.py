@@ -384,7 +384,9 @@ def test_probe_functions_agree_with_checker_formulas():
         mem, grid, block = mgb.probe_of(mgb.mgb_bfs_probe, n, m)
         oracle.lib().orc_bfs_probe(C.c_uint64(n), C.c_uint64(m), out)
         assert [mem, *grid.tuple(), *block.tuple()] == list(out), (n, m)
-        assert mem == (n + 1 + m) * 4 + n * 4 + mgb.mgb_bfs_work_bytes(n)
+        # counters + two queues of n entries + three bitmaps of n bits (256-byte pieces), written out
+        work = 256 + 2 * (-(-n * 4 // 256) * 256) + 3 * (-(-(-(-n // 32)) // 64) * 64 * 4)
+        assert mem == (n + 1 + m) * 4 + n * 4 + work and mgb.mgb_bfs_work_bytes(n) == work
     mem, grid, block = mgb.mgb_dim3(), None, None
     assert mgb.mgb_jacobi_probe(2, 1, C.byref(C.c_uint64()), C.byref(mgb.mgb_dim3()),
                                 C.byref(mgb.mgb_dim3())) == mgb.MGB_E_UNSUPPORTED
