@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Bench: one "step" = one pass of a whole task mix (default Mix-16: 16 tasks, Poisson arrivals,
 Jacobi 4096^2 x100 / fp32 GEMM 4096^3 / BFS 2^20) through probe -> admit -> CU partition ->
-launch -> complete on one MI355X, inputs resident in HBM.  Prints ONE JSON line."""
+launch -> release on one MI355X, inputs resident in HBM.  Prints ONE JSON line."""
 import argparse
 import json
 import os
@@ -20,29 +20,32 @@ def parse():
     ap.add_argument("--mix", default="mix16", choices=["mix4", "mix16", "cnn8", "mixed128", "kinds5"])
     ap.add_argument("--policy", default="hard", choices=["hard", "soft", "serial"])
     ap.add_argument("--queue", default="backfill", choices=["backfill", "fifo"])
+    ap.add_argument("--harness", default="native", choices=["native", "python"],
+                    help="worker pool inside the library (mgb_pool_run) or Python threads over the same calls")
+    ap.add_argument("--release", default="stream", choices=["stream", "host"],
+                    help="hand resources back when the last kernel is enqueued (ordered on the device) or when the host has seen it finish")
+    ap.add_argument("--batch", action="store_true", help="timed region with all tasks queued at t = 0 instead of arrivals")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip serialised / alone / batch comparisons")
+    ap.add_argument("--dump-records", default=None, help="write the last timed pass's task records (JSON) to this path")
     ap.add_argument("--seed", type=int, default=None)
     return ap.parse_args()
 
 
-# HBM-side bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/mix16_hbm_traffic.md (each counter scaled by its reading for the 1 GiB stream copy).
-# Valid for the kernels as they stand in csrc/ and for the Mix-16 task shapes only.
-MEASURED_TRAFFIC_BYTES = {
-    ("mix16", "gemm_f32_dma_kernel"): 470.4e6,  # per 4096^3 launch
-    ("mix16", "jacobi_stream"): 182.1e6,       # per launch (2 eight-sweep + 12 seven-sweep launches per task)
-    ("mix16", "bfs_level"): 20.7e6,            # per level launch, averaged over the 8 launches of a traversal
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "mix16_hbm_traffic.md")
 
 
 def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
+def med(v):
+    v = sorted(v)
+    return 0.5 * (v[(len(v) - 1) // 2] + v[len(v) // 2])
+
+
 def cpu_baseline(spec):
     """Serial CPU checker timed on a bounded sample of the same workload, scaled by work."""
-    import numpy as np
     import oracle
     import workloads as W
     per_kind, sample = {}, []
@@ -100,7 +103,6 @@ def cpu_baseline(spec):
 def lazy_leg(mgb, cap):
     """One fp32 GEMM 1024^3 task built through the lazy runtime (Sec. III-A): host time of each
     stage.  Host buffers cross PCIe here, unlike the timed region of the bench."""
-    import ctypes as C
     import numpy as np
     import workloads as W
     n = 1024
@@ -159,6 +161,18 @@ def ipc_leg(mgb):
     return dict(probe_plus_complete_us=round(via, 2), in_process_us=round(direct, 2))
 
 
+# what bounds each kernel, its peak and the unit of `achieved`.  The Jacobi kernels fuse up to eight
+# sweeps per pass over the grid, so they are not bound by 8 bytes per update through HBM but by
+# plain fp32 vector arithmetic: adds and one multiply per update, no fused multiply-adds, no packed
+# fp32 (not used in this code base), i.e. one flop per lane per issue slot.  That rate is
+# 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 Tflop/s (the published 157.3 TFLOP/s counts a
+# packed fused multiply-add as four flops per lane and clock).
+VALU_PLAIN_TFLOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+PEAKS = dict(jacobi_sweeps=("alu", VALU_PLAIN_TFLOPS, "TFLOP/s"), jacobi_stream=("alu", VALU_PLAIN_TFLOPS, "TFLOP/s"),
+             bfs_level=("hbm", 8000.0, "GB/s"), gemm_f32_dma_kernel=("mfma", 157.3, "TFLOP/s"),
+             gemm_bf16_dma_kernel=("mfma", 2500.0, "TFLOP/s"), conv3x3_kernel=("mfma", 2500.0, "TFLOP/s"))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -173,8 +187,15 @@ def main():
         import __graft_entry__
         __graft_entry__.build()
     import paper_2107_08538_amd as mgb
-    from paper_2107_08538_amd import harness
+    from paper_2107_08538_amd import harness, profsum
     import workloads as W
+
+    native = args.harness == "native"
+    on_stream = args.release == "stream"
+
+    def run(sched, tasks, release_on_stream=False, **kw):
+        fn = harness.run_mix_native if native else harness.run_mix
+        return fn(sched, tasks, release_on_stream=release_on_stream, **kw)
 
     mixfn = W.MIXES[args.mix]
     spec = mixfn(args.seed) if args.seed is not None else mixfn()
@@ -186,6 +207,7 @@ def main():
     del data
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
+    n_tasks = len(tasks)
 
     # measured stream-copy ceiling (plain copy kernel of known size, also the counter calibration point)
     import ctypes as C
@@ -224,22 +246,27 @@ def main():
     sched = mgb.Sched(policy=pol, queue_mode=qm, mem_cap_bytes=cap)
 
     log("inputs resident (%d tasks, %.1f s); stream copy %.0f GB/s; MFMA loop %.0f (f32) / %.0f (bf16) TFLOP/s"
-        % (len(tasks), t_gen, copy_gbps, mfma_tflops["f32"], mfma_tflops["bf16"]))
+        % (n_tasks, t_gen, copy_gbps, mfma_tflops["f32"], mfma_tflops["bf16"]))
+    timed_kw = dict(release_on_stream=on_stream, use_arrivals=not args.batch)
     for _ in range(args.warmup):
-        harness.run_mix(sched, tasks)
+        run(sched, tasks, **timed_kw)
     log("warm-up done, %d masked streams" % sched.stats().n_streams)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     runs = []
     for _ in range(args.steps):
-        runs.append(harness.run_mix(sched, tasks))
+        runs.append(run(sched, tasks, **timed_kw))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    n_tasks = len(tasks)
     log("timed region done: %d steps in %.3f s, %d masked streams" % (args.steps, elapsed, sched.stats().n_streams))
     sums = [harness.summarize(r, m) for r, m in runs]
     value = n_tasks * args.steps / elapsed
     mean_turn = sum(s["mean_turnaround_ms"] for s in sums) / len(sums)
+    if args.dump_records:
+        with open(args.dump_records, "w") as f:
+            json.dump([dict(task_id=r["task_id"], kind=r["kind"], granule_mask=int(r["record"].granule_mask),
+                            gpu_start_ms=r["record"].gpu_start_ms, gpu_stop_ms=r["record"].gpu_stop_ms,
+                            gpu_ms=r["record"].gpu_ms) for r in runs[-1][0] if r.get("record") is not None], f)
 
     # per-kernel figures from the timed region (HIP events bracket each task on its own stream)
     kern = {}
@@ -250,116 +277,167 @@ def main():
             k["ms"] += r["gpu_ms"]; k["launches"] += launches; k["tasks"] += 1
             k["bytes"] += t.alg_bytes; k["flops"] += t.alg_flops; k["edges"] += t.edges
     dominant = max(kern, key=lambda n: kern[n]["ms"])
-    kd = kern[dominant]
-    peaks = dict(jacobi_sweeps=("hbm", 8000.0, "GB/s"), jacobi_stream=("hbm", 8000.0, "GB/s"), bfs_level=("hbm", 8000.0, "GB/s"),
-                 gemm_f32_dma_kernel=("mfma", 157.3, "TFLOP/s"), gemm_bf16_dma_kernel=("mfma", 2500.0, "TFLOP/s"),
-                 conv3x3_kernel=("mfma", 2500.0, "TFLOP/s"))
 
     def measured_ceiling(name):
         # what this device sustains on the same resource with nothing else in the way: the plain copy
-        # kernel for HBM-bound kernels, the register-only MFMA loop of the kernel's dtype otherwise
-        if peaks[name][0] == "hbm":
+        # kernel for HBM-bound kernels, the register-only MFMA loop of the kernel's dtype for the
+        # matrix kernels (none for plain vector arithmetic)
+        bound = PEAKS[name][0]
+        if bound == "hbm":
             return copy_gbps
-        return mfma_tflops["f32" if name == "gemm_f32_dma_kernel" else "bf16"]
+        if bound == "mfma":
+            return mfma_tflops["f32" if name == "gemm_f32_dma_kernel" else "bf16"]
+        return None
+
+    def traffic_of(name):
+        # HBM-side bytes per launch from the counter runs summarised under profiles/ (Mix-16 shapes
+        # only), None once the kernel's source differs from the one that was measured
+        return profsum.traffic_for(TRAFFIC_TABLE, name) if args.mix == "mix16" else None
 
     def roof(name, k):
-        bound, peak, unit = peaks[name]
+        bound, peak, unit = PEAKS[name]
+        secs = k["ms"] / 1e3
         work = k["bytes"] / 1e9 if bound == "hbm" else k["flops"] / 1e12
-        ach = work / (k["ms"] / 1e3)
-        out = dict(kernel=name, bound=bound, achieved=round(ach, 2), peak=peak, unit=unit,
-                   frac=round(ach / peak, 4), measured_ceiling=round(measured_ceiling(name), 1),
-                   frac_of_measured=round(ach / measured_ceiling(name), 4), traffic=MEASURED_TRAFFIC_BYTES.get((args.mix, name)),
+        ach = work / secs
+        tr = traffic_of(name)
+        out = dict(kernel=name, bound=bound, achieved=round(ach, 2), peak=round(peak, 1), unit=unit,
+                   frac=round(ach / peak, 4), traffic=None if tr is None else round(tr),
                    avg_launch_us=round(1e3 * k["ms"] / k["launches"], 2), launches=k["launches"])
+        ceil = measured_ceiling(name)
+        if ceil:
+            out["measured_ceiling"] = round(ceil, 1)
+            out["frac_of_measured"] = round(ach / ceil, 4)
+        if tr is not None:
+            # the same launches against the HBM peak, from the counters
+            out["hbm_counter_gbs"] = round(tr * k["launches"] / secs / 1e9, 1)
+            out["hbm_counter_frac"] = round(tr * k["launches"] / secs / 1e9 / 8000.0, 4)
+        if bound == "alu":
+            # bonus figure: 8 bytes per cell update as if every sweep went through HBM (fused sweeps
+            # move a fraction of that, so this may exceed the HBM peak and is no roofline fraction)
+            out["one_sweep_per_pass_equivalent_gbs"] = round(k["bytes"] / 1e9 / secs, 1)
         if k["edges"]:
-            out["gteps"] = round(k["edges"] / (k["ms"] / 1e3) / 1e9, 2)      # stored directed edges per second of traversal
+            out["gteps"] = round(k["edges"] / secs / 1e9, 2)      # stored directed edges per second of traversal
         return out
 
-    out = dict(metric="aggregate tasks/s through probe+admit+partition+launch+complete (with mean turnaround, max slowdown)",
+    out = dict(metric="aggregate tasks/s through probe+admit+partition+launch+release (with mean turnaround, max slowdown)",
                value=round(value, 2), unit="tasks/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=round(1e3 * elapsed / args.steps, 3), higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="f32", data="synthetic",
                config=dict(workload="%s: %s" % (spec["name"], ", ".join(sorted({t.kind for t in spec["tasks"]}))),
                            policy=args.policy, queue=args.queue, tasks=n_tasks, workers=min(n_tasks, harness.MAX_WORKERS),
-                           cap_bytes=cap, granule_cus=int(sched.desc.granule_cus), n_cu=256),
+                           arrivals="all at t=0" if args.batch else "as the mix states", harness=args.harness,
+                           release=args.release, cap_bytes=cap, granule_cus=int(sched.desc.granule_cus), n_cu=256),
                mean_turnaround_ms=round(mean_turn, 3),
+               median_turnaround_ms=round(med([s["mean_turnaround_ms"] for s in sums]), 3),
                mean_wait_ms=round(sum(s["mean_wait_ms"] for s in sums) / len(sums), 3),
                input_gen_s=round(t_gen, 1), stream_copy_gbps=round(copy_gbps, 1),
                mfma_loop_tflops={k: round(v, 1) for k, v in mfma_tflops.items()})
-    out["roofline"] = roof(dominant, kd)
+    out["roofline"] = roof(dominant, kern[dominant])
     out["kernels"] = [roof(n, k) for n, k in kern.items() if n != dominant]
 
     if not args.no_extras:
-        # the same mix, serialised: one task at a time on all 256 CUs in arrival order
+        kinds = sorted({t.spec.kind for t in tasks})
+
+        def per_task_median(passes):
+            return [med([p[0][i]["gpu_ms"] for p in passes]) for i in range(n_tasks)]
+
+        def slowdown(co, ref):
+            s = [c / a - 1.0 for c, a in zip(co, ref) if a > 0 and c > 0]
+            return dict(max_pct=round(100 * max(s), 2), mean_pct=round(100 * sum(s) / len(s), 2),
+                        by_kind_max_pct={k: round(100 * max(x for x, t in zip(s, tasks) if t.spec.kind == k), 2) for k in kinds})
+
+        # the same mix, serialised: one task at a time on all 256 CUs in arrival order, a task owning the
+        # device until the host has seen it finish (single assignment, Sec. IV); same harness, same
+        # warm-up, medians over the passes
         log("serialised comparator")
         ser = mgb.Sched(policy=mgb.MGB_POLICY_SERIAL, queue_mode=mgb.MGB_QUEUE_FIFO, mem_cap_bytes=cap)
-        harness.run_mix(ser, tasks)
-        t1 = time.perf_counter()
-        sruns = [harness.run_mix(ser, tasks) for _ in range(max(2, args.steps // 2))]
-        torch.cuda.synchronize()
-        sel = time.perf_counter() - t1
+        for _ in range(max(1, args.warmup)):
+            run(ser, tasks, use_arrivals=not args.batch)
+        sruns = [run(ser, tasks, use_arrivals=not args.batch) for _ in range(max(3, args.steps // 2))]
         ssum = [harness.summarize(r, m) for r, m in sruns]
-        out["serialised_gpu"] = dict(tasks_per_s=round(n_tasks * len(sruns) / sel, 2),
-                                     mean_turnaround_ms=round(sum(s["mean_turnaround_ms"] for s in ssum) / len(ssum), 3))
-        # kernel slowdown as the paper defines it (Sec. V, last experiment): GPU time of a task in the
-        # shared run against the same task in the single-assignment run of the same workload
-        # (per task the median over the passes: one pass in which a 0.2 ms task meets a host hiccup
-        # would otherwise decide the maximum over tasks)
-        def mid(v):
-            v = sorted(v)
-            return 0.5 * (v[(len(v) - 1) // 2] + v[len(v) // 2])
-        co = [mid([run[0][i]["gpu_ms"] for run in runs]) for i in range(n_tasks)]
-        sa = [mid([run[0][i]["gpu_ms"] for run in sruns]) for i in range(n_tasks)]
-        slow = [c / a - 1.0 for c, a in zip(co, sa)]
-        kinds = sorted({t.spec.kind for t in tasks})
-        out["max_slowdown_pct"] = round(100 * max(slow), 2)
-        out["mean_slowdown_pct"] = round(100 * sum(slow) / len(slow), 2)
-        out["slowdown_by_kind_pct"] = {k: round(100 * max(s for s, t in zip(slow, tasks) if t.spec.kind == k), 2)
-                                       for k in kinds}
+        out["serialised_gpu"] = dict(tasks_per_s=round(med([s["tasks_per_s"] for s in ssum]), 2),
+                                     mean_turnaround_ms=round(med([s["mean_turnaround_ms"] for s in ssum]), 3),
+                                     passes=len(sruns), release="host")
+        out["speedup_vs_serialised"] = dict(
+            throughput=round(med([s["tasks_per_s"] for s in sums]) / out["serialised_gpu"]["tasks_per_s"], 4),
+            turnaround=round(out["serialised_gpu"]["mean_turnaround_ms"] / med([s["mean_turnaround_ms"] for s in sums]), 4))
+        # kernel slowdown as the paper defines it (Sec. V, kernel-slowdown table): GPU time of a task in
+        # the shared run over the same task in the single-assignment run of the same workload; per task
+        # the median over the passes
+        co, sa = per_task_median(runs), per_task_median(sruns)
+        sl = slowdown(co, sa)
+        out["max_slowdown_pct"], out["mean_slowdown_pct"], out["slowdown_by_kind_pct"] = sl["max_pct"], sl["mean_pct"], sl["by_kind_max_pct"]
         out["corun_gpu_ms"] = {k: round(max(c for c, t in zip(co, tasks) if t.spec.kind == k), 4) for k in kinds}
         out["serialised_gpu_ms"] = {k: round(max(c for c, t in zip(sa, tasks) if t.spec.kind == k), 4) for k in kinds}
-        # each task alone, back to back on a busy (clocked-up) device: the kernels' own speed
+        # each task alone, back to back on a busy (clocked-up) device: on all 256 CUs (single assignment)
+        # and in the partition its own probe is granted on an otherwise empty device
         log("tasks alone")
-        alone = []
+        alone256, alone_part = [], []
         for t in tasks:
-            harness.run_mix(ser, [t], use_arrivals=False)
-            vals = [harness.run_mix(ser, [t], use_arrivals=False)[0][0]["gpu_ms"] for _ in range(4)]
-            alone.append(sum(vals) / len(vals))
-        out["alone_back_to_back_gpu_ms"] = {k: round(min(a for a, t in zip(alone, tasks) if t.spec.kind == k), 4)
-                                            for k in kinds}
+            for sch, dst in ((ser, alone256), (sched, alone_part)):
+                run(sch, [t], use_arrivals=False)
+                dst.append(med([run(sch, [t], use_arrivals=False)[0][0]["gpu_ms"] for _ in range(5)]))
+        out["alone_back_to_back_gpu_ms"] = {k: round(min(a for a, t in zip(alone256, tasks) if t.spec.kind == k), 4) for k in kinds}
+        out["slowdown_vs_alone_on_256_cus"] = slowdown(co, alone256)
+        out["slowdown_vs_alone_in_the_same_partition"] = slowdown(co, alone_part)
         # the dominant kernel's own speed: the same figure as `roofline`, from the back-to-back launches
         # (the timed region above has idle gaps between arrivals, and the clocks ramp after each)
-        da = [(a, t) for a, t in zip(alone, tasks) if t.kernel_name == dominant]
+        da = [(a, t) for a, t in zip(alone256, tasks) if t.kernel_name == dominant]
         if da:
-            bound, peak, unit = peaks[dominant]
+            bound, peak, unit = PEAKS[dominant]
             work = sum((t.alg_bytes / 1e9 if bound == "hbm" else t.alg_flops / 1e12) for _, t in da)
             ach = work / (sum(a for a, _ in da) / 1e3)
-            out["roofline_back_to_back"] = dict(kernel=dominant, bound=bound, achieved=round(ach, 2), peak=peak,
-                                                unit=unit, frac=round(ach / peak, 4),
-                                                frac_of_measured=round(ach / measured_ceiling(dominant), 4))
-        out["speedup_vs_serialised"] = dict(
-            throughput=round(value / out["serialised_gpu"]["tasks_per_s"], 4),
-            turnaround=round(out["serialised_gpu"]["mean_turnaround_ms"] / mean_turn, 4))
+            out["roofline_back_to_back"] = dict(kernel=dominant, bound=bound, achieved=round(ach, 2), peak=round(peak, 1),
+                                                unit=unit, frac=round(ach / peak, 4))
+            if measured_ceiling(dominant):
+                out["roofline_back_to_back"]["frac_of_measured"] = round(ach / measured_ceiling(dominant), 4)
+
         # batch variant (all tasks queued at t = 0, the paper's setting): capacity rather than arrival bound
+        def batch_leg(sch, release_on_stream, passes=5):
+            run(sch, tasks, use_arrivals=False, release_on_stream=release_on_stream)
+            rr = [run(sch, tasks, use_arrivals=False, release_on_stream=release_on_stream) for _ in range(passes)]
+            ss = [harness.summarize(r, m) for r, m in rr]
+            return rr, dict(tasks_per_s=round(med([x["tasks_per_s"] for x in ss]), 2),
+                            mean_turnaround_ms=round(med([x["mean_turnaround_ms"] for x in ss]), 3),
+                            makespan_ms=round(med([x["makespan_ms"] for x in ss]), 3),
+                            gpu_busy_ms=round(med([x["gpu_busy_ms"] for x in ss]), 3),
+                            tasks_per_s_min_max=[round(min(x["tasks_per_s"] for x in ss), 1), round(max(x["tasks_per_s"] for x in ss), 1)])
+
         log("batch at t=0")
-        # (medians of five passes: the worker threads' scheduling makes single passes vary by several per cent)
-        def med(runs, key):
-            return sorted(x[key] for x in runs)[len(runs) // 2]
-        harness.run_mix(sched, tasks, use_arrivals=False)
-        b = [harness.summarize(*harness.run_mix(sched, tasks, use_arrivals=False)) for _ in range(5)]
-        bs = [harness.summarize(*harness.run_mix(ser, tasks, use_arrivals=False)) for _ in range(5)]
-        out["batch_t0"] = dict(tasks_per_s=round(med(b, "tasks_per_s"), 2),
-                               mean_turnaround_ms=round(med(b, "mean_turnaround_ms"), 3),
-                               tasks_per_s_min_max=[round(min(x["tasks_per_s"] for x in b), 1), round(max(x["tasks_per_s"] for x in b), 1)],
-                               serialised_tasks_per_s=round(med(bs, "tasks_per_s"), 2),
-                               serialised_mean_turnaround_ms=round(med(bs, "mean_turnaround_ms"), 3))
-        # what the co-run sustains as a whole: the tasks' algorithmic HBM bytes and flops over the makespan
-        mk = 1e-3 * med(b, "makespan_ms")
-        out["batch_t0"]["corun_algorithmic_hbm_gbs"] = round(sum(t.alg_bytes for t in tasks) / mk / 1e9, 1)
-        out["batch_t0"]["corun_tflops"] = round(sum(t.alg_flops for t in tasks) / mk / 1e12, 2)
+        brun, b = batch_leg(sched, on_stream)
+        bsrun, bs = batch_leg(ser, False)
+        _, bs_stream = batch_leg(ser, True)
+        _, b_host = batch_leg(sched, False)
+        b["release"] = args.release
+        b["serialised_tasks_per_s"], b["serialised_mean_turnaround_ms"] = bs["tasks_per_s"], bs["mean_turnaround_ms"]
+        b["speedup_vs_serialised"] = round(b["tasks_per_s"] / bs["tasks_per_s"], 4)
+        b["turnaround_speedup_vs_serialised"] = round(bs["mean_turnaround_ms"] / b["mean_turnaround_ms"], 4)
+        # the same two schedulers with the release the other way round, so that what the stream-ordered
+        # release buys and what the partitioning buys can be told apart
+        b["host_release_tasks_per_s"] = b_host["tasks_per_s"]
+        b["serialised_stream_release_tasks_per_s"] = bs_stream["tasks_per_s"]
+        b["slowdown_vs_serialised_batch"] = slowdown(per_task_median(brun), per_task_median(bsrun))
+        # what the co-run sustains as a whole over the makespan: algorithmic bytes and flops of the tasks,
+        # and HBM-side bytes from the hardware counters (bytes per launch of each kernel x its launches)
+        mk = 1e-3 * b["makespan_ms"]
+        b["corun_algorithmic_hbm_gbs"] = round(sum(t.alg_bytes for t in tasks) / mk / 1e9, 1)
+        b["corun_tflops"] = round(sum(t.alg_flops for t in tasks) / mk / 1e12, 2)
+        trs = [traffic_of(t.kernel_name) for t in tasks]
+        if all(x is not None for x in trs):
+            moved = sum(x * (t.launches if t.launches is not None else max(1, int(t.depth.value))) for x, t in zip(trs, tasks))
+            b["corun_hbm_gbs"] = round(moved / mk / 1e9, 1)
+            b["corun_hbm_frac_of_peak"] = round(moved / mk / 1e9 / 8000.0, 4)
+            b["corun_hbm_source"] = "rocprofv3 FETCH_SIZE + WRITE_SIZE per launch (profiles/mix16_hbm_traffic.md) x launches / makespan"
+        else:
+            b["corun_hbm_gbs"] = None
+        b["corun_mfma_frac_of_peak"] = round(sum(t.alg_flops for t in tasks if t.kernel_name == "gemm_f32_dma_kernel") / mk / 1e12 / 157.3, 4)
+        out["batch_t0"] = b
+
         # the other policies on the same mix: Alg. 3 analogue (overlapping masks), FIFO queue,
         # HARD with one workgroup per CU as the residency limit ("spread": a task gets as many
         # CUs as it has workgroups, so only tasks that cannot fill the device share it), and the
-        # memory-blind CG baseline of Sec. IV at four jobs per device
+        # memory-blind CG baseline of Sec. IV at four jobs per device; kernel slowdown of each against
+        # the single-assignment run
         sched.destroy()
         sched = None
         sweep = {}
@@ -369,14 +447,16 @@ def main():
                                             ("cg_ratio4", mgb.MGB_POLICY_CG, mgb.MGB_QUEUE_BACKFILL, 32, 4)):
             log("policy sweep: " + name)
             s2 = mgb.Sched(policy=pol2, queue_mode=q2, mem_cap_bytes=cap, max_wg_per_cu=wgcu, max_running=ratio)
-            harness.run_mix(s2, tasks)
-            a = [harness.summarize(*harness.run_mix(s2, tasks)) for _ in range(3)]
-            harness.run_mix(s2, tasks, use_arrivals=False)
-            bb = [harness.summarize(*harness.run_mix(s2, tasks, use_arrivals=False)) for _ in range(5)]
-            sweep[name] = dict(tasks_per_s=round(sum(x["tasks_per_s"] for x in a) / 3, 2),
-                               mean_turnaround_ms=round(sum(x["mean_turnaround_ms"] for x in a) / 3, 3),
-                               batch_tasks_per_s=round(med(bb, "tasks_per_s"), 2),
-                               batch_mean_turnaround_ms=round(med(bb, "mean_turnaround_ms"), 3))
+            run(s2, tasks, release_on_stream=on_stream)
+            aruns = [run(s2, tasks, release_on_stream=on_stream) for _ in range(3)]
+            a = [harness.summarize(r, m) for r, m in aruns]
+            bruns, bb = batch_leg(s2, on_stream)
+            sweep[name] = dict(tasks_per_s=round(med([x["tasks_per_s"] for x in a]), 2),
+                               mean_turnaround_ms=round(med([x["mean_turnaround_ms"] for x in a]), 3),
+                               max_slowdown_pct=slowdown(per_task_median(aruns), sa)["max_pct"],
+                               batch_tasks_per_s=bb["tasks_per_s"], batch_mean_turnaround_ms=bb["mean_turnaround_ms"],
+                               batch_speedup_vs_serialised=round(bb["tasks_per_s"] / bs["tasks_per_s"], 4),
+                               batch_max_slowdown_pct=slowdown(per_task_median(bruns), per_task_median(bsrun))["max_pct"])
             s2.destroy()
         out["other_policies"] = sweep
         ser.destroy()

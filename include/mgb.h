@@ -199,7 +199,12 @@ int mgb_task_grow(mgb_sched* s, uint64_t ticket, uint64_t extra_bytes);
 
 /* Run enqueue(stream, user) on the task's stream, bracketed by timing events
  * (HIP backend).  enqueue must only enqueue work on `stream` (it may
- * synchronise that stream).  Its return value != 0 is passed back.          */
+ * synchronise that stream).  Its return value != 0 is passed back.
+ * Profiling aid: if MGB_TAG_PARTITIONS was set in the environment when the
+ * scheduler was created, an empty kernel partition_tag_kernel is launched on
+ * the stream first, with (first granted granule * 64 + number of granted
+ * granules) workgroups of 64 threads, so that a kernel trace shows which
+ * partition each hardware queue serves.                                      */
 int mgb_task_launch(mgb_sched* s, uint64_t ticket, int (*enqueue)(void* stream, void* user),
                     void* user);
 

@@ -81,6 +81,17 @@ __global__ __launch_bounds__(256, 1) void mfma_loop_kernel(float* __restrict__ o
 
 }  // namespace
 
+// Marks, in a profiler's kernel trace, which partition a hardware queue belongs to: an empty
+// kernel whose grid encodes the partition (first granule * 64 + number of granules workgroups of
+// one wave).  Launched by mgb_task_launch in front of a task's kernels when MGB_TAG_PARTITIONS is
+// set in the environment.
+__global__ __launch_bounds__(64) void partition_tag_kernel() {}
+
+int mgb_internal_tag_partition(hipStream_t stream, uint32_t first_granule, uint32_t n_granules) {
+  hipLaunchKernelGGL(partition_tag_kernel, dim3(first_granule * 64u + n_granules), dim3(64), 0, stream);
+  return mgb_check_launch("partition_tag_kernel");
+}
+
 extern "C" int mgb_mfma_loop_enqueue(void* stream, uint32_t bf16, uint32_t n_blocks, uint32_t iters,
                                      float* out, double* flops) {
   if (!out || n_blocks == 0u || n_blocks > 65536u || iters == 0u || iters > (1u << 24)) return MGB_E_INVAL;

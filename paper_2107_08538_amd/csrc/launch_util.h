@@ -18,3 +18,5 @@ static inline int mgb_check_launch(const char* what) {
 struct mgb_sched;
 unsigned mgb_internal_backend(const mgb_sched* s);   // MGB_BACKEND_*
 int mgb_internal_device(const mgb_sched* s);         // HIP device ordinal
+// Profiling aid: an empty kernel on `stream` whose grid size names the partition (see cu_trace.hip).
+int mgb_internal_tag_partition(hipStream_t stream, uint32_t first_granule, uint32_t n_granules);

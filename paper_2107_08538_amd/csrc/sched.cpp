@@ -33,6 +33,7 @@
 #include <chrono>
 #include <condition_variable>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <deque>
 #include <mutex>
@@ -137,6 +138,7 @@ struct mgb_sched {
   std::vector<MemPending> mem_pending;
   uint64_t pending_mem = 0;
   hipEvent_t epoch = nullptr;                 // device-clock origin of gpu_start_ms / gpu_stop_ms
+  bool tag_partitions = false;                // MGB_TAG_PARTITIONS: a marker kernel in front of every task
   // one record per ticket (tickets record_base + 1 ...); the older half is dropped at kTraceCap
   std::deque<mgb_task_record> records;
   uint64_t record_base = 0;
@@ -595,6 +597,7 @@ int mgb_sched_create(const mgb_device_desc* desc, mgb_sched** out) {
   s->free_map = s->all_mask;
   s->load.assign(s->G, 0);
   s->gran_pending.assign(s->G, Dep{0, nullptr});
+  s->tag_partitions = std::getenv("MGB_TAG_PARTITIONS") != nullptr;
   if (d.backend == MGB_BACKEND_HIP) {
     hipError_t e = hipSetDevice(d.device);
     if (e == hipSuccess) e = hipEventCreate(&s->epoch);
@@ -806,6 +809,7 @@ int mgb_task_launch(mgb_sched* s, uint64_t ticket, int (*enqueue)(void* stream, 
   hipStream_t stream = nullptr;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   bool hip = false;
+  uint32_t granted = 0;
   {
     std::unique_lock<std::mutex> lk(s->mu);
     auto it = s->tasks.find(ticket);
@@ -822,6 +826,13 @@ int mgb_task_launch(mgb_sched* s, uint64_t ticket, int (*enqueue)(void* stream, 
     e0 = it->second.ev_start;
     e1 = it->second.ev_stop;
     it->second.launched = true;
+    granted = it->second.granted;
+  }
+  if (hip && s->tag_partitions && granted != 0u) {
+    uint32_t first = 0, count = 0;
+    while (!(granted >> first & 1u)) ++first;
+    for (uint32_t g = 0; g < 32u; ++g) count += granted >> g & 1u;
+    (void)mgb_internal_tag_partition(stream, first, count);
   }
   if (hip) {
     hipError_t e = hipSetDevice(s->d.device);
