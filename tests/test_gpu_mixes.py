@@ -6,7 +6,8 @@ import pytest
 
 import oracle
 import workloads as W
-from helpers import assert_trace_matches_replay, check_ledger_invariants, verify_task_output
+from helpers import (FREIVALDS_TOL, assert_trace_matches_replay, band_samples, check_ledger_invariants, cnn_patch_for,
+                     freivalds_ratio, frobenius_rel, verify_task_output, verify_task_output_at_full_size)
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -188,6 +189,80 @@ def test_mixed128_reduced_sizes():
     assert s.destroy() == 0
 
 
+def test_mixed128_full_size_every_output_verified():
+    """All 128 tasks at the sizes the mix states (Jacobi side and GEMM dimension 1024 - 8192, BFS on
+    2^16 - 2^22 vertices), queued at t = 0 and run as the bench runs them (worker pool inside the
+    library, releases ordered on the device).  Every output is checked: BFS levels in full, Jacobi on
+    the dependency cones of sampled cells, every GEMM on one sample per 64 x 64 block of C and by
+    Freivalds' check of the whole product.  Decisions replay; partitions keep one owner in device time."""
+    from concurrent.futures import ThreadPoolExecutor
+    spec = W.mixed128()
+    with ThreadPoolExecutor(max_workers=16) as ex:
+        data = list(ex.map(W.task_data, spec["tasks"]))
+    print("mixed128 full: inputs drawn", flush=True)
+    tasks = [harness.build_task(t, d) for t, d in zip(spec["tasks"], data)]
+    s = mgb.Sched(mem_cap_bytes=min(spec["cap_bytes"], torch.cuda.mem_get_info()[1]))
+    rec, _ = harness.run_mix_native(s, tasks, use_arrivals=False, release_on_stream=True)
+    print("mixed128 full: mix ran", flush=True)
+    with ThreadPoolExecutor(max_workers=16) as ex:                   # the checker's calls release the interpreter lock
+        ratios = list(ex.map(lambda td: verify_task_output_at_full_size(*td), zip(tasks, data)))
+    ratios = [r for r in ratios if r is not None]
+    print("mixed128 full: %d GEMMs, largest Freivalds ratio %.3g (tolerance %.1g)" % (len(ratios), max(ratios), FREIVALDS_TOL), flush=True)
+    assert len(ratios) == sum(t.spec.kind.startswith("gemm") for t in tasks) == 40
+    trace = s.trace()
+    dec = assert_trace_matches_replay(s.desc, trace)
+    check_ledger_invariants(s.desc, trace)
+    assert (dec["kind"] == oracle.D_ADMIT).sum() == 128 and (dec["kind"] == oracle.D_WAIT).sum() > 64
+    _assert_one_owner_in_device_time(rec)
+    # the launch geometries the probes carried span two orders of magnitude (24 workgroups for the
+    # smallest traversal ... 3488 for the largest stencil) and every partition size from an eighth of
+    # the device to all of it is asked for, so small tasks do share the device
+    grids = sorted(int(r["grid"][0]) for r in trace if r["kind"] == mgb.MGB_EV_PROBE)
+    assert grids[0] <= 32 and grids[-1] >= 2048 and grids[-1] >= 100 * grids[0]
+    assert {bin(r["record"].granule_mask).count("1") for r in rec} == {1, 2, 4, 8}
+    assert s.destroy() == 0
+
+
+def test_cnn8_full_size_in_the_mix_sampled_output_pixels():
+    """The eight 10-layer nets on 416 x 416 images at the batch sizes the mix draws, queued at t = 0
+    through the worker pool.  The fp32 output (batch x 13 x 13 x 512) is checked on sampled pixels:
+    each is recomputed by the serial checker's whole chain (bf16 rounding between layers included)
+    from the window of the input image that decides it."""
+    from concurrent.futures import ThreadPoolExecutor
+    spec = W.cnn8()
+    data = [W.task_data(t) for t in spec["tasks"]]
+    tasks = [harness.build_task(t, d) for t, d in zip(spec["tasks"], data)]
+    assert {t.spec.params["batch"] for t in tasks} <= {1, 2, 4, 8} and len({t.spec.params["batch"] for t in tasks}) >= 3
+    s = mgb.Sched(mem_cap_bytes=min(spec["cap_bytes"], torch.cuda.mem_get_info()[1]))
+    rec, _ = harness.run_mix_native(s, tasks, use_arrivals=False, release_on_stream=True)
+    jobs = []
+    for t, d in zip(tasks, data):
+        b = t.spec.params["batch"]
+        rng = np.random.default_rng(100 + t.spec.task_id)
+        got = t.tensors["out"].cpu().numpy().reshape(b, 13, 13, 512)
+        strides = [L["stride"] for L in d["layers"]]
+        pix = [(b - 1, 0, 0), (0, 12, 12), (int(rng.integers(0, b)), int(rng.integers(0, 13)), int(rng.integers(0, 13))),
+               (int(rng.integers(0, b)), 12, int(rng.integers(0, 13)))]
+        for (bi, oy, ox) in pix:
+            jobs.append((t.spec.task_id, d, strides, got[bi, oy, ox].astype(np.float64), bi, oy, ox))
+
+    def one(job):
+        tid, d, strides, got, bi, oy, ox = job
+        y0, y1, x0, x1, ly, lx = cnn_patch_for(oy, ox, 416, 416)
+        ref = oracle.cnn_forward(np.ascontiguousarray(d["x"][bi:bi + 1, y0:y1, x0:x1, :]), d["weights"], strides)[0, ly, lx]
+        return tid, frobenius_rel(got, ref), float(np.abs(ref).max())
+    with ThreadPoolExecutor(max_workers=16) as ex:
+        res = list(ex.map(one, jobs))
+    worst = max(r[1] for r in res)
+    print("cnn8 full: %d output pixels x 512 channels, worst relative Frobenius error %.3g" % (len(res), worst), flush=True)
+    assert worst <= 1e-2 and all(r[2] > 0 for r in res)              # (a pixel of zeros would prove nothing)
+    trace = s.trace()
+    assert_trace_matches_replay(s.desc, trace)
+    check_ledger_invariants(s.desc, trace)
+    _assert_one_owner_in_device_time(rec)
+    assert s.destroy() == 0
+
+
 def test_pressure32_full_size_sampled():
     """16 fp32 GEMM 32768^3 (12 GiB each) + 16 Jacobi 16384^2 x50 (2 GiB each), all at t = 0, cap =
     summed footprints / 1.5 so that admission has to queue.  Inputs of this size are drawn on the
@@ -213,9 +288,12 @@ def test_pressure32_full_size_sampled():
             probe = mgb.probe_of(mgb.mgb_gemm_f32_probe, n, n, n)
             assert probe[0] == 12 * 2 ** 30
             fn = (lambda A, B, Cc, n: lambda st: mgb.mgb_gemm_f32_enqueue(st, P(A), P(B), P(Cc), n, n, n))(A, B, Cc, n)
-            rows, cols = rng.integers(0, n, 24), rng.integers(0, n, 24)
-            rows[:2], cols[:2] = [0, n - 1], [n - 1, 0]
-            checks[t.task_id] = ("gemm", A[rows].cpu().numpy(), B[:, cols].contiguous().cpu().numpy(), rows, cols)
+            # one row per band of 256 rows and one column per band of 256 columns: the 128 x 128 = 16384
+            # entries at their crossings put a sample into every 256 x 256 tile of C
+            rows, cols = band_samples(n, n, 256, 1000 + t.task_id)
+            rows[0], cols[-1] = 0, n - 1
+            dev_r, dev_c = torch.from_numpy(rows).to("cuda:0"), torch.from_numpy(cols).to("cuda:0")
+            checks[t.task_id] = ("gemm", A[dev_r].cpu().numpy(), B[:, dev_c].contiguous().cpu().numpy(), rows, cols)
             tasks.append(harness.Task(t, dict(A=A, B=B, C=Cc), probe, fn, "gemm_f32_dma_kernel", 1))
         else:
             n, it = t.params["n"], t.params["iters"]
@@ -245,10 +323,11 @@ def test_pressure32_full_size_sampled():
         kind = checks[t.spec.task_id][0]
         if kind == "gemm":
             _, a_rows, b_cols, rows, cols = checks[t.spec.task_id]
-            got = t.tensors["C"][rows, cols].cpu().numpy().astype(np.float64)
-            idx = np.arange(len(rows), dtype=np.uint32)
-            ref, den = oracle.gemm_f32_entries(a_rows, b_cols, idx, idx)
-            assert (np.abs(got - ref) / den).max() <= 1e-4, t.spec.task_id
+            dev_r, dev_c = torch.from_numpy(rows).to("cuda:0"), torch.from_numpy(cols).to("cuda:0")
+            got = t.tensors["C"][dev_r][:, dev_c].cpu().numpy().astype(np.float64).ravel()
+            ri, ci = np.meshgrid(np.arange(len(rows), dtype=np.uint32), np.arange(len(cols), dtype=np.uint32), indexing="ij")
+            ref, den = oracle.gemm_f32_entries(a_rows, b_cols, ri.ravel(), ci.ravel())
+            assert len(ref) == 16384 and (np.abs(got - ref) / den).max() <= 1e-4, t.spec.task_id
         else:
             _, patches, it = checks[t.spec.task_id]
             res = t.tensors["u0"] if it % 2 == 0 else t.tensors["u1"]
@@ -257,6 +336,12 @@ def test_pressure32_full_size_sampled():
                 # own ring; elsewhere the rim is at least it + 1 cells from (r, c), out of reach in `it` sweeps
                 want = oracle.jacobi_f32(np.ascontiguousarray(patch), it)[r - r0, c - c0]
                 assert float(res[r, c]) == float(want), (t.spec.task_id, r, c)
+    # Freivalds' check of two whole 32768^3 products on the host (A, B, C copied back: 12 GiB each)
+    gemms = [t for t in tasks if t.spec.kind == "gemm_f32"]
+    for t in (gemms[0], gemms[-1]):
+        ratio = freivalds_ratio(t.tensors["A"].cpu().numpy(), t.tensors["B"].cpu().numpy(), t.tensors["C"].cpu().numpy(), t.spec.task_id)
+        print("pressure32: task %d Freivalds ratio %.3g (tolerance %.1g)" % (t.spec.task_id, ratio, FREIVALDS_TOL), flush=True)
+        assert ratio <= FREIVALDS_TOL, (t.spec.task_id, ratio)
     trace = s.trace()
     dec = assert_trace_matches_replay(s.desc, trace)
     check_ledger_invariants(s.desc, trace)
