@@ -24,7 +24,8 @@ class Task:
         self.tensors = tensors          # keeps the device buffers alive
         self.mem, self.grid, self.block = probe
         self.enqueue = enqueue          # fn(stream) -> status
-        self.kernel_name = kernel_name
+        self.kernel_name = kernel_name  # label of the task's kernels in reports: "jacobi" (the fused-sweep kernels of
+                                        # jacobi.hip), "conv_net" (the layer launches of a net), else the kernel itself
         self.launches = launches        # kernel launches per task (None if data dependent)
         self.alg_bytes = alg_bytes      # algorithmic HBM bytes of the whole task
         self.alg_flops = alg_flops
@@ -41,9 +42,7 @@ def build_task(spec, data, device="cuda:0"):
         u1 = u0.clone()
         probe = mgb.probe_of(mgb.mgb_jacobi_probe, n, it)
         fn = lambda st: mgb.mgb_jacobi_enqueue(st, _ptr(u0), _ptr(u1), n, it)
-        # launches of five to eight sweeps (grids of 4096 columns and more) are the streaming kernel
-        name = "jacobi_stream" if n >= 4096 and n % 4 == 0 and it >= 5 else "jacobi_sweeps"
-        t = Task(spec, dict(u0=u0, u1=u1), probe, fn, name, int(mgb.mgb_jacobi_launch_count(n, it)),
+        t = Task(spec, dict(u0=u0, u1=u1), probe, fn, "jacobi", int(mgb.mgb_jacobi_launch_count(n, it)),
                  alg_bytes=8.0 * (n - 2) * (n - 2) * it, alg_flops=4.0 * (n - 2) * (n - 2) * it,
                  wg_per_cu=int(mgb.mgb_jacobi_residency(n)))
         t.native = (mgb.MGB_TASK_JACOBI, [u0, u1], [n, it], 0, None, None)
@@ -104,7 +103,7 @@ def build_task(spec, data, device="cuda:0"):
         fn = lambda st: mgb.mgb_cnn_enqueue(st, arr, len(layers), _ptr(X), ptrs, _ptr(a0), _ptr(a1), _ptr(out), b, h, w)
         flops = sum(2.0 * b * L["h_out"] * L["w_out"] * L["c_out"] * 9 * L["c_in"] for L in layers)
         t = Task(spec, dict(X=X, W=Wd, a0=a0, a1=a1, out=out, arr=arr, ptrs=ptrs), (mem.value, g, blk), fn,
-                 "conv3x3_kernel", len(layers), alg_bytes=float(mem.value - act.value), alg_flops=flops,
+                 "conv_net", len(layers), alg_bytes=float(mem.value - act.value), alg_flops=flops,
                  wg_per_cu=int(mgb.mgb_cnn_residency(arr, len(layers), b, h, w)))
         t.native = (mgb.MGB_TASK_CNN, [X, a0, a1, out], [b, h, w], len(layers), arr, ptrs)
         return t

@@ -317,7 +317,7 @@ def test_pressure32_full_size_sampled():
                 c0 = min(max(0, c - it - 1), n - side)
                 patches.append((r, c, r0, c0, u0[r0:r0 + side, c0:c0 + side].cpu().numpy().copy()))
             checks[t.task_id] = ("jacobi", patches, it)
-            tasks.append(harness.Task(t, dict(u0=u0, u1=u1), probe, fn, "jacobi_sweeps", 1))
+            tasks.append(harness.Task(t, dict(u0=u0, u1=u1), probe, fn, "jacobi", 1))
     s = mgb.Sched(mem_cap_bytes=spec["cap_bytes"])
     rec, makespan = harness.run_mix(s, tasks, use_arrivals=False)
     for t in tasks:
