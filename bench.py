@@ -15,7 +15,7 @@ sys.path.insert(0, ROOT)
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--mix", default="mix16", choices=["mix4", "mix16", "cnn8", "mixed128", "kinds5"])
     ap.add_argument("--policy", default="hard", choices=["hard", "soft", "serial"])
@@ -353,7 +353,7 @@ def main():
         ser = mgb.Sched(policy=mgb.MGB_POLICY_SERIAL, queue_mode=mgb.MGB_QUEUE_FIFO, mem_cap_bytes=cap)
         for _ in range(max(1, args.warmup)):
             run(ser, tasks, use_arrivals=not args.batch)
-        sruns = [run(ser, tasks, use_arrivals=not args.batch) for _ in range(max(3, args.steps // 2))]
+        sruns = [run(ser, tasks, use_arrivals=not args.batch) for _ in range(max(5, args.steps // 2))]
         ssum = [harness.summarize(r, m) for r, m in sruns]
         out["serialised_gpu"] = dict(tasks_per_s=round(med([s["tasks_per_s"] for s in ssum]), 2),
                                      mean_turnaround_ms=round(med([s["mean_turnaround_ms"] for s in ssum]), 3),
@@ -393,11 +393,26 @@ def main():
                 out["roofline_back_to_back"]["frac_of_measured"] = round(ach / measured_ceiling(dominant), 4)
 
         # batch variant (all tasks queued at t = 0, the paper's setting): capacity rather than arrival bound
+        def device_idle(rec):
+            # device clock (the events around every task, no profiler in the way): time during which no
+            # task's kernels were between their start and stop events, by the kind of task that ended before it
+            iv = sorted((r["record"].gpu_start_ms, r["record"].gpu_stop_ms, r["kind"]) for r in rec if r.get("record") is not None)
+            idle, end, prev = {}, iv[0][1], iv[0][2]
+            for a, b, kind in iv[1:]:
+                if a > end:
+                    idle[prev] = idle.get(prev, 0.0) + (a - end)
+                if b > end:
+                    end, prev = b, kind
+            return idle, end - iv[0][0]
+
         def batch_leg(sch, release_on_stream, passes=5):
             run(sch, tasks, use_arrivals=False, release_on_stream=release_on_stream)
             rr = [run(sch, tasks, use_arrivals=False, release_on_stream=release_on_stream) for _ in range(passes)]
             ss = [harness.summarize(r, m) for r, m in rr]
+            idles = [device_idle(r) for r, _ in rr]
             return rr, dict(tasks_per_s=round(med([x["tasks_per_s"] for x in ss]), 2),
+                            device_span_ms=round(med([sp for _, sp in idles]), 3),
+                            device_idle_ms_after={k: round(med([i.get(k, 0.0) for i, _ in idles]), 4) for k in kinds},
                             mean_turnaround_ms=round(med([x["mean_turnaround_ms"] for x in ss]), 3),
                             makespan_ms=round(med([x["makespan_ms"] for x in ss]), 3),
                             gpu_busy_ms=round(med([x["gpu_busy_ms"] for x in ss]), 3),
@@ -416,6 +431,8 @@ def main():
         # release buys and what the partitioning buys can be told apart
         b["host_release_tasks_per_s"] = b_host["tasks_per_s"]
         b["serialised_stream_release_tasks_per_s"] = bs_stream["tasks_per_s"]
+        b["host_release_device_idle_ms_after"] = b_host["device_idle_ms_after"]
+        b["serialised_device_idle_ms_after"] = bs["device_idle_ms_after"]
         b["slowdown_vs_serialised_batch"] = slowdown(per_task_median(brun), per_task_median(bsrun))
         # what the co-run sustains as a whole over the makespan: algorithmic bytes and flops of the tasks,
         # and HBM-side bytes from the hardware counters (bytes per launch of each kernel x its launches)

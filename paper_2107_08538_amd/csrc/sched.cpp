@@ -71,6 +71,7 @@ enum class State { Waiting, Running, Draining };
 struct Dep {
   uint64_t ticket;     // the draining task whose stop event orders the start
   hipEvent_t ev;       // (nullptr with the null backend)
+  hipStream_t stream;  // the stream that task ran on: a successor on the same stream is ordered already
 };
 
 struct Task {
@@ -128,13 +129,16 @@ struct mgb_sched {
   std::vector<IdleStream> idle_streams;
   std::unordered_map<hipStream_t, uint32_t> stream_users;   // bound streams -> resident tasks on them
   uint64_t stamp = 0;
-  std::vector<hipEvent_t> idle_events;
+  // idle timing events.  A start event only ever measures time, so it is created without the
+  // system-scope fence (the record then does not flush and invalidate the caches in front of the
+  // task's first kernel); a stop event is also what mgb_task_sync and successors wait for and keeps it.
+  std::vector<hipEvent_t> idle_start_events, idle_stop_events;
   uint32_t n_streams = 0;   // created so far
   uint32_t n_alive = 0;     // created and not destroyed
   // stream-ordered releases: per granule the draining task that owned it last (exclusive
   // policies), and every draining task with the bytes it may still be using
   std::vector<Dep> gran_pending;
-  struct MemPending { uint64_t ticket; hipEvent_t ev; uint64_t mem; };
+  struct MemPending { uint64_t ticket; hipEvent_t ev; uint64_t mem; hipStream_t stream; };
   std::vector<MemPending> mem_pending;
   uint64_t pending_mem = 0;
   hipEvent_t epoch = nullptr;                 // device-clock origin of gpu_start_ms / gpu_stop_ms
@@ -153,22 +157,23 @@ struct mgb_sched {
   // behind all of them.
   void collect_deps(Task& t, uint64_t free_before) {
     t.deps.clear();
-    auto add = [&](uint64_t ticket, hipEvent_t ev) {
+    auto add = [&](uint64_t ticket, hipEvent_t ev, hipStream_t st) {
       for (const Dep& d0 : t.deps)
         if (d0.ticket == ticket) return;
-      t.deps.push_back({ticket, ev});
+      t.deps.push_back({ticket, ev, st});
     };
     if (d.policy == MGB_POLICY_HARD || d.policy == MGB_POLICY_SERIAL)
       for (uint32_t g = 0; g < G; ++g)
-        if ((t.granted >> g & 1u) && gran_pending[g].ticket != 0u) add(gran_pending[g].ticket, gran_pending[g].ev);
+        if ((t.granted >> g & 1u) && gran_pending[g].ticket != 0u)
+          add(gran_pending[g].ticket, gran_pending[g].ev, gran_pending[g].stream);
     if (d.policy != MGB_POLICY_CG && pending_mem != 0u && t.mem > free_before - std::min(free_before, pending_mem))
-      for (const MemPending& m : mem_pending) add(m.ticket, m.ev);
+      for (const MemPending& m : mem_pending) add(m.ticket, m.ev, m.stream);
   }
 
   // A draining task's kernels are known to have finished: nothing needs to start behind it any more.
   void forget_pending(uint64_t ticket) {
     for (Dep& g : gran_pending)
-      if (g.ticket == ticket) g = Dep{0, nullptr};
+      if (g.ticket == ticket) g = Dep{0, nullptr, nullptr};
     for (size_t i = 0; i < mem_pending.size(); ++i)
       if (mem_pending[i].ticket == ticket) {
         pending_mem -= mem_pending[i].mem;
@@ -424,13 +429,15 @@ struct mgb_sched {
       tp->stream = st;
       stream_users[st] = 1;
     }
-    for (hipEvent_t* ev : {&tp->ev_start, &tp->ev_stop}) {
+    for (int which = 0; which < 2; ++which) {
+      hipEvent_t* ev = which == 0 ? &tp->ev_start : &tp->ev_stop;
+      std::vector<hipEvent_t>& pool = which == 0 ? idle_start_events : idle_stop_events;
       if (*ev) continue;
-      if (!idle_events.empty()) {
-        *ev = idle_events.back();
-        idle_events.pop_back();
+      if (!pool.empty()) {
+        *ev = pool.back();
+        pool.pop_back();
       } else {
-        hipError_t e = hipEventCreate(ev);
+        hipError_t e = hipEventCreateWithFlags(ev, which == 0 ? hipEventDisableSystemFence : hipEventDefault);
         if (e != hipSuccess) {
           set_error("hipEventCreate", e);
           return MGB_E_BACKEND;
@@ -440,7 +447,7 @@ struct mgb_sched {
     // start behind the draining tasks whose granules or bytes this one took over
     if (!tp->deps_issued) {
       for (const Dep& dep : tp->deps) {
-        if (!dep.ev) continue;
+        if (!dep.ev || dep.stream == tp->stream) continue;      // (its own stream runs in order anyway)
         hipError_t e = hipStreamWaitEvent(tp->stream, dep.ev, 0);
         if (e != hipSuccess) {
           set_error("hipStreamWaitEvent", e);
@@ -459,8 +466,8 @@ struct mgb_sched {
     }
     t.stream = nullptr;
     if (keep_events) return;
-    if (t.ev_start) idle_events.push_back(t.ev_start);
-    if (t.ev_stop) idle_events.push_back(t.ev_stop);
+    if (t.ev_start) idle_start_events.push_back(t.ev_start);
+    if (t.ev_stop) idle_stop_events.push_back(t.ev_stop);
     t.ev_start = t.ev_stop = nullptr;
   }
 
@@ -489,8 +496,8 @@ struct mgb_sched {
       if (t.launched || d.backend != MGB_BACKEND_HIP) {      // (never launched on a device: nothing to wait for)
         if (d.policy == MGB_POLICY_HARD || d.policy == MGB_POLICY_SERIAL)
           for (uint32_t g = 0; g < G; ++g)
-            if (t.granted >> g & 1u) gran_pending[g] = Dep{ticket, ev};
-        mem_pending.push_back({ticket, ev, t.mem});
+            if (t.granted >> g & 1u) gran_pending[g] = Dep{ticket, ev, t.stream};
+        mem_pending.push_back({ticket, ev, t.mem, t.stream});
         pending_mem += t.mem;
       }
       unbind_stream(t, true);
@@ -510,8 +517,8 @@ struct mgb_sched {
     if (it == tasks.end() || it->second.state != State::Draining) return;
     forget_pending(ticket);
     Task& t = it->second;
-    if (t.ev_start) idle_events.push_back(t.ev_start);
-    if (t.ev_stop) idle_events.push_back(t.ev_stop);
+    if (t.ev_start) idle_start_events.push_back(t.ev_start);
+    if (t.ev_stop) idle_stop_events.push_back(t.ev_stop);
     tasks.erase(it);
   }
 
@@ -596,7 +603,7 @@ int mgb_sched_create(const mgb_device_desc* desc, mgb_sched** out) {
   s->free_bytes = d.mem_cap_bytes;
   s->free_map = s->all_mask;
   s->load.assign(s->G, 0);
-  s->gran_pending.assign(s->G, Dep{0, nullptr});
+  s->gran_pending.assign(s->G, Dep{0, nullptr, nullptr});
   s->tag_partitions = std::getenv("MGB_TAG_PARTITIONS") != nullptr;
   if (d.backend == MGB_BACKEND_HIP) {
     hipError_t e = hipSetDevice(d.device);
@@ -645,9 +652,11 @@ int mgb_sched_destroy(mgb_sched* s) {
       (void)hipStreamDestroy(is.stream);
       --g_live_streams;
     }
-    for (hipEvent_t e : s->idle_events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : s->idle_start_events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : s->idle_stop_events) (void)hipEventDestroy(e);
     s->idle_streams.clear();
-    s->idle_events.clear();
+    s->idle_start_events.clear();
+    s->idle_stop_events.clear();
   }
   delete s;
   return MGB_OK;

@@ -13,6 +13,7 @@ Three tables:
 Usage:  python -m paper_2107_08538_amd.profsum stats   <kernel_stats.csv>
         python -m paper_2107_08538_amd.profsum traffic <fetch_counter_collection.csv> <write_counter_collection.csv>
         python -m paper_2107_08538_amd.profsum overlap <kernel_trace.csv> [<tasks per pass> [<fetch csv> <write csv>]]
+        python -m paper_2107_08538_amd.profsum gaps <kernel_trace.csv> <tasks per pass>
         python -m paper_2107_08538_amd.profsum counters <counter_collection.csv> <Counter1,Counter2>
 Each prints markdown on stdout."""
 import csv
@@ -227,6 +228,41 @@ def overlap_md(trace_csv, n_tasks=None, fetch_csv=None, write_csv=None, granule_
     return "\n".join(out)
 
 
+def gaps_md(trace_csv, n_tasks):
+    """Where the device idles inside the last pass of a mix (run with MGB_TAG_PARTITIONS): every
+    interval during which no kernel runs, attributed to the kernel that ended before it and the one
+    that starts after it; a tag dispatch marks the first kernel of a task."""
+    rows = _trace_rows(trace_csv)
+    tag_starts = [s for s, e, name, q, threads in rows if _tag_of(name, threads) is not None]
+    begin = tag_starts[-n_tasks] if len(tag_starts) >= n_tasks else 0
+    rows = [r for r in rows if r[0] >= begin]
+    work = [(s, e, n.split("<")[0]) for s, e, n, q, th in rows]
+    busy = sum(e - s for s, e, n in work if "partition_tag" not in n)
+    t0, t1 = work[0][0], max(e for s, e, n in work)
+    kinds = {}
+    end, prev, after_tag = work[0][1], work[0][2], False
+    for s, e, n in work[1:]:
+        if "partition_tag" in n:
+            after_tag = True
+        if s > end:
+            what = "between two tasks (%s -> %s)" % (prev, "next task") if after_tag or "partition_tag" in n else \
+                   "inside a task (%s -> %s)" % (prev, n)
+            k = kinds.setdefault(what, [0, 0])
+            k[0] += 1
+            k[1] += s - end
+        if e > end:
+            end = e
+            if "partition_tag" not in n:
+                prev, after_tag = n, False
+    idle = sum(v[1] for v in kinds.values())
+    out = ["Last pass: %.3f ms from the first dispatch to the end of the last, kernels busy %.3f ms (summed over queues), device idle %.3f ms (%.1f %%):"
+           % ((t1 - t0) / 1e6, busy / 1e6, idle / 1e6, 100.0 * idle / (t1 - t0)), "",
+           "| idle interval | count | total us | mean us |", "|---|---|---|---|"]
+    for what, (cnt, tot) in sorted(kinds.items(), key=lambda kv: -kv[1][1]):
+        out.append("| %s | %d | %.1f | %.2f |" % (what, cnt, tot / 1e3, tot / 1e3 / cnt))
+    return "\n".join(out)
+
+
 def partition_counters_md(counter_csv, counters, granule_cus=32):
     """Mean of derived counters per (kernel, partition size) from a --pmc run with MGB_TAG_PARTITIONS
     set (counter collection runs one dispatch at a time: these are figures of each kernel inside
@@ -277,6 +313,8 @@ if __name__ == "__main__":
     elif cmd == "overlap":
         a = sys.argv[2:] + [None] * 4
         print(overlap_md(a[0], int(a[1]) if a[1] else None, a[2], a[3]))
+    elif cmd == "gaps":
+        print(gaps_md(sys.argv[2], int(sys.argv[3])))
     elif cmd == "counters":
         print(partition_counters_md(sys.argv[2], sys.argv[3].split(",")))
     else:
