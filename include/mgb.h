@@ -229,8 +229,10 @@ int mgb_task_complete(mgb_sched* s, uint64_t ticket);
  * their kernels end (allocated up front, or freed in stream order); a task that frees its memory
  * from the host right after the call must use mgb_task_complete.
  * Afterwards the ticket is gone for every call except mgb_task_sync, which waits for the task's
- * kernels, reports their time and forgets the task (mgb_sched_destroy does so for tasks nobody
- * synchronised).  Errors as mgb_task_complete.                                   */
+ * kernels, reports their time and forgets the task (one thread may do so: a second concurrent
+ * mgb_task_sync on the ticket gets MGB_E_BAD_STATE; mgb_sched_destroy does it for tasks nobody
+ * synchronised).  A later mgb_task_grow of another task into bytes such a task may still be using
+ * orders that task's further work behind it in the same way.  Errors as mgb_task_complete.      */
 int mgb_task_complete_on_stream(mgb_sched* s, uint64_t ticket);
 
 /* Tickets of the released-on-stream tasks that the resident task `ticket` starts behind (those

@@ -84,6 +84,7 @@ struct Task {
   bool launched = false;
   std::vector<Dep> deps;        // draining tasks this one must start behind
   bool deps_issued = false;     // the waits are on the task's stream
+  bool syncing = false;         // draining: a thread is waiting for its stop event and will retire it
 };
 
 // What is known of a task from its probe to its end (mgb_task_records).
@@ -402,11 +403,20 @@ struct mgb_sched {
     if (!tp->stream) {
       hipStream_t victim = nullptr;
       if (!idle_streams.empty() && g_live_streams.load() >= kStreamsAlive) {
-        size_t v = 0;
-        for (size_t i = 1; i < idle_streams.size(); ++i)
-          if (idle_streams[i].stamp < idle_streams[v].stamp) v = i;
-        victim = idle_streams[v].stream;
-        idle_streams.erase(idle_streams.begin() + (long)v);
+        // least recently used, but never a stream on which a released-on-stream task may still run
+        // (successors compare stream handles to tell whether they are ordered behind it already)
+        auto named = [&](hipStream_t st) {
+          for (const MemPending& m : mem_pending)
+            if (m.stream == st) return true;
+          return false;
+        };
+        size_t v = idle_streams.size();
+        for (size_t i = 0; i < idle_streams.size(); ++i)
+          if (!named(idle_streams[i].stream) && (v == idle_streams.size() || idle_streams[i].stamp < idle_streams[v].stamp)) v = i;
+        if (v != idle_streams.size()) {
+          victim = idle_streams[v].stream;
+          idle_streams.erase(idle_streams.begin() + (long)v);
+        }
       }
       const uint32_t mask = tp->granted;
       const uint64_t ticket = tp->ticket;
@@ -806,6 +816,16 @@ int mgb_task_grow(mgb_sched* s, uint64_t ticket, uint64_t extra_bytes) {
     s->log(MGB_EV_REJECT, &t, 0, 0, 0, {}, {}, 0, MGB_E_BUSY, cause);
     return MGB_E_BUSY;
   }
+  // bytes that released-on-stream tasks may still be using: what the task enqueues from now on
+  // starts behind them
+  if (s->pending_mem != 0u && extra_bytes > s->free_bytes - std::min(s->free_bytes, s->pending_mem))
+    for (const mgb_sched::MemPending& m : s->mem_pending) {
+      bool have = false;
+      for (const Dep& d0 : t.deps) have = have || d0.ticket == m.ticket;
+      if (have) continue;
+      t.deps.push_back({m.ticket, m.ev, m.stream});
+      if (t.deps_issued && t.stream && m.ev && m.stream != t.stream) (void)hipStreamWaitEvent(t.stream, m.ev, 0);
+    }
   s->free_bytes -= extra_bytes;
   t.mem += extra_bytes;
   s->log(MGB_EV_GROWN, &t, 0, 0, 0, {}, {}, t.granted, 0, cause);
@@ -872,6 +892,11 @@ int mgb_task_sync(mgb_sched* s, uint64_t ticket, double* gpu_ms) {
     if (it == s->tasks.end()) return MGB_E_UNKNOWN_TICKET;
     if (it->second.state == State::Waiting) return MGB_E_BAD_STATE;
     draining = it->second.state == State::Draining;
+    if (draining) {
+      // one thread waits for a draining task and forgets it; its events go back to the pool then
+      if (it->second.syncing) return MGB_E_BAD_STATE;
+      it->second.syncing = true;
+    }
     e0 = it->second.ev_start;
     e1 = it->second.ev_stop;
     launched = it->second.launched;

@@ -282,3 +282,21 @@ def test_pool_counts_jobs_lost_to_memory_blind_packing_and_refuses_bad_descripto
     assert mgb.mgb_pool_run(s.h, descs, n, 0, 0, res, None) == mgb.MGB_E_INVAL
     assert mgb.mgb_pool_run(s.h, None, 0, 1, 0, None, None) == 0
     assert s.destroy() == 0
+
+
+def test_growth_into_bytes_that_may_still_be_in_use_and_one_waiter_per_draining_task():
+    s = sched(policy=mgb.MGB_POLICY_SOFT, mem_cap_bytes=100)
+    rc, x = admit(s, 1, 1, mem=60)
+    rc, t = admit(s, 2, 1, mem=20)
+    assert s.deps(t.ticket) == []
+    launch(s, x.ticket)
+    assert s.complete_on_stream(x.ticket) == 0                      # ledger: 80 free, of which 60 may still be in use
+    assert s.grow(t.ticket, 20) == mgb.MGB_OK and s.deps(t.ticket) == []            # 20 <= 80 - 60 certainly unused
+    assert s.grow(t.ticket, 30) == mgb.MGB_OK and s.deps(t.ticket) == [x.ticket]    # 30 > 60 - 60
+    assert s.grow(t.ticket, 40) == mgb.MGB_E_BUSY                   # only 30 left in the ledger
+    # two threads may not both wait for the draining task: the second is refused while the first waits
+    # (null backend: the wait returns at once, so the calls follow each other and the second finds it gone)
+    assert s.sync(x.ticket)[0] == 0 and s.sync(x.ticket)[0] == mgb.MGB_E_UNKNOWN_TICKET
+    assert s.complete(t.ticket) == 0
+    assert_trace_matches_replay(s.desc, s.trace())
+    assert s.destroy() == 0
