@@ -25,6 +25,7 @@ def parse():
     ap.add_argument("--release", default="stream", choices=["stream", "host"],
                     help="hand resources back when the last kernel is enqueued (ordered on the device) or when the host has seen it finish")
     ap.add_argument("--batch", action="store_true", help="timed region with all tasks queued at t = 0 instead of arrivals")
+    ap.add_argument("--workers", type=int, default=None, help="size of the worker pool (default: min(#tasks, 32), the paper's largest pool)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip serialised / alone / batch comparisons")
     ap.add_argument("--dump-records", default=None, help="write the last timed pass's task records (JSON) to this path")
@@ -195,7 +196,7 @@ def main():
 
     def run(sched, tasks, release_on_stream=False, **kw):
         fn = harness.run_mix_native if native else harness.run_mix
-        return fn(sched, tasks, release_on_stream=release_on_stream, **kw)
+        return fn(sched, tasks, release_on_stream=release_on_stream, workers=args.workers, **kw)
 
     mixfn = W.MIXES[args.mix]
     spec = mixfn(args.seed) if args.seed is not None else mixfn()
@@ -324,7 +325,7 @@ def main():
                ms_per_step=round(1e3 * elapsed / args.steps, 3), higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="f32", data="synthetic",
                config=dict(workload="%s: %s" % (spec["name"], ", ".join(sorted({t.kind for t in spec["tasks"]}))),
-                           policy=args.policy, queue=args.queue, tasks=n_tasks, workers=min(n_tasks, harness.MAX_WORKERS),
+                           policy=args.policy, queue=args.queue, tasks=n_tasks, workers=min(n_tasks, args.workers or harness.MAX_WORKERS),
                            arrivals="all at t=0" if args.batch else "as the mix states", harness=args.harness,
                            release=args.release, cap_bytes=cap, granule_cus=int(sched.desc.granule_cus), n_cu=256),
                mean_turnaround_ms=round(mean_turn, 3),
@@ -414,6 +415,7 @@ def main():
                             device_span_ms=round(med([sp for _, sp in idles]), 3),
                             device_idle_ms_after={k: round(med([i.get(k, 0.0) for i, _ in idles]), 4) for k in kinds},
                             mean_turnaround_ms=round(med([x["mean_turnaround_ms"] for x in ss]), 3),
+                            mean_wait_ms=round(med([x["mean_wait_ms"] for x in ss]), 3),
                             makespan_ms=round(med([x["makespan_ms"] for x in ss]), 3),
                             gpu_busy_ms=round(med([x["gpu_busy_ms"] for x in ss]), 3),
                             tasks_per_s_min_max=[round(min(x["tasks_per_s"] for x in ss), 1), round(max(x["tasks_per_s"] for x in ss), 1)])
@@ -472,6 +474,7 @@ def main():
                                mean_turnaround_ms=round(med([x["mean_turnaround_ms"] for x in a]), 3),
                                max_slowdown_pct=slowdown(per_task_median(aruns), sa)["max_pct"],
                                batch_tasks_per_s=bb["tasks_per_s"], batch_mean_turnaround_ms=bb["mean_turnaround_ms"],
+                               batch_mean_wait_ms=bb["mean_wait_ms"],
                                batch_speedup_vs_serialised=round(bb["tasks_per_s"] / bs["tasks_per_s"], 4),
                                batch_max_slowdown_pct=slowdown(per_task_median(bruns), per_task_median(bsrun))["max_pct"])
             s2.destroy()
