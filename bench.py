@@ -450,6 +450,13 @@ def main():
         else:
             b["corun_hbm_gbs"] = None
         b["corun_mfma_frac_of_peak"] = round(sum(t.alg_flops for t in tasks if t.kernel_name == "gemm_f32_dma_kernel") / mk / 1e12 / 157.3, 4)
+        # busy cycles of the matrix and vector pipes over the co-run, from the counters: each kernel's share
+        # of busy cycles (rocprofv3 MfmaUtil / VALUBusy, taken per kernel) weighted by its share of the makespan
+        if args.mix == "mix16":
+            per_task = per_task_median(brun)
+            for key, counter in (("corun_mfma_util_pct", "MfmaUtil"), ("corun_valu_busy_pct", "VALUBusy")):
+                u = [profsum.utilisation_for(TRAFFIC_TABLE, t.kernel_name, counter) for t in tasks]
+                b[key] = None if any(x is None for x in u) else round(sum(x * ms for x, ms in zip(u, per_task)) / b["makespan_ms"], 2)
         out["batch_t0"] = b
 
         # the other policies on the same mix: Alg. 3 analogue (overlapping masks), FIFO queue,

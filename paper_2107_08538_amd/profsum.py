@@ -13,6 +13,7 @@ Three tables:
 Usage:  python -m paper_2107_08538_amd.profsum stats   <kernel_stats.csv>
         python -m paper_2107_08538_amd.profsum traffic <fetch_counter_collection.csv> <write_counter_collection.csv>
         python -m paper_2107_08538_amd.profsum overlap <kernel_trace.csv> [<tasks per pass> [<fetch csv> <write csv>]]
+        python -m paper_2107_08538_amd.profsum utilisation <MfmaUtil csv> <VALUBusy csv> <MeanOccupancyPerActiveCU csv>
         python -m paper_2107_08538_amd.profsum gaps <kernel_trace.csv> <tasks per pass>
         python -m paper_2107_08538_amd.profsum counters <counter_collection.csv> <Counter1,Counter2>
 Each prints markdown on stdout."""
@@ -104,6 +105,42 @@ def traffic_for(md_path, kernel_fragment):
         return None
     n = sum(v[1] for _, v in rows)
     return sum(v[0] * v[1] for _, v in rows) / n
+
+
+UTIL_COUNTERS = ("MfmaUtil", "VALUBusy", "MeanOccupancyPerActiveCU")
+
+
+def utilisation_md(csv_by_counter):
+    """Per kernel: mean over its dispatches of MfmaUtil (share of cycles the matrix pipes are busy, per
+    cent), VALUBusy (the same for the vector units) and MeanOccupancyPerActiveCU, one --pmc run each
+    ({counter: counter_collection.csv}); with the kernel's source hash, like the traffic table."""
+    agg = {c: _pmc(path, c) for c, path in csv_by_counter.items()}
+    mean = lambda v: sum(v) / len(v)
+    kernels = sorted({k for a in agg.values() for k in a if not k.startswith("at::") and "rocclr" not in k})
+    out = ["| kernel | dispatches | " + " | ".join(UTIL_COUNTERS) + " | source sha256/16 (utilisation) |", "|---|---|" + "---|" * (len(UTIL_COUNTERS) + 1)]
+    for k in kernels:
+        n = max(len(agg[c].get(k, [])) for c in agg)
+        cells = ["%.2f" % mean(agg[c][k]) if c in agg and k in agg[c] else "" for c in UTIL_COUNTERS]
+        out.append("| %s | %d | %s | %s |" % (k, n, " | ".join(cells), source_hash(k)))
+    return "\n".join(out)
+
+
+def utilisation_for(md_path, kernel_fragment, counter):
+    """Dispatch-weighted mean of a counter of utilisation_md's table over the rows whose kernel name
+    contains the fragment; None if there is none or the kernel's source has changed since."""
+    col = 2 + UTIL_COUNTERS.index(counter)
+    tot = n = 0.0
+    if not os.path.exists(md_path):
+        return None
+    for line in open(md_path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) != 3 + len(UTIL_COUNTERS) or kernel_fragment not in cells[0] or not re.fullmatch(r"[0-9a-f]{16}", cells[-1] or "x"):
+            continue
+        if cells[-1] != source_hash(cells[0]) or not cells[col]:
+            return None
+        tot += float(cells[col]) * int(cells[1])
+        n += int(cells[1])
+    return tot / n if n else None
 
 
 def _tag_of(name, threads):
@@ -313,6 +350,8 @@ if __name__ == "__main__":
     elif cmd == "overlap":
         a = sys.argv[2:] + [None] * 4
         print(overlap_md(a[0], int(a[1]) if a[1] else None, a[2], a[3]))
+    elif cmd == "utilisation":
+        print(utilisation_md(dict(zip(UTIL_COUNTERS, sys.argv[2:5]))))
     elif cmd == "gaps":
         print(gaps_md(sys.argv[2], int(sys.argv[3])))
     elif cmd == "counters":
