@@ -83,6 +83,27 @@ def test_mix16_and_cnn8_through_the_native_worker_pool(release_on_stream):
         assert s.destroy() == 0
 
 
+@pytest.mark.parametrize("policy,ratio", [(mgb.MGB_POLICY_SOFT, 8), (mgb.MGB_POLICY_CG, 4)])
+def test_mix16_pool_with_overlapping_policies_released_on_stream(policy, ratio):
+    # Alg. 3's analogue and the ratio baseline let tasks share CUs, so a release on the stream orders
+    # nothing for compute (and memory never binds at 288 GB): tasks do overlap in device time, and every
+    # output and decision is still what the checker says
+    spec = W.mix16(seed=7)
+    data = [W.task_data(t) for t in spec["tasks"]]
+    tasks = [harness.build_task(t, d) for t, d in zip(spec["tasks"], data)]
+    s = mgb.Sched(mem_cap_bytes=min(spec["cap_bytes"], torch.cuda.mem_get_info()[1]), policy=policy, max_running=ratio)
+    rec, _ = harness.run_mix_native(s, tasks, use_arrivals=False, release_on_stream=True)
+    for t, d in zip(tasks, data):
+        (verify_task_output_at_full_size if t.spec.kind == "jacobi" else verify_task_output)(t, d)
+    assert_trace_matches_replay(s.desc, s.trace())
+    if policy != mgb.MGB_POLICY_CG:                                       # (CG shares the whole-device mask by definition)
+        check_ledger_invariants(s.desc, s.trace())
+    iv = sorted((r["record"].gpu_start_ms, r["record"].gpu_stop_ms) for r in rec)
+    assert any(b0 < a1 for (a0, a1), (b0, b1) in zip(iv, iv[1:]))         # some tasks did run at the same time
+    assert harness.summarize(rec, 0.0)["tasks"] == 16
+    assert s.destroy() == 0
+
+
 def test_mixed128_reduced_released_on_stream_partitions_keep_one_owner():
     # small tasks share the device in disjoint partitions; a partition changes hands on the device
     s, tasks, data, rec = _run(W.mixed128(shrink=4), use_arrivals=False, release_on_stream=True)
