@@ -28,6 +28,7 @@ def parse():
     ap.add_argument("--workers", type=int, default=None, help="size of the worker pool (default: min(#tasks, 32), the paper's largest pool)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip serialised / alone / batch comparisons")
+    ap.add_argument("--no-other-mixes", action="store_true", help="skip the batch legs of CNN-8, Mixed-128 and the memory-tight mix")
     ap.add_argument("--dump-records", default=None, help="write the last timed pass's task records (JSON) to this path")
     ap.add_argument("--seed", type=int, default=None)
     return ap.parse_args()
@@ -160,6 +161,50 @@ def ipc_leg(mgb):
     sv.stop()
     s.destroy()
     return dict(probe_plus_complete_us=round(via, 2), in_process_us=round(direct, 2))
+
+
+def other_mixes(mgb, harness, W, run, total_b, on_stream):
+    """The mixes in which tasks do share the device, all jobs queued at t = 0 (the paper's setting), HARD
+    against single assignment through the same pool; and the memory-tight mix on which packing by a
+    fixed jobs-per-device ratio without looking at footprints (Sec. IV's CG baseline) loses jobs."""
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    res = {}
+    for name, passes in (("cnn8", 7), ("mixed128", 3)):
+        log("other mixes: " + name)
+        spec = W.MIXES[name]()
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            data = list(ex.map(W.task_data, spec["tasks"]))
+        tasks = [harness.build_task(t, d) for t, d in zip(spec["tasks"], data)]
+        del data
+        cap = min(spec["cap_bytes"], total_b)
+        row = {}
+        for key, pol, q, ros in (("hard", mgb.MGB_POLICY_HARD, mgb.MGB_QUEUE_BACKFILL, on_stream),
+                                 ("serialised", mgb.MGB_POLICY_SERIAL, mgb.MGB_QUEUE_FIFO, False)):
+            s = mgb.Sched(policy=pol, queue_mode=q, mem_cap_bytes=cap)
+            run(s, tasks, use_arrivals=False, release_on_stream=ros)
+            ss = [harness.summarize(*run(s, tasks, use_arrivals=False, release_on_stream=ros)) for _ in range(passes)]
+            row[key] = dict(tasks_per_s=round(med([x["tasks_per_s"] for x in ss]), 1),
+                            mean_turnaround_ms=round(med([x["mean_turnaround_ms"] for x in ss]), 3),
+                            mean_wait_ms=round(med([x["mean_wait_ms"] for x in ss]), 3))
+            s.destroy()
+        row["throughput_vs_serialised"] = round(row["hard"]["tasks_per_s"] / row["serialised"]["tasks_per_s"], 4)
+        row["turnaround_vs_serialised"] = round(row["serialised"]["mean_turnaround_ms"] / row["hard"]["mean_turnaround_ms"], 4)
+        row["tasks"] = len(tasks)
+        res[name + "_batch_t0"] = row
+        del tasks
+        torch.cuda.empty_cache()
+    log("other mixes: memory-tight")
+    spec = W.pressure32(seed=9, scale=1 / 32)                     # 32 tasks whose footprints sum to 1.5 x the cap
+    tasks = [harness.build_task(t, W.task_data(t)) for t in spec["tasks"]]
+    row = {}
+    for key, pol, ratio in (("hard", mgb.MGB_POLICY_HARD, 8), ("cg_ratio8", mgb.MGB_POLICY_CG, 8), ("cg_ratio32", mgb.MGB_POLICY_CG, 32)):
+        s = mgb.Sched(policy=pol, max_running=ratio, mem_cap_bytes=spec["cap_bytes"])
+        sm = harness.summarize(*run(s, tasks, use_arrivals=False))
+        row[key] = dict(finished=sm["tasks"], lost_to_out_of_memory=sm["crashed"])
+        s.destroy()
+    res["memory_tight_32_tasks"] = row
+    return res
 
 
 # what bounds each kernel, its peak and the unit of `achieved`.  The Jacobi kernels fuse up to eight
@@ -487,6 +532,8 @@ def main():
             s2.destroy()
         out["other_policies"] = sweep
         ser.destroy()
+        if not args.no_other_mixes and args.mix == "mix16":
+            out["other_mixes"] = other_mixes(mgb, harness, W, run, total_b, on_stream)
         log("lazy runtime")
         out["lazy_runtime"] = lazy_leg(mgb, cap)
         log("multi-process front end")
