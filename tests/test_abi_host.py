@@ -414,3 +414,27 @@ def test_trace_keeps_the_last_million_records():
     assert mgb.mgb_trace_read(s.h, st.n_events - 2, vp, 8) == 2 and tail["seq"][1] == st.n_events - 1
     assert mgb.mgb_trace_read(s.h, st.n_events, vp, 8) == 0
     assert s.destroy() == 0
+
+
+def test_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 on its own, and the record sizes that
+    # cross it must be what the binding assumes
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("gcc not found")
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "mgb.h"\n'
+                   "int a[sizeof(mgb_trace_rec) == 128 ? 1 : -1];\n"
+                   "int b[sizeof(mgb_task_record) == %d ? 1 : -1];\n"
+                   "int c[sizeof(mgb_pool_result) == %d ? 1 : -1];\n"
+                   "int d[sizeof(mgb_task_desc) == %d ? 1 : -1];\n"
+                   "int e[sizeof(mgb_summary) == %d ? 1 : -1];\n"
+                   "int f[sizeof(mgb_placement) == %d ? 1 : -1];\n"
+                   "int main(void) { mgb_task_desc j = {0}; j.kind = MGB_TASK_CUSTOM; return (int)j.kind - 5; }\n"
+                   % (C.sizeof(mgb.mgb_task_record), C.sizeof(mgb.mgb_pool_result), C.sizeof(mgb.mgb_task_desc),
+                      C.sizeof(mgb.mgb_summary), C.sizeof(mgb.mgb_placement)))
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-fsyntax-only", str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
