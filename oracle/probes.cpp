@@ -109,16 +109,42 @@ void orc_gemm_bf16_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
 }
 
 // One 3x3 conv layer (pad 1): bf16 input, weights and output.  Workgroup shape by layer:
-//   c_in % 32 == 0 and c_out % 8 == 0: 256 threads per 128 pixels x 128 channels (256 x 64 when
+//   stride 1, c_in % 64 == 0 and c_out % 8 == 0: 256 threads per tile of one image's output and
+//     64 channels, if that gives at least 128 workgroups.  A tile is th x tw output pixels with
+//     th * tw <= 256 whose input patch of (th + 2) x (tw + 2) pixels is at most 352 pixels (44 KiB
+//     of LDS at 64 channels); the image is cut into the fewest such tiles;
+//   else c_in % 32 == 0 and c_out % 8 == 0: 256 threads per 128 pixels x 128 channels (256 x 64 when
 //     c_out <= 64); if that gives fewer than 256 workgroups, 64 x 64 tiles instead, with 256
 //     threads (the depth split four ways) when c_in % 64 == 0, else 64 threads;
 //   c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64: 256 threads per 256 pixels (all channels);
 //   otherwise 256 threads per 128 pixels x 64 channels (128 channels when c_out > 64).
-static uint64_t conv_workgroups(uint64_t pixels, uint64_t c_in, uint64_t c_out, uint64_t stride,
+static uint64_t patch_tiles_per_image(uint64_t h, uint64_t w) {
+  uint64_t best = ~0ull;
+  for (uint64_t ny = 1; ny <= h; ++ny) {                 // ny rows of tiles, each ceil(h / ny) pixels high
+    const uint64_t th = ceil_div(h, ny);
+    if (th > 256) continue;
+    for (uint64_t nx = 1; nx <= w && ny * nx < best; ++nx) {
+      const uint64_t tw = ceil_div(w, nx);
+      if (th * tw <= 256 && (th + 2) * (tw + 2) <= 352) { best = ny * nx; break; }
+    }
+  }
+  return best;
+}
+
+static bool conv_patch_path(uint64_t batch, uint64_t ho, uint64_t wo, uint64_t c_in, uint64_t c_out, uint64_t stride,
+                            uint64_t* wgs) {
+  if (stride != 1 || c_in % 64 != 0 || c_out % 8 != 0) return false;
+  *wgs = batch * patch_tiles_per_image(ho, wo) * ceil_div(c_out, 64);
+  return *wgs >= 128;
+}
+
+static uint64_t conv_workgroups(uint64_t batch, uint64_t ho, uint64_t wo, uint64_t c_in, uint64_t c_out, uint64_t stride,
                                 uint64_t* threads, bool* depth_split) {
+  const uint64_t pixels = batch * ho * wo;
   uint64_t wgs;
   *threads = 256;
   *depth_split = false;
+  if (conv_patch_path(batch, ho, wo, c_in, c_out, stride, &wgs)) return wgs;
   if (c_in % 32 == 0 && c_out % 8 == 0) {
     wgs = c_out > 64 ? ceil_div(pixels, 128) * ceil_div(c_out, 128) : ceil_div(pixels, 256) * ceil_div(c_out, 64);
     if (wgs < 256) {
@@ -141,7 +167,7 @@ void orc_conv3x3_probe(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, ui
   out[0] = (batch * h * w * c_in + 9 * c_in * c_out + pixels * c_out) * 2;
   uint64_t threads;
   bool split;
-  uint64_t wgs = conv_workgroups(pixels, c_in, c_out, stride, &threads, &split);
+  uint64_t wgs = conv_workgroups(batch, ho, wo, c_in, c_out, stride, &threads, &split);
   out[1] = round8(wgs); out[2] = 1; out[3] = 1;
   out[4] = threads; out[5] = 1; out[6] = 1;
 }
@@ -174,7 +200,7 @@ void orc_cnn_probe(const uint64_t* c, uint64_t n_layers, uint64_t batch, uint64_
     uint64_t ho = (hh - 1) / stride + 1, wo = (ww - 1) / stride + 1;
     uint64_t pixels = batch * ho * wo, elems = pixels * c_out, th;
     bool split;
-    uint64_t wgs = conv_workgroups(pixels, c_in, c_out, stride, &th, &split);
+    uint64_t wgs = conv_workgroups(batch, ho, wo, c_in, c_out, stride, &th, &split);
     if (split && wgs <= 96 && c_in >= 512) {
       uint64_t own = i + 1 < n_layers ? ceil_div(elems * 2, 256) * 256 : 0;
       uint64_t spare = act_max > own ? act_max - own : 0;
@@ -212,11 +238,14 @@ uint64_t orc_gemm_bf16_residency(uint64_t m, uint64_t n, uint64_t k) {
   }
   return 2;
 }
-//   conv: ring of (pixels + channels) x 32 bf16 x 4 stages (x 64 bf16 for the depth-split tiles); first-layer kernel: 3 strips of 260 pixels padded to 4 bf16 +
+//   conv: patch kernel as said there; else ring of (pixels + channels) x 32 bf16 x 4 stages (x 64 bf16 for the depth-split tiles); first-layer kernel: 3 strips of 260 pixels padded to 4 bf16 +
 //   256 x c_out' bf16 of output staging (c_out' = c_out rounded up to 32); register-staged: 2.
 uint64_t orc_conv3x3_residency(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, uint64_t c_out,
                                uint64_t stride) {
   uint64_t ho = (h - 1) / stride + 1, wo = (w - 1) / stride + 1, pixels = batch * ho * wo;
+  uint64_t patch_wgs;
+  if (conv_patch_path(batch, ho, wo, c_in, c_out, stride, &patch_wgs))
+    return (160 * 1024) / (352 * 64 * 2 + 4 * 64 * 64 * 2);      // the patch and four weight tiles of 64 x 64
   if (c_in % 32 == 0 && c_out % 8 == 0) {
     uint64_t tp = c_out > 64 ? 128 : 256, tc = c_out > 64 ? 128 : 64;
     uint64_t bk = 32;

@@ -1,11 +1,14 @@
 // 3x3 convolution + ReLU (padding 1, stride 1 or 2) as an implicit GEMM on the
 // bf16 matrix cores, and a chain of such layers run as one task.
 //
-// Kernels (each described where it is defined): conv3x3_dma_kernel (c_in % 32 == 0, c_out % 8 == 0:
-// global -> LDS DMA ring, tiles 128 x 128 / 256 x 64 / 64 x 64), conv3x3_dma_ksplit_kernel
-// (c_in % 64 == 0, layers with few tiles: the depth split over the waves of a workgroup and,
-// inside a chain, over workgroups, with conv_split_reduce_kernel), conv3x3_c3_kernel (the
-// 3-channel first layer) and the register-staged conv3x3_kernel for every other shape:
+// Kernels (each described where it is defined): conv3x3_patch_kernel (stride 1, c_in % 64 == 0:
+// the input patch of a 2-D output tile resident in LDS, weights through a DMA ring),
+// conv3x3_dma_kernel (c_in % 32 == 0, c_out % 8 == 0: global -> LDS DMA ring, tiles 128 x 128 /
+// 256 x 64 / 64 x 64) and conv3x3_dma64_kernel (the same tiles with stages of depth 64 when
+// c_in % 64 == 0), conv3x3_dma_ksplit_kernel (c_in % 64 == 0, layers with few tiles: the depth
+// split over the waves of a workgroup and, inside a chain, over workgroups, with
+// conv_split_reduce_kernel), conv3x3_c3_kernel (the 3-channel first layer) and the
+// register-staged conv3x3_kernel for every other shape:
 //
 // GEMM view: rows = output pixels (n, oh, ow), columns = output channels,
 // depth = (r, s, c) = 9 * c_in.  Activations are N,H,W,C and weights K,3,3,C,
@@ -36,6 +39,30 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte chu
 
 constexpr uint32_t CV_BM = 128, CV_THREADS = 256;
 
+// Unsigned division by a number fixed at launch: q = n / d for every 32-bit n, as a multiply-high
+// and two shifts (the round-up method for invariant divisors).  The kernels decode tile and pixel
+// indices with it; the compiler's general division costs some forty instructions each, and a
+// workgroup's set-up runs a dozen or two of them per lane before its first load can be issued.
+struct FastDiv {
+  uint32_t d, m, s1, s2;
+};
+
+FastDiv fast_div(uint32_t d) {
+  uint32_t l = 0u;
+  while (l < 32u && (1ull << l) < d) ++l;                       // ceil(log2(d)), d >= 1
+  FastDiv f;
+  f.d = d;
+  f.m = (uint32_t)(((1ull << 32) * ((1ull << l) - d)) / d + 1ull);
+  f.s1 = l < 1u ? l : 1u;
+  f.s2 = l > 0u ? l - 1u : 0u;
+  return f;
+}
+
+__device__ __forceinline__ uint32_t operator/(uint32_t n, const FastDiv& f) {
+  const uint32_t t = __umulhi(f.m, n);
+  return (t + ((n - t) >> f.s1)) >> f.s2;
+}
+
 struct ConvArgs {
   const uint16_t* x;
   const uint16_t* w;
@@ -45,6 +72,9 @@ struct ConvArgs {
   uint32_t tiles_n, tiles_total, out_f32;
   uint32_t splits;             // depth-split kernel only: workgroups that share one output tile
   float* work;                 // splits > 1: fp32 partial sums [split][pixel][channel]
+  uint32_t th, tw, tiles_y, tiles_x;   // patch kernel only: output tile of th x tw pixels, tiles per image
+  FastDiv by_tiles_n, by_plane, by_wo; // divisors tiles_n, Ho * Wo, Wo
+  FastDiv by_tiles_x, by_tiles_y, by_pw, by_tw;   // patch kernel only: tiles_x, tiles_y, tw + 2, tw
 };
 
 // 16 bytes of zeros in device memory: the source of every padded / out-of-range operand chunk
@@ -108,9 +138,9 @@ __global__ __launch_bounds__(CV_THREADS, 2) void conv3x3_kernel(ConvArgs a) {
     const uint32_t p = bm + row0 + RSTEP * h;
     pv[h] = p < a.pixels;
     const uint32_t pp = pv[h] ? p : 0u;
-    const uint32_t b = pp / (a.Ho * a.Wo);
+    const uint32_t b = pp / a.by_plane;
     const uint32_t rem = pp - b * a.Ho * a.Wo;
-    const uint32_t oh = rem / a.Wo, ow = rem - oh * a.Wo;
+    const uint32_t oh = rem / a.by_wo, ow = rem - oh * a.Wo;
     ih0[h] = (int32_t)(oh * a.stride) - 1;
     iw0[h] = (int32_t)(ow * a.stride) - 1;
     img[h] = b * a.H * a.W;                          // pixel index of the image origin
@@ -249,6 +279,92 @@ __global__ __launch_bounds__(CV_THREADS, 2) void conv3x3_kernel(ConvArgs a) {
       }
 }
 
+// ---- results of a wave's 64 pixels x 64 channels to memory through LDS --------------------------
+//
+// In the out^T accumulator layout (weights as the MFMA's first operand) a lane holds, per quad,
+// four consecutive channels of one pixel: stored straight from the registers that is 8 bytes per
+// lane into 32 different cache lines per instruction, and the write path takes about twice as
+// long over it as the whole depth loop of a 64-channel layer.  Here the wave first lays its tile
+// out in LDS as [pixel][channel] (16-byte chunks XOR-swizzled by the pixel) and then writes 16
+// bytes per lane, the lanes of a pixel's row side by side: whole 128-byte lines (bf16; fp32: 256
+// bytes per pixel).  `stage` is this wave's own 16 KiB of LDS (OUT_STAGE_BYTES; with TABLE 256
+// bytes more), free of other use.  Where the wave's pixels go: with TABLE, pix[i] is the output
+// pixel of lane block i (l32 = lane % 32), negative if there is none, and the lanes exchange them
+// through a table behind the tile; without, pixel r of the tile is output pixel pix[0] + r as long
+// as that is below pix[1].  ch0 is the first of the 64 channels (channels >= c_out are dropped;
+// c_out % 8 == 0).
+constexpr uint32_t OUT_STAGE_BYTES = 64u * 256u;
+
+template <bool TABLE>
+__device__ __forceinline__ void store_tile_via_lds(uint8_t* stage, const f32x16 (&acc)[2][2], const int32_t (&pix)[2],
+                                                   uint32_t ch0, uint32_t K, uint32_t out_f32, void* y) {
+  const uint32_t lane = threadIdx.x & 63u, l32 = lane & 31u, lhi = lane >> 5;
+  int32_t* index = reinterpret_cast<int32_t*>(stage + OUT_STAGE_BYTES);
+  if (TABLE && lhi == 0u) {
+    index[l32] = pix[0];
+    index[32u + l32] = pix[1];
+  }
+  auto pixel_of = [&](uint32_t px) -> int32_t {
+    if (TABLE) return index[px];
+    const int32_t p = pix[0] + (int32_t)px;
+    return p < pix[1] ? p : -1;
+  };
+  if (!out_f32) {
+    // bf16: rows of 128 bytes, chunk = 8 channels; a lane owns half a chunk per quad
+#pragma unroll
+    for (uint32_t i = 0; i < 2; ++i) {
+      const uint32_t px = 32u * i + l32;
+#pragma unroll
+      for (uint32_t j = 0; j < 2; ++j)
+#pragma unroll
+        for (uint32_t g = 0; g < 4; ++g) {
+          uint2 q;
+          q.x = pack_bf16x2(fmaxf(acc[i][j][4u * g], 0.f), fmaxf(acc[i][j][4u * g + 1u], 0.f));
+          q.y = pack_bf16x2(fmaxf(acc[i][j][4u * g + 2u], 0.f), fmaxf(acc[i][j][4u * g + 3u], 0.f));
+          *reinterpret_cast<uint2*>(stage + px * 128u + (((4u * j + g) ^ ((px ^ (px >> 3)) & 7u)) << 4) + 8u * lhi) = q;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    uint16_t* out = reinterpret_cast<uint16_t*>(y);
+#pragma unroll
+    for (uint32_t it = 0; it < 8u; ++it) {
+      const uint32_t px = 8u * it + (lane >> 3), c = lane & 7u;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(stage + px * 128u + ((c ^ ((px ^ (px >> 3)) & 7u)) << 4));
+      const int32_t p = pixel_of(px);
+      const uint32_t ch = ch0 + 8u * c;
+      if (p >= 0 && ch < K) *reinterpret_cast<u32x4*>(out + (size_t)p * K + ch) = v;
+    }
+  } else {
+    // fp32: rows of 256 bytes, chunk = 4 channels = one quad of a lane
+#pragma unroll
+    for (uint32_t i = 0; i < 2; ++i) {
+      const uint32_t px = 32u * i + l32;
+#pragma unroll
+      for (uint32_t j = 0; j < 2; ++j)
+#pragma unroll
+        for (uint32_t g = 0; g < 4; ++g) {
+          const float4 q = make_float4(fmaxf(acc[i][j][4u * g], 0.f), fmaxf(acc[i][j][4u * g + 1u], 0.f),
+                                       fmaxf(acc[i][j][4u * g + 2u], 0.f), fmaxf(acc[i][j][4u * g + 3u], 0.f));
+          *reinterpret_cast<float4*>(stage + px * 256u + (((8u * j + 2u * g + lhi) ^ (px & 15u)) << 4)) = q;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    float* out = reinterpret_cast<float*>(y);
+#pragma unroll
+    for (uint32_t it = 0; it < 16u; ++it) {
+      const uint32_t px = 4u * it + (lane >> 4), c = lane & 15u;
+      const float4 v = *reinterpret_cast<const float4*>(stage + px * 256u + ((c ^ (px & 15u)) << 4));
+      const int32_t p = pixel_of(px);
+      const uint32_t ch = ch0 + 4u * c;
+      if (p >= 0 && ch < K) *reinterpret_cast<float4*>(out + (size_t)p * K + ch) = v;
+    }
+  }
+}
+
 // ---- DMA-ring implicit GEMM (c_in % 32 == 0, c_out % 8 == 0, 16-byte aligned tensors) -----------
 //
 // Same pipeline as the DMA bf16 GEMM: operand tiles of depth 32 go global -> LDS directly
@@ -281,8 +397,9 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma_kernel(ConvArgs a
   const uint32_t per_xcd = (a.tiles_total + 7u) / 8u;
   const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
   if ((blockIdx.x >> 3) >= per_xcd || tile >= a.tiles_total) return;
-  const uint32_t bm = (tile / a.tiles_n) * BMP;
-  const uint32_t bn = (tile % a.tiles_n) * BNC;
+  const uint32_t tile_m = tile / a.by_tiles_n;
+  const uint32_t bm = tile_m * BMP;
+  const uint32_t bn = (tile - tile_m * a.tiles_n) * BNC;
 
   const uint32_t lds_base = lds_address_of(smem);
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
@@ -305,9 +422,9 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma_kernel(ConvArgs a
     const uint32_t p = bm + row;
     const bool pv = p < a.pixels;
     const uint32_t pp = pv ? p : 0u;
-    const uint32_t b = pp / (a.Ho * a.Wo);
+    const uint32_t b = pp / a.by_plane;
     const uint32_t rem = pp - b * a.Ho * a.Wo;
-    const uint32_t oh = rem / a.Wo, ow = rem - oh * a.Wo;
+    const uint32_t oh = rem / a.by_wo, ow = rem - oh * a.Wo;
     const int32_t ih0 = (int32_t)(oh * a.stride) - 1, iw0 = (int32_t)(ow * a.stride) - 1;
     uint32_t taps = 0u;
 #pragma unroll
@@ -420,30 +537,10 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma_kernel(ConvArgs a
   }
   __builtin_amdgcn_s_waitcnt(vm_wait(0));    // no DMA may be in flight when the LDS is given back
 
-  // out^T quads: acc[i][j][4g .. 4g+3] = channels wn + 32j + 8g + 4*lhi + (0..3) of pixel wm + 32i + l32
-#pragma unroll
-  for (uint32_t i = 0; i < 2; ++i) {
-    const uint32_t p = bm + wm + 32u * i + l32;
-#pragma unroll
-    for (uint32_t j = 0; j < 2; ++j)
-#pragma unroll
-      for (uint32_t g = 0; g < 4; ++g) {
-        const uint32_t ch = bn + wn + 32u * j + 8u * g + 4u * lhi;
-        if (p < a.pixels && ch < a.K) {                   // c_out % 4 == 0: a quad is inside or outside as a whole
-          float v[4];
-#pragma unroll
-          for (uint32_t e = 0; e < 4; ++e) v[e] = fmaxf(acc[i][j][4u * g + e], 0.f);
-          if (a.out_f32) {
-            *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.y) + (size_t)p * a.K + ch) = make_float4(v[0], v[1], v[2], v[3]);
-          } else {
-            uint2 q;
-            q.x = pack_bf16x2(v[0], v[1]);
-            q.y = pack_bf16x2(v[2], v[3]);
-            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.y) + (size_t)p * a.K + ch) = q;
-          }
-        }
-      }
-  }
+  // every wave is done with the ring: each takes a part of the LDS to stage its 64 pixels x 64 channels
+  __syncthreads();
+  const int32_t pix[2] = {(int32_t)(bm + wm), (int32_t)a.pixels};
+  store_tile_via_lds<false>(smem + wave * OUT_STAGE_BYTES, acc, pix, bn + wn, a.K, a.out_f32, a.y);
 }
 
 // ---- DMA-ring implicit GEMM with the depth split over the waves of a workgroup ------------------
@@ -470,8 +567,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
   const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
   if ((blockIdx.x >> 3) >= per_xcd || tile >= a.tiles_total) return;    // tiles_total counts (tile, split) pairs
   const uint32_t split = tile % a.splits, otile = tile / a.splits;
-  const uint32_t bm = (otile / a.tiles_n) * 64u;
-  const uint32_t bn = (otile % a.tiles_n) * 64u;
+  const uint32_t tile_m = otile / a.by_tiles_n;
+  const uint32_t bm = tile_m * 64u;
+  const uint32_t bn = (otile - tile_m * a.tiles_n) * 64u;
   const uint32_t kt0 = split * (a.depth / KS_BK) / a.splits;             // this workgroup's depth tiles [kt0, kt0 + nk)
   const uint32_t nk = (split + 1u) * (a.depth / KS_BK) / a.splits - kt0;
 
@@ -492,9 +590,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
     const uint32_t p = bm + row;
     const bool pv = p < a.pixels;
     const uint32_t pp = pv ? p : 0u;
-    const uint32_t b = pp / (a.Ho * a.Wo);
+    const uint32_t b = pp / a.by_plane;
     const uint32_t rem = pp - b * a.Ho * a.Wo;
-    const uint32_t oh = rem / a.Wo, ow = rem - oh * a.Wo;
+    const uint32_t oh = rem / a.by_wo, ow = rem - oh * a.Wo;
     const int32_t ih0 = (int32_t)(oh * a.stride) - 1, iw0 = (int32_t)(ow * a.stride) - 1;
     uint32_t taps = 0u;
 #pragma unroll
@@ -656,6 +754,369 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(const float* __r
   }
 }
 
+// ---- DMA-ring implicit GEMM with operand tiles of depth 64 (c_in % 64 == 0) ---------------------
+//
+// The tiles of conv3x3_dma_kernel with rows of 128 bytes instead of 64.  A row of an operand tile
+// is then one whole cache line of the tensor (a pixel's 64 consecutive channels, a filter's 64
+// consecutive depth values) instead of half of one: the 64-byte rows of the depth-32 tiles make
+// the vector cache fetch every line twice, in two steps a few hundred nanoseconds apart, by which
+// time a CU's two workgroups have pushed it out again, and a load that uses half of each line it
+// touches runs at half the rate (measured: 28 against 56 bytes per clock and CU out of L2, 4.7
+// against 10 TB/s out of the last-level cache, where the activations of a large batch live).
+//
+// The ring has two stages of depth 64 (the same bytes as four of depth 32).  A stage is consumed
+// as four 16-deep slices; the whole DMA of tile t+2 is issued between the MFMAs of slice 3 of tile
+// t, right after the barrier that frees tile t's stage, and has the three other slices of tile
+// t+1 (and the CU's other workgroup) to land.  Rows are XOR-swizzled in 16-byte chunks
+// (row_swz8) through each lane's choice of source chunk.
+template <uint32_t WM, uint32_t WN>
+__global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma64_kernel(ConvArgs a) {
+  constexpr uint32_t NW = WM * WN;
+  constexpr uint32_t BMP = 64u * WM, BNC = 64u * WN;             // pixels x channels per workgroup
+  constexpr uint32_t A_BYTES = BMP * 128u, B_BYTES = BNC * 128u, STAGE = A_BYTES + B_BYTES;
+  constexpr uint32_t NA = BMP / 8u / NW, NB = BNC / 8u / NW;     // DMA instructions per wave per tile
+  constexpr uint32_t ND = NA + NB;
+  static_assert(NA >= 1u && NB >= 1u, "every wave takes part in both operand copies");
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+  const uint32_t per_xcd = (a.tiles_total + 7u) / 8u;
+  const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || tile >= a.tiles_total) return;
+  const uint32_t tile_m = tile / a.by_tiles_n;
+  const uint32_t bm = tile_m * BMP;
+  const uint32_t bn = (tile - tile_m * a.tiles_n) * BNC;
+
+  const uint32_t lds_base = lds_address_of(smem);
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t wm = (wave / WN) * 64u, wn = (wave % WN) * 64u;
+  const uint32_t l32 = lane & 31u, lhi = lane >> 5;
+  const uint16_t* zeros = reinterpret_cast<const uint16_t*>(g_zero16);
+
+  // DMA roles.  Instruction h of wave w fills the 1 KiB block b = N*w + h of an operand part:
+  // rows 8b .. 8b+7, lane -> row 8b + lane/8, LDS chunk lane%8, source chunk swizzled.
+  int64_t a_src[NA];        // element offset of the pixel's (ih0, iw0) corner, plus the chunk
+  uint32_t a_taps[NA];      // bit 3r+s: tap (r, s) lies inside the image (0 for pixels past the end)
+  const uint16_t* b_src[NB];
+#pragma unroll
+  for (uint32_t h = 0; h < NA; ++h) {
+    const uint32_t row = 8u * (NA * wave + h) + (lane >> 3);
+    const uint32_t p = bm + row;
+    const bool pv = p < a.pixels;
+    const uint32_t pp = pv ? p : 0u;
+    const uint32_t b = pp / a.by_plane;
+    const uint32_t rem = pp - b * a.Ho * a.Wo;
+    const uint32_t oh = rem / a.by_wo, ow = rem - oh * a.Wo;
+    const int32_t ih0 = (int32_t)(oh * a.stride) - 1, iw0 = (int32_t)(ow * a.stride) - 1;
+    uint32_t taps = 0u;
+#pragma unroll
+    for (int32_t r = 0; r < 3; ++r)
+#pragma unroll
+      for (int32_t t = 0; t < 3; ++t)
+        if (pv && (uint32_t)(ih0 + r) < a.H && (uint32_t)(iw0 + t) < a.W) taps |= 1u << (3 * r + t);
+    a_taps[h] = taps;
+    a_src[h] = (((int64_t)b * a.H + ih0) * a.W + iw0) * a.C + 8u * ((lane & 7u) ^ row_swz8(row));
+  }
+#pragma unroll
+  for (uint32_t h = 0; h < NB; ++h) {
+    const uint32_t row = 8u * (NB * wave + h) + (lane >> 3);
+    b_src[h] = a.w + (size_t)min(bn + row, a.K - 1u) * a.depth + 8u * ((lane & 7u) ^ row_swz8(row));
+  }
+
+  const uint32_t nk = a.depth / 64u;
+  uint32_t td = 0u, a_tap = 0u, a_c0 = 0u;   // DMA cursor: tile, its filter tap, first channel
+  // instruction h of tile td's DMA (pixel blocks first, then weight blocks)
+  auto dma_part = [&](uint32_t h) {
+    const uint32_t stage = lds_base + (td & 1u) * STAGE;
+    if (h < NA) {
+      const uint32_t r = (a_tap * 11u) >> 5, t = a_tap - 3u * r;
+      const int64_t delta = ((int64_t)r * a.W + t) * a.C + a_c0;
+      const uint32_t ok = (a_taps[h] >> a_tap) & 1u;
+      dma16(pick(a.x + a_src[h] + delta, zeros, ok), stage + (NA * wave + h) * 1024u);
+    } else {
+      dma16(b_src[h - NA] + (size_t)td * 64u, stage + A_BYTES + (NB * wave + h - NA) * 1024u);
+    }
+  };
+  auto next_tile = [&]() {
+    a_c0 += 64u;
+    if (a_c0 == a.C) { a_c0 = 0u; ++a_tap; }
+    ++td;
+  };
+
+  f32x16 acc[2][2];                          // [pixel block][channel block]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // fragment addresses inside a stage for slice 0; slice q lies at the address ^ (q << 5)
+  uint32_t p_off[2], w_off[2];
+#pragma unroll
+  for (uint32_t i = 0; i < 2; ++i) {
+    const uint32_t prow = wm + 32u * i + l32, wrow = wn + 32u * i + l32;
+    p_off[i] = prow * 128u + ((lhi ^ row_swz8(prow)) << 4);
+    w_off[i] = A_BYTES + wrow * 128u + ((lhi ^ row_swz8(wrow)) << 4);
+  }
+  u32x4 fp[2][2], fw[2][2];                  // [slot][block]
+  auto frag_load = [&](const uint8_t* st, uint32_t q, uint32_t slot, uint32_t m) {   // m: w0, p0, p1, w1
+    if (m == 0u) fw[slot][0] = *reinterpret_cast<const u32x4*>(st + (w_off[0] ^ (q << 5)));
+    else if (m == 3u) fw[slot][1] = *reinterpret_cast<const u32x4*>(st + (w_off[1] ^ (q << 5)));
+    else fp[slot][m - 1u] = *reinterpret_cast<const u32x4*>(st + (p_off[m - 1u] ^ (q << 5)));
+  };
+  // 4 MFMAs on fragment slot `slot` (order (j, i) = (0,0) (0,1) (1,0) (1,1)); spread between them
+  // the 4 fragment reads of slice fq of the stage at fst into the other slot and, if `dma`, the
+  // DMA of tile td
+  auto block = [&](uint32_t slot, const uint8_t* fst, uint32_t fq, bool dma) {
+#pragma unroll
+    for (uint32_t m = 0; m < 4u; ++m) {
+      const uint32_t j = m >> 1, i = m & 1u;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fw[slot][j]), as_bf16x8(fp[slot][i]), acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      frag_load(fst, fq, slot ^ 1u, m);
+      if (dma) {
+#pragma unroll
+        for (uint32_t h = m * ND / 4u; h < (m + 1u) * ND / 4u; ++h) dma_part(h);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+#pragma unroll
+  for (uint32_t t = 0; t < 2u; ++t) {        // depth = 9 * c_in: at least nine tiles
+#pragma unroll
+    for (uint32_t h = 0; h < ND; ++h) dma_part(h);
+    next_tile();
+  }
+  __builtin_amdgcn_s_waitcnt(vm_wait(ND));   // this wave's part of tile 0 has landed
+  __syncthreads();
+#pragma unroll
+  for (uint32_t m = 0; m < 4u; ++m) frag_load(smem, 0u, 0u, m);
+  for (uint32_t kt = 0; kt < nk; ++kt) {
+    const uint8_t* cur = smem + (kt & 1u) * STAGE;
+    const uint8_t* nxt = smem + ((kt + 1u) & 1u) * STAGE;
+    block(0u, cur, 1u, false);
+    block(1u, cur, 2u, false);
+    block(0u, cur, 3u, false);
+    // Every fragment read of tile kt has been issued; once they have returned and every DMA this
+    // wave issued has landed (the last were tile kt+1's), the barrier tells that tile kt+1 is
+    // complete and that tile kt's stage may be overwritten.
+    __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) and lgkmcnt(0)
+    __syncthreads();
+    if (kt + 2u < nk) {
+      block(1u, nxt, 0u, true);              // tile kt+2 into the stage tile kt leaves
+      next_tile();
+    } else {
+      block(1u, nxt, 0u, false);             // (past the last tile the reads fetch stale bytes nobody uses)
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(vm_wait(0));    // no DMA may be in flight when the LDS is given back
+
+  // every wave is done with the ring: each takes a part of the LDS to stage its 64 pixels x 64 channels
+  __syncthreads();
+  const int32_t pix[2] = {(int32_t)(bm + wm), (int32_t)a.pixels};
+  store_tile_via_lds<false>(smem + wave * OUT_STAGE_BYTES, acc, pix, bn + wn, a.K, a.out_f32, a.y);
+}
+
+// ---- stride-1 layers with the input patch of a 2-D output tile held in LDS (c_in % 64 == 0) ------
+//
+// The implicit-GEMM kernels above fetch every activation once per filter tap: nine times, from L2
+// or the last-level cache, and that traffic together with the address arithmetic of its DMA is
+// what bounds them on the layers with many pixels.  Here a workgroup owns th x tw output pixels of
+// one image (th * tw <= 256) and 64 output channels.  For each block of 64 input channels it
+// copies the (th + 2) x (tw + 2) input pixels around its tile into LDS once (128 bytes per pixel,
+// zeros for the padding ring outside the image), and the nine taps read their pixel operand from
+// that patch at a shifted position: patch pixel (ty + r, tx + s) for output pixel (ty, tx) and tap
+// (r, s).  Only the weights stream through a DMA ring (four stages of 64 channels x 64 depth
+// values, one stage per tap).  The tile shape is chosen per layer on the host so that the tiles
+// cover the image with little overhang.
+//
+// Four waves, each 64 pixels x 64 channels; pixel q = 64 * wave + 32 * i + l32 of the tile is
+// (q / tw, q % tw).  Patch pixels and weight rows are 128-byte rows with their 16-byte chunks
+// XOR-swizzled: weight rows by row_swz8 of the channel as in the depth-64 kernel; patch pixels by
+// the low three bits of the pixel index, which keeps any eight consecutive pixels on different
+// chunks whatever the tap's shift (row_swz8 assumes an even first row).
+// Schedule per tap (one weight tile): four 16-deep slices of 4 MFMAs; the fragments of the next
+// slice are read between the MFMAs of the current one; a barrier after slice 0 tells that the
+// next weight tile has landed and that every wave is done with the previous tap, then the weight
+// tile three taps ahead is requested into the stage the previous tap leaves.  The patch is single:
+// when a channel block is finished the next one is requested and awaited (the CU's other
+// workgroup computes meanwhile).  The results leave through store_tile_via_lds.
+constexpr uint32_t PT_WST = 4u, PT_WTILE = 64u * 128u;
+constexpr uint32_t PT_NPB = 11u;                          // patch DMA instructions per wave, 8 pixels each
+constexpr uint32_t PT_MAX_SLOTS = 4u * PT_NPB * 8u;       // 352 patch pixels
+constexpr uint32_t PT_PATCH = PT_MAX_SLOTS * 128u;        // 44 KiB
+constexpr uint32_t PT_LDS = PT_PATCH + PT_WST * PT_WTILE; // 76 KiB: two workgroups per CU
+constexpr uint32_t PT_MIN_TILES = 128u;                   // layers with fewer tiles take the depth-split kernel
+
+__global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(ConvArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+  const uint32_t per_xcd = (a.tiles_total + 7u) / 8u;
+  const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || tile >= a.tiles_total) return;
+  uint32_t rest = tile / a.by_tiles_n;
+  const uint32_t bn = (tile - rest * a.tiles_n) * 64u;
+  uint32_t up = rest / a.by_tiles_x;
+  const uint32_t tile_x = rest - up * a.tiles_x;
+  const uint32_t img = up / a.by_tiles_y, tile_y = up - img * a.tiles_y;
+  const uint32_t oh0 = tile_y * a.th, ow0 = tile_x * a.tw;
+  const uint32_t pw = a.tw + 2u, slots = (a.th + 2u) * pw;
+  const uint32_t nph = ((slots + 7u) / 8u + 3u) / 4u;    // patch DMA instructions per wave that carry pixels
+
+  const uint32_t lds_base = lds_address_of(smem);
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t l32 = lane & 31u, lhi = lane >> 5;
+  const uint16_t* zeros = reinterpret_cast<const uint16_t*>(g_zero16);
+  const uint32_t ncb = a.C / 64u, nk = 9u * ncb;
+
+  // Patch DMA roles: instruction h of wave w fills the 1 KiB block 4h + w = patch pixels
+  // 8 * (4h + w) .. + 7; lane -> pixel + lane / 8, LDS chunk lane % 8, source chunk swizzled.
+  // A pixel outside the image (the padding ring) or past the patch reads the block of zeros,
+  // and its source does not advance from one channel block to the next.  The first channel
+  // block is requested here, each instruction as soon as its address is known.
+  // (origin: the input pixel under patch pixel (0, 0); it lies outside the tensor for tiles at the
+  // top or left edge, and is only ever used with offsets that lead back inside)
+  const uint16_t* origin = a.x + (((int64_t)img * a.H + oh0) * a.W + ow0 - (int64_t)a.W - 1) * a.C;
+  const uint16_t* a_ptr[PT_NPB];
+  uint32_t a_real = 0u;                      // bit h: instruction h of this lane reads the tensor
+#pragma unroll
+  for (uint32_t h = 0; h < PT_NPB; ++h) {
+    const uint32_t slot = 8u * (4u * h + wave) + (lane >> 3);
+    const uint32_t py = slot / a.by_pw, px = slot - py * pw;
+    const bool ok = slot < slots && oh0 + py - 1u < a.H && ow0 + px - 1u < a.W;   // (- 1 wraps to a huge value above / left of the image)
+    const uint16_t* src = origin + (uint64_t)(py * a.W + px) * a.C + 8u * ((lane & 7u) ^ (slot & 7u));
+    a_ptr[h] = ok ? src : zeros;
+    a_real |= (ok ? 1u : 0u) << h;
+    if (h < nph) {
+      dma16(a_ptr[h], lds_base + (4u * h + wave) * 1024u);
+      a_ptr[h] = reinterpret_cast<const uint16_t*>(reinterpret_cast<uintptr_t>(a_ptr[h]) + ((ok ? 1u : 0u) << 7));
+    }
+  }
+  // weights: instruction h of wave w fills rows 8 * (2w + h) .. + 7 of a stage
+  const uint16_t* b_src[2];
+#pragma unroll
+  for (uint32_t h = 0; h < 2; ++h) {
+    const uint32_t row = 8u * (2u * wave + h) + (lane >> 3);
+    b_src[h] = a.w + (size_t)min(bn + row, a.K - 1u) * a.depth + 8u * ((lane & 7u) ^ row_swz8(row));
+  }
+  // weight tile t belongs to channel block t / 9 and tap t % 9: depth offset tap * C + 64 * block.
+  // The cursor stops at the last tile; the requests past it land in stages nobody reads and
+  // keep the count of outstanding requests the same in every iteration.
+  uint32_t wt = 0u, w_tap = 0u, w_cb = 0u;
+  auto dma_weights = [&]() {
+    const size_t off = (size_t)w_tap * a.C + 64u * w_cb;
+    const uint32_t stage = lds_base + PT_PATCH + (wt & (PT_WST - 1u)) * PT_WTILE;
+#pragma unroll
+    for (uint32_t h = 0; h < 2; ++h) dma16(b_src[h] + off, stage + (2u * wave + h) * 1024u);
+    if (wt + 1u < nk) {
+      if (++w_tap == 9u) { w_tap = 0u; ++w_cb; }
+    }
+    ++wt;
+  };
+#pragma unroll
+  for (uint32_t t = 0; t < PT_WST - 1u; ++t) dma_weights();   // depth = 9 * c_in: at least nine tiles
+
+  f32x16 acc[2][2];                          // [pixel block][channel block]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // this lane's two pixels: patch pixel index of tap (0, 0), and where the result goes
+  uint32_t slot0[2];
+  int64_t out_px[2];                         // output pixel index, -1 if the lane has none
+#pragma unroll
+  for (uint32_t i = 0; i < 2; ++i) {
+    const uint32_t q = 64u * wave + 32u * i + l32;
+    const uint32_t ty = q / a.by_tw, tx = q - ty * a.tw;
+    const bool ok = q < a.th * a.tw && oh0 + ty < a.Ho && ow0 + tx < a.Wo;
+    slot0[i] = q < a.th * a.tw ? ty * pw + tx : 0u;
+    out_px[i] = ok ? ((int64_t)img * a.Ho + oh0 + ty) * a.Wo + ow0 + tx : -1;
+  }
+  // byte address (inside the patch) of slice 0 of the pixel fragment for a tap whose patch offset is `shift`
+  auto patch_off = [&](uint32_t i, uint32_t shift) {
+    const uint32_t slot = slot0[i] + shift;
+    return slot * 128u + ((lhi ^ (slot & 7u)) << 4);
+  };
+  uint32_t w_off[2];                         // the same for the weight fragment, inside a stage
+#pragma unroll
+  for (uint32_t j = 0; j < 2; ++j) {
+    const uint32_t wrow = 32u * j + l32;
+    w_off[j] = wrow * 128u + ((lhi ^ row_swz8(wrow)) << 4);
+  }
+
+  u32x4 fp[2][2], fw[2][2];                  // [slot][block]
+  // fragment m (w0, p0, p1, w1) of slice q: pixels at p_at[] inside the patch, weights in stage wst
+  auto frag_load = [&](const uint32_t (&p_at)[2], const uint8_t* wst, uint32_t q, uint32_t slot, uint32_t m) {
+    if (m == 0u) fw[slot][0] = *reinterpret_cast<const u32x4*>(wst + (w_off[0] ^ (q << 5)));
+    else if (m == 3u) fw[slot][1] = *reinterpret_cast<const u32x4*>(wst + (w_off[1] ^ (q << 5)));
+    else fp[slot][m - 1u] = *reinterpret_cast<const u32x4*>(smem + (p_at[m - 1u] ^ (q << 5)));
+  };
+  // 4 MFMAs on fragment slot `slot`; between them the 4 fragment reads of slice fq (pixels at
+  // p_at, weights in wst) into the other slot and, if `dma`, the request for the next weight tile
+  auto block = [&](uint32_t slot, const uint32_t (&p_at)[2], const uint8_t* wst, uint32_t fq, bool dma) {
+#pragma unroll
+    for (uint32_t m = 0; m < 4u; ++m) {
+      const uint32_t j = m >> 1, i = m & 1u;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fw[slot][j]), as_bf16x8(fp[slot][i]), acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      frag_load(p_at, wst, fq, slot ^ 1u, m);
+      if (dma && m == 1u) dma_weights();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  uint32_t kt = 0u;
+  for (uint32_t cb = 0; cb < ncb; ++cb) {
+    if (cb != 0u) {
+      // the patch of this channel block, once every wave has read the previous one to the end
+      __builtin_amdgcn_s_waitcnt(0xC07Fu);   // lgkmcnt(0)
+      __syncthreads();
+#pragma unroll
+      for (uint32_t h = 0; h < PT_NPB; ++h)
+        if (h < nph) {
+          dma16(a_ptr[h], lds_base + (4u * h + wave) * 1024u);
+          a_ptr[h] = reinterpret_cast<const uint16_t*>(reinterpret_cast<uintptr_t>(a_ptr[h]) + (((a_real >> h) & 1u) << 7));
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(vm_wait(0));
+    __syncthreads();
+    uint32_t p_at[2] = {patch_off(0u, 0u), patch_off(1u, 0u)};
+    {
+      const uint8_t* wst = smem + PT_PATCH + (kt & (PT_WST - 1u)) * PT_WTILE;
+#pragma unroll
+      for (uint32_t m = 0; m < 4u; ++m) frag_load(p_at, wst, 0u, 0u, m);
+    }
+    for (uint32_t tap = 0; tap < 9u; ++tap, ++kt) {
+      const uint8_t* wst = smem + PT_PATCH + (kt & (PT_WST - 1u)) * PT_WTILE;
+      block(0u, p_at, wst, 1u, false);
+      // At most the weight tile after the next is outstanding: the next one has landed, and the
+      // barrier tells so for every wave's part.  It also tells that every wave has finished the
+      // previous tap (its last MFMAs needed that tap's last fragments), whose stage the request
+      // of the following block overwrites with the tile three taps ahead.
+      __builtin_amdgcn_s_waitcnt(vm_wait(2));
+      __syncthreads();
+      block(1u, p_at, wst, 2u, true);
+      block(0u, p_at, wst, 3u, false);
+      const uint32_t nt = tap + 1u < 9u ? tap + 1u : 8u;     // (after the last tap the reads fetch bytes nobody uses)
+      const uint32_t r = (nt * 11u) >> 5, t = nt - 3u * r;
+      p_at[0] = patch_off(0u, r * pw + t);
+      p_at[1] = patch_off(1u, r * pw + t);
+      block(1u, p_at, smem + PT_PATCH + ((kt + 1u) & (PT_WST - 1u)) * PT_WTILE, 0u, false);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(vm_wait(0));    // no DMA may be in flight when the LDS is given back
+
+  // the patch and the ring are done with: every wave takes a part of the LDS to stage its results
+  __syncthreads();
+  const int32_t pix[2] = {(int32_t)out_px[0], (int32_t)out_px[1]};
+  store_tile_via_lds<true>(smem + wave * (OUT_STAGE_BYTES + 256u), acc, pix, bn, a.K, a.out_f32, a.y);
+}
+
 // ---- 3-channel first layer (c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64) ------------------
 //
 // Depth 27: the kernel is bound by writing its output (c_out / 3 times the input).  A workgroup
@@ -679,15 +1140,22 @@ __global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
   const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
   const uint32_t l32 = lane & 31u, lhi = lane >> 5;
 
-  // input strips (H = Ho, W = Wo with stride 1: input and output pixels share their flattened index)
+  // input strips (H = Ho, W = Wo with stride 1: input and output pixels share their flattened index).
+  // All loads of the set-up, strips and weights, are issued before the first of them is used:
+  // one trip to memory instead of one per loop iteration.
   const int64_t total = (int64_t)a.pixels;
-  for (uint32_t idx = tid; idx < 3u * C3_STRIP_PIX; idx += 256u) {
+  constexpr uint32_t STRIP_ITERS = (3u * C3_STRIP_PIX + 255u) / 256u;
+  uint32_t sc[STRIP_ITERS][3];
+  bool sok[STRIP_ITERS];
+#pragma unroll
+  for (uint32_t it = 0; it < STRIP_ITERS; ++it) {
+    const uint32_t idx = tid + 256u * it;
     const uint32_t r = idx / C3_STRIP_PIX, e = idx - r * C3_STRIP_PIX;
     const int64_t g = (int64_t)bm - 1 + ((int64_t)r - 1) * a.W + e;
-    const bool ok = g >= 0 && g < total;
-    const int64_t gc = ok ? g : 0;
-    const uint32_t c0 = a.x[gc * 3], c1 = a.x[gc * 3 + 1], c2 = a.x[gc * 3 + 2];
-    strip[idx] = ok ? make_uint2(c0 | (c1 << 16), c2) : make_uint2(0u, 0u);
+    sok[it] = idx < 3u * C3_STRIP_PIX && g >= 0 && g < total;
+    const int64_t gc = sok[it] ? g : 0;
+#pragma unroll
+    for (uint32_t c = 0; c < 3; ++c) sc[it][c] = a.x[gc * 3 + c];
   }
 
   // weight fragments of filter row r: channel 32j + l32, operand e = (s, c) = (2*lhi + e/4, e%4)
@@ -707,6 +1175,12 @@ __global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
       }
       fw[r][j] = u32x4{wd[0], wd[1], wd[2], wd[3]};
     }
+#pragma unroll
+  for (uint32_t it = 0; it < STRIP_ITERS; ++it) {
+    const uint32_t idx = tid + 256u * it;
+    if (idx < 3u * C3_STRIP_PIX)
+      strip[idx] = sok[it] ? make_uint2(sc[it][0] | (sc[it][1] << 16), sc[it][2]) : make_uint2(0u, 0u);
+  }
   __syncthreads();
 
   f32x16 acc[2][NJ];
@@ -781,12 +1255,34 @@ __global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
   }
 }
 
-enum Path { PATH_GENERIC, PATH_DMA_128x128, PATH_DMA_256x64, PATH_DMA_64x64, PATH_DMA_KSPLIT, PATH_C3 };
+enum Path { PATH_GENERIC, PATH_DMA_128x128, PATH_DMA_256x64, PATH_DMA_64x64, PATH_DMA_KSPLIT, PATH_C3, PATH_PATCH };
 
 struct Geometry {
   uint32_t Ho, Wo, pixels, bn, tiles_n, total, blocks, threads;
   Path path;
+  uint32_t th, tw, tiles_y, tiles_x;   // PATH_PATCH: output tile, tiles per image
 };
+
+// Output tile of the patch kernel for an h x w image: th * tw <= 256 pixels whose patch of
+// (th + 2) * (tw + 2) pixels fits the kernel's LDS, such that the fewest tiles cover the image
+// (every tile costs the MFMAs of 256 pixels); among those the one with the smallest patch.
+void patch_tile(uint32_t h, uint32_t w, uint32_t* th, uint32_t* tw) {
+  uint64_t best_tiles = ~0ull;
+  uint32_t best_slots = 0u;
+  *th = *tw = 1u;
+  for (uint32_t x = 1u; x <= 256u && x <= w; ++x)
+    for (uint32_t y = 1u; y <= 256u / x && y <= h; ++y) {
+      const uint32_t slots = (x + 2u) * (y + 2u);
+      if (slots > PT_MAX_SLOTS) break;
+      const uint64_t tiles = (uint64_t)((h + y - 1u) / y) * ((w + x - 1u) / x);
+      if (tiles < best_tiles || (tiles == best_tiles && slots < best_slots)) {
+        best_tiles = tiles;
+        best_slots = slots;
+        *th = y;
+        *tw = x;
+      }
+    }
+}
 
 bool shape_ok(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_out, uint32_t stride) {
   if (batch == 0u || h == 0u || w == 0u || c_in == 0u || c_out == 0u) return false;
@@ -799,7 +1295,9 @@ bool shape_ok(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_
 }
 
 // Which kernel a layer gets, and its launch shape.
-//   c_in % 32 == 0 and c_out % 8 == 0: DMA-ring kernel; 128 x 128 tiles (256 pixels x 64 channels
+//   stride 1, c_in % 64 == 0 and c_out % 8 == 0: the patch kernel, if its tiles (patch_tile) times
+//     blocks of 64 channels make at least PT_MIN_TILES workgroups;
+//   else c_in % 32 == 0 and c_out % 8 == 0: DMA-ring kernel; 128 x 128 tiles (256 pixels x 64 channels
 //     when c_out <= 64) if that gives at least one workgroup per CU, else 64 x 64 tiles: four
 //     waves that split the depth when c_in % 64 == 0, one wave per workgroup otherwise;
 //   c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64: the first-layer kernel;
@@ -811,6 +1309,21 @@ Geometry geometry(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_
   g.Wo = (w - 1u) / stride + 1u;
   g.pixels = batch * g.Ho * g.Wo;
   g.threads = CV_THREADS;
+  g.th = g.tw = g.tiles_y = g.tiles_x = 0u;
+  if (allow_fast && stride == 1u && c_in % 64u == 0u && c_out % 8u == 0u) {
+    patch_tile(h, w, &g.th, &g.tw);
+    g.tiles_y = (h + g.th - 1u) / g.th;
+    g.tiles_x = (w + g.tw - 1u) / g.tw;
+    const uint64_t total = (uint64_t)batch * g.tiles_y * g.tiles_x * ((c_out + 63u) / 64u);
+    if (total >= PT_MIN_TILES && total <= 0x7fffffffull) {
+      g.bn = 64u;
+      g.tiles_n = (c_out + 63u) / 64u;
+      g.total = (uint32_t)total;
+      g.path = PATH_PATCH;
+      g.blocks = (g.total + 7u) / 8u * 8u;
+      return g;
+    }
+  }
   if (allow_fast && c_in % 32u == 0u && c_out % 8u == 0u) {
     const uint32_t bmp = c_out > 64u ? 128u : 256u;
     g.bn = c_out > 64u ? 128u : 64u;
@@ -892,16 +1405,23 @@ int plan_chain(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, 
 
 constexpr uint32_t MAX_LAYERS = 64;
 
+// the depth-64 kernel when c_in allows it and `deep` says so, else the depth-32 kernel: both rings take the same LDS
 template <uint32_t WM, uint32_t WN>
-hipError_t launch_dma(hipStream_t st, const Geometry& g, const ConvArgs& a) {
+hipError_t launch_dma(hipStream_t st, const Geometry& g, const ConvArgs& a, bool deep = false) {
   constexpr uint32_t lds = CD_NST * (64u * WM + 64u * WN) * 64u;
+  static_assert(lds == 2u * (64u * WM + 64u * WN) * 128u, "two stages of depth 64 = four of depth 32");
   static std::once_flag once;
   static hipError_t attr = hipSuccess;
   std::call_once(once, [] {
     attr = hipFuncSetAttribute((const void*)conv3x3_dma_kernel<WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (attr == hipSuccess)
+      attr = hipFuncSetAttribute((const void*)conv3x3_dma64_kernel<WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   });
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL((conv3x3_dma_kernel<WM, WN>), dim3(g.blocks), dim3(64u * WM * WN), lds, st, a);
+  if (deep && a.C % 64u == 0u)
+    hipLaunchKernelGGL((conv3x3_dma64_kernel<WM, WN>), dim3(g.blocks), dim3(64u * WM * WN), lds, st, a);
+  else
+    hipLaunchKernelGGL((conv3x3_dma_kernel<WM, WN>), dim3(g.blocks), dim3(64u * WM * WN), lds, st, a);
   return hipSuccess;
 }
 
@@ -921,10 +1441,18 @@ int launch_layer(hipStream_t st, const uint16_t* x, const uint16_t* w, void* y, 
   a.Ho = g.Ho; a.Wo = g.Wo; a.pixels = g.pixels; a.depth = 9u * c_in;
   a.tiles_n = g.tiles_n; a.tiles_total = g.total; a.out_f32 = out_f32;
   a.splits = splits; a.work = work;
+  a.th = g.th; a.tw = g.tw; a.tiles_y = g.tiles_y; a.tiles_x = g.tiles_x;
+  a.by_tiles_n = fast_div(g.tiles_n);
+  a.by_plane = fast_div(g.Ho * g.Wo);
+  a.by_wo = fast_div(g.Wo);
+  a.by_tiles_x = fast_div(g.tiles_x ? g.tiles_x : 1u);
+  a.by_tiles_y = fast_div(g.tiles_y ? g.tiles_y : 1u);
+  a.by_pw = fast_div(g.tw + 2u);
+  a.by_tw = fast_div(g.tw ? g.tw : 1u);
   hipError_t e = hipSuccess;
   switch (g.path) {
-    case PATH_DMA_128x128: e = launch_dma<2, 2>(st, g, a); break;
-    case PATH_DMA_256x64: e = launch_dma<4, 1>(st, g, a); break;
+    case PATH_DMA_128x128: e = launch_dma<2, 2>(st, g, a, true); break;
+    case PATH_DMA_256x64: e = launch_dma<4, 1>(st, g, a, true); break;
     case PATH_DMA_64x64: e = launch_dma<1, 1>(st, g, a); break;
     case PATH_DMA_KSPLIT: {
       static std::once_flag once;
@@ -940,6 +1468,16 @@ int launch_layer(hipStream_t st, const uint16_t* x, const uint16_t* w, void* y, 
           hipLaunchKernelGGL(conv_split_reduce_kernel, dim3((quads + 255u) / 256u), dim3(256), 0, st, work, y, splits, quads, out_f32);
         }
       }
+      break;
+    }
+    case PATH_PATCH: {
+      static std::once_flag once;
+      static hipError_t attr = hipSuccess;
+      std::call_once(once, [] {
+        attr = hipFuncSetAttribute((const void*)conv3x3_patch_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)PT_LDS);
+      });
+      e = attr;
+      if (e == hipSuccess) hipLaunchKernelGGL(conv3x3_patch_kernel, dim3(g.blocks), dim3(256), PT_LDS, st, a);
       break;
     }
     case PATH_C3:
@@ -990,6 +1528,7 @@ static uint32_t residency_of(const Geometry& g, uint32_t c_out) {
     case PATH_DMA_KSPLIT: return 2u;                  // 64 KiB ring
     case PATH_C3: return c_out <= 32u ? 7u : 4u;      // 22 / 38 KiB of strips and output staging
     case PATH_GENERIC: return 2u;                     // 162 - 244 registers per lane
+    case PATH_PATCH: return 2u;                       // 76 KiB of patch and weight ring
   }
   return 0u;
 }

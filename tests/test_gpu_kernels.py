@@ -291,7 +291,12 @@ def _conv_inputs(seed, n, h, wd, c, k, sigma=0.2):
     # 64 x 64 tiles with the depth split over four waves (c_in % 64 == 0): odd and even tile counts
     (1, 1, 1, 64, 8, 1), (2, 9, 7, 192, 72, 2), (1, 13, 13, 512, 520, 1), (2, 31, 29, 64, 136, 1),
     # DMA ring, 128 x 128 and 256 x 64 tiles (at least 256 workgroups), stride 1 and 2, ragged tails
-    (2, 130, 127, 32, 136, 1), (3, 150, 151, 32, 64, 1), (5, 141, 150, 64, 40, 2)])
+    (2, 130, 127, 32, 136, 1), (3, 150, 151, 32, 64, 1), (5, 141, 150, 64, 40, 2),
+    # the same tiles fed by operand tiles of depth 64 (c_in % 64 == 0): 128 x 128, 256 x 64 at stride 1 and 2
+    (2, 130, 127, 64, 136, 1), (3, 150, 151, 128, 64, 1), (13, 141, 150, 64, 40, 2),
+    # stride 1 with the input patch in LDS: whole small images as tiles (idle pixel slots), three channel
+    # blocks, ragged channels; 8 output channels (weight rows clamped)
+    (70, 12, 13, 192, 72, 1), (4, 100, 90, 64, 8, 1)])
 def test_conv_layer_fp32_and_bf16_outputs(n, h, wd, c, k, stride):
     x, w = _conv_inputs(n * 100 + c, n, h, wd, c, k)
     ref = oracle.conv3x3_relu(x, w, stride)

@@ -109,8 +109,13 @@ def test_bf16_gemm_variants(reports):
 def test_conv_variants(reports):
     lib = oracle.lib()
     lib.orc_conv3x3_residency.restype = C.c_uint64
-    cases = [((8, 104, 104, 128, 128, 1), _kernel(reports, "conv3x3_dma_kernel", "ILj2ELj2E"), 4, ring(256, 32, 2)),   # 128 x 128
+    cases = [((8, 104, 104, 96, 128, 1), _kernel(reports, "conv3x3_dma_kernel", "ILj2ELj2E"), 4, ring(256, 32, 2)),    # 128 x 128
              ((8, 416, 416, 32, 64, 2), _kernel(reports, "conv3x3_dma_kernel", "ILj4ELj1E"), 4, ring(320, 32, 2)),     # 256 x 64
+             # the same tiles fed by two stages of depth 64 (c_in % 64 == 0; stride 2: stride 1 takes the patch kernel)
+             ((8, 208, 208, 64, 128, 2), _kernel(reports, "conv3x3_dma64_kernel", "ILj2ELj2E"), 4, ring(256, 64, 2) // 2),
+             ((8, 416, 416, 64, 64, 2), _kernel(reports, "conv3x3_dma64_kernel", "ILj4ELj1E"), 4, ring(320, 64, 2) // 2),
+             # stride 1, c_in % 64 == 0: patch of 352 pixels x 128 bytes and four weight tiles of 8 KiB
+             ((8, 104, 104, 128, 128, 1), _kernel(reports, "conv3x3_patch_kernel"), 4, 352 * 128 + 4 * 8 * KIB),
              ((1, 104, 104, 128, 128, 1), _kernel(reports, "conv3x3_dma_ksplit_kernel"), 4, ring(128, 64, 2)),         # 64 x 64, depth 64
              ((1, 52, 52, 96, 72, 1), _kernel(reports, "conv3x3_dma_kernel", "ILj1ELj1E"), 1, ring(128, 32, 2)),       # 64 x 64, one wave
              ((1, 416, 416, 3, 32, 1), _kernel(reports, "conv3x3_c3_kernel", "ILj1E"), 4, 0),
@@ -120,7 +125,7 @@ def test_conv_variants(reports):
         w = wg_per_cu(rep, waves, ring_bytes)
         want.append(w)
         assert mgb.mgb_conv3x3_residency(*shape) == w == lib.orc_conv3x3_residency(*[U(x) for x in shape]), (shape, rep)
-    assert want == [2, 2, 2, 5, 7, 4]
+    assert want == [2, 2, 2, 2, 2, 2, 5, 7, 4]
     # the register-staged kernels (any other shape) are reported as 2 per CU: never more than they can hold
     for frag in ("ILj64ELb1E", "ILj64ELb0E", "ILj128ELb1E", "ILj128ELb0E"):
         assert wg_per_cu(_kernel(reports, "conv3x3_kernel", frag), 4) >= 2

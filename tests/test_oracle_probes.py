@@ -141,8 +141,46 @@ def test_conv_grids_cover_pixels_times_channels(shape):
     fits = [t for t, th in CONV_TILES if out[1] == round8(ceil_div(pixels, t[0]) * ceil_div(co, t[1])) and out[4] == th]
     if ci == 3 and co <= 64:                                           # first-layer kernel: 256 pixels, all channels
         fits += [(256, co)] if out[1] == round8(ceil_div(pixels, 256)) and out[4] == 256 else []
+    if st == 1 and ci % 64 == 0 and co % 8 == 0 and not fits:
+        # tiles of one image's output, at most 256 pixels each, times blocks of 64 channels: at least as
+        # many as the pixels need, no image shares a tile, and the path is only taken from 128 workgroups up
+        per_image = ceil_div(h * w, 256)
+        assert out[4] == 256 and out[1] >= max(128, b * per_image * ceil_div(co, 64)), (shape, out)
+        assert out[1] <= round8(2 * b * per_image * ceil_div(co, 64)), (shape, out)      # and not wastefully many
+        fits = [(256, 64)]
     assert fits, (shape, out)
     assert out[1] * max(t[0] * t[1] for t in fits) >= pixels * co
+
+
+# Tiles per image of the stride-1 kernel that keeps its input patch in LDS: th x tw output pixels, th * tw <= 256,
+# (th + 2) * (tw + 2) <= 352, as few as cover the image.  Worked by hand:
+#   208 x 208: 169 = 13 x 13 tiles of 16 x 16 (patch 18 x 18 = 324); 43264 / 256 = 169 is the least possible.
+#   104 x 104: at least 43 (10816 / 256 = 42.25).  43 is prime and 44 = 4 x 11 = 2 x 22 would need a tile 26 high
+#     (104 / 4) and 10 wide (104 / 11 rounded up) = 260 pixels, or 52 high: neither fits.  45 = 5 x 9: tiles of 21 x 12
+#     (252 pixels, patch 23 x 14 = 322).
+#   52 x 52: at least 11 (2704 / 256 = 10.6); 11 is prime: one row of 11 tiles would be 52 high and then at most 4 wide.
+#     12 = 2 x 6: tiles of 26 x 9 (234 pixels, patch 28 x 11 = 308).
+#   26 x 26: at least 3; 3 x 1: tiles of 9 x 26 (234 pixels, patch 11 x 28 = 308).
+#   12 x 13: the whole image (156 pixels, patch 14 x 15 = 210).
+#   100 x 90: at least 36 (9000 / 256 = 35.2); 6 x 6 tiles of 17 x 15 (255 pixels, patch 19 x 17 = 323).
+@pytest.mark.parametrize("h,w,tiles", [(208, 208, 169), (104, 104, 45), (52, 52, 12), (26, 26, 3), (12, 13, 1), (100, 90, 36)])
+def test_patch_kernel_tiles_per_image_worked_by_hand(h, w, tiles):
+    batch = ceil_div(128, tiles)                                       # enough images for the path to be taken
+    out = _probe("orc_conv3x3_probe", batch, h, w, 64, 64, 1)
+    assert out[1:] == [round8(batch * tiles), 1, 1, 256, 1, 1]
+    out = _probe("orc_conv3x3_probe", batch, h, w, 128, 136, 1)        # three blocks of 64 channels
+    assert out[1] == round8(batch * tiles * 3)
+    # one workgroup short of 128: the layer takes the other kernels (tiles of flattened pixels)
+    if batch * tiles - tiles < 128 and batch > 1:
+        out = _probe("orc_conv3x3_probe", batch - 1, h, w, 64, 64, 1)
+        pixels = (batch - 1) * h * w
+        assert out[1] in (round8(ceil_div(pixels, 256)), round8(ceil_div(pixels, 64)))
+
+
+def test_patch_kernel_residency_from_its_lds():
+    # 352 patch pixels x 64 channels x 2 bytes + four weight tiles of 64 x 64 x 2 bytes = 77824 bytes: two per CU
+    assert (160 * 1024) // (352 * 128 + 4 * 8192) == 2
+    assert _lib().orc_conv3x3_residency(*[U(x) for x in (8, 104, 104, 128, 128, 1)]) == 2
 
 
 def test_net_geometry_is_its_largest_launch():
