@@ -113,19 +113,25 @@ void orc_gemm_bf16_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
 //     64 channels, if that gives at least 128 workgroups.  A tile is th x tw output pixels with
 //     th * tw <= 256 whose input patch of (th + 2) x (tw + 2) pixels is at most 352 pixels (44 KiB
 //     of LDS at 64 channels); the image is cut into the fewest such tiles;
+//   stride 2, c_in == 32, c_out % 8 == 0 and c_out <= 64: 256 threads per tile of one image's output
+//     (all channels), if that gives at least 256 workgroups.  A tile is th x tw output pixels with
+//     th * tw <= 128 whose input patch of (2 th + 1) x (2 tw + 1) pixels is at most 576 pixels (36 KiB
+//     of LDS at 32 channels); the image is cut into the fewest such tiles;
 //   else c_in % 32 == 0 and c_out % 8 == 0: 256 threads per 128 pixels x 128 channels (256 x 64 when
 //     c_out <= 64); if that gives fewer than 256 workgroups, 64 x 64 tiles instead, with 256
 //     threads (the depth split four ways) when c_in % 64 == 0, else 64 threads;
 //   c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64: 256 threads per 256 pixels (all channels);
 //   otherwise 256 threads per 128 pixels x 64 channels (128 channels when c_out > 64).
-static uint64_t patch_tiles_per_image(uint64_t h, uint64_t w) {
+static uint64_t patch_tiles_per_image(uint64_t h, uint64_t w, uint64_t stride) {
+  const uint64_t max_px = stride == 1 ? 256 : 128, max_patch = stride == 1 ? 352 : 576;
   uint64_t best = ~0ull;
   for (uint64_t ny = 1; ny <= h; ++ny) {                 // ny rows of tiles, each ceil(h / ny) pixels high
     const uint64_t th = ceil_div(h, ny);
-    if (th > 256) continue;
+    if (th > max_px) continue;
     for (uint64_t nx = 1; nx <= w && ny * nx < best; ++nx) {
       const uint64_t tw = ceil_div(w, nx);
-      if (th * tw <= 256 && (th + 2) * (tw + 2) <= 352) { best = ny * nx; break; }
+      const uint64_t patch = stride == 1 ? (th + 2) * (tw + 2) : (2 * th + 1) * (2 * tw + 1);
+      if (th * tw <= max_px && patch <= max_patch) { best = ny * nx; break; }
     }
   }
   return best;
@@ -134,8 +140,15 @@ static uint64_t patch_tiles_per_image(uint64_t h, uint64_t w) {
 static bool conv_patch_path(uint64_t batch, uint64_t ho, uint64_t wo, uint64_t c_in, uint64_t c_out, uint64_t stride,
                             uint64_t* wgs) {
   if (stride != 1 || c_in % 64 != 0 || c_out % 8 != 0) return false;
-  *wgs = batch * patch_tiles_per_image(ho, wo) * ceil_div(c_out, 64);
+  *wgs = batch * patch_tiles_per_image(ho, wo, 1) * ceil_div(c_out, 64);
   return *wgs >= 128;
+}
+
+static bool conv_stride2_32_path(uint64_t batch, uint64_t ho, uint64_t wo, uint64_t c_in, uint64_t c_out, uint64_t stride,
+                                 uint64_t* wgs) {
+  if (stride != 2 || c_in != 32 || c_out % 8 != 0 || c_out > 64) return false;
+  *wgs = batch * patch_tiles_per_image(ho, wo, 2);
+  return *wgs >= 256;
 }
 
 static uint64_t conv_workgroups(uint64_t batch, uint64_t ho, uint64_t wo, uint64_t c_in, uint64_t c_out, uint64_t stride,
@@ -145,6 +158,7 @@ static uint64_t conv_workgroups(uint64_t batch, uint64_t ho, uint64_t wo, uint64
   *threads = 256;
   *depth_split = false;
   if (conv_patch_path(batch, ho, wo, c_in, c_out, stride, &wgs)) return wgs;
+  if (conv_stride2_32_path(batch, ho, wo, c_in, c_out, stride, &wgs)) return wgs;
   if (c_in % 32 == 0 && c_out % 8 == 0) {
     wgs = c_out > 64 ? ceil_div(pixels, 128) * ceil_div(c_out, 128) : ceil_div(pixels, 256) * ceil_div(c_out, 64);
     if (wgs < 256) {
@@ -246,6 +260,8 @@ uint64_t orc_conv3x3_residency(uint64_t batch, uint64_t h, uint64_t w, uint64_t 
   uint64_t patch_wgs;
   if (conv_patch_path(batch, ho, wo, c_in, c_out, stride, &patch_wgs))
     return (160 * 1024) / (352 * 64 * 2 + 4 * 64 * 64 * 2);      // the patch and four weight tiles of 64 x 64
+  if (conv_stride2_32_path(batch, ho, wo, c_in, c_out, stride, &patch_wgs))
+    return (160 * 1024) / (576 * 32 * 2 + 64 * 9 * 32 * 2 + 576 * 4);   // the patch, the filter of 64 channels, a table of 576 words
   if (c_in % 32 == 0 && c_out % 8 == 0) {
     uint64_t tp = c_out > 64 ? 128 : 256, tc = c_out > 64 ? 128 : 64;
     uint64_t bk = 32;

@@ -72,9 +72,9 @@ struct ConvArgs {
   uint32_t tiles_n, tiles_total, out_f32;
   uint32_t splits;             // depth-split kernel only: workgroups that share one output tile
   float* work;                 // splits > 1: fp32 partial sums [split][pixel][channel]
-  uint32_t th, tw, tiles_y, tiles_x;   // patch kernel only: output tile of th x tw pixels, tiles per image
+  uint32_t th, tw, tiles_y, tiles_x;   // patch kernels only: output tile of th x tw pixels, tiles per image
   FastDiv by_tiles_n, by_plane, by_wo; // divisors tiles_n, Ho * Wo, Wo
-  FastDiv by_tiles_x, by_tiles_y, by_pw, by_tw;   // patch kernel only: tiles_x, tiles_y, tw + 2, tw
+  FastDiv by_tiles_x, by_tiles_y, by_pw, by_tw;   // patch kernels only: tiles_x, tiles_y, patch width, tw
 };
 
 // 16 bytes of zeros in device memory: the source of every padded / out-of-range operand chunk
@@ -288,21 +288,21 @@ __global__ __launch_bounds__(CV_THREADS, 2) void conv3x3_kernel(ConvArgs a) {
 // out in LDS as [pixel][channel] (16-byte chunks XOR-swizzled by the pixel) and then writes 16
 // bytes per lane, the lanes of a pixel's row side by side: whole 128-byte lines (bf16; fp32: 256
 // bytes per pixel).  `stage` is this wave's own 16 KiB of LDS (OUT_STAGE_BYTES; with TABLE 256
-// bytes more), free of other use.  Where the wave's pixels go: with TABLE, pix[i] is the output
+// bytes more), free of other use (NI = 1: a wave of 32 pixels x 64 channels, half of all that).  Where the wave's pixels go: with TABLE, pix[i] is the output
 // pixel of lane block i (l32 = lane % 32), negative if there is none, and the lanes exchange them
 // through a table behind the tile; without, pixel r of the tile is output pixel pix[0] + r as long
 // as that is below pix[1].  ch0 is the first of the 64 channels (channels >= c_out are dropped;
 // c_out % 8 == 0).
 constexpr uint32_t OUT_STAGE_BYTES = 64u * 256u;
 
-template <bool TABLE>
-__device__ __forceinline__ void store_tile_via_lds(uint8_t* stage, const f32x16 (&acc)[2][2], const int32_t (&pix)[2],
+template <bool TABLE, uint32_t NI = 2u>
+__device__ __forceinline__ void store_tile_via_lds(uint8_t* stage, const f32x16 (&acc)[NI][2], const int32_t (&pix)[2],
                                                    uint32_t ch0, uint32_t K, uint32_t out_f32, void* y) {
   const uint32_t lane = threadIdx.x & 63u, l32 = lane & 31u, lhi = lane >> 5;
-  int32_t* index = reinterpret_cast<int32_t*>(stage + OUT_STAGE_BYTES);
+  int32_t* index = reinterpret_cast<int32_t*>(stage + NI * 32u * 256u);
   if (TABLE && lhi == 0u) {
     index[l32] = pix[0];
-    index[32u + l32] = pix[1];
+    if (NI == 2u) index[32u + l32] = pix[1];
   }
   auto pixel_of = [&](uint32_t px) -> int32_t {
     if (TABLE) return index[px];
@@ -312,7 +312,7 @@ __device__ __forceinline__ void store_tile_via_lds(uint8_t* stage, const f32x16 
   if (!out_f32) {
     // bf16: rows of 128 bytes, chunk = 8 channels; a lane owns half a chunk per quad
 #pragma unroll
-    for (uint32_t i = 0; i < 2; ++i) {
+    for (uint32_t i = 0; i < NI; ++i) {
       const uint32_t px = 32u * i + l32;
 #pragma unroll
       for (uint32_t j = 0; j < 2; ++j)
@@ -329,7 +329,7 @@ __device__ __forceinline__ void store_tile_via_lds(uint8_t* stage, const f32x16 
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     uint16_t* out = reinterpret_cast<uint16_t*>(y);
 #pragma unroll
-    for (uint32_t it = 0; it < 8u; ++it) {
+    for (uint32_t it = 0; it < 4u * NI; ++it) {
       const uint32_t px = 8u * it + (lane >> 3), c = lane & 7u;
       const u32x4 v = *reinterpret_cast<const u32x4*>(stage + px * 128u + ((c ^ ((px ^ (px >> 3)) & 7u)) << 4));
       const int32_t p = pixel_of(px);
@@ -339,7 +339,7 @@ __device__ __forceinline__ void store_tile_via_lds(uint8_t* stage, const f32x16 
   } else {
     // fp32: rows of 256 bytes, chunk = 4 channels = one quad of a lane
 #pragma unroll
-    for (uint32_t i = 0; i < 2; ++i) {
+    for (uint32_t i = 0; i < NI; ++i) {
       const uint32_t px = 32u * i + l32;
 #pragma unroll
       for (uint32_t j = 0; j < 2; ++j)
@@ -355,7 +355,7 @@ __device__ __forceinline__ void store_tile_via_lds(uint8_t* stage, const f32x16 
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     float* out = reinterpret_cast<float*>(y);
 #pragma unroll
-    for (uint32_t it = 0; it < 16u; ++it) {
+    for (uint32_t it = 0; it < 8u * NI; ++it) {
       const uint32_t px = 4u * it + (lane >> 4), c = lane & 15u;
       const float4 v = *reinterpret_cast<const float4*>(stage + px * 256u + ((c ^ (px & 15u)) << 4));
       const int32_t p = pixel_of(px);
@@ -971,29 +971,49 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(ConvArgs a) {
   const uint16_t* zeros = reinterpret_cast<const uint16_t*>(g_zero16);
   const uint32_t ncb = a.C / 64u, nk = 9u * ncb;
 
+  // Where the patch pixels come from: entry s of a table in LDS (in the weight stage that is filled
+  // last) is the input pixel under patch pixel s, counted from the one under patch pixel (0, 0), or
+  // all ones if s lies outside the image (the padding ring) or past the patch.  Each thread works
+  // out at most two entries; the DMA roles below then cost a table read instead of a division and
+  // four comparisons each.
+  uint32_t* pixel_of_slot = reinterpret_cast<uint32_t*>(smem + PT_PATCH + (PT_WST - 1u) * PT_WTILE);
+#pragma unroll
+  for (uint32_t e = 0; e < (PT_MAX_SLOTS + 255u) / 256u; ++e) {
+    const uint32_t slot = tid + 256u * e;
+    const uint32_t py = slot / a.by_pw, px = slot - py * pw;
+    const uint32_t ok = (uint32_t)(slot < slots) & (uint32_t)(oh0 + py - 1u < a.H) & (uint32_t)(ow0 + px - 1u < a.W);   // (- 1 wraps to a huge value above / left of the image)
+    if (slot < PT_MAX_SLOTS) pixel_of_slot[slot] = ok ? py * a.W + px : 0xffffffffu;
+  }
+  __syncthreads();
   // Patch DMA roles: instruction h of wave w fills the 1 KiB block 4h + w = patch pixels
-  // 8 * (4h + w) .. + 7; lane -> pixel + lane / 8, LDS chunk lane % 8, source chunk swizzled.
-  // A pixel outside the image (the padding ring) or past the patch reads the block of zeros,
-  // and its source does not advance from one channel block to the next.  The first channel
-  // block is requested here, each instruction as soon as its address is known.
+  // 8 * (4h + w) .. + 7; lane -> pixel + lane / 8, LDS chunk lane % 8, source chunk swizzled
+  // (the pixel's low three bits are lane / 8 whatever h and w).  A pixel without a source reads
+  // the block of zeros, and its source does not advance from one channel block to the next.
+  // The first channel block is requested here, each instruction as soon as its address is known.
   // (origin: the input pixel under patch pixel (0, 0); it lies outside the tensor for tiles at the
   // top or left edge, and is only ever used with offsets that lead back inside)
-  const uint16_t* origin = a.x + (((int64_t)img * a.H + oh0) * a.W + ow0 - (int64_t)a.W - 1) * a.C;
+  const uint16_t* origin = a.x + (((int64_t)img * a.H + oh0) * a.W + ow0 - (int64_t)a.W - 1) * a.C +
+                           8u * ((lane & 7u) ^ ((lane >> 3) & 7u));
   const uint16_t* a_ptr[PT_NPB];
   uint32_t a_real = 0u;                      // bit h: instruction h of this lane reads the tensor
+  uint32_t a_pixel[PT_NPB];                  // (all table reads first: a DMA request orders later LDS reads behind it)
+#pragma unroll
+  for (uint32_t h = 0; h < PT_NPB; ++h) a_pixel[h] = pixel_of_slot[8u * (4u * h + wave) + (lane >> 3)];
 #pragma unroll
   for (uint32_t h = 0; h < PT_NPB; ++h) {
-    const uint32_t slot = 8u * (4u * h + wave) + (lane >> 3);
-    const uint32_t py = slot / a.by_pw, px = slot - py * pw;
-    const bool ok = slot < slots && oh0 + py - 1u < a.H && ow0 + px - 1u < a.W;   // (- 1 wraps to a huge value above / left of the image)
-    const uint16_t* src = origin + (uint64_t)(py * a.W + px) * a.C + 8u * ((lane & 7u) ^ (slot & 7u));
-    a_ptr[h] = ok ? src : zeros;
-    a_real |= (ok ? 1u : 0u) << h;
     if (h < nph) {
+      const uint32_t pixel = a_pixel[h];
+      const bool ok = pixel != 0xffffffffu;
+      a_ptr[h] = ok ? origin + (uint64_t)pixel * a.C : zeros;
+      a_real |= (ok ? 1u : 0u) << h;
       dma16(a_ptr[h], lds_base + (4u * h + wave) * 1024u);
       a_ptr[h] = reinterpret_cast<const uint16_t*>(reinterpret_cast<uintptr_t>(a_ptr[h]) + ((ok ? 1u : 0u) << 7));
+    } else {
+      a_ptr[h] = zeros;
     }
   }
+  // (the table's stage takes weights only after the loop's first barrier, which every wave
+  // reaches after it has used what it read here)
   // weights: instruction h of wave w fills rows 8 * (2w + h) .. + 7 of a stage
   const uint16_t* b_src[2];
 #pragma unroll
@@ -1117,6 +1137,121 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(ConvArgs a) {
   store_tile_via_lds<true>(smem + wave * (OUT_STAGE_BYTES + 256u), acc, pix, bn, a.K, a.out_f32, a.y);
 }
 
+// ---- stride-2 layer with 32 input channels (c_out % 8 == 0, c_out <= 64) -------------------------
+//
+// The second layer of the net: few channels, many pixels, nine depth tiles of 32 only.  As an
+// implicit GEMM it spends its time in set-up, in 2.25 fetches of every activation and in
+// half-used cache lines (a pixel's 32 channels are 64 bytes).  Here a workgroup owns th x tw output
+// pixels of one image (th * tw <= 128) and all output channels, and holds in LDS
+//   * the whole filter, c_out rows of 9 * 32 values (576 bytes), the low two bits of a row's
+//     16-byte chunk index XORed with bits 2..3 of the row: the rows of 16 consecutive channels
+//     then hit 16 different 16-byte slots of a 256-byte bank sweep;
+//   * the (2 th + 1) x (2 tw + 1) input pixels its tile reads (64 bytes each, zeros outside the
+//     image), every patch row stored as its even columns followed by its odd columns, so that the
+//     pixels the 32 lanes of a fragment read for one tap are neighbours in LDS although they are
+//     two apart in the image: output pixel (ty, tx), tap (r, s) reads row 2 ty + r, even column
+//     tx (s = 0) or tx + 1 (s = 2), or odd column tx (s = 1).
+// Nothing streams: one barrier after the copies, then 9 taps x 2 slices of 16 with no further
+// synchronisation.  Four waves, each 32 pixels x 64 channels.  16-byte chunks of a pixel are
+// XOR-swizzled by bits 2..3 of the pixel's LDS index.
+constexpr uint32_t S2_NPB = 9u;                           // patch DMA instructions per wave, 16 pixels each
+constexpr uint32_t S2_MAX_SLOTS = 4u * S2_NPB * 16u;      // 576 patch pixels
+constexpr uint32_t S2_PATCH = S2_MAX_SLOTS * 64u;         // 36 KiB
+constexpr uint32_t S2_WPITCH = 576u, S2_WBYTES = 64u * S2_WPITCH;
+constexpr uint32_t S2_LDS = S2_PATCH + S2_WBYTES + S2_MAX_SLOTS * 4u;   // 76032 bytes: two workgroups per CU
+constexpr uint32_t S2_MIN_TILES = 256u;
+
+__global__ __launch_bounds__(256, 2) void conv3x3_s2c32_kernel(ConvArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+  const uint32_t per_xcd = (a.tiles_total + 7u) / 8u;
+  const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || tile >= a.tiles_total) return;
+  const uint32_t up = tile / a.by_tiles_x;
+  const uint32_t tile_x = tile - up * a.tiles_x;
+  const uint32_t img = up / a.by_tiles_y, tile_y = up - img * a.tiles_y;
+  const uint32_t oh0 = tile_y * a.th, ow0 = tile_x * a.tw;
+  const uint32_t pw = 2u * a.tw + 1u, slots = (2u * a.th + 1u) * pw;
+  const uint32_t nph = ((slots + 15u) / 16u + 3u) / 4u;   // patch DMA instructions per wave that carry pixels
+
+  const uint32_t lds_base = lds_address_of(smem);
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t l32 = lane & 31u, lhi = lane >> 5;
+  const uint16_t* zeros = reinterpret_cast<const uint16_t*>(g_zero16);
+  uint8_t* wl = smem + S2_PATCH;
+
+  // entry s of the table: the input pixel stored at LDS index s, counted from the one under patch
+  // pixel (0, 0), or all ones if it lies outside the image or s is past the patch
+  uint32_t* pixel_of_slot = reinterpret_cast<uint32_t*>(smem + S2_PATCH + S2_WBYTES);
+#pragma unroll
+  for (uint32_t e = 0; e < (S2_MAX_SLOTS + 255u) / 256u; ++e) {
+    const uint32_t slot = tid + 256u * e;
+    const uint32_t py = slot / a.by_pw, rem = slot - py * pw;
+    const uint32_t px = rem <= a.tw ? 2u * rem : 2u * (rem - a.tw) - 1u;        // even columns first, then the odd ones
+    const uint32_t ok = (uint32_t)(slot < slots) & (uint32_t)(2u * oh0 + py - 1u < a.H) & (uint32_t)(2u * ow0 + px - 1u < a.W);
+    if (slot < S2_MAX_SLOTS) pixel_of_slot[slot] = ok ? py * a.W + px : 0xffffffffu;
+  }
+  __syncthreads();
+  // patch: instruction h of wave w fills the 1 KiB block 4h + w = LDS pixels 16 * (4h + w) .. + 15;
+  // lane -> pixel + lane / 4, LDS chunk lane % 4, source chunk swizzled (bits 2..3 of the pixel
+  // index are bits 4..5 of the lane whatever h and w)
+  const uint16_t* origin = a.x + (((int64_t)img * a.H + 2 * (int64_t)oh0) * a.W + 2 * (int64_t)ow0 - (int64_t)a.W - 1) * 32 +
+                           8u * ((lane & 3u) ^ ((lane >> 4) & 3u));
+  uint32_t a_pixel[S2_NPB];                  // (all table reads first: a DMA request orders later LDS reads behind it)
+#pragma unroll
+  for (uint32_t h = 0; h < S2_NPB; ++h) a_pixel[h] = pixel_of_slot[16u * (4u * h + wave) + (lane >> 2)];
+#pragma unroll
+  for (uint32_t h = 0; h < S2_NPB; ++h)
+    if (h < nph) dma16(a_pixel[h] != 0xffffffffu ? origin + (uint64_t)a_pixel[h] * 32u : zeros, lds_base + (4u * h + wave) * 1024u);
+  // filter: 36 chunks of 16 bytes per channel, 2304 in all = 36 DMA instructions, 9 per wave.
+  // Chunk c of channel row sits at LDS chunk 36 * row + (c with its low two bits ^ bits 2..3 of
+  // the row); channels past c_out repeat the last one (they feed outputs that are never stored).
+#pragma unroll
+  for (uint32_t e = 0; e < 9u; ++e) {
+    const uint32_t at = 64u * (4u * e + wave) + lane, row = at / 36u, pos = at - 36u * row;
+    const uint32_t c = pos ^ ((row >> 2) & 3u);
+    dma16(a.w + (size_t)min(row, a.K - 1u) * 288u + 8u * c, lds_base + S2_PATCH + (4u * e + wave) * 1024u);
+  }
+
+  f32x16 acc[1][2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[0][j][r] = 0.f;
+  // this lane's pixel: LDS index of its tap (0, 0), and where the result goes
+  const uint32_t q = 32u * wave + l32;
+  const uint32_t ty = q / a.by_tw, tx = q - ty * a.tw;
+  const bool mine = q < a.th * a.tw;
+  const uint32_t slot0 = mine ? 2u * ty * pw + tx : 0u;
+  const int32_t pix[2] = {mine && oh0 + ty < a.Ho && ow0 + tx < a.Wo ? (int32_t)((img * a.Ho + oh0 + ty) * a.Wo + ow0 + tx) : -1, -1};
+  // weight fragments: row 32 j + l32 (bits 2..3 the same for both j), depth chunk 4 * tap + 2 * slice + lhi
+  const uint32_t w_at = l32 * S2_WPITCH, w_swz = (l32 >> 2) & 3u;
+
+  __builtin_amdgcn_s_waitcnt(vm_wait(0));
+  __syncthreads();
+  // slice n = 2 * tap + half: the fragments of slice n + 1 are read before the MFMAs of slice n
+  u32x4 fp[2], fw[2][2];
+  auto frag_load = [&](uint32_t n, uint32_t set) {
+    const uint32_t tap = n >> 1, sl = n & 1u;
+    const uint32_t r = tap / 3u, t = tap - 3u * r;
+    const uint32_t slot = slot0 + r * pw + (t == 1u ? a.tw + 1u : t >> 1);
+    fp[set] = *reinterpret_cast<const u32x4*>(smem + slot * 64u + (((2u * sl + lhi) ^ ((slot >> 2) & 3u)) << 4));
+    const uint32_t at = w_at + 64u * tap + (((2u * sl + lhi) ^ w_swz) << 4);
+    fw[set][0] = *reinterpret_cast<const u32x4*>(wl + at);
+    fw[set][1] = *reinterpret_cast<const u32x4*>(wl + at + 32u * S2_WPITCH);
+  };
+  frag_load(0u, 0u);
+#pragma unroll
+  for (uint32_t n = 0; n < 18u; ++n) {
+    if (n + 1u < 18u) frag_load(n + 1u, (n + 1u) & 1u);
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fw[n & 1u][0]), as_bf16x8(fp[n & 1u]), acc[0][0], 0, 0, 0);
+    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fw[n & 1u][1]), as_bf16x8(fp[n & 1u]), acc[0][1], 0, 0, 0);
+  }
+  // every wave is done with the patch: each takes a part of it to stage its results
+  __syncthreads();
+  store_tile_via_lds<true, 1u>(smem + wave * (OUT_STAGE_BYTES / 2u + 128u), acc, pix, 0u, a.K, a.out_f32, a.y);
+}
+
 // ---- 3-channel first layer (c_in == 3, stride 1, c_out % 8 == 0, c_out <= 64) ------------------
 //
 // Depth 27: the kernel is bound by writing its output (c_out / 3 times the input).  A workgroup
@@ -1158,6 +1293,30 @@ __global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
     for (uint32_t c = 0; c < 3; ++c) sc[it][c] = a.x[gc * 3 + c];
   }
 
+  // The filter (27 values per channel) goes through LDS, in the space the results are staged in
+  // later: 27 * c_out loads per workgroup instead of 24 per lane and block of 32 channels.  The
+  // CU's address unit handles a load instruction in the same time whatever its width, and with
+  // the per-lane gather the kernel was bound by it.
+  constexpr uint32_t W_ITERS = (32u * NJ * 27u + 255u) / 256u;
+  uint32_t wv[W_ITERS];
+#pragma unroll
+  for (uint32_t it = 0; it < W_ITERS; ++it) {
+    const uint32_t idx = tid + 256u * it;
+    wv[it] = a.w[idx < a.K * 27u ? idx : 0u];
+  }
+#pragma unroll
+  for (uint32_t it = 0; it < STRIP_ITERS; ++it) {
+    const uint32_t idx = tid + 256u * it;
+    if (idx < 3u * C3_STRIP_PIX)
+      strip[idx] = sok[it] ? make_uint2(sc[it][0] | (sc[it][1] << 16), sc[it][2]) : make_uint2(0u, 0u);
+  }
+#pragma unroll
+  for (uint32_t it = 0; it < W_ITERS; ++it) {
+    const uint32_t idx = tid + 256u * it;
+    if (idx < 32u * NJ * 27u) outs[idx] = (uint16_t)(idx < a.K * 27u ? wv[it] : 0u);
+  }
+  __syncthreads();
+
   // weight fragments of filter row r: channel 32j + l32, operand e = (s, c) = (2*lhi + e/4, e%4)
   u32x4 fw[3][NJ];
 #pragma unroll
@@ -1169,27 +1328,20 @@ __global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
 #pragma unroll
       for (uint32_t e = 0; e < 8; ++e) {
         const uint32_t t = 2u * lhi + (e >> 2), c = e & 3u;
-        const uint32_t ok = (uint32_t)(t < 3u) & (uint32_t)(c < 3u) & (uint32_t)(ch < a.K);
-        const uint32_t v = a.w[ok ? ch * 27u + r * 9u + t * 3u + c : 0u];
+        const uint32_t ok = (uint32_t)(t < 3u) & (uint32_t)(c < 3u);      // (channels >= c_out hold zeros)
+        const uint32_t v = outs[ok ? ch * 27u + r * 9u + t * 3u + c : 0u];
         wd[e >> 1] |= (ok ? v : 0u) << (16u * (e & 1u));
       }
       fw[r][j] = u32x4{wd[0], wd[1], wd[2], wd[3]};
     }
-#pragma unroll
-  for (uint32_t it = 0; it < STRIP_ITERS; ++it) {
-    const uint32_t idx = tid + 256u * it;
-    if (idx < 3u * C3_STRIP_PIX)
-      strip[idx] = sok[it] ? make_uint2(sc[it][0] | (sc[it][1] << 16), sc[it][2]) : make_uint2(0u, 0u);
-  }
-  __syncthreads();
 
   f32x16 acc[2][NJ];
 #pragma unroll
   for (uint32_t i = 0; i < 2; ++i) {
     const uint32_t pl = 64u * wave + 32u * i + l32;            // pixel inside the workgroup's 256
     const uint32_t p = bm + pl;
-    const uint32_t rem = p % (a.H * a.W);
-    const uint32_t oh = rem / a.W, ow = rem - oh * a.W;
+    const uint32_t rem = p - (p / a.by_plane) * (a.H * a.W);     // (stride 1: Ho = H, Wo = W)
+    const uint32_t oh = rem / a.by_wo, ow = rem - oh * a.W;
     uint32_t taps = 0u;
 #pragma unroll
     for (int32_t r = 0; r < 3; ++r)
@@ -1216,6 +1368,7 @@ __global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
     }
   }
 
+  __syncthreads();            // every wave has read the filter out of `outs`
   // ReLU + rounding; transpose through LDS: outs[pixel][channel], c_out values per pixel
   const uint32_t Kc = a.K;
   if (!a.out_f32) {
@@ -1255,7 +1408,7 @@ __global__ __launch_bounds__(256) void conv3x3_c3_kernel(ConvArgs a) {
   }
 }
 
-enum Path { PATH_GENERIC, PATH_DMA_128x128, PATH_DMA_256x64, PATH_DMA_64x64, PATH_DMA_KSPLIT, PATH_C3, PATH_PATCH };
+enum Path { PATH_GENERIC, PATH_DMA_128x128, PATH_DMA_256x64, PATH_DMA_64x64, PATH_DMA_KSPLIT, PATH_C3, PATH_PATCH, PATH_S2C32 };
 
 struct Geometry {
   uint32_t Ho, Wo, pixels, bn, tiles_n, total, blocks, threads;
@@ -1263,17 +1416,18 @@ struct Geometry {
   uint32_t th, tw, tiles_y, tiles_x;   // PATH_PATCH: output tile, tiles per image
 };
 
-// Output tile of the patch kernel for an h x w image: th * tw <= 256 pixels whose patch of
-// (th + 2) * (tw + 2) pixels fits the kernel's LDS, such that the fewest tiles cover the image
-// (every tile costs the MFMAs of 256 pixels); among those the one with the smallest patch.
-void patch_tile(uint32_t h, uint32_t w, uint32_t* th, uint32_t* tw) {
+// Output tile of a patch kernel for an image of h x w output pixels: th * tw <= max_px pixels
+// whose input patch ((th + 2) * (tw + 2) pixels at stride 1, (2 th + 1) * (2 tw + 1) at stride 2)
+// fits max_slots, such that the fewest tiles cover the image (every tile costs the MFMAs of
+// max_px pixels); among those the one with the smallest patch.
+void patch_tile(uint32_t h, uint32_t w, uint32_t stride, uint32_t max_px, uint32_t max_slots, uint32_t* th, uint32_t* tw) {
   uint64_t best_tiles = ~0ull;
   uint32_t best_slots = 0u;
   *th = *tw = 1u;
-  for (uint32_t x = 1u; x <= 256u && x <= w; ++x)
-    for (uint32_t y = 1u; y <= 256u / x && y <= h; ++y) {
-      const uint32_t slots = (x + 2u) * (y + 2u);
-      if (slots > PT_MAX_SLOTS) break;
+  for (uint32_t x = 1u; x <= max_px && x <= w; ++x)
+    for (uint32_t y = 1u; y <= max_px / x && y <= h; ++y) {
+      const uint32_t slots = stride == 1u ? (x + 2u) * (y + 2u) : (2u * x + 1u) * (2u * y + 1u);
+      if (slots > max_slots) break;
       const uint64_t tiles = (uint64_t)((h + y - 1u) / y) * ((w + x - 1u) / x);
       if (tiles < best_tiles || (tiles == best_tiles && slots < best_slots)) {
         best_tiles = tiles;
@@ -1297,6 +1451,8 @@ bool shape_ok(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_
 // Which kernel a layer gets, and its launch shape.
 //   stride 1, c_in % 64 == 0 and c_out % 8 == 0: the patch kernel, if its tiles (patch_tile) times
 //     blocks of 64 channels make at least PT_MIN_TILES workgroups;
+//   stride 2, c_in == 32, c_out % 8 == 0 and c_out <= 64: the kernel with the filter and the
+//     tile's patch in LDS, if its tiles (at most 128 pixels) make at least S2_MIN_TILES workgroups;
 //   else c_in % 32 == 0 and c_out % 8 == 0: DMA-ring kernel; 128 x 128 tiles (256 pixels x 64 channels
 //     when c_out <= 64) if that gives at least one workgroup per CU, else 64 x 64 tiles: four
 //     waves that split the depth when c_in % 64 == 0, one wave per workgroup otherwise;
@@ -1311,7 +1467,7 @@ Geometry geometry(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_
   g.threads = CV_THREADS;
   g.th = g.tw = g.tiles_y = g.tiles_x = 0u;
   if (allow_fast && stride == 1u && c_in % 64u == 0u && c_out % 8u == 0u) {
-    patch_tile(h, w, &g.th, &g.tw);
+    patch_tile(h, w, 1u, 256u, PT_MAX_SLOTS, &g.th, &g.tw);
     g.tiles_y = (h + g.th - 1u) / g.th;
     g.tiles_x = (w + g.tw - 1u) / g.tw;
     const uint64_t total = (uint64_t)batch * g.tiles_y * g.tiles_x * ((c_out + 63u) / 64u);
@@ -1320,6 +1476,20 @@ Geometry geometry(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_
       g.tiles_n = (c_out + 63u) / 64u;
       g.total = (uint32_t)total;
       g.path = PATH_PATCH;
+      g.blocks = (g.total + 7u) / 8u * 8u;
+      return g;
+    }
+  }
+  if (allow_fast && stride == 2u && c_in == 32u && c_out % 8u == 0u && c_out <= 64u) {
+    patch_tile(g.Ho, g.Wo, 2u, 128u, S2_MAX_SLOTS, &g.th, &g.tw);
+    g.tiles_y = (g.Ho + g.th - 1u) / g.th;
+    g.tiles_x = (g.Wo + g.tw - 1u) / g.tw;
+    const uint64_t total = (uint64_t)batch * g.tiles_y * g.tiles_x;
+    if (total >= S2_MIN_TILES && total <= 0x7fffffffull) {
+      g.bn = 64u;
+      g.tiles_n = 1u;
+      g.total = (uint32_t)total;
+      g.path = PATH_S2C32;
       g.blocks = (g.total + 7u) / 8u * 8u;
       return g;
     }
@@ -1447,7 +1617,7 @@ int launch_layer(hipStream_t st, const uint16_t* x, const uint16_t* w, void* y, 
   a.by_wo = fast_div(g.Wo);
   a.by_tiles_x = fast_div(g.tiles_x ? g.tiles_x : 1u);
   a.by_tiles_y = fast_div(g.tiles_y ? g.tiles_y : 1u);
-  a.by_pw = fast_div(g.tw + 2u);
+  a.by_pw = fast_div(g.path == PATH_S2C32 ? 2u * g.tw + 1u : g.tw + 2u);
   a.by_tw = fast_div(g.tw ? g.tw : 1u);
   hipError_t e = hipSuccess;
   switch (g.path) {
@@ -1478,6 +1648,16 @@ int launch_layer(hipStream_t st, const uint16_t* x, const uint16_t* w, void* y, 
       });
       e = attr;
       if (e == hipSuccess) hipLaunchKernelGGL(conv3x3_patch_kernel, dim3(g.blocks), dim3(256), PT_LDS, st, a);
+      break;
+    }
+    case PATH_S2C32: {
+      static std::once_flag once;
+      static hipError_t attr = hipSuccess;
+      std::call_once(once, [] {
+        attr = hipFuncSetAttribute((const void*)conv3x3_s2c32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S2_LDS);
+      });
+      e = attr;
+      if (e == hipSuccess) hipLaunchKernelGGL(conv3x3_s2c32_kernel, dim3(g.blocks), dim3(256), S2_LDS, st, a);
       break;
     }
     case PATH_C3:
@@ -1529,6 +1709,7 @@ static uint32_t residency_of(const Geometry& g, uint32_t c_out) {
     case PATH_C3: return c_out <= 32u ? 7u : 4u;      // 22 / 38 KiB of strips and output staging
     case PATH_GENERIC: return 2u;                     // 162 - 244 registers per lane
     case PATH_PATCH: return 2u;                       // 76 KiB of patch and weight ring
+    case PATH_S2C32: return 2u;                       // 74.25 KiB of patch, filter and table
   }
   return 0u;
 }

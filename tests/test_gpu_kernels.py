@@ -296,7 +296,9 @@ def _conv_inputs(seed, n, h, wd, c, k, sigma=0.2):
     (2, 130, 127, 64, 136, 1), (3, 150, 151, 128, 64, 1), (13, 141, 150, 64, 40, 2),
     # stride 1 with the input patch in LDS: whole small images as tiles (idle pixel slots), three channel
     # blocks, ragged channels; 8 output channels (weight rows clamped)
-    (70, 12, 13, 192, 72, 1), (4, 100, 90, 64, 8, 1)])
+    (70, 12, 13, 192, 72, 1), (4, 100, 90, 64, 8, 1),
+    # stride 2 from 32 channels with the filter and the patch in LDS: ragged tiles, 64 and 40 output channels
+    (5, 150, 151, 32, 64, 2), (6, 141, 150, 32, 40, 2)])
 def test_conv_layer_fp32_and_bf16_outputs(n, h, wd, c, k, stride):
     x, w = _conv_inputs(n * 100 + c, n, h, wd, c, k)
     ref = oracle.conv3x3_relu(x, w, stride)

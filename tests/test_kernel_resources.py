@@ -110,7 +110,9 @@ def test_conv_variants(reports):
     lib = oracle.lib()
     lib.orc_conv3x3_residency.restype = C.c_uint64
     cases = [((8, 104, 104, 96, 128, 1), _kernel(reports, "conv3x3_dma_kernel", "ILj2ELj2E"), 4, ring(256, 32, 2)),    # 128 x 128
-             ((8, 416, 416, 32, 64, 2), _kernel(reports, "conv3x3_dma_kernel", "ILj4ELj1E"), 4, ring(320, 32, 2)),     # 256 x 64
+             ((8, 416, 416, 32, 64, 1), _kernel(reports, "conv3x3_dma_kernel", "ILj4ELj1E"), 4, ring(320, 32, 2)),     # 256 x 64
+             # stride 2 from 32 channels: patch of 576 pixels x 64 bytes, the filter of 64 channels, a table of 576 words
+             ((8, 416, 416, 32, 64, 2), _kernel(reports, "conv3x3_s2c32_kernel"), 4, 576 * 64 + 64 * 576 + 576 * 4),
              # the same tiles fed by two stages of depth 64 (c_in % 64 == 0; stride 2: stride 1 takes the patch kernel)
              ((8, 208, 208, 64, 128, 2), _kernel(reports, "conv3x3_dma64_kernel", "ILj2ELj2E"), 4, ring(256, 64, 2) // 2),
              ((8, 416, 416, 64, 64, 2), _kernel(reports, "conv3x3_dma64_kernel", "ILj4ELj1E"), 4, ring(320, 64, 2) // 2),
@@ -125,7 +127,7 @@ def test_conv_variants(reports):
         w = wg_per_cu(rep, waves, ring_bytes)
         want.append(w)
         assert mgb.mgb_conv3x3_residency(*shape) == w == lib.orc_conv3x3_residency(*[U(x) for x in shape]), (shape, rep)
-    assert want == [2, 2, 2, 2, 2, 2, 5, 7, 4]
+    assert want == [2, 2, 2, 2, 2, 2, 2, 5, 7, 4]
     # the register-staged kernels (any other shape) are reported as 2 per CU: never more than they can hold
     for frag in ("ILj64ELb1E", "ILj64ELb0E", "ILj128ELb1E", "ILj128ELb0E"):
         assert wg_per_cu(_kernel(reports, "conv3x3_kernel", frag), 4) >= 2

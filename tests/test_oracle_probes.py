@@ -141,6 +141,11 @@ def test_conv_grids_cover_pixels_times_channels(shape):
     fits = [t for t, th in CONV_TILES if out[1] == round8(ceil_div(pixels, t[0]) * ceil_div(co, t[1])) and out[4] == th]
     if ci == 3 and co <= 64:                                           # first-layer kernel: 256 pixels, all channels
         fits += [(256, co)] if out[1] == round8(ceil_div(pixels, 256)) and out[4] == 256 else []
+    if st == 2 and ci == 32 and co % 8 == 0 and co <= 64 and not fits:
+        # tiles of one image's output, at most 128 pixels each, all channels: from 256 workgroups up
+        per_image = ceil_div(ceil_div(h, 2) * ceil_div(w, 2), 128)
+        assert out[4] == 256 and max(256, b * per_image) <= out[1] <= round8(2 * b * per_image), (shape, out)
+        fits = [(128, 64)]
     if st == 1 and ci % 64 == 0 and co % 8 == 0 and not fits:
         # tiles of one image's output, at most 256 pixels each, times blocks of 64 channels: at least as
         # many as the pixels need, no image shares a tile, and the path is only taken from 128 workgroups up
@@ -175,6 +180,28 @@ def test_patch_kernel_tiles_per_image_worked_by_hand(h, w, tiles):
         out = _probe("orc_conv3x3_probe", batch - 1, h, w, 64, 64, 1)
         pixels = (batch - 1) * h * w
         assert out[1] in (round8(ceil_div(pixels, 256)), round8(ceil_div(pixels, 64)))
+
+
+# The stride-2 kernel for 32 input channels: tiles of th x tw output pixels, th * tw <= 128,
+# (2 th + 1) * (2 tw + 1) <= 576.  Worked by hand:
+#   208 x 208 (the net's second layer at 416 x 416): 338 = 26 x 13 tiles of 8 x 16 (patch 17 x 33 = 561);
+#     43264 / 128 = 338 is the least possible.
+#   75 x 76: at least 45 (5700 / 128 = 44.5).  45 = 9 x 5 needs tiles 9 high (75 / 9 rounded up) and 16 wide
+#     (76 / 5 rounded up) = 144 pixels, 5 x 9 tiles 15 x 9 = 135, 3 x 15 tiles 25 x 6 = 150, 15 x 3 tiles 5 x 26 = 130:
+#     none fits; 46 = 2 x 23 and 47 fit no better (tiles 38 or 75 high); 48 = 8 x 6: tiles of 10 x 13 = 130 do not fit,
+#     6 x 8: 13 x 10 = 130 neither, 4 x 12: 19 x 7 = 133, 12 x 4: 7 x 19 = 133, 3 x 16: 25 x 5 = 125 pixels with a patch of
+#     51 x 11 = 561: fits.  So 48.
+@pytest.mark.parametrize("h,w,tiles", [(416, 416, 338), (150, 151, 48)])
+def test_stride2_kernel_tiles_per_image_worked_by_hand(h, w, tiles):
+    batch = ceil_div(256, tiles)
+    out = _probe("orc_conv3x3_probe", batch, h, w, 32, 64, 2)
+    assert out[1:] == [round8(batch * tiles), 1, 1, 256, 1, 1]
+    assert _probe("orc_conv3x3_probe", batch, h, w, 32, 40, 2)[1] == round8(batch * tiles)     # all channels in one workgroup
+    # more than 64 channels: the ring kernel, 128 pixels x 128 channels per workgroup
+    assert _probe("orc_conv3x3_probe", 8, h, w, 32, 136, 2)[1] == round8(ceil_div(8 * ceil_div(h, 2) * ceil_div(w, 2), 128) * 2)
+    # 36864 (patch) + 36864 (filter) + 2304 (table) = 76032 bytes of LDS: two per CU
+    assert (160 * 1024) // (576 * 64 + 64 * 576 + 576 * 4) == 2
+    assert _lib().orc_conv3x3_residency(*[U(x) for x in (batch, h, w, 32, 64, 2)]) == 2
 
 
 def test_patch_kernel_residency_from_its_lds():
