@@ -115,8 +115,8 @@ void orc_gemm_bf16_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
 //     of LDS at 64 channels); the image is cut into the fewest such tiles;
 //   stride 2, c_in == 32, c_out % 8 == 0 and c_out <= 64: 256 threads per tile of one image's output
 //     (all channels), if that gives at least 256 workgroups.  A tile is th x tw output pixels with
-//     th * tw <= 128 whose input patch of (2 th + 1) x (2 tw + 1) pixels is at most 576 pixels (36 KiB
-//     of LDS at 32 channels); the image is cut into the fewest such tiles;
+//     th * tw <= 128 and th + tw <= 30 whose input patch of (2 th + 1) x (2 tw + 1) pixels is at most
+//     576 pixels (36 KiB of LDS at 32 channels); the image is cut into the fewest such tiles;
 //   else c_in % 32 == 0 and c_out % 8 == 0: 256 threads per 128 pixels x 128 channels (256 x 64 when
 //     c_out <= 64); if that gives fewer than 256 workgroups, 64 x 64 tiles instead, with 256
 //     threads (the depth split four ways) when c_in % 64 == 0, else 64 threads;
@@ -131,7 +131,7 @@ static uint64_t patch_tiles_per_image(uint64_t h, uint64_t w, uint64_t stride) {
     for (uint64_t nx = 1; nx <= w && ny * nx < best; ++nx) {
       const uint64_t tw = ceil_div(w, nx);
       const uint64_t patch = stride == 1 ? (th + 2) * (tw + 2) : (2 * th + 1) * (2 * tw + 1);
-      if (th * tw <= max_px && patch <= max_patch) { best = ny * nx; break; }
+      if (th * tw <= max_px && patch <= max_patch && (stride == 1 || th + tw <= 30)) { best = ny * nx; break; }
     }
   }
   return best;
@@ -192,6 +192,9 @@ void orc_conv3x3_probe(uint64_t batch, uint64_t h, uint64_t w, uint64_t c_in, ui
 // most threads.
 // c[3*i..3*i+2] = {c_in, c_out, stride} of layer i.
 //
+// A first layer of 3 -> 32 channels at stride 1 in front of a layer that takes the stride-2 kernel for
+// 32 input channels has no launch of its own (that kernel computes it on the fly).
+//
 // Inside a chain a depth-split layer of at most 96 tiles with c_in >= 512 is split further, over
 // min(16, 512 / tiles, (9 c_in / 64) / 4) workgroups per tile, as far as the fp32 partial sums fit the
 // idle part of a ping-pong buffer (behind the layer's own output rounded up to 256 bytes; the
@@ -215,6 +218,10 @@ void orc_cnn_probe(const uint64_t* c, uint64_t n_layers, uint64_t batch, uint64_
     uint64_t pixels = batch * ho * wo, elems = pixels * c_out, th;
     bool split;
     uint64_t wgs = conv_workgroups(batch, ho, wo, c_in, c_out, stride, &th, &split);
+    if (c_in == 3 && c_out == 32 && stride == 1 && i + 1 < n_layers) {
+      uint64_t s2 = c[3 * i + 5], ho2 = (ho - 1) / s2 + 1, wo2 = (wo - 1) / s2 + 1, next_wgs;
+      if (conv_stride2_32_path(batch, ho2, wo2, c[3 * i + 3], c[3 * i + 4], s2, &next_wgs)) { hh = ho; ww = wo; continue; }
+    }
     if (split && wgs <= 96 && c_in >= 512) {
       uint64_t own = i + 1 < n_layers ? ceil_div(elems * 2, 256) * 256 : 0;
       uint64_t spare = act_max > own ? act_max - own : 0;

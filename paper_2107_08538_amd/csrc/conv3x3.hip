@@ -75,6 +75,8 @@ struct ConvArgs {
   uint32_t th, tw, tiles_y, tiles_x;   // patch kernels only: output tile of th x tw pixels, tiles per image
   FastDiv by_tiles_n, by_plane, by_wo; // divisors tiles_n, Ho * Wo, Wo
   FastDiv by_tiles_x, by_tiles_y, by_pw, by_tw;   // patch kernels only: tiles_x, tiles_y, patch width, tw
+  const uint16_t* w_first;             // fused first two layers only: the 3-channel layer's filter
+  FastDiv by_iw;                       // the same: patch width + 2
 };
 
 // 16 bytes of zeros in device memory: the source of every padded / out-of-range operand chunk
@@ -1154,13 +1156,30 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(ConvArgs a) {
 // Nothing streams: one barrier after the copies, then 9 taps x 2 slices of 16 with no further
 // synchronisation.  Four waves, each 32 pixels x 64 channels.  16-byte chunks of a pixel are
 // XOR-swizzled by bits 2..3 of the pixel's LDS index.
+//
+// FUSED: the layer in front is the net's 3-channel first layer with 32 output channels, and the
+// patch is computed here instead of being read: the workgroup loads the raw 3-channel pixels
+// under its patch (two more rows and columns), runs the first layer on them exactly as
+// conv3x3_c3_kernel does (three MFMA steps per 32 pixels, one per filter row, same operand
+// layout, so the same bits come out), applies ReLU and the bf16 rounding and writes the values
+// where the DMA would have put them (zeros where the patch leaves the image: that is the second
+// layer's padding, not a first-layer output).  The first layer's output, 32 channels at full
+// resolution and the largest tensor of the net, is then neither written nor read back.
 constexpr uint32_t S2_NPB = 9u;                           // patch DMA instructions per wave, 16 pixels each
 constexpr uint32_t S2_MAX_SLOTS = 4u * S2_NPB * 16u;      // 576 patch pixels
 constexpr uint32_t S2_PATCH = S2_MAX_SLOTS * 64u;         // 36 KiB
 constexpr uint32_t S2_WPITCH = 576u, S2_WBYTES = 64u * S2_WPITCH;
 constexpr uint32_t S2_LDS = S2_PATCH + S2_WBYTES + S2_MAX_SLOTS * 4u;   // 76032 bytes: two workgroups per CU
 constexpr uint32_t S2_MIN_TILES = 256u;
+// tiles are kept to th + tw <= 30: patch height + width <= 62, so that the raw pixels under a
+// patch (height + 2 by width + 2) are at most 576 + 2 * 62 + 4 = 704
+constexpr uint32_t S2_MAX_SIDES = 30u;
+constexpr uint32_t S2_FIRST_W = 32u * 27u * 2u;           // the first layer's filter, 1728 bytes
+constexpr uint32_t S2_RAW_MAX = 704u;                     // raw pixels under a patch, 8 bytes each
+constexpr uint32_t S2_LDS_FUSED = S2_PATCH + S2_WBYTES + S2_FIRST_W + (S2_RAW_MAX + 1u) * 8u;   // 81096 bytes: two per CU (one
+                                                          // entry more: the padding tap of the last pixel reads it)
 
+template <bool FUSED>
 __global__ __launch_bounds__(256, 2) void conv3x3_s2c32_kernel(ConvArgs a) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   const uint32_t per_xcd = (a.tiles_total + 7u) / 8u;
@@ -1178,31 +1197,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_s2c32_kernel(ConvArgs a) {
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t l32 = lane & 31u, lhi = lane >> 5;
   const uint16_t* zeros = reinterpret_cast<const uint16_t*>(g_zero16);
+  (void)zeros;
   uint8_t* wl = smem + S2_PATCH;
 
-  // entry s of the table: the input pixel stored at LDS index s, counted from the one under patch
-  // pixel (0, 0), or all ones if it lies outside the image or s is past the patch
-  uint32_t* pixel_of_slot = reinterpret_cast<uint32_t*>(smem + S2_PATCH + S2_WBYTES);
-#pragma unroll
-  for (uint32_t e = 0; e < (S2_MAX_SLOTS + 255u) / 256u; ++e) {
-    const uint32_t slot = tid + 256u * e;
-    const uint32_t py = slot / a.by_pw, rem = slot - py * pw;
-    const uint32_t px = rem <= a.tw ? 2u * rem : 2u * (rem - a.tw) - 1u;        // even columns first, then the odd ones
-    const uint32_t ok = (uint32_t)(slot < slots) & (uint32_t)(2u * oh0 + py - 1u < a.H) & (uint32_t)(2u * ow0 + px - 1u < a.W);
-    if (slot < S2_MAX_SLOTS) pixel_of_slot[slot] = ok ? py * a.W + px : 0xffffffffu;
-  }
-  __syncthreads();
-  // patch: instruction h of wave w fills the 1 KiB block 4h + w = LDS pixels 16 * (4h + w) .. + 15;
-  // lane -> pixel + lane / 4, LDS chunk lane % 4, source chunk swizzled (bits 2..3 of the pixel
-  // index are bits 4..5 of the lane whatever h and w)
-  const uint16_t* origin = a.x + (((int64_t)img * a.H + 2 * (int64_t)oh0) * a.W + 2 * (int64_t)ow0 - (int64_t)a.W - 1) * 32 +
-                           8u * ((lane & 3u) ^ ((lane >> 4) & 3u));
-  uint32_t a_pixel[S2_NPB];                  // (all table reads first: a DMA request orders later LDS reads behind it)
-#pragma unroll
-  for (uint32_t h = 0; h < S2_NPB; ++h) a_pixel[h] = pixel_of_slot[16u * (4u * h + wave) + (lane >> 2)];
-#pragma unroll
-  for (uint32_t h = 0; h < S2_NPB; ++h)
-    if (h < nph) dma16(a_pixel[h] != 0xffffffffu ? origin + (uint64_t)a_pixel[h] * 32u : zeros, lds_base + (4u * h + wave) * 1024u);
   // filter: 36 chunks of 16 bytes per channel, 2304 in all = 36 DMA instructions, 9 per wave.
   // Chunk c of channel row sits at LDS chunk 36 * row + (c with its low two bits ^ bits 2..3 of
   // the row); channels past c_out repeat the last one (they feed outputs that are never stored).
@@ -1213,6 +1210,123 @@ __global__ __launch_bounds__(256, 2) void conv3x3_s2c32_kernel(ConvArgs a) {
     dma16(a.w + (size_t)min(row, a.K - 1u) * 288u + 8u * c, lds_base + S2_PATCH + (4u * e + wave) * 1024u);
   }
 
+  if (FUSED) {
+    // raw pixels under the patch: rows 2 oh0 - 2 .. 2 oh0 + 2 th, columns 2 ow0 - 2 .. 2 ow0 + 2 tw, each
+    // padded to four channels (8 bytes), zeros outside the image; and the first layer's filter.
+    // All loads are issued before the first of them is used.
+    uint16_t* w0l = reinterpret_cast<uint16_t*>(smem + S2_PATCH + S2_WBYTES);
+    uint2* raw = reinterpret_cast<uint2*>(smem + S2_PATCH + S2_WBYTES + S2_FIRST_W);
+    const uint32_t rw = pw + 2u, raws = (2u * a.th + 3u) * rw;
+    constexpr uint32_t RAW_ITERS = (S2_RAW_MAX + 255u) / 256u, W_ITERS = (32u * 27u + 255u) / 256u;
+    uint32_t rc[RAW_ITERS][3], wv[W_ITERS];
+    bool rok[RAW_ITERS];
+#pragma unroll
+    for (uint32_t it = 0; it < RAW_ITERS; ++it) {
+      const uint32_t idx = tid + 256u * it;
+      const uint32_t iy = idx / a.by_iw, ix = idx - iy * rw;
+      const uint32_t gy = 2u * oh0 + iy - 2u, gx = 2u * ow0 + ix - 2u;      // (wraps to a huge value above / left of the image)
+      rok[it] = idx < raws && gy < a.H && gx < a.W;
+      const int64_t g = rok[it] ? ((int64_t)img * a.H + gy) * a.W + gx : 0;
+#pragma unroll
+      for (uint32_t c = 0; c < 3; ++c) rc[it][c] = a.x[g * 3 + c];
+    }
+#pragma unroll
+    for (uint32_t it = 0; it < W_ITERS; ++it) {
+      const uint32_t idx = tid + 256u * it;
+      wv[it] = a.w_first[idx < 32u * 27u ? idx : 0u];
+    }
+#pragma unroll
+    for (uint32_t it = 0; it < RAW_ITERS; ++it) {
+      const uint32_t idx = tid + 256u * it;
+      if (idx < S2_RAW_MAX) raw[idx] = rok[it] ? make_uint2(rc[it][0] | (rc[it][1] << 16), rc[it][2]) : make_uint2(0u, 0u);
+    }
+#pragma unroll
+    for (uint32_t it = 0; it < W_ITERS; ++it) {
+      const uint32_t idx = tid + 256u * it;
+      if (idx < 32u * 27u) w0l[idx] = (uint16_t)wv[it];
+    }
+    __syncthreads();
+    // first-layer weight fragments of filter row r: channel l32, operand e = (s, c) = (2*lhi + e/4, e%4)
+    u32x4 f0[3];
+#pragma unroll
+    for (uint32_t r = 0; r < 3; ++r) {
+      uint32_t wd[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (uint32_t e = 0; e < 8; ++e) {
+        const uint32_t t = 2u * lhi + (e >> 2), c = e & 3u;
+        const uint32_t ok = (uint32_t)(t < 3u) & (uint32_t)(c < 3u);
+        const uint32_t v = w0l[ok ? l32 * 27u + r * 9u + t * 3u + c : 0u];
+        wd[e >> 1] |= (ok ? v : 0u) << (16u * (e & 1u));
+      }
+      f0[r] = u32x4{wd[0], wd[1], wd[2], wd[3]};
+    }
+    // the first layer on the patch, 32 patch pixels (row-major) per block, the waves taking turns;
+    // two blocks at a time, so that one block's chain of three dependent MFMAs fills the gaps of the other's
+    for (uint32_t first = 32u * wave; first < slots; first += 256u) {
+      uint32_t py[2], px[2];
+      bool in_patch[2];
+      f32x16 z[2];
+#pragma unroll
+      for (uint32_t u = 0; u < 2; ++u) {
+        const uint32_t qp = first + 128u * u + l32;
+        in_patch[u] = qp < slots;
+        const uint32_t qq = in_patch[u] ? qp : 0u;
+        py[u] = qq / a.by_pw;
+        px[u] = qq - py[u] * pw;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) z[u][r] = 0.f;
+      }
+#pragma unroll
+      for (uint32_t r = 0; r < 3; ++r)
+#pragma unroll
+        for (uint32_t u = 0; u < 2; ++u) {
+          // taps s = 2*lhi and 2*lhi + 1 of row r: raw pixels (py + r, px + s), (py + r, px + s + 1)
+          const uint2 d0 = raw[(py[u] + r) * rw + px[u] + 2u * lhi];
+          const uint2 d1 = raw[(py[u] + r) * rw + px[u] + 2u * lhi + 1u];
+          const uint32_t m1 = lhi ? 0u : 0xffffffffu;                        // s = 3 is padding
+          z[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(f0[r]), as_bf16x8(u32x4{d0.x, d0.y, d1.x & m1, d1.y & m1}), z[u], 0, 0, 0);
+        }
+#pragma unroll
+      for (uint32_t u = 0; u < 2; ++u) {
+        // channels 8g + 4*lhi + (0..3) of patch pixel (py, px) -> its LDS place (even columns first)
+        const bool real = 2u * oh0 + py[u] - 1u < a.H && 2u * ow0 + px[u] - 1u < a.W;
+        const uint32_t slot = py[u] * pw + ((px[u] & 1u) ? a.tw + 1u + (px[u] >> 1) : (px[u] >> 1));
+        if (in_patch[u]) {
+#pragma unroll
+          for (uint32_t g = 0; g < 4; ++g) {
+            uint2 v;
+            v.x = real ? pack_bf16x2(fmaxf(z[u][4u * g], 0.f), fmaxf(z[u][4u * g + 1u], 0.f)) : 0u;
+            v.y = real ? pack_bf16x2(fmaxf(z[u][4u * g + 2u], 0.f), fmaxf(z[u][4u * g + 3u], 0.f)) : 0u;
+            *reinterpret_cast<uint2*>(smem + slot * 64u + ((g ^ ((slot >> 2) & 3u)) << 4) + 8u * lhi) = v;
+          }
+        }
+      }
+    }
+  } else {
+    // entry s of the table: the input pixel stored at LDS index s, counted from the one under patch
+    // pixel (0, 0), or all ones if it lies outside the image or s is past the patch
+    uint32_t* pixel_of_slot = reinterpret_cast<uint32_t*>(smem + S2_PATCH + S2_WBYTES);
+  #pragma unroll
+    for (uint32_t e = 0; e < (S2_MAX_SLOTS + 255u) / 256u; ++e) {
+      const uint32_t slot = tid + 256u * e;
+      const uint32_t py = slot / a.by_pw, rem = slot - py * pw;
+      const uint32_t px = rem <= a.tw ? 2u * rem : 2u * (rem - a.tw) - 1u;        // even columns first, then the odd ones
+      const uint32_t ok = (uint32_t)(slot < slots) & (uint32_t)(2u * oh0 + py - 1u < a.H) & (uint32_t)(2u * ow0 + px - 1u < a.W);
+      if (slot < S2_MAX_SLOTS) pixel_of_slot[slot] = ok ? py * a.W + px : 0xffffffffu;
+    }
+    __syncthreads();
+    // patch: instruction h of wave w fills the 1 KiB block 4h + w = LDS pixels 16 * (4h + w) .. + 15;
+    // lane -> pixel + lane / 4, LDS chunk lane % 4, source chunk swizzled (bits 2..3 of the pixel
+    // index are bits 4..5 of the lane whatever h and w)
+    const uint16_t* origin = a.x + (((int64_t)img * a.H + 2 * (int64_t)oh0) * a.W + 2 * (int64_t)ow0 - (int64_t)a.W - 1) * 32 +
+                             8u * ((lane & 3u) ^ ((lane >> 4) & 3u));
+    uint32_t a_pixel[S2_NPB];                  // (all table reads first: a DMA request orders later LDS reads behind it)
+  #pragma unroll
+    for (uint32_t h = 0; h < S2_NPB; ++h) a_pixel[h] = pixel_of_slot[16u * (4u * h + wave) + (lane >> 2)];
+  #pragma unroll
+    for (uint32_t h = 0; h < S2_NPB; ++h)
+      if (h < nph) dma16(a_pixel[h] != 0xffffffffu ? origin + (uint64_t)a_pixel[h] * 32u : zeros, lds_base + (4u * h + wave) * 1024u);
+  }
   f32x16 acc[1][2];
 #pragma unroll
   for (int j = 0; j < 2; ++j)
@@ -1420,14 +1534,15 @@ struct Geometry {
 // whose input patch ((th + 2) * (tw + 2) pixels at stride 1, (2 th + 1) * (2 tw + 1) at stride 2)
 // fits max_slots, such that the fewest tiles cover the image (every tile costs the MFMAs of
 // max_px pixels); among those the one with the smallest patch.
-void patch_tile(uint32_t h, uint32_t w, uint32_t stride, uint32_t max_px, uint32_t max_slots, uint32_t* th, uint32_t* tw) {
+void patch_tile(uint32_t h, uint32_t w, uint32_t stride, uint32_t max_px, uint32_t max_slots, uint32_t* th, uint32_t* tw,
+                uint32_t max_sides = 0xffffffffu) {      // max_sides: limit on th + tw
   uint64_t best_tiles = ~0ull;
   uint32_t best_slots = 0u;
   *th = *tw = 1u;
   for (uint32_t x = 1u; x <= max_px && x <= w; ++x)
     for (uint32_t y = 1u; y <= max_px / x && y <= h; ++y) {
       const uint32_t slots = stride == 1u ? (x + 2u) * (y + 2u) : (2u * x + 1u) * (2u * y + 1u);
-      if (slots > max_slots) break;
+      if (slots > max_slots || x + y > max_sides) break;
       const uint64_t tiles = (uint64_t)((h + y - 1u) / y) * ((w + x - 1u) / x);
       if (tiles < best_tiles || (tiles == best_tiles && slots < best_slots)) {
         best_tiles = tiles;
@@ -1452,7 +1567,8 @@ bool shape_ok(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_t c_
 //   stride 1, c_in % 64 == 0 and c_out % 8 == 0: the patch kernel, if its tiles (patch_tile) times
 //     blocks of 64 channels make at least PT_MIN_TILES workgroups;
 //   stride 2, c_in == 32, c_out % 8 == 0 and c_out <= 64: the kernel with the filter and the
-//     tile's patch in LDS, if its tiles (at most 128 pixels) make at least S2_MIN_TILES workgroups;
+//     tile's patch in LDS, if its tiles (at most 128 pixels, th + tw <= 30) make at least
+//     S2_MIN_TILES workgroups;
 //   else c_in % 32 == 0 and c_out % 8 == 0: DMA-ring kernel; 128 x 128 tiles (256 pixels x 64 channels
 //     when c_out <= 64) if that gives at least one workgroup per CU, else 64 x 64 tiles: four
 //     waves that split the depth when c_in % 64 == 0, one wave per workgroup otherwise;
@@ -1481,7 +1597,7 @@ Geometry geometry(uint32_t batch, uint32_t h, uint32_t w, uint32_t c_in, uint32_
     }
   }
   if (allow_fast && stride == 2u && c_in == 32u && c_out % 8u == 0u && c_out <= 64u) {
-    patch_tile(g.Ho, g.Wo, 2u, 128u, S2_MAX_SLOTS, &g.th, &g.tw);
+    patch_tile(g.Ho, g.Wo, 2u, 128u, S2_MAX_SLOTS, &g.th, &g.tw, S2_MAX_SIDES);
     g.tiles_y = (g.Ho + g.th - 1u) / g.th;
     g.tiles_x = (g.Wo + g.tw - 1u) / g.tw;
     const uint64_t total = (uint64_t)batch * g.tiles_y * g.tiles_x;
@@ -1532,6 +1648,7 @@ struct LayerPlan {
   Geometry g;
   uint32_t splits;
   uint64_t work_off;     // byte offset of the partial sums in that buffer
+  bool in_next;          // this layer is computed inside the next layer's kernel: no launch of its own
 };
 
 int plan_chain(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, uint32_t h, uint32_t w,
@@ -1545,6 +1662,7 @@ int plan_chain(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, 
     plan[i].g = geometry(batch, ch, cw, L.c_in, L.c_out, L.stride, allow_fast);
     plan[i].splits = 1u;
     plan[i].work_off = 0u;
+    plan[i].in_next = false;
     *weights += 9ull * L.c_in * L.c_out * 2;
     const uint64_t elems = (uint64_t)plan[i].g.pixels * L.c_out;
     if (i + 1u < n_layers) *act_max = *act_max > elems * 2 ? *act_max : elems * 2;
@@ -1552,6 +1670,10 @@ int plan_chain(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batch, 
     ch = plan[i].g.Ho;
     cw = plan[i].g.Wo;
   }
+  // The 3-channel first layer with 32 output channels in front of a layer that takes the
+  // stride-2 kernel for 32 input channels is computed inside that kernel.
+  for (uint32_t i = 0; i + 1u < n_layers; ++i)
+    plan[i].in_next = plan[i].g.path == PATH_C3 && layers[i].c_out == 32u && plan[i + 1u].g.path == PATH_S2C32;
   for (uint32_t i = 0; i < n_layers; ++i) {
     Geometry& g = plan[i].g;
     if (g.path != PATH_DMA_KSPLIT || g.total > 96u || layers[i].c_in < 512u) continue;
@@ -1596,12 +1718,19 @@ hipError_t launch_dma(hipStream_t st, const Geometry& g, const ConvArgs& a, bool
 }
 
 // `splits` > 1 (depth-split path only): `work` holds splits * pixels * c_out floats
+// `w_first`: the layer in front (3 channels -> 32, stride 1, reading `x`) is computed inside this
+// layer's kernel; h, wd and c_in describe this layer's input as if it existed.
 int launch_layer(hipStream_t st, const uint16_t* x, const uint16_t* w, void* y, uint32_t batch,
                  uint32_t h, uint32_t wd, uint32_t c_in, uint32_t c_out, uint32_t stride,
-                 uint32_t out_f32, uint32_t splits = 1u, float* work = nullptr) {
+                 uint32_t out_f32, uint32_t splits = 1u, float* work = nullptr, const uint16_t* w_first = nullptr) {
   // the fast paths move 16 bytes at a time (the probe assumed aligned tensors)
-  const bool aligned = (((uintptr_t)x | (uintptr_t)w | (uintptr_t)y | (uintptr_t)work) & 15u) == 0u;
+  // (a fused first layer's 3-channel input is read two bytes at a time: any alignment will do)
+  const bool aligned = (((w_first ? (uintptr_t)0 : (uintptr_t)x) | (uintptr_t)w | (uintptr_t)y | (uintptr_t)work) & 15u) == 0u;
   Geometry g = geometry(batch, h, wd, c_in, c_out, stride, aligned);
+  if (w_first && g.path != PATH_S2C32) {
+    mgb_internal_set_error_text("conv chain: a first layer planned into the second layer's kernel, which the second layer's tensors do not allow (alignment)");
+    return MGB_E_INVAL;
+  }
   if (splits > 1u && (g.path != PATH_DMA_KSPLIT || !work)) splits = 1u;
   g.total *= splits;
   g.blocks = (g.total + 7u) / 8u * 8u;
@@ -1619,6 +1748,8 @@ int launch_layer(hipStream_t st, const uint16_t* x, const uint16_t* w, void* y, 
   a.by_tiles_y = fast_div(g.tiles_y ? g.tiles_y : 1u);
   a.by_pw = fast_div(g.path == PATH_S2C32 ? 2u * g.tw + 1u : g.tw + 2u);
   a.by_tw = fast_div(g.tw ? g.tw : 1u);
+  a.w_first = w_first;
+  a.by_iw = fast_div(2u * g.tw + 3u);
   hipError_t e = hipSuccess;
   switch (g.path) {
     case PATH_DMA_128x128: e = launch_dma<2, 2>(st, g, a, true); break;
@@ -1654,10 +1785,15 @@ int launch_layer(hipStream_t st, const uint16_t* x, const uint16_t* w, void* y, 
       static std::once_flag once;
       static hipError_t attr = hipSuccess;
       std::call_once(once, [] {
-        attr = hipFuncSetAttribute((const void*)conv3x3_s2c32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S2_LDS);
+        attr = hipFuncSetAttribute((const void*)conv3x3_s2c32_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S2_LDS);
+        if (attr == hipSuccess)
+          attr = hipFuncSetAttribute((const void*)conv3x3_s2c32_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S2_LDS_FUSED);
       });
       e = attr;
-      if (e == hipSuccess) hipLaunchKernelGGL(conv3x3_s2c32_kernel, dim3(g.blocks), dim3(256), S2_LDS, st, a);
+      if (e == hipSuccess) {
+        if (w_first) hipLaunchKernelGGL(conv3x3_s2c32_kernel<true>, dim3(g.blocks), dim3(256), S2_LDS_FUSED, st, a);
+        else hipLaunchKernelGGL(conv3x3_s2c32_kernel<false>, dim3(g.blocks), dim3(256), S2_LDS, st, a);
+      }
       break;
     }
     case PATH_C3:
@@ -1729,6 +1865,7 @@ uint32_t mgb_cnn_residency(const mgb_conv_layer* layers, uint32_t n_layers, uint
   uint32_t blocks = 0, threads = CV_THREADS, res = 0;
   for (uint32_t i = 0; i < n_layers; ++i) {
     const Geometry& g = plan[i].g;
+    if (plan[i].in_next) continue;                     // no launch of its own
     if ((uint64_t)g.blocks * g.threads > (uint64_t)blocks * threads) {   // the launch that gives the task its geometry
       blocks = g.blocks;
       threads = g.threads;
@@ -1762,6 +1899,7 @@ int mgb_cnn_probe(const mgb_conv_layer* layers, uint32_t n_layers, uint32_t batc
   const uint64_t input = (uint64_t)batch * h * w * layers[0].c_in * 2;
   for (uint32_t i = 0; i < n_layers; ++i) {
     const Geometry& g = plan[i].g;
+    if (plan[i].in_next) continue;                     // no launch of its own
     // launches are stream-ordered: the one with the most waves counts
     if ((uint64_t)g.blocks * g.threads > (uint64_t)blocks * threads) {
       blocks = g.blocks;
@@ -1800,10 +1938,16 @@ int mgb_cnn_enqueue(void* stream, const mgb_conv_layer* layers, uint32_t n_layer
     uint16_t* pong = (i & 1u) ? act1 : act0;           // the buffer this layer does not read
     void* dst = last ? (void*)out : (void*)pong;
     float* work = plan[i].splits > 1u ? reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(pong) + plan[i].work_off) : nullptr;
-    rc = launch_layer(st, src, weights[i], dst, batch, ch, cw, L.c_in, L.c_out, L.stride, last ? 1u : 0u,
-                      plan[i].splits, work);
-    if (rc != MGB_OK) return rc;
-    src = (const uint16_t*)dst;
+    if (plan[i].in_next) {
+      // computed by the next layer's kernel straight from this layer's input: nothing is launched
+      // and nothing written; the next layer keeps `src` and its own destination buffer
+    } else {
+      const uint16_t* w_first = i > 0u && plan[i - 1u].in_next ? weights[i - 1u] : nullptr;
+      rc = launch_layer(st, src, weights[i], dst, batch, ch, cw, L.c_in, L.c_out, L.stride, last ? 1u : 0u,
+                        plan[i].splits, work, w_first);
+      if (rc != MGB_OK) return rc;
+      src = (const uint16_t*)dst;
+    }
     ch = (ch - 1u) / L.stride + 1u;
     cw = (cw - 1u) / L.stride + 1u;
   }

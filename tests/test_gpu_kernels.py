@@ -365,6 +365,28 @@ def test_cnn_ten_layer_chain_reduced_image():
     assert (g.x, b.x) == (128, 256)
 
 
+def test_first_two_layers_in_one_kernel_match_the_layers_run_apart():
+    # 3 -> 32 channels at stride 1, then 32 -> 64 (and 40) at stride 2: inside a chain the first layer is
+    # computed by the second layer's kernel from the raw pixels under each patch.  Ragged tiles at
+    # the right and bottom edges; 6 images x 48 tiles = 288 workgroups.
+    batch, h, wd = 6, 150, 151
+    for k2 in (64, 40):
+        layers = [dict(c_in=3, c_out=32, stride=1, h_in=h, w_in=wd, h_out=h, w_out=wd),
+                  dict(c_in=32, c_out=k2, stride=2, h_in=h, w_in=wd, h_out=75, w_out=76)]
+        weights = W.cnn_weights(41 + k2, layers, sigma=0.2)
+        xb = W.cnn_input(41, batch, h, wd)
+        got, mem, g, b = run_cnn(xb, weights, layers, batch, h, wd)
+        assert (g.x, b.x) == (288, 256)                              # the one launch of the chain
+        # the same two layers through the single-layer entry point: the first layer's own kernel writes
+        # its bf16 output, the second reads it back.  Same arithmetic in the same order: the same bits.
+        y0 = run_conv(xb, weights[0], 1, False)
+        apart = run_conv(y0, weights[1], 2, True)
+        assert np.array_equal(got, apart)
+        ref = oracle.cnn_forward(xb, weights, [1, 2])
+        assert (ref == 0).any() and np.linalg.norm(ref) > 0
+        assert frobenius_rel(got, ref) <= 1e-2 and frobenius_rel(got, ref) <= 1e-5
+
+
 def test_cnn_full_size_layers_sampled():
     # 416x416 input, batch 1: every layer of the real net is checked on sampled output pixels,
     # each recomputed by the checker from the 3x3xC patch of that layer's (GPU-produced) input

@@ -112,7 +112,7 @@ def test_conv_variants(reports):
     cases = [((8, 104, 104, 96, 128, 1), _kernel(reports, "conv3x3_dma_kernel", "ILj2ELj2E"), 4, ring(256, 32, 2)),    # 128 x 128
              ((8, 416, 416, 32, 64, 1), _kernel(reports, "conv3x3_dma_kernel", "ILj4ELj1E"), 4, ring(320, 32, 2)),     # 256 x 64
              # stride 2 from 32 channels: patch of 576 pixels x 64 bytes, the filter of 64 channels, a table of 576 words
-             ((8, 416, 416, 32, 64, 2), _kernel(reports, "conv3x3_s2c32_kernel"), 4, 576 * 64 + 64 * 576 + 576 * 4),
+             ((8, 416, 416, 32, 64, 2), _kernel(reports, "conv3x3_s2c32_kernel", "ILb0E"), 4, 576 * 64 + 64 * 576 + 576 * 4),
              # the same tiles fed by two stages of depth 64 (c_in % 64 == 0; stride 2: stride 1 takes the patch kernel)
              ((8, 208, 208, 64, 128, 2), _kernel(reports, "conv3x3_dma64_kernel", "ILj2ELj2E"), 4, ring(256, 64, 2) // 2),
              ((8, 416, 416, 64, 64, 2), _kernel(reports, "conv3x3_dma64_kernel", "ILj4ELj1E"), 4, ring(320, 64, 2) // 2),
@@ -128,6 +128,12 @@ def test_conv_variants(reports):
         want.append(w)
         assert mgb.mgb_conv3x3_residency(*shape) == w == lib.orc_conv3x3_residency(*[U(x) for x in shape]), (shape, rep)
     assert want == [2, 2, 2, 2, 2, 2, 2, 5, 7, 4]
+    # the same kernel computing the 3-channel first layer on the fly (inside a chain): the first layer's filter
+    # (32 x 27 values) and 705 raw pixels of 8 bytes instead of the table
+    fused = wg_per_cu(_kernel(reports, "conv3x3_s2c32_kernel", "ILb1E"), 4, 576 * 64 + 64 * 576 + 32 * 27 * 2 + 705 * 8)
+    net = [(3, 32, 1), (32, 64, 2)]
+    flat = (mgb.mgb_conv_layer * 2)(*[mgb.mgb_conv_layer(*L) for L in net])
+    assert mgb.mgb_cnn_residency(flat, 2, 8, 416, 416) == fused == 2
     # the register-staged kernels (any other shape) are reported as 2 per CU: never more than they can hold
     for frag in ("ILj64ELb1E", "ILj64ELb0E", "ILj128ELb1E", "ILj128ELb0E"):
         assert wg_per_cu(_kernel(reports, "conv3x3_kernel", frag), 4) >= 2

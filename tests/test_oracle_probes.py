@@ -182,14 +182,14 @@ def test_patch_kernel_tiles_per_image_worked_by_hand(h, w, tiles):
         assert out[1] in (round8(ceil_div(pixels, 256)), round8(ceil_div(pixels, 64)))
 
 
-# The stride-2 kernel for 32 input channels: tiles of th x tw output pixels, th * tw <= 128,
+# The stride-2 kernel for 32 input channels: tiles of th x tw output pixels, th * tw <= 128, th + tw <= 30,
 # (2 th + 1) * (2 tw + 1) <= 576.  Worked by hand:
 #   208 x 208 (the net's second layer at 416 x 416): 338 = 26 x 13 tiles of 8 x 16 (patch 17 x 33 = 561);
 #     43264 / 128 = 338 is the least possible.
 #   75 x 76: at least 45 (5700 / 128 = 44.5).  45 = 9 x 5 needs tiles 9 high (75 / 9 rounded up) and 16 wide
 #     (76 / 5 rounded up) = 144 pixels, 5 x 9 tiles 15 x 9 = 135, 3 x 15 tiles 25 x 6 = 150, 15 x 3 tiles 5 x 26 = 130:
 #     none fits; 46 = 2 x 23 and 47 fit no better (tiles 38 or 75 high); 48 = 8 x 6: tiles of 10 x 13 = 130 do not fit,
-#     6 x 8: 13 x 10 = 130 neither, 4 x 12: 19 x 7 = 133, 12 x 4: 7 x 19 = 133, 3 x 16: 25 x 5 = 125 pixels with a patch of
+#     6 x 8: 13 x 10 = 130 neither, 4 x 12: 19 x 7 = 133, 12 x 4: 7 x 19 = 133, 3 x 16: 25 x 5 = 125 pixels (25 + 5 = 30) with a patch of
 #     51 x 11 = 561: fits.  So 48.
 @pytest.mark.parametrize("h,w,tiles", [(416, 416, 338), (150, 151, 48)])
 def test_stride2_kernel_tiles_per_image_worked_by_hand(h, w, tiles):
@@ -219,12 +219,17 @@ def test_net_geometry_is_its_largest_launch():
         for ci, co, st in net:
             per_layer.append(_probe("orc_conv3x3_probe", batch, h, h, ci, co, st))
             h = ceil_div(h, st)
-        # (a small deep layer may be split further inside a chain, so the chain's largest launch is
-        # at least the largest single-layer launch)
-        assert out[1] * out[4] >= max(p[1] * p[4] for p in per_layer)
-        # layer 1 at batch >= 2: 416 * 416 * batch pixels in tiles of 256 = 676 * batch workgroups
+        # (a small deep layer may be split further inside a chain, so the chain's largest launch is at
+        # least the largest single-layer launch; the first layer has no launch of its own here: the
+        # second layer's kernel computes it on the fly)
+        assert out[1] * out[4] >= max(p[1] * p[4] for p in per_layer[1:])
+        # the second layer: 208 x 208 output pixels per image in tiles of 8 x 16 = 338 * batch workgroups,
+        # the third: 13 x 13 tiles of 16 x 16 per image = 169 * batch; at batch 1 a deeper, split layer has more
+        assert per_layer[1][1:5] == [round8(338 * batch), 1, 1, 256] and per_layer[2][1] == round8(169 * batch)
         if batch >= 2:
-            assert out[1] * out[4] >= 676 * batch * 256
+            assert out[1:] == [round8(338 * batch), 1, 1, 256, 1, 1]
+        # with the first layer alone (nothing behind it to compute it in) its own launch counts
+        assert _cnn_probe(net[:1], batch, 416, 416)[1] == round8(676 * batch)
 
 
 @pytest.mark.parametrize("n", [1, 100, 4096, 4097, 1 << 16, 1 << 20, (1 << 20) + 1, 1 << 22, 5000000])
