@@ -836,12 +836,16 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma64_kernel(ConvArgs
       const uint32_t ok = (a_taps[h] >> a_tap) & 1u;
       dma16(pick(a.x + a_src[h] + delta, zeros, ok), stage + (NA * wave + h) * 1024u);
     } else {
-      dma16(b_src[h - NA] + (size_t)td * 64u, stage + A_BYTES + (NB * wave + h - NA) * 1024u);
+      dma16(b_src[h - NA] + (size_t)min(td, nk - 1u) * 64u, stage + A_BYTES + (NB * wave + h - NA) * 1024u);
     }
   };
+  // (the cursor stops at the last tile: the requests past it re-read that tile into a stage nobody
+  // reads any more, so that every iteration issues the same instructions)
   auto next_tile = [&]() {
-    a_c0 += 64u;
-    if (a_c0 == a.C) { a_c0 = 0u; ++a_tap; }
+    if (td + 1u < nk) {
+      a_c0 += 64u;
+      if (a_c0 == a.C) { a_c0 = 0u; ++a_tap; }
+    }
     ++td;
   };
 
@@ -906,12 +910,8 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma64_kernel(ConvArgs
     // complete and that tile kt's stage may be overwritten.
     __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) and lgkmcnt(0)
     __syncthreads();
-    if (kt + 2u < nk) {
-      block(1u, nxt, 0u, true);              // tile kt+2 into the stage tile kt leaves
-      next_tile();
-    } else {
-      block(1u, nxt, 0u, false);             // (past the last tile the reads fetch stale bytes nobody uses)
-    }
+    block(1u, nxt, 0u, true);                // tile kt+2 into the stage tile kt leaves
+    next_tile();
   }
   __builtin_amdgcn_s_waitcnt(vm_wait(0));    // no DMA may be in flight when the LDS is given back
 
