@@ -98,10 +98,12 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 q) { return __builtin_bit_cast(bf16x8, q); }
 
-// p if ok (0 or 1) else z, by integer arithmetic: the compiler cannot turn it into a branch
+// p if ok (0 or 1) else z, as a select on the address bits (two conditional moves; written on
+// pointers the compiler may turn it into a branch around the load that follows)
 __device__ __forceinline__ const uint16_t* pick(const uint16_t* p, const uint16_t* z, uint32_t ok) {
-  const uintptr_t pz = (uintptr_t)z;
-  return (const uint16_t*)(pz + (((uintptr_t)p - pz) & (uintptr_t)(0 - (int64_t)ok)));
+  const uintptr_t a = (uintptr_t)p, b = (uintptr_t)z;
+  const uint32_t lo = ok ? (uint32_t)a : (uint32_t)b, hi = ok ? (uint32_t)(a >> 32) : (uint32_t)(b >> 32);
+  return (const uint16_t*)(((uintptr_t)hi << 32) | lo);
 }
 
 // VEC (c_in % 8 == 0) runs depth 64 per step; the element-wise path (3-channel first layer,
@@ -608,25 +610,48 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
     b_src[h] = a.w + (size_t)min(bn + row, a.K - 1u) * a.depth + (size_t)kt0 * KS_BK + 8u * chunk;
   }
 
-  // DMA cursor: tile relative to kt0 (source clamped to the last one), its tap, first channel
+  // DMA cursor: tile relative to kt0, its tap, first channel; and the four sources of the tile,
+  // kept as running pointers.  A workgroup advances one depth tile per pass over this code with
+  // one wave per SIMD, so the pass is kept short: within a filter tap every source moves on by
+  // 64 values (128 bytes; a pixel source that reads the block of zeros stays), and only a new
+  // tap works the pixel sources out again.  At the last tile the sources stop: the requests past
+  // it re-read that tile into stages nobody reads any more.
   uint32_t td = 0u, a_tap = kt0 * KS_BK / a.C, a_c0 = kt0 * KS_BK - a_tap * a.C;
-  auto dma_tile_part = [&](uint32_t q) {     // q = 0, 1: pixel blocks; 2, 3: weight blocks
-    const uint32_t stage = lds_base + (td % KS_NST) * KS_STAGE;
-    if (q < 2u) {
-      const uint32_t r = (a_tap * 11u) >> 5, t = a_tap - 3u * r;
-      const int64_t delta = ((int64_t)r * a.W + t) * a.C + a_c0;
+  const uint16_t* a_cur[2];
+  uint64_t a_step[2], b_step = nk > 1u ? 2u * KS_BK : 0u;
+  auto new_tap = [&]() {
+    const uint32_t r = (a_tap * 11u) >> 5, t = a_tap - 3u * r;
+    const int64_t delta = ((int64_t)r * a.W + t) * a.C + a_c0;
+#pragma unroll
+    for (uint32_t q = 0; q < 2u; ++q) {
       const uint32_t ok = (a_taps[q] >> a_tap) & 1u;
-      dma16(pick(a.x + a_src[q] + delta, zeros, ok), stage + (2u * wave + q) * 1024u);
-    } else {
-      dma16(b_src[q - 2u] + (size_t)min(td, nk - 1u) * KS_BK, stage + KS_PART + (2u * wave + q - 2u) * 1024u);
+      a_cur[q] = pick(a.x + a_src[q] + delta, zeros, ok);
+      a_step[q] = nk > 1u ? (uint64_t)ok * (2u * KS_BK) : 0u;
     }
   };
+  new_tap();
+  auto dma_tile_part = [&](uint32_t q) {     // q = 0, 1: pixel blocks; 2, 3: weight blocks
+    const uint32_t stage = lds_base + (td % KS_NST) * KS_STAGE;
+    if (q < 2u) dma16(a_cur[q], stage + (2u * wave + q) * 1024u);
+    else dma16(b_src[q - 2u], stage + KS_PART + (2u * wave + q - 2u) * 1024u);
+  };
   auto next_tile = [&]() {
-    if (td + 1u < nk) {
-      a_c0 += KS_BK;
-      if (a_c0 == a.C) { a_c0 = 0u; ++a_tap; }
-    }
     ++td;
+    if (td < nk) {
+      a_c0 += KS_BK;
+      if (a_c0 == a.C) {
+        a_c0 = 0u;
+        ++a_tap;
+        new_tap();
+      } else {
+#pragma unroll
+        for (uint32_t q = 0; q < 2u; ++q)
+          a_cur[q] = reinterpret_cast<const uint16_t*>(reinterpret_cast<uintptr_t>(a_cur[q]) + a_step[q]);
+      }
+#pragma unroll
+      for (uint32_t q = 0; q < 2u; ++q)
+        b_src[q] = reinterpret_cast<const uint16_t*>(reinterpret_cast<uintptr_t>(b_src[q]) + b_step);
+    }
   };
 
   f32x16 acc[2][2];                          // [pixel block][channel block]
@@ -681,11 +706,13 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
   __syncthreads();
 #pragma unroll
   for (uint32_t q = 0; q < 4u; ++q) frag_load(smem, 0u, q);
-  for (uint32_t kt = 0; kt < nk; kt += 2u) {
+  // two tiles per iteration (the fragment slots alternate), an odd last tile after the loop
+  uint32_t kt = 0u;
+  for (; kt + 1u < nk; kt += 2u) {
     step(0u, kt);
-    if (kt + 1u >= nk) break;
     step(1u, kt + 1u);
   }
+  if (kt < nk) step(0u, kt);
   __builtin_amdgcn_s_waitcnt(vm_wait(0));    // no DMA in flight, then the ring becomes the reduction buffer
   __syncthreads();
 
