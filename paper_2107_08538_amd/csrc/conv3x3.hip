@@ -1,28 +1,26 @@
-// 3x3 convolution + ReLU (padding 1, stride 1 or 2) as an implicit GEMM on the
-// bf16 matrix cores, and a chain of such layers run as one task.
+// 3x3 convolution + ReLU (padding 1, stride 1 or 2) on the bf16 matrix cores, and a chain of
+// such layers run as one task.
 //
-// Kernels (each described where it is defined): conv3x3_patch_kernel (stride 1, c_in % 64 == 0:
-// the input patch of a 2-D output tile resident in LDS, weights through a DMA ring),
-// conv3x3_dma_kernel (c_in % 32 == 0, c_out % 8 == 0: global -> LDS DMA ring, tiles 128 x 128 /
-// 256 x 64 / 64 x 64) and conv3x3_dma64_kernel (the same tiles with stages of depth 64 when
-// c_in % 64 == 0), conv3x3_dma_ksplit_kernel (c_in % 64 == 0, layers with few tiles: the depth
-// split over the waves of a workgroup and, inside a chain, over workgroups, with
-// conv_split_reduce_kernel), conv3x3_c3_kernel (the 3-channel first layer) and the
-// register-staged conv3x3_kernel for every other shape:
+// GEMM view: rows = output pixels (n, oh, ow), columns = output channels, depth = (r, s, c) =
+// 9 * c_in.  Activations are N,H,W,C and weights K,3,3,C, so for a fixed filter tap the channel
+// run is contiguous for both operands and neither needs a transpose.
 //
-// GEMM view: rows = output pixels (n, oh, ow), columns = output channels,
-// depth = (r, s, c) = 9 * c_in.  Activations are N,H,W,C and weights K,3,3,C,
-// so for a fixed filter tap the channel run is contiguous for both operands:
-// neither needs a transpose, the A tile is gathered straight from the input
-// image (zeros outside it) into LDS, 8 channels per 16-byte load when c_in is
-// a multiple of 8, element-wise otherwise (the 3-channel first layer).
-// A workgroup of 4 waves (2 x 2) owns 128 pixels x BN channels, depth 64 per
-// step.  The late layers of a small batch have only a handful of workgroups, so
-// a step's memory latency cannot be hidden by other workgroups: the tiles of
-// the next TWO steps are kept in flight in registers while the MFMAs of the
-// current step run from LDS.
-// Wide layers are MFMA-bound; the first layer and the small late layers of a
-// small batch are bandwidth / latency bound.
+// Kernels (each described where it is defined; geometry() says which layer gets which):
+//   conv3x3_patch_kernel       stride 1, c_in % 64 == 0: the input patch of a 2-D output tile in
+//                              LDS, read nine times at shifted positions; weights through a ring
+//   conv3x3_s2c32_kernel       stride 2 from 32 channels: filter and patch in LDS; inside a chain it
+//                              also computes the 3-channel first layer in front of it
+//   conv3x3_dma_kernel         implicit GEMM, c_in % 32 == 0: every DMA lane gathers its own
+//   conv3x3_dma64_kernel         pixel; the same with stages of depth 64 (c_in % 64 == 0)
+//   conv3x3_dma_ksplit_kernel  layers with few tiles: the depth split over the waves of a
+//                              workgroup and, inside a chain, over workgroups
+//                              (conv_split_reduce_kernel adds the parts)
+//   conv3x3_c3_kernel          the 3-channel first layer on its own
+//   conv3x3_kernel             register-staged, any other shape
+// At the sizes of the net none of them is bound by the matrix pipes or by bytes: a CU holds two of
+// their workgroups (LDS), and what a workgroup's waves spend on addresses, set-up and result stores
+// is not hidden by anyone else.  Hence store_tile_via_lds, FastDiv, the source tables and the
+// running pointers below.
 #include "../../include/mgb.h"
 #include "launch_util.h"
 #include "lds_dma.h"
@@ -106,8 +104,11 @@ __device__ __forceinline__ const uint16_t* pick(const uint16_t* p, const uint16_
   return (const uint16_t*)(((uintptr_t)hi << 32) | lo);
 }
 
-// VEC (c_in % 8 == 0) runs depth 64 per step; the element-wise path (3-channel first layer,
-// total depth 27) runs depth 32 per step.
+// Register-staged kernel for shapes none of the others takes.  A workgroup of 4 waves (2 x 2)
+// owns 128 pixels x BN channels; the A tile is gathered from the input image (zeros outside it)
+// into LDS, 8 channels per 16-byte load when c_in % 8 == 0 (VEC, depth 64 per step), element-wise
+// otherwise (depth 32 per step).  The tiles of the next two steps are kept in flight in registers
+// while the MFMAs of the current step run from LDS.
 template <uint32_t BN, bool VEC>
 __global__ __launch_bounds__(CV_THREADS, 2) void conv3x3_kernel(ConvArgs a) {
   constexpr uint32_t CV_BK = VEC ? 64u : 32u;
