@@ -1959,6 +1959,8 @@ int mgb_cnn_enqueue(void* stream, const mgb_conv_layer* layers, uint32_t n_layer
   if (rc != MGB_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   const uint16_t* src = x;
+  const uint16_t* first_w = nullptr;       // the filter of a layer left to the next layer's kernel
+  bool skipped = false;
   uint32_t ch = h, cw = w;
   for (uint32_t i = 0; i < n_layers; ++i) {
     const mgb_conv_layer& L = layers[i];
@@ -1966,15 +1968,25 @@ int mgb_cnn_enqueue(void* stream, const mgb_conv_layer* layers, uint32_t n_layer
     uint16_t* pong = (i & 1u) ? act1 : act0;           // the buffer this layer does not read
     void* dst = last ? (void*)out : (void*)pong;
     float* work = plan[i].splits > 1u ? reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(pong) + plan[i].work_off) : nullptr;
+    // Planned into the next layer's kernel: that kernel moves 16 bytes at a time, so it takes the
+    // two layers only if the next layer's filter and destination are aligned for it; otherwise
+    // both run on their own.
     if (plan[i].in_next) {
-      // computed by the next layer's kernel straight from this layer's input: nothing is launched
-      // and nothing written; the next layer keeps `src` and its own destination buffer
+      const bool next_last = i + 2u == n_layers;
+      const void* next_dst = next_last ? (const void*)out : (const void*)(((i + 1u) & 1u) ? act1 : act0);
+      skipped = (((uintptr_t)weights[i + 1u] | (uintptr_t)next_dst) & 15u) == 0u;
     } else {
-      const uint16_t* w_first = i > 0u && plan[i - 1u].in_next ? weights[i - 1u] : nullptr;
+      skipped = false;
+    }
+    if (skipped) {
+      // nothing is launched and nothing written; the next layer reads `src` and writes its own destination
+      first_w = weights[i];
+    } else {
       rc = launch_layer(st, src, weights[i], dst, batch, ch, cw, L.c_in, L.c_out, L.stride, last ? 1u : 0u,
-                        plan[i].splits, work, w_first);
+                        plan[i].splits, work, first_w);
       if (rc != MGB_OK) return rc;
       src = (const uint16_t*)dst;
+      first_w = nullptr;
     }
     ch = (ch - 1u) / L.stride + 1u;
     cw = (cw - 1u) / L.stride + 1u;

@@ -387,6 +387,36 @@ def test_first_two_layers_in_one_kernel_match_the_layers_run_apart():
         assert frobenius_rel(got, ref) <= 1e-2 and frobenius_rel(got, ref) <= 1e-5
 
 
+def test_chain_whose_buffers_are_not_16_byte_aligned_runs_its_first_two_layers_apart():
+    # the same two layers, but the second layer's filter and both ping-pong buffers start 2 bytes off
+    # a 16-byte boundary: the kernel that takes both layers cannot be used, each layer falls back to
+    # a kernel without alignment needs, and the chain still matches the checker
+    batch, h, wd = 6, 150, 151
+    layers = [dict(c_in=3, c_out=32, stride=1, h_in=h, w_in=wd, h_out=h, w_out=wd),
+              dict(c_in=32, c_out=64, stride=2, h_in=h, w_in=wd, h_out=75, w_out=76),
+              dict(c_in=64, c_out=16, stride=2, h_in=75, w_in=76, h_out=38, w_out=38)]
+    weights = W.cnn_weights(77, layers, sigma=0.2)
+    xb = W.cnn_input(77, batch, h, wd)
+    arr = _layer_structs(layers)
+    mem, act, ob = C.c_uint64(), C.c_uint64(), C.c_uint64()
+    g, b = mgb.mgb_dim3(), mgb.mgb_dim3()
+    assert mgb.mgb_cnn_probe(arr, 3, batch, h, wd, C.byref(mem), C.byref(act), C.byref(ob), C.byref(g), C.byref(b)) == 0
+    X = torch.from_numpy(xb.view(np.int16)).to(DEV)
+    Wd = [torch.zeros(w.size + 8, dtype=torch.int16, device=DEV) for w in weights]
+    for t, w in zip(Wd, weights):
+        t[1:1 + w.size] = torch.from_numpy(w.view(np.int16).ravel()).to(DEV)
+    ptrs = (C.c_void_p * 3)(*[t.data_ptr() + 2 for t in Wd])
+    a0 = torch.zeros(act.value // 2 + 8, dtype=torch.int16, device=DEV)
+    a1 = torch.zeros(act.value // 2 + 8, dtype=torch.int16, device=DEV)
+    out = torch.zeros(ob.value // 4, dtype=torch.float32, device=DEV)
+    rc = mgb.mgb_cnn_enqueue(None, arr, 3, P(X), ptrs, C.c_void_p(a0.data_ptr() + 2), C.c_void_p(a1.data_ptr() + 2), P(out), batch, h, wd)
+    assert rc == 0, mgb.mgb_last_error()
+    sync()
+    got = out.cpu().numpy().reshape(batch, 38, 38, 16)
+    ref = oracle.cnn_forward(xb, weights, [1, 2, 2])
+    assert np.linalg.norm(ref) > 0 and frobenius_rel(got, ref) <= 1e-2
+
+
 def test_cnn_full_size_layers_sampled():
     # 416x416 input, batch 1: every layer of the real net is checked on sampled output pixels,
     # each recomputed by the checker from the 3x3xC patch of that layer's (GPU-produced) input
