@@ -285,6 +285,31 @@ def main():
         mfma_tflops[name] = 3 * fl.value / (e0.elapsed_time(e1) / 1e3) / 1e12
     del mout
 
+    # measured operand-fetch and LDS-read rates (what the tile shapes of the MFMA kernels were chosen by):
+    # bytes per clock and CU at the nominal 2.4 GHz; rows of 64 bytes are half cache lines
+    rates = {}
+    rsrc = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda:0")
+    rsink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    nb = C.c_double(0.0)
+
+    def rate(fn):
+        fn()
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return nb.value / (e0.elapsed_time(e1) / 1e3) / 256 / 2.4e9
+
+    for label, foot, row in (("l2_rows_64B", 2 << 20, 64), ("l2_rows_128B", 2 << 20, 128),
+                             ("llc_rows_64B", 64 << 20, 64), ("llc_rows_128B", 64 << 20, 128)):
+        rates[label] = round(rate(lambda: mgb.check(mgb.mgb_fetch_rate_enqueue(
+            cs, C.c_void_p(rsrc.data_ptr()), foot, row, 8192, 512, 500, C.c_void_p(rsink.data_ptr()), C.byref(nb)),
+            "mgb_fetch_rate_enqueue")), 1)
+    for label, swz in (("lds_fragment_reads_swizzled", 1), ("lds_fragment_reads_plain", 0)):
+        rates[label] = round(rate(lambda: mgb.check(mgb.mgb_lds_read_rate_enqueue(
+            cs, swz, 512, 1000, C.c_void_p(rsink.data_ptr()), C.byref(nb)), "mgb_lds_read_rate_enqueue")), 1)
+    del rsrc
+
     pol = dict(hard=mgb.MGB_POLICY_HARD, soft=mgb.MGB_POLICY_SOFT, serial=mgb.MGB_POLICY_SERIAL)[args.policy]
     qm = dict(backfill=mgb.MGB_QUEUE_BACKFILL, fifo=mgb.MGB_QUEUE_FIFO)[args.queue]
     free_b, total_b = torch.cuda.mem_get_info()
@@ -377,7 +402,8 @@ def main():
                median_turnaround_ms=round(med([s["mean_turnaround_ms"] for s in sums]), 3),
                mean_wait_ms=round(sum(s["mean_wait_ms"] for s in sums) / len(sums), 3),
                input_gen_s=round(t_gen, 1), stream_copy_gbps=round(copy_gbps, 1),
-               mfma_loop_tflops={k: round(v, 1) for k, v in mfma_tflops.items()})
+               mfma_loop_tflops={k: round(v, 1) for k, v in mfma_tflops.items()},
+               bytes_per_clk_per_cu=rates)
     out["roofline"] = roof(dominant, kern[dominant])
     out["kernels"] = [roof(n, k) for n, k in kern.items() if n != dominant]
 

@@ -571,6 +571,26 @@ int mgb_copy_enqueue(void* stream, void* dst, const void* src, uint64_t bytes);
 int mgb_mfma_loop_enqueue(void* stream, uint32_t bf16, uint32_t n_blocks, uint32_t iters, float* out,
                           double* flops);
 
+/* Diagnostic: the rate at which the CUs bring operand rows from memory into LDS with the
+ * instruction the DMA-ring kernels use (16 bytes per lane, 1 KiB per wave instruction).
+ * n_blocks workgroups of four waves issue iters rounds of 8 such instructions each; the 64 lanes
+ * of an instruction cover 1024 / row_bytes rows of row_bytes bytes (64, 128, or 1024 = one
+ * contiguous KiB; then `pitch` is ignored), `pitch` bytes apart (a multiple of 16, >= row_bytes),
+ * and every wave walks its own sequence of places through src[0, footprint_bytes) (device, 16-byte
+ * aligned; the footprint decides which level of the memory hierarchy answers).  Rows of 64 bytes
+ * are half cache lines: the figure that tells what depth-32 bf16 operand tiles cost against
+ * depth-64 ones.  `sink` (device, one uint32) is never written in practice; *bytes (host, may be
+ * NULL) receives the bytes requested by the launch.  n_blocks <= 65536, iters in [1, 2^20].    */
+int mgb_fetch_rate_enqueue(void* stream, const void* src, uint64_t footprint_bytes, uint32_t row_bytes,
+                           uint32_t pitch, uint32_t n_blocks, uint32_t iters, uint32_t* sink, double* bytes);
+
+/* Diagnostic: the rate at which the waves of a CU read 16-byte matrix fragments from LDS (32 rows
+ * of 128 bytes per half-wave), with the chunk swizzle of the conv kernels (swizzled != 0) or
+ * without (bank conflicts).  n_blocks workgroups of four waves, iters rounds of 8 reads per lane;
+ * *bytes (host, may be NULL) receives the bytes read.  n_blocks <= 65536, iters in [1, 2^24].  */
+int mgb_lds_read_rate_enqueue(void* stream, uint32_t swizzled, uint32_t n_blocks, uint32_t iters, uint32_t* sink,
+                              double* bytes);
+
 #ifdef __cplusplus
 }
 #endif

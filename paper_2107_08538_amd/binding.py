@@ -181,6 +181,8 @@ mgb_bfs_enqueue_static = _sig("mgb_bfs_enqueue_static", C.c_int, _vp, _vp, _vp, 
 mgb_cu_trace_enqueue = _sig("mgb_cu_trace_enqueue", C.c_int, _vp, _vp, _u32)
 mgb_copy_enqueue = _sig("mgb_copy_enqueue", C.c_int, _vp, _vp, _vp, _u64)
 mgb_mfma_loop_enqueue = _sig("mgb_mfma_loop_enqueue", C.c_int, _vp, _u32, _u32, _u32, _vp, _P(C.c_double))
+mgb_fetch_rate_enqueue = _sig("mgb_fetch_rate_enqueue", C.c_int, _vp, _vp, _u64, _u32, _u32, _u32, _u32, _vp, _P(C.c_double))
+mgb_lds_read_rate_enqueue = _sig("mgb_lds_read_rate_enqueue", C.c_int, _vp, _u32, _u32, _u32, _vp, _P(C.c_double))
 
 EXPORTS = [
     "mgb_device_desc_default", "mgb_sched_create", "mgb_sched_destroy", "mgb_task_probe",
@@ -195,7 +197,7 @@ EXPORTS = [
     "mgb_jacobi_probe", "mgb_jacobi_enqueue", "mgb_jacobi_launch_count", "mgb_gemm_f32_probe", "mgb_gemm_f32_enqueue",
     "mgb_gemm_bf16_probe", "mgb_gemm_bf16_enqueue", "mgb_conv3x3_probe", "mgb_conv3x3_enqueue",
     "mgb_cnn_probe", "mgb_cnn_enqueue", "mgb_bfs_work_bytes", "mgb_bfs_probe", "mgb_bfs_enqueue", "mgb_bfs_directed_enqueue", "mgb_bfs_enqueue_static",
-    "mgb_cu_trace_enqueue", "mgb_copy_enqueue", "mgb_mfma_loop_enqueue", "mgb_jacobi_residency",
+    "mgb_cu_trace_enqueue", "mgb_copy_enqueue", "mgb_mfma_loop_enqueue", "mgb_fetch_rate_enqueue", "mgb_lds_read_rate_enqueue", "mgb_jacobi_residency",
 ]
 
 

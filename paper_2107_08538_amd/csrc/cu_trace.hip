@@ -92,6 +92,58 @@ int mgb_internal_tag_partition(hipStream_t stream, uint32_t first_granule, uint3
   return mgb_check_launch("partition_tag_kernel");
 }
 
+// Rate at which a CU moves operand rows from memory into LDS with the DMA instruction the ring
+// kernels use (16 bytes per lane, 1 KiB per instruction).  Every wave walks its own sequence of
+// places through a footprint; an instruction's 64 lanes cover 1024 / row_bytes rows of row_bytes
+// bytes, `pitch` bytes apart (row_bytes = 1024: one contiguous KiB).
+__global__ __launch_bounds__(256, 2) void fetch_rate_kernel(const uint8_t* src, uint32_t* sink, uint32_t iters, uint32_t row_bytes,
+                                                            uint32_t pitch, uint32_t places, uint32_t place_bytes) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t fetch_lds[];
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)fetch_lds);
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t per_row = row_bytes / 16u;                       // lanes per row
+  const size_t lane_off = row_bytes == 1024u ? 16u * lane : (size_t)(lane / per_row) * pitch + 16u * (lane % per_row);
+  uint32_t cur = ((blockIdx.x * 4u + wave) * 2654435761u) % places;
+  for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+    for (uint32_t h = 0; h < 8u; ++h) {
+      const uint8_t* g = src + (size_t)cur * place_bytes + lane_off;
+      const uint32_t at = lds_base + (wave * 8u + h) * 1024u;
+      asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(at) : "memory", "m0");
+      cur += 7u;
+      if (cur >= places) cur -= places;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F78);                            // vmcnt(8): one round in flight behind this one
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);                              // vmcnt(0)
+  __syncthreads();
+  const uint32_t v = reinterpret_cast<const uint32_t*>(fetch_lds)[tid];
+  if (v == 0x12345678u) sink[0] = v;                               // (keeps the copies alive)
+}
+
+// Rate at which a CU's waves read 16-byte MFMA fragments from LDS: 32 rows of 128 bytes, the
+// chunk of a row XOR-swizzled as in the conv kernels (`swizzled` != 0) or not (every lane of a
+// half-wave on the same banks).
+__global__ __launch_bounds__(256, 2) void lds_read_rate_kernel(uint32_t* sink, uint32_t iters, uint32_t swizzled) {
+  __shared__ __attribute__((aligned(16))) uint32_t rows[4u * 2048u];
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  for (uint32_t i = tid; i < 4u * 2048u; i += 256u) rows[i] = i;
+  __syncthreads();
+  const uint32_t row = lane & 31u, hi = lane >> 5;
+  const uint32_t swz = swizzled ? (((row >> 1) & 3u) | (((row ^ (row >> 3)) & 1u) << 2)) : 0u;
+  const uint32_t base = wave * 8192u + row * 128u + ((hi ^ swz) << 4);
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+    for (uint32_t u = 0; u < 8u; ++u)
+      acc ^= *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint8_t*>(rows) + (base ^ ((u & 3u) << 5)));
+    asm volatile("" : "+v"(acc) : : "memory");
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345678u) sink[0] = acc.x;
+}
+
 extern "C" int mgb_mfma_loop_enqueue(void* stream, uint32_t bf16, uint32_t n_blocks, uint32_t iters,
                                      float* out, double* flops) {
   if (!out || n_blocks == 0u || n_blocks > 65536u || iters == 0u || iters > (1u << 24)) return MGB_E_INVAL;
@@ -117,4 +169,34 @@ extern "C" int mgb_copy_enqueue(void* stream, void* dst, const void* src, uint64
   hipLaunchKernelGGL(stream_copy_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream,
                      (uint4*)dst, (const uint4*)src, n16);
   return mgb_check_launch("stream_copy_kernel");
+}
+
+extern "C" int mgb_fetch_rate_enqueue(void* stream, const void* src, uint64_t footprint_bytes, uint32_t row_bytes,
+                                      uint32_t pitch, uint32_t n_blocks, uint32_t iters, uint32_t* sink, double* bytes) {
+  if (!src || !sink || n_blocks == 0u || n_blocks > 65536u || iters == 0u || iters > (1u << 20)) return MGB_E_INVAL;
+  if (row_bytes != 64u && row_bytes != 128u && row_bytes != 1024u) return MGB_E_INVAL;
+  if ((uintptr_t)src & 15u) return MGB_E_INVAL;
+  if (row_bytes != 1024u && (pitch < row_bytes || (pitch & 15u))) return MGB_E_INVAL;
+  // what one instruction spans, and the granularity of a wave's places
+  const uint64_t span = row_bytes == 1024u ? 1024u : (uint64_t)(1024u / row_bytes) * pitch;
+  const uint32_t place_bytes = row_bytes == 1024u || pitch == row_bytes ? 1024u : row_bytes;
+  if (footprint_bytes < span + place_bytes || (footprint_bytes - span) / place_bytes > 0xffffffffull) return MGB_E_INVAL;
+  const uint32_t places = (uint32_t)((footprint_bytes - span) / place_bytes);
+  static hipError_t attr = hipFuncSetAttribute((const void*)fetch_rate_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 32768);
+  if (attr != hipSuccess) {
+    mgb_internal_set_error("fetch_rate_kernel: dynamic LDS size", attr);
+    return MGB_E_BACKEND;
+  }
+  if (bytes) *bytes = (double)n_blocks * 4.0 * (double)iters * 8.0 * 1024.0;
+  hipLaunchKernelGGL(fetch_rate_kernel, dim3(n_blocks), dim3(256), 32768, (hipStream_t)stream, (const uint8_t*)src, sink, iters,
+                     row_bytes, pitch, places, place_bytes);
+  return mgb_check_launch("fetch_rate_kernel");
+}
+
+extern "C" int mgb_lds_read_rate_enqueue(void* stream, uint32_t swizzled, uint32_t n_blocks, uint32_t iters, uint32_t* sink,
+                                         double* bytes) {
+  if (!sink || n_blocks == 0u || n_blocks > 65536u || iters == 0u || iters > (1u << 24)) return MGB_E_INVAL;
+  if (bytes) *bytes = (double)n_blocks * 256.0 * (double)iters * 8.0 * 16.0;
+  hipLaunchKernelGGL(lds_read_rate_kernel, dim3(n_blocks), dim3(256), 0, (hipStream_t)stream, sink, iters, swizzled);
+  return mgb_check_launch("lds_read_rate_kernel");
 }

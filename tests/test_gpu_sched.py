@@ -264,3 +264,41 @@ def test_mfma_loop_diagnostic_sums_what_its_operands_give(bf16):
     assert mgb.mgb_mfma_loop_enqueue(st, bf16, 0, iters, P(out), None) == mgb.MGB_E_INVAL
     assert mgb.mgb_mfma_loop_enqueue(st, bf16, n_blocks, 0, P(out), None) == mgb.MGB_E_INVAL
     assert mgb.mgb_mfma_loop_enqueue(st, bf16, n_blocks, iters, None, None) == mgb.MGB_E_INVAL
+
+
+def test_fetch_and_lds_rate_diagnostics():
+    # the two rate probes behind the tile shapes of the MFMA kernels: argument checks, the byte counts
+    # they report, and the two orderings the kernels rely on (whole cache lines beat half lines out of
+    # L2; swizzled fragment reads beat reads that pile onto the same banks)
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    src = torch.zeros(4 << 20, dtype=torch.uint8, device=DEV)
+    sink = torch.zeros(1, dtype=torch.int32, device=DEV)
+    nb = C.c_double(0.0)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn):
+        assert fn() == 0, mgb.mgb_last_error()
+        e0.record()
+        assert fn() == 0
+        e1.record()
+        torch.cuda.synchronize()
+        return nb.value / e0.elapsed_time(e1)
+
+    fetch = lambda row: mgb.mgb_fetch_rate_enqueue(st, P(src), 2 << 20, row, 8192, 512, 200, P(sink), C.byref(nb))
+    half, whole = timed(lambda: fetch(64)), timed(lambda: fetch(128))
+    assert nb.value == 512 * 4 * 200 * 8 * 1024
+    assert whole > 1.4 * half
+    timed(lambda: fetch(1024))
+    lds = lambda swz: mgb.mgb_lds_read_rate_enqueue(st, swz, 512, 500, P(sink), C.byref(nb))
+    good, bad = timed(lambda: lds(1)), timed(lambda: lds(0))
+    assert nb.value == 512 * 256 * 500 * 8 * 16
+    assert good > 2 * bad
+    assert int(sink.item()) == 0
+    inval = mgb.MGB_E_INVAL
+    assert mgb.mgb_fetch_rate_enqueue(st, P(src), 2 << 20, 96, 8192, 512, 10, P(sink), None) == inval      # row size
+    assert mgb.mgb_fetch_rate_enqueue(st, P(src), 2 << 20, 64, 40, 512, 10, P(sink), None) == inval        # pitch below the row
+    assert mgb.mgb_fetch_rate_enqueue(st, P(src), 1024, 128, 8192, 512, 10, P(sink), None) == inval        # footprint below one instruction's span
+    assert mgb.mgb_fetch_rate_enqueue(st, None, 2 << 20, 64, 8192, 512, 10, P(sink), None) == inval
+    assert mgb.mgb_fetch_rate_enqueue(st, P(src), 2 << 20, 64, 8192, 0, 10, P(sink), None) == inval
+    assert mgb.mgb_lds_read_rate_enqueue(st, 1, 512, 0, P(sink), None) == inval
+    assert mgb.mgb_lds_read_rate_enqueue(st, 1, 512, 10, None, None) == inval
