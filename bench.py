@@ -215,7 +215,7 @@ def other_mixes(mgb, harness, W, run, total_b, on_stream):
 # packed fused multiply-add as four flops per lane and clock).
 VALU_PLAIN_TFLOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 PEAKS = dict(jacobi=("alu", VALU_PLAIN_TFLOPS, "TFLOP/s"), bfs_level=("hbm", 8000.0, "GB/s"),
-             gemm_f32_dma_kernel=("mfma", 157.3, "TFLOP/s"), gemm_bf16_dma_kernel=("mfma", 2500.0, "TFLOP/s"),
+             gemm_f32_dma_kernel=("mfma", 157.3, "TFLOP/s"), gemm_bf16_dma=("mfma", 2500.0, "TFLOP/s"),
              conv_net=("mfma", 2500.0, "TFLOP/s"))
 
 

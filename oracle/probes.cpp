@@ -250,11 +250,13 @@ uint64_t orc_gemm_f32_residency(uint64_t m, uint64_t n, uint64_t k) {
   }
   return 32 / 8;
 }
-//   bf16 GEMM: ring of (tile_m + tile_n) x 32 bf16 x 4 stages; the 256 x 256 kernel also needs all
+//   bf16 GEMM: ring of (tile_m + tile_n) x 32 bf16 x 4 stages, or (k % 64 == 0) three stages of
+//   tile_m x 64 for A beside the four of 32 x tile_n for B; the 256 x 256 kernel also needs all
 //   512 registers of a lane; the register-staged kernel 207 registers (2 waves per SIMD, 4-wave groups).
 uint64_t orc_gemm_bf16_residency(uint64_t m, uint64_t n, uint64_t k) {
   if (k % 32 == 0 && n % 8 == 0) {
     uint64_t tile = ceil_div(m, 256) * ceil_div(n, 256) < 128 ? 128 : 256;
+    if (k % 64 == 0) return (160 * 1024) / (3 * tile * 64 * 2 + 4 * tile * 32 * 2);   // A: three stages 64 deep
     return (160 * 1024) / (4 * (tile + tile) * 32 * 2);
   }
   return 2;

@@ -1,7 +1,11 @@
 // bf16 GEMM C(fp32) = A(bf16) * B(bf16), all row-major, fp32 accumulation on
 // the bf16 matrix cores (v_mfma_f32_32x32x16_bf16).
 //
-// Two kernels.
+// Three kernels.
+//
+// gemm_bf16_dma_a64_kernel (k % 64 == 0, n % 8 == 0, 16-byte aligned operands): the kernel
+// described next, with A fetched in pieces of depth 64 (whole cache lines per row) into a ring of
+// its own; see the comment at the kernel.
 //
 // gemm_bf16_dma_kernel (k % 32 == 0, n % 8 == 0, 16-byte aligned operands): one
 // workgroup of 4 waves owns a 256 x 256 tile of C, each wave a 128 x 128 piece
@@ -367,6 +371,202 @@ __global__ __launch_bounds__(GD_THREADS, WT == 4u ? 1 : 2) void gemm_bf16_dma_ke
       }
 }
 
+// ---- DMA ring kernel, A fetched 64 deep (k % 64 == 0) -------------------------------------------
+// Tiles, waves, the B ring, the order of fragment reads and the MFMA / memory interleave are those
+// of gemm_bf16_dma_kernel.  What differs is how A travels.  A row of a depth-32 tile is 64 bytes,
+// half a cache line, and a request for half a line costs the L2 -> CU path as much as one for a
+// whole line (measured: 64-byte rows arrive at half the rate of 128-byte rows), so A took two
+// thirds of the kernel's fetch time.  Here A is fetched in pieces of depth 64: rows of 128 bytes,
+// 8 chunks, swizzled by row_swz8 through the lane's choice of source chunk, into a ring of its own
+// with GA_NA = 3 stages; one A stage serves two consecutive tiles of B, which keeps its ring of
+// four depth-32 stages (rows of 2 BN bytes are whole lines already).  LDS: 3 x 32 KiB + 4 x 16 KiB
+// = 160 KiB for 256 x 256 tiles, all a CU has; half of that per workgroup for 128 x 128 tiles.
+//
+// Order of DMA issue per wave (ND = WT instructions per item; A(u) = columns 64 u .. 64 u + 63 of
+// the A tile in two halves of ND instructions, B(t) = rows 32 t .. 32 t + 31 of the B tile):
+//   A(0) B(0) B(1) A(1) B(2) A(2)h0 | B(3) A(2)h1 | B(4) A(3)h0 | B(5) A(3)h1 | ...
+// one `|` per loop iteration.  Iteration t needs tile t + 1 = B(t + 1) and A((t + 1) / 2) at its
+// barrier; 4 ND instructions follow B(t + 1) in this order and A((t + 1) / 2) precedes it, so
+// "at most 4 ND outstanding" says both have landed.  A(u + 3) goes into the stage of A(u), which
+// the barrier of iteration 2 u + 1 frees (every wave has then issued its last reads of it).
+constexpr uint32_t GA_NA = 3;
+constexpr uint32_t ga_lds_bytes(uint32_t wt) { return GA_NA * (64u * wt * 128u) + GD_NST * (GD_BK * 64u * wt * 2u); }
+
+// chunk swizzle of an unpadded 128-byte LDS row (8 chunks): 16 consecutive rows read at one logical
+// chunk fall into 16 different 16-byte slots of a 256-byte bank sweep
+__device__ __forceinline__ uint32_t row_swz8(uint32_t row) {
+  return ((row >> 1) & 3u) | (((row ^ (row >> 3)) & 1u) << 2);
+}
+
+template <uint32_t WT>
+__global__ __launch_bounds__(GD_THREADS, WT == 4u ? 1 : 2) void gemm_bf16_dma_a64_kernel(const uint16_t* __restrict__ A,
+                                                                                       const uint16_t* __restrict__ B,
+                                                                                       float* __restrict__ C, uint32_t M,
+                                                                                       uint32_t N, uint32_t K,
+                                                                                       uint32_t tiles_n,
+                                                                                       uint32_t tiles_total) {
+  constexpr uint32_t BM = 64u * WT, BN = 64u * WT;
+  constexpr uint32_t A_BYTES = BM * 128u;                      // one A stage: BM rows of depth 64
+  constexpr uint32_t B_BYTES = GD_BK * BN * 2u;                // one B stage: 32 k rows
+  constexpr uint32_t B_BASE = GA_NA * A_BYTES;
+  constexpr uint32_t ND = WT;                                  // DMA instructions per wave: B tile, half an A stage
+  constexpr uint32_t B_ROW = BN * 2u, B_CPR = BN / 8u;
+  constexpr uint32_t NF = 3u * WT, NM = WT * WT;
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+  const uint32_t per_xcd = (tiles_total + 7u) / 8u;
+  const uint32_t seq = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per_xcd || seq >= tiles_total) return;
+  const uint32_t tiles_m = tiles_total / tiles_n;
+  const uint32_t band = seq / (GD_BAND * tiles_n);
+  const uint32_t band_rows = min(GD_BAND, tiles_m - GD_BAND * band);
+  const uint32_t in_band = seq - band * GD_BAND * tiles_n;
+  const uint32_t bm = (GD_BAND * band + in_band % band_rows) * BM;
+  const uint32_t bn = (in_band / band_rows) * BN;
+
+  const uint32_t lds_base = lds_address_of(smem);
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t wm = (wave >> 1) * (32u * WT), wn = (wave & 1u) * (32u * WT);
+  const uint32_t l32 = lane & 31u, lhi = lane >> 5;
+  const uint32_t tq = lane >> 4, ts = lane & 15u;
+  const uint32_t tr_row = 8u * (tq >> 1) + (ts >> 2);
+  const uint32_t tr_col = 16u * (tq & 1u) + 4u * (ts & 3u);
+
+  // DMA roles.  A: wave w, instruction g (0 .. 2 ND - 1) fills the 1 KiB block b = 2 ND w + g of an
+  // A stage = rows 8 b .. 8 b + 7 (128 bytes each); lane -> row 8 b + lane / 8, LDS chunk lane % 8.
+  // B: as in gemm_bf16_dma_kernel.  Rows beyond M and column chunks beyond N are clamped.
+  const uint16_t* ga[2u * ND];
+  const uint16_t* gb[ND];
+#pragma unroll
+  for (uint32_t g = 0; g < 2u * ND; ++g) {
+    const uint32_t ar = 8u * (2u * ND * wave + g) + (lane >> 3);
+    ga[g] = A + (size_t)min(bm + ar, M - 1u) * K + 8u * ((lane & 7u) ^ row_swz8(ar));
+  }
+#pragma unroll
+  for (uint32_t h = 0; h < ND; ++h) {
+    const uint32_t b = ND * wave + h;
+    const uint32_t bk = (1024u / B_ROW) * b + lane / B_CPR;
+    gb[h] = B + (size_t)bk * N + min(bn + 8u * ((lane % B_CPR) ^ b_swz(bk)), N - 8u);
+  }
+
+  f32x16 acc[WT][WT];
+#pragma unroll
+  for (uint32_t i = 0; i < WT; ++i)
+#pragma unroll
+    for (uint32_t j = 0; j < WT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // fragment addresses: A inside an A stage for the four 16-wide k quarters of its 64, B inside a
+  // B stage for the two halves of its 32
+  uint32_t a_off[4][WT], b_lo[2][WT], b_hi[2][WT];
+  auto b_off = [&](uint32_t krow, uint32_t col) -> uint32_t {
+    return krow * B_ROW + (((col >> 3) ^ b_swz(krow)) << 4) + (col & 7u) * 2u;
+  };
+#pragma unroll
+  for (uint32_t i = 0; i < WT; ++i) {
+    const uint32_t row = wm + 32u * i + l32;
+#pragma unroll
+    for (uint32_t s4 = 0; s4 < 4u; ++s4) a_off[s4][i] = row * 128u + (((2u * s4 + lhi) ^ row_swz8(row)) << 4);
+  }
+#pragma unroll
+  for (uint32_t s = 0; s < 2; ++s)
+#pragma unroll
+    for (uint32_t j = 0; j < WT; ++j) {
+      b_lo[s][j] = b_off(16u * s + tr_row, wn + 32u * j + tr_col);
+      b_hi[s][j] = b_off(16u * s + 4u + tr_row, wn + 32u * j + tr_col);
+    }
+
+  u32x4 fa[2][WT];
+  s16x4 blo[2][WT], bhi[2][WT];
+  const uint32_t nk = K / GD_BK, nk2 = K / 64u;
+  // one fragment read, in the order of gemm_bf16_dma_kernel: a0, b0 lo, b0 hi, b1 lo, .., a1, a2, ..
+  auto frag_load = [&](const uint8_t* ast, uint32_t s4, const uint8_t* bst, uint32_t s, uint32_t slot, uint32_t q) {
+    if (q == 0u || q > 2u * WT) {
+      const uint32_t i = q == 0u ? 0u : q - 2u * WT;
+      fa[slot][i] = *reinterpret_cast<const u32x4*>(ast + a_off[s4][i]);
+    } else {
+      const uint32_t j = (q - 1u) >> 1;
+      if ((q - 1u) & 1u) bhi[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(bst + b_hi[s][j]));
+      else blo[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(bst + b_lo[s][j]));
+    }
+  };
+  // tile / stage indices beyond the end are clamped: every iteration issues the same number of
+  // loads (the vmcnt arithmetic relies on it), the redundant ones land in stages nobody reads again
+  auto dma_b = [&](uint32_t t, uint32_t h) {
+    dma16(gb[h] + (size_t)min(t, nk - 1u) * GD_BK * N, lds_base + B_BASE + (t % GD_NST) * B_BYTES + (ND * wave + h) * 1024u);
+  };
+  auto dma_a = [&](uint32_t u, uint32_t stage_off, uint32_t g) {
+    dma16(ga[g] + (size_t)min(u, nk2 - 1u) * 64u, lds_base + stage_off + (2u * ND * wave + g) * 1024u);
+  };
+  // NM MFMAs on fragment slot `slot`; between them the NF fragment reads of the next half tile into
+  // the other slot (A quarter s4 of the stage at ast, B half s of the stage at bst), then ND DMA
+  // instructions dma(0 .. ND - 1)
+  auto block = [&](uint32_t slot, const uint8_t* ast, uint32_t s4, const uint8_t* bst, uint32_t s, auto&& dma) {
+#pragma unroll
+    for (uint32_t m = 0; m < NM; ++m) {
+      const uint32_t i = m / WT, j = m % WT;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fa[slot][i]), join_bf16x8(blo[slot][j], bhi[slot][j]),
+                                                          acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (uint32_t x = m * (NF + ND) / NM; x < (m + 1u) * (NF + ND) / NM; ++x) {
+        if (x < NF) frag_load(ast, s4, bst, s, slot ^ 1u, x);
+        else dma(x - NF);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto b_stage = [&](uint32_t t) -> const uint8_t* { return smem + B_BASE + (t % GD_NST) * B_BYTES; };
+
+#pragma unroll
+  for (uint32_t g = 0; g < 2u * ND; ++g) dma_a(0u, 0u, g);
+#pragma unroll
+  for (uint32_t h = 0; h < ND; ++h) dma_b(0u, h);
+#pragma unroll
+  for (uint32_t h = 0; h < ND; ++h) dma_b(1u, h);
+#pragma unroll
+  for (uint32_t g = 0; g < 2u * ND; ++g) dma_a(1u, A_BYTES, g);
+#pragma unroll
+  for (uint32_t h = 0; h < ND; ++h) dma_b(2u, h);
+#pragma unroll
+  for (uint32_t g = 0; g < ND; ++g) dma_a(2u, 2u * A_BYTES, g);
+  __builtin_amdgcn_s_waitcnt(vm_wait(5u * ND));            // this wave's part of A(0) and B(0) has landed
+  __syncthreads();
+#pragma unroll
+  for (uint32_t q = 0; q < NF; ++q) frag_load(smem, 0u, b_stage(0u), 0u, 0u, q);
+  // sa0, sa1, sa2: stages of A(u), A(u + 1), A(u + 2)
+  uint32_t sa0 = 0u, sa1 = A_BYTES, sa2 = 2u * A_BYTES;
+  for (uint32_t u = 0; u < nk2; ++u) {
+    const uint32_t kt = 2u * u;
+    block(0u, smem + sa0, 1u, b_stage(kt), 1u, [&](uint32_t x) { dma_b(kt + 3u, x); });
+    __builtin_amdgcn_s_waitcnt(vm_wait(4u * ND));          // tile kt + 1 has landed (this wave's part)
+    __syncthreads();                                       // ... everybody's; all reads of B(kt) are issued
+    block(1u, smem + sa0, 2u, b_stage(kt + 1u), 0u, [&](uint32_t x) { dma_a(u + 2u, sa2, ND + x); });
+    block(0u, smem + sa0, 3u, b_stage(kt + 1u), 1u, [&](uint32_t x) { dma_b(kt + 4u, x); });
+    __builtin_amdgcn_s_waitcnt(vm_wait(4u * ND));
+    __syncthreads();                                       // all reads of B(kt + 1) and of A(u) are issued
+    block(1u, smem + sa1, 0u, b_stage(kt + 2u), 0u, [&](uint32_t x) { dma_a(u + 3u, sa0, x); });
+    const uint32_t freed = sa0;
+    sa0 = sa1;
+    sa1 = sa2;
+    sa2 = freed;
+  }
+  __builtin_amdgcn_s_waitcnt(vm_wait(0));                  // no DMA may be in flight when the LDS is given back
+
+#pragma unroll
+  for (uint32_t i = 0; i < WT; ++i)
+#pragma unroll
+    for (uint32_t j = 0; j < WT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t row = bm + wm + 32u * i + 8u * (r >> 2) + 4u * lhi + (r & 3);
+        const uint32_t col = bn + wn + 32u * j + l32;
+        if (row < M && col < N) C[(size_t)row * N + col] = acc[i][j][r];
+      }
+}
+
 struct Geometry {
   uint32_t tiles_m, tiles_n, total, blocks;
   bool dma;        // shape fits the DMA kernel (operand alignment is checked at enqueue)
@@ -426,8 +626,9 @@ int mgb_gemm_bf16_probe(uint32_t m, uint32_t n, uint32_t k, uint64_t* mem_bytes,
 uint32_t mgb_gemm_bf16_residency(uint32_t m, uint32_t n, uint32_t k) {
   if (!shape_ok(m, n, k)) return 0u;
   const Geometry g = geometry(m, n, k);
-  // 256 x 256 tiles: 512 registers per lane and a 128 KiB ring, one workgroup per CU; 128 x 128: a
-  // 64 KiB ring; the register-staged kernel: 207 registers per lane, two waves per SIMD
+  // 256 x 256 tiles: 512 registers per lane and rings of 128 KiB (160 KiB when A travels 64 deep),
+  // one workgroup per CU; 128 x 128: 64 KiB (80 KiB); the register-staged kernel: 207 registers
+  // per lane, two waves per SIMD
   return g.dma ? (g.wt == 4u ? 1u : 2u) : 2u;
 }
 
@@ -451,6 +652,29 @@ int mgb_gemm_bf16_enqueue(void* stream, const uint16_t* A, const uint16_t* B, fl
     if (attr != hipSuccess) {
       mgb_internal_set_error("gemm_bf16_dma_kernel: dynamic LDS size", attr);
       return MGB_E_BACKEND;
+    }
+    if (k % 64u == 0u) {
+      // A fetched 64 deep: whole cache lines per row
+      static std::once_flag once64;
+      static hipError_t attr64 = hipSuccess;
+      std::call_once(once64, [] {
+        attr64 = hipFuncSetAttribute((const void*)gemm_bf16_dma_a64_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)ga_lds_bytes(4));
+        if (attr64 == hipSuccess)
+          attr64 = hipFuncSetAttribute((const void*)gemm_bf16_dma_a64_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)ga_lds_bytes(2));
+      });
+      if (attr64 != hipSuccess) {
+        mgb_internal_set_error("gemm_bf16_dma_a64_kernel: dynamic LDS size", attr64);
+        return MGB_E_BACKEND;
+      }
+      if (g.wt == 4u)
+        hipLaunchKernelGGL(gemm_bf16_dma_a64_kernel<4>, dim3(g.blocks), dim3(GD_THREADS), ga_lds_bytes(4), st, A, B, C,
+                           m, n, k, g.tiles_n, g.total);
+      else
+        hipLaunchKernelGGL(gemm_bf16_dma_a64_kernel<2>, dim3(g.blocks), dim3(GD_THREADS), ga_lds_bytes(2), st, A, B, C,
+                           m, n, k, g.tiles_n, g.total);
+      return mgb_check_launch("gemm_bf16_dma_a64_kernel");
     }
     if (g.wt == 4u)
       hipLaunchKernelGGL(gemm_bf16_dma_kernel<4>, dim3(g.blocks), dim3(GD_THREADS), gd_lds_bytes(4), st, A, B, C, m,

@@ -25,7 +25,8 @@ class Task:
         self.mem, self.grid, self.block = probe
         self.enqueue = enqueue          # fn(stream) -> status
         self.kernel_name = kernel_name  # label of the task's kernels in reports: "jacobi" (the fused-sweep kernels of
-                                        # jacobi.hip), "conv_net" (the layer launches of a net), else the kernel itself
+                                        # jacobi.hip), "conv_net" (the layer launches of a net), "gemm_bf16_dma" (the
+                                        # two DMA-ring kernels of gemm_bf16.hip), else the kernel itself
         self.launches = launches        # kernel launches per task (None if data dependent)
         self.alg_bytes = alg_bytes      # algorithmic HBM bytes of the whole task
         self.alg_flops = alg_flops
@@ -65,7 +66,7 @@ def build_task(spec, data, device="cuda:0"):
         Cc = torch.zeros(m, n, device=device)
         probe = mgb.probe_of(mgb.mgb_gemm_bf16_probe, m, n, kk)
         fn = lambda st: mgb.mgb_gemm_bf16_enqueue(st, _ptr(A), _ptr(B), _ptr(Cc), m, n, kk)
-        t = Task(spec, dict(A=A, B=B, C=Cc), probe, fn, "gemm_bf16_dma_kernel", 1,
+        t = Task(spec, dict(A=A, B=B, C=Cc), probe, fn, "gemm_bf16_dma", 1,
                  alg_bytes=2.0 * (m * kk + kk * n) + 4.0 * m * n, alg_flops=2.0 * m * n * kk,
                  wg_per_cu=int(mgb.mgb_gemm_bf16_residency(m, n, kk)))
         t.native = (mgb.MGB_TASK_GEMM_BF16, [A, B, Cc], [m, n, kk], 0, None, None)

@@ -211,7 +211,11 @@ def run_gemm_bf16(ab, bb):
                                    (1, 8, 32), (256, 8, 64), (300, 520, 64), (513, 264, 2048),
                                    (1024, 1024, 32), (768, 512, 96), (2000, 1096, 1056),
                                    # at least 128 tiles of 256 x 256: the big-tile variant (the others above take 128 x 128)
-                                   (2816, 2824, 64), (3000, 2816, 96)])
+                                   (2816, 2824, 64), (3000, 2816, 96),
+                                   # k % 64 == 0: A travels 64 deep through a ring of three stages; fewer pieces
+                                   # than stages, as many, more, ragged rows / columns, both tile sizes
+                                   (256, 264, 128), (260, 256, 192), (520, 392, 704), (1000, 1032, 1088),
+                                   (2830, 2816, 448), (2816, 2832, 128)])
 def test_gemm_bf16_frobenius_error(m, n, k):
     ab, bb = W.gemm_operands_bf16(m + 3 * k, m, n, k)
     got = run_gemm_bf16(ab, bb)
@@ -232,12 +236,13 @@ def test_gemm_bf16_unaligned_operands_take_the_staged_kernel():
     assert frobenius_rel(Cd.cpu().numpy(), oracle.gemm_bf16(ab, bb)) <= 1e-5
 
 
-def test_gemm_bf16_layout_exact_small_integers():
+@pytest.mark.parametrize("k", [160, 448])           # depth-32 ring for both operands; A 64 deep
+def test_gemm_bf16_layout_exact_small_integers(k):
     # small integers are exact in bf16 and their dot products exact in fp32: any operand
     # layout mistake shows as a wrong integer
     rng = np.random.default_rng(2)
-    a = rng.integers(-4, 5, (256, 160)).astype(np.float32)
-    b = rng.integers(-4, 5, (160, 384)).astype(np.float32)
+    a = rng.integers(-4, 5, (256, k)).astype(np.float32)
+    b = rng.integers(-4, 5, (k, 384)).astype(np.float32)
     got = run_gemm_bf16(W.f32_to_bf16_bits(a), W.f32_to_bf16_bits(b))
     assert np.array_equal(got, a @ b)
 

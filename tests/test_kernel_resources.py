@@ -95,15 +95,19 @@ def test_fp32_gemm_variants(reports):
 def test_bf16_gemm_variants(reports):
     lib = oracle.lib()
     lib.orc_gemm_bf16_residency.restype = C.c_uint64
-    cases = [((4096, 4096, 4096), _kernel(reports, "gemm_bf16_dma_kernel", "ILj4E"), 4, ring(512, 32, 2)),
-             ((1024, 1024, 1024), _kernel(reports, "gemm_bf16_dma_kernel", "ILj2E"), 4, ring(256, 32, 2)),
+    def a64(tile):                                              # A: three stages 64 deep; B: four stages 32 deep
+        return 3 * tile * 64 * 2 + 4 * 32 * tile * 2
+    cases = [((4096, 4096, 4064), _kernel(reports, "gemm_bf16_dma_kernel", "ILj4E"), 4, ring(512, 32, 2)),
+             ((1024, 1024, 992), _kernel(reports, "gemm_bf16_dma_kernel", "ILj2E"), 4, ring(256, 32, 2)),
+             ((4096, 4096, 4096), _kernel(reports, "gemm_bf16_dma_a64_kernel", "ILj4E"), 4, a64(256)),
+             ((1024, 1024, 1024), _kernel(reports, "gemm_bf16_dma_a64_kernel", "ILj2E"), 4, a64(128)),
              ((129, 257, 17), _kernel(reports, "gemm_bf16_kernel", "ILb0E"), 4, 0)]
     want = []
     for shape, rep, waves, ring_bytes in cases:
         w = wg_per_cu(rep, waves, ring_bytes)
         want.append(w)
         assert mgb.mgb_gemm_bf16_residency(*shape) == w == lib.orc_gemm_bf16_residency(*[U(x) for x in shape]), (shape, rep)
-    assert want == [1, 2, 2]
+    assert want == [1, 2, 1, 2, 2]
 
 
 def test_conv_variants(reports):
