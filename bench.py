@@ -29,6 +29,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip serialised / alone / batch comparisons")
     ap.add_argument("--no-other-mixes", action="store_true", help="skip the batch legs of CNN-8, Mixed-128 and the memory-tight mix")
+    ap.add_argument("--vendor-libraries", action="store_true",
+                    help="also time the same GEMMs and the conv chain through the vendor libraries torch calls "
+                         "(rocBLAS / hipBLASLt, MIOpen) on this box and report them beside this library's kernels")
     ap.add_argument("--dump-records", default=None, help="write the last timed pass's task records (JSON) to this path")
     ap.add_argument("--seed", type=int, default=None)
     return ap.parse_args()
@@ -217,6 +220,92 @@ VALU_PLAIN_TFLOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 PEAKS = dict(jacobi=("alu", VALU_PLAIN_TFLOPS, "TFLOP/s"), bfs_level=("hbm", 8000.0, "GB/s"),
              gemm_f32_dma_kernel=("mfma", 157.3, "TFLOP/s"), gemm_bf16_dma=("mfma", 2500.0, "TFLOP/s"),
              conv_net=("mfma", 2500.0, "TFLOP/s"))
+
+
+def vendor_libraries(torch, mgb, W, log):
+    """The task kernels against the vendor libraries on the same box and the same shapes, back to back on
+    one stream: fp32 and bf16 GEMM through torch.matmul (rocBLAS / hipBLASLt), the ten-layer conv chain through
+    torch's conv2d + relu per layer (MIOpen, channels-last bf16).  Context for the kernel figures, not a part of
+    the metric; the libraries' first calls (kernel selection) are outside the timed regions."""
+    import ctypes as C
+    import torch.nn.functional as F
+    dev = "cuda:0"
+    cs = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    P = lambda t: C.c_void_p(t.data_ptr())
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def ms_of(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(3):
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) / reps)
+        return best
+
+    res = {}
+    torch.backends.cuda.matmul.allow_tf32 = False
+    for n in (4096, 8192):
+        reps = 20 if n == 4096 else 4
+        a, b = torch.randn(n, n, device=dev), torch.randn(n, n, device=dev)
+        c = torch.empty(n, n, device=dev)
+        ours = ms_of(lambda: mgb.check(mgb.mgb_gemm_f32_enqueue(cs, P(a), P(b), P(c), n, n, n), "gemm_f32"), reps)
+        lib = ms_of(lambda: torch.matmul(a, b, out=c), reps)
+        res["gemm_f32_%d" % n] = dict(unit="TFLOP/s", this_library=round(2.0 * n ** 3 / ours / 1e9, 1),
+                                      torch_matmul=round(2.0 * n ** 3 / lib / 1e9, 1))
+        ah, bh = a.bfloat16(), b.bfloat16()
+        a16, b16 = ah.view(torch.int16), bh.view(torch.int16)
+        ours = ms_of(lambda: mgb.check(mgb.mgb_gemm_bf16_enqueue(cs, P(a16), P(b16), P(c), n, n, n), "gemm_bf16"), reps * 4)
+        ch = torch.empty(n, n, device=dev, dtype=torch.bfloat16)
+        lib = ms_of(lambda: torch.matmul(ah, bh, out=ch), reps * 4)     # writes bf16, half the output bytes of ours
+        res["gemm_bf16_%d" % n] = dict(unit="TFLOP/s", this_library=round(2.0 * n ** 3 / ours / 1e9, 1),
+                                       torch_matmul_bf16_out=round(2.0 * n ** 3 / lib / 1e9, 1))
+        log("vendor libraries: GEMM %d done" % n)
+        del a, b, c, ah, bh, ch
+    layers = W.cnn_layers()
+    arr = (mgb.mgb_conv_layer * len(layers))(*[mgb.mgb_conv_layer(L["c_in"], L["c_out"], L["stride"]) for L in layers])
+    wbits = W.cnn_weights(7, layers)
+    for batch in (8, 1):
+        mem, act, ob = C.c_uint64(), C.c_uint64(), C.c_uint64()
+        g, blk = mgb.mgb_dim3(), mgb.mgb_dim3()
+        mgb.check(mgb.mgb_cnn_probe(arr, len(layers), batch, 416, 416, C.byref(mem), C.byref(act), C.byref(ob),
+                                    C.byref(g), C.byref(blk)), "mgb_cnn_probe")
+        X = torch.from_numpy(W.cnn_input(7, batch).view("int16")).to(dev)
+        Wd = [torch.from_numpy(x.view("int16")).to(dev) for x in wbits]
+        ptrs = (C.c_void_p * len(Wd))(*[t.data_ptr() for t in Wd])
+        a0 = torch.zeros(act.value // 2, dtype=torch.int16, device=dev)
+        a1 = torch.zeros(act.value // 2, dtype=torch.int16, device=dev)
+        out = torch.zeros(ob.value // 4, dtype=torch.float32, device=dev)
+        ours = ms_of(lambda: mgb.check(mgb.mgb_cnn_enqueue(cs, arr, len(layers), P(X), ptrs, P(a0), P(a1), P(out),
+                                                           batch, 416, 416), "mgb_cnn_enqueue"), 20)
+        # the same tensors as torch sees them: NHWC activations = channels-last NCHW, KRSC filters = channels-last KCRS
+        xt = X.view(torch.bfloat16).view(batch, 416, 416, 3).permute(0, 3, 1, 2)
+        wt = [t.view(torch.bfloat16).view(L["c_out"], 3, 3, L["c_in"]).permute(0, 3, 1, 2) for t, L in zip(Wd, layers)]
+
+        def chain():
+            y = xt
+            for wl, L in zip(wt, layers):
+                y = F.relu(F.conv2d(y, wl, stride=L["stride"], padding=1))
+            return y
+        t0 = time.perf_counter()
+        y = chain()
+        torch.cuda.synchronize()
+        setup = time.perf_counter() - t0
+        ref = y.permute(0, 2, 3, 1).float().reshape(-1)
+        diff = float((out - ref).norm() / ref.norm())
+        lib = ms_of(chain, 20)
+        flops = sum(2.0 * batch * L["h_out"] * L["w_out"] * L["c_out"] * 9 * L["c_in"] for L in layers)
+        res["conv_chain_416_batch%d" % batch] = dict(unit="ms", this_library=round(ours, 4), torch_conv2d_relu=round(lib, 4),
+                                                     this_library_tflops=round(flops / ours / 1e9, 1),
+                                                     torch_tflops=round(flops / lib / 1e9, 1),
+                                                     outputs_rel_diff=round(diff, 5), torch_first_call_s=round(setup, 1))
+        log("vendor libraries: conv chain batch %d done" % batch)
+    return res
 
 
 def main():
@@ -564,6 +653,9 @@ def main():
         out["lazy_runtime"] = lazy_leg(mgb, cap)
         log("multi-process front end")
         out["ipc_front_end"] = ipc_leg(mgb)
+    if args.vendor_libraries:
+        log("vendor libraries")
+        out["vendor_libraries"] = vendor_libraries(torch, mgb, W, log)
     if not args.no_cpu_baseline:
         log("cpu baseline")
         out["cpu_baseline"] = cpu_baseline(spec)

@@ -36,6 +36,9 @@
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));      // native vector: a load through it is one 16-byte LDS read
+typedef const f32x4 __attribute__((address_space(3))) * lds_f4_ptr;
+typedef const float __attribute__((address_space(3))) * lds_f1_ptr;
 
 constexpr uint32_t GF_BM = 128, GF_BN = 128, GF_BK = 16;
 constexpr uint32_t GF_WM = GF_WAVES_M, GF_WN = 2;                  // wave grid
@@ -192,6 +195,15 @@ __global__ __launch_bounds__(GF_THREADS) void gemm_f32_kernel(const float* __res
 constexpr uint32_t FD_BK = 16, FD_NST = 4, FD_BAND = 8;
 constexpr uint32_t fd_lds_bytes(uint32_t bm, uint32_t bn) { return FD_NST * (bm + bn) * FD_BK * 4u; }
 
+// With one wave per SIMD nothing hides what a wave issues between two MFMAs, and not everything is
+// free there: a vector-ALU instruction (an address add) holds the matrix pipe up for about 14
+// clocks, a load with a 64-bit vector address for about 43, one with a 32-bit vector offset for
+// about 24, while scalar instructions and LDS reads cost nothing (measured with a loop of MFMAs
+// and one such instruction after every fourth).  So the main loop holds no vector arithmetic at
+// all: the ring is walked by unrolling the loop over its four stages, which turns every stage
+// offset into the immediate offset of the LDS read (the A ring and the B ring are 64 KiB or less
+// each, the reach of that field), and the DMA goes through buffer resources whose walk along k is
+// a scalar offset (A) or a new base (B), computed by the scalar unit.
 template <uint32_t WGM, uint32_t WGN, uint32_t TM, uint32_t TN>
 __global__ __launch_bounds__(64 * WGM * WGN, TM * TN >= 16 ? 1 : 2) void gemm_f32_dma_kernel(const float* __restrict__ A,
                                                                        const float* __restrict__ B,
@@ -200,7 +212,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, TM * TN >= 16 ? 1 : 2) void gemm_f3
                                                                        uint32_t tiles_total) {
   constexpr uint32_t NW = WGM * WGN;
   constexpr uint32_t BM = 32u * TM * WGM, BN = 32u * TN * WGN;
-  constexpr uint32_t A_BYTES = BM * 64u, B_BYTES = FD_BK * BN * 4u, STAGE = A_BYTES + B_BYTES;
+  constexpr uint32_t A_BYTES = BM * 64u, B_BYTES = FD_BK * BN * 4u;
+  constexpr uint32_t B_BASE = FD_NST * A_BYTES;      // LDS: the four A stages, then the four B stages
+  static_assert(FD_NST * A_BYTES <= 65536u && FD_NST * B_BYTES <= 65536u, "a stage offset must fit the offset field of an LDS read");
   constexpr uint32_t NDA = BM / 16u / NW, NDB = BN / 16u / NW;   // DMA instructions per wave per tile
   static_assert(NDA >= 1u && NDB >= 1u, "every wave takes part in both operand copies");
   constexpr uint32_t B_ROW = BN * 4u;                // bytes of a B k-row in LDS
@@ -229,21 +243,23 @@ __global__ __launch_bounds__(64 * WGM * WGN, TM * TN >= 16 ? 1 : 2) void gemm_f3
   // two halves of a wave (k rows s and 8 + s) read different banks
   auto b_swz = [](uint32_t k) -> uint32_t { return ((k >> 3) & 1u) << 3; };
 
-  // DMA roles: wave w, instruction h fills the 1 KiB block b = ND*w + h of an operand part.
+  // DMA roles: wave w, instruction h fills the 1 KiB block b = ND*w + h of an operand stage.
   //   A block b: rows 16b .. 16b+15 (64 bytes = 16 k each); lane -> row 16b + lane/4, chunk lane%4
   //   B block b: 1024 / B_ROW consecutive k rows;             lane -> its k row and chunk
   // Rows beyond M and column chunks beyond N are clamped: they only feed entries never stored.
-  const float* ga[NDA];
-  const float* gb[NDB];
+  // A's resource covers this workgroup's rows (at most 2^26 bytes; the scalar offset walks along
+  // k), B's is rebased for every tile to its 16 k rows (at most 2^22 bytes).
+  const buf_rsrc rsrc_a = make_buf_rsrc(A + (size_t)bm * K, min(BM, M - bm) * K * 4u);
+  uint32_t va[NDA], vb[NDB];
 #pragma unroll
   for (uint32_t h = 0; h < NDA; ++h) {
     const uint32_t ar = 16u * (NDA * wave + h) + (lane >> 2);
-    ga[h] = A + (size_t)min(bm + ar, M - 1u) * K + 4u * ((lane & 3u) ^ row_swz(ar));
+    va[h] = (min(bm + ar, M - 1u) - bm) * K * 4u + 16u * ((lane & 3u) ^ row_swz(ar));
   }
 #pragma unroll
   for (uint32_t h = 0; h < NDB; ++h) {
     const uint32_t bk = (1024u / B_ROW) * (NDB * wave + h) + lane / B_CPR;
-    gb[h] = B + (size_t)bk * N + min(bn + 4u * ((lane % B_CPR) ^ b_swz(bk)), N - 4u);
+    vb[h] = (bk * N + min(bn + 4u * ((lane % B_CPR) ^ b_swz(bk)), N - 4u)) * 4u;
   }
 
   f32x16 acc[TM][TN];
@@ -254,51 +270,60 @@ __global__ __launch_bounds__(64 * WGM * WGN, TM * TN >= 16 ? 1 : 2) void gemm_f3
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // fragment addresses inside a stage: half hf covers steps 4 hf .. 4 hf + 3
+  // LDS addresses of the fragments in stage 0 of each ring: half hf covers steps 4 hf .. 4 hf + 3.
+  // They are kept as integers and a stage is added as a constant, which the LDS read takes as its
+  // immediate offset (formed from the array's address the constant stays a vector add).
   uint32_t a_off[2][TM], b_off[2][2][TN];   // B: steps 0 and 2 of a half; steps 1 and 3 are one row further
 #pragma unroll
   for (uint32_t hf = 0; hf < 2; ++hf) {
 #pragma unroll
     for (uint32_t i = 0; i < TM; ++i) {
       const uint32_t row = wm + 32u * i + l32;
-      a_off[hf][i] = row * 64u + (((2u * lhi + hf) ^ row_swz(row)) << 4);      // k = 8 lhi + 4 hf .. + 3
+      a_off[hf][i] = lds_base + row * 64u + (((2u * lhi + hf) ^ row_swz(row)) << 4);      // k = 8 lhi + 4 hf .. + 3
     }
 #pragma unroll
     for (uint32_t s = 0; s < 2; ++s)
 #pragma unroll
       for (uint32_t j = 0; j < TN; ++j) {
         const uint32_t krow = 8u * lhi + 4u * hf + 2u * s, col = wn + 32u * j + l32;
-        b_off[hf][s][j] = A_BYTES + krow * B_ROW + (((col >> 2) ^ b_swz(krow)) << 4) + (col & 3u) * 4u;
+        b_off[hf][s][j] = lds_base + B_BASE + krow * B_ROW + (((col >> 2) ^ b_swz(krow)) << 4) + (col & 3u) * 4u;
       }
   }
 
-  float4 fa[2][TM];            // [slot][block row]: A operands of four steps
+  f32x4 fa[2][TM];             // [slot][block row]: A operands of four steps
   float fb[2][4][TN];          // [slot][step][block column]
   const uint32_t nk = K / FD_BK;
-  // one fragment read of a half tile, in the order the MFMAs need them: the A operands (one read
-  // serves four steps), then the B operands, two steps (two k rows, one two-address LDS read) at a time
-  auto frag_load = [&](const uint8_t* st, uint32_t hf, uint32_t slot, uint32_t q) {
-    if (q < TM) fa[slot][q] = *reinterpret_cast<const float4*>(st + a_off[hf][q]);
+  // one fragment read of a half tile of the tile in ring stage `st` (a constant where it is called),
+  // in the order the MFMAs need them: the A operands (one read serves four steps), then the B
+  // operands, two steps (two k rows, one two-address LDS read) at a time
+  auto frag_load = [&](uint32_t st, uint32_t hf, uint32_t slot, uint32_t q) {
+    if (q < TM) fa[slot][q] = *(lds_f4_ptr)(a_off[hf][q] + st * A_BYTES);
     else {
       // the next step's k row is the next LDS row (same swizzle: a half never crosses k = 8), a
       // constant distance away, so the pair becomes one two-address read
       const uint32_t x = q - TM, s2 = 2u * (x / TN), j = x % TN;
-      const uint8_t* p = st + b_off[hf][s2 / 2u][j];
-      fb[slot][s2][j] = *reinterpret_cast<const float*>(p);
-      fb[slot][s2 + 1u][j] = *reinterpret_cast<const float*>(p + B_ROW);
+      const uint32_t p = b_off[hf][s2 / 2u][j] + st * B_BYTES;
+      fb[slot][s2][j] = *(lds_f1_ptr)p;
+      fb[slot][s2 + 1u][j] = *(lds_f1_ptr)(p + B_ROW);
     }
   };
-  auto dma_one = [&](uint32_t kt, uint32_t part, uint32_t h) {
-    const uint32_t t = min(kt, nk - 1u);              // clamped: the schedule never changes, see the wait counts
-    const uint32_t st = lds_base + (kt % FD_NST) * STAGE;
-    if (part == 0u) dma16(ga[h] + (size_t)t * FD_BK, st + (NDA * wave + h) * 1024u);
-    else dma16(gb[h] + (size_t)t * FD_BK * N, st + A_BYTES + (NDB * wave + h) * 1024u);
+  // tile indices beyond the end are clamped: the schedule never changes (see the wait counts), the
+  // redundant loads land in stages nobody reads any more
+  const uint32_t dst_a = lds_base + NDA * wave * 1024u, dst_b = lds_base + B_BASE + NDB * wave * 1024u;
+  auto b_rsrc = [&](uint32_t kt) -> buf_rsrc {
+    const uint32_t t = min(kt, nk - 1u);
+    return make_buf_rsrc(B + (size_t)t * FD_BK * N, FD_BK * N * 4u);
   };
+  auto dma_a = [&](uint32_t kt, uint32_t st, uint32_t h) {
+    buf_dma16(va[h], rsrc_a, min(kt, nk - 1u) * (FD_BK * 4u), dst_a + st * A_BYTES + h * 1024u);
+  };
+  auto dma_b = [&](const buf_rsrc& rb, uint32_t st, uint32_t h) { buf_dma16(vb[h], rb, 0u, dst_b + st * B_BYTES + h * 1024u); };
   // NM MFMAs (4 steps) on fragment slot `slot`; spread between them: the NF fragment reads of
-  // (tile ft, half fh) into the other slot, then the DMA instructions of (tile dt, part dpart)
-  auto block = [&](uint32_t slot, uint32_t ft, uint32_t fh, uint32_t dt, uint32_t dpart) {
-    const uint8_t* fst = smem + (ft % FD_NST) * STAGE;
+  // (stage fst, half fh) into the other slot, then the DMA instructions of tile dt into stage dst
+  // (dpart 0: its A part, 1: its B part)
+  auto block = [&](uint32_t slot, uint32_t fst, uint32_t fh, uint32_t dt, uint32_t dst, uint32_t dpart) {
     const uint32_t nd = dpart == 0u ? NDA : NDB;
+    const buf_rsrc rb = b_rsrc(dt);
 #pragma unroll
     for (uint32_t m = 0; m < NM; ++m) {
       const uint32_t s = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
@@ -308,7 +333,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, TM * TN >= 16 ? 1 : 2) void gemm_f3
 #pragma unroll
       for (uint32_t x = m * (NF + nd) / NM; x < (m + 1u) * (NF + nd) / NM; ++x) {
         if (x < NF) frag_load(fst, fh, slot ^ 1u, x);
-        else dma_one(dt, dpart, x - NF);
+        else if (dpart == 0u) dma_a(dt, dst, x - NF);
+        else dma_b(rb, dst, x - NF);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -318,23 +344,30 @@ __global__ __launch_bounds__(64 * WGM * WGN, TM * TN >= 16 ? 1 : 2) void gemm_f3
 #pragma unroll
   for (uint32_t t = 0; t < FD_NST - 1u; ++t) {
 #pragma unroll
-    for (uint32_t h = 0; h < NDA; ++h) dma_one(t, 0u, h);
+    for (uint32_t h = 0; h < NDA; ++h) dma_a(t, t, h);
+    const buf_rsrc rb = b_rsrc(t);
 #pragma unroll
-    for (uint32_t h = 0; h < NDB; ++h) dma_one(t, 1u, h);
+    for (uint32_t h = 0; h < NDB; ++h) dma_b(rb, t, h);
   }
 #pragma unroll
-  for (uint32_t h = 0; h < NDA; ++h) dma_one(FD_NST - 1u, 0u, h);
+  for (uint32_t h = 0; h < NDA; ++h) dma_a(FD_NST - 1u, FD_NST - 1u, h);
   __builtin_amdgcn_s_waitcnt(vm_wait((NDA + NDB) * (FD_NST - 2u) + NDA));   // this wave's part of tile 0 has landed
   __syncthreads();
 #pragma unroll
-  for (uint32_t q = 0; q < NF; ++q) frag_load(smem, 0u, 0u, q);
-  for (uint32_t kt = 0; kt < nk; ++kt) {
-    block(0u, kt, 1u, kt + FD_NST - 1u, 1u);          // reads the second half of tile kt; B(kt + NST - 1)
-    // tile kt+1 has landed when no more than the (NDA + NDB)(NST-2) instructions issued after it
-    // are outstanding; the barrier makes that true for every wave and frees tile kt's stage
-    __builtin_amdgcn_s_waitcnt(vm_wait((NDA + NDB) * (FD_NST - 2u)));
-    __syncthreads();
-    block(1u, kt + 1u, 0u, kt + FD_NST, 0u);          // reads the first half of tile kt+1; A(kt + NST)
+  for (uint32_t q = 0; q < NF; ++q) frag_load(0u, 0u, 0u, q);
+  for (uint32_t kt0 = 0; kt0 < nk; kt0 += FD_NST) {
+#pragma unroll
+    for (uint32_t u = 0; u < FD_NST; ++u) {           // tile kt lives in stage u: every stage index below is a constant
+      const uint32_t kt = kt0 + u;
+      if (kt < nk) {
+        block(0u, u, 1u, kt + FD_NST - 1u, (u + FD_NST - 1u) % FD_NST, 1u);   // reads the second half of tile kt; B(kt + NST - 1)
+        // tile kt+1 has landed when no more than the (NDA + NDB)(NST-2) instructions issued after it
+        // are outstanding; the barrier makes that true for every wave and frees tile kt's stage
+        __builtin_amdgcn_s_waitcnt(vm_wait((NDA + NDB) * (FD_NST - 2u)));
+        __syncthreads();
+        block(1u, (u + 1u) % FD_NST, 0u, kt + FD_NST, u, 0u);                 // reads the first half of tile kt+1; A(kt + NST)
+      }
+    }
   }
   __builtin_amdgcn_s_waitcnt(vm_wait(0));             // no DMA may be in flight when the LDS is given back
 

@@ -21,6 +21,31 @@ __device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(lds_addr) : "memory", "m0");
 }
 
+// The same transfer through a buffer resource: lane address = resource base + voff + soff, where
+// soff is wave-uniform (a scalar register), so that walking along k needs no vector arithmetic.
+// It matters to a kernel that runs one wave per SIMD: every vector-ALU instruction issued between
+// two MFMAs holds the matrix pipe up for ~14 clocks and a load ~21 clocks per address register
+// (43 for a 64-bit global address, 24 here), while scalar instructions and LDS reads are free.
+// The resource is raw (stride 0) and bounds-checked by the hardware: a lane whose offset lies at
+// or beyond `bytes` receives zeros and touches no memory.  Callers keep a resource to the piece
+// one workgroup (or one tile) reads, so its size always fits 32 bits.
+typedef uint32_t buf_rsrc __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ buf_rsrc make_buf_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t b = (uint64_t)(uintptr_t)base;
+  buf_rsrc r;
+  r.x = __builtin_amdgcn_readfirstlane((uint32_t)b);
+  r.y = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));                  // stride 0 in the upper half
+  r.z = __builtin_amdgcn_readfirstlane(bytes);
+  r.w = 0x00020000u;                                                         // 32-bit data format, raw addressing
+  return r;
+}
+
+__device__ __forceinline__ void buf_dma16(uint32_t voff, buf_rsrc rsrc, uint32_t soff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tbuffer_load_dwordx4 %0, %1, %3 offen lds"
+               : : "v"(voff), "s"(rsrc), "s"(lds_addr), "s"(soff) : "memory", "m0");
+}
+
 // Chunk swizzle of an unpadded 64-byte LDS row (4 chunks of 16 bytes): physical chunk = logical
 // chunk ^ row_swz(row).  16 consecutive rows read at one logical chunk hit 16 different 16-byte
 // slots of a 256-byte bank sweep, 8 consecutive rows 8 different slots of a 128-byte sweep.
