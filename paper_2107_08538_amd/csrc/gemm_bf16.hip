@@ -398,6 +398,15 @@ __device__ __forceinline__ uint32_t row_swz8(uint32_t row) {
   return ((row >> 1) & 3u) | (((row ^ (row >> 3)) & 1u) << 2);
 }
 
+// The main loop holds no vector arithmetic and no load with a 64-bit vector address: with one wave
+// per SIMD each vector-ALU instruction between two MFMAs holds the matrix pipe up for ~14 clocks
+// (an MFMA here lasts 32) and such a load for ~17 more, while scalar instructions, LDS reads and
+// loads with a scalar base and a 32-bit vector offset cost nothing.  So the loop is unrolled over
+// twelve tiles (three A stages of two tiles, four B stages), which makes every stage offset an
+// immediate of the LDS read, and the DMA goes through buffer resources: A's walk along k is a
+// scalar offset, B's resource is rebased for every tile by the scalar unit.
+typedef const u32x4 __attribute__((address_space(3))) * lds_u32x4_ptr;
+
 template <uint32_t WT>
 __global__ __launch_bounds__(GD_THREADS, WT == 4u ? 1 : 2) void gemm_bf16_dma_a64_kernel(const uint16_t* __restrict__ A,
                                                                                        const uint16_t* __restrict__ B,
@@ -412,6 +421,7 @@ __global__ __launch_bounds__(GD_THREADS, WT == 4u ? 1 : 2) void gemm_bf16_dma_a6
   constexpr uint32_t ND = WT;                                  // DMA instructions per wave: B tile, half an A stage
   constexpr uint32_t B_ROW = BN * 2u, B_CPR = BN / 8u;
   constexpr uint32_t NF = 3u * WT, NM = WT * WT;
+  static_assert(2u * A_BYTES <= 65536u && GD_NST * B_BYTES <= 65536u, "stage offsets must fit the offset field of an LDS read");
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
   const uint32_t per_xcd = (tiles_total + 7u) / 8u;
@@ -436,18 +446,20 @@ __global__ __launch_bounds__(GD_THREADS, WT == 4u ? 1 : 2) void gemm_bf16_dma_a6
   // DMA roles.  A: wave w, instruction g (0 .. 2 ND - 1) fills the 1 KiB block b = 2 ND w + g of an
   // A stage = rows 8 b .. 8 b + 7 (128 bytes each); lane -> row 8 b + lane / 8, LDS chunk lane % 8.
   // B: as in gemm_bf16_dma_kernel.  Rows beyond M and column chunks beyond N are clamped.
-  const uint16_t* ga[2u * ND];
-  const uint16_t* gb[ND];
+  // A's resource covers this workgroup's rows (at most 2^25 bytes; the scalar offset walks along
+  // k), B's is rebased for every tile to its 32 k rows (at most 2^22 bytes).
+  const buf_rsrc rsrc_a = make_buf_rsrc(A + (size_t)bm * K, min(BM, M - bm) * K * 2u);
+  uint32_t va[2u * ND], vb[ND];
 #pragma unroll
   for (uint32_t g = 0; g < 2u * ND; ++g) {
     const uint32_t ar = 8u * (2u * ND * wave + g) + (lane >> 3);
-    ga[g] = A + (size_t)min(bm + ar, M - 1u) * K + 8u * ((lane & 7u) ^ row_swz8(ar));
+    va[g] = (min(bm + ar, M - 1u) - bm) * K * 2u + 16u * ((lane & 7u) ^ row_swz8(ar));
   }
 #pragma unroll
   for (uint32_t h = 0; h < ND; ++h) {
     const uint32_t b = ND * wave + h;
     const uint32_t bk = (1024u / B_ROW) * b + lane / B_CPR;
-    gb[h] = B + (size_t)bk * N + min(bn + 8u * ((lane % B_CPR) ^ b_swz(bk)), N - 8u);
+    vb[h] = (bk * N + min(bn + 8u * ((lane % B_CPR) ^ b_swz(bk)), N - 8u)) * 2u;
   }
 
   f32x16 acc[WT][WT];
@@ -458,17 +470,20 @@ __global__ __launch_bounds__(GD_THREADS, WT == 4u ? 1 : 2) void gemm_bf16_dma_a6
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // fragment addresses: A inside an A stage for the four 16-wide k quarters of its 64, B inside a
-  // B stage for the two halves of its 32
-  uint32_t a_off[4][WT], b_lo[2][WT], b_hi[2][WT];
+  // LDS addresses of the fragments (integers; a stage is added as a constant that becomes the
+  // read's immediate offset).  A: quarter s4 (16 k) of a stage; two bases, for stages 0 - 1 and
+  // for stage 2, because the offset field reaches 64 KiB; block row i is 4096 i further on
+  // (rows 32 apart share their swizzle).  B: half s of a stage, block column j.
+  uint32_t a_adr[2][4], b_lo[2][WT], b_hi[2][WT];
   auto b_off = [&](uint32_t krow, uint32_t col) -> uint32_t {
-    return krow * B_ROW + (((col >> 3) ^ b_swz(krow)) << 4) + (col & 7u) * 2u;
+    return lds_base + B_BASE + krow * B_ROW + (((col >> 3) ^ b_swz(krow)) << 4) + (col & 7u) * 2u;
   };
 #pragma unroll
-  for (uint32_t i = 0; i < WT; ++i) {
-    const uint32_t row = wm + 32u * i + l32;
-#pragma unroll
-    for (uint32_t s4 = 0; s4 < 4u; ++s4) a_off[s4][i] = row * 128u + (((2u * s4 + lhi) ^ row_swz8(row)) << 4);
+  for (uint32_t s4 = 0; s4 < 4u; ++s4) {
+    const uint32_t row = wm + l32;
+    a_adr[0][s4] = lds_base + row * 128u + (((2u * s4 + lhi) ^ row_swz8(row)) << 4);
+    a_adr[1][s4] = a_adr[0][s4] + 2u * A_BYTES;
+    asm volatile("" : "+v"(a_adr[1][s4]));      // kept in a register of its own: recomputed from a_adr[0] it is a vector add in the loop
   }
 #pragma unroll
   for (uint32_t s = 0; s < 2; ++s)
@@ -482,28 +497,33 @@ __global__ __launch_bounds__(GD_THREADS, WT == 4u ? 1 : 2) void gemm_bf16_dma_a6
   s16x4 blo[2][WT], bhi[2][WT];
   const uint32_t nk = K / GD_BK, nk2 = K / 64u;
   // one fragment read, in the order of gemm_bf16_dma_kernel: a0, b0 lo, b0 hi, b1 lo, .., a1, a2, ..
-  auto frag_load = [&](const uint8_t* ast, uint32_t s4, const uint8_t* bst, uint32_t s, uint32_t slot, uint32_t q) {
+  // sa: A stage (0 .. 2), s4: its quarter; sb: B stage (0 .. 3), s: its half -- constants where called
+  auto frag_load = [&](uint32_t sa, uint32_t s4, uint32_t sb, uint32_t s, uint32_t slot, uint32_t q) {
     if (q == 0u || q > 2u * WT) {
       const uint32_t i = q == 0u ? 0u : q - 2u * WT;
-      fa[slot][i] = *reinterpret_cast<const u32x4*>(ast + a_off[s4][i]);
+      fa[slot][i] = *(lds_u32x4_ptr)(a_adr[sa >> 1][s4] + ((sa & 1u) * A_BYTES + 4096u * i));
     } else {
       const uint32_t j = (q - 1u) >> 1;
-      if ((q - 1u) & 1u) bhi[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(bst + b_hi[s][j]));
-      else blo[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(bst + b_lo[s][j]));
+      if ((q - 1u) & 1u) bhi[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(b_hi[s][j] + sb * B_BYTES));
+      else blo[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(b_lo[s][j] + sb * B_BYTES));
     }
   };
-  // tile / stage indices beyond the end are clamped: every iteration issues the same number of
+  // tile / piece indices beyond the end are clamped: every iteration issues the same number of
   // loads (the vmcnt arithmetic relies on it), the redundant ones land in stages nobody reads again
-  auto dma_b = [&](uint32_t t, uint32_t h) {
-    dma16(gb[h] + (size_t)min(t, nk - 1u) * GD_BK * N, lds_base + B_BASE + (t % GD_NST) * B_BYTES + (ND * wave + h) * 1024u);
+  const uint32_t dst_a = lds_base + 2u * ND * wave * 1024u, dst_b = lds_base + B_BASE + ND * wave * 1024u;
+  auto b_rsrc = [&](uint32_t t) -> buf_rsrc {
+    return make_buf_rsrc(B + (size_t)min(t, nk - 1u) * GD_BK * N, GD_BK * N * 2u);
   };
-  auto dma_a = [&](uint32_t u, uint32_t stage_off, uint32_t g) {
-    dma16(ga[g] + (size_t)min(u, nk2 - 1u) * 64u, lds_base + stage_off + (2u * ND * wave + g) * 1024u);
+  auto dma_b = [&](const buf_rsrc& rb, uint32_t sb, uint32_t h) { buf_dma16(vb[h], rb, 0u, dst_b + sb * B_BYTES + h * 1024u); };
+  auto dma_a = [&](uint32_t u, uint32_t sa, uint32_t g) {
+    buf_dma16(va[g], rsrc_a, min(u, nk2 - 1u) * 128u, dst_a + sa * A_BYTES + g * 1024u);
   };
   // NM MFMAs on fragment slot `slot`; between them the NF fragment reads of the next half tile into
-  // the other slot (A quarter s4 of the stage at ast, B half s of the stage at bst), then ND DMA
-  // instructions dma(0 .. ND - 1)
-  auto block = [&](uint32_t slot, const uint8_t* ast, uint32_t s4, const uint8_t* bst, uint32_t s, auto&& dma) {
+  // the other slot, then ND DMA instructions: of B tile dt into B stage dsb (dpart 1), or of half
+  // dhalf of A piece dt into A stage dsa (dpart 0)
+  auto block = [&](uint32_t slot, uint32_t sa, uint32_t s4, uint32_t sb, uint32_t s, uint32_t dpart, uint32_t dt,
+                   uint32_t dstage, uint32_t dhalf) {
+    const buf_rsrc rb = b_rsrc(dt);
 #pragma unroll
     for (uint32_t m = 0; m < NM; ++m) {
       const uint32_t i = m / WT, j = m % WT;
@@ -512,46 +532,52 @@ __global__ __launch_bounds__(GD_THREADS, WT == 4u ? 1 : 2) void gemm_bf16_dma_a6
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (uint32_t x = m * (NF + ND) / NM; x < (m + 1u) * (NF + ND) / NM; ++x) {
-        if (x < NF) frag_load(ast, s4, bst, s, slot ^ 1u, x);
-        else dma(x - NF);
+        if (x < NF) frag_load(sa, s4, sb, s, slot ^ 1u, x);
+        else if (dpart == 1u) dma_b(rb, dstage, x - NF);
+        else dma_a(dt, dstage, dhalf * ND + (x - NF));
       }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  auto b_stage = [&](uint32_t t) -> const uint8_t* { return smem + B_BASE + (t % GD_NST) * B_BYTES; };
 
+  // prologue: A(0) B(0) B(1) A(1) B(2) A(2)h0
 #pragma unroll
   for (uint32_t g = 0; g < 2u * ND; ++g) dma_a(0u, 0u, g);
+  {
+    const buf_rsrc r0 = b_rsrc(0u), r1 = b_rsrc(1u), r2 = b_rsrc(2u);
 #pragma unroll
-  for (uint32_t h = 0; h < ND; ++h) dma_b(0u, h);
+    for (uint32_t h = 0; h < ND; ++h) dma_b(r0, 0u, h);
 #pragma unroll
-  for (uint32_t h = 0; h < ND; ++h) dma_b(1u, h);
+    for (uint32_t h = 0; h < ND; ++h) dma_b(r1, 1u, h);
 #pragma unroll
-  for (uint32_t g = 0; g < 2u * ND; ++g) dma_a(1u, A_BYTES, g);
+    for (uint32_t g = 0; g < 2u * ND; ++g) dma_a(1u, 1u, g);
 #pragma unroll
-  for (uint32_t h = 0; h < ND; ++h) dma_b(2u, h);
+    for (uint32_t h = 0; h < ND; ++h) dma_b(r2, 2u, h);
+  }
 #pragma unroll
-  for (uint32_t g = 0; g < ND; ++g) dma_a(2u, 2u * A_BYTES, g);
+  for (uint32_t g = 0; g < ND; ++g) dma_a(2u, 2u, g);
   __builtin_amdgcn_s_waitcnt(vm_wait(5u * ND));            // this wave's part of A(0) and B(0) has landed
   __syncthreads();
 #pragma unroll
-  for (uint32_t q = 0; q < NF; ++q) frag_load(smem, 0u, b_stage(0u), 0u, 0u, q);
-  // sa0, sa1, sa2: stages of A(u), A(u + 1), A(u + 2)
-  uint32_t sa0 = 0u, sa1 = A_BYTES, sa2 = 2u * A_BYTES;
-  for (uint32_t u = 0; u < nk2; ++u) {
-    const uint32_t kt = 2u * u;
-    block(0u, smem + sa0, 1u, b_stage(kt), 1u, [&](uint32_t x) { dma_b(kt + 3u, x); });
-    __builtin_amdgcn_s_waitcnt(vm_wait(4u * ND));          // tile kt + 1 has landed (this wave's part)
-    __syncthreads();                                       // ... everybody's; all reads of B(kt) are issued
-    block(1u, smem + sa0, 2u, b_stage(kt + 1u), 0u, [&](uint32_t x) { dma_a(u + 2u, sa2, ND + x); });
-    block(0u, smem + sa0, 3u, b_stage(kt + 1u), 1u, [&](uint32_t x) { dma_b(kt + 4u, x); });
-    __builtin_amdgcn_s_waitcnt(vm_wait(4u * ND));
-    __syncthreads();                                       // all reads of B(kt + 1) and of A(u) are issued
-    block(1u, smem + sa1, 0u, b_stage(kt + 2u), 0u, [&](uint32_t x) { dma_a(u + 3u, sa0, x); });
-    const uint32_t freed = sa0;
-    sa0 = sa1;
-    sa1 = sa2;
-    sa2 = freed;
+  for (uint32_t q = 0; q < NF; ++q) frag_load(0u, 0u, 0u, 0u, 0u, q);
+  // piece u of A (tiles 2 u and 2 u + 1 of B) lives in A stage u % 3, tile t in B stage t % 4: six
+  // pieces per pass make every stage index below a constant
+  for (uint32_t u0 = 0; u0 < nk2; u0 += 6u) {
+#pragma unroll
+    for (uint32_t p = 0; p < 6u; ++p) {
+      const uint32_t u = u0 + p, kt = 2u * u;
+      if (u < nk2) {
+        const uint32_t sa = p % 3u, sb = (2u * p) % 4u;
+        block(0u, sa, 1u, sb, 1u, 1u, kt + 3u, (sb + 3u) % 4u, 0u);                 // B(kt + 3)
+        __builtin_amdgcn_s_waitcnt(vm_wait(4u * ND));          // tile kt + 1 has landed (this wave's part)
+        __syncthreads();                                       // ... everybody's; all reads of B(kt) are issued
+        block(1u, sa, 2u, (sb + 1u) % 4u, 0u, 0u, u + 2u, (sa + 2u) % 3u, 1u);      // second half of A(u + 2)
+        block(0u, sa, 3u, (sb + 1u) % 4u, 1u, 1u, kt + 4u, sb, 0u);                 // B(kt + 4)
+        __builtin_amdgcn_s_waitcnt(vm_wait(4u * ND));
+        __syncthreads();                                       // all reads of B(kt + 1) and of A(u) are issued
+        block(1u, (sa + 1u) % 3u, 0u, (sb + 2u) % 4u, 0u, 0u, u + 3u, sa, 0u);      // first half of A(u + 3) into the stage just freed
+      }
+    }
   }
   __builtin_amdgcn_s_waitcnt(vm_wait(0));                  // no DMA may be in flight when the LDS is given back
 

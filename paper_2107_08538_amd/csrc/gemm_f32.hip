@@ -197,9 +197,11 @@ constexpr uint32_t fd_lds_bytes(uint32_t bm, uint32_t bn) { return FD_NST * (bm 
 
 // With one wave per SIMD nothing hides what a wave issues between two MFMAs, and not everything is
 // free there: a vector-ALU instruction (an address add) holds the matrix pipe up for about 14
-// clocks, a load with a 64-bit vector address for about 43, one with a 32-bit vector offset for
-// about 24, while scalar instructions and LDS reads cost nothing (measured with a loop of MFMAs
-// and one such instruction after every fourth).  So the main loop holds no vector arithmetic at
+// clocks, a load with a 64-bit vector address for 10-17 more, while scalar instructions, LDS
+// reads and loads with a scalar base and a 32-bit vector offset cost nothing (measured with a
+// loop of 64 MFMAs and one such instruction after every fourth: the mix this loop used to have,
+// an add before each LDS read and before each DMA, ran at 90 % of the MFMA-only rate, the
+// present mix at 100 %).  So the main loop holds no vector arithmetic at
 // all: the ring is walked by unrolling the loop over its four stages, which turns every stage
 // offset into the immediate offset of the LDS read (the A ring and the B ring are 64 KiB or less
 // each, the reach of that field), and the DMA goes through buffer resources whose walk along k is

@@ -24,8 +24,10 @@ __device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
 // The same transfer through a buffer resource: lane address = resource base + voff + soff, where
 // soff is wave-uniform (a scalar register), so that walking along k needs no vector arithmetic.
 // It matters to a kernel that runs one wave per SIMD: every vector-ALU instruction issued between
-// two MFMAs holds the matrix pipe up for ~14 clocks and a load ~21 clocks per address register
-// (43 for a 64-bit global address, 24 here), while scalar instructions and LDS reads are free.
+// two MFMAs holds the matrix pipe up for ~14 clocks (the 64-bit add that forms a global address
+// counts) and a load with a 64-bit vector address for 10-17 more, while scalar instructions, LDS
+// reads and loads with a scalar base and a 32-bit vector offset, like this one, are free
+// (measured: a loop of 64 fp32 MFMAs with one such instruction after every fourth).
 // The resource is raw (stride 0) and bounds-checked by the hardware: a lane whose offset lies at
 // or beyond `bytes` receives zeros and touches no memory.  Callers keep a resource to the piece
 // one workgroup (or one tile) reads, so its size always fits 32 bits.
