@@ -27,15 +27,20 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 
 SOURCE_OF = (("gemm_f32", "gemm_f32.hip"), ("gemm_bf16", "gemm_bf16.hip"), ("jacobi", "jacobi.hip"), ("bfs", "bfs.hip"),
-             ("conv", "conv3x3.hip"), ("stream_copy", "cu_trace.hip"), ("mfma_loop", "cu_trace.hip"))
+             ("conv", "conv3x3.hip"), ("stream_copy", "cu_trace.hip"), ("mfma_loop", "cu_trace.hip"),
+             ("fetch_rate", "cu_trace.hip"), ("lds_read_rate", "cu_trace.hip"))
 
 
 def source_hash(kernel_name):
-    """First 16 hex digits of the SHA-256 of the source file that defines the kernel ('' if unknown)."""
+    """First 16 hex digits of the SHA-256 of the source file that defines the kernel followed by the
+    device headers of csrc/ it may include ('' if unknown)."""
     for frag, src in SOURCE_OF:
         if frag in kernel_name:
-            with open(os.path.join(CSRC, src), "rb") as f:
-                return hashlib.sha256(f.read()).hexdigest()[:16]
+            h = hashlib.sha256()
+            for name in [src] + sorted(n for n in os.listdir(CSRC) if n.endswith(".h")):
+                with open(os.path.join(CSRC, name), "rb") as f:
+                    h.update(f.read())
+            return h.hexdigest()[:16]
     return ""
 
 
