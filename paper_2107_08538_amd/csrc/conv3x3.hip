@@ -799,6 +799,16 @@ __global__ __launch_bounds__(256) void conv_split_reduce_kernel(const float* __r
 // t, right after the barrier that frees tile t's stage, and has the three other slices of tile
 // t+1 (and the CU's other workgroup) to land.  Rows are XOR-swizzled in 16-byte chunks
 // (row_swz8) through each lane's choice of source chunk.
+//
+// The loop holds no vector arithmetic and no load with a 64-bit vector address (each of those
+// between two MFMAs holds the matrix pipe up: ~14 clocks per vector-ALU instruction, 10-17 per
+// such load, halved but not gone with two waves per SIMD).  Both operands travel through buffer
+// resources: a lane's offset into the tensor is a 32-bit register that changes only when the
+// filter tap does (then it is either the pixel's offset or, where the tap falls into the padding
+// ring, an offset beyond the resource, for which the hardware delivers zeros), the walk along the
+// depth is a scalar offset; the two stages are told apart by unrolling the loop over them, which
+// makes a stage the immediate offset of an LDS read.  The host takes this kernel only for inputs
+// below 2 GiB (the reach of the offsets).
 template <uint32_t WM, uint32_t WN>
 __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma64_kernel(ConvArgs a) {
   constexpr uint32_t NW = WM * WN;
@@ -807,6 +817,7 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma64_kernel(ConvArgs
   constexpr uint32_t NA = BMP / 8u / NW, NB = BNC / 8u / NW;     // DMA instructions per wave per tile
   constexpr uint32_t ND = NA + NB;
   static_assert(NA >= 1u && NB >= 1u, "every wave takes part in both operand copies");
+  static_assert(STAGE + 4096u < 65536u, "the second stage must be within reach of an LDS read's offset field");
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
   const uint32_t per_xcd = (a.tiles_total + 7u) / 8u;
@@ -821,13 +832,21 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma64_kernel(ConvArgs
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t wm = (wave / WN) * 64u, wn = (wave % WN) * 64u;
   const uint32_t l32 = lane & 31u, lhi = lane >> 5;
-  const uint16_t* zeros = reinterpret_cast<const uint16_t*>(g_zero16);
+
+  // Resources.  Pixels: the whole input, its base moved back by one image row and one pixel (the
+  // padding shift), so that the offset of a pixel's tap (0, 0) corner is never negative; nothing
+  // in front of the tensor is ever read, because a tap outside the image takes the offset
+  // `beyond` instead.  Weights: the rows of this workgroup's channels.
+  const uint32_t shift = (a.W + 1u) * a.C * 2u;
+  const uint32_t beyond = a.batch * a.H * a.W * a.C * 2u + shift;
+  const buf_rsrc rsrc_x = make_buf_rsrc(reinterpret_cast<const uint8_t*>(a.x) - shift, beyond);
+  const buf_rsrc rsrc_w = make_buf_rsrc(a.w + (size_t)bn * a.depth, min(BNC, a.K - bn) * a.depth * 2u);
 
   // DMA roles.  Instruction h of wave w fills the 1 KiB block b = N*w + h of an operand part:
   // rows 8b .. 8b+7, lane -> row 8b + lane/8, LDS chunk lane%8, source chunk swizzled.
-  int64_t a_src[NA];        // element offset of the pixel's (ih0, iw0) corner, plus the chunk
+  uint32_t a_voff[NA];      // byte offset of the pixel's tap (0, 0) corner in the pixel resource, plus the chunk
   uint32_t a_taps[NA];      // bit 3r+s: tap (r, s) lies inside the image (0 for pixels past the end)
-  const uint16_t* b_src[NB];
+  uint32_t b_voff[NB];
 #pragma unroll
   for (uint32_t h = 0; h < NA; ++h) {
     const uint32_t row = 8u * (NA * wave + h) + (lane >> 3);
@@ -845,26 +864,30 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma64_kernel(ConvArgs
       for (int32_t t = 0; t < 3; ++t)
         if (pv && (uint32_t)(ih0 + r) < a.H && (uint32_t)(iw0 + t) < a.W) taps |= 1u << (3 * r + t);
     a_taps[h] = taps;
-    a_src[h] = (((int64_t)b * a.H + ih0) * a.W + iw0) * a.C + 8u * ((lane & 7u) ^ row_swz8(row));
+    a_voff[h] = (((b * a.H + oh * a.stride) * a.W + ow * a.stride) * a.C + 8u * ((lane & 7u) ^ row_swz8(row))) * 2u;
   }
 #pragma unroll
   for (uint32_t h = 0; h < NB; ++h) {
     const uint32_t row = 8u * (NB * wave + h) + (lane >> 3);
-    b_src[h] = a.w + (size_t)min(bn + row, a.K - 1u) * a.depth + 8u * ((lane & 7u) ^ row_swz8(row));
+    b_voff[h] = ((min(bn + row, a.K - 1u) - bn) * a.depth + 8u * ((lane & 7u) ^ row_swz8(row))) * 2u;
   }
 
   const uint32_t nk = a.depth / 64u;
   uint32_t td = 0u, a_tap = 0u, a_c0 = 0u;   // DMA cursor: tile, its filter tap, first channel
+  uint32_t a_cur[NA];                        // this lane's pixel offsets for the cursor's tap
+  auto select_tap = [&]() {
+#pragma unroll
+    for (uint32_t h = 0; h < NA; ++h) a_cur[h] = ((a_taps[h] >> a_tap) & 1u) ? a_voff[h] : beyond;
+  };
+  select_tap();
   // instruction h of tile td's DMA (pixel blocks first, then weight blocks)
   auto dma_part = [&](uint32_t h) {
     const uint32_t stage = lds_base + (td & 1u) * STAGE;
     if (h < NA) {
       const uint32_t r = (a_tap * 11u) >> 5, t = a_tap - 3u * r;
-      const int64_t delta = ((int64_t)r * a.W + t) * a.C + a_c0;
-      const uint32_t ok = (a_taps[h] >> a_tap) & 1u;
-      dma16(pick(a.x + a_src[h] + delta, zeros, ok), stage + (NA * wave + h) * 1024u);
+      buf_dma16(a_cur[h], rsrc_x, ((r * a.W + t) * a.C + a_c0) * 2u, stage + (NA * wave + h) * 1024u);
     } else {
-      dma16(b_src[h - NA] + (size_t)min(td, nk - 1u) * 64u, stage + A_BYTES + (NB * wave + h - NA) * 1024u);
+      buf_dma16(b_voff[h - NA], rsrc_w, min(td, nk - 1u) * 128u, stage + A_BYTES + (NB * wave + h - NA) * 1024u);
     }
   };
   // (the cursor stops at the last tile: the requests past it re-read that tile into a stage nobody
@@ -872,7 +895,11 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma64_kernel(ConvArgs
   auto next_tile = [&]() {
     if (td + 1u < nk) {
       a_c0 += 64u;
-      if (a_c0 == a.C) { a_c0 = 0u; ++a_tap; }
+      if (a_c0 == a.C) {
+        a_c0 = 0u;
+        ++a_tap;
+        select_tap();
+      }
     }
     ++td;
   };
@@ -885,24 +912,29 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma64_kernel(ConvArgs
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // fragment addresses inside a stage for slice 0; slice q lies at the address ^ (q << 5)
-  uint32_t p_off[2], w_off[2];
+  // LDS addresses of the fragments of block 0 in stage 0, one per 16-deep slice q (the slice flips
+  // two bits of the swizzled chunk, so it is not an offset); block 1 lies 32 rows = 4096 bytes
+  // further on with the same swizzle, stage 1 STAGE bytes further on: both immediates of the read
+  uint32_t p_adr[4], w_adr[4];
+  {
+    const uint32_t prow = wm + l32, wrow = wn + l32;
 #pragma unroll
-  for (uint32_t i = 0; i < 2; ++i) {
-    const uint32_t prow = wm + 32u * i + l32, wrow = wn + 32u * i + l32;
-    p_off[i] = prow * 128u + ((lhi ^ row_swz8(prow)) << 4);
-    w_off[i] = A_BYTES + wrow * 128u + ((lhi ^ row_swz8(wrow)) << 4);
+    for (uint32_t q = 0; q < 4u; ++q) {
+      p_adr[q] = lds_base + ((prow * 128u + ((lhi ^ row_swz8(prow)) << 4)) ^ (q << 5));
+      w_adr[q] = lds_base + A_BYTES + ((wrow * 128u + ((lhi ^ row_swz8(wrow)) << 4)) ^ (q << 5));
+    }
   }
+  typedef const u32x4 __attribute__((address_space(3))) * lds_u32x4_ptr;
   u32x4 fp[2][2], fw[2][2];                  // [slot][block]
-  auto frag_load = [&](const uint8_t* st, uint32_t q, uint32_t slot, uint32_t m) {   // m: w0, p0, p1, w1
-    if (m == 0u) fw[slot][0] = *reinterpret_cast<const u32x4*>(st + (w_off[0] ^ (q << 5)));
-    else if (m == 3u) fw[slot][1] = *reinterpret_cast<const u32x4*>(st + (w_off[1] ^ (q << 5)));
-    else fp[slot][m - 1u] = *reinterpret_cast<const u32x4*>(st + (p_off[m - 1u] ^ (q << 5)));
+  auto frag_load = [&](uint32_t st, uint32_t q, uint32_t slot, uint32_t m) {   // m: w0, p0, p1, w1; st: stage, a constant
+    if (m == 0u) fw[slot][0] = *(lds_u32x4_ptr)(w_adr[q] + st * STAGE);
+    else if (m == 3u) fw[slot][1] = *(lds_u32x4_ptr)(w_adr[q] + (st * STAGE + 4096u));
+    else fp[slot][m - 1u] = *(lds_u32x4_ptr)(p_adr[q] + (st * STAGE + (m - 1u) * 4096u));
   };
   // 4 MFMAs on fragment slot `slot` (order (j, i) = (0,0) (0,1) (1,0) (1,1)); spread between them
-  // the 4 fragment reads of slice fq of the stage at fst into the other slot and, if `dma`, the
+  // the 4 fragment reads of slice fq of stage fst into the other slot and, if `dma`, the
   // DMA of tile td
-  auto block = [&](uint32_t slot, const uint8_t* fst, uint32_t fq, bool dma) {
+  auto block = [&](uint32_t slot, uint32_t fst, uint32_t fq, bool dma) {
 #pragma unroll
     for (uint32_t m = 0; m < 4u; ++m) {
       const uint32_t j = m >> 1, i = m & 1u;
@@ -926,20 +958,23 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma64_kernel(ConvArgs
   __builtin_amdgcn_s_waitcnt(vm_wait(ND));   // this wave's part of tile 0 has landed
   __syncthreads();
 #pragma unroll
-  for (uint32_t m = 0; m < 4u; ++m) frag_load(smem, 0u, 0u, m);
-  for (uint32_t kt = 0; kt < nk; ++kt) {
-    const uint8_t* cur = smem + (kt & 1u) * STAGE;
-    const uint8_t* nxt = smem + ((kt + 1u) & 1u) * STAGE;
-    block(0u, cur, 1u, false);
-    block(1u, cur, 2u, false);
-    block(0u, cur, 3u, false);
-    // Every fragment read of tile kt has been issued; once they have returned and every DMA this
-    // wave issued has landed (the last were tile kt+1's), the barrier tells that tile kt+1 is
-    // complete and that tile kt's stage may be overwritten.
-    __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) and lgkmcnt(0)
-    __syncthreads();
-    block(1u, nxt, 0u, true);                // tile kt+2 into the stage tile kt leaves
-    next_tile();
+  for (uint32_t m = 0; m < 4u; ++m) frag_load(0u, 0u, 0u, m);
+  for (uint32_t kt0 = 0; kt0 < nk; kt0 += 2u) {
+#pragma unroll
+    for (uint32_t u = 0; u < 2u; ++u) {      // tile kt0 + u lives in stage u
+      if (kt0 + u < nk) {
+        block(0u, u, 1u, false);
+        block(1u, u, 2u, false);
+        block(0u, u, 3u, false);
+        // Every fragment read of this tile has been issued; once they have returned and every DMA this
+        // wave issued has landed (the last were the next tile's), the barrier tells that the next tile is
+        // complete and that this tile's stage may be overwritten.
+        __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) and lgkmcnt(0)
+        __syncthreads();
+        block(1u, u ^ 1u, 0u, true);             // the tile after the next into the stage this tile leaves
+        next_tile();
+      }
+    }
   }
   __builtin_amdgcn_s_waitcnt(vm_wait(0));    // no DMA may be in flight when the LDS is given back
 
@@ -1738,7 +1773,9 @@ hipError_t launch_dma(hipStream_t st, const Geometry& g, const ConvArgs& a, bool
       attr = hipFuncSetAttribute((const void*)conv3x3_dma64_kernel<WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   });
   if (attr != hipSuccess) return attr;
-  if (deep && a.C % 64u == 0u)
+  // (the depth-64 kernel addresses its input with 32-bit offsets)
+  const bool fits = (uint64_t)a.batch * a.H * a.W * a.C * 2u + ((uint64_t)a.W + 1u) * a.C * 2u < (1ull << 31);
+  if (deep && a.C % 64u == 0u && fits)
     hipLaunchKernelGGL((conv3x3_dma64_kernel<WM, WN>), dim3(g.blocks), dim3(64u * WM * WN), lds, st, a);
   else
     hipLaunchKernelGGL((conv3x3_dma_kernel<WM, WN>), dim3(g.blocks), dim3(64u * WM * WN), lds, st, a);
