@@ -582,19 +582,36 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t l32 = lane & 31u, lhi = lane >> 5;
-  const uint16_t* zeros = reinterpret_cast<const uint16_t*>(g_zero16);
+
+  // A workgroup advances one depth tile per pass over its loop with one wave per SIMD and only
+  // four MFMAs per wave and tile, so what is issued between the MFMAs decides its speed: the loop
+  // holds no vector arithmetic and no load with a 64-bit vector address (see the depth-64 ring
+  // kernel).  Both operands travel through buffer resources.  Pixels: the resource spans what this
+  // workgroup's 64 pixels can read, from the tap (0, 0) pixel of its first pixel to the tap (2, 2)
+  // pixel of its last (input pixel indices grow with output pixel indices, also across images), so
+  // its size fits 32 bits whatever the tensor's; a lane's offset changes only with the filter
+  // tap, and a tap in the padding ring takes the offset `beyond`, for which the hardware delivers
+  // zeros.  The walk along the depth is a scalar offset.
+  auto corner = [&](uint32_t p) -> uint32_t {            // input pixel under tap (1, 1) of output pixel p
+    const uint32_t b = p / a.by_plane;
+    const uint32_t rem = p - b * a.Ho * a.Wo;
+    const uint32_t oh = rem / a.by_wo, ow = rem - oh * a.Wo;
+    return (b * a.H + oh * a.stride) * a.W + ow * a.stride;
+  };
+  const uint32_t lin0 = corner(bm), lin1 = corner(min(bm + 64u, a.pixels) - 1u);
+  const uint32_t beyond = (lin1 - lin0 + 2u * a.W + 3u) * a.C * 2u;
+  const buf_rsrc rsrc_x = make_buf_rsrc(a.x + ((int64_t)lin0 - (int64_t)a.W - 1) * a.C, beyond);
+  const buf_rsrc rsrc_w = make_buf_rsrc(a.w + (size_t)bn * a.depth, min(64u, a.K - bn) * a.depth * 2u);
 
   // DMA roles: instruction h of wave w fills the 1 KiB block b = 2w + h of an operand part
   // (rows 8b .. 8b+7; lane -> row 8b + lane/8, LDS chunk lane%8, source chunk swizzled)
-  int64_t a_src[2];
-  uint32_t a_taps[2];
-  const uint16_t* b_src[2];
+  uint32_t a_voff[2], a_taps[2], b_voff[2];
 #pragma unroll
   for (uint32_t h = 0; h < 2; ++h) {
     const uint32_t row = 8u * (2u * wave + h) + (lane >> 3);
     const uint32_t p = bm + row;
     const bool pv = p < a.pixels;
-    const uint32_t pp = pv ? p : 0u;
+    const uint32_t pp = pv ? p : bm;
     const uint32_t b = pp / a.by_plane;
     const uint32_t rem = pp - b * a.Ho * a.Wo;
     const uint32_t oh = rem / a.by_wo, ow = rem - oh * a.Wo;
@@ -607,34 +624,28 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
         if (pv && (uint32_t)(ih0 + r) < a.H && (uint32_t)(iw0 + t) < a.W) taps |= 1u << (3 * r + t);
     a_taps[h] = taps;
     const uint32_t chunk = (lane & 7u) ^ row_swz8(row);
-    a_src[h] = (((int64_t)b * a.H + ih0) * a.W + iw0) * a.C + 8u * chunk;
-    b_src[h] = a.w + (size_t)min(bn + row, a.K - 1u) * a.depth + (size_t)kt0 * KS_BK + 8u * chunk;
+    a_voff[h] = ((((b * a.H + oh * a.stride) * a.W + ow * a.stride) - lin0) * a.C + 8u * chunk) * 2u;
+    b_voff[h] = ((min(bn + row, a.K - 1u) - bn) * a.depth + 8u * chunk) * 2u;
   }
 
-  // DMA cursor: tile relative to kt0, its tap, first channel; and the four sources of the tile,
-  // kept as running pointers.  A workgroup advances one depth tile per pass over this code with
-  // one wave per SIMD, so the pass is kept short: within a filter tap every source moves on by
-  // 64 values (128 bytes; a pixel source that reads the block of zeros stays), and only a new
-  // tap works the pixel sources out again.  At the last tile the sources stop: the requests past
-  // it re-read that tile into stages nobody reads any more.
+  // DMA cursor: tile relative to kt0, its tap, first channel, and this lane's pixel offsets for
+  // that tap.  At the last tile the cursor stops: the requests past it re-read that tile into
+  // stages nobody reads any more.
   uint32_t td = 0u, a_tap = kt0 * KS_BK / a.C, a_c0 = kt0 * KS_BK - a_tap * a.C;
-  const uint16_t* a_cur[2];
-  uint64_t a_step[2], b_step = nk > 1u ? 2u * KS_BK : 0u;
+  uint32_t a_cur[2];
   auto new_tap = [&]() {
-    const uint32_t r = (a_tap * 11u) >> 5, t = a_tap - 3u * r;
-    const int64_t delta = ((int64_t)r * a.W + t) * a.C + a_c0;
 #pragma unroll
-    for (uint32_t q = 0; q < 2u; ++q) {
-      const uint32_t ok = (a_taps[q] >> a_tap) & 1u;
-      a_cur[q] = pick(a.x + a_src[q] + delta, zeros, ok);
-      a_step[q] = nk > 1u ? (uint64_t)ok * (2u * KS_BK) : 0u;
-    }
+    for (uint32_t q = 0; q < 2u; ++q) a_cur[q] = ((a_taps[q] >> a_tap) & 1u) ? a_voff[q] : beyond;
   };
   new_tap();
-  auto dma_tile_part = [&](uint32_t q) {     // q = 0, 1: pixel blocks; 2, 3: weight blocks
-    const uint32_t stage = lds_base + (td % KS_NST) * KS_STAGE;
-    if (q < 2u) dma16(a_cur[q], stage + (2u * wave + q) * 1024u);
-    else dma16(b_src[q - 2u], stage + KS_PART + (2u * wave + q - 2u) * 1024u);
+  const uint32_t dst_a = lds_base + 2u * wave * 1024u, dst_b = dst_a + KS_PART;
+  auto dma_tile_part = [&](uint32_t st, uint32_t q) {     // st: ring stage; q = 0, 1: pixel blocks; 2, 3: weight blocks
+    if (q < 2u) {
+      const uint32_t r = (a_tap * 11u) >> 5, t = a_tap - 3u * r;
+      buf_dma16(a_cur[q], rsrc_x, ((r * a.W + t) * a.C + a_c0) * 2u, dst_a + st * KS_STAGE + q * 1024u);
+    } else {
+      buf_dma16(b_voff[q - 2u], rsrc_w, (kt0 + min(td, nk - 1u)) * (2u * KS_BK), dst_b + st * KS_STAGE + (q - 2u) * 1024u);
+    }
   };
   auto next_tile = [&]() {
     ++td;
@@ -644,14 +655,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
         a_c0 = 0u;
         ++a_tap;
         new_tap();
-      } else {
-#pragma unroll
-        for (uint32_t q = 0; q < 2u; ++q)
-          a_cur[q] = reinterpret_cast<const uint16_t*>(reinterpret_cast<uintptr_t>(a_cur[q]) + a_step[q]);
       }
-#pragma unroll
-      for (uint32_t q = 0; q < 2u; ++q)
-        b_src[q] = reinterpret_cast<const uint16_t*>(reinterpret_cast<uintptr_t>(b_src[q]) + b_step);
     }
   };
 
@@ -663,35 +667,33 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint32_t p_off[2], w_off[2];               // this wave's 16-deep slice: chunks 2*wave, 2*wave + 1
-#pragma unroll
-  for (uint32_t i = 0; i < 2; ++i) {
-    const uint32_t row = 32u * i + l32;
-    p_off[i] = row * 128u + (((2u * wave + lhi) ^ row_swz8(row)) << 4);
-    w_off[i] = KS_PART + p_off[i];
-  }
+  // LDS address of this wave's 16-deep slice (chunks 2*wave, 2*wave + 1) of pixel block 0 in stage
+  // 0; pixel block 1 lies 4096 bytes further on (same swizzle), the weight blocks KS_PART further,
+  // a stage KS_STAGE further: all immediates of the reads
+  const uint32_t p_adr = lds_base + l32 * 128u + (((2u * wave + lhi) ^ row_swz8(l32)) << 4);
+  typedef const u32x4 __attribute__((address_space(3))) * lds_u32x4_ptr;
   u32x4 fp[2][2], fw[2][2];                  // [slot][block]
-  auto frag_load = [&](const uint8_t* st, uint32_t slot, uint32_t q) {   // q: w0, p0, p1, w1
-    if (q == 0u) fw[slot][0] = *reinterpret_cast<const u32x4*>(st + w_off[0]);
-    else if (q == 3u) fw[slot][1] = *reinterpret_cast<const u32x4*>(st + w_off[1]);
-    else fp[slot][q - 1u] = *reinterpret_cast<const u32x4*>(st + p_off[q - 1u]);
+  auto frag_load = [&](uint32_t st, uint32_t slot, uint32_t q) {   // st: stage, a constant where called; q: w0, p0, p1, w1
+    if (q == 0u) fw[slot][0] = *(lds_u32x4_ptr)(p_adr + (st * KS_STAGE + KS_PART));
+    else if (q == 3u) fw[slot][1] = *(lds_u32x4_ptr)(p_adr + (st * KS_STAGE + KS_PART + 4096u));
+    else fp[slot][q - 1u] = *(lds_u32x4_ptr)(p_adr + (st * KS_STAGE + (q - 1u) * 4096u));
   };
-  // tile kt: 4 MFMAs on slot `slot`; between them the fragment reads of tile kt+1 into the other
-  // slot and this wave's part of tile kt + NST, which goes into the stage tile kt leaves
-  auto step = [&](uint32_t slot, uint32_t kt) {
+  // tile kt, which lives in stage st: 4 MFMAs on slot `slot`; between them the fragment reads of
+  // tile kt+1 into the other slot and this wave's part of tile kt + NST, which goes into the stage
+  // tile kt leaves
+  auto step = [&](uint32_t slot, uint32_t st) {
     // 2 tiles' worth of instructions were issued after tile kt+1's: it has landed when no more
     // are outstanding; the barrier extends that to every wave's part and tells that tile kt's
     // fragments are in registers everywhere
     __builtin_amdgcn_s_waitcnt(vm_wait((KS_NST - 2u) * 4u));
     __syncthreads();
-    const uint8_t* fst = smem + ((kt + 1u) % KS_NST) * KS_STAGE;
 #pragma unroll
     for (uint32_t m = 0; m < 4u; ++m) {
       const uint32_t j = m >> 1, i = m & 1u;
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fw[slot][j]), as_bf16x8(fp[slot][i]), acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      frag_load(fst, slot ^ 1u, m);
-      dma_tile_part(m);
+      frag_load((st + 1u) % KS_NST, slot ^ 1u, m);
+      dma_tile_part(st, m);
       __builtin_amdgcn_sched_barrier(0);
     }
     next_tile();
@@ -700,20 +702,19 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
 #pragma unroll
   for (uint32_t t = 0; t < KS_NST; ++t) {
 #pragma unroll
-    for (uint32_t q = 0; q < 4u; ++q) dma_tile_part(q);
+    for (uint32_t q = 0; q < 4u; ++q) dma_tile_part(t, q);
     next_tile();
   }
   __builtin_amdgcn_s_waitcnt(vm_wait((KS_NST - 1u) * 4u));   // this wave's part of tile 0
   __syncthreads();
 #pragma unroll
-  for (uint32_t q = 0; q < 4u; ++q) frag_load(smem, 0u, q);
-  // two tiles per iteration (the fragment slots alternate), an odd last tile after the loop
-  uint32_t kt = 0u;
-  for (; kt + 1u < nk; kt += 2u) {
-    step(0u, kt);
-    step(1u, kt + 1u);
+  for (uint32_t q = 0; q < 4u; ++q) frag_load(0u, 0u, q);
+  // four tiles per pass: the ring stage and the fragment slot of each are constants
+  for (uint32_t kt = 0u; kt < nk; kt += KS_NST) {
+#pragma unroll
+    for (uint32_t u = 0; u < KS_NST; ++u)
+      if (kt + u < nk) step(u & 1u, u);
   }
-  if (kt < nk) step(0u, kt);
   __builtin_amdgcn_s_waitcnt(vm_wait(0));    // no DMA in flight, then the ring becomes the reduction buffer
   __syncthreads();
 
