@@ -487,6 +487,11 @@ def main():
                            policy=args.policy, queue=args.queue, tasks=n_tasks, workers=min(n_tasks, args.workers or harness.MAX_WORKERS),
                            arrivals="all at t=0" if args.batch else "as the mix states", harness=args.harness,
                            release=args.release, cap_bytes=cap, granule_cus=int(sched.desc.granule_cus), n_cu=256),
+               # `value` is over the whole timed region; the comparisons below (serialised run, other policies) are
+               # medians of per-pass figures, so the per-pass median and what lies between the passes (the pool's
+               # start and join, the records) are given too
+               tasks_per_s_median_of_passes=round(med([s["tasks_per_s"] for s in sums]), 2),
+               between_passes_ms=round(1e3 * (elapsed - sum(m for _, m in runs)) / args.steps, 3),
                mean_turnaround_ms=round(mean_turn, 3),
                median_turnaround_ms=round(med([s["mean_turnaround_ms"] for s in sums]), 3),
                mean_wait_ms=round(sum(s["mean_wait_ms"] for s in sums) / len(sums), 3),
