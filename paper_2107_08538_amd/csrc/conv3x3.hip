@@ -674,9 +674,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_ksplit_kernel(ConvArgs a) 
   typedef const u32x4 __attribute__((address_space(3))) * lds_u32x4_ptr;
   u32x4 fp[2][2], fw[2][2];                  // [slot][block]
   auto frag_load = [&](uint32_t st, uint32_t slot, uint32_t q) {   // st: stage, a constant where called; q: w0, p0, p1, w1
-    if (q == 0u) fw[slot][0] = *(lds_u32x4_ptr)(p_adr + (st * KS_STAGE + KS_PART));
-    else if (q == 3u) fw[slot][1] = *(lds_u32x4_ptr)(p_adr + (st * KS_STAGE + KS_PART + 4096u));
-    else fp[slot][q - 1u] = *(lds_u32x4_ptr)(p_adr + (st * KS_STAGE + (q - 1u) * 4096u));
+    if (q == 0u) fw[slot][0] = *(lds_u32x4_ptr)(uintptr_t)(p_adr + (st * KS_STAGE + KS_PART));
+    else if (q == 3u) fw[slot][1] = *(lds_u32x4_ptr)(uintptr_t)(p_adr + (st * KS_STAGE + KS_PART + 4096u));
+    else fp[slot][q - 1u] = *(lds_u32x4_ptr)(uintptr_t)(p_adr + (st * KS_STAGE + (q - 1u) * 4096u));
   };
   // tile kt, which lives in stage st: 4 MFMAs on slot `slot`; between them the fragment reads of
   // tile kt+1 into the other slot and this wave's part of tile kt + NST, which goes into the stage
@@ -928,9 +928,9 @@ __global__ __launch_bounds__(64 * WM * WN, 2) void conv3x3_dma64_kernel(ConvArgs
   typedef const u32x4 __attribute__((address_space(3))) * lds_u32x4_ptr;
   u32x4 fp[2][2], fw[2][2];                  // [slot][block]
   auto frag_load = [&](uint32_t st, uint32_t q, uint32_t slot, uint32_t m) {   // m: w0, p0, p1, w1; st: stage, a constant
-    if (m == 0u) fw[slot][0] = *(lds_u32x4_ptr)(w_adr[q] + st * STAGE);
-    else if (m == 3u) fw[slot][1] = *(lds_u32x4_ptr)(w_adr[q] + (st * STAGE + 4096u));
-    else fp[slot][m - 1u] = *(lds_u32x4_ptr)(p_adr[q] + (st * STAGE + (m - 1u) * 4096u));
+    if (m == 0u) fw[slot][0] = *(lds_u32x4_ptr)(uintptr_t)(w_adr[q] + st * STAGE);
+    else if (m == 3u) fw[slot][1] = *(lds_u32x4_ptr)(uintptr_t)(w_adr[q] + (st * STAGE + 4096u));
+    else fp[slot][m - 1u] = *(lds_u32x4_ptr)(uintptr_t)(p_adr[q] + (st * STAGE + (m - 1u) * 4096u));
   };
   // 4 MFMAs on fragment slot `slot` (order (j, i) = (0,0) (0,1) (1,0) (1,1)); spread between them
   // the 4 fragment reads of slice fq of stage fst into the other slot and, if `dma`, the

@@ -501,11 +501,11 @@ __global__ __launch_bounds__(GD_THREADS, WT == 4u ? 1 : 2) void gemm_bf16_dma_a6
   auto frag_load = [&](uint32_t sa, uint32_t s4, uint32_t sb, uint32_t s, uint32_t slot, uint32_t q) {
     if (q == 0u || q > 2u * WT) {
       const uint32_t i = q == 0u ? 0u : q - 2u * WT;
-      fa[slot][i] = *(lds_u32x4_ptr)(a_adr[sa >> 1][s4] + ((sa & 1u) * A_BYTES + 4096u * i));
+      fa[slot][i] = *(lds_u32x4_ptr)(uintptr_t)(a_adr[sa >> 1][s4] + ((sa & 1u) * A_BYTES + 4096u * i));
     } else {
       const uint32_t j = (q - 1u) >> 1;
-      if ((q - 1u) & 1u) bhi[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(b_hi[s][j] + sb * B_BYTES));
-      else blo[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(b_lo[s][j] + sb * B_BYTES));
+      if ((q - 1u) & 1u) bhi[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)(b_hi[s][j] + sb * B_BYTES));
+      else blo[slot][j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)(b_lo[s][j] + sb * B_BYTES));
     }
   };
   // tile / piece indices beyond the end are clamped: every iteration issues the same number of

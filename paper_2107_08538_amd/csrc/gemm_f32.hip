@@ -299,14 +299,14 @@ __global__ __launch_bounds__(64 * WGM * WGN, TM * TN >= 16 ? 1 : 2) void gemm_f3
   // in the order the MFMAs need them: the A operands (one read serves four steps), then the B
   // operands, two steps (two k rows, one two-address LDS read) at a time
   auto frag_load = [&](uint32_t st, uint32_t hf, uint32_t slot, uint32_t q) {
-    if (q < TM) fa[slot][q] = *(lds_f4_ptr)(a_off[hf][q] + st * A_BYTES);
+    if (q < TM) fa[slot][q] = *(lds_f4_ptr)(uintptr_t)(a_off[hf][q] + st * A_BYTES);
     else {
       // the next step's k row is the next LDS row (same swizzle: a half never crosses k = 8), a
       // constant distance away, so the pair becomes one two-address read
       const uint32_t x = q - TM, s2 = 2u * (x / TN), j = x % TN;
       const uint32_t p = b_off[hf][s2 / 2u][j] + st * B_BYTES;
-      fb[slot][s2][j] = *(lds_f1_ptr)p;
-      fb[slot][s2 + 1u][j] = *(lds_f1_ptr)(p + B_ROW);
+      fb[slot][s2][j] = *(lds_f1_ptr)(uintptr_t)p;
+      fb[slot][s2 + 1u][j] = *(lds_f1_ptr)(uintptr_t)(p + B_ROW);
     }
   };
   // tile indices beyond the end are clamped: the schedule never changes (see the wait counts), the

@@ -159,3 +159,61 @@ def test_bfs_and_jacobi_variants(reports):
     assert (windows, streams, one) == (3, 2, 8)
     for n, w in ((2048, windows), (512, windows), (4096, min(windows, streams)), (16384, min(windows, streams)), (77, one)):
         assert mgb.mgb_jacobi_residency(n) == w == lib.orc_jacobi_residency(U(n)), n
+
+
+# ---- what the main loops of the MFMA kernels issue between their MFMAs -----------------------------
+#
+# With one wave per SIMD a vector-ALU instruction between two MFMAs holds the matrix pipe up for ~14
+# clocks and a load with a 64-bit vector address for 10-17 more, while scalar instructions, LDS reads
+# with immediate offsets and buffer loads with scalar offsets are free.  The ring kernels are written so
+# that their main loops hold none of the former; this reads the compiler's assembly to keep it so.
+
+def _assembly(name):
+    cmd = ["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "-x", "hip", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wno-inline-asm", "-S", "--cuda-device-only", os.path.join(CSRC, name), "-o", "-"]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-3000:]
+    return r.stdout.split("\n")
+
+
+@pytest.fixture(scope="module")
+def assemblies():
+    if shutil.which("hipcc") is None:
+        pytest.skip("hipcc not found")
+    names = ["gemm_f32.hip", "gemm_bf16.hip", "conv3x3.hip"]
+    with ThreadPoolExecutor(max_workers=3) as ex:
+        return dict(zip(names, ex.map(_assembly, names)))
+
+
+def _main_loop(lines, fragment):
+    """Instruction names from the loop header that is followed by the most MFMAs to the kernel's last MFMA."""
+    start = [i for i, l in enumerate(lines) if fragment in l and "@function" in l]
+    assert len(start) == 1, (fragment, len(start))
+    end = [i for i, l in enumerate(lines) if i > start[0] and l.strip().startswith(".size") and fragment in l][0]
+    body = lines[start[0]:end]
+    mfma = [i for i, l in enumerate(body) if "v_mfma" in l]
+    headers = [i for i, l in enumerate(body) if "Loop Header" in l and i < mfma[-1]]
+    assert headers, fragment
+    h = max(headers, key=lambda i: sum(1 for j in mfma if i < j < i + 3000))
+    return [l.split()[0] for l in body[h:mfma[-1] + 1]
+            if l.startswith("\t") and l.strip() and not l.strip().startswith((";", "."))]
+
+
+@pytest.mark.parametrize("source,fragment,mfmas,max_valu,kinds", [
+    # four ring stages per pass; the compiler recomputes a few addresses at the loop header
+    ("gemm_f32.hip", "gemm_f32_dma_kernelILj2ELj2ELj4ELj4E", 512, 8, {"v_add_u32_e32"}),
+    ("gemm_f32.hip", "gemm_f32_dma_kernelILj2ELj4ELj2ELj1E", 64, 8, {"v_add_u32_e32"}),
+    # twelve combinations of A and B stage per pass
+    ("gemm_bf16.hip", "gemm_bf16_dma_a64_kernelILj4E", 384, 8, {"v_add_u32_e32"}),
+    ("gemm_bf16.hip", "gemm_bf16_dma_a64_kernelILj2E", 96, 8, {"v_add_u32_e32"}),
+    # conv: a new filter tap selects each lane's offsets (and, compare, select per DMA instruction), nothing per tile
+    ("conv3x3.hip", "conv3x3_dma64_kernelILj2ELj2E", 32, 16, {"v_and_b32_e32", "v_cmp_eq_u32_e32", "v_cndmask_b32_e32", "v_mov_b32_e32"}),
+    ("conv3x3.hip", "conv3x3_dma_ksplit_kernel", 16, 24, {"v_and_b32_e32", "v_cmp_eq_u32_e32", "v_cndmask_b32_e32", "v_mov_b32_e32"}),
+])
+def test_main_loops_hold_no_vector_arithmetic_between_mfmas(assemblies, source, fragment, mfmas, max_valu, kinds):
+    ops = _main_loop(assemblies[source], fragment)
+    assert sum(1 for o in ops if "v_mfma" in o) == mfmas, (fragment, sum(1 for o in ops if "v_mfma" in o))
+    valu = [o for o in ops if o.startswith("v_") and "mfma" not in o and not o.startswith("v_accvgpr")]
+    assert len(valu) <= max_valu and set(valu) <= kinds, (fragment, sorted(set(valu)), len(valu))
+    assert not [o for o in ops if o.startswith(("global_load", "flat_load"))], fragment     # DMA: buffer loads only
+    assert [o for o in ops if o.startswith("buffer_load")], fragment
