@@ -1080,22 +1080,26 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(ConvArgs a) {
   }
   // (the table's stage takes weights only after the loop's first barrier, which every wave
   // reaches after it has used what it read here)
-  // weights: instruction h of wave w fills rows 8 * (2w + h) .. + 7 of a stage
-  const uint16_t* b_src[2];
+  // weights: instruction h of wave w fills rows 8 * (2w + h) .. + 7 of a stage.  They travel
+  // through a buffer resource over this workgroup's 64 filters: the lane offset is fixed, the
+  // tile's place in the depth a scalar offset, so that a request costs the loop no vector
+  // arithmetic (see the depth-64 ring kernel)
+  const buf_rsrc rsrc_w = make_buf_rsrc(a.w + (size_t)bn * a.depth, min(64u, a.K - bn) * a.depth * 2u);
+  uint32_t b_voff[2];
 #pragma unroll
   for (uint32_t h = 0; h < 2; ++h) {
     const uint32_t row = 8u * (2u * wave + h) + (lane >> 3);
-    b_src[h] = a.w + (size_t)min(bn + row, a.K - 1u) * a.depth + 8u * ((lane & 7u) ^ row_swz8(row));
+    b_voff[h] = ((min(bn + row, a.K - 1u) - bn) * a.depth + 8u * ((lane & 7u) ^ row_swz8(row))) * 2u;
   }
   // weight tile t belongs to channel block t / 9 and tap t % 9: depth offset tap * C + 64 * block.
   // The cursor stops at the last tile; the requests past it land in stages nobody reads and
   // keep the count of outstanding requests the same in every iteration.
   uint32_t wt = 0u, w_tap = 0u, w_cb = 0u;
   auto dma_weights = [&]() {
-    const size_t off = (size_t)w_tap * a.C + 64u * w_cb;
+    const uint32_t off = (w_tap * a.C + 64u * w_cb) * 2u;
     const uint32_t stage = lds_base + PT_PATCH + (wt & (PT_WST - 1u)) * PT_WTILE;
 #pragma unroll
-    for (uint32_t h = 0; h < 2; ++h) dma16(b_src[h] + off, stage + (2u * wave + h) * 1024u);
+    for (uint32_t h = 0; h < 2; ++h) buf_dma16(b_voff[h], rsrc_w, off, stage + (2u * wave + h) * 1024u);
     if (wt + 1u < nk) {
       if (++w_tap == 9u) { w_tap = 0u; ++w_cb; }
     }
@@ -1128,29 +1132,30 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(ConvArgs a) {
     const uint32_t slot = slot0[i] + shift;
     return slot * 128u + ((lhi ^ (slot & 7u)) << 4);
   };
-  uint32_t w_off[2];                         // the same for the weight fragment, inside a stage
+  // LDS address of the weight fragment of block 0 in ring stage 0, one per 16-deep slice (the slice
+  // flips two bits of the swizzled chunk); block 1 lies 32 rows = 4096 bytes further on.  A tap
+  // adds its stage to the four of them in one go (w_at), so that no read waits for an add.
+  uint32_t w_adr[4];
 #pragma unroll
-  for (uint32_t j = 0; j < 2; ++j) {
-    const uint32_t wrow = 32u * j + l32;
-    w_off[j] = wrow * 128u + ((lhi ^ row_swz8(wrow)) << 4);
-  }
+  for (uint32_t q = 0; q < 4u; ++q) w_adr[q] = lds_base + PT_PATCH + ((l32 * 128u + ((lhi ^ row_swz8(l32)) << 4)) ^ (q << 5));
+  typedef const u32x4 __attribute__((address_space(3))) * lds_u32x4_ptr;
 
   u32x4 fp[2][2], fw[2][2];                  // [slot][block]
-  // fragment m (w0, p0, p1, w1) of slice q: pixels at p_at[] inside the patch, weights in stage wst
-  auto frag_load = [&](const uint32_t (&p_at)[2], const uint8_t* wst, uint32_t q, uint32_t slot, uint32_t m) {
-    if (m == 0u) fw[slot][0] = *reinterpret_cast<const u32x4*>(wst + (w_off[0] ^ (q << 5)));
-    else if (m == 3u) fw[slot][1] = *reinterpret_cast<const u32x4*>(wst + (w_off[1] ^ (q << 5)));
+  // fragment m (w0, p0, p1, w1) of slice q: pixels at p_at[] inside the patch, weights at LDS address wq
+  auto frag_load = [&](const uint32_t (&p_at)[2], uint32_t wq, uint32_t q, uint32_t slot, uint32_t m) {
+    if (m == 0u) fw[slot][0] = *(lds_u32x4_ptr)(uintptr_t)wq;
+    else if (m == 3u) fw[slot][1] = *(lds_u32x4_ptr)(uintptr_t)(wq + 4096u);
     else fp[slot][m - 1u] = *reinterpret_cast<const u32x4*>(smem + (p_at[m - 1u] ^ (q << 5)));
   };
   // 4 MFMAs on fragment slot `slot`; between them the 4 fragment reads of slice fq (pixels at
-  // p_at, weights in wst) into the other slot and, if `dma`, the request for the next weight tile
-  auto block = [&](uint32_t slot, const uint32_t (&p_at)[2], const uint8_t* wst, uint32_t fq, bool dma) {
+  // p_at, weights at wq) into the other slot and, if `dma`, the request for the next weight tile
+  auto block = [&](uint32_t slot, const uint32_t (&p_at)[2], uint32_t wq, uint32_t fq, bool dma) {
 #pragma unroll
     for (uint32_t m = 0; m < 4u; ++m) {
       const uint32_t j = m >> 1, i = m & 1u;
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fw[slot][j]), as_bf16x8(fp[slot][i]), acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      frag_load(p_at, wst, fq, slot ^ 1u, m);
+      frag_load(p_at, wq, fq, slot ^ 1u, m);
       if (dma && m == 1u) dma_weights();
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -1173,26 +1178,31 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(ConvArgs a) {
     __syncthreads();
     uint32_t p_at[2] = {patch_off(0u, 0u), patch_off(1u, 0u)};
     {
-      const uint8_t* wst = smem + PT_PATCH + (kt & (PT_WST - 1u)) * PT_WTILE;
+      const uint32_t w0 = w_adr[0] + (kt & (PT_WST - 1u)) * PT_WTILE;
 #pragma unroll
-      for (uint32_t m = 0; m < 4u; ++m) frag_load(p_at, wst, 0u, 0u, m);
+      for (uint32_t m = 0; m < 4u; ++m) frag_load(p_at, w0, 0u, 0u, m);
     }
-    for (uint32_t tap = 0; tap < 9u; ++tap, ++kt) {
-      const uint8_t* wst = smem + PT_PATCH + (kt & (PT_WST - 1u)) * PT_WTILE;
-      block(0u, p_at, wst, 1u, false);
+#pragma unroll
+    for (uint32_t tap = 0; tap < 9u; ++tap, ++kt) {       // (unrolled: a tap's patch offsets are then constants of the code)
+      // this tap's stage for slices 1 .. 3, the next tap's for its slice 0
+      const uint32_t cur = (kt & (PT_WST - 1u)) * PT_WTILE, nxt = ((kt + 1u) & (PT_WST - 1u)) * PT_WTILE;
+      uint32_t w_at[4] = {w_adr[0] + nxt, w_adr[1] + cur, w_adr[2] + cur, w_adr[3] + cur};
+      asm volatile("" : "+v"(w_at[0]), "+v"(w_at[1]), "+v"(w_at[2]), "+v"(w_at[3]));   // all four here, in one burst: left to
+      __builtin_amdgcn_sched_barrier(0);                                                // itself the compiler sinks each add to its read
+      block(0u, p_at, w_at[1], 1u, false);
       // At most the weight tile after the next is outstanding: the next one has landed, and the
       // barrier tells so for every wave's part.  It also tells that every wave has finished the
       // previous tap (its last MFMAs needed that tap's last fragments), whose stage the request
       // of the following block overwrites with the tile three taps ahead.
       __builtin_amdgcn_s_waitcnt(vm_wait(2));
       __syncthreads();
-      block(1u, p_at, wst, 2u, true);
-      block(0u, p_at, wst, 3u, false);
+      block(1u, p_at, w_at[2], 2u, true);
+      block(0u, p_at, w_at[3], 3u, false);
       const uint32_t nt = tap + 1u < 9u ? tap + 1u : 8u;     // (after the last tap the reads fetch bytes nobody uses)
       const uint32_t r = (nt * 11u) >> 5, t = nt - 3u * r;
       p_at[0] = patch_off(0u, r * pw + t);
       p_at[1] = patch_off(1u, r * pw + t);
-      block(1u, p_at, smem + PT_PATCH + ((kt + 1u) & (PT_WST - 1u)) * PT_WTILE, 0u, false);
+      block(1u, p_at, w_at[0], 0u, false);
     }
   }
   __builtin_amdgcn_s_waitcnt(vm_wait(0));    // no DMA may be in flight when the LDS is given back
