@@ -3,6 +3,7 @@
 Jacobi 4096^2 x100 / fp32 GEMM 4096^3 / BFS 2^20) through probe -> admit -> CU partition ->
 launch -> release on one MI355X, inputs resident in HBM.  Prints ONE JSON line."""
 import argparse
+import gc
 import json
 import os
 import sys
@@ -411,6 +412,10 @@ def main():
     for _ in range(args.warmup):
         run(sched, tasks, **timed_kw)
     log("warm-up done, %d masked streams" % sched.stats().n_streams)
+    # (the interpreter's cyclic collector would otherwise run a full collection of this process's large heap
+    # once or twice inside the timed region, tens of milliseconds each, between two passes)
+    gc.collect()
+    gc.disable()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     runs = []
@@ -418,6 +423,7 @@ def main():
         runs.append(run(sched, tasks, **timed_kw))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    gc.enable()
     log("timed region done: %d steps in %.3f s, %d masked streams" % (args.steps, elapsed, sched.stats().n_streams))
     sums = [harness.summarize(r, m) for r, m in runs]
     value = n_tasks * args.steps / elapsed
