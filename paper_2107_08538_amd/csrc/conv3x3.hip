@@ -11,16 +11,17 @@
 //   conv3x3_s2c32_kernel       stride 2 from 32 channels: filter and patch in LDS; inside a chain it
 //                              also computes the 3-channel first layer in front of it
 //   conv3x3_dma_kernel         implicit GEMM, c_in % 32 == 0: every DMA lane gathers its own
-//   conv3x3_dma64_kernel         pixel; the same with stages of depth 64 (c_in % 64 == 0)
+//   conv3x3_dma64_kernel         pixel; the same with stages of depth 64 (c_in % 64 == 0) and both
+//                              operands through buffer resources (no vector arithmetic in its loop)
 //   conv3x3_dma_ksplit_kernel  layers with few tiles: the depth split over the waves of a
 //                              workgroup and, inside a chain, over workgroups
-//                              (conv_split_reduce_kernel adds the parts)
+//                              (conv_split_reduce_kernel adds the parts); buffer resources too
 //   conv3x3_c3_kernel          the 3-channel first layer on its own
 //   conv3x3_kernel             register-staged, any other shape
 // At the sizes of the net none of them is bound by the matrix pipes or by bytes: a CU holds two of
 // their workgroups (LDS), and what a workgroup's waves spend on addresses, set-up and result stores
 // is not hidden by anyone else.  Hence store_tile_via_lds, FastDiv, the source tables and the
-// running pointers below.
+// buffer resources with scalar offsets below.
 #include "../../include/mgb.h"
 #include "launch_util.h"
 #include "lds_dma.h"
