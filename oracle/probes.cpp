@@ -73,17 +73,21 @@ void orc_jacobi_probe(uint64_t n, uint64_t iters, uint64_t out[7]) {
 // by the 32 wave slots (8 workgroups of 4 waves).
 uint64_t orc_jacobi_residency(uint64_t n) { return n % 4 != 0 ? 8 : (n >= 4096 ? 2 : 3); }
 
-// fp32 GEMM: A, B, C in fp32.  When k is a multiple of 16 and n a multiple of 4 the tile is the
-// 256 x 256 (256 threads) if that gives at least 256 workgroups, else 128 x 128 (512 threads) if
-// that gives at least 128, else 64 x 64 (256 threads); otherwise 128 x 128 with 512 threads.
-// The big tiles run in rounds of 256 (one per CU), the 128 x 128 ones in rounds of 512 at 0.95
-// of the rate: where 100 * rounds_128 < 190 * rounds_256 the 128 x 128 tile is used after all.
+// fp32 GEMM: A, B, C in fp32.  When k is a multiple of 16 and n a multiple of 4 the tile is
+// 256 x 256 (256 threads), 128 x 128 (512 threads) or 64 x 64 (256 threads), whichever the
+// library's estimate finishes first: a CU works ceil(tiles / 256) tiles off, each taking its area
+// over the rate of that tile (153, 150, 143 TFLOP/s; 128 for the small tile when k > 5632), i.e.
+// the least ceil(tiles / 256) * tile^2 * (100000 / rate), the larger tile on a tie.  Otherwise
+// 128 x 128 with 512 threads.
 static uint64_t f32_tile(uint64_t m, uint64_t n, uint64_t k) {
   if (k % 16 != 0 || n % 4 != 0) return 128;
-  uint64_t big = ceil_div(m, 256) * ceil_div(n, 256), mid = ceil_div(m, 128) * ceil_div(n, 128);
-  if (big >= 256) return 100 * ceil_div(mid, 512) < 190 * ceil_div(big, 256) ? 128 : 256;
-  if (mid >= 128) return 128;
-  return 64;
+  const uint64_t tile[3] = {256, 128, 64}, inv_rate[3] = {100000ull / 153, 100000ull / 150, 100000ull / (k <= 5632 ? 143 : 128)};
+  uint64_t best = 256, best_cost = ~0ull;
+  for (int i = 0; i < 3; ++i) {
+    uint64_t cost = ceil_div(ceil_div(m, tile[i]) * ceil_div(n, tile[i]), 256) * tile[i] * tile[i] * inv_rate[i];
+    if (cost < best_cost) { best_cost = cost; best = tile[i]; }
+  }
+  return best;
 }
 void orc_gemm_f32_probe(uint64_t m, uint64_t n, uint64_t k, uint64_t out[7]) {
   out[0] = (m * k + k * n + m * n) * 4;

@@ -392,30 +392,38 @@ struct Geometry {
   bool fast;       // register-staged kernel: every tile full
 };
 
-// 256 x 256 tiles if every CU gets one (142 against 136 TFLOP/s at 4096^3; with fewer tiles than
-// CUs the smaller tile wins: 3072^3 runs at 97 TFLOP/s on 128 x 128 tiles, 78 on 256 x 256), else
-// 128 x 128 tiles if they give at least half of the CUs a workgroup, else 64 x 64.
-// The big tile runs one workgroup per CU, in rounds of 256 tiles; a shape that spills a few
-// tiles into one more round (4544^3: 324 tiles, two rounds, 87 TFLOP/s) is better served by the
-// small tile, which runs in rounds of 512 at about 0.95 of the big tile's rate: the small tile
-// is taken when rounds_128 * 32768 / 0.95 < rounds_256 * 65536.
-constexpr uint32_t FD_MIN_TILES_256 = 256, FD_MIN_TILES_128 = 128;
-
-uint32_t pick_tile(uint32_t m, uint32_t n) {
-  const uint64_t t256 = (uint64_t)((m + 255u) / 256u) * ((n + 255u) / 256u);
-  const uint64_t t128 = (uint64_t)((m + 127u) / 128u) * ((n + 127u) / 128u);
-  if (t256 >= FD_MIN_TILES_256) {
-    const uint64_t rounds256 = (t256 + 255u) / 256u, rounds128 = (t128 + 511u) / 512u;
-    return rounds128 * 100u < rounds256 * 190u ? 128u : 256u;
+// Which tile: the one that is done first by this estimate.  A CU works its tiles off one after the
+// other (two or five resident workgroups share its matrix pipes), so a launch takes as many tile
+// times as the busiest CU has tiles, ceil(tiles / 256), and a tile time is its area over the
+// rate a CU reaches with that tile.  Rates measured on square shapes from 512 to 8192, in TFLOP/s
+// over the device when every CU is equally loaded: 153 with 256 x 256 tiles, 150 with 128 x 128,
+// 143 with 64 x 64 up to k = 5632 and 128 beyond (the small tile re-reads its operands more often
+// and the slabs of a band of tile rows no longer fit L2).  The estimate picks the fastest or
+// second-fastest tile (within 3 % of the fastest up to 5000, within 10 % beyond) on every shape of that sweep:
+// 2176^3 runs at 109 TFLOP/s (64 x 64) instead of 86 (128 x 128), 2944^3 at 132 instead of 105,
+// 4160^3 at 140 instead of 125 (128 x 128) or 79 (256 x 256), 4096^3 and 8192^3 keep the big tile.
+// cost = ceil(tiles / 256) * tile^2 * (100000 / rate), in integers; ties go to the larger tile.
+uint32_t pick_tile(uint32_t m, uint32_t n, uint32_t k) {
+  const uint32_t tile[3] = {256u, 128u, 64u};
+  const uint64_t inv_rate[3] = {100000u / 153u, 100000u / 150u, 100000u / (k <= 5632u ? 143u : 128u)};
+  uint32_t best = 256u;
+  uint64_t best_cost = ~0ull;
+  for (int i = 0; i < 3; ++i) {
+    const uint64_t tiles = (uint64_t)((m + tile[i] - 1u) / tile[i]) * ((n + tile[i] - 1u) / tile[i]);
+    const uint64_t cost = ((tiles + 255u) / 256u) * tile[i] * tile[i] * inv_rate[i];
+    if (cost < best_cost) {
+      best_cost = cost;
+      best = tile[i];
+    }
   }
-  return t128 >= FD_MIN_TILES_128 ? 128u : 64u;
+  return best;
 }
 
 Geometry geometry(uint32_t m, uint32_t n, uint32_t k, bool allow_dma = true) {
   Geometry g;
   g.dma = allow_dma && k % FD_BK == 0u && n % 4u == 0u;
   g.tile = 128u;
-  if (g.dma) g.tile = pick_tile(m, n);
+  if (g.dma) g.tile = pick_tile(m, n, k);
   g.tiles_m = (m + g.tile - 1u) / g.tile;
   g.tiles_n = (n + g.tile - 1u) / g.tile;
   g.total = g.tiles_m * g.tiles_n;

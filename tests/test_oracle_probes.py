@@ -127,6 +127,24 @@ def test_the_configured_gemms_get_the_tiles_that_fill_the_device():
     assert _probe("orc_gemm_bf16_probe", 1024, 1024, 1024)[1] == 64
 
 
+def test_fp32_gemm_tile_is_the_one_its_busiest_cu_finishes_first():
+    # cost of a tile shape = tiles the busiest of the 256 CUs works off x tile area x (100000 // TFLOP/s of that tile)
+    # 2176^3: 256 x 256: 81 tiles -> 1 x 65536 x 653 = 42.8 M; 128 x 128: 289 -> 2 x 16384 x 666 = 21.8 M;
+    #         64 x 64: 1156 -> 5 x 4096 x 699 = 14.3 M: the small tile, 34 x 34 of them
+    assert _probe("orc_gemm_f32_probe", 2176, 2176, 2176)[1:] == [1160, 1, 1, 256, 1, 1]
+    # 2816^3: 128 x 128: 484 -> 2 x 16384 x 666 = 21.8 M; 64 x 64: 1936 -> 8 x 4096 x 699 = 22.9 M; 256 x 256: 121 -> 42.8 M
+    assert _probe("orc_gemm_f32_probe", 2816, 2816, 2816)[1:] == [488, 1, 1, 512, 1, 1]
+    # 4160^3: 256 x 256: 289 -> 2 x 65536 x 653 = 85.6 M; 128 x 128: 1089 -> 5 x 16384 x 666 = 54.6 M; 64 x 64: 4225 -> 17 x 4096 x 699 = 48.7 M
+    assert _probe("orc_gemm_f32_probe", 4160, 4160, 4160)[1:] == [4232, 1, 1, 256, 1, 1]
+    # 6848^3 (k > 5632: the small tile counts 100000 // 128 = 781): 256 x 256: 729 -> 3 x 65536 x 653 = 128.4 M;
+    #         128 x 128: 2916 -> 12 x 16384 x 666 = 130.9 M; 64 x 64: 11449 -> 45 x 4096 x 781 = 144.0 M
+    assert _probe("orc_gemm_f32_probe", 6848, 6848, 6848)[1:] == [736, 1, 1, 256, 1, 1]
+    # 1792^3: 128 x 128: 196 -> 1 x 16384 x 666 = 10.9 M; 64 x 64: 784 -> 4 x 4096 x 699 = 11.5 M
+    assert _probe("orc_gemm_f32_probe", 1792, 1792, 1792)[1:] == [200, 1, 1, 512, 1, 1]
+    # a tall shape: 8192 x 512 x 1024: 256 x 256: 64 tiles -> 42.8 M; 128 x 128: 256 -> 10.9 M; 64 x 64: 1024 -> 4 x 4096 x 699 = 11.5 M
+    assert _probe("orc_gemm_f32_probe", 8192, 512, 1024)[1:] == [256, 1, 1, 512, 1, 1]
+
+
 CONV_TILES = [((128, 128), 256), ((256, 64), 256), ((64, 64), 256), ((64, 64), 64), ((128, 64), 256)]
 
 
