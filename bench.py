@@ -483,6 +483,10 @@ def main():
             out["one_sweep_per_pass_equivalent_gbs"] = round(k["bytes"] / 1e9 / secs, 1)
         if k["edges"]:
             out["gteps"] = round(k["edges"] / secs / 1e9, 2)      # stored directed edges per second of traversal
+            # the same traversal if every 4-byte probe of a neighbour's state cost a whole 32-byte sector of
+            # HBM (a model figure beside the algorithmic one: the level kernel probes a bitmap that it keeps
+            # in LDS or L2, and its counter traffic stays near the algorithmic bytes)
+            out["sector_granular_equivalent_gbs"] = round((k["bytes"] + 28.0 * k["edges"]) / secs / 1e9, 1)
         return out
 
     out = dict(metric="aggregate tasks/s through probe+admit+partition+launch+release (with mean turnaround, max slowdown)",
