@@ -401,7 +401,7 @@ int mgb_client_stream(mgb_client* c, const mgb_placement* placement, void** stre
  * ring is a fixed boundary: v = 0.25f * ((N + S) + (W + E)) on the interior,
  * `iters` sweeps ping-ponging between u0 (initial state) and u1; the result is
  * in u0 if iters is even, else u1.  Both buffers must hold the same ring.
- * Up to four sweeps are fused into one launch, up to eight for n >= 4096
+ * Up to four sweeps are fused into one launch, up to eight for n >= 2048
  * (bit-identical to single sweeps).  The probe's grid is the largest among
  * the task's launches.  mgb_jacobi_residency(n) = workgroups of these kernels
  * that one CU holds (registers), 0 if n is unsupported.

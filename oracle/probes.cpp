@@ -22,7 +22,7 @@ extern "C" {
 
 // Jacobi n x n: two fp32 grids.  n % 4 != 0: one column per thread, 256 columns x 8 rows per
 // workgroup, one sweep per launch.  n % 4 == 0: sweeps are fused, up to 4 per launch (up to 8
-// from n = 4096 on), planned in chunks of 128 sweeps: the fewest launches whose number has the
+// from n = 2048 on), planned in chunks of 128 sweeps: the fewest launches whose number has the
 // parity of the chunk, the sweeps spread evenly over them.  A launch of t <= 4 sweeps: a wave takes a window of 256 columns x 8 output
 // rows, windows step by 248 columns (4 stale columns on each side of a window, none next to the
 // grid's own boundary).  A launch of t > 4 sweeps: a wave
@@ -60,7 +60,7 @@ void orc_jacobi_probe(uint64_t n, uint64_t iters, uint64_t out[7]) {
   } else if (iters == 0) {
     wg = jacobi_blocks(n, 4);
   } else {
-    uint64_t maxt = n >= 4096 ? 8 : 4;
+    uint64_t maxt = n >= 2048 ? 8 : 4;
     wg = jacobi_chunk_blocks(n, iters > 128 ? 128 : iters, maxt);
     if (iters > 128 && iters % 128 != 0) wg = std::max(wg, jacobi_chunk_blocks(n, iters % 128, maxt));
   }
@@ -69,9 +69,9 @@ void orc_jacobi_probe(uint64_t n, uint64_t iters, uint64_t out[7]) {
   out[4] = 256; out[5] = 1; out[6] = 1;
 }
 // Workgroups per CU: the window kernels need up to 168 registers per lane (three waves per SIMD),
-// the streaming kernels used from 4096 columns on up to 224 (two); the one-sweep kernel is limited
+// the streaming kernels used from 2048 columns on up to 224 (two); the one-sweep kernel is limited
 // by the 32 wave slots (8 workgroups of 4 waves).
-uint64_t orc_jacobi_residency(uint64_t n) { return n % 4 != 0 ? 8 : (n >= 4096 ? 2 : 3); }
+uint64_t orc_jacobi_residency(uint64_t n) { return n % 4 != 0 ? 8 : (n >= 2048 ? 2 : 3); }
 
 // fp32 GEMM: A, B, C in fp32.  When k is a multiple of 16 and n a multiple of 4 the tile is
 // 256 x 256 (256 threads), 128 x 128 (512 threads) or 64 x 64 (256 threads), whichever the

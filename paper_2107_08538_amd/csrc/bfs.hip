@@ -29,7 +29,7 @@
 // The host does not know the depth in advance: it enqueues a batch of level
 // kernels whose grids do not depend on the frontier size (the kernels read the
 // size from device memory and exit at once on an empty frontier), then reads
-// the per-level counters back once per batch (8 levels, then 16, then 32 at a
+// the per-level counters back once per batch (8 levels, then 4, 8, 16, then 32 at a
 // time; the read-back polls the stream rather than sleeping on it).
 #include "../../include/mgb.h"
 #include "launch_util.h"
@@ -44,7 +44,8 @@ namespace {
 
 constexpr uint32_t BFS_THREADS = 512;
 constexpr uint32_t BFS_WAVES = BFS_THREADS / 64;
-constexpr uint32_t BFS_BATCH0 = 8;            // levels before the first host round trip, doubled after each
+constexpr uint32_t BFS_BATCH0 = 8;            // levels before the first host round trip
+constexpr uint32_t BFS_BATCH1 = 4;            // levels of the second batch, doubled after each
 constexpr uint32_t BFS_BATCH = 32;            // up to this many (all even: keeps queue parity)
 constexpr uint32_t BFS_CUM = BFS_BATCH + 1;   // control word: vertices reached before this batch's first frontier
 constexpr uint32_t BFS_BU_SPAN = 256;         // vertices a wave scans per bottom-up pass (4 per lane)
@@ -596,7 +597,10 @@ static int bfs_run(void* stream, const int32_t* row_ptr, const int32_t* col_idx,
     levels_done += nb;
     if (levels_done >= n) return MGB_OK;        // cannot happen: depth < n
     hipLaunchKernelGGL(bfs_roll, dim3(1), dim3(64), 0, st, w.ctrl, nb);
-    if (nb < BFS_BATCH) nb *= 2u;
+    // A random graph that is not done after eight levels is nearly done (its frontier peaked two or
+    // three levels ago): a short second batch spares it a dozen empty launches; a deep graph pays
+    // one more round trip on its way to batches of 32
+    nb = levels_done == BFS_BATCH0 ? BFS_BATCH1 : (nb < BFS_BATCH ? nb * 2u : nb);
   }
 }
 

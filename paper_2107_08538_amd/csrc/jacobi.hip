@@ -1,5 +1,5 @@
 // fp32 5-point Jacobi relaxation, up to four sweeps per kernel launch in the window form
-// described first, five to eight in the streaming form (grids of 4096 columns and more).
+// described first, five to eight in the streaming form (grids of 2048 columns and more).
 //
 // One sweep per launch is HBM-bound at 8 bytes per cell update (one read and
 // one write of every cell).  Fusing T sweeps into a launch divides that traffic
@@ -30,6 +30,9 @@
 #ifndef JB_ROWS_DEF
 #define JB_ROWS_DEF 8
 #endif
+#ifndef JB_STREAM_MIN_N
+#define JB_STREAM_MIN_N 2048     // grids from this many columns on fuse five to eight sweeps (streaming form)
+#endif
 
 namespace {
 
@@ -38,11 +41,12 @@ constexpr uint32_t JB_ROWS = JB_ROWS_DEF;     // output rows per window
 constexpr uint32_t JB_WIN = 256;              // window width in columns (64 lanes x 4)
 constexpr uint32_t JB_MAXT = 8;
 constexpr uint32_t JS_ROWS = 40;              // output rows per run of the streaming form (large grids)
-// Sweeps fused per launch.  Launches of up to four sweeps use the window form below; from 4096
-// columns on, launches of five to eight sweeps use the streaming form further down (measured:
-// 4096^2 8 %, 8192^2 9 %, 16384^2 24 % faster than windows of four / six sweeps; smaller grids
-// have too few strips to fill the device with long runs and are slower that way).
-constexpr uint32_t fused_sweeps(uint32_t n) { return n >= 4096u ? JB_MAXT : 4u; }
+// Sweeps fused per launch.  Launches of up to four sweeps use the window form below; from 2048
+// columns on, launches of five to eight sweeps use the streaming form further down (measured,
+// 50 sweeps against windows of four: 2048^2 7 %, 2816^2 20 %, 3584^2 27 %, 4032^2 28 % faster,
+// 8192^2 9 %, 16384^2 24 % against windows of six; below about 1900 columns a grid has too few
+// strips to fill the device with runs of useful length and is 1-20 % slower that way).
+constexpr uint32_t fused_sweeps(uint32_t n) { return n >= JB_STREAM_MIN_N ? JB_MAXT : 4u; }
 // columns lost on each side of a window: at least the sweeps of the launch, a multiple of 4 (16-byte alignment)
 constexpr uint32_t halo_of(uint32_t t) { return t > 4u ? 8u : 4u; }
 constexpr uint32_t step_of(uint32_t halo) { return JB_WIN - 2u * halo; }   // exact columns per window: 248 or 240
@@ -388,12 +392,12 @@ int mgb_jacobi_probe(uint32_t n, uint32_t iters, uint64_t* mem_bytes, mgb_dim3* 
 
 // workgroups a CU holds (one workgroup's four waves go to the four SIMDs): the window kernels
 // take up to 168 registers per lane (three waves per SIMD), the streaming kernels of grids from
-// 4096 columns on up to 224 (two); the one-sweep kernel for n % 4 != 0 is limited by the 32 wave
+// 2048 columns on up to 224 (two); the one-sweep kernel for n % 4 != 0 is limited by the 32 wave
 // slots alone
 uint32_t mgb_jacobi_residency(uint32_t n) {
   if (n < 3u || n > 65536u) return 0u;
   if (n % 4u != 0u) return 8u;
-  return n >= 4096u ? 2u : 3u;
+  return n >= JB_STREAM_MIN_N ? 2u : 3u;
 }
 
 uint32_t mgb_jacobi_launch_count(uint32_t n, uint32_t iters) {

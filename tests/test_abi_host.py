@@ -122,7 +122,7 @@ def test_residency_fact_enters_the_demand_and_the_trace():
     lib.orc_jacobi_residency.restype = C.c_uint64
     for n in (3, 4, 77, 512, 4096, 4097, 65536):
         assert mgb.mgb_jacobi_residency(n) == lib.orc_jacobi_residency(U(n)), n
-    assert (mgb.mgb_jacobi_residency(4096), mgb.mgb_jacobi_residency(2048), mgb.mgb_jacobi_residency(77), mgb.mgb_jacobi_residency(2)) == (2, 3, 8, 0)
+    assert (mgb.mgb_jacobi_residency(4096), mgb.mgb_jacobi_residency(2048), mgb.mgb_jacobi_residency(2044), mgb.mgb_jacobi_residency(77), mgb.mgb_jacobi_residency(2)) == (2, 2, 3, 8, 0)
     lib.orc_bfs_residency.restype = C.c_uint64
     for n in (1, 1000, 1 << 16, 1 << 18, (1 << 18) + 1, 1 << 19, 1 << 20, (1 << 20) + 1, 1 << 24):
         assert mgb.mgb_bfs_residency(n) == lib.orc_bfs_residency(U(n)), n
@@ -148,15 +148,15 @@ def test_grow_in_the_library():
 
 def test_jacobi_launch_plan_keeps_buffer_parity():
     # the result must end in buffer iters % 2, so the number of (fused) launches has that parity;
-    # up to four sweeps per launch below 4096 columns, up to eight from there on
-    for n, maxt in ((2048, 4), (4096, 8), (16384, 8)):
+    # up to four sweeps per launch below 2048 columns, up to eight from there on
+    for n, maxt in ((2044, 4), (1024, 4), (2048, 8), (4096, 8), (16384, 8)):
         for it in list(range(0, 40)) + [50, 100, 127, 128, 129, 1000]:
             c = mgb.mgb_jacobi_launch_count(n, it)
             fewest = (it + maxt - 1) // maxt
             assert c % 2 == it % 2 and fewest <= c <= fewest + (it // 128 + 1), (n, it, c)
     for it in (0, 1, 5, 100):
         assert mgb.mgb_jacobi_launch_count(77, it) == it                 # n % 4 != 0: one sweep per launch
-    assert mgb.mgb_jacobi_launch_count(2048, 100) == 26 and mgb.mgb_jacobi_launch_count(2, 5) == 0
+    assert mgb.mgb_jacobi_launch_count(2044, 100) == 26 and mgb.mgb_jacobi_launch_count(2048, 100) == 14 and mgb.mgb_jacobi_launch_count(2, 5) == 0
     assert mgb.mgb_jacobi_launch_count(4096, 100) == 14 and mgb.mgb_jacobi_launch_count(16384, 50) == 8
     assert mgb.mgb_jacobi_launch_count(8192, 8) == 2 and mgb.mgb_jacobi_launch_count(8192, 7) == 1
 

@@ -68,7 +68,7 @@ def test_jacobi_nonzero_ring_and_constant_field():
 
 
 def test_jacobi_streaming_keeps_a_nonzero_ring():
-    # the streaming launches (4096 columns and more, five to eight sweeps) with values on the ring
+    # the streaming launches (2048 columns and more, five to eight sweeps) with values on the ring
     n = 4100
     rng = np.random.default_rng(1)
     u = rng.random((n, n), dtype=np.float32)
@@ -86,9 +86,10 @@ def test_jacobi_full_size_mix16_task():
 
 
 @pytest.mark.parametrize("n,iters,launches", [(8200, 5, 1), (8192, 12, 2), (8444, 17, 3), (4100, 7, 1), (4096, 13, 3),
-                                              (5000, 21, 3), (4344, 32, 4), (4096, 6, 2)])
+                                              (5000, 21, 3), (4344, 32, 4), (4096, 6, 2),
+                                              (2048, 8, 2), (2052, 7, 1), (2816, 15, 3), (3000, 50, 8), (3964, 24, 4)])
 def test_jacobi_streaming_launches_of_five_to_eight_sweeps(n, iters, launches):
-    # from 4096 columns on a launch fuses up to eight sweeps; launches of five and more stream down
+    # from 2048 columns on a launch fuses up to eight sweeps; launches of five and more stream down
     # strips of 240 columns in runs of 40 rows (ragged last strips and runs in every case here),
     # launches of up to four (13 = 5 + 4 + 4, 6 = 3 + 3) use the window kernel
     u = W.jacobi_field(321, n)

@@ -157,7 +157,7 @@ def test_bfs_and_jacobi_variants(reports):
     streams = min(wg_per_cu(_kernel(reports, "jacobi_stream", "ILj%dE" % t), 4) for t in (5, 6, 7, 8))
     one = wg_per_cu(_kernel(reports, "jacobi_sweep_v1"), 4)
     assert (windows, streams, one) == (3, 2, 8)
-    for n, w in ((2048, windows), (512, windows), (4096, min(windows, streams)), (16384, min(windows, streams)), (77, one)):
+    for n, w in ((2044, windows), (512, windows), (2048, min(windows, streams)), (4096, min(windows, streams)), (16384, min(windows, streams)), (77, one)):
         assert mgb.mgb_jacobi_residency(n) == w == lib.orc_jacobi_residency(U(n)), n
 
 

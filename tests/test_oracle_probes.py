@@ -271,7 +271,7 @@ def test_jacobi_grid_covers_the_interior(n, iters):
         # a wave never produces more than 248 columns x (rows of its run): at most 248 x 8 cells per wave
         # for the window kernels; the streaming kernels produce 240 columns x a run of rows, and a run
         # is never longer than the whole interior
-        most = 248 * 8 if not (n >= 4096 and iters >= 5) else 240 * (n - 2)
+        most = 248 * 8 if not (n >= 2048 and iters >= 5) else 240 * (n - 2)
         assert waves * most >= (n - 2) * (n - 2)
         assert waves >= ceil_div(n - 2, 248)                        # at least one wave per column window
 
@@ -281,6 +281,11 @@ def test_configured_jacobi_launch_shapes():
     # runs chosen so that the waves are one round of 2048: 2048 // 18 = 113 runs -> ceil(4094 / 113) = 37 rows
     # -> ceil(4094 / 37) = 111 runs -> 18 * 111 = 1998 waves -> 500 workgroups -> 504
     assert _probe("orc_jacobi_probe", 4096, 100)[1] == 504
+    # 2048^2 x100 (the smallest grid that streams): 9 strips (2048 = 256 + 7.47 * 240), 2048 // 9 = 227 runs ->
+    # ceil(2046 / 227) = 10 rows -> ceil(2046 / 10) = 205 runs -> 9 * 205 = 1845 waves -> 462 workgroups -> 464
+    assert _probe("orc_jacobi_probe", 2048, 100)[1] == 464
+    # 2044^2 x100: windows of 248 columns x 8 rows: (1 + ceil(1788 / 248)) x ceil(2042 / 8) = 9 x 256 waves = 576 workgroups
+    assert _probe("orc_jacobi_probe", 2044, 100)[1] == 576
     # 512^2 x20 (the smoke mix): windows of 248 columns x 8 rows: 3 x 64 waves = 48 workgroups
     assert _probe("orc_jacobi_probe", 512, 20)[1] == 48
 
@@ -341,8 +346,8 @@ def test_residency_follows_from_lds_registers_and_wave_slots():
     # Jacobi: 4 waves per workgroup; one sweep per launch (n % 4 != 0): small kernels, the wave slots bind;
     # window kernels up to 168 registers (3 waves per SIMD); streaming kernels (n >= 4096) up to 224 (2)
     assert lib.orc_jacobi_residency(U(77)) == wg_per_cu(0, 11, 4) == 8
-    assert lib.orc_jacobi_residency(U(2048)) == wg_per_cu(0, 168, 4) == 3
-    assert lib.orc_jacobi_residency(U(4096)) == wg_per_cu(0, 224, 4) == 2
+    assert lib.orc_jacobi_residency(U(2044)) == wg_per_cu(0, 168, 4) == 3
+    assert lib.orc_jacobi_residency(U(2048)) == lib.orc_jacobi_residency(U(4096)) == wg_per_cu(0, 224, 4) == 2
 
 
 def test_demands_of_the_mix16_kinds_follow_from_grid_and_residency():
