@@ -410,7 +410,7 @@ int mgb_jacobi_probe(uint32_t n, uint32_t iters, uint64_t* mem_bytes, mgb_dim3* 
 uint32_t mgb_jacobi_residency(uint32_t n);
 int mgb_jacobi_enqueue(void* stream, float* u0, float* u1, uint32_t n, uint32_t iters);
 /* Number of kernel launches mgb_jacobi_enqueue issues for (n, iters): sweeps are fused up to
- * four (n >= 4096: eight) per launch, with the launch count kept at the parity of iters (0 if n
+ * four (n >= 2048: eight) per launch, with the launch count kept at the parity of iters (0 if n
  * is unsupported). */
 uint32_t mgb_jacobi_launch_count(uint32_t n, uint32_t iters);
 

@@ -344,7 +344,7 @@ def test_residency_follows_from_lds_registers_and_wave_slots():
     assert lib.orc_bfs_residency(U(1 << 16)) == wg_per_cu(29184 + 8 * KIB, 120, 8) == 2
     assert lib.orc_bfs_residency(U((1 << 20) + 1)) == wg_per_cu(29184, 120, 8) == 2
     # Jacobi: 4 waves per workgroup; one sweep per launch (n % 4 != 0): small kernels, the wave slots bind;
-    # window kernels up to 168 registers (3 waves per SIMD); streaming kernels (n >= 4096) up to 224 (2)
+    # window kernels up to 168 registers (3 waves per SIMD); streaming kernels (n >= 2048) up to 224 (2)
     assert lib.orc_jacobi_residency(U(77)) == wg_per_cu(0, 11, 4) == 8
     assert lib.orc_jacobi_residency(U(2044)) == wg_per_cu(0, 168, 4) == 3
     assert lib.orc_jacobi_residency(U(2048)) == lib.orc_jacobi_residency(U(4096)) == wg_per_cu(0, 224, 4) == 2
