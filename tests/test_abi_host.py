@@ -97,6 +97,49 @@ def test_stuck_task_does_not_block_tasks_that_fit():
         assert list(pl.cu_mask) == [0] * (4 + i // 4) + [0xFF << (8 * (i % 4))] + [0] * (3 - i // 4)
 
 
+def test_pressure32_footprints_under_both_caps_worked_by_hand():
+    """The 32-task memory-pressure mix at its stated footprints (16 x 12 GiB GEMM, 16 x 2 GiB Jacobi,
+    alternating, all probing at t = 0), memory as the only hard resource (SOFT, no limit on resident
+    tasks).  Cap = summed footprints / 1.5 = 149.33 GiB: ten GEMM + Jacobi pairs make 140 GiB, the
+    eleventh GEMM (task 20) would make 152 and waits, the Jacobi tasks 21, 23, 25, 27 still fit
+    (142, 144, 146, 148 GiB), task 29 would make 150 and waits, as do all later GEMMs: 24 resident,
+    8 queued.  Under the device's full 288e9 bytes (268.2 GiB >= 224) nobody waits for memory."""
+    import workloads as W
+    GIB = 1 << 30
+    spec = W.pressure32()
+    assert spec["cap_bytes"] == int(224 * GIB / 1.5)
+    for cap, waiting in ((spec["cap_bytes"], [20, 22, 24, 26, 28, 29, 30, 31]), (288 * 10 ** 9, [])):
+        s = _null(mem_cap_bytes=cap, policy=mgb.MGB_POLICY_SOFT, max_running=0)
+        tickets, queued = {}, []
+        for t in spec["tasks"]:
+            if t.kind == "gemm_f32":
+                mem, grid, block = mgb.probe_of(mgb.mgb_gemm_f32_probe, t.params["m"], t.params["n"], t.params["k"])
+                assert mem == 12 * GIB
+            else:
+                mem, grid, block = mgb.probe_of(mgb.mgb_jacobi_probe, t.params["n"], t.params["iters"])
+                assert mem == 2 * GIB
+            rc, pl = s.probe(t.task_id, mem, grid, block)
+            assert rc in (mgb.MGB_OK, mgb.MGB_WAIT)
+            tickets[t.task_id] = pl.ticket
+            if rc == mgb.MGB_WAIT:
+                queued.append(t.task_id)
+        assert queued == waiting
+        resident = 32 - len(waiting)
+        used = sum((12 if t.task_id % 2 == 0 else 2) * GIB for t in spec["tasks"] if t.task_id not in waiting)
+        assert s.stats().free_bytes == cap - used and (not waiting or used == 148 * GIB)
+        # the first GEMM to finish lets exactly one waiter in: 12 GiB come back, task 20 (12 GiB) takes them,
+        # and nothing is left for task 22 (148 GiB resident again)
+        if waiting:
+            assert s.complete(tickets[0]) == mgb.MGB_OK
+            rc, pl = s.wait(tickets[20], 0)
+            assert rc == mgb.MGB_OK
+            rc, pl = s.wait(tickets[22], 0)
+            assert rc == mgb.MGB_TIMEOUT
+            assert s.stats().free_bytes == cap - 148 * GIB
+        assert_trace_matches_replay(s.desc, s.trace())
+        assert resident == 24 or resident == 32
+
+
 def test_residency_fact_enters_the_demand_and_the_trace():
     s = _null(mem_cap_bytes=10 ** 6)                                  # 32 granules of 8 CUs
     g, b = (256, 1, 1), (256, 1, 1)                                   # 4 waves per workgroup: 8 per CU by wave slots
