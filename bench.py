@@ -505,6 +505,10 @@ def main():
                mean_turnaround_ms=round(mean_turn, 3),
                median_turnaround_ms=round(med([s["mean_turnaround_ms"] for s in sums]), 3),
                mean_wait_ms=round(sum(s["mean_wait_ms"] for s in sums) / len(sums), 3),
+               # admission - probe; with releases ordered on the stream a task can be admitted while its predecessor's
+               # kernels still run, so the time a task spends not running (turnaround - its kernels' time: waiting
+               # for admission, queued on the device behind its predecessor, hand-over) is given beside it
+               mean_not_running_ms=round(sum(s["mean_turnaround_ms"] - s["gpu_busy_ms"] / max(1, s["tasks"]) for s in sums) / len(sums), 3),
                input_gen_s=round(t_gen, 1), stream_copy_gbps=round(copy_gbps, 1),
                mfma_loop_tflops={k: round(v, 1) for k, v in mfma_tflops.items()},
                bytes_per_clk_per_cu=rates)

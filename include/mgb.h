@@ -265,7 +265,9 @@ typedef struct {
   double tasks_per_s;          /* n_done / (last completion - first arrival)                    */
   double makespan_ms;          /* last completion - first arrival                               */
   double mean_turnaround_ms, max_turnaround_ms;   /* completion - arrival                       */
-  double mean_wait_ms, max_wait_ms;               /* admission - probe                          */
+  double mean_wait_ms, max_wait_ms;               /* admission - probe (a task admitted behind a
+                                  task released on the stream may still wait on the device for that task's
+                                  kernels: that time is in its turnaround, not here)            */
   double gpu_busy_ms;          /* sum of the tasks' gpu_ms                                      */
   double max_slowdown, mean_slowdown;             /* gpu_ms / reference - 1 over the tasks given one */
 } mgb_summary;
